@@ -1,0 +1,201 @@
+/*
+ * csgs -- one partition's sampled GCN layer step with communication-efficient
+ * (locality-skewed) layer-wise neighbor sampling, for AMD MI355X (gfx950).
+ *
+ * The five operations follow the paper's statement of the method:
+ *   csgs_build_probs   importance weights ||w_*j||^2 over the neighbors of S_l (Section 4.1),
+ *                      skewed linear weighted sampling distribution (Section 4.2, Eq. 10;
+ *                      Eq. 7 when skew = 1)
+ *   csgs_sample_layer  B draws from that distribution, inclusion probability (Eq. 8), sampled
+ *                      adjacency with every kept edge divided by it (Eq. 3)
+ *   csgs_remote_count  sampled nodes that live on other partitions = communication volume (Eq. 4)
+ *   csgs_aggregate     Z = P~ sigma(H_prev)   (Section 3, Eq. 1: gather of rows + sparse x dense)
+ *   csgs_layer_gemm    H = Z W                (Section 3, Eq. 1: dense layer weights)
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers unless the comment says "host".  All buffers are owned by
+ *     the caller; the library never allocates, frees or synchronises.  Work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = default stream) and the call returns at once.
+ *   - Return value: CSGS_OK or a negative CSGS_E* code found synchronously from host-visible
+ *     arguments; in that case nothing was enqueued.
+ *   - Failures that depend on device data (capacity overflow, a non-finite edge value, an id
+ *     out of range, an empty candidate set) OR the matching CSGS_ST_* bit into the int32 word
+ *     `status` (device).  The caller zeroes it and reads it when it next synchronises.  When a
+ *     bit is set the outputs of that call are unspecified but every access stayed in bounds.
+ *   - `ws` is scratch of at least csgs_workspace_bytes() bytes, 256-byte aligned, prepared once
+ *     with csgs_workspace_init().  Every call leaves it in the prepared state.  Calls that share
+ *     one workspace must be ordered on one stream.
+ */
+#ifndef CSGS_H
+#define CSGS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CSGS_OK = 0,
+    CSGS_EINVAL = -1,       /* null pointer, non-positive size, skew < 1, lo > hi, bad alignment */
+    CSGS_EWORKSPACE = -2,   /* ws_bytes too small */
+    CSGS_EUNSUPPORTED = -3, /* dtype or dimension outside what the kernels cover */
+    CSGS_ERANGE = -4,       /* fixed-point format would keep fewer than 24 fraction bits */
+    CSGS_ELAUNCH = -5       /* the HIP runtime refused a launch */
+};
+
+enum {
+    CSGS_ST_CAND_OVERFLOW = 1,    /* more candidates than `cap` */
+    CSGS_ST_BAD_EDGE_VALUE = 2,   /* a scanned edge value is NaN or infinite */
+    CSGS_ST_EMPTY_CANDIDATES = 4, /* the rows of S have no edges at all */
+    CSGS_ST_ADJ_OVERFLOW = 8,     /* sampled adjacency needs more than adj_cap entries */
+    CSGS_ST_BAD_NODE_ID = 16      /* an entry of S is outside [0, n_nodes) */
+};
+
+enum { CSGS_F32 = 0, CSGS_BF16 = 1 };
+
+/* Propagation matrix P in CSR (host struct holding device pointers).  Columns ascend within a
+ * row.  [local_lo, local_hi) is the id range of the partition this GPU owns (the paper splits
+ * nodes evenly by id, Section 5.1).  rownorm2_max bounds max_i sum_j P_ij^2 (1 for the
+ * symmetric or row normalisation); it fixes the fixed-point scale of the weights. */
+typedef struct csgs_graph {
+    int64_t n_nodes;
+    int64_t nnz;
+    const int64_t *rowptr; /* [n_nodes + 1] */
+    const int32_t *colidx; /* [nnz] */
+    const float *val;      /* [nnz] */
+    int32_t local_lo, local_hi;
+    float rownorm2_max;
+} csgs_graph;
+
+/* Written by csgs_build_probs (device).  |L|, |R| and the weight sums are over CANDIDATES
+ * (Section 4.2 splits N(S_l) into local and remote nodes). */
+typedef struct csgs_prob_stats {
+    int64_t n_cand;        /* |N(S_l)| */
+    int64_t n_local;       /* |L| */
+    int64_t n_remote;      /* |R| */
+    int64_t edges_scanned; /* sum of deg(i), i in S_l */
+    uint64_t w_local;      /* sum_{k in L} ||w_*k||^2, fixed point, unskewed */
+    uint64_t w_remote;     /* sum_{k in R} ||w_*k||^2 */
+    uint64_t total;        /* denominator of Eq. 10 in fixed point = cdf[n_cand - 1] */
+    int32_t shift;         /* fraction bits of the fixed-point weights */
+    int32_t pad_;
+} csgs_prob_stats;
+
+/* Scratch size for graphs of n_nodes nodes, row sets up to nS_max and up to B_max draws. */
+size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max);
+
+/* Size of the leading part of the workspace that is all-zero whenever no call is in flight
+ * (accumulators, bitmaps, rank table); the rest is per-call scratch.  For tests and debugging. */
+size_t csgs_workspace_clean_bytes(int64_t n_nodes);
+
+/* Zero-fills the workspace (a fill kernel, safe under graph capture).  Call once per workspace. */
+int csgs_workspace_init(void *ws, size_t ws_bytes, void *stream);
+
+/* Host-only helper: the fixed-point parameters csgs_build_probs will use (see there).
+ * shift and s_fx are host pointers, nullable.  Returns CSGS_EINVAL for nS <= 0, skew < 1 or
+ * > 2^20, rownorm2_max <= 0; CSGS_ERANGE when fewer than 24 fraction bits would remain. */
+int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift, int64_t *s_fx);
+
+/*
+ * Sampling distribution over the candidates N(S_l) = union of the neighbors of the rows in S
+ * (Section 4.1; the layer-wise sampler of Section 5.1).
+ *
+ * Weight of candidate j:  ||w_*j||^2 = sum_{i in S} P_ij^2, held as an exact integer
+ *   sum_i max(1, rne(P_ij^2 * 2^shift)),  shift = min(52, 61 - ceil(log2 nS) - ceil(log2 s_fx)
+ *   - ceil(log2 rownorm2_max)),  s_fx = round(16 * skew),
+ * so that the result does not depend on summation order.  Skewed weight (Eq. 10 numerator):
+ * weight * s_fx for local j, weight * 16 for remote j.
+ *
+ *   S        [nS] distinct node ids, any order
+ *   skew     s >= 1 (s = 1 is linear weighted sampling, Eq. 7); used in 1/16 steps
+ *   cand_id  [cap] out: candidate ids ascending
+ *   cand_w   [cap] out: fixed-point ||w_*j||^2 (unskewed)
+ *   cdf      [cap] out: inclusive running sum of the skewed weights (cdf[n_cand-1] = total)
+ *   q        [cap] out, nullable: Eq. 10 as float = skewed weight / total
+ *   stats    out, see above
+ * Host errors: CSGS_EINVAL, CSGS_ERANGE (shift < 24), CSGS_EWORKSPACE.
+ * Status bits: CAND_OVERFLOW, BAD_EDGE_VALUE, EMPTY_CANDIDATES, BAD_NODE_ID.
+ */
+int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float skew,
+                     int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
+                     csgs_prob_stats *stats, void *ws, size_t ws_bytes, int32_t *status,
+                     void *stream);
+
+/*
+ * B independent draws from q (Section 4.1: the sampling is run B times), deduplicated into
+ * the next layer's node set, and the sampled adjacency of Eq. 3.
+ *
+ * Draw t uses Philox4x32-10 with key (seed_lo, seed_hi) and counter (t, layer, iter_lo, iter_hi);
+ * r = x0 | x1 << 32;  u = floor(r * total / 2^64);  the draw is the first candidate k with
+ * cdf[k] > u.  Inclusion probability p_j = 1 - (1 - q_j)^B (Eq. 8) in double.
+ *
+ *   cand_id, cdf, stats   as written by csgs_build_probs for the same S (device);
+ *            cand_cap = the capacity those arrays were given there
+ *   S_next   [B] out: distinct sampled ids ascending; *n_next of them
+ *   mult     [B] out: how many of the B draws hit each
+ *   p_incl   [B] out: p_j as float
+ *   adj_rowptr [nS+1], adj_col [adj_cap], adj_val [adj_cap], adj_nnz: out, CSR of P~ with rows in
+ *            the order of S, adj_col = position in S_next (ascending within a row),
+ *            adj_val = (float)((double)P_ij / p_j)
+ * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE.  Status bits: ADJ_OVERFLOW.
+ */
+int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
+                      const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
+                      const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter, uint32_t layer,
+                      int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
+                      int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
+                      int64_t *adj_nnz, void *ws, size_t ws_bytes, int32_t *status, void *stream);
+
+/*
+ * Communication volume of the step (Eq. 4; Section 5.2 reports the number of nodes whose
+ * feature vectors are transferred): sampled ids outside [local_lo, local_hi).
+ *
+ *   S_next [*n_next] ascending (device), n_next device
+ *   part_bounds [P+1] nullable: partition p owns [b[p], b[p+1]); per_part [P] nullable out
+ *   remote_total out (device int64)
+ *   src_row [*n_next] nullable out: where the aggregation finds the feature row of S_next[k]:
+ *            id - local_lo for a local node, -1 - (rank among the sampled remote nodes) otherwise
+ *   remote_ids [*n_next] nullable out: the sampled remote ids ascending (the request list whose
+ *            rows the caller stages, in this order, for csgs_aggregate)
+ */
+int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo,
+                      int32_t local_hi, const int32_t *part_bounds, int32_t P,
+                      int64_t *remote_total, int64_t *per_part, int32_t *src_row,
+                      int32_t *remote_ids, void *stream);
+
+/*
+ * Z = P~ sigma?(X)  (Eq. 1; sigma = ReLU on the INPUT rows, none for the bottom layer).
+ *
+ *   adj_*     CSR of P~ from csgs_sample_layer; nS rows
+ *   n_next    device, nullable: number of columns of P~ (bounds adj_col; NULL = not checked
+ *             against it)
+ *   X_local   row-major, rows_local rows, leading dimension ld_local elements (NULL allowed
+ *             when rows_local = 0); X_remote nullable, rows_remote rows, ld_remote
+ *   src_row   nullable.  NULL: column c reads row c of X_local (upper layers: compact input).
+ *             Else column c reads row src_row[c] of X_local if >= 0, row -1 - src_row[c] of X_remote.
+ *   F         feature width; dtype CSGS_F32 or CSGS_BF16 (bf16 widened exactly, fp32 accumulate)
+ *   Z         [nS x F] float out, leading dimension ldz; rows without kept edges are zero
+ * Products are accumulated in double in ascending edge order and rounded to float once.  An edge whose column or source row lies
+ * outside the tables contributes nothing (no status word here; every load stays in bounds).
+ */
+int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val,
+                   int32_t nS, const int32_t *n_next, const void *X_local, int64_t ld_local,
+                   int64_t rows_local, const void *X_remote, int64_t ld_remote, int64_t rows_remote,
+                   const int32_t *src_row, int32_t F, int dtype, int relu_on_input, float *Z,
+                   int64_t ldz, void *stream);
+
+/* H [M x Nout] = Z [M x K] W [K x Nout], all row-major fp32 (Eq. 1).  fp32 MFMA over runs of 16
+ * consecutive k, the runs summed in double, one rounding to float.
+ * Host errors: CSGS_EINVAL; CSGS_EUNSUPPORTED for M above 64 * 65535. */
+int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const float *W,
+                    int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
+
+/* Static string for a CSGS_E* code. */
+const char *csgs_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSGS_H */

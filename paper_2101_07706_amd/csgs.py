@@ -1,0 +1,166 @@
+"""Thin Python binding of libcsgs.so: argument marshalling only.
+
+Same names as the C entry points in include/csgs.h.  Tensors are torch CUDA
+(ROCm) tensors used purely as device memory; every step of the method runs in
+the library's HIP kernels.  There is no fallback: if the shared library is
+missing the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcsgs.so")
+
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, ERANGE, ELAUNCH = 0, -1, -2, -3, -4, -5
+ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BAD_NODE_ID = 1, 2, 4, 8, 16
+F32, BF16 = 0, 1
+
+EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
+           "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror"]
+
+
+class CsgsError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+        self.code = code
+
+
+class Graph(C.Structure):
+    """csgs_graph: host struct of device pointers."""
+    _fields_ = [("n_nodes", C.c_int64), ("nnz", C.c_int64), ("rowptr", C.c_void_p),
+                ("colidx", C.c_void_p), ("val", C.c_void_p), ("local_lo", C.c_int32),
+                ("local_hi", C.c_int32), ("rownorm2_max", C.c_float)]
+
+
+class ProbStats(C.Structure):
+    """csgs_prob_stats as laid out on the device (64 bytes)."""
+    _fields_ = [("n_cand", C.c_int64), ("n_local", C.c_int64), ("n_remote", C.c_int64),
+                ("edges_scanned", C.c_int64), ("w_local", C.c_uint64), ("w_remote", C.c_uint64),
+                ("total", C.c_uint64), ("shift", C.c_int32), ("pad_", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u64, u32, f32, sz = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_uint32,
+                                           C.c_float, C.c_size_t)
+        L.csgs_workspace_bytes.restype = sz
+        L.csgs_workspace_bytes.argtypes = [i64, i32, i32]
+        L.csgs_workspace_clean_bytes.restype = sz
+        L.csgs_workspace_clean_bytes.argtypes = [i64]
+        L.csgs_workspace_init.argtypes = [vp, sz, vp]
+        L.csgs_fixed_point.argtypes = [i32, f32, f32, C.POINTER(i32), C.POINTER(i64)]
+        L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, f32, vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
+        L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
+                                        vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
+        L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
+        L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
+                                     C.c_int, vp, i64, vp]
+        L.csgs_layer_gemm.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, i64, vp]
+        L.csgs_strerror.restype = C.c_char_p
+        L.csgs_strerror.argtypes = [C.c_int]
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().csgs_strerror(code).decode()
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _chk(rc, where):
+    if rc != OK:
+        raise CsgsError(rc, where)
+
+
+def make_graph(rowptr, colidx, val, local_lo, local_hi, rownorm2_max=1.0) -> Graph:
+    assert rowptr.dtype == torch.int64 and colidx.dtype == torch.int32 and val.dtype == torch.float32
+    g = Graph(rowptr.numel() - 1, colidx.numel(), rowptr.data_ptr(), colidx.data_ptr(), val.data_ptr(),
+              local_lo, local_hi, rownorm2_max)
+    g._keep = (rowptr, colidx, val)
+    return g
+
+
+def csgs_workspace_bytes(n_nodes, nS_max, B_max) -> int:
+    return int(lib().csgs_workspace_bytes(n_nodes, nS_max, B_max))
+
+
+def csgs_workspace_clean_bytes(n_nodes) -> int:
+    return int(lib().csgs_workspace_clean_bytes(n_nodes))
+
+
+def csgs_workspace_init(ws, stream=None):
+    _chk(lib().csgs_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "csgs_workspace_init")
+
+
+def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
+    sh, sfx = C.c_int32(0), C.c_int64(0)
+    rc = lib().csgs_fixed_point(nS, skew, rownorm2_max, C.byref(sh), C.byref(sfx))
+    return rc, sh.value, sfx.value
+
+
+def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None):
+    _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
+                                _ptr(q), cand_id.numel(), _ptr(stats), _ptr(ws), ws.numel() * ws.element_size(),
+                                _ptr(status), _stream(stream)), "csgs_build_probs")
+
+
+def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
+                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None):
+    _chk(lib().csgs_sample_layer(C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
+                                 _ptr(stats), B, seed, it, layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
+                                 _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
+                                 _ptr(adj_nnz), _ptr(ws), ws.numel() * ws.element_size(), _ptr(status),
+                                 _stream(stream)), "csgs_sample_layer")
+
+
+def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_total, per_part=None,
+                      src_row=None, remote_ids=None, stream=None):
+    P = 0 if part_bounds is None else part_bounds.numel() - 1
+    _chk(lib().csgs_remote_count(_ptr(S_next), _ptr(n_next), local_lo, local_hi, _ptr(part_bounds), P,
+                                 _ptr(remote_total), _ptr(per_part), _ptr(src_row), _ptr(remote_ids),
+                                 _stream(stream)), "csgs_remote_count")
+
+
+def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_row, relu_on_input, Z,
+                   stream=None):
+    """X_* are 2-D float32 tensors or int16/uint16/bfloat16 tensors holding bfloat16 rows."""
+    dtype = F32 if X_local.dtype == torch.float32 else BF16
+    F = X_local.shape[1]
+    rows_r = 0 if X_remote is None else X_remote.shape[0]
+    ld_r = 0 if X_remote is None else X_remote.stride(0)
+    if X_remote is not None and rows_r == 0:
+        X_remote = None
+    Xl_ptr = _ptr(X_local) if X_local.shape[0] > 0 else None
+    _chk(lib().csgs_aggregate(_ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
+                              _ptr(n_next), Xl_ptr, X_local.stride(0), X_local.shape[0], _ptr(X_remote),
+                              ld_r, rows_r, _ptr(src_row), F, dtype, 1 if relu_on_input else 0, _ptr(Z),
+                              Z.stride(0), _stream(stream)), "csgs_aggregate")
+
+
+def csgs_layer_gemm(Z, W, H, stream=None):
+    M, K = Z.shape
+    K2, N = W.shape
+    assert K == K2 and H.shape == (M, N)
+    _chk(lib().csgs_layer_gemm(_ptr(Z), Z.stride(0), M, K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
+                               _stream(stream)), "csgs_layer_gemm")

@@ -1,0 +1,199 @@
+// csgs_aggregate: Z = P~ sigma?(X)  (Section 3, Eq. 1 with the sampled operator P~).
+//
+// A group of G lanes (16, 32 or 64) owns one output row and spreads over the feature dimension
+// with V-element vector loads, so every gathered source row is read as one contiguous burst.
+// The row's edges (column, value, resolved source pointer) are fetched G at a time, one edge per
+// lane, and broadcast lane-to-lane.  Products are accumulated in double, in ascending edge order,
+// and rounded to float once: sampled rows carry 1/p_j discounts of 10^2..10^3, so near-cancelling
+// outputs would lose the 1e-5 absolute tolerance with a float accumulator; the kernel is bound
+// by memory traffic, so the wider adds are free.
+#include "common.hpp"
+
+namespace csgs {
+
+template <int V>
+struct Vec {
+    float x[V];
+};
+
+template <typename T, int V>
+__device__ inline Vec<V> load_row(const T *p);
+
+template <>
+__device__ inline Vec<1> load_row<float, 1>(const float *p) { return Vec<1>{{p[0]}}; }
+template <>
+__device__ inline Vec<2> load_row<float, 2>(const float *p)
+{
+    const float2 v = *reinterpret_cast<const float2 *>(p);
+    return Vec<2>{{v.x, v.y}};
+}
+template <>
+__device__ inline Vec<4> load_row<float, 4>(const float *p)
+{
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    return Vec<4>{{v.x, v.y, v.z, v.w}};
+}
+// bfloat16 bit patterns: widening is a 16-bit left shift
+template <>
+__device__ inline Vec<1> load_row<uint16_t, 1>(const uint16_t *p) { return Vec<1>{{__uint_as_float((uint32_t)p[0] << 16)}}; }
+template <>
+__device__ inline Vec<2> load_row<uint16_t, 2>(const uint16_t *p)
+{
+    const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+    return Vec<2>{{__uint_as_float(v << 16), __uint_as_float(v & 0xFFFF0000u)}};
+}
+template <>
+__device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
+{
+    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    return Vec<4>{{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                   __uint_as_float(v.y & 0xFFFF0000u)}};
+}
+
+template <typename T, int V, int G, bool RELU>
+__global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
+                                                   const int32_t *__restrict__ adj_col,
+                                                   const float *__restrict__ adj_val, int32_t nS,
+                                                   const int32_t *__restrict__ n_cols_p, const T *__restrict__ Xl,
+                                                   int64_t ldl, int64_t rows_l, const T *__restrict__ Xr, int64_t ldr,
+                                                   int64_t rows_r, const int32_t *__restrict__ src_row, int32_t F,
+                                                   float *__restrict__ Z, int64_t ldz)
+{
+    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+    const int tid = (int)threadIdx.x;
+    const int g = tid & (G - 1);  // lane within the row group
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + tid) / G;
+    // Rows past the end still take part in the lane broadcasts of their wavefront with an empty range.
+    int32_t beg = 0, end = 0;
+    if (row < nS) { beg = adj_rowptr[row]; end = adj_rowptr[row + 1]; }
+    // trip count of the edge loop must be uniform over the wavefront when G < 64
+    int32_t len = end - beg;
+    int32_t maxlen = len;
+    if (G < 64) {
+#pragma unroll
+        for (int off = G; off < WAVE; off <<= 1) {
+            const int32_t o = __shfl_xor(maxlen, off, WAVE);
+            maxlen = o > maxlen ? o : maxlen;
+        }
+    }
+    for (int32_t f0 = 0; f0 < F; f0 += G * V) {
+        const int32_t f = f0 + g * V;
+        const bool active = f < F;  // F is a multiple of V (checked on the host)
+        double acc[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] = 0.0;
+        for (int32_t c0 = 0; c0 < maxlen; c0 += G) {
+            // stage up to G edges of this row: one per lane
+            const int32_t e = beg + c0 + g;
+            const T *src = nullptr;  // stays null for an edge that must not be read
+            float w = 0.f;
+            if (e < end) {
+                const int32_t c = adj_col[e];
+                // a column or source row outside the tables contributes nothing (keeps every load in bounds)
+                if (c >= 0 && c < n_cols) {
+                    const int64_t sr = src_row ? (int64_t)src_row[c] : (int64_t)c;
+                    if (sr >= 0 && sr < rows_l) {
+                        src = Xl + sr * ldl;
+                        w = adj_val[e];
+                    } else if (sr < 0 && -1 - sr < rows_r) {
+                        src = Xr + (-1 - sr) * ldr;
+                        w = adj_val[e];
+                    }
+                }
+            }
+            const int32_t n_here = (len - c0) < G ? (len - c0) : G;  // edges of my row in this chunk (may be <= 0)
+            const int32_t n_max = (maxlen - c0) < G ? (maxlen - c0) : G;
+            for (int32_t j = 0; j < n_max; ++j) {
+                const int srcl = (tid & (WAVE - 1) & ~(G - 1)) + j;
+                const uint64_t pj = __shfl((uint64_t)(uintptr_t)src, srcl, WAVE);
+                const double wj = (double)__shfl(w, srcl, WAVE);
+                if (active && j < n_here && pj) {
+                    Vec<V> x = load_row<T, V>(reinterpret_cast<const T *>((uintptr_t)pj) + f);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        float xv = x.x[v];
+                        if (RELU) xv = xv > 0.f ? xv : 0.f;
+                        acc[v] = fma(wj, (double)xv, acc[v]);
+                    }
+                }
+            }
+        }
+        if (active && row < nS) {
+            float *z = Z + row * ldz + f;
+            if (V == 4)
+                *reinterpret_cast<float4 *>(z) = make_float4((float)acc[0], (float)acc[1], (float)acc[V > 2 ? 2 : 0],
+                                                             (float)acc[V > 3 ? 3 : 0]);
+            else if (V == 2)
+                *reinterpret_cast<float2 *>(z) = make_float2((float)acc[0], (float)acc[V > 1 ? 1 : 0]);
+            else
+                z[0] = (float)acc[0];
+        }
+    }
+}
+
+template <typename T, int V, int G>
+static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+                      int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
+                      hipStream_t st)
+{
+    const int rows_per_block = 256 / G;
+    const unsigned blocks = (unsigned)((nS + rows_per_block - 1) / rows_per_block);
+    if (relu)
+        hipLaunchKernelGGL((aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), 0, st, rp, col, val, nS, ncp, (const T *)Xl,
+                           ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+    else
+        hipLaunchKernelGGL((aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), 0, st, rp, col, val, nS, ncp,
+                           (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+template <typename T, int V>
+static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+                      int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
+                      hipStream_t st)
+{
+    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    return launch_agg<T, V, 64>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+}
+
+template <typename T>
+static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+                    int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
+                    hipStream_t st)
+{
+    // widest vector for which every row start and F are aligned
+    auto ok = [&](int v) {
+        const uintptr_t bytes = (uintptr_t)v * sizeof(T);
+        return F % v == 0 && (!Xl || (ldl % v == 0 && ((uintptr_t)Xl % bytes) == 0)) &&
+               (!Xr || (ldr % v == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % v == 0 &&
+               ((uintptr_t)Z % ((uintptr_t)v * sizeof(float))) == 0;
+    };
+    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    return pick_group<T, 1>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+}
+
+}  // namespace csgs
+
+using namespace csgs;
+
+extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int32_t nS,
+                              const int32_t *n_next, const void *X_local, int64_t ld_local, int64_t rows_local,
+                              const void *X_remote, int64_t ld_remote, int64_t rows_remote, const int32_t *src_row,
+                              int32_t F, int dtype, int relu_on_input, float *Z, int64_t ldz, void *stream)
+{
+    if (!adj_rowptr || !adj_col || !adj_val || nS <= 0 || F <= 0 || rows_local < 0 || (rows_local > 0 && !X_local) ||
+        (X_local && ld_local < F) || !Z || ldz < F || (X_remote && (ld_remote < F || rows_remote < 0)))
+        return CSGS_EINVAL;
+    if (!X_remote) rows_remote = 0;
+    if (!X_local || rows_local == 0) { X_local = nullptr; rows_local = 0; ld_local = F; }
+    if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == CSGS_F32)
+        return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, n_next, X_local, ld_local, rows_local, X_remote,
+                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
+    return pick_vec<uint16_t>(adj_rowptr, adj_col, adj_val, nS, n_next, X_local, ld_local, rows_local, X_remote,
+                              ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
+}

@@ -1,0 +1,322 @@
+// csgs_sample_layer and csgs_remote_count.
+//
+// B draws with replacement from the skewed distribution (Section 4.1: the sampling is run B
+// times), deduplicated; inclusion probability p_j = 1 - (1 - q_j)^B (Eq. 8); sampled adjacency
+// with every kept edge divided by p_j (Eq. 3); number of sampled remote nodes (Eq. 4).
+//
+// Kernels:
+//   draw          one thread per draw: Philox4x32-10 word -> u = mulhi(r, total) -> first cdf
+//                 entry above u.  The top levels of the search run on a strided sample of the
+//                 CDF staged in LDS, the rest on the global array.  Hits are counted per
+//                 candidate position with integer atomics; first hits set a position bitmap.
+//   compact_hits  one block walks the bitmap: S_next ascending, mult, p_incl, node -> rank table
+//   adj_count / adj_scan / adj_fill   CSR of the sampled adjacency in the row order of S
+//   rank_clear    restores the rank table
+//   remote_count  one block
+#include <math.h>
+#include "common.hpp"
+
+namespace csgs {
+
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): each round multiplies two
+// counter words by fixed odd constants, swaps halves around and xors in the key, then the key
+// advances by two Weyl increments.
+__device__ inline uint64_t philox_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return (uint64_t)c0 | ((uint64_t)c1 << 32);
+}
+
+constexpr int DRAW_BLOCK = 1024;
+constexpr int TOP = 4096;  // CDF samples staged in LDS per block (32 KB)
+
+__global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ cdf,
+                                                   const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
+                                                   int32_t B, uint32_t seed_lo, uint32_t seed_hi, uint32_t iter_lo,
+                                                   uint32_t iter_hi, uint32_t layer, uint32_t *__restrict__ hit,
+                                                   uint64_t *__restrict__ cbitmap)
+{
+    __shared__ uint64_t top[TOP];
+    int64_t n = stats->n_cand;
+    if (n > cand_cap) n = cand_cap;
+    if (n <= 0) return;
+    const uint64_t total = cdf[n - 1];
+    if (total == 0) return;
+    // top[i] = cdf[(i + 1) * stride - 1] for the i with that index inside the array
+    const int64_t stride = (n + TOP - 1) / TOP;
+    const int64_t n_top = n / stride;  // number of complete strides
+    for (int64_t i = threadIdx.x; i < n_top; i += blockDim.x) top[i] = cdf[(i + 1) * stride - 1];
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= B) return;
+    const uint64_t r = philox_word((uint32_t)t, layer, iter_lo, iter_hi, seed_lo, seed_hi);
+    const uint64_t u = __umul64hi(r, total);
+    // first sample above u: the answer lies in stride block a
+    int64_t a = 0, b = n_top;
+    while (a < b) {
+        const int64_t m = (a + b) >> 1;
+        if (top[m] > u) b = m; else a = m + 1;
+    }
+    int64_t lo = a * stride;
+    int64_t hi = (a < n_top) ? (a + 1) * stride - 1 : n - 1;  // cdf[hi] > u is known
+    while (lo < hi) {
+        const int64_t m = (lo + hi) >> 1;
+        if (cdf[m] > u) hi = m; else lo = m + 1;
+    }
+    const uint32_t old = atomicAdd(&hit[lo], 1u);
+    if (old == 0) atomicOr((unsigned long long *)&cbitmap[lo >> 6], 1ull << (lo & 63));
+}
+
+__global__ __launch_bounds__(1024) void compact_hits(const int32_t *__restrict__ cand_id,
+                                                     const uint64_t *__restrict__ cdf,
+                                                     const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
+                                                     int64_t n_nodes, int32_t B, uint32_t *__restrict__ hit,
+                                                     uint64_t *__restrict__ cbitmap, int32_t *__restrict__ rank,
+                                                     int32_t *__restrict__ S_next, int32_t *__restrict__ mult,
+                                                     float *__restrict__ p_incl, double *__restrict__ pdbl,
+                                                     int32_t *__restrict__ n_next)
+{
+    __shared__ uint32_t lds[17];
+    int64_t n = stats->n_cand;
+    if (n > cand_cap) n = cand_cap;
+    if (n < 0) n = 0;
+    const int64_t n_words = (n + 63) / 64;
+    const double total = n > 0 ? (double)cdf[n - 1] : 1.0;
+    // contiguous run of words per thread, so that output order = ascending position
+    const int64_t per = (n_words + blockDim.x - 1) / blockDim.x;
+    const int64_t w0 = (int64_t)threadIdx.x * per;
+    const int64_t w1 = (w0 + per < n_words) ? w0 + per : n_words;
+    uint32_t cnt = 0;
+    for (int64_t w = w0; w < w1; ++w) cnt += (uint32_t)__popcll(cbitmap[w]);
+    uint32_t tot;
+    uint32_t pos = block_exclusive_scan<uint32_t>(cnt, lds, &tot);
+    for (int64_t w = w0; w < w1; ++w) {
+        uint64_t word = cbitmap[w];
+        if (!word) continue;
+        cbitmap[w] = 0ull;
+        while (word) {
+            const int bit = __ffsll((unsigned long long)word) - 1;
+            word &= word - 1;
+            const int64_t k = w * 64 + bit;
+            const uint32_t m = hit[k];
+            hit[k] = 0u;
+            if (pos < (uint32_t)B) {  // at most B distinct hits exist; guard keeps stores in bounds regardless
+                const uint64_t wk = cdf[k] - (k ? cdf[k - 1] : 0ull);
+                const double qk = (double)wk / total;
+                const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
+                const int32_t id = cand_id[k];
+                S_next[pos] = id;
+                mult[pos] = (int32_t)m;
+                p_incl[pos] = (float)pk;
+                pdbl[pos] = pk;
+                if (id >= 0 && id < n_nodes) rank[id] = (int32_t)pos + 1;
+            }
+            ++pos;
+        }
+    }
+    if (threadIdx.x == 0) *n_next = (int32_t)(tot < (uint32_t)B ? tot : (uint32_t)B);
+}
+
+__global__ __launch_bounds__(256) void adj_count(const int64_t *__restrict__ rowptr,
+                                                 const int32_t *__restrict__ colidx, int64_t n_nodes,
+                                                 const int32_t *__restrict__ S, int32_t nS,
+                                                 const int32_t *__restrict__ rank, int32_t *__restrict__ rowcnt)
+{
+    const int lane = lane_id();
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (row >= nS) return;
+    const int32_t i = S[row];
+    int32_t cnt = 0;
+    if (i >= 0 && i < n_nodes) {
+        const int64_t beg = rowptr[i], end = rowptr[i + 1];
+        for (int64_t e = beg + lane; e < end; e += WAVE) {
+            const int32_t c = colidx[e];
+            if (c >= 0 && c < n_nodes && rank[c] != 0) ++cnt;
+        }
+    }
+    cnt = wave_sum(cnt);
+    if (lane == 0) rowcnt[row] = cnt;
+}
+
+__global__ __launch_bounds__(1024) void adj_scan(const int32_t *__restrict__ rowcnt, int32_t nS,
+                                                 int32_t *__restrict__ adj_rowptr, int64_t adj_cap,
+                                                 int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
+{
+    __shared__ int64_t lds[17];
+    int64_t base = 0;
+    for (int32_t a0 = 0; a0 < nS; a0 += blockDim.x) {
+        const int32_t a = a0 + threadIdx.x;
+        const int64_t c = a < nS ? rowcnt[a] : 0;
+        int64_t tot;
+        const int64_t ex = block_exclusive_scan<int64_t>(c, lds, &tot);
+        if (a < nS) {
+            const int64_t v = base + ex;
+            adj_rowptr[a] = (int32_t)(v < 0x7FFFFFFFll ? v : 0x7FFFFFFFll);
+        }
+        base += tot;
+    }
+    if (threadIdx.x == 0) {
+        adj_rowptr[nS] = (int32_t)(base < 0x7FFFFFFFll ? base : 0x7FFFFFFFll);
+        *adj_nnz = base;
+        if (base > adj_cap || base > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
+    }
+}
+
+__global__ __launch_bounds__(256) void adj_fill(const int64_t *__restrict__ rowptr,
+                                                const int32_t *__restrict__ colidx, const float *__restrict__ val,
+                                                int64_t n_nodes, const int32_t *__restrict__ S, int32_t nS,
+                                                const int32_t *__restrict__ rank, const double *__restrict__ pdbl,
+                                                const int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
+                                                float *__restrict__ adj_val, int64_t adj_cap)
+{
+    const int lane = lane_id();
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (row >= nS) return;
+    const int32_t i = S[row];
+    if (i < 0 || i >= n_nodes) return;
+    if (adj_rowptr[row + 1] == adj_rowptr[row]) return;
+    int64_t out = adj_rowptr[row];
+    const int64_t beg = rowptr[i], end = rowptr[i + 1];
+    for (int64_t e0 = beg; e0 < end; e0 += WAVE) {  // uniform trip count: ballots need the whole wave
+        const int64_t e = e0 + lane;
+        int32_t r = 0;
+        if (e < end) {
+            const int32_t c = colidx[e];
+            if (c >= 0 && c < n_nodes) r = rank[c];
+        }
+        const uint64_t keep = __ballot(r != 0);
+        if (r != 0) {
+            const int64_t pos = out + __popcll(keep & ((1ull << lane) - 1ull));
+            if (pos < adj_cap) {
+                adj_col[pos] = r - 1;
+                adj_val[pos] = (float)((double)val[e] / pdbl[r - 1]);
+            }
+        }
+        out += __popcll(keep);
+    }
+}
+
+__global__ void rank_clear(const int32_t *__restrict__ S_next, const int32_t *__restrict__ n_next, int32_t B,
+                           int64_t n_nodes, int32_t *__restrict__ rank)
+{
+    int32_t n = *n_next;
+    if (n > B) n = B;
+    for (int32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < n; k += gridDim.x * blockDim.x) {
+        const int32_t id = S_next[k];
+        if (id >= 0 && id < n_nodes) rank[id] = 0;
+    }
+}
+
+constexpr int MAX_PARTS = 4096;
+
+__global__ __launch_bounds__(1024) void remote_count_k(const int32_t *__restrict__ S_next,
+                                                       const int32_t *__restrict__ n_next, int32_t lo, int32_t hi,
+                                                       const int32_t *__restrict__ part_bounds, int32_t P,
+                                                       int64_t *__restrict__ remote_total,
+                                                       int64_t *__restrict__ per_part, int32_t *__restrict__ src_row,
+                                                       int32_t *__restrict__ remote_ids)
+{
+    __shared__ uint32_t lds[17];
+    __shared__ uint32_t hist[MAX_PARTS];
+    const int32_t n = *n_next;
+    for (int p = threadIdx.x; p < P; p += blockDim.x) hist[p] = 0;
+    __syncthreads();
+    uint32_t base = 0;  // remote nodes before this chunk
+    for (int32_t k0 = 0; k0 < n; k0 += blockDim.x) {
+        const int32_t k = k0 + threadIdx.x;
+        int32_t j = 0;
+        uint32_t rem = 0;
+        if (k < n) {
+            j = S_next[k];
+            rem = (j < lo || j >= hi) ? 1u : 0u;
+            if (per_part) {
+                // partition of j: last p with bounds[p] <= j
+                int a = 0, b = P;
+                while (a < b) {
+                    const int m = (a + b) >> 1;
+                    if (part_bounds[m + 1] > j) b = m; else a = m + 1;
+                }
+                if (a < P && j >= part_bounds[0]) atomicAdd(&hist[a], 1u);
+            }
+        }
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan<uint32_t>(rem, lds, &tot);
+        if (k < n) {
+            if (rem) {
+                if (src_row) src_row[k] = -1 - (int32_t)(base + ex);
+                if (remote_ids) remote_ids[base + ex] = j;
+            } else if (src_row) {
+                src_row[k] = j - lo;
+            }
+        }
+        base += tot;
+    }
+    __syncthreads();
+    if (per_part)
+        for (int p = threadIdx.x; p < P; p += blockDim.x) per_part[p] = (int64_t)hist[p];
+    if (threadIdx.x == 0) *remote_total = (int64_t)base;
+}
+
+}  // namespace csgs
+
+using namespace csgs;
+
+extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
+                                 const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
+                                 uint64_t iter, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
+                                 int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
+                                 int64_t adj_cap, int64_t *adj_nnz, void *ws, size_t ws_bytes, int32_t *status,
+                                 void *stream)
+{
+    if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !S || nS <= 0 ||
+        !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next || !mult || !p_incl || !n_next || !adj_rowptr || !adj_col ||
+        !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status || ((uintptr_t)ws & 255))
+        return CSGS_EINVAL;
+    Workspace w = carve(ws, g->n_nodes, nS, B);
+    if (w.bytes > ws_bytes) return CSGS_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (cand_cap > g->n_nodes) cand_cap = g->n_nodes;  // there are never more candidates than nodes
+
+    hipLaunchKernelGGL(draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), 0, st, cdf, stats,
+                       cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32),
+                       layer, w.hit, w.cbitmap);
+    CSGS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(compact_hits, dim3(1), dim3(1024), 0, st, cand_id, cdf, stats, cand_cap, g->n_nodes, B, w.hit, w.cbitmap,
+                       w.rank, S_next, mult, p_incl, w.pdbl, n_next);
+    CSGS_LAUNCH_CHECK();
+    const unsigned row_blocks = (unsigned)(((int64_t)nS * WAVE + 255) / 256);
+    hipLaunchKernelGGL(adj_count, dim3(row_blocks), dim3(256), 0, st, g->rowptr, g->colidx, g->n_nodes, S, nS, w.rank,
+                       w.rowcnt);
+    CSGS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(adj_scan, dim3(1), dim3(1024), 0, st, w.rowcnt, nS, adj_rowptr, adj_cap, adj_nnz, status);
+    CSGS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(adj_fill, dim3(row_blocks), dim3(256), 0, st, g->rowptr, g->colidx, g->val, g->n_nodes, S, nS,
+                       w.rank, w.pdbl, adj_rowptr, adj_col, adj_val, adj_cap);
+    CSGS_LAUNCH_CHECK();
+    const unsigned clr_blocks = (unsigned)((B + 255) / 256 < 1024 ? (B + 255) / 256 : 1024);
+    hipLaunchKernelGGL(rank_clear, dim3(clr_blocks), dim3(256), 0, st, S_next, n_next, B, g->n_nodes, w.rank);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo, int32_t local_hi,
+                                 const int32_t *part_bounds, int32_t P, int64_t *remote_total, int64_t *per_part,
+                                 int32_t *src_row, int32_t *remote_ids, void *stream)
+{
+    if (!S_next || !n_next || local_lo > local_hi || !remote_total) return CSGS_EINVAL;
+    if (per_part && (!part_bounds || P <= 0)) return CSGS_EINVAL;
+    if (per_part && P > MAX_PARTS) return CSGS_EUNSUPPORTED;
+    hipLaunchKernelGGL(remote_count_k, dim3(1), dim3(1024), 0, (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
+                       part_bounds, per_part ? P : 0, remote_total, per_part, src_row, remote_ids);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}

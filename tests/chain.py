@@ -1,0 +1,156 @@
+"""Runs one sampled mini-batch through the CPU oracle and through the HIP library on the
+same seeded inputs and compares every output.  Used by the GPU parity tests and the smoke check."""
+from __future__ import annotations
+
+from types import SimpleNamespace
+
+import numpy as np
+
+import oracle
+from paper_2101_07706_amd import synth
+
+RTOL, ATOL = 1e-4, 1e-5          # fp32 aggregation and GEMM outputs (stated target of the build)
+P_RTOL = 2.5e-7                  # p_incl, adj_val: fp64 results rounded to fp32, libm differences <= 2 ulp
+
+
+def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False):
+    """Top-down sampling then bottom-up compute.  Ws: bottom layer first.  Returns per-step records."""
+    M = len(Ws)
+    steps = []
+    S = np.ascontiguousarray(S0, np.int32)
+    for l in range(M):
+        pr = oracle.build_probs(g, S, skew)
+        sm = oracle.sample_layer(g, S, pr, B, seed, it, l)
+        rc = oracle.remote_count(sm.S_next, g.local_lo, g.local_hi, g.part_bounds)
+        steps.append(SimpleNamespace(S=S, pr=pr, sm=sm, rc=rc))
+        S = sm.S_next
+    Xs = synth.to_bf16_bits(X) if bf16 else X
+    H = None
+    for l in range(M - 1, -1, -1):
+        st = steps[l]
+        W = Ws[M - 1 - l]
+        if l == M - 1:
+            X_local = Xs[g.local_lo:g.local_hi]
+            X_remote = Xs[st.rc.remote_ids]
+            st.Z = oracle.aggregate(st.sm.adj_rowptr, st.sm.adj_col, st.sm.adj_val, X_local, X_remote, st.rc.src_row)
+        else:
+            st.Z = oracle.aggregate(st.sm.adj_rowptr, st.sm.adj_col, st.sm.adj_val, H, relu_on_input=True)
+        st.H = oracle.layer_gemm(st.Z, W)
+        H = st.H
+    return steps
+
+
+def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None):
+    import torch
+    from paper_2101_07706_amd import pipeline
+    dev = torch.device("cuda:0")
+    dg = dg or pipeline.DeviceGraph(g, dev)
+    M = len(Ws)
+    nS_max = max(len(S0), B)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, dev)
+    if bf16:
+        Xd = torch.from_numpy(synth.to_bf16_bits(X).view(np.int16)).to(dev)
+    else:
+        Xd = torch.from_numpy(X).to(dev)
+    Wd = [torch.from_numpy(W).to(dev) for W in Ws]
+    steps = []
+    S = torch.from_numpy(np.ascontiguousarray(S0, np.int32)).to(dev)
+    for l in range(M):
+        Sh = S.cpu().numpy().astype(np.int64)
+        cap = adj_cap or int((g.rowptr[Sh + 1] - g.rowptr[Sh]).sum())
+        lb = pipeline.LayerBuffers(S.numel(), B, g.n_nodes, cap, dg.n_parts, dev)
+        pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lb)
+        n = int(lb.n_next.item())
+        steps.append(SimpleNamespace(S=S, lb=lb, n_next=n, status=int(lb.status.item())))
+        S = lb.S_next[:n].clone()
+    H = None
+    for l in range(M - 1, -1, -1):
+        st = steps[l]
+        lb = st.lb
+        nS = st.S.numel()
+        W = Wd[M - 1 - l]
+        Z = torch.full((nS, W.shape[0]), float("nan"), dtype=torch.float32, device=dev)
+        Hn = torch.full((nS, W.shape[1]), float("nan"), dtype=torch.float32, device=dev)
+        if l == M - 1:
+            r = int(lb.remote_total.item())
+            X_local = Xd[g.local_lo:g.local_hi]
+            X_remote = Xd[lb.remote_ids[:r].long()]      # stands in for the exchange of remote rows
+            pipeline.compute_step(lb, nS, X_local, X_remote, True, False, W, Z, Hn)
+        else:
+            pipeline.compute_step(lb, nS, H, None, False, True, W, Z, Hn)
+        st.Z, st.H = Z, Hn
+        H = Hn
+    torch.cuda.synchronize()
+    # workspace must be back in its prepared (all-zero) state
+    from paper_2101_07706_amd import csgs
+    clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0, "workspace not restored"
+    return steps, ws
+
+
+def u64(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def assert_close(got, want, rtol, atol, what):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, what
+    err = np.abs(got - want)
+    tol = atol + rtol * np.abs(want)
+    bad = err > tol
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst at {i}: "
+                             f"got {got[i]!r} want {want[i]!r} err {err[i]:.3e} tol {tol[i]:.3e}")
+    return float((err / tol).max()) if err.size else 0.0
+
+
+def compare_chain(osteps, gsteps, check_compute=True):
+    worst = {}
+    for l, (o, gs) in enumerate(zip(osteps, gsteps)):
+        lb = gs.lb
+        assert gs.status == 0, f"layer {l}: status {gs.status}"
+        st = lb.stats_host()
+        pr, sm, rc = o.pr, o.sm, o.rc
+        for k in ("n_cand", "n_local", "n_remote", "edges_scanned", "w_local", "w_remote", "total", "shift"):
+            assert int(getattr(st, k)) == int(getattr(pr, k)), f"layer {l}: stats.{k}"
+        n = pr.n_cand
+        np.testing.assert_array_equal(lb.cand_id[:n].cpu().numpy(), pr.cand_id, err_msg=f"layer {l} cand_id")
+        np.testing.assert_array_equal(u64(lb.cand_w[:n]), pr.cand_w, err_msg=f"layer {l} cand_w")
+        np.testing.assert_array_equal(u64(lb.cdf[:n]), pr.cdf, err_msg=f"layer {l} cdf")
+        qg = lb.q[:n].cpu().numpy()
+        np.testing.assert_array_equal(qg, pr.q, err_msg=f"layer {l} q")
+        # sort order of the probabilities: keys (weight desc, id asc) are integers, so exact
+        wsk_g = np.diff(np.concatenate([[np.uint64(0)], u64(lb.cdf[:n])]))
+        wsk_o = np.diff(np.concatenate([[np.uint64(0)], pr.cdf]))
+        np.testing.assert_array_equal(np.lexsort((pr.cand_id, -wsk_g.astype(np.int64))),
+                                      np.lexsort((pr.cand_id, -wsk_o.astype(np.int64))))
+        m = sm.n_next
+        assert gs.n_next == m, f"layer {l}: n_next {gs.n_next} != {m}"
+        np.testing.assert_array_equal(lb.S_next[:m].cpu().numpy(), sm.S_next, err_msg=f"layer {l} S_next")
+        np.testing.assert_array_equal(lb.mult[:m].cpu().numpy(), sm.mult, err_msg=f"layer {l} mult")
+        assert_close(lb.p_incl[:m].cpu().numpy(), sm.p_incl, P_RTOL, 0.0, f"layer {l} p_incl")
+        nS = len(o.S)
+        np.testing.assert_array_equal(lb.adj_rowptr[:nS + 1].cpu().numpy(), sm.adj_rowptr, err_msg=f"layer {l} adj_rowptr")
+        nnz = sm.adj_nnz
+        assert int(lb.adj_nnz.item()) == nnz
+        np.testing.assert_array_equal(lb.adj_col[:nnz].cpu().numpy(), sm.adj_col, err_msg=f"layer {l} adj_col")
+        assert_close(lb.adj_val[:nnz].cpu().numpy(), sm.adj_val, P_RTOL, 0.0, f"layer {l} adj_val")
+        assert int(lb.remote_total.item()) == rc.remote_total, f"layer {l} remote_total"
+        np.testing.assert_array_equal(lb.per_part.cpu().numpy(), rc.per_part, err_msg=f"layer {l} per_part")
+        np.testing.assert_array_equal(lb.src_row[:m].cpu().numpy(), rc.src_row, err_msg=f"layer {l} src_row")
+        np.testing.assert_array_equal(lb.remote_ids[:rc.remote_total].cpu().numpy(), rc.remote_ids)
+        if check_compute:
+            worst[f"Z{l}"] = assert_close(gs.Z.cpu().numpy(), o.Z, RTOL, ATOL, f"layer {l} Z")
+            worst[f"H{l}"] = assert_close(gs.H.cpu().numpy(), o.H, RTOL, ATOL, f"layer {l} H")
+    return worst
+
+
+def config_inputs(name, it=0):
+    cfg = synth.CONFIGS[name]
+    g = synth.make_graph(cfg)
+    X = synth.make_features(cfg.n_nodes, cfg.feat_dim, cfg.seed)
+    Ws = [synth.glorot_uniform(fi, fo, cfg.seed) for fi, fo in synth.layer_dims(cfg)]
+    S0 = synth.make_batch(g, cfg.batch, cfg.seed, it)
+    return cfg, g, X, Ws, S0

@@ -1,0 +1,225 @@
+"""HIP library against the CPU oracle, element by element, through the C-ABI binding.
+Integer outputs (candidates, fixed-point weights, CDF, sampled ids, multiplicities, adjacency
+structure, remote counts) must be bit-exact; fp32 aggregation and GEMM within 1e-4 rel + 1e-5 abs."""
+import sys
+
+import numpy as np
+import pytest
+
+import chain
+import oracle
+from paper_2101_07706_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2101_07706_amd import csgs
+    csgs.lib()
+    return torch.device("cuda:0")
+
+
+def run_config(name, it=0, skew=None, bf16=None):
+    cfg, g, X, Ws, S0 = chain.config_inputs(name, it)
+    skew = cfg.skew if skew is None else skew
+    bf16 = (cfg.feat_dtype == "bf16") if bf16 is None else bf16
+    say(f"[{name}] it={it} skew={skew} bf16={bf16} nnz={g.nnz}")
+    osteps = chain.oracle_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16)
+    worst = chain.compare_chain(osteps, gsteps)
+    say(f"[{name}] layers: " + ", ".join(
+        f"nS={len(o.S)} E={o.pr.edges_scanned} nc={o.pr.n_cand} n'={o.sm.n_next} nnz={o.sm.adj_nnz} rem={o.rc.remote_total}"
+        for o in osteps) + f" worst err/tol {worst}")
+
+
+def test_tiny_config(dev):
+    run_config("tiny")
+    run_config("tiny", it=3, skew=1.0)
+
+
+def test_medium_config(dev):
+    run_config("medium")
+
+
+def test_mid_config(dev):
+    run_config("mid")
+
+
+class SmallGraph:
+    """Random symmetric-normalised graph with self-loops and a few isolated (self-loop only) nodes."""
+
+    def __init__(self, n, avg_deg, seed, lo, hi, n_parts=3):
+        rng = np.random.default_rng(seed)
+        m = int(n * avg_deg / 2)
+        u = rng.integers(0, n, m)
+        v = rng.integers(0, n, m)
+        keep = u != v
+        u, v = u[keep], v[keep]
+        keys = np.unique(np.concatenate([u * n + v, v * n + u, np.arange(n) * (n + 1)]))
+        row, col = keys // n, keys % n
+        deg = np.bincount(row, minlength=n)
+        self.n_nodes = n
+        self.rowptr = np.zeros(n + 1, np.int64)
+        np.cumsum(deg, out=self.rowptr[1:])
+        self.colidx = col.astype(np.int32)
+        self.val = (1.0 / np.sqrt(deg[row].astype(np.float64) * deg[col])).astype(np.float32)
+        self.local_lo, self.local_hi = lo, hi
+        self.rownorm2_max = 1.0
+        self.part_bounds = np.array(sorted({0, lo, hi, n}), np.int32)
+
+    @property
+    def nnz(self):
+        return len(self.colidx)
+
+
+@pytest.mark.parametrize("n,avg_deg,nS,B,skew,lo,hi", [
+    (1, 0, 1, 1, 1.0, 0, 1),            # a single self-loop
+    (70, 3, 1, 5, 2.0, 10, 40),         # one row
+    (70, 3, 70, 500, 16.0, 0, 70),      # everything local, B far above the candidate count
+    (1000, 8, 65, 64, 4.0, 300, 600),   # ragged: one row more than a wavefront multiple
+    (5000, 40, 333, 257, 8.0, 0, 1250),
+    (5000, 2, 1023, 1025, 2.5, 4000, 5000),
+    (3000, 5, 17, 4100, 1.0, 1000, 1000),   # empty local range: every candidate is remote
+])
+def test_small_graphs(dev, n, avg_deg, nS, B, skew, lo, hi):
+    g = SmallGraph(n, avg_deg, seed=n + nS, lo=lo, hi=hi)
+    rng = np.random.default_rng(7)
+    S0 = rng.choice(n, size=nS, replace=False).astype(np.int32)       # unsorted on purpose
+    F = 12
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    Ws = [synth.glorot_uniform(F, 9, 1), synth.glorot_uniform(9, 6, 2)]
+    say(f"[small] n={n} nS={nS} B={B} skew={skew}")
+    osteps = chain.oracle_chain(g, X, Ws, S0, skew, B, 42, 7)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, skew, B, 42, 7)
+    chain.compare_chain(osteps, gsteps)
+
+
+def test_status_bits_and_restored_workspace(dev):
+    from paper_2101_07706_amd import csgs, pipeline
+    g = SmallGraph(500, 6, seed=1, lo=0, hi=200)
+    S = torch.from_numpy(np.arange(0, 100, dtype=np.int32)).to(dev)
+    B = 64
+    ws = pipeline.Workspace(g.n_nodes, 128, B, dev)
+    clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
+
+    def fresh(cand_cap, adj_cap):
+        return pipeline.LayerBuffers(128, B, cand_cap, adj_cap, len(g.part_bounds) - 1, dev)
+
+    # candidate capacity too small
+    dg = pipeline.DeviceGraph(g, dev)
+    lb = fresh(10, 4096)
+    pipeline.sample_step(dg, ws, S, 2.0, B, 1, 0, 0, lb)
+    torch.cuda.synchronize()
+    assert int(lb.status.item()) & csgs.ST_CAND_OVERFLOW
+    assert lb.stats_host().n_cand == oracle.build_probs(g, S.cpu().numpy(), 2.0).n_cand
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0
+    # adjacency capacity too small
+    lb = fresh(g.n_nodes, 3)
+    pipeline.sample_step(dg, ws, S, 2.0, B, 1, 0, 0, lb)
+    torch.cuda.synchronize()
+    assert int(lb.status.item()) == csgs.ST_ADJ_OVERFLOW
+    assert int(lb.adj_nnz.item()) > 3
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0
+    # a NaN edge value and an id outside the graph
+    g2 = SmallGraph(500, 6, seed=1, lo=0, hi=200)
+    g2.val = g2.val.copy()
+    g2.val[g2.rowptr[5]] = np.nan
+    dg2 = pipeline.DeviceGraph(g2, dev)
+    lb = fresh(g.n_nodes, 4096)
+    S_bad = S.clone()
+    S_bad[7] = 100000
+    pipeline.sample_step(dg2, ws, S_bad, 2.0, B, 1, 0, 0, lb)
+    torch.cuda.synchronize()
+    st = int(lb.status.item())
+    assert st & csgs.ST_BAD_EDGE_VALUE and st & csgs.ST_BAD_NODE_ID
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0
+    # rows without any edge: no candidates
+    g3 = SmallGraph(50, 0, seed=2, lo=0, hi=25)
+    g3.rowptr = np.zeros(51, np.int64)
+    g3.colidx = np.zeros(1, np.int32)
+    g3.val = np.zeros(1, np.float32)
+    dg3 = pipeline.DeviceGraph(g3, dev)
+    ws3 = pipeline.Workspace(50, 128, B, dev)
+    lb = fresh(50, 16)
+    pipeline.sample_step(dg3, ws3, S[:10].contiguous(), 2.0, B, 1, 0, 0, lb)
+    torch.cuda.synchronize()
+    assert int(lb.status.item()) & csgs.ST_EMPTY_CANDIDATES
+    assert int(lb.n_next.item()) == 0 and int(lb.adj_nnz.item()) == 0 and int(lb.remote_total.item()) == 0
+    # after all that the same workspace still gives exact results
+    lb = fresh(g.n_nodes, 4096)
+    pipeline.sample_step(dg, ws, S, 2.0, B, 1, 0, 0, lb)
+    torch.cuda.synchronize()
+    pr = oracle.build_probs(g, S.cpu().numpy(), 2.0)
+    sm = oracle.sample_layer(g, S.cpu().numpy(), pr, B, 1, 0, 0)
+    assert int(lb.status.item()) == 0
+    np.testing.assert_array_equal(lb.S_next[:sm.n_next].cpu().numpy(), sm.S_next)
+    np.testing.assert_array_equal(chain.u64(lb.cdf[:pr.n_cand]), pr.cdf)
+
+
+def _random_adj(rng, n_rows, n_cols, max_len):
+    lens = rng.integers(0, max_len + 1, n_rows)
+    lens[rng.integers(0, n_rows)] = 0
+    lens = np.minimum(lens, n_cols)
+    rowptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=rowptr[1:])
+    col = np.concatenate([np.sort(rng.choice(n_cols, size=l, replace=False)) for l in lens] + [np.zeros(0, np.int64)])
+    val = (rng.standard_normal(len(col)) * 3).astype(np.float32)
+    return rowptr, col.astype(np.int32), val
+
+
+@pytest.mark.parametrize("F,bf16", [(64, False), (128, False), (256, False), (512, False), (300, False),
+                                    (602, False), (7, False), (100, True), (100, False), (33, True), (256, True)])
+@pytest.mark.parametrize("mode", ["compact_relu", "src_row"])
+def test_aggregate_shapes(dev, F, bf16, mode):
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(F)
+    n_rows, n_cols = 777, 500
+    rowptr, col, val = _random_adj(rng, n_rows, n_cols, 150)
+    say(f"[aggregate] F={F} bf16={bf16} mode={mode} nnz={len(col)}")
+    Xl = rng.standard_normal((n_cols if mode == "compact_relu" else 900, F)).astype(np.float32)
+    Xr = rng.standard_normal((60, F)).astype(np.float32)
+    if bf16:
+        Xl_h, Xr_h = synth.to_bf16_bits(Xl), synth.to_bf16_bits(Xr)
+        Xl_d = torch.from_numpy(Xl_h.view(np.int16)).to(dev)
+        Xr_d = torch.from_numpy(Xr_h.view(np.int16)).to(dev)
+    else:
+        Xl_h, Xr_h = Xl, Xr
+        Xl_d, Xr_d = torch.from_numpy(Xl).to(dev), torch.from_numpy(Xr).to(dev)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    n_next = torch.tensor([n_cols], dtype=torch.int32, device=dev)
+    Z = torch.full((n_rows, F), float("nan"), dtype=torch.float32, device=dev)
+    if mode == "compact_relu":
+        want = oracle.aggregate(rowptr, col, val, Xl_h, relu_on_input=True)
+        csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d, None, None, True, Z)
+    else:
+        src = np.where(rng.random(n_cols) < 0.8, rng.integers(0, 900, n_cols), -1 - rng.integers(0, 60, n_cols)).astype(np.int32)
+        want = oracle.aggregate(rowptr, col, val, Xl_h, Xr_h, src)
+        csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d, Xr_d, t(src), False, Z)
+    torch.cuda.synchronize()
+    chain.assert_close(Z.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"aggregate F={F}")
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (33, 17, 5), (256, 64, 64), (1024, 128, 256), (2048, 602, 256),
+                                   (2048, 256, 41), (4096, 300, 512), (4096, 512, 100), (8192, 100, 256),
+                                   (8192, 256, 256), (8192, 256, 47), (100, 1000, 70)])
+def test_layer_gemm_shapes(dev, M, K, N):
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(M + K + N)
+    say(f"[gemm] {M}x{K}x{N}")
+    Z = rng.standard_normal((M, K)).astype(np.float32)
+    W = synth.glorot_uniform(K, N, 5)
+    want = oracle.layer_gemm(Z, W)
+    H = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    csgs.csgs_layer_gemm(torch.from_numpy(Z).to(dev), torch.from_numpy(W).to(dev), H)
+    torch.cuda.synchronize()
+    chain.assert_close(H.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"gemm {M}x{K}x{N}")
