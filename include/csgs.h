@@ -192,6 +192,19 @@ int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const floa
 int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const float *W,
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the
+ * library is bracketed by two HIP events on its stream.  csgs_profile_collect, called after the
+ * caller has synchronised, fills ms_sum[k] / launches[k] (host arrays of
+ * csgs_profile_kernel_count() entries) with the summed elapsed milliseconds and the number of
+ * launches per kernel since the last collect, and resets.  Process-wide, not thread-safe;
+ * creates HIP events on first use, so it is not for callers that may not allocate.
+ */
+int csgs_profile_enable(int on);
+int csgs_profile_kernel_count(void);
+const char *csgs_profile_kernel_name(int kernel);
+int csgs_profile_collect(double *ms_sum /*host*/, int64_t *launches /*host*/);
+
 /* Static string for a CSGS_E* code. */
 const char *csgs_strerror(int code);
 

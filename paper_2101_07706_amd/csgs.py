@@ -20,7 +20,8 @@ ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BA
 F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
-           "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror"]
+           "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
+           "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect"]
 
 
 class CsgsError(RuntimeError):
@@ -69,6 +70,10 @@ def lib():
         L.csgs_layer_gemm.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, i64, vp]
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
+        L.csgs_profile_enable.argtypes = [C.c_int]
+        L.csgs_profile_kernel_name.restype = C.c_char_p
+        L.csgs_profile_kernel_name.argtypes = [C.c_int]
+        L.csgs_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in EXPORTS:
             getattr(L, name)
         _lib = L
@@ -164,3 +169,16 @@ def csgs_layer_gemm(Z, W, H, stream=None):
     assert K == K2 and H.shape == (M, N)
     _chk(lib().csgs_layer_gemm(_ptr(Z), Z.stride(0), M, K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
                                _stream(stream)), "csgs_layer_gemm")
+
+
+def csgs_profile_enable(on: bool):
+    _chk(lib().csgs_profile_enable(1 if on else 0), "csgs_profile_enable")
+
+
+def csgs_profile_collect():
+    """{kernel name: (summed ms, launches)} since the last collect; call after synchronising."""
+    n = lib().csgs_profile_kernel_count()
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _chk(lib().csgs_profile_collect(ms, cnt), "csgs_profile_collect")
+    return {lib().csgs_profile_kernel_name(k).decode(): (ms[k], cnt[k]) for k in range(n) if cnt[k]}

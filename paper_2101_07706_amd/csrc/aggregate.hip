@@ -139,10 +139,10 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     const int rows_per_block = 256 / G;
     const unsigned blocks = (unsigned)((nS + rows_per_block - 1) / rows_per_block);
     if (relu)
-        hipLaunchKernelGGL((aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), 0, st, rp, col, val, nS, ncp, (const T *)Xl,
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp, (const T *)Xl,
                            ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
     else
-        hipLaunchKernelGGL((aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), 0, st, rp, col, val, nS, ncp,
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp,
                            (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "csgs.h"
+#include "profile.hpp"
 
 namespace csgs {
 

@@ -80,7 +80,7 @@ extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K
     if (!Z || !W || !H || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldw < Nout || ldh < Nout) return CSGS_EINVAL;
     const dim3 grid((unsigned)((Nout + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     if (grid.y > 65535u) return CSGS_EUNSUPPORTED;
-    hipLaunchKernelGGL(gemm_f32_k, grid, dim3(256), 0, (hipStream_t)stream, Z, ldz, W, ldw, H, ldh, M, Nout, K);
+    CSGS_LAUNCH(K_GEMM, gemm_f32_k, grid, dim3(256), (hipStream_t)stream, Z, ldz, W, ldw, H, ldh, M, Nout, K);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -246,7 +246,7 @@ extern "C" int csgs_workspace_init(void *ws, size_t ws_bytes, void *stream)
     if (!ws || ws_bytes == 0 || ((uintptr_t)ws & 255) || (ws_bytes & 7)) return CSGS_EINVAL;
     const size_t n = ws_bytes / 8;
     const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(fill_zero, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint64_t *)ws, n);
+    CSGS_LAUNCH(K_FILL_ZERO, fill_zero, dim3(blocks), dim3(256), (hipStream_t)stream, (uint64_t *)ws, n);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -286,16 +286,16 @@ extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t n
     const int64_t n_tiles = (g->n_nodes + CAND_TILE - 1) / CAND_TILE;
 
     const int64_t scan_blocks = ((int64_t)nS * WAVE + 255) / 256;
-    hipLaunchKernelGGL(scan_edges, dim3((unsigned)scan_blocks), dim3(256), 0, st, g->rowptr, g->colidx, g->val,
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3((unsigned)scan_blocks), dim3(256), st, g->rowptr, g->colidx, g->val,
                        g->n_nodes, S, nS, ldexp(1.0, shift), w.wtable, w.nbitmap, status);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cand_partials, dim3((unsigned)n_tiles), dim3(256), 0, st, w.wtable, w.nbitmap, n_words,
+    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.nbitmap, n_words,
                        g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cand_scan, dim3(1), dim3(1024), 0, st, w.partial, n_tiles, g->rowptr, S, nS, g->n_nodes,
+    CSGS_LAUNCH(K_CAND_SCAN, cand_scan, dim3(1), dim3(1024), st, w.partial, n_tiles, g->rowptr, S, nS, g->n_nodes,
                        shift, cap, stats, status);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cand_emit, dim3((unsigned)n_tiles), dim3(256), 0, st, w.wtable, w.nbitmap, n_words,
+    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.nbitmap, n_words,
                        g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial, stats, cand_id, cand_w, cdf, q, cap);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;

@@ -1,0 +1,74 @@
+// Per-kernel timing: every launch made while timing is enabled is bracketed by a pair of HIP
+// events on the launch stream; csgs_profile_collect() (after the caller synchronised) sums the
+// elapsed times per kernel.  Process-wide state, one thread at a time.
+#include <vector>
+#include "common.hpp"
+#include "profile.hpp"
+
+namespace csgs {
+namespace prof {
+
+bool g_enabled = false;
+
+struct Pair {
+    hipEvent_t a, b;
+    int kid;
+};
+static std::vector<Pair> g_pool;   // created once, reused
+static size_t g_used = 0;
+static bool g_open = false;
+static const size_t kMaxPairs = 1 << 16;
+
+static const char *const kNames[K_COUNT] = {"scan_edges", "cand_partials", "cand_scan", "cand_emit", "draw",
+                                            "compact_hits", "adj_count", "adj_scan", "adj_fill", "rank_clear",
+                                            "remote_count", "aggregate", "layer_gemm", "fill_zero"};
+
+void record(int kid, hipStream_t st, bool start)
+{
+    if (start) {
+        g_open = false;
+        if (g_used >= kMaxPairs) return;
+        if (g_used == g_pool.size()) {
+            Pair p;
+            if (hipEventCreate(&p.a) != hipSuccess) return;
+            if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return; }
+            g_pool.push_back(p);
+        }
+        g_pool[g_used].kid = kid;
+        if (hipEventRecord(g_pool[g_used].a, st) == hipSuccess) g_open = true;
+    } else if (g_open) {
+        (void)hipEventRecord(g_pool[g_used].b, st);
+        ++g_used;
+        g_open = false;
+    }
+}
+
+}  // namespace prof
+}  // namespace csgs
+
+using namespace csgs::prof;
+
+extern "C" int csgs_profile_enable(int on)
+{
+    g_enabled = on != 0;
+    return CSGS_OK;
+}
+
+extern "C" int csgs_profile_kernel_count(void) { return K_COUNT; }
+
+extern "C" const char *csgs_profile_kernel_name(int kid) { return (kid >= 0 && kid < K_COUNT) ? kNames[kid] : ""; }
+
+extern "C" int csgs_profile_collect(double *ms_sum, int64_t *launches)
+{
+    if (!ms_sum || !launches) return CSGS_EINVAL;
+    for (int k = 0; k < K_COUNT; ++k) { ms_sum[k] = 0.0; launches[k] = 0; }
+    for (size_t i = 0; i < g_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) == hipSuccess) {
+            ms_sum[g_pool[i].kid] += (double)ms;
+            launches[g_pool[i].kid] += 1;
+        }
+    }
+    g_used = 0;
+    return CSGS_OK;
+}

@@ -1,0 +1,31 @@
+// Optional per-kernel timing with HIP events (off by default; a measuring aid for benchmarks).
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace csgs {
+namespace prof {
+
+enum Kid {
+    K_SCAN_EDGES = 0, K_CAND_PARTIALS, K_CAND_SCAN, K_CAND_EMIT, K_DRAW, K_COMPACT_HITS, K_ADJ_COUNT, K_ADJ_SCAN,
+    K_ADJ_FILL, K_RANK_CLEAR, K_REMOTE_COUNT, K_AGGREGATE, K_GEMM, K_FILL_ZERO, K_COUNT
+};
+
+extern bool g_enabled;
+void record(int kid, hipStream_t st, bool start);
+
+struct Scope {
+    int kid;
+    hipStream_t st;
+    Scope(int k, hipStream_t s) : kid(k), st(s) { if (g_enabled) record(kid, st, true); }
+    ~Scope() { if (g_enabled) record(kid, st, false); }
+};
+
+}  // namespace prof
+}  // namespace csgs
+
+// Launch `kernel` on `stream`; when timing is enabled the launch is bracketed by two events.
+#define CSGS_LAUNCH(kid, kernel, grid, block, stream, ...)                     \
+    do {                                                                       \
+        ::csgs::prof::Scope scope_(::csgs::prof::kid, stream);                 \
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);       \
+    } while (0)

@@ -286,24 +286,24 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
     hipStream_t st = (hipStream_t)stream;
     if (cand_cap > g->n_nodes) cand_cap = g->n_nodes;  // there are never more candidates than nodes
 
-    hipLaunchKernelGGL(draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), 0, st, cdf, stats,
+    CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), st, cdf, stats,
                        cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32),
                        layer, w.hit, w.cbitmap);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(compact_hits, dim3(1), dim3(1024), 0, st, cand_id, cdf, stats, cand_cap, g->n_nodes, B, w.hit, w.cbitmap,
+    CSGS_LAUNCH(K_COMPACT_HITS, compact_hits, dim3(1), dim3(1024), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B, w.hit, w.cbitmap,
                        w.rank, S_next, mult, p_incl, w.pdbl, n_next);
     CSGS_LAUNCH_CHECK();
     const unsigned row_blocks = (unsigned)(((int64_t)nS * WAVE + 255) / 256);
-    hipLaunchKernelGGL(adj_count, dim3(row_blocks), dim3(256), 0, st, g->rowptr, g->colidx, g->n_nodes, S, nS, w.rank,
+    CSGS_LAUNCH(K_ADJ_COUNT, adj_count, dim3(row_blocks), dim3(256), st, g->rowptr, g->colidx, g->n_nodes, S, nS, w.rank,
                        w.rowcnt);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(adj_scan, dim3(1), dim3(1024), 0, st, w.rowcnt, nS, adj_rowptr, adj_cap, adj_nnz, status);
+    CSGS_LAUNCH(K_ADJ_SCAN, adj_scan, dim3(1), dim3(1024), st, w.rowcnt, nS, adj_rowptr, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(adj_fill, dim3(row_blocks), dim3(256), 0, st, g->rowptr, g->colidx, g->val, g->n_nodes, S, nS,
+    CSGS_LAUNCH(K_ADJ_FILL, adj_fill, dim3(row_blocks), dim3(256), st, g->rowptr, g->colidx, g->val, g->n_nodes, S, nS,
                        w.rank, w.pdbl, adj_rowptr, adj_col, adj_val, adj_cap);
     CSGS_LAUNCH_CHECK();
     const unsigned clr_blocks = (unsigned)((B + 255) / 256 < 1024 ? (B + 255) / 256 : 1024);
-    hipLaunchKernelGGL(rank_clear, dim3(clr_blocks), dim3(256), 0, st, S_next, n_next, B, g->n_nodes, w.rank);
+    CSGS_LAUNCH(K_RANK_CLEAR, rank_clear, dim3(clr_blocks), dim3(256), st, S_next, n_next, B, g->n_nodes, w.rank);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -315,7 +315,7 @@ extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, i
     if (!S_next || !n_next || local_lo > local_hi || !remote_total) return CSGS_EINVAL;
     if (per_part && (!part_bounds || P <= 0)) return CSGS_EINVAL;
     if (per_part && P > MAX_PARTS) return CSGS_EUNSUPPORTED;
-    hipLaunchKernelGGL(remote_count_k, dim3(1), dim3(1024), 0, (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
+    CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(1), dim3(1024), (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
                        part_bounds, per_part ? P : 0, remote_total, per_part, src_row, remote_ids);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
