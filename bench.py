@@ -66,7 +66,7 @@ def main():
     Wd = [torch.from_numpy(W).to(dev) for W in Ws]
     Sd = [torch.from_numpy(b).to(dev) for b in batches]
     nS_max = max(cfg.batch, B)
-    ws = pipeline.Workspace(g.n_nodes, nS_max, B, dev)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
     adj_cap = int(min(g.nnz, 48_000_000))
     lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
     Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
@@ -139,8 +139,8 @@ def main():
         add("scan_edges", 8 * E + 20 * nS + 8 * nc)
         add("cand_partials", N / 8 + 8 * nc)
         add("cand_emit", N / 8 + 8 * nc + 24 * nc)
-        add("adj_count", 4 * E + 20 * nS + 4 * nS)
-        add("adj_fill", 4 * E + 20 * nS + 12 * nnz)
+        add("adj_flag", 4 * E + 16 * nS + E / 8)
+        add("adj_emit", E / 8 + 16 * nS + 4 * nS + 20 * nnz)
         add("aggregate", n2 * Fi * el + 8 * nnz + 4 * (nS + 1) + 4 * nS * Fi)
         add("layer_gemm", 4 * (nS * Fi + Fi * Fo + nS * Fo))
         flops += 2.0 * nS * Fi * Fo

@@ -50,7 +50,8 @@ enum {
     CSGS_ST_BAD_EDGE_VALUE = 2,   /* a scanned edge value is NaN or infinite */
     CSGS_ST_EMPTY_CANDIDATES = 4, /* the rows of S have no edges at all */
     CSGS_ST_ADJ_OVERFLOW = 8,     /* sampled adjacency needs more than adj_cap entries */
-    CSGS_ST_BAD_NODE_ID = 16      /* an entry of S is outside [0, n_nodes) */
+    CSGS_ST_BAD_NODE_ID = 16,     /* an entry of S is outside [0, n_nodes) */
+    CSGS_ST_EDGE_OVERFLOW = 32    /* the rows of S hold more edges than the workspace was sized for */
 };
 
 enum { CSGS_F32 = 0, CSGS_BF16 = 1 };
@@ -83,8 +84,9 @@ typedef struct csgs_prob_stats {
     int32_t pad_;
 } csgs_prob_stats;
 
-/* Scratch size for graphs of n_nodes nodes, row sets up to nS_max and up to B_max draws. */
-size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max);
+/* Scratch size for graphs of n_nodes nodes, row sets up to nS_max rows holding up to edges_max
+ * edges in total (the graph's nnz is always enough), and up to B_max draws.  0 on bad input. */
+size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max);
 
 /* Size of the leading part of the workspace that is all-zero whenever no call is in flight
  * (accumulators, bitmaps, rank table); the rest is per-call scratch.  For tests and debugging. */
@@ -116,7 +118,7 @@ int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift,
  *   q        [cap] out, nullable: Eq. 10 as float = skewed weight / total
  *   stats    out, see above
  * Host errors: CSGS_EINVAL, CSGS_ERANGE (shift < 24), CSGS_EWORKSPACE.
- * Status bits: CAND_OVERFLOW, BAD_EDGE_VALUE, EMPTY_CANDIDATES, BAD_NODE_ID.
+ * Status bits: CAND_OVERFLOW, BAD_EDGE_VALUE, EMPTY_CANDIDATES, BAD_NODE_ID, EDGE_OVERFLOW.
  */
 int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float skew,
                      int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
@@ -132,14 +134,15 @@ int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
  * cdf[k] > u.  Inclusion probability p_j = 1 - (1 - q_j)^B (Eq. 8) in double.
  *
  *   cand_id, cdf, stats   as written by csgs_build_probs for the same S (device);
- *            cand_cap = the capacity those arrays were given there
+ *            cand_cap = the capacity those arrays were given there.  The call must follow that
+ *            csgs_build_probs call on the same workspace: it reuses the row offsets left there.
  *   S_next   [B] out: distinct sampled ids ascending; *n_next of them
  *   mult     [B] out: how many of the B draws hit each
  *   p_incl   [B] out: p_j as float
  *   adj_rowptr [nS+1], adj_col [adj_cap], adj_val [adj_cap], adj_nnz: out, CSR of P~ with rows in
  *            the order of S, adj_col = position in S_next (ascending within a row),
  *            adj_val = (float)((double)P_ij / p_j)
- * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE.  Status bits: ADJ_OVERFLOW.
+ * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE.  Status bits: ADJ_OVERFLOW, EDGE_OVERFLOW.
  */
 int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
                       const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcsgs.so")
 
 OK, EINVAL, EWORKSPACE, EUNSUPPORTED, ERANGE, ELAUNCH = 0, -1, -2, -3, -4, -5
 ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BAD_NODE_ID = 1, 2, 4, 8, 16
+ST_EDGE_OVERFLOW = 32
 F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
@@ -56,7 +57,7 @@ def lib():
         vp, i32, i64, u64, u32, f32, sz = (C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_uint32,
                                            C.c_float, C.c_size_t)
         L.csgs_workspace_bytes.restype = sz
-        L.csgs_workspace_bytes.argtypes = [i64, i32, i32]
+        L.csgs_workspace_bytes.argtypes = [i64, i32, i32, i64]
         L.csgs_workspace_clean_bytes.restype = sz
         L.csgs_workspace_clean_bytes.argtypes = [i64]
         L.csgs_workspace_init.argtypes = [vp, sz, vp]
@@ -106,8 +107,8 @@ def make_graph(rowptr, colidx, val, local_lo, local_hi, rownorm2_max=1.0) -> Gra
     return g
 
 
-def csgs_workspace_bytes(n_nodes, nS_max, B_max) -> int:
-    return int(lib().csgs_workspace_bytes(n_nodes, nS_max, B_max))
+def csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max) -> int:
+    return int(lib().csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max))
 
 
 def csgs_workspace_clean_bytes(n_nodes) -> int:

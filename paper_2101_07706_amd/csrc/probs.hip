@@ -2,157 +2,191 @@
 // linear weighted sampling distribution (Section 4.2, Eq. 10) as an integer CDF.
 //
 // Kernels:
-//   scan_edges     one wavefront per row of S: square each edge value exactly, round to the
-//                  fixed-point grid, add into a per-node 64-bit accumulator with integer atomics
-//                  (order-independent), mark first touches in a node bitmap
-//   cand_partials  per tile of 1024 node ids: candidate count and weight sums
+//   row_prefix     one block: degrees of the rows of S, their exclusive prefix (the flat edge
+//                  numbering), CSR start of every row, total edges
+//   scan_edges     flat over the edges of S (chunks of 1024, rows of a chunk staged in LDS, so
+//                  hub rows and short rows cost the same per edge): square each edge value
+//                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
+//                  with fire-and-forget integer atomics (order-independent); flag the 64-node
+//                  word of the target with a plain byte store
+//   cand_partials  per tile of 1024 node ids: candidate count and weight sums of flagged words
 //   cand_scan      one block: exclusive scan of the tile partials, writes the stats
-//   cand_emit      per tile: positions by bitmap popcount, inclusive wave scan of the skewed
-//                  weights -> cand_id / cand_w / cdf / q; restores the accumulator and bitmap to zero
+//   cand_emit      per tile: positions by ballot popcount, inclusive wave scan of the skewed
+//                  weights -> cand_id / cand_w / cdf / q; restores accumulator and flags to zero
 #include <math.h>
 #include "common.hpp"
 
 namespace csgs {
 
-__global__ __launch_bounds__(256) void scan_edges(const int64_t *__restrict__ rowptr,
-                                                  const int32_t *__restrict__ colidx,
-                                                  const float *__restrict__ val, int64_t n_nodes,
-                                                  const int32_t *__restrict__ S, int32_t nS, double scale,
-                                                  uint64_t *__restrict__ wtable,
-                                                  uint64_t *__restrict__ nbitmap,
+__global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
+                                                   const int32_t *__restrict__ S, int32_t nS,
+                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
+                                                   int64_t edge_cap, csgs_prob_stats *__restrict__ stats,
+                                                   int32_t *__restrict__ status)
+{
+    __shared__ int64_t lds[17];
+    int64_t base = 0;
+    bool bad = false;
+    for (int32_t a0 = 0; a0 < nS; a0 += blockDim.x) {
+        const int32_t a = a0 + threadIdx.x;
+        int64_t deg = 0, beg = 0;
+        if (a < nS) {
+            const int32_t i = S[a];
+            if (i >= 0 && i < n_nodes) {
+                beg = rowptr[i];
+                deg = rowptr[i + 1] - beg;
+                if (deg < 0) deg = 0;
+            } else {
+                bad = true;
+            }
+        }
+        int64_t tot;
+        const int64_t ex = block_exclusive_scan<int64_t>(deg, lds, &tot);
+        if (a < nS) {
+            eoff[a] = base + ex;
+            rowstart[a] = beg;
+        }
+        base += tot;
+    }
+    if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);
+    if (threadIdx.x == 0) {
+        // an edge count the workspace cannot hold is reported and treated as empty
+        if (base > edge_cap) {
+            atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
+            stats->edges_scanned = base;
+            base = 0;
+        } else {
+            stats->edges_scanned = base;
+        }
+        eoff[nS] = base;
+    }
+}
+
+__global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
+                                                  int64_t n_nodes, int32_t nS, const int64_t *__restrict__ eoff,
+                                                  const int64_t *__restrict__ rowstart, double scale,
+                                                  uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
                                                   int32_t *__restrict__ status)
 {
-    const int lane = lane_id();
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (row >= nS) return;
-    const int32_t i = S[row];
-    if (i < 0 || i >= n_nodes) {
-        if (lane == 0) atomicOr(status, CSGS_ST_BAD_NODE_ID);
-        return;
-    }
-    const int64_t beg = rowptr[i], end = rowptr[i + 1];
+    __shared__ RowSlice slice;
+    const int64_t E = eoff[nS];
     bool bad = false;
-    for (int64_t e = beg + lane; e < end; e += WAVE) {
-        const int32_t c = colidx[e];
-        const float v = val[e];
-        if (!isfinite(v) || c < 0 || c >= n_nodes) {
-            bad = true;
-            continue;
+    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
+        const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
+        stage_slice(slice, eoff, rowstart, nS, c0, c1);
+        const int32_t len = (int32_t)(c1 - c0);
+#pragma unroll
+        for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            const int32_t x = (int32_t)threadIdx.x + k * 256;
+            if (x >= len) break;
+            int32_t r;
+            const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
+            const int32_t c = colidx[e];
+            const float v = val[e];
+            if (!isfinite(v) || c < 0 || c >= n_nodes) {
+                bad = true;
+                continue;
+            }
+            const double sq = (double)v * (double)v;      // exact: 24 x 24 bit product
+            long long q = __double2ll_rn(sq * scale);     // scale is a power of two: exact, then RNE
+            if (q < 1) q = 1;                             // every candidate stays drawable
+            (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)q, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            tileflag[c >> 6] = 1;  // same value from every writer
         }
-        const double sq = (double)v * (double)v;      // exact: 24 x 24 bit product
-        long long x = __double2ll_rn(sq * scale);     // scale is a power of two: exact, then RNE
-        if (x < 1) x = 1;                             // every candidate stays drawable
-        const unsigned long long old = atomicAdd((unsigned long long *)&wtable[c], (unsigned long long)x);
-        if (old == 0) atomicOr((unsigned long long *)&nbitmap[c >> 6], 1ull << (c & 63));
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
 }
 
-struct TileSums {
-    uint32_t count, n_local;
-    uint64_t wskew, wlocal, wremote;
+// 4 running sums scanned together: candidates | local candidates (packed), skewed weight,
+// local weight, remote weight.
+struct Sums4 {
+    uint64_t cn, wsk, wl, wr;
 };
+__device__ inline Sums4 operator+(const Sums4 &a, const Sums4 &b) { return {a.cn + b.cn, a.wsk + b.wsk, a.wl + b.wl, a.wr + b.wr}; }
 
-// Loads the accumulator of node `id` if its bitmap bit is set.
-__device__ inline uint64_t node_weight(const uint64_t *wtable, uint64_t word, int lane, int64_t id)
+__device__ inline Sums4 wave_sum4(Sums4 v)
 {
-    return ((word >> lane) & 1ull) ? wtable[id] : 0ull;
+    v.cn = wave_sum(v.cn); v.wsk = wave_sum(v.wsk); v.wl = wave_sum(v.wl); v.wr = wave_sum(v.wr);
+    return v;
 }
 
 __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
-                                                     const uint64_t *__restrict__ nbitmap, int64_t n_words,
-                                                     int32_t lo, int32_t hi, uint64_t s_fx,
+                                                     const uint8_t *__restrict__ tileflag, int64_t n_words,
+                                                     int64_t n_nodes, int32_t lo, int32_t hi, uint64_t s_fx,
                                                      uint64_t *__restrict__ partial)
 {
     __shared__ uint64_t lds[4][4];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    uint64_t cnt = 0, nloc = 0, wskew = 0, wloc = 0, wrem = 0;
+    Sums4 acc = {0, 0, 0, 0};
     constexpr int WORDS = CAND_TILE / WAVE;  // 16 words per block, 4 per wave
+#pragma unroll
     for (int k = 0; k < WORDS / 4; ++k) {
         const int64_t word_idx = (int64_t)blockIdx.x * WORDS + wave * (WORDS / 4) + k;
         if (word_idx >= n_words) break;
-        const uint64_t word = nbitmap[word_idx];
-        if (word == 0) continue;
+        if (tileflag[word_idx] == 0) continue;
         const int64_t id = word_idx * 64 + lane;
-        const uint64_t w = node_weight(wtable, word, lane, id);
-        const bool local = id >= lo && id < hi;
+        const uint64_t w = id < n_nodes ? wtable[id] : 0ull;
         if (w) {
-            cnt += 1;
-            if (local) { nloc += 1; wloc += w; wskew += w * s_fx; }
-            else       { wrem += w; wskew += w * 16ull; }
+            const bool local = id >= lo && id < hi;
+            acc.cn += (1ull << 32) | (local ? 1ull : 0ull);
+            acc.wsk += w * (local ? s_fx : 16ull);
+            if (local) acc.wl += w; else acc.wr += w;
         }
     }
-    cnt = wave_sum(cnt); nloc = wave_sum(nloc); wskew = wave_sum(wskew);
-    wloc = wave_sum(wloc); wrem = wave_sum(wrem);
-    if (lane == 0) {
-        lds[wave][0] = (cnt << 32) | nloc; lds[wave][1] = wskew; lds[wave][2] = wloc; lds[wave][3] = wrem;
-    }
+    acc = wave_sum4(acc);
+    if (lane == 0) { lds[wave][0] = acc.cn; lds[wave][1] = acc.wsk; lds[wave][2] = acc.wl; lds[wave][3] = acc.wr; }
     __syncthreads();
-    if (threadIdx.x < 4) {
-        uint64_t a = lds[0][threadIdx.x], b = lds[1][threadIdx.x], c = lds[2][threadIdx.x], d = lds[3][threadIdx.x];
-        partial[(int64_t)blockIdx.x * 4 + threadIdx.x] = a + b + c + d;  // count|nloc halves cannot carry: <= 1024 each
-    }
+    if (threadIdx.x < 4)  // packed count halves cannot carry: each is at most 1024 per tile
+        partial[(int64_t)blockIdx.x * 4 + threadIdx.x] = lds[0][threadIdx.x] + lds[1][threadIdx.x] + lds[2][threadIdx.x] + lds[3][threadIdx.x];
 }
 
-__global__ __launch_bounds__(1024) void cand_scan(uint64_t *__restrict__ partial, int64_t n_tiles,
-                                                  const int64_t *__restrict__ rowptr,
-                                                  const int32_t *__restrict__ S, int32_t nS, int64_t n_nodes,
-                                                  int32_t shift, int64_t cap, csgs_prob_stats *__restrict__ stats,
+__global__ __launch_bounds__(1024) void cand_scan(uint64_t *__restrict__ partial, int64_t n_tiles, int32_t shift,
+                                                  int64_t cap, csgs_prob_stats *__restrict__ stats,
                                                   int32_t *__restrict__ status)
 {
     __shared__ uint64_t lds[17];
-    // running totals carried across chunks of 1024 tiles
-    uint64_t base_cnt = 0, base_w = 0, tot_loc = 0, tot_wloc = 0, tot_wrem = 0;
-    for (int64_t t0 = 0; t0 < n_tiles; t0 += blockDim.x) {
-        const int64_t t = t0 + threadIdx.x;
-        uint64_t cn = 0, wsk = 0, wl = 0, wr = 0;
-        if (t < n_tiles) {
-            cn = partial[t * 4 + 0]; wsk = partial[t * 4 + 1]; wl = partial[t * 4 + 2]; wr = partial[t * 4 + 3];
-        }
-        const uint64_t cnt = cn >> 32, nloc = cn & 0xFFFFFFFFull;
-        uint64_t tot;
-        const uint64_t ex_cnt = block_exclusive_scan<uint64_t>(cnt, lds, &tot);
-        const uint64_t chunk_cnt = tot;
-        const uint64_t ex_w = block_exclusive_scan<uint64_t>(wsk, lds, &tot);
-        const uint64_t chunk_w = tot;
-        block_exclusive_scan<uint64_t>(nloc, lds, &tot); tot_loc += tot;
-        block_exclusive_scan<uint64_t>(wl, lds, &tot);   tot_wloc += tot;
-        block_exclusive_scan<uint64_t>(wr, lds, &tot);   tot_wrem += tot;
-        if (t < n_tiles) {
-            partial[t * 4 + 0] = base_cnt + ex_cnt;   // candidates before this tile
-            partial[t * 4 + 1] = base_w + ex_w;       // skewed weight before this tile
-        }
-        base_cnt += chunk_cnt;
-        base_w += chunk_w;
+    // every thread owns a contiguous run of tiles
+    const int64_t per = (n_tiles + blockDim.x - 1) / blockDim.x;
+    const int64_t t0 = (int64_t)threadIdx.x * per;
+    const int64_t t1 = (t0 + per < n_tiles) ? t0 + per : n_tiles;
+    uint64_t cnt = 0, nloc = 0, wsk = 0, wl = 0, wr = 0;
+    for (int64_t t = t0; t < t1; ++t) {
+        const uint64_t cn = partial[t * 4 + 0];
+        cnt += cn >> 32; nloc += cn & 0xFFFFFFFFull;
+        wsk += partial[t * 4 + 1]; wl += partial[t * 4 + 2]; wr += partial[t * 4 + 3];
     }
-    // edges scanned = sum of the degrees of the rows of S
-    uint64_t deg = 0;
-    for (int32_t a = threadIdx.x; a < nS; a += blockDim.x) {
-        const int32_t i = S[a];
-        if (i >= 0 && i < n_nodes) deg += (uint64_t)(rowptr[i + 1] - rowptr[i]);
+    uint64_t tot_cnt, tot_w, tot_loc, tot_wl, tot_wr;
+    uint64_t ex_cnt = block_exclusive_scan<uint64_t>(cnt, lds, &tot_cnt);
+    uint64_t ex_w = block_exclusive_scan<uint64_t>(wsk, lds, &tot_w);
+    block_exclusive_scan<uint64_t>(nloc, lds, &tot_loc);
+    block_exclusive_scan<uint64_t>(wl, lds, &tot_wl);
+    block_exclusive_scan<uint64_t>(wr, lds, &tot_wr);
+    for (int64_t t = t0; t < t1; ++t) {
+        const uint64_t c = partial[t * 4 + 0] >> 32, w = partial[t * 4 + 1];
+        partial[t * 4 + 0] = ex_cnt;   // candidates before this tile
+        partial[t * 4 + 1] = ex_w;     // skewed weight before this tile
+        ex_cnt += c; ex_w += w;
     }
-    uint64_t edges;
-    block_exclusive_scan<uint64_t>(deg, lds, &edges);
     if (threadIdx.x == 0) {
-        stats->n_cand = (int64_t)base_cnt;
+        stats->n_cand = (int64_t)tot_cnt;
         stats->n_local = (int64_t)tot_loc;
-        stats->n_remote = (int64_t)(base_cnt - tot_loc);
-        stats->edges_scanned = (int64_t)edges;
-        stats->w_local = tot_wloc;
-        stats->w_remote = tot_wrem;
-        stats->total = base_w;
+        stats->n_remote = (int64_t)(tot_cnt - tot_loc);
+        stats->w_local = tot_wl;
+        stats->w_remote = tot_wr;
+        stats->total = tot_w;
         stats->shift = shift;
         stats->pad_ = 0;
         int32_t st = 0;
-        if (base_cnt == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
-        if ((int64_t)base_cnt > cap) st |= CSGS_ST_CAND_OVERFLOW;
+        if (tot_cnt == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
+        if ((int64_t)tot_cnt > cap) st |= CSGS_ST_CAND_OVERFLOW;
         if (st) atomicOr(status, st);
     }
 }
 
-__global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint64_t *__restrict__ nbitmap,
-                                                 int64_t n_words, int32_t lo, int32_t hi, uint64_t s_fx,
+__global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
+                                                 int64_t n_words, int64_t n_nodes, int32_t lo, int32_t hi, uint64_t s_fx,
                                                  const uint64_t *__restrict__ partial,
                                                  const csgs_prob_stats *__restrict__ stats,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
@@ -169,14 +203,16 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     for (int k = 0; k < WORDS / 4; ++k) {
         const int slot = wave * (WORDS / 4) + k;
         const int64_t word_idx = (int64_t)blockIdx.x * WORDS + slot;
-        uint64_t word = word_idx < n_words ? nbitmap[word_idx] : 0ull;
+        const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
         const int64_t id = word_idx * 64 + lane;
-        uint64_t wv = word ? node_weight(wtable, word, lane, id) : 0ull;
+        const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
         const bool local = id >= lo && id < hi;
         const uint64_t wsk = wv * (local ? s_fx : 16ull);
-        words[k] = word; w[k] = wv;
+        words[k] = __ballot(wv != 0);
+        w[k] = wv;
         wsk_incl[k] = wave_inclusive_scan(wsk);
-        if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(word); s_w[slot] = wsk_incl[k]; }
+        if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
+        if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
     }
     __syncthreads();
     // prefix over the 16 words of the tile (tiny: done redundantly by every thread)
@@ -203,7 +239,6 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
                     if (q) q[pos] = (float)((double)(w[k] * (local ? s_fx : 16ull)) / total);
                 }
             }
-            if (lane == 0) nbitmap[word_idx] = 0ull;
         }
         base_cnt += s_cnt[slot];
         base_w += s_w[slot];
@@ -228,16 +263,17 @@ static int ceil_log2_u64(uint64_t n)
 
 using namespace csgs;
 
-extern "C" size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max)
+extern "C" size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max)
 {
     if (n_nodes <= 0 || nS_max <= 0 || B_max <= 0) return 0;
-    return carve(nullptr, n_nodes, nS_max, B_max).bytes;
+    if (edges_max <= 0) return 0;
+    return carve(nullptr, n_nodes, nS_max, B_max, 0, edges_max).bytes;
 }
 
 extern "C" size_t csgs_workspace_clean_bytes(int64_t n_nodes)
 {
     if (n_nodes <= 0) return 0;
-    const Workspace w = carve(nullptr, n_nodes, 1, 1);
+    const Workspace w = carve(nullptr, n_nodes, 1, 1, 0, 1);
     return (size_t)((char *)w.partial - (char *)nullptr);
 }
 
@@ -279,24 +315,25 @@ extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t n
     int64_t s_fx;
     int rc = csgs_fixed_point(nS, skew, g->rownorm2_max, &shift, &s_fx);
     if (rc != CSGS_OK) return rc;
-    Workspace w = carve(ws, g->n_nodes, nS, 1);
-    if (w.bytes > ws_bytes) return CSGS_EWORKSPACE;
+    Workspace w = carve(ws, g->n_nodes, nS, 1, ws_bytes, 0);
+    if (w.fixed_bytes > ws_bytes || w.edge_cap < EDGE_TILE) return CSGS_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int64_t n_words = (g->n_nodes + 63) / 64;
     const int64_t n_tiles = (g->n_nodes + CAND_TILE - 1) / CAND_TILE;
 
-    const int64_t scan_blocks = ((int64_t)nS * WAVE + 255) / 256;
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3((unsigned)scan_blocks), dim3(256), st, g->rowptr, g->colidx, g->val,
-                       g->n_nodes, S, nS, ldexp(1.0, shift), w.wtable, w.nbitmap, status);
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, g->rowptr, g->n_nodes, S, nS, w.eoff, w.rowstart,
+                w.edge_cap, stats, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.nbitmap, n_words,
-                       g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial);
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, nS, w.eoff,
+                w.rowstart, ldexp(1.0, shift), w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_SCAN, cand_scan, dim3(1), dim3(1024), st, w.partial, n_tiles, g->rowptr, S, nS, g->n_nodes,
-                       shift, cap, stats, status);
+    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+                g->n_nodes, g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.nbitmap, n_words,
-                       g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial, stats, cand_id, cand_w, cdf, q, cap);
+    CSGS_LAUNCH(K_CAND_SCAN, cand_scan, dim3(1), dim3(1024), st, w.partial, n_tiles, shift, cap, stats, status);
+    CSGS_LAUNCH_CHECK();
+    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+                g->n_nodes, g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial, stats, cand_id, cand_w, cdf, q, cap);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -9,8 +9,14 @@
 //                 entry above u.  The top levels of the search run on a strided sample of the
 //                 CDF staged in LDS, the rest on the global array.  Hits are counted per
 //                 candidate position with integer atomics; first hits set a position bitmap.
-//   compact_hits  one block walks the bitmap: S_next ascending, mult, p_incl, node -> rank table
-//   adj_count / adj_scan / adj_fill   CSR of the sampled adjacency in the row order of S
+//   compact_hits  one block: bitmap -> ordered list of hit positions, then one thread per distinct
+//                 hit: S_next ascending, mult, p_incl, node -> rank table
+//   adj_flag      flat over the edges of S (same chunking as the weight scan): keep = the target
+//                 was sampled; keep bits per 64 edges and the kept count per chunk
+//   adj_scan      one block: exclusive scan of the chunk counts
+//   adj_emit      flat again: the kept edges in flat order ARE the CSR of P~ (rows in the order
+//                 of S, columns ascending), so position = chunk base + popcount of earlier keep
+//                 bits; row pointers are the positions at the row starts
 //   rank_clear    restores the rank table
 //   remote_count  one block
 #include <math.h>
@@ -81,9 +87,9 @@ __global__ __launch_bounds__(1024) void compact_hits(const int32_t *__restrict__
                                                      const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
                                                      int64_t n_nodes, int32_t B, uint32_t *__restrict__ hit,
                                                      uint64_t *__restrict__ cbitmap, int32_t *__restrict__ rank,
-                                                     int32_t *__restrict__ S_next, int32_t *__restrict__ mult,
-                                                     float *__restrict__ p_incl, double *__restrict__ pdbl,
-                                                     int32_t *__restrict__ n_next)
+                                                     int32_t *__restrict__ hitpos, int32_t *__restrict__ S_next,
+                                                     int32_t *__restrict__ mult, float *__restrict__ p_incl,
+                                                     double *__restrict__ pdbl, int32_t *__restrict__ n_next)
 {
     __shared__ uint32_t lds[17];
     int64_t n = stats->n_cand;
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(1024) void compact_hits(const int32_t *__restrict__
     if (n < 0) n = 0;
     const int64_t n_words = (n + 63) / 64;
     const double total = n > 0 ? (double)cdf[n - 1] : 1.0;
-    // contiguous run of words per thread, so that output order = ascending position
+    // phase 1: contiguous run of words per thread, so that list order = ascending position
     const int64_t per = (n_words + blockDim.x - 1) / blockDim.x;
     const int64_t w0 = (int64_t)threadIdx.x * per;
     const int64_t w1 = (w0 + per < n_words) ? w0 + per : n_words;
@@ -99,109 +105,168 @@ __global__ __launch_bounds__(1024) void compact_hits(const int32_t *__restrict__
     for (int64_t w = w0; w < w1; ++w) cnt += (uint32_t)__popcll(cbitmap[w]);
     uint32_t tot;
     uint32_t pos = block_exclusive_scan<uint32_t>(cnt, lds, &tot);
-    for (int64_t w = w0; w < w1; ++w) {
-        uint64_t word = cbitmap[w];
-        if (!word) continue;
-        cbitmap[w] = 0ull;
-        while (word) {
-            const int bit = __ffsll((unsigned long long)word) - 1;
-            word &= word - 1;
-            const int64_t k = w * 64 + bit;
-            const uint32_t m = hit[k];
-            hit[k] = 0u;
-            if (pos < (uint32_t)B) {  // at most B distinct hits exist; guard keeps stores in bounds regardless
-                const uint64_t wk = cdf[k] - (k ? cdf[k - 1] : 0ull);
-                const double qk = (double)wk / total;
-                const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
-                const int32_t id = cand_id[k];
-                S_next[pos] = id;
-                mult[pos] = (int32_t)m;
-                p_incl[pos] = (float)pk;
-                pdbl[pos] = pk;
-                if (id >= 0 && id < n_nodes) rank[id] = (int32_t)pos + 1;
+    if (cnt) {
+        for (int64_t w = w0; w < w1; ++w) {
+            uint64_t word = cbitmap[w];
+            if (!word) continue;
+            cbitmap[w] = 0ull;
+            while (word) {
+                const int bit = __ffsll((unsigned long long)word) - 1;
+                word &= word - 1;
+                if (pos < (uint32_t)B) hitpos[pos] = (int32_t)(w * 64 + bit);  // at most B distinct hits exist
+                ++pos;
             }
-            ++pos;
         }
     }
-    if (threadIdx.x == 0) *n_next = (int32_t)(tot < (uint32_t)B ? tot : (uint32_t)B);
+    __syncthreads();  // hitpos (global) written above is read by other threads of this block below
+    const uint32_t n_hit = tot < (uint32_t)B ? tot : (uint32_t)B;
+    // phase 2: one thread per distinct hit
+    for (uint32_t r = threadIdx.x; r < n_hit; r += blockDim.x) {
+        const int64_t k = hitpos[r];
+        const uint32_t m = hit[k];
+        hit[k] = 0u;
+        const uint64_t wk = cdf[k] - (k ? cdf[k - 1] : 0ull);
+        const double qk = (double)wk / total;
+        const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
+        const int32_t id = cand_id[k];
+        S_next[r] = id;
+        mult[r] = (int32_t)m;
+        p_incl[r] = (float)pk;
+        pdbl[r] = pk;
+        if (id >= 0 && id < n_nodes) rank[id] = (int32_t)r + 1;
+    }
+    if (threadIdx.x == 0) *n_next = (int32_t)n_hit;
 }
 
-__global__ __launch_bounds__(256) void adj_count(const int64_t *__restrict__ rowptr,
-                                                 const int32_t *__restrict__ colidx, int64_t n_nodes,
-                                                 const int32_t *__restrict__ S, int32_t nS,
-                                                 const int32_t *__restrict__ rank, int32_t *__restrict__ rowcnt)
+__global__ __launch_bounds__(256) void adj_flag(const int32_t *__restrict__ colidx, int64_t n_nodes, int32_t nS,
+                                                const int64_t *__restrict__ eoff,
+                                                const int64_t *__restrict__ rowstart,
+                                                const int32_t *__restrict__ rank, int64_t edge_cap,
+                                                uint64_t *__restrict__ keepmask, int64_t *__restrict__ chunkcnt,
+                                                int32_t *__restrict__ status)
 {
+    __shared__ RowSlice slice;
+    __shared__ int32_t wave_cnt[4];
     const int lane = lane_id();
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (row >= nS) return;
-    const int32_t i = S[row];
-    int32_t cnt = 0;
-    if (i >= 0 && i < n_nodes) {
-        const int64_t beg = rowptr[i], end = rowptr[i + 1];
-        for (int64_t e = beg + lane; e < end; e += WAVE) {
-            const int32_t c = colidx[e];
-            if (c >= 0 && c < n_nodes && rank[c] != 0) ++cnt;
-        }
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t E = eoff[nS];
+    if (E > edge_cap) {  // the per-edge scratch cannot hold this step
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
+        return;
     }
-    cnt = wave_sum(cnt);
-    if (lane == 0) rowcnt[row] = cnt;
+    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
+        const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
+        stage_slice(slice, eoff, rowstart, nS, c0, c1);
+        const int32_t len = (int32_t)(c1 - c0);
+        int32_t cnt = 0;
+        // wave w owns positions [w * 256, w * 256 + 256): four 64-edge words
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int32_t x = wave * 256 + k * 64 + lane;
+            bool keep = false;
+            if (x < len) {
+                int32_t r;
+                const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
+                const int32_t c = colidx[e];
+                keep = c >= 0 && c < n_nodes && rank[c] != 0;
+            }
+            const uint64_t m = __ballot(keep);
+            if (lane == 0) keepmask[(c0 >> 6) + wave * 4 + k] = m;
+            cnt += __popcll(m);
+        }
+        if (lane == 0) wave_cnt[wave] = cnt;
+        __syncthreads();
+        if (threadIdx.x == 0) chunkcnt[c0 / EDGE_TILE] = (int64_t)(wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3]);
+    }
 }
 
-__global__ __launch_bounds__(1024) void adj_scan(const int32_t *__restrict__ rowcnt, int32_t nS,
+// chunkbase[c] holds the kept count of chunk c on entry and the exclusive prefix on exit.
+__global__ __launch_bounds__(1024) void adj_scan(int64_t *__restrict__ chunkbase, int32_t nS,
+                                                 const int64_t *__restrict__ eoff, int64_t edge_cap,
                                                  int32_t *__restrict__ adj_rowptr, int64_t adj_cap,
                                                  int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
 {
     __shared__ int64_t lds[17];
-    int64_t base = 0;
-    for (int32_t a0 = 0; a0 < nS; a0 += blockDim.x) {
-        const int32_t a = a0 + threadIdx.x;
-        const int64_t c = a < nS ? rowcnt[a] : 0;
-        int64_t tot;
-        const int64_t ex = block_exclusive_scan<int64_t>(c, lds, &tot);
-        if (a < nS) {
-            const int64_t v = base + ex;
-            adj_rowptr[a] = (int32_t)(v < 0x7FFFFFFFll ? v : 0x7FFFFFFFll);
-        }
-        base += tot;
+    int64_t E = eoff[nS];
+    if (E > edge_cap) E = 0;
+    const int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
+    const int64_t per = (n_chunks + blockDim.x - 1) / blockDim.x;
+    const int64_t t0 = (int64_t)threadIdx.x * per;
+    const int64_t t1 = (t0 + per < n_chunks) ? t0 + per : n_chunks;
+    int64_t sum = 0;
+    for (int64_t t = t0; t < t1; ++t) sum += chunkbase[t];
+    int64_t total;
+    int64_t ex = block_exclusive_scan<int64_t>(sum, lds, &total);
+    for (int64_t t = t0; t < t1; ++t) {
+        const int64_t c = chunkbase[t];
+        chunkbase[t] = ex;
+        ex += c;
     }
+    // rows that start at or after the last edge (trailing empty rows, and the end pointer)
+    const int32_t clamp = (int32_t)(total < 0x7FFFFFFFll ? total : 0x7FFFFFFFll);
+    const int64_t first_tail = E > 0 ? lower_bound_i64(eoff, (int64_t)nS + 1, E) : 0;
+    for (int64_t a = first_tail + threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = clamp;
     if (threadIdx.x == 0) {
-        adj_rowptr[nS] = (int32_t)(base < 0x7FFFFFFFll ? base : 0x7FFFFFFFll);
-        *adj_nnz = base;
-        if (base > adj_cap || base > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
+        *adj_nnz = total;
+        if (total > adj_cap || total > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
     }
 }
 
-__global__ __launch_bounds__(256) void adj_fill(const int64_t *__restrict__ rowptr,
-                                                const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                int64_t n_nodes, const int32_t *__restrict__ S, int32_t nS,
+__global__ __launch_bounds__(256) void adj_emit(const int32_t *__restrict__ colidx, const float *__restrict__ val,
+                                                int32_t nS, const int64_t *__restrict__ eoff,
+                                                const int64_t *__restrict__ rowstart,
                                                 const int32_t *__restrict__ rank, const double *__restrict__ pdbl,
-                                                const int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
+                                                int64_t edge_cap, const uint64_t *__restrict__ keepmask,
+                                                const int64_t *__restrict__ chunkbase,
+                                                int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
                                                 float *__restrict__ adj_val, int64_t adj_cap)
 {
+    __shared__ RowSlice slice;
+    __shared__ uint64_t s_mask[EDGE_TILE / 64];
+    __shared__ int32_t s_pre[EDGE_TILE / 64 + 1];
     const int lane = lane_id();
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (row >= nS) return;
-    const int32_t i = S[row];
-    if (i < 0 || i >= n_nodes) return;
-    if (adj_rowptr[row + 1] == adj_rowptr[row]) return;
-    int64_t out = adj_rowptr[row];
-    const int64_t beg = rowptr[i], end = rowptr[i + 1];
-    for (int64_t e0 = beg; e0 < end; e0 += WAVE) {  // uniform trip count: ballots need the whole wave
-        const int64_t e = e0 + lane;
-        int32_t r = 0;
-        if (e < end) {
-            const int32_t c = colidx[e];
-            if (c >= 0 && c < n_nodes) r = rank[c];
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t E = eoff[nS];
+    if (E > edge_cap) return;
+    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
+        const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
+        stage_slice(slice, eoff, rowstart, nS, c0, c1);
+        if (threadIdx.x < EDGE_TILE / 64) s_mask[threadIdx.x] = keepmask[(c0 >> 6) + threadIdx.x];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int32_t acc = 0;
+            for (int i = 0; i < EDGE_TILE / 64; ++i) { s_pre[i] = acc; acc += __popcll(s_mask[i]); }
+            s_pre[EDGE_TILE / 64] = acc;
         }
-        const uint64_t keep = __ballot(r != 0);
-        if (r != 0) {
-            const int64_t pos = out + __popcll(keep & ((1ull << lane) - 1ull));
-            if (pos < adj_cap) {
-                adj_col[pos] = r - 1;
-                adj_val[pos] = (float)((double)val[e] / pdbl[r - 1]);
+        __syncthreads();
+        const int64_t base = chunkbase[c0 / EDGE_TILE];
+        const int32_t len = (int32_t)(c1 - c0);
+        // row pointers of the rows that start inside this chunk: kept edges before the row start
+        const int32_t R = slice.R;
+        const int64_t a_first = slice.a_first;
+        for (int32_t r = threadIdx.x; r < R; r += blockDim.x) {
+            const int64_t off = slice.in_lds ? (int64_t)slice.off[r] : eoff[a_first + r] - c0;
+            if (off >= 0 && off < len) {
+                const int64_t v = base + s_pre[off >> 6] + __popcll(s_mask[off >> 6] & ((1ull << (off & 63)) - 1ull));
+                adj_rowptr[a_first + r] = (int32_t)(v < 0x7FFFFFFFll ? v : 0x7FFFFFFFll);
             }
         }
-        out += __popcll(keep);
+        if (s_pre[EDGE_TILE / 64] == 0) continue;  // nothing kept in this chunk (uniform over the block)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int32_t word = wave * 4 + k;
+            const uint64_t m = s_mask[word];
+            if (!((m >> lane) & 1ull)) continue;
+            const int32_t x = word * 64 + lane;
+            int32_t r;
+            const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
+            const int64_t pos = base + s_pre[word] + __popcll(m & ((1ull << lane) - 1ull));
+            const int32_t rk = rank[colidx[e]];
+            if (pos < adj_cap && rk > 0) {
+                adj_col[pos] = rk - 1;
+                adj_val[pos] = (float)((double)val[e] / pdbl[rk - 1]);
+            }
+        }
     }
 }
 
@@ -281,26 +346,26 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
         !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next || !mult || !p_incl || !n_next || !adj_rowptr || !adj_col ||
         !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status || ((uintptr_t)ws & 255))
         return CSGS_EINVAL;
-    Workspace w = carve(ws, g->n_nodes, nS, B);
-    if (w.bytes > ws_bytes) return CSGS_EWORKSPACE;
+    Workspace w = carve(ws, g->n_nodes, nS, B, ws_bytes, 0);
+    if (w.fixed_bytes > ws_bytes || w.edge_cap < EDGE_TILE) return CSGS_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (cand_cap > g->n_nodes) cand_cap = g->n_nodes;  // there are never more candidates than nodes
 
     CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), st, cdf, stats,
-                       cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32),
-                       layer, w.hit, w.cbitmap);
+                cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32), layer, w.hit,
+                w.cbitmap);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_COMPACT_HITS, compact_hits, dim3(1), dim3(1024), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B, w.hit, w.cbitmap,
-                       w.rank, S_next, mult, p_incl, w.pdbl, n_next);
+    CSGS_LAUNCH(K_COMPACT_HITS, compact_hits, dim3(1), dim3(1024), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B,
+                w.hit, w.cbitmap, w.rank, w.hitpos, S_next, mult, p_incl, w.pdbl, n_next);
     CSGS_LAUNCH_CHECK();
-    const unsigned row_blocks = (unsigned)(((int64_t)nS * WAVE + 255) / 256);
-    CSGS_LAUNCH(K_ADJ_COUNT, adj_count, dim3(row_blocks), dim3(256), st, g->rowptr, g->colidx, g->n_nodes, S, nS, w.rank,
-                       w.rowcnt);
+    CSGS_LAUNCH(K_ADJ_FLAG, adj_flag, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->n_nodes, nS, w.eoff, w.rowstart,
+                w.rank, w.edge_cap, w.keepmask, w.chunkbase, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_ADJ_SCAN, adj_scan, dim3(1), dim3(1024), st, w.rowcnt, nS, adj_rowptr, adj_cap, adj_nnz, status);
+    CSGS_LAUNCH(K_ADJ_SCAN, adj_scan, dim3(1), dim3(1024), st, w.chunkbase, nS, w.eoff, w.edge_cap, adj_rowptr,
+                adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_ADJ_FILL, adj_fill, dim3(row_blocks), dim3(256), st, g->rowptr, g->colidx, g->val, g->n_nodes, S, nS,
-                       w.rank, w.pdbl, adj_rowptr, adj_col, adj_val, adj_cap);
+    CSGS_LAUNCH(K_ADJ_EMIT, adj_emit, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, nS, w.eoff, w.rowstart,
+                w.rank, w.pdbl, w.edge_cap, w.keepmask, w.chunkbase, adj_rowptr, adj_col, adj_val, adj_cap);
     CSGS_LAUNCH_CHECK();
     const unsigned clr_blocks = (unsigned)((B + 255) / 256 < 1024 ? (B + 255) / 256 : 1024);
     CSGS_LAUNCH(K_RANK_CLEAR, rank_clear, dim3(clr_blocks), dim3(256), st, S_next, n_next, B, g->n_nodes, w.rank);

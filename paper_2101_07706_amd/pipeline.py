@@ -31,8 +31,8 @@ class DeviceGraph:
 
 
 class Workspace:
-    def __init__(self, n_nodes, nS_max, B_max, device):
-        nbytes = csgs.csgs_workspace_bytes(n_nodes, nS_max, B_max)
+    def __init__(self, n_nodes, nS_max, B_max, edges_max, device):
+        nbytes = csgs.csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max)
         self.buf = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
         assert self.buf.data_ptr() % 256 == 0
         csgs.csgs_workspace_init(self.buf)

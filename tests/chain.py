@@ -47,7 +47,7 @@ def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None
     dg = dg or pipeline.DeviceGraph(g, dev)
     M = len(Ws)
     nS_max = max(len(S0), B)
-    ws = pipeline.Workspace(g.n_nodes, nS_max, B, dev)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
     if bf16:
         Xd = torch.from_numpy(synth.to_bf16_bits(X).view(np.int16)).to(dev)
     else:

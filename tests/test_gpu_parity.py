@@ -104,12 +104,47 @@ def test_small_graphs(dev, n, avg_deg, nS, B, skew, lo, hi):
     chain.compare_chain(osteps, gsteps)
 
 
+def _drop_rows(g, rows):
+    """Remove every edge of the given rows (they become empty rows; P is no longer symmetric, which
+    the method does not need)."""
+    keep = np.ones(g.nnz, bool)
+    for i in rows:
+        keep[g.rowptr[i]:g.rowptr[i + 1]] = False
+    row = np.repeat(np.arange(g.n_nodes), np.diff(g.rowptr))[keep]
+    g.colidx, g.val = g.colidx[keep], g.val[keep]
+    g.rowptr = np.zeros(g.n_nodes + 1, np.int64)
+    np.cumsum(np.bincount(row, minlength=g.n_nodes), out=g.rowptr[1:])
+
+
+@pytest.mark.parametrize("case", ["scattered", "leading_trailing", "long_run"])
+def test_empty_rows_in_S(dev, case):
+    n = 6000
+    g = SmallGraph(n, 30, seed=11, lo=1000, hi=3000)
+    rng = np.random.default_rng(3)
+    if case == "scattered":
+        empty = rng.choice(n, size=n // 2, replace=False)
+        S0 = rng.choice(n, size=700, replace=False)
+    elif case == "leading_trailing":
+        S0 = rng.choice(n, size=300, replace=False)
+        empty = np.concatenate([S0[:40], S0[-25:], S0[100:103]])
+    else:   # more consecutive empty rows than one staged slice can hold, then ordinary rows
+        S0 = rng.permutation(n)[:4000]
+        empty = S0[200:3500]
+    _drop_rows(g, empty)
+    X = rng.standard_normal((n, 8)).astype(np.float32)
+    Ws = [synth.glorot_uniform(8, 8, 1), synth.glorot_uniform(8, 4, 2)]
+    say(f"[empty rows] {case}: nnz={g.nnz}")
+    osteps = chain.oracle_chain(g, X, Ws, S0.astype(np.int32), 4.0, 300, 5, 1)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0.astype(np.int32), 4.0, 300, 5, 1)
+    chain.compare_chain(osteps, gsteps)
+
+
 def test_status_bits_and_restored_workspace(dev):
     from paper_2101_07706_amd import csgs, pipeline
     g = SmallGraph(500, 6, seed=1, lo=0, hi=200)
     S = torch.from_numpy(np.arange(0, 100, dtype=np.int32)).to(dev)
     B = 64
-    ws = pipeline.Workspace(g.n_nodes, 128, B, dev)
+    ws = pipeline.Workspace(g.n_nodes, 128, B, g.nnz, dev)
     clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
 
     def fresh(cand_cap, adj_cap):
@@ -149,7 +184,7 @@ def test_status_bits_and_restored_workspace(dev):
     g3.colidx = np.zeros(1, np.int32)
     g3.val = np.zeros(1, np.float32)
     dg3 = pipeline.DeviceGraph(g3, dev)
-    ws3 = pipeline.Workspace(50, 128, B, dev)
+    ws3 = pipeline.Workspace(50, 128, B, 64, dev)
     lb = fresh(50, 16)
     pipeline.sample_step(dg3, ws3, S[:10].contiguous(), 2.0, B, 1, 0, 0, lb)
     torch.cuda.synchronize()
