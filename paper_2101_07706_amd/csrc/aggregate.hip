@@ -50,6 +50,79 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
                    __uint_as_float(v.y & 0xFFFF0000u)}};
 }
 
+constexpr int LONG_ROW = 128;   // rows with more kept edges than this go to the block-cooperative kernel
+constexpr int UNR = 8;          // gathered rows in flight per lane
+
+// Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.
+template <typename T>
+__device__ inline void resolve_edge(int32_t e, const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
+                                    int64_t n_cols, const int32_t *__restrict__ src_row, const T *__restrict__ Xl,
+                                    int64_t ldl, int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                    const T **src, float *w)
+{
+    *src = nullptr;
+    *w = 0.f;
+    const int32_t c = adj_col[e];
+    // a column or source row outside the tables contributes nothing (keeps every load in bounds)
+    if (c >= 0 && c < n_cols) {
+        const int64_t sr = src_row ? (int64_t)src_row[c] : (int64_t)c;
+        if (sr >= 0 && sr < rows_l) {
+            *src = Xl + sr * ldl;
+            *w = adj_val[e];
+        } else if (sr < 0 && -1 - sr < rows_r) {
+            *src = Xr + (-1 - sr) * ldr;
+            *w = adj_val[e];
+        }
+    }
+}
+
+// acc += sum over the n_max staged edges (held one per lane, group base lane `gbase`) of w * x[f..f+V).
+// Loads are issued UNR at a time so that a row with many edges is not a chain of load latencies.
+template <typename T, int V, bool RELU>
+__device__ inline void accumulate_staged(double (&acc)[V], const T *src, float w, int gbase, int32_t n_here,
+                                         int32_t n_max, bool active, int32_t f)
+{
+    for (int32_t j0 = 0; j0 < n_max; j0 += UNR) {
+        Vec<V> x[UNR];
+        float wj[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int srcl = gbase + ((j0 + u) & (WAVE - 1));
+            const uint64_t pj = __shfl((uint64_t)(uintptr_t)src, srcl, WAVE);
+            wj[u] = __shfl(w, srcl, WAVE);
+            const bool ok = active && (j0 + u) < n_here && pj != 0;
+            if (ok) {
+                x[u] = load_row<T, V>(reinterpret_cast<const T *>((uintptr_t)pj) + f);
+            } else {
+                wj[u] = 0.f;
+#pragma unroll
+                for (int v = 0; v < V; ++v) x[u].x[v] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float xv = x[u].x[v];
+                if (RELU) xv = xv > 0.f ? xv : 0.f;
+                acc[v] = fma((double)wj[u], (double)xv, acc[v]);
+            }
+        }
+    }
+}
+
+template <int V>
+__device__ inline void store_row(float *z, const double (&acc)[V])
+{
+    if (V == 4)
+        *reinterpret_cast<float4 *>(z) = make_float4((float)acc[0], (float)acc[1], (float)acc[V > 2 ? 2 : 0],
+                                                     (float)acc[V > 3 ? 3 : 0]);
+    else if (V == 2)
+        *reinterpret_cast<float2 *>(z) = make_float2((float)acc[0], (float)acc[V > 1 ? 1 : 0]);
+    else
+        z[0] = (float)acc[0];
+}
+
 template <typename T, int V, int G, bool RELU>
 __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                    const int32_t *__restrict__ adj_col,
@@ -62,12 +135,16 @@ __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ a
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
     const int tid = (int)threadIdx.x;
     const int g = tid & (G - 1);  // lane within the row group
+    const int gbase = tid & (WAVE - 1) & ~(G - 1);
     const int64_t row = ((int64_t)blockIdx.x * blockDim.x + tid) / G;
-    // Rows past the end still take part in the lane broadcasts of their wavefront with an empty range.
+    // Rows past the end, and long rows (left to aggregate_long_k), take part in the lane broadcasts of
+    // their wavefront with an empty range.
     int32_t beg = 0, end = 0;
     if (row < nS) { beg = adj_rowptr[row]; end = adj_rowptr[row + 1]; }
+    const bool mine = row < nS && (end - beg) <= LONG_ROW;
+    if (!mine) end = beg;
     // trip count of the edge loop must be uniform over the wavefront when G < 64
-    int32_t len = end - beg;
+    const int32_t len = end - beg;
     int32_t maxlen = len;
     if (G < 64) {
 #pragma unroll
@@ -85,48 +162,82 @@ __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ a
         for (int32_t c0 = 0; c0 < maxlen; c0 += G) {
             // stage up to G edges of this row: one per lane
             const int32_t e = beg + c0 + g;
-            const T *src = nullptr;  // stays null for an edge that must not be read
+            const T *src = nullptr;
             float w = 0.f;
-            if (e < end) {
-                const int32_t c = adj_col[e];
-                // a column or source row outside the tables contributes nothing (keeps every load in bounds)
-                if (c >= 0 && c < n_cols) {
-                    const int64_t sr = src_row ? (int64_t)src_row[c] : (int64_t)c;
-                    if (sr >= 0 && sr < rows_l) {
-                        src = Xl + sr * ldl;
-                        w = adj_val[e];
-                    } else if (sr < 0 && -1 - sr < rows_r) {
-                        src = Xr + (-1 - sr) * ldr;
-                        w = adj_val[e];
-                    }
-                }
-            }
+            if (e < end) resolve_edge<T>(e, adj_col, adj_val, n_cols, src_row, Xl, ldl, rows_l, Xr, ldr, rows_r, &src, &w);
             const int32_t n_here = (len - c0) < G ? (len - c0) : G;  // edges of my row in this chunk (may be <= 0)
             const int32_t n_max = (maxlen - c0) < G ? (maxlen - c0) : G;
-            for (int32_t j = 0; j < n_max; ++j) {
-                const int srcl = (tid & (WAVE - 1) & ~(G - 1)) + j;
-                const uint64_t pj = __shfl((uint64_t)(uintptr_t)src, srcl, WAVE);
-                const double wj = (double)__shfl(w, srcl, WAVE);
-                if (active && j < n_here && pj) {
-                    Vec<V> x = load_row<T, V>(reinterpret_cast<const T *>((uintptr_t)pj) + f);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        float xv = x.x[v];
-                        if (RELU) xv = xv > 0.f ? xv : 0.f;
-                        acc[v] = fma(wj, (double)xv, acc[v]);
-                    }
-                }
-            }
+            accumulate_staged<T, V, RELU>(acc, src, w, gbase, n_here, n_max, active, f);
         }
-        if (active && row < nS) {
-            float *z = Z + row * ldz + f;
-            if (V == 4)
-                *reinterpret_cast<float4 *>(z) = make_float4((float)acc[0], (float)acc[1], (float)acc[V > 2 ? 2 : 0],
-                                                             (float)acc[V > 3 ? 3 : 0]);
-            else if (V == 2)
-                *reinterpret_cast<float2 *>(z) = make_float2((float)acc[0], (float)acc[V > 1 ? 1 : 0]);
-            else
-                z[0] = (float)acc[0];
+        if (active && mine) store_row<V>(Z + row * ldz + f, acc);
+    }
+}
+
+// Rows with more than LONG_ROW kept edges (hubs among the rows of S): one block of 16 wavefronts
+// per row, each wavefront takes a contiguous sixteenth of the row's edges, partial sums are added
+// in wavefront order through LDS (fixed order: the result does not depend on timing).
+template <typename T, int V, bool RELU>
+__global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restrict__ adj_rowptr,
+                                                         const int32_t *__restrict__ adj_col,
+                                                         const float *__restrict__ adj_val, int32_t nS,
+                                                         const int32_t *__restrict__ n_cols_p,
+                                                         const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
+                                                         const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                                         const int32_t *__restrict__ src_row, int32_t F,
+                                                         float *__restrict__ Z, int64_t ldz)
+{
+    __shared__ double part[16][WAVE * V];
+    __shared__ int32_t long_rows[1024];
+    __shared__ int32_t n_long;
+    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    // this block's share of the rows, searched in parallel for long ones
+    const int32_t per = (nS + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;
+    const int32_t r0 = (int32_t)blockIdx.x * per;
+    if (tid == 0) n_long = 0;
+    __syncthreads();
+    for (int32_t i = tid; i < per; i += 1024) {   // per <= 1024 is arranged by the host
+        const int32_t row = r0 + i;
+        if (row < nS && adj_rowptr[row + 1] - adj_rowptr[row] > LONG_ROW) long_rows[atomicAdd(&n_long, 1)] = row;
+    }
+    __syncthreads();
+    const int32_t cnt = n_long;
+    for (int32_t li = 0; li < cnt; ++li) {
+        const int32_t row = long_rows[li];
+        const int32_t beg = adj_rowptr[row], end = adj_rowptr[row + 1];
+        const int32_t share = (end - beg + 15) / 16;
+        const int32_t wbeg = beg + wave * share;
+        const int32_t wend = (wbeg + share < end) ? wbeg + share : end;
+        const int32_t len = wend > wbeg ? wend - wbeg : 0;
+        for (int32_t f0 = 0; f0 < F; f0 += WAVE * V) {
+            const int32_t f = f0 + lane * V;
+            const bool active = f < F;
+            double acc[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[v] = 0.0;
+            for (int32_t c0 = 0; c0 < len; c0 += WAVE) {
+                const int32_t e = wbeg + c0 + lane;
+                const T *src = nullptr;
+                float w = 0.f;
+                if (e < wend) resolve_edge<T>(e, adj_col, adj_val, n_cols, src_row, Xl, ldl, rows_l, Xr, ldr, rows_r, &src, &w);
+                const int32_t n_here = (len - c0) < WAVE ? (len - c0) : WAVE;
+                accumulate_staged<T, V, RELU>(acc, src, w, 0, n_here, n_here, active, f);
+            }
+            __syncthreads();  // part[] of the previous feature chunk / row has been read
+#pragma unroll
+            for (int v = 0; v < V; ++v) part[wave][lane * V + v] = acc[v];
+            __syncthreads();
+            if (wave == 0 && active) {
+                double sum[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) sum[v] = 0.0;
+                for (int w2 = 0; w2 < 16; ++w2) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) sum[v] += part[w2][lane * V + v];
+                }
+                store_row<V>(Z + (int64_t)row * ldz + f, sum);
+            }
         }
     }
 }
@@ -138,12 +249,22 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 {
     const int rows_per_block = 256 / G;
     const unsigned blocks = (unsigned)((nS + rows_per_block - 1) / rows_per_block);
-    if (relu)
+    // long-row kernel: every block looks at no more than 1024 rows
+    unsigned lblocks = 512;
+    if ((nS + 1023) / 1024 > (int)lblocks) lblocks = (unsigned)((nS + 1023) / 1024);
+    if (relu) {
         CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp, (const T *)Xl,
-                           ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
-    else
+                    ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+        CSGS_LAUNCH_CHECK();
+        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, true>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+    } else {
         CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp,
-                           (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+        CSGS_LAUNCH_CHECK();
+        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, false>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
+    }
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -18,6 +18,8 @@
 
 namespace csgs {
 
+constexpr int RP_ITEMS = 8;  // rows per thread and round in row_prefix
+
 __global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
                                                    const int32_t *__restrict__ S, int32_t nS,
                                                    int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
@@ -25,38 +27,55 @@ __global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ r
                                                    int32_t *__restrict__ status)
 {
     __shared__ int64_t lds[17];
-    int64_t base = 0;
+    __shared__ int32_t s_deg[1024 * RP_ITEMS];
     bool bad = false;
-    for (int32_t a0 = 0; a0 < nS; a0 += blockDim.x) {
-        const int32_t a = a0 + threadIdx.x;
-        int64_t deg = 0, beg = 0;
-        if (a < nS) {
-            const int32_t i = S[a];
-            if (i >= 0 && i < n_nodes) {
-                beg = rowptr[i];
-                deg = rowptr[i + 1] - beg;
-                if (deg < 0) deg = 0;
-            } else {
-                bad = true;
+    int64_t base = 0;
+    // rounds of 8192 rows: degrees are fetched striped (coalesced, all loads independent), handed
+    // through LDS to a blocked arrangement, and scanned with one block scan per round
+    for (int32_t r0 = 0; r0 < nS; r0 += 1024 * RP_ITEMS) {
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < RP_ITEMS; ++k) {
+            const int32_t a = r0 + k * 1024 + (int32_t)threadIdx.x;
+            int64_t deg = 0, beg = 0;
+            if (a < nS) {
+                const int32_t i = S[a];
+                if (i >= 0 && i < n_nodes) {
+                    beg = rowptr[i];
+                    deg = rowptr[i + 1] - beg;
+                    if (deg < 0 || deg > 0x7FFFFFFFll) deg = 0;
+                } else {
+                    bad = true;
+                }
+                rowstart[a] = beg;
             }
+            s_deg[k * 1024 + threadIdx.x] = (int32_t)deg;
         }
-        int64_t tot;
-        const int64_t ex = block_exclusive_scan<int64_t>(deg, lds, &tot);
-        if (a < nS) {
-            eoff[a] = base + ex;
-            rowstart[a] = beg;
+        __syncthreads();
+        int32_t d[RP_ITEMS];
+        int64_t sum = 0;
+#pragma unroll
+        for (int k = 0; k < RP_ITEMS; ++k) {
+            d[k] = s_deg[threadIdx.x * RP_ITEMS + k];
+            sum += d[k];
         }
-        base += tot;
+        int64_t total;
+        int64_t ex = base + block_exclusive_scan<int64_t>(sum, lds, &total);
+#pragma unroll
+        for (int k = 0; k < RP_ITEMS; ++k) {
+            const int32_t a = r0 + (int32_t)threadIdx.x * RP_ITEMS + k;
+            if (a < nS) eoff[a] = ex;
+            ex += d[k];
+        }
+        base += total;
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);
     if (threadIdx.x == 0) {
+        stats->edges_scanned = base;
         // an edge count the workspace cannot hold is reported and treated as empty
         if (base > edge_cap) {
             atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
-            stats->edges_scanned = base;
             base = 0;
-        } else {
-            stats->edges_scanned = base;
         }
         eoff[nS] = base;
     }

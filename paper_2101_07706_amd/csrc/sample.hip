@@ -281,8 +281,6 @@ __global__ void rank_clear(const int32_t *__restrict__ S_next, const int32_t *__
     }
 }
 
-constexpr int MAX_PARTS = 4096;
-
 __global__ __launch_bounds__(1024) void remote_count_k(const int32_t *__restrict__ S_next,
                                                        const int32_t *__restrict__ n_next, int32_t lo, int32_t hi,
                                                        const int32_t *__restrict__ part_bounds, int32_t P,
@@ -291,44 +289,47 @@ __global__ __launch_bounds__(1024) void remote_count_k(const int32_t *__restrict
                                                        int32_t *__restrict__ remote_ids)
 {
     __shared__ uint32_t lds[17];
-    __shared__ uint32_t hist[MAX_PARTS];
     const int32_t n = *n_next;
-    for (int p = threadIdx.x; p < P; p += blockDim.x) hist[p] = 0;
-    __syncthreads();
-    uint32_t base = 0;  // remote nodes before this chunk
-    for (int32_t k0 = 0; k0 < n; k0 += blockDim.x) {
-        const int32_t k = k0 + threadIdx.x;
-        int32_t j = 0;
-        uint32_t rem = 0;
-        if (k < n) {
-            j = S_next[k];
-            rem = (j < lo || j >= hi) ? 1u : 0u;
-            if (per_part) {
-                // partition of j: last p with bounds[p] <= j
-                int a = 0, b = P;
-                while (a < b) {
-                    const int m = (a + b) >> 1;
-                    if (part_bounds[m + 1] > j) b = m; else a = m + 1;
-                }
-                if (a < P && j >= part_bounds[0]) atomicAdd(&hist[a], 1u);
-            }
-        }
-        uint32_t tot;
-        const uint32_t ex = block_exclusive_scan<uint32_t>(rem, lds, &tot);
-        if (k < n) {
-            if (rem) {
-                if (src_row) src_row[k] = -1 - (int32_t)(base + ex);
-                if (remote_ids) remote_ids[base + ex] = j;
+    // every thread owns a contiguous run of the (ascending) sampled ids: one block scan in total
+    const int32_t per = (n + (int32_t)blockDim.x - 1) / (int32_t)blockDim.x;
+    const int32_t k0 = (int32_t)threadIdx.x * per;
+    const int32_t k1 = (k0 + per < n) ? k0 + per : n;
+    uint32_t rem = 0;
+    for (int32_t k = k0; k < k1; ++k) {
+        const int32_t j = S_next[k];
+        rem += (j < lo || j >= hi) ? 1u : 0u;
+    }
+    uint32_t tot;
+    uint32_t ex = block_exclusive_scan<uint32_t>(rem, lds, &tot);
+    if (src_row || remote_ids) {
+        for (int32_t k = k0; k < k1; ++k) {
+            const int32_t j = S_next[k];
+            if (j < lo || j >= hi) {
+                if (src_row) src_row[k] = -1 - (int32_t)ex;
+                if (remote_ids) remote_ids[ex] = j;
+                ++ex;
             } else if (src_row) {
                 src_row[k] = j - lo;
             }
         }
-        base += tot;
     }
-    __syncthreads();
-    if (per_part)
-        for (int p = threadIdx.x; p < P; p += blockDim.x) per_part[p] = (int64_t)hist[p];
-    if (threadIdx.x == 0) *remote_total = (int64_t)base;
+    if (threadIdx.x == 0) *remote_total = (int64_t)tot;
+    // S_next ascends, so partition p holds the ids between two lower bounds
+    if (per_part) {
+        for (int p = threadIdx.x; p < P; p += blockDim.x) {
+            int32_t cut[2];
+            for (int s = 0; s < 2; ++s) {
+                const int32_t key = part_bounds[p + s];
+                int32_t a = 0, b = n;
+                while (a < b) {
+                    const int32_t m = (a + b) >> 1;
+                    if (S_next[m] >= key) b = m; else a = m + 1;
+                }
+                cut[s] = a;
+            }
+            per_part[p] = (int64_t)(cut[1] > cut[0] ? cut[1] - cut[0] : 0);
+        }
+    }
 }
 
 }  // namespace csgs
@@ -379,7 +380,6 @@ extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, i
 {
     if (!S_next || !n_next || local_lo > local_hi || !remote_total) return CSGS_EINVAL;
     if (per_part && (!part_bounds || P <= 0)) return CSGS_EINVAL;
-    if (per_part && P > MAX_PARTS) return CSGS_EUNSUPPORTED;
     CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(1), dim3(1024), (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
                        part_bounds, per_part ? P : 0, remote_total, per_part, src_row, remote_ids);
     CSGS_LAUNCH_CHECK();
