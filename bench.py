@@ -32,6 +32,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer (scaled-up variant)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share); --gpus above 1 is not supported",
@@ -46,6 +47,9 @@ def main():
     assert torch.cuda.is_available(), "needs a GPU"
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.config]
+    if args.scale != 1:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, batch=cfg.batch * args.scale, samples=cfg.samples * args.scale)
     bf16 = cfg.feat_dtype == "bf16"
     t0 = time.time()
     g = synth.make_graph(cfg)
