@@ -189,9 +189,9 @@ int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const floa
                    const int32_t *src_row, int32_t F, int dtype, int relu_on_input, float *Z,
                    int64_t ldz, void *stream);
 
-/* H [M x Nout] = Z [M x K] W [K x Nout], all row-major fp32 (Eq. 1).  fp32 MFMA over runs of 16
- * consecutive k, the runs summed in double, one rounding to float.
- * Host errors: CSGS_EINVAL; CSGS_EUNSUPPORTED for M above 64 * 65535. */
+/* H [M x Nout] = Z [M x K] W [K x Nout], all row-major fp32 (Eq. 1).  Operands are widened to
+ * double, products accumulate in double on the matrix cores, one rounding to float.
+ * Host errors: CSGS_EINVAL; CSGS_EUNSUPPORTED when the tile count exceeds 2^30. */
 int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const float *W,
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
 

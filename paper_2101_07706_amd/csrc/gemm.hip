@@ -1,19 +1,22 @@
-// csgs_layer_gemm: H = Z W (Section 3, Eq. 1), fp32 in, fp32 out.
+// csgs_layer_gemm: H = Z W (Section 3, Eq. 1), fp32 in, fp32 out, fp64 matrix-core accumulation.
 //
-// Products and short partial sums (32 consecutive k) come from fp32 MFMA
-// (v_mfma_f32_32x32x2_f32); the partial sums are folded into double master accumulators, which
-// keeps the rounding error of a near-cancelling output below the 1e-5 absolute tolerance even
-// for K in the hundreds and products of magnitude 1 (error ~ sqrt(32 K) / 2.8 * 2^-24 * |z w|).
+// Why double: sampled rows carry 1/p_j discounts that compound over the layers, so the products
+// z*w of a near-cancelling output reach magnitude 10 and more while the tolerance is 1e-5
+// absolute.  fp32 MFMA with double master accumulators over runs of 32 k was measured to miss it
+// (5.9e-5 against 3.5e-5 allowed on one output of the largest configuration).  The operands are
+// widened to double after the LDS read (exact), products of two 24-bit mantissas are exact in
+// double, and v_mfma_f64_16x16x4_f64 accumulates in double, so the only rounding is the final
+// conversion to float.
 //
 // Block tile 128 (M) x BN (64 or 32), K chunks of 32, four wavefronts stacked along M, each
-// owning a 32 x BN strip (BN / 32 MFMA tiles that share the A operand).  Global -> register ->
-// LDS with the next chunk's loads in flight during the current chunk's MFMAs (two LDS buffers).
+// owning a 32 x BN strip = 2 x BN/16 MFMA tiles of 16 x 16.  Global -> register -> LDS with the
+// next chunk's loads in flight during the current chunk's MFMAs (two LDS buffers).
 //
-// LDS layout: A row-major [128][36], B transposed [BN][36] (k contiguous, 16-byte aligned rows
-// whose stride of 36 words spreads 16 lanes' 128-bit reads over all 64 banks).  The k order
-// inside a run of 16 is permuted -- lanes 0..31 feed k = 0..7 of the run, lanes 32..63 feed
-// k = 8..15, for both operands alike, which leaves the sum unchanged -- so that every lane
-// fetches its 8 operand values of a run with two 128-bit LDS reads.
+// LDS layout (fp32): A row-major [128][36], B transposed [BN][36] (k contiguous, 16-byte aligned
+// rows whose stride of 36 words spreads 16 lanes' 128-bit reads over all 64 banks).  The k order
+// inside a chunk is permuted -- the lane group l / 16 = g feeds k = 8 g + s at step s, for both
+// operands alike, which leaves the sum unchanged -- so that every lane fetches the 8 values it
+// needs per operand row with two 128-bit LDS reads.
 //
 // Block ids are remapped so that consecutive tiles (same rows of Z, neighbouring column tiles)
 // land on the same XCD and share its L2.
@@ -21,7 +24,7 @@
 
 namespace csgs {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BK = 32;
 constexpr int LDS_STRIDE = BK + 4;
@@ -101,12 +104,12 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, int M, int N, int K, int n_tiles_n, int n_tiles)
 {
-    constexpr int NT = BN / 32;   // MFMA tiles per wavefront
+    constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront (times 2 row tiles)
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDS_STRIDE];
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, l32 = lane & 31;
+    const int grp = lane >> 4, l16 = lane & 15;
     // XCD-aware tile order: hardware deals consecutive block ids round-robin to the 8 XCDs
     const int bid = (int)blockIdx.x;
     const int per_xcd = (n_tiles + 7) / 8;
@@ -114,69 +117,69 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM, n0 = (int64_t)(tile % n_tiles_n) * BN;
 
-    double master[NT][16];
+    doublex4 acc[2][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) master[t][i] = 0.0;
-    float4 ra[4], rb[NT];
+        for (int t = 0; t < NT; ++t) acc[r][t] = doublex4{0.0, 0.0, 0.0, 0.0};
+    float4 ra[4], rb[BN / 32];
     const int n_chunks = (K + BK - 1) / BK;
     fetch_a<VA, FULL>(A, lda, M, K, m0, 0, tid, ra);
     fetch_b<BN, FULL>(Bm, ldb, K, N, 0, n0, tid, rb);
     stash<BN>(As[0], Bs[0], tid, ra, rb);
     __syncthreads();
-    const int a_off = (wave * 32 + l32) * LDS_STRIDE + 8 * half;
-    const int b_off = l32 * LDS_STRIDE + 8 * half;
+    const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
+    const int b_off = l16 * LDS_STRIDE + 8 * grp;
     for (int c = 0; c < n_chunks; ++c) {
         const int cur = c & 1;
         if (c + 1 < n_chunks) {
             fetch_a<VA, FULL>(A, lda, M, K, m0, (c + 1) * BK, tid, ra);
             fetch_b<BN, FULL>(Bm, ldb, K, N, (c + 1) * BK, n0, tid, rb);
         }
-        floatx16 acc[NT];
+        float av[2][8], bv[NT][8];
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-#pragma unroll
-        for (int run = 0; run < 2; ++run) {   // two runs of 16 k
-            const float *ap = &As[cur][a_off + run * 16];
-            const float4 a0 = *reinterpret_cast<const float4 *>(ap), a1 = *reinterpret_cast<const float4 *>(ap + 4);
-            const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-            float bv[NT][8];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float *bp = &Bs[cur][b_off + t * 32 * LDS_STRIDE + run * 16];
-                const float4 b0 = *reinterpret_cast<const float4 *>(bp), b1 = *reinterpret_cast<const float4 *>(bp + 4);
-                bv[t][0] = b0.x; bv[t][1] = b0.y; bv[t][2] = b0.z; bv[t][3] = b0.w;
-                bv[t][4] = b1.x; bv[t][5] = b1.y; bv[t][6] = b1.z; bv[t][7] = b1.w;
-            }
-#pragma unroll
-            for (int s = 0; s < 8; ++s)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s], bv[t][s], acc[t], 0, 0, 0);
+        for (int r = 0; r < 2; ++r) {
+            const float *ap = &As[cur][a_off + r * 16 * LDS_STRIDE];
+            const float4 x = *reinterpret_cast<const float4 *>(ap), y = *reinterpret_cast<const float4 *>(ap + 4);
+            av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
+            av[r][4] = y.x; av[r][5] = y.y; av[r][6] = y.z; av[r][7] = y.w;
         }
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t) {
+            const float *bp = &Bs[cur][b_off + t * 16 * LDS_STRIDE];
+            const float4 x = *reinterpret_cast<const float4 *>(bp), y = *reinterpret_cast<const float4 *>(bp + 4);
+            bv[t][0] = x.x; bv[t][1] = x.y; bv[t][2] = x.z; bv[t][3] = x.w;
+            bv[t][4] = y.x; bv[t][5] = y.y; bv[t][6] = y.z; bv[t][7] = y.w;
+        }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) master[t][i] += (double)acc[t][i];
+        for (int s = 0; s < 8; ++s) {
+            const double a0 = (double)av[0][s], a1 = (double)av[1][s];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const double b = (double)bv[t][s];
+                acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+            }
+        }
         if (c + 1 < n_chunks) {
             stash<BN>(As[cur ^ 1], Bs[cur ^ 1], tid, ra, rb);
             __syncthreads();
         }
     }
-    // accumulator register i of lane l holds row 8 * (i / 4) + 4 * (l / 32) + i % 4, column l % 32
+    // accumulator element i of lane l holds row l / 16 + 4 * i, column l % 16 of its 16 x 16 tile
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int64_t row = m0 + wave * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-        if (FULL || row < M) {
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int64_t col = n0 + t * 32 + l32;
-                if (FULL || col < N) C[row * ldc + col] = (float)master[t][i];
+        for (int i = 0; i < 4; ++i) {
+            const int64_t row = m0 + wave * 32 + r * 16 + grp + 4 * i;
+            if (FULL || row < M) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int64_t col = n0 + t * 16 + l16;
+                    if (FULL || col < N) C[row * ldc + col] = (float)acc[r][t][i];
+                }
             }
         }
-    }
 }
 
 static int widest(const float *p, int64_t ld)

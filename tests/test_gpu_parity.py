@@ -55,6 +55,52 @@ def test_mid_config(dev):
     run_config("mid")
 
 
+_cache = {}
+
+
+def cached_inputs(name):
+    """Full-size inputs are generated once per test session."""
+    if name not in _cache:
+        _cache.clear()          # one big graph in host memory at a time
+        _cache[name] = chain.config_inputs(name)
+    return _cache[name]
+
+
+def run_full_size(name, skews, its=(0,)):
+    from paper_2101_07706_amd import pipeline
+    cfg, g, X, Ws, _ = cached_inputs(name)
+    bf16 = cfg.feat_dtype == "bf16"
+    dg = pipeline.DeviceGraph(g, torch.device("cuda:0"))
+    for skew in skews:
+        for it in its:
+            S0 = synth.make_batch(g, cfg.batch, cfg.seed, it)
+            say(f"[{name}] full size, skew={skew} it={it}")
+            osteps = chain.oracle_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16)
+            gsteps, _ = chain.gpu_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16, dg=dg)
+            worst = chain.compare_chain(osteps, gsteps)
+            say(f"[{name}] " + ", ".join(
+                f"nS={len(o.S)} E={o.pr.edges_scanned} nc={o.pr.n_cand} n'={o.sm.n_next} nnz={o.sm.adj_nnz} rem={o.rc.remote_total}"
+                for o in osteps) + f" worst err/tol {max(worst.values()):.3f}")
+    return osteps
+
+
+def test_dense_config_skew_sweep(dev):
+    """Dense-neighborhood config at full size (114 M edges), every output element by element, over
+    the skew sweep; the bottom layer's remote count must fall as the skew grows."""
+    cfg = synth.CONFIGS["dense"]
+    remote = []
+    for s in cfg.skews:
+        osteps = run_full_size("dense", [s])
+        remote.append(osteps[-1].rc.remote_total)
+    say(f"[dense] remote nodes of the bottom layer over skews {cfg.skews}: {remote}")
+    assert remote[0] > remote[-1]
+
+
+def test_large_config(dev):
+    """Large config at full size (the workload bench.py times), bf16 features, two different batches."""
+    run_full_size("large", [synth.CONFIGS["large"].skew], its=(0, 7))
+
+
 class SmallGraph:
     """Random symmetric-normalised graph with self-loops and a few isolated (self-loop only) nodes."""
 
