@@ -85,7 +85,7 @@ def main():
         rows = []
         for l in range(M):
             lb = lbs[l]
-            pipeline.sample_step(dg, ws, S, cfg.skew, B, seed, it, l, lb)
+            pipeline.sample_step(dg, ws, S, cfg.skew, B, seed, it, l, lb, want_q=False)
             n = int(lb.n_next.item())
             rows.append(S)
             S = lb.S_next[:n]
@@ -141,10 +141,8 @@ def main():
         nS, E, nc, n2, nnz, Fi, Fo, el = s["nS"], s["E"], s["nc"], s["n_next"], s["nnz"], s["F_in"], s["F_out"], s["elt"]
         add = lambda k, b: alg.__setitem__(k, alg.get(k, 0.0) + b)
         add("scan_edges", 8 * E + 20 * nS + 8 * nc)
-        add("cand_partials", N / 8 + 8 * nc)
-        add("cand_emit", N / 8 + 8 * nc + 24 * nc)
-        add("adj_flag", 4 * E + 16 * nS + E / 8)
-        add("adj_emit", E / 8 + 16 * nS + 4 * nS + 20 * nnz)
+        add("cand_fused", N / 64 + 8 * nc + 20 * nc)
+        add("adj_fused", 4 * E + 16 * nS + 4 * nS + 20 * nnz)
         add("aggregate", n2 * Fi * el + 8 * nnz + 4 * (nS + 1) + 4 * nS * Fi)
         add("layer_gemm", 4 * (nS * Fi + Fi * Fo + nS * Fo))
         flops += 2.0 * nS * Fi * Fo

@@ -22,9 +22,9 @@
  *     out of range, an empty candidate set) OR the matching CSGS_ST_* bit into the int32 word
  *     `status` (device).  The caller zeroes it and reads it when it next synchronises.  When a
  *     bit is set the outputs of that call are unspecified but every access stayed in bounds.
- *   - `ws` is scratch of at least csgs_workspace_bytes() bytes, 256-byte aligned, prepared once
- *     with csgs_workspace_init().  Every call leaves it in the prepared state.  Calls that share
- *     one workspace must be ordered on one stream.
+ *   - `ws` describes scratch memory (see csgs_workspace), prepared once with
+ *     csgs_workspace_init().  Every call leaves it ready for the next.  Calls that share one
+ *     workspace must be ordered on one stream.
  */
 #ifndef CSGS_H
 #define CSGS_H
@@ -51,7 +51,8 @@ enum {
     CSGS_ST_EMPTY_CANDIDATES = 4, /* the rows of S have no edges at all */
     CSGS_ST_ADJ_OVERFLOW = 8,     /* sampled adjacency needs more than adj_cap entries */
     CSGS_ST_BAD_NODE_ID = 16,     /* an entry of S is outside [0, n_nodes) */
-    CSGS_ST_EDGE_OVERFLOW = 32    /* the rows of S hold more edges than the workspace was sized for */
+    CSGS_ST_EDGE_OVERFLOW = 32,   /* the rows of S hold more edges than the workspace was sized for */
+    CSGS_ST_INTERNAL = 64         /* a bounded wait between blocks ran out (should not happen) */
 };
 
 enum { CSGS_F32 = 0, CSGS_BF16 = 1 };
@@ -84,16 +85,30 @@ typedef struct csgs_prob_stats {
     int32_t pad_;
 } csgs_prob_stats;
 
-/* Scratch size for graphs of n_nodes nodes, row sets up to nS_max rows holding up to edges_max
- * edges in total (the graph's nnz is always enough), and up to B_max draws.  0 on bad input. */
+/* Scratch memory of the sampling calls: a host descriptor of a caller-owned device buffer.
+ * `base` is 256-byte aligned and holds at least csgs_workspace_bytes(n_nodes, nS_max, B_max,
+ * edges_max) bytes.  The four sizes fix the layout, so they must not change while the buffer is
+ * in use (and the descriptor is used by one host thread at a time): n_nodes = nodes of the graph, nS_max = most rows a call passes, B_max = most draws,
+ * edges_max = most edges the rows of one call hold in total (the graph's nnz is always enough). */
+typedef struct csgs_workspace {
+    void *base;
+    size_t bytes;
+    int64_t n_nodes;
+    int32_t nS_max, B_max;
+    int64_t edges_max;
+    uint64_t epoch; /* owned by the library: calls made with this workspace; set to 0 before init */
+} csgs_workspace;
+
+/* Bytes needed for a workspace of these sizes; 0 on bad input. */
 size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max);
 
 /* Size of the leading part of the workspace that is all-zero whenever no call is in flight
- * (accumulators, bitmaps, rank table); the rest is per-call scratch.  For tests and debugging. */
+ * (accumulators, flags, bitmaps, rank table).  For tests and debugging. */
 size_t csgs_workspace_clean_bytes(int64_t n_nodes);
 
-/* Zero-fills the workspace (a fill kernel, safe under graph capture).  Call once per workspace. */
-int csgs_workspace_init(void *ws, size_t ws_bytes, void *stream);
+/* Zero-fills the buffer of `ws` (a fill kernel, safe under graph capture).  Call once before the
+ * first use, and again after a call was aborted.  Host errors: CSGS_EINVAL, CSGS_EWORKSPACE. */
+int csgs_workspace_init(csgs_workspace *ws /*host*/, void *stream);
 
 /* Host-only helper: the fixed-point parameters csgs_build_probs will use (see there).
  * shift and s_fx are host pointers, nullable.  Returns CSGS_EINVAL for nS <= 0, skew < 1 or
@@ -122,7 +137,7 @@ int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift,
  */
 int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float skew,
                      int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
-                     csgs_prob_stats *stats, void *ws, size_t ws_bytes, int32_t *status,
+                     csgs_prob_stats *stats, csgs_workspace *ws /*host*/, int32_t *status,
                      void *stream);
 
 /*
@@ -149,7 +164,8 @@ int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS
                       const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter, uint32_t layer,
                       int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
                       int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
-                      int64_t *adj_nnz, void *ws, size_t ws_bytes, int32_t *status, void *stream);
+                      int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
+                      void *stream);
 
 /*
  * Communication volume of the step (Eq. 4; Section 5.2 reports the number of nodes whose

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcsgs.so")
 
 OK, EINVAL, EWORKSPACE, EUNSUPPORTED, ERANGE, ELAUNCH = 0, -1, -2, -3, -4, -5
 ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BAD_NODE_ID = 1, 2, 4, 8, 16
-ST_EDGE_OVERFLOW = 32
+ST_EDGE_OVERFLOW, ST_INTERNAL = 32, 64
 F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
@@ -36,6 +36,12 @@ class Graph(C.Structure):
     _fields_ = [("n_nodes", C.c_int64), ("nnz", C.c_int64), ("rowptr", C.c_void_p),
                 ("colidx", C.c_void_p), ("val", C.c_void_p), ("local_lo", C.c_int32),
                 ("local_hi", C.c_int32), ("rownorm2_max", C.c_float)]
+
+
+class Workspace(C.Structure):
+    """csgs_workspace: host descriptor of the caller-owned scratch buffer."""
+    _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("n_nodes", C.c_int64),
+                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("epoch", C.c_uint64)]
 
 
 class ProbStats(C.Structure):
@@ -60,11 +66,11 @@ def lib():
         L.csgs_workspace_bytes.argtypes = [i64, i32, i32, i64]
         L.csgs_workspace_clean_bytes.restype = sz
         L.csgs_workspace_clean_bytes.argtypes = [i64]
-        L.csgs_workspace_init.argtypes = [vp, sz, vp]
+        L.csgs_workspace_init.argtypes = [C.POINTER(Workspace), vp]
         L.csgs_fixed_point.argtypes = [i32, f32, f32, C.POINTER(i32), C.POINTER(i64)]
-        L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, f32, vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
+        L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
-                                        vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
+                                        vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
         L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
                                      C.c_int, vp, i64, vp]
@@ -115,8 +121,15 @@ def csgs_workspace_clean_bytes(n_nodes) -> int:
     return int(lib().csgs_workspace_clean_bytes(n_nodes))
 
 
+def make_workspace(buf, n_nodes, nS_max, B_max, edges_max) -> Workspace:
+    """Descriptor for `buf` (a torch tensor of at least csgs_workspace_bytes(...) bytes)."""
+    ws = Workspace(buf.data_ptr(), buf.numel() * buf.element_size(), n_nodes, nS_max, B_max, edges_max, 0)
+    ws._keep = buf
+    return ws
+
+
 def csgs_workspace_init(ws, stream=None):
-    _chk(lib().csgs_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "csgs_workspace_init")
+    _chk(lib().csgs_workspace_init(C.byref(ws), _stream(stream)), "csgs_workspace_init")
 
 
 def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
@@ -127,8 +140,8 @@ def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
 
 def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None):
     _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
-                                _ptr(q), cand_id.numel(), _ptr(stats), _ptr(ws), ws.numel() * ws.element_size(),
-                                _ptr(status), _stream(stream)), "csgs_build_probs")
+                                _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream)),
+         "csgs_build_probs")
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
@@ -136,8 +149,7 @@ def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mul
     _chk(lib().csgs_sample_layer(C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
                                  _ptr(stats), B, seed, it, layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
-                                 _ptr(adj_nnz), _ptr(ws), ws.numel() * ws.element_size(), _ptr(status),
-                                 _stream(stream)), "csgs_sample_layer")
+                                 _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream)), "csgs_sample_layer")
 
 
 def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_total, per_part=None,

@@ -21,28 +21,42 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 // last; how many edges they can hold follows from the size the caller passed.
 constexpr int CAND_TILE = 1024;   // node ids per block in the candidate scan
 constexpr int EDGE_TILE = 1024;   // edges per chunk in the flat edge passes
-constexpr int EDGE_GRID = 2048;   // blocks of a flat edge pass (grid-stride over chunks)
+constexpr int EDGE_GRID = 2048;   // blocks of the weight scan (grid-stride over chunks, no waits between blocks)
+constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in the hit compaction
+
+// Words of workspace a single-pass scan over at most `tiles` tiles with nv sums per tile needs
+// (one tag word and nv sums per tile, and twice that per group of 64 tiles).
+__host__ __device__ inline size_t scan_state_words(int64_t tiles, int nv)
+{
+    return (size_t)(1 + nv) * (size_t)(tiles + 2 * (tiles / 64 + 2));
+}
 
 struct Workspace {
-    uint64_t *wtable;    // [n_nodes]  clean: per-node fixed-point weight accumulator
-    uint8_t *tileflag;   // [ceil(n_nodes/64)] clean: 1 = some node of this 64-id word was touched
-    int32_t *rank;       // [n_nodes]  clean: position in S_next + 1
-    uint32_t *hit;       // [n_nodes]  clean: draws per candidate position
-    uint64_t *cbitmap;   // [ceil(n_nodes/64)] clean: bit set = candidate position was drawn
-    uint64_t *partial;   // [4 * n_tiles] per-tile partial sums of the candidate scan
+    // clean: all-zero whenever no call is in flight
+    uint64_t *wtable;    // [n_nodes]  per-node fixed-point weight accumulator
+    uint8_t *tileflag;   // [ceil(n_nodes/64)] 1 = some node of this 64-id word was touched
+    uint32_t *hit;       // [n_nodes]  draws per candidate position
+    uint64_t *cbitmap;   // [ceil(n_nodes/64)] bit set = candidate position was drawn
+    // persistent: zeroed once, then never cleared; an entry counts only if it carries the tag of
+    // the current call
+    uint64_t *rank;      // [n_nodes]  (tag << 32) | (position in S_next + 1)
+    uint64_t *cand_ts;   // scan state of the candidate tiles (4 sums per tile)
+    uint64_t *hit_ts;    // scan state of the hit tiles (1 sum per tile)
+    // per call
     int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows of S
     int64_t *rowstart;   // [nS]     rowptr[S[a]]
-    int32_t *hitpos;     // [B]      candidate position of the k-th distinct hit
+    uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
     double *pdbl;        // [B]      inclusion probabilities in double
-    int64_t *chunkbase;  // [edge_chunks + 1] kept edges per chunk, then their exclusive prefix
-    uint64_t *keepmask;  // [edge_cap / 64] bit = edge survives into the sampled adjacency
-    int64_t edge_cap;    // edges the per-edge sections can hold (multiple of EDGE_TILE)
-    size_t fixed_bytes;  // everything except the per-edge sections
+    int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
+    int64_t n_tiles, hit_tiles;
+    size_t clean_bytes;  // size of the clean part
     size_t bytes;
 };
 
-// Layout for a workspace of `ws_bytes` bytes; pass ws_bytes = 0 together with edges_max to size one.
-__host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS, int64_t B, size_t ws_bytes, int64_t edges_max)
+// Layout of a workspace sized for (n_nodes, nS_max, B_max, edges_max).  Every call carves with the
+// same four numbers (they travel in the caller's csgs_workspace descriptor), so the persistent
+// parts never move.
+__host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int64_t B_max, int64_t edges_max)
 {
     Workspace w;
     size_t off = 0;
@@ -52,37 +66,51 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS, int64_t
         return (char *)base + o;
     };
     const size_t words = (size_t)(n_nodes + 63) / 64;
-    const size_t tiles = (size_t)(n_nodes + CAND_TILE - 1) / CAND_TILE;
+    w.n_tiles = (n_nodes + CAND_TILE - 1) / CAND_TILE;
+    w.hit_tiles = ((int64_t)words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
+    w.chunk_cap = (edges_max + EDGE_TILE - 1) / EDGE_TILE;
+    if (w.chunk_cap < 1) w.chunk_cap = 1;
     w.wtable = (uint64_t *)take((size_t)n_nodes * 8);
     w.tileflag = (uint8_t *)take(words);
-    w.rank = (int32_t *)take((size_t)n_nodes * 4);
     w.hit = (uint32_t *)take((size_t)n_nodes * 4);
     w.cbitmap = (uint64_t *)take(words * 8);
-    w.partial = (uint64_t *)take(tiles * 4 * 8);
-    w.eoff = (int64_t *)take((size_t)(nS + 1) * 8);
-    w.rowstart = (int64_t *)take((size_t)nS * 8);
-    w.hitpos = (int32_t *)take((size_t)B * 4);
-    w.pdbl = (double *)take((size_t)B * 8);
-    w.fixed_bytes = off;
-    // per-edge part: 8 bytes per chunk (+1 entry) and 1 bit per edge
-    auto per_edge_bytes = [](int64_t chunks) {
-        return align_up((size_t)(chunks + 1) * 8, 256) + align_up((size_t)chunks * (EDGE_TILE / 8), 256);
-    };
-    int64_t chunks;
-    if (ws_bytes == 0) {
-        chunks = (edges_max + EDGE_TILE - 1) / EDGE_TILE;
-        if (chunks < 1) chunks = 1;
-    } else {
-        // largest chunk count that fits (per_edge_bytes is monotone; 136 bytes per chunk plus padding)
-        const size_t room = ws_bytes > off ? ws_bytes - off : 0;
-        chunks = (int64_t)(room / (8 + EDGE_TILE / 8));
-        while (chunks > 0 && per_edge_bytes(chunks) > room) --chunks;
-    }
-    w.chunkbase = (int64_t *)take((size_t)(chunks + 1) * 8);
-    w.keepmask = (uint64_t *)take((size_t)chunks * (EDGE_TILE / 8));
-    w.edge_cap = chunks * EDGE_TILE;
+    w.clean_bytes = off;
+    w.rank = (uint64_t *)take((size_t)n_nodes * 8);
+    w.cand_ts = (uint64_t *)take(scan_state_words(w.n_tiles, 4) * 8);
+    w.hit_ts = (uint64_t *)take(scan_state_words(w.hit_tiles, 1) * 8);
+    w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
+    w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
+    w.rowstart = (int64_t *)take((size_t)nS_max * 8);
+    w.pdbl = (double *)take((size_t)B_max * 8);
     w.bytes = off;
     return w;
+}
+
+// Checks a descriptor against a call's sizes and carves it.  Returns CSGS_OK or an error code.
+__host__ inline int open_workspace(csgs_workspace *d, int64_t n_nodes, int64_t nS, int64_t B, Workspace *out)
+{
+    if (!d || !d->base || ((uintptr_t)d->base & 255) || d->n_nodes != n_nodes || d->nS_max <= 0 || d->B_max <= 0 ||
+        d->edges_max <= 0)
+        return CSGS_EINVAL;
+    if (nS > d->nS_max || B > d->B_max) return CSGS_EWORKSPACE;
+    *out = carve(d->base, d->n_nodes, d->nS_max, d->B_max, d->edges_max);
+    return out->bytes <= d->bytes ? CSGS_OK : CSGS_EWORKSPACE;
+}
+
+// Blocks of 256 threads that are certainly resident at the same time on the current device: two
+// per compute unit (far below what registers and LDS of these kernels allow).  Kernels whose blocks
+// wait for each other never launch more.
+__host__ inline int resident_grid()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 64;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 32;
+        cached[dev] = 2 * cus;
+    }
+    return cached[dev];
 }
 
 // ---------------------------------------------------------------- wave helpers

@@ -9,12 +9,15 @@
 //                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
 //                  with fire-and-forget integer atomics (order-independent); flag the 64-node
 //                  word of the target with a plain byte store
-//   cand_partials  per tile of 1024 node ids: candidate count and weight sums of flagged words
-//   cand_scan      one block: exclusive scan of the tile partials, writes the stats
-//   cand_emit      per tile: positions by ballot popcount, inclusive wave scan of the skewed
-//                  weights -> cand_id / cand_w / cdf / q; restores accumulator and flags to zero
+//   cand_fused     per tile of 1024 node ids, single pass: candidate count and weight sums of the
+//                  flagged words, prefix over earlier tiles by decoupled look-back, positions by
+//                  ballot popcount, inclusive wave scan of the skewed weights -> cand_id / cand_w /
+//                  cdf; restores accumulator and flags to zero; the last tile writes the stats
+//   fill_q         only when q is requested: skewed weight / total (the total is known only after
+//                  the last tile)
 #include <math.h>
 #include "common.hpp"
+#include "lookback.hpp"
 
 namespace csgs {
 
@@ -117,150 +120,112 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
 }
 
-// 4 running sums scanned together: candidates | local candidates (packed), skewed weight,
-// local weight, remote weight.
-struct Sums4 {
-    uint64_t cn, wsk, wl, wr;
-};
-__device__ inline Sums4 operator+(const Sums4 &a, const Sums4 &b) { return {a.cn + b.cn, a.wsk + b.wsk, a.wl + b.wl, a.wr + b.wr}; }
-
-__device__ inline Sums4 wave_sum4(Sums4 v)
+__global__ __launch_bounds__(256) void cand_fused(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
+                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
+                                                  int32_t hi, uint64_t s_fx, unsigned long long tag,
+                                                  uint64_t *__restrict__ ts_mem, int32_t shift,
+                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
+                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
+                                                  uint64_t *__restrict__ cdf, int64_t cap)
 {
-    v.cn = wave_sum(v.cn); v.wsk = wave_sum(v.wsk); v.wl = wave_sum(v.wl); v.wr = wave_sum(v.wr);
-    return v;
-}
-
-__global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
-                                                     const uint8_t *__restrict__ tileflag, int64_t n_words,
-                                                     int64_t n_nodes, int32_t lo, int32_t hi, uint64_t s_fx,
-                                                     uint64_t *__restrict__ partial)
-{
-    __shared__ uint64_t lds[4][4];
-    const int lane = lane_id();
-    const int wave = (int)(threadIdx.x >> 6);
-    Sums4 acc = {0, 0, 0, 0};
-    constexpr int WORDS = CAND_TILE / WAVE;  // 16 words per block, 4 per wave
-#pragma unroll
-    for (int k = 0; k < WORDS / 4; ++k) {
-        const int64_t word_idx = (int64_t)blockIdx.x * WORDS + wave * (WORDS / 4) + k;
-        if (word_idx >= n_words) break;
-        if (tileflag[word_idx] == 0) continue;
-        const int64_t id = word_idx * 64 + lane;
-        const uint64_t w = id < n_nodes ? wtable[id] : 0ull;
-        if (w) {
-            const bool local = id >= lo && id < hi;
-            acc.cn += (1ull << 32) | (local ? 1ull : 0ull);
-            acc.wsk += w * (local ? s_fx : 16ull);
-            if (local) acc.wl += w; else acc.wr += w;
-        }
-    }
-    acc = wave_sum4(acc);
-    if (lane == 0) { lds[wave][0] = acc.cn; lds[wave][1] = acc.wsk; lds[wave][2] = acc.wl; lds[wave][3] = acc.wr; }
-    __syncthreads();
-    if (threadIdx.x < 4)  // packed count halves cannot carry: each is at most 1024 per tile
-        partial[(int64_t)blockIdx.x * 4 + threadIdx.x] = lds[0][threadIdx.x] + lds[1][threadIdx.x] + lds[2][threadIdx.x] + lds[3][threadIdx.x];
-}
-
-__global__ __launch_bounds__(1024) void cand_scan(uint64_t *__restrict__ partial, int64_t n_tiles, int32_t shift,
-                                                  int64_t cap, csgs_prob_stats *__restrict__ stats,
-                                                  int32_t *__restrict__ status)
-{
-    __shared__ uint64_t lds[17];
-    // every thread owns a contiguous run of tiles
-    const int64_t per = (n_tiles + blockDim.x - 1) / blockDim.x;
-    const int64_t t0 = (int64_t)threadIdx.x * per;
-    const int64_t t1 = (t0 + per < n_tiles) ? t0 + per : n_tiles;
-    uint64_t cnt = 0, nloc = 0, wsk = 0, wl = 0, wr = 0;
-    for (int64_t t = t0; t < t1; ++t) {
-        const uint64_t cn = partial[t * 4 + 0];
-        cnt += cn >> 32; nloc += cn & 0xFFFFFFFFull;
-        wsk += partial[t * 4 + 1]; wl += partial[t * 4 + 2]; wr += partial[t * 4 + 3];
-    }
-    uint64_t tot_cnt, tot_w, tot_loc, tot_wl, tot_wr;
-    uint64_t ex_cnt = block_exclusive_scan<uint64_t>(cnt, lds, &tot_cnt);
-    uint64_t ex_w = block_exclusive_scan<uint64_t>(wsk, lds, &tot_w);
-    block_exclusive_scan<uint64_t>(nloc, lds, &tot_loc);
-    block_exclusive_scan<uint64_t>(wl, lds, &tot_wl);
-    block_exclusive_scan<uint64_t>(wr, lds, &tot_wr);
-    for (int64_t t = t0; t < t1; ++t) {
-        const uint64_t c = partial[t * 4 + 0] >> 32, w = partial[t * 4 + 1];
-        partial[t * 4 + 0] = ex_cnt;   // candidates before this tile
-        partial[t * 4 + 1] = ex_w;     // skewed weight before this tile
-        ex_cnt += c; ex_w += w;
-    }
-    if (threadIdx.x == 0) {
-        stats->n_cand = (int64_t)tot_cnt;
-        stats->n_local = (int64_t)tot_loc;
-        stats->n_remote = (int64_t)(tot_cnt - tot_loc);
-        stats->w_local = tot_wl;
-        stats->w_remote = tot_wr;
-        stats->total = tot_w;
-        stats->shift = shift;
-        stats->pad_ = 0;
-        int32_t st = 0;
-        if (tot_cnt == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
-        if ((int64_t)tot_cnt > cap) st |= CSGS_ST_CAND_OVERFLOW;
-        if (st) atomicOr(status, st);
-    }
-}
-
-__global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                 int64_t n_words, int64_t n_nodes, int32_t lo, int32_t hi, uint64_t s_fx,
-                                                 const uint64_t *__restrict__ partial,
-                                                 const csgs_prob_stats *__restrict__ stats,
-                                                 int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
-                                                 uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
-{
-    constexpr int WORDS = CAND_TILE / WAVE;  // 16
+    constexpr int WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
     __shared__ uint32_t s_cnt[WORDS];
     __shared__ uint64_t s_w[WORDS];
+    __shared__ uint64_t s_aux[4][3];
+    __shared__ unsigned long long s_lb[4];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    uint64_t words[WORDS / 4], w[WORDS / 4], wsk_incl[WORDS / 4];
-    // pass 1: per-word totals
+    const TileState<4> ts(ts_mem, n_tiles);
+    // one tile per block (the loop also covers a smaller, fully resident grid)
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        uint64_t words[WORDS / 4], w[WORDS / 4], wsk_incl[WORDS / 4];
+        uint64_t nloc = 0, wl = 0, wr = 0;
 #pragma unroll
-    for (int k = 0; k < WORDS / 4; ++k) {
-        const int slot = wave * (WORDS / 4) + k;
-        const int64_t word_idx = (int64_t)blockIdx.x * WORDS + slot;
-        const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
-        const int64_t id = word_idx * 64 + lane;
-        const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
-        const bool local = id >= lo && id < hi;
-        const uint64_t wsk = wv * (local ? s_fx : 16ull);
-        words[k] = __ballot(wv != 0);
-        w[k] = wv;
-        wsk_incl[k] = wave_inclusive_scan(wsk);
-        if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
-        if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
-    }
-    __syncthreads();
-    // prefix over the 16 words of the tile (tiny: done redundantly by every thread)
-    uint64_t base_cnt = partial[(int64_t)blockIdx.x * 4 + 0];
-    uint64_t base_w = partial[(int64_t)blockIdx.x * 4 + 1];
-    for (int s = 0; s < wave * (WORDS / 4); ++s) { base_cnt += s_cnt[s]; base_w += s_w[s]; }
-    const double total = (double)stats->total;
-#pragma unroll
-    for (int k = 0; k < WORDS / 4; ++k) {
-        const int slot = wave * (WORDS / 4) + k;
-        const int64_t word_idx = (int64_t)blockIdx.x * WORDS + slot;
-        const uint64_t word = words[k];
-        if (word) {
+        for (int k = 0; k < WORDS / 4; ++k) {
+            const int slot = wave * (WORDS / 4) + k;
+            const int64_t word_idx = t * WORDS + slot;
+            const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
             const int64_t id = word_idx * 64 + lane;
-            const bool set = (word >> lane) & 1ull;
-            const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
-            if (set) {
-                wtable[id] = 0ull;  // back to the clean state
-                if (pos < cap) {
-                    const bool local = id >= lo && id < hi;
-                    cand_id[pos] = (int32_t)id;
-                    cand_w[pos] = w[k];
-                    cdf[pos] = base_w + wsk_incl[k];
-                    if (q) q[pos] = (float)((double)(w[k] * (local ? s_fx : 16ull)) / total);
+            const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
+            const bool local = id >= lo && id < hi;
+            const uint64_t wsk = wv * (local ? s_fx : 16ull);
+            if (wv) {
+                if (local) { nloc += 1; wl += wv; } else { wr += wv; }
+            }
+            words[k] = __ballot(wv != 0);
+            w[k] = wv;
+            wsk_incl[k] = wave_inclusive_scan(wsk);
+            if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
+            if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
+        }
+        nloc = wave_sum(nloc); wl = wave_sum(wl); wr = wave_sum(wr);
+        if (lane == 0) { s_aux[wave][0] = nloc; s_aux[wave][1] = wl; s_aux[wave][2] = wr; }
+        __syncthreads();
+        // tile totals (tiny: computed redundantly by every thread)
+        uint64_t tile_cnt = 0, tile_w = 0, my_cnt = 0, my_w = 0;
+        for (int sl = 0; sl < WORDS; ++sl) {
+            if (sl == wave * (WORDS / 4)) { my_cnt = tile_cnt; my_w = tile_w; }
+            tile_cnt += s_cnt[sl]; tile_w += s_w[sl];
+        }
+        unsigned long long local[4], excl[4];
+        local[0] = (tile_cnt << 32) | (s_aux[0][0] + s_aux[1][0] + s_aux[2][0] + s_aux[3][0]);  // both halves stay below 2^31
+        local[1] = tile_w;
+        local[2] = s_aux[0][1] + s_aux[1][1] + s_aux[2][1] + s_aux[3][1];
+        local[3] = s_aux[0][2] + s_aux[1][2] + s_aux[2][2] + s_aux[3][2];
+        lookback<4>(ts, tag, t, n_tiles, local, excl, s_lb, status);
+        uint64_t base_cnt = (excl[0] >> 32) + my_cnt;
+        uint64_t base_w = excl[1] + my_w;
+#pragma unroll
+        for (int k = 0; k < WORDS / 4; ++k) {
+            const int slot = wave * (WORDS / 4) + k;
+            const int64_t word_idx = t * WORDS + slot;
+            const uint64_t word = words[k];
+            if (word) {
+                const int64_t id = word_idx * 64 + lane;
+                const bool set = (word >> lane) & 1ull;
+                const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
+                if (set) {
+                    wtable[id] = 0ull;  // back to the clean state
+                    if (pos < cap) {
+                        cand_id[pos] = (int32_t)id;
+                        cand_w[pos] = w[k];
+                        cdf[pos] = base_w + wsk_incl[k];
+                    }
                 }
             }
+            base_cnt += s_cnt[slot];
+            base_w += s_w[slot];
         }
-        base_cnt += s_cnt[slot];
-        base_w += s_w[slot];
+        if (t == n_tiles - 1 && threadIdx.x == 0) {
+            const uint64_t tot_cnt = (excl[0] >> 32) + tile_cnt;
+            const uint64_t tot_loc = (excl[0] & 0xFFFFFFFFull) + (local[0] & 0xFFFFFFFFull);
+            stats->n_cand = (int64_t)tot_cnt;
+            stats->n_local = (int64_t)tot_loc;
+            stats->n_remote = (int64_t)(tot_cnt - tot_loc);
+            stats->w_local = excl[2] + local[2];
+            stats->w_remote = excl[3] + local[3];
+            stats->total = excl[1] + tile_w;
+            stats->shift = shift;
+            stats->pad_ = 0;
+            int32_t st = 0;
+            if (tot_cnt == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
+            if ((int64_t)tot_cnt > cap) st |= CSGS_ST_CAND_OVERFLOW;
+            if (st) atomicOr(status, st);
+        }
+        __syncthreads();  // the shared arrays are reused by the next tile
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_q(const uint64_t *__restrict__ cdf,
+                                              const csgs_prob_stats *__restrict__ stats, int64_t cap,
+                                              float *__restrict__ q)
+{
+    int64_t n = stats->n_cand;
+    if (n > cap) n = cap;
+    const double total = (double)stats->total;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (int64_t)gridDim.x * blockDim.x) {
+        const uint64_t wsk = cdf[k] - (k ? cdf[k - 1] : 0ull);
+        q[k] = (float)((double)wsk / total);
     }
 }
 
@@ -284,24 +249,26 @@ using namespace csgs;
 
 extern "C" size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max)
 {
-    if (n_nodes <= 0 || nS_max <= 0 || B_max <= 0) return 0;
-    if (edges_max <= 0) return 0;
-    return carve(nullptr, n_nodes, nS_max, B_max, 0, edges_max).bytes;
+    if (n_nodes <= 0 || n_nodes > 0x7FFFFFFFll || nS_max <= 0 || B_max <= 0 || edges_max <= 0) return 0;
+    return carve(nullptr, n_nodes, nS_max, B_max, edges_max).bytes;
 }
 
 extern "C" size_t csgs_workspace_clean_bytes(int64_t n_nodes)
 {
     if (n_nodes <= 0) return 0;
-    const Workspace w = carve(nullptr, n_nodes, 1, 1, 0, 1);
-    return (size_t)((char *)w.partial - (char *)nullptr);
+    return carve(nullptr, n_nodes, 1, 1, 1).clean_bytes;
 }
 
-extern "C" int csgs_workspace_init(void *ws, size_t ws_bytes, void *stream)
+extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
 {
-    if (!ws || ws_bytes == 0 || ((uintptr_t)ws & 255) || (ws_bytes & 7)) return CSGS_EINVAL;
-    const size_t n = ws_bytes / 8;
+    if (!ws) return CSGS_EINVAL;
+    ws->epoch = 0;
+    Workspace w;
+    const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
+    if (rc != CSGS_OK) return rc;
+    const size_t n = w.bytes / 8;
     const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    CSGS_LAUNCH(K_FILL_ZERO, fill_zero, dim3(blocks), dim3(256), (hipStream_t)stream, (uint64_t *)ws, n);
+    CSGS_LAUNCH(K_FILL_ZERO, fill_zero, dim3(blocks), dim3(256), (hipStream_t)stream, (uint64_t *)ws->base, n);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -324,35 +291,38 @@ extern "C" int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int3
 
 extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t nS, float skew, int32_t *cand_id,
                                 uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap, csgs_prob_stats *stats,
-                                void *ws, size_t ws_bytes, int32_t *status, void *stream)
+                                csgs_workspace *ws, int32_t *status, void *stream)
 {
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll ||
-        g->local_lo > g->local_hi || !S || nS <= 0 || !cand_id || !cand_w || !cdf || cap <= 0 || !stats || !ws ||
-        !status || ((uintptr_t)ws & 255))
+        g->local_lo > g->local_hi || !S || nS <= 0 || !cand_id || !cand_w || !cdf || cap <= 0 || !stats || !ws || !status)
         return CSGS_EINVAL;
     int32_t shift;
     int64_t s_fx;
     int rc = csgs_fixed_point(nS, skew, g->rownorm2_max, &shift, &s_fx);
     if (rc != CSGS_OK) return rc;
-    Workspace w = carve(ws, g->n_nodes, nS, 1, ws_bytes, 0);
-    if (w.fixed_bytes > ws_bytes || w.edge_cap < EDGE_TILE) return CSGS_EWORKSPACE;
+    Workspace w;
+    rc = open_workspace(ws, g->n_nodes, nS, 1, &w);
+    if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int64_t n_words = (g->n_nodes + 63) / 64;
-    const int64_t n_tiles = (g->n_nodes + CAND_TILE - 1) / CAND_TILE;
 
     CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, g->rowptr, g->n_nodes, S, nS, w.eoff, w.rowstart,
-                w.edge_cap, stats, status);
+                w.chunk_cap * EDGE_TILE, stats, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, nS, w.eoff,
                 w.rowstart, ldexp(1.0, shift), w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial);
+    const unsigned long long tag = ++ws->epoch;
+    const int64_t cand_grid = w.n_tiles;  // one tile per block, dispatched in ascending order
+    CSGS_LAUNCH(K_CAND_FUSED, cand_fused, dim3((unsigned)cand_grid), dim3(256), st, w.wtable, w.tileflag, n_words,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, (uint64_t)s_fx, tag, w.cand_ts, shift, stats, status,
+                cand_id, cand_w, cdf, cap);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_SCAN, cand_scan, dim3(1), dim3(1024), st, w.partial, n_tiles, shift, cap, stats, status);
-    CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, g->local_lo, g->local_hi, (uint64_t)s_fx, w.partial, stats, cand_id, cand_w, cdf, q, cap);
-    CSGS_LAUNCH_CHECK();
+    if (q) {
+        const int64_t qn = cap < g->n_nodes ? cap : g->n_nodes;
+        const unsigned qb = (unsigned)((qn + 255) / 256 < 2048 ? (qn + 255) / 256 : 2048);
+        CSGS_LAUNCH(K_FILL_Q, fill_q, dim3(qb), dim3(256), st, cdf, stats, cap, q);
+        CSGS_LAUNCH_CHECK();
+    }
     return CSGS_OK;
 }

@@ -6,8 +6,8 @@ namespace csgs {
 namespace prof {
 
 enum Kid {
-    K_ROW_PREFIX = 0, K_SCAN_EDGES, K_CAND_PARTIALS, K_CAND_SCAN, K_CAND_EMIT, K_DRAW, K_COMPACT_HITS, K_ADJ_FLAG,
-    K_ADJ_SCAN, K_ADJ_EMIT, K_RANK_CLEAR, K_REMOTE_COUNT, K_AGGREGATE, K_AGG_LONG, K_GEMM, K_FILL_ZERO, K_COUNT
+    K_ROW_PREFIX = 0, K_SCAN_EDGES, K_CAND_FUSED, K_FILL_Q, K_DRAW, K_HITS_FUSED, K_ADJ_FUSED, K_REMOTE_COUNT,
+    K_AGGREGATE, K_AGG_LONG, K_GEMM, K_FILL_ZERO, K_COPY, K_COUNT
 };
 
 extern bool g_enabled;

@@ -9,20 +9,28 @@
 //                 entry above u.  The top levels of the search run on a strided sample of the
 //                 CDF staged in LDS, the rest on the global array.  Hits are counted per
 //                 candidate position with integer atomics; first hits set a position bitmap.
-//   compact_hits  one block: bitmap -> ordered list of hit positions, then one thread per distinct
-//                 hit: S_next ascending, mult, p_incl, node -> rank table
-//   adj_flag      flat over the edges of S (same chunking as the weight scan): keep = the target
-//                 was sampled; keep bits per 64 edges and the kept count per chunk
-//   adj_scan      one block: exclusive scan of the chunk counts
-//   adj_emit      flat again: the kept edges in flat order ARE the CSR of P~ (rows in the order
-//                 of S, columns ascending), so position = chunk base + popcount of earlier keep
-//                 bits; row pointers are the positions at the row starts
-//   rank_clear    restores the rank table
+//   hits_fused    single pass over the position bitmap (tiles of 1024 words): per-tile count,
+//                 prefix over earlier tiles by decoupled look-back, then every thread emits the
+//                 hits of its words: S_next ascending, mult, p_incl, node -> rank table
+//   adj_fused     flat over the edges of S (same chunking as the weight scan), single pass: keep
+//                 = the target was sampled; the kept edges in flat order ARE the CSR of P~ (rows
+//                 in the order of S, columns ascending), so position = look-back prefix of the
+//                 chunk + popcount of earlier keep bits, and the row pointers are the positions
+//                 at the row starts.  The node -> rank table is never cleared: its entries carry the
+//                 tag of the call that wrote them
 //   remote_count  one block
 #include <math.h>
 #include "common.hpp"
+#include "lookback.hpp"
 
 namespace csgs {
+
+__global__ void fill_zero_u64(uint64_t *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0ull;
+}
 
 // Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): each round multiplies two
 // counter words by fixed odd constants, swaps halves around and xors in the key, then the key
@@ -82,156 +90,139 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
     if (old == 0) atomicOr((unsigned long long *)&cbitmap[lo >> 6], 1ull << (lo & 63));
 }
 
-__global__ __launch_bounds__(1024) void compact_hits(const int32_t *__restrict__ cand_id,
-                                                     const uint64_t *__restrict__ cdf,
-                                                     const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
-                                                     int64_t n_nodes, int32_t B, uint32_t *__restrict__ hit,
-                                                     uint64_t *__restrict__ cbitmap, int32_t *__restrict__ rank,
-                                                     int32_t *__restrict__ hitpos, int32_t *__restrict__ S_next,
-                                                     int32_t *__restrict__ mult, float *__restrict__ p_incl,
-                                                     double *__restrict__ pdbl, int32_t *__restrict__ n_next)
+__global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ cand_id,
+                                                  const uint64_t *__restrict__ cdf,
+                                                  const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
+                                                  int64_t n_nodes, int32_t B, unsigned long long tag,
+                                                  uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
+                                                  uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
+                                                  uint64_t *__restrict__ rank, int32_t *__restrict__ S_next,
+                                                  int32_t *__restrict__ mult, float *__restrict__ p_incl,
+                                                  double *__restrict__ pdbl, int32_t *__restrict__ n_next,
+                                                  int32_t *__restrict__ status)
 {
     __shared__ uint32_t lds[17];
+    __shared__ unsigned long long s_lb[1];
+    __shared__ uint16_t s_list[HIT_TILE_WORDS * 64];   // drawn positions of the tile, ascending
+    const TileState<1> ts(ts_mem, ts_tiles);
     int64_t n = stats->n_cand;
     if (n > cand_cap) n = cand_cap;
     if (n < 0) n = 0;
     const int64_t n_words = (n + 63) / 64;
-    const double total = n > 0 ? (double)cdf[n - 1] : 1.0;
-    // phase 1: contiguous run of words per thread, so that list order = ascending position
-    const int64_t per = (n_words + blockDim.x - 1) / blockDim.x;
-    const int64_t w0 = (int64_t)threadIdx.x * per;
-    const int64_t w1 = (w0 + per < n_words) ? w0 + per : n_words;
-    uint32_t cnt = 0;
-    for (int64_t w = w0; w < w1; ++w) cnt += (uint32_t)__popcll(cbitmap[w]);
-    uint32_t tot;
-    uint32_t pos = block_exclusive_scan<uint32_t>(cnt, lds, &tot);
-    if (cnt) {
-        for (int64_t w = w0; w < w1; ++w) {
-            uint64_t word = cbitmap[w];
-            if (!word) continue;
-            cbitmap[w] = 0ull;
-            while (word) {
-                const int bit = __ffsll((unsigned long long)word) - 1;
-                word &= word - 1;
-                if (pos < (uint32_t)B) hitpos[pos] = (int32_t)(w * 64 + bit);  // at most B distinct hits exist
-                ++pos;
-            }
-        }
-    }
-    __syncthreads();  // hitpos (global) written above is read by other threads of this block below
-    const uint32_t n_hit = tot < (uint32_t)B ? tot : (uint32_t)B;
-    // phase 2: one thread per distinct hit
-    for (uint32_t r = threadIdx.x; r < n_hit; r += blockDim.x) {
-        const int64_t k = hitpos[r];
-        const uint32_t m = hit[k];
-        hit[k] = 0u;
-        const uint64_t wk = cdf[k] - (k ? cdf[k - 1] : 0ull);
-        const double qk = (double)wk / total;
-        const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
-        const int32_t id = cand_id[k];
-        S_next[r] = id;
-        mult[r] = (int32_t)m;
-        p_incl[r] = (float)pk;
-        pdbl[r] = pk;
-        if (id >= 0 && id < n_nodes) rank[id] = (int32_t)r + 1;
-    }
-    if (threadIdx.x == 0) *n_next = (int32_t)n_hit;
-}
-
-__global__ __launch_bounds__(256) void adj_flag(const int32_t *__restrict__ colidx, int64_t n_nodes, int32_t nS,
-                                                const int64_t *__restrict__ eoff,
-                                                const int64_t *__restrict__ rowstart,
-                                                const int32_t *__restrict__ rank, int64_t edge_cap,
-                                                uint64_t *__restrict__ keepmask, int64_t *__restrict__ chunkcnt,
-                                                int32_t *__restrict__ status)
-{
-    __shared__ RowSlice slice;
-    __shared__ int32_t wave_cnt[4];
-    const int lane = lane_id();
-    const int wave = (int)(threadIdx.x >> 6);
-    const int64_t E = eoff[nS];
-    if (E > edge_cap) {  // the per-edge scratch cannot hold this step
-        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
+    const int64_t n_tiles = (n_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
+    if (n_tiles == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *n_next = 0;  // no candidates at all
         return;
     }
-    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
-        const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
-        stage_slice(slice, eoff, rowstart, nS, c0, c1);
-        const int32_t len = (int32_t)(c1 - c0);
-        int32_t cnt = 0;
-        // wave w owns positions [w * 256, w * 256 + 256): four 64-edge words
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int32_t x = wave * 256 + k * 64 + lane;
-            bool keep = false;
-            if (x < len) {
-                int32_t r;
-                const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
-                const int32_t c = colidx[e];
-                keep = c >= 0 && c < n_nodes && rank[c] != 0;
-            }
-            const uint64_t m = __ballot(keep);
-            if (lane == 0) keepmask[(c0 >> 6) + wave * 4 + k] = m;
-            cnt += __popcll(m);
+    const double total = (double)cdf[n - 1];
+    const uint64_t rank_tag = (tag & 0xFFFFFFFFull) << 32;
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        // one bitmap word per thread -> ordered list of the tile's drawn positions in LDS
+        const int64_t wi = t * HIT_TILE_WORDS + threadIdx.x;
+        uint64_t word = wi < n_words ? cbitmap[wi] : 0ull;
+        const uint32_t cnt = (uint32_t)__popcll(word);
+        uint32_t tile_total;
+        uint32_t ex = block_exclusive_scan<uint32_t>(cnt, lds, &tile_total);
+        if (word) cbitmap[wi] = 0ull;  // back to the clean state
+        while (word) {
+            const int bit = __ffsll((unsigned long long)word) - 1;
+            word &= word - 1;
+            s_list[ex++] = (uint16_t)(threadIdx.x * 64 + bit);
         }
-        if (lane == 0) wave_cnt[wave] = cnt;
-        __syncthreads();
-        if (threadIdx.x == 0) chunkcnt[c0 / EDGE_TILE] = (int64_t)(wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3]);
+        unsigned long long local[1] = {tile_total}, excl[1];
+        lookback<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);   // its barriers also publish s_list
+        // one thread per distinct hit
+        for (uint32_t i = threadIdx.x; i < tile_total; i += blockDim.x) {
+            const int64_t kpos = t * (HIT_TILE_WORDS * 64) + s_list[i];
+            const uint64_t pos = excl[0] + i;
+            const uint32_t m = hit[kpos];
+            hit[kpos] = 0u;
+            if (pos < (uint64_t)B) {  // at most B distinct hits exist; the guard keeps stores in bounds regardless
+                const uint64_t wk = cdf[kpos] - (kpos ? cdf[kpos - 1] : 0ull);
+                const double qk = (double)wk / total;
+                const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
+                const int32_t id = cand_id[kpos];
+                S_next[pos] = id;
+                mult[pos] = (int32_t)m;
+                p_incl[pos] = (float)pk;
+                pdbl[pos] = pk;
+                if (id >= 0 && id < n_nodes) rank[id] = rank_tag | (pos + 1);
+            }
+        }
+        if (t == n_tiles - 1 && threadIdx.x == 0) {
+            const uint64_t tot = excl[0] + tile_total;
+            *n_next = (int32_t)(tot < (uint64_t)B ? tot : (uint64_t)B);
+        }
+        __syncthreads();  // s_list is reused by the next tile
     }
 }
 
-// chunkbase[c] holds the kept count of chunk c on entry and the exclusive prefix on exit.
-__global__ __launch_bounds__(1024) void adj_scan(int64_t *__restrict__ chunkbase, int32_t nS,
-                                                 const int64_t *__restrict__ eoff, int64_t edge_cap,
-                                                 int32_t *__restrict__ adj_rowptr, int64_t adj_cap,
-                                                 int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
+// rank entry of node c for the call tagged rank_tag: position in S_next + 1, or 0
+__device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, uint64_t rank_tag)
 {
-    __shared__ int64_t lds[17];
-    int64_t E = eoff[nS];
-    if (E > edge_cap) E = 0;
-    const int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
-    const int64_t per = (n_chunks + blockDim.x - 1) / blockDim.x;
-    const int64_t t0 = (int64_t)threadIdx.x * per;
-    const int64_t t1 = (t0 + per < n_chunks) ? t0 + per : n_chunks;
-    int64_t sum = 0;
-    for (int64_t t = t0; t < t1; ++t) sum += chunkbase[t];
-    int64_t total;
-    int64_t ex = block_exclusive_scan<int64_t>(sum, lds, &total);
-    for (int64_t t = t0; t < t1; ++t) {
-        const int64_t c = chunkbase[t];
-        chunkbase[t] = ex;
-        ex += c;
-    }
-    // rows that start at or after the last edge (trailing empty rows, and the end pointer)
-    const int32_t clamp = (int32_t)(total < 0x7FFFFFFFll ? total : 0x7FFFFFFFll);
-    const int64_t first_tail = E > 0 ? lower_bound_i64(eoff, (int64_t)nS + 1, E) : 0;
-    for (int64_t a = first_tail + threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = clamp;
-    if (threadIdx.x == 0) {
-        *adj_nnz = total;
-        if (total > adj_cap || total > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
-    }
+    const uint64_t e = rank[c];
+    return (e & 0xFFFFFFFF00000000ull) == rank_tag ? (int32_t)(e & 0xFFFFFFFFull) : 0;
 }
 
-__global__ __launch_bounds__(256) void adj_emit(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                int32_t nS, const int64_t *__restrict__ eoff,
-                                                const int64_t *__restrict__ rowstart,
-                                                const int32_t *__restrict__ rank, const double *__restrict__ pdbl,
-                                                int64_t edge_cap, const uint64_t *__restrict__ keepmask,
-                                                const int64_t *__restrict__ chunkbase,
-                                                int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
-                                                float *__restrict__ adj_val, int64_t adj_cap)
+__global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
+                                                 int64_t n_nodes, int32_t nS, const int64_t *__restrict__ eoff,
+                                                 const int64_t *__restrict__ rowstart,
+                                                 const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
+                                                 unsigned long long tag, unsigned long long hits_tag,
+                                                 uint64_t *__restrict__ ts_mem, int64_t chunk_cap,
+                                                 int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
+                                                 float *__restrict__ adj_val, int64_t adj_cap,
+                                                 int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
 {
     __shared__ RowSlice slice;
     __shared__ uint64_t s_mask[EDGE_TILE / 64];
     __shared__ int32_t s_pre[EDGE_TILE / 64 + 1];
+    __shared__ unsigned long long s_lb[1];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    const int64_t E = eoff[nS];
-    if (E > edge_cap) return;
-    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
+    const TileState<1> ts(ts_mem, chunk_cap);
+    const uint64_t rank_tag = (hits_tag & 0xFFFFFFFFull) << 32;
+    int64_t E = eoff[nS];
+    int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
+    bool overflow = false;
+    if (n_chunks > chunk_cap) {  // the workspace cannot describe this many chunks: report, emit nothing
+        overflow = true;
+        E = 0;
+        n_chunks = 0;
+    }
+    if (n_chunks == 0) {
+        if (blockIdx.x == 0) {
+            for (int32_t a = threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = 0;
+            if (threadIdx.x == 0) {
+                *adj_nnz = 0;
+                if (overflow) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
+            }
+        }
+        return;
+    }
+    // all blocks are resident; block b takes chunks b, b + grid, ... in ascending order
+    for (int64_t t = blockIdx.x; t < n_chunks; t += gridDim.x) {
+        const int64_t c0 = t * EDGE_TILE;
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
         stage_slice(slice, eoff, rowstart, nS, c0, c1);
-        if (threadIdx.x < EDGE_TILE / 64) s_mask[threadIdx.x] = keepmask[(c0 >> 6) + threadIdx.x];
+        const int32_t len = (int32_t)(c1 - c0);
+        // wave w owns positions [w * 256, w * 256 + 256): four 64-edge words
+        int32_t rk[4];
+        int64_t ea[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int32_t x = wave * 256 + k * 64 + lane;
+            rk[k] = 0;
+            ea[k] = 0;
+            if (x < len) {
+                int32_t r;
+                ea[k] = edge_address(slice, eoff, rowstart, c0, x, &r);
+                const int32_t c = colidx[ea[k]];
+                if (c >= 0 && c < n_nodes) rk[k] = rank_of(rank, c, rank_tag);
+            }
+            const uint64_t m = __ballot(rk[k] > 0);
+            if (lane == 0) s_mask[wave * 4 + k] = m;
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
             int32_t acc = 0;
@@ -239,8 +230,10 @@ __global__ __launch_bounds__(256) void adj_emit(const int32_t *__restrict__ coli
             s_pre[EDGE_TILE / 64] = acc;
         }
         __syncthreads();
-        const int64_t base = chunkbase[c0 / EDGE_TILE];
-        const int32_t len = (int32_t)(c1 - c0);
+        const int32_t tile_cnt = s_pre[EDGE_TILE / 64];
+        unsigned long long local[1] = {(unsigned long long)tile_cnt}, excl[1];
+        lookback<1>(ts, tag, t, n_chunks, local, excl, s_lb, status);
+        const int64_t base = (int64_t)excl[0];
         // row pointers of the rows that start inside this chunk: kept edges before the row start
         const int32_t R = slice.R;
         const int64_t a_first = slice.a_first;
@@ -251,33 +244,29 @@ __global__ __launch_bounds__(256) void adj_emit(const int32_t *__restrict__ coli
                 adj_rowptr[a_first + r] = (int32_t)(v < 0x7FFFFFFFll ? v : 0x7FFFFFFFll);
             }
         }
-        if (s_pre[EDGE_TILE / 64] == 0) continue;  // nothing kept in this chunk (uniform over the block)
+        if (tile_cnt) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int32_t word = wave * 4 + k;
-            const uint64_t m = s_mask[word];
-            if (!((m >> lane) & 1ull)) continue;
-            const int32_t x = word * 64 + lane;
-            int32_t r;
-            const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
-            const int64_t pos = base + s_pre[word] + __popcll(m & ((1ull << lane) - 1ull));
-            const int32_t rk = rank[colidx[e]];
-            if (pos < adj_cap && rk > 0) {
-                adj_col[pos] = rk - 1;
-                adj_val[pos] = (float)((double)val[e] / pdbl[rk - 1]);
+            for (int k = 0; k < 4; ++k) {
+                if (rk[k] <= 0) continue;
+                const int32_t word = wave * 4 + k;
+                const int64_t pos = base + s_pre[word] + __popcll(s_mask[word] & ((1ull << lane) - 1ull));
+                if (pos < adj_cap) {
+                    adj_col[pos] = rk[k] - 1;
+                    adj_val[pos] = (float)((double)val[ea[k]] / pdbl[rk[k] - 1]);
+                }
             }
         }
-    }
-}
-
-__global__ void rank_clear(const int32_t *__restrict__ S_next, const int32_t *__restrict__ n_next, int32_t B,
-                           int64_t n_nodes, int32_t *__restrict__ rank)
-{
-    int32_t n = *n_next;
-    if (n > B) n = B;
-    for (int32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < n; k += gridDim.x * blockDim.x) {
-        const int32_t id = S_next[k];
-        if (id >= 0 && id < n_nodes) rank[id] = 0;
+        if (t == n_chunks - 1) {
+            // rows that start at or after the last edge (trailing empty rows, and the end pointer)
+            const int64_t total = base + tile_cnt;
+            const int32_t clamp = (int32_t)(total < 0x7FFFFFFFll ? total : 0x7FFFFFFFll);
+            const int64_t first_tail = lower_bound_i64(eoff, (int64_t)nS + 1, E);
+            for (int64_t a = first_tail + threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = clamp;
+            if (threadIdx.x == 0) {
+                *adj_nnz = total;
+                if (total > adj_cap || total > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
+            }
+        }
     }
 }
 
@@ -340,15 +329,16 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
                                  const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
                                  uint64_t iter, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
                                  int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
-                                 int64_t adj_cap, int64_t *adj_nnz, void *ws, size_t ws_bytes, int32_t *status,
+                                 int64_t adj_cap, int64_t *adj_nnz, csgs_workspace *ws, int32_t *status,
                                  void *stream)
 {
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !S || nS <= 0 ||
         !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next || !mult || !p_incl || !n_next || !adj_rowptr || !adj_col ||
-        !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status || ((uintptr_t)ws & 255))
+        !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
         return CSGS_EINVAL;
-    Workspace w = carve(ws, g->n_nodes, nS, B, ws_bytes, 0);
-    if (w.fixed_bytes > ws_bytes || w.edge_cap < EDGE_TILE) return CSGS_EWORKSPACE;
+    Workspace w;
+    const int rc = open_workspace(ws, g->n_nodes, nS, B, &w);
+    if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (cand_cap > g->n_nodes) cand_cap = g->n_nodes;  // there are never more candidates than nodes
 
@@ -356,20 +346,25 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
                 cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32), layer, w.hit,
                 w.cbitmap);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_COMPACT_HITS, compact_hits, dim3(1), dim3(1024), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B,
-                w.hit, w.cbitmap, w.rank, w.hitpos, S_next, mult, p_incl, w.pdbl, n_next);
+    // rank entries carry the low 32 bits of the tag; when those wrap, stale entries could look
+    // current, so the table is wiped once every 2^32 calls
+    const unsigned long long hits_tag = ++ws->epoch;
+    if ((hits_tag & 0xFFFFFFFFull) == 0) {
+        const size_t n = (size_t)g->n_nodes;
+        const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+        CSGS_LAUNCH(K_FILL_ZERO, fill_zero_u64, dim3(blocks), dim3(256), st, w.rank, n);
+        CSGS_LAUNCH_CHECK();
+    }
+    const int64_t cap_words = (cand_cap + 63) / 64;
+    const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
+    const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid() ? hit_tiles : resident_grid());
+    CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B,
+                hits_tag, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_ADJ_FLAG, adj_flag, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->n_nodes, nS, w.eoff, w.rowstart,
-                w.rank, w.edge_cap, w.keepmask, w.chunkbase, status);
-    CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_ADJ_SCAN, adj_scan, dim3(1), dim3(1024), st, w.chunkbase, nS, w.eoff, w.edge_cap, adj_rowptr,
+    const unsigned long long adj_tag = ++ws->epoch;
+    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes, nS,
+                w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, hits_tag, w.adj_ts, w.chunk_cap, adj_rowptr, adj_col, adj_val,
                 adj_cap, adj_nnz, status);
-    CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_ADJ_EMIT, adj_emit, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, nS, w.eoff, w.rowstart,
-                w.rank, w.pdbl, w.edge_cap, w.keepmask, w.chunkbase, adj_rowptr, adj_col, adj_val, adj_cap);
-    CSGS_LAUNCH_CHECK();
-    const unsigned clr_blocks = (unsigned)((B + 255) / 256 < 1024 ? (B + 255) / 256 : 1024);
-    CSGS_LAUNCH(K_RANK_CLEAR, rank_clear, dim3(clr_blocks), dim3(256), st, S_next, n_next, B, g->n_nodes, w.rank);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

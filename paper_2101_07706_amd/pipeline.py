@@ -33,9 +33,11 @@ class DeviceGraph:
 class Workspace:
     def __init__(self, n_nodes, nS_max, B_max, edges_max, device):
         nbytes = csgs.csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max)
+        assert nbytes > 0
         self.buf = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
         assert self.buf.data_ptr() % 256 == 0
-        csgs.csgs_workspace_init(self.buf)
+        self.desc = csgs.make_workspace(self.buf, n_nodes, nS_max, B_max, edges_max)
+        csgs.csgs_workspace_init(self.desc)
 
 
 class LayerBuffers:
@@ -64,13 +66,14 @@ class LayerBuffers:
                                total=s.total, shift=s.shift)
 
 
-def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None):
+def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True):
     """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32)."""
     nS = S.numel()
-    csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, lb.q, lb.stats, ws.buf, lb.status, stream)
+    csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, lb.q if want_q else None, lb.stats, ws.desc,
+                          lb.status, stream)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
-                           ws.buf, lb.status, stream)
+                           ws.desc, lb.status, stream)
     csgs.csgs_remote_count(lb.S_next, lb.n_next, dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total,
                            lb.per_part, lb.src_row, lb.remote_ids, stream)
 
