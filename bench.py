@@ -5,9 +5,15 @@ A step = the whole hot path over one batch of synthetic input: for every GCN lay
 csgs_build_probs -> csgs_sample_layer -> csgs_remote_count; then, bottom-up, csgs_aggregate ->
 csgs_layer_gemm.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large] [--scale S]
+
+Besides the named workload the default run also times a scaled-up variant of it (batch and samples
+per layer x16, same graph): the named batch moves only a few MB per kernel, which no kernel can
+turn into a large fraction of 8 TB/s within its launch latency, so the scaled run is where the
+kernels' bandwidth / MFMA efficiency shows.  It is reported under "scaled", never as `value`.
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -18,11 +24,150 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
-MFMA_F32_PEAK_TFLOPS = 157.3
+MFMA_F64_PEAK_TFLOPS = 78.6     # the layer GEMM accumulates on the fp64 matrix cores
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(s, N):
+    """Bytes each kernel must move for one layer step of the given sizes (each item once)."""
+    nS, E, nc, n2, nnz, Fi, Fo, el, B = (s[k] for k in ("nS", "E", "nc", "n_next", "nnz", "F_in", "F_out", "elt", "B"))
+    agg = n2 * Fi * el + 8 * nnz + 4 * (nS + 1) + 4 * nS * Fi
+    return {
+        "row_prefix": 28 * nS,                              # S, two row pointers, prefix + start written
+        "scan_edges": 8 * E + 16 * nS + 8 * nc,             # col + val per edge, row slices, accumulators
+        "cand_fused": N / 64 + 8 * nc + 20 * nc,            # flags, accumulators read, id + weight + cdf written
+        "draw": 12 * B,                                     # cdf probes are cache traffic
+        "hits_fused": nc / 8 + 36 * n2,                     # position bitmap, per hit: count, 2 cdf, id, 4 outputs
+        "adj_fused": 4 * E + 16 * nS + 4 * nS + 20 * nnz,   # col per edge, row slices, row pointers, kept edges
+        "remote_count": 12 * n2,
+        "aggregate": agg, "aggregate_long": 0.0,            # long rows are part of the same algorithmic volume
+        "layer_gemm": 4 * (nS * Fi + Fi * Fo + nS * Fo),
+    }
+
+
+class Workload:
+    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs):
+        self.cfg, self.g, self.dg, self.Xd, self.dev = cfg, g, dg, Xd, dev
+        self.torch, self.pipeline, self.csgs = torch, pipeline, csgs
+        self.bf16 = cfg.feat_dtype == "bf16"
+        self.dims = synth.layer_dims(cfg)
+        self.M = len(self.dims)
+        self.B = cfg.samples
+        self.seed = 1234 + cfg.seed
+        self.Ws = [synth.glorot_uniform(fi, fo, cfg.seed) for fi, fo in self.dims]
+        self.batches = [synth.make_batch(g, cfg.batch, cfg.seed, it) for it in range(n_batches)]
+        self.X_local = Xd[g.local_lo:g.local_hi]
+        self.Wd = [torch.from_numpy(W).to(dev) for W in self.Ws]
+        self.Sd = [torch.from_numpy(b).to(dev) for b in self.batches]
+        M, B, dims = self.M, self.B, self.dims
+        nS_max = max(len(self.batches[0]), B)
+        self.ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
+        adj_cap = int(min(g.nnz, 48_000_000))
+        self.lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
+        self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
+        self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
+        self.elt = 2 if self.bf16 else 4
+
+    def step(self, it, sizes=None):
+        """One whole mini-batch.  The host learns each layer's sampled-set size (it sizes the next launch)."""
+        cfg, M, B, lbs, pipeline = self.cfg, self.M, self.B, self.lbs, self.pipeline
+        S = self.Sd[it]
+        rows = []
+        for l in range(M):
+            lb = lbs[l]
+            pipeline.sample_step(self.dg, self.ws, S, cfg.skew, B, self.seed, it, l, lb, want_q=False)
+            n = int(lb.n_next.item())
+            rows.append(S)
+            S = lb.S_next[:n]
+        r = int(lbs[M - 1].remote_total.item())
+        X_remote = self.Xd[lbs[M - 1].remote_ids[:r].long()]      # stands in for the exchange of remote rows
+        H = None
+        for l in range(M - 1, -1, -1):
+            lb = lbs[l]
+            nS = rows[l].numel()
+            Z, Hn = self.Zs[l][:nS], self.Hs[l][:nS]
+            if l == M - 1:
+                pipeline.compute_step(lb, nS, self.X_local, X_remote, True, False, self.Wd[M - 1 - l], Z, Hn)
+            else:
+                pipeline.compute_step(lb, nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn)
+            H = Hn
+        if sizes is not None:
+            self.torch.cuda.synchronize()
+            for l in range(M):
+                st = lbs[l].stats_host()
+                sizes.append(dict(layer=l, nS=rows[l].numel(), E=st.edges_scanned, nc=st.n_cand, B=B,
+                                  n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
+                                  remote=int(lbs[l].remote_total.item()), F_in=self.dims[M - 1 - l][0],
+                                  F_out=self.dims[M - 1 - l][1], elt=self.elt if l == M - 1 else 4,
+                                  status=int(lbs[l].status.item())))
+        return H
+
+    def measure(self, steps, warmup):
+        """Timed region, then the same steps again with every kernel launch bracketed by HIP events
+        (recorded on the launch stream)."""
+        torch, csgs = self.torch, self.csgs
+        for it in range(warmup):
+            self.step(it)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(warmup, warmup + steps):
+            self.step(it)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+        sizes = []
+        csgs.csgs_profile_enable(True)
+        for it in range(warmup, warmup + steps):
+            self.step(it, sizes)
+        torch.cuda.synchronize()
+        csgs.csgs_profile_enable(False)
+        prof = csgs.csgs_profile_collect()
+        assert all(s["status"] == 0 for s in sizes), "a status bit was set"
+        alg, flops = {}, 0.0
+        for s in sizes:
+            for k, b in algorithmic_bytes(s, self.g.n_nodes).items():
+                alg[k] = alg.get(k, 0.0) + b
+            flops += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
+        kernels = {}
+        for k, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            kernels[k] = dict(avg_us=ms / cnt * 1e3, launches_per_step=cnt / steps, ms_per_step=ms / steps,
+                              alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
+            if alg.get(k):
+                kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
+        # the aggregation is two launches (ordinary rows, long rows) over one algorithmic volume
+        agg_ms = prof.get("aggregate", (0, 1))[0] + prof.get("aggregate_long", (0, 1))[0]
+        agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
+        gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
+        kernels["layer_gemm"]["TFLOPs"] = gemm_TF
+        kernels["layer_gemm"]["flop_per_launch"] = flops / prof["layer_gemm"][1]
+        tot = lambda key: sum(s[key] for s in sizes) / steps
+        per_step = dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
+                        sampled_edges=tot("nnz"), remote_nodes=tot("remote"))
+        return dict(ms_per_step=ms_per_step, kernels=kernels, per_step=per_step, sizes=sizes,
+                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
+
+
+def roofline_of(kernels, name, traffic):
+    k = kernels[name]
+    if name == "layer_gemm":
+        r = dict(bound="mfma", kernel=name, achieved=k["TFLOPs"], peak=MFMA_F64_PEAK_TFLOPS, unit="TFLOP/s",
+                 frac=k["TFLOPs"] / MFMA_F64_PEAK_TFLOPS, alg_per_launch=k["flop_per_launch"])
+    else:
+        a = k.get("alg_GBps", 0.0)
+        r = dict(bound="hbm", kernel=name, achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS,
+                 alg_per_launch=k["alg_bytes_per_launch"])
+    r["traffic"] = (traffic or {}).get(name)
+    r["avg_launch_us"] = k["avg_us"]
+    return r
+
+
+def load_traffic(key):
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    return json.load(open(path)).get(key)
 
 
 def main():
@@ -31,8 +176,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="large")
+    ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer (scaled-up variant)")
+    ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share); --gpus above 1 is not supported",
@@ -48,158 +194,95 @@ def main():
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.config]
     if args.scale != 1:
-        import dataclasses
         cfg = dataclasses.replace(cfg, batch=cfg.batch * args.scale, samples=cfg.samples * args.scale)
+    name = cfg.name if args.scale == 1 else f"{cfg.name}_x{args.scale}"
     bf16 = cfg.feat_dtype == "bf16"
     t0 = time.time()
     g = synth.make_graph(cfg)
     log(f"graph {cfg.name}: N={g.n_nodes} nnz={g.nnz} local=[{g.local_lo},{g.local_hi}) in {time.time() - t0:.1f}s")
     X = synth.make_features(cfg.n_nodes, cfg.feat_dim, cfg.seed)
-    dims = synth.layer_dims(cfg)
-    Ws = [synth.glorot_uniform(fi, fo, cfg.seed) for fi, fo in dims]
-    M = len(dims)
-    B = cfg.samples
-    n_batches = args.steps + args.warmup
-    batches = [synth.make_batch(g, cfg.batch, cfg.seed, it) for it in range(n_batches)]
-    seed = 1234 + cfg.seed
-
     dg = pipeline.DeviceGraph(g, dev)
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
-    X_local = Xd[g.local_lo:g.local_hi]
-    Wd = [torch.from_numpy(W).to(dev) for W in Ws]
-    Sd = [torch.from_numpy(b).to(dev) for b in batches]
-    nS_max = max(cfg.batch, B)
-    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
-    adj_cap = int(min(g.nnz, 48_000_000))
-    lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
-    Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
-    Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
-    counts_pinned = torch.zeros(2, dtype=torch.int64).pin_memory()
-    elt = 2 if bf16 else 4
-    log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
+    mk = lambda c, nb: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs)
 
-    def step(it, sizes=None):
-        """One whole mini-batch.  The host learns each layer's sampled-set size (it sizes the next launch)."""
-        S = Sd[it]
-        rows = []
-        for l in range(M):
-            lb = lbs[l]
-            pipeline.sample_step(dg, ws, S, cfg.skew, B, seed, it, l, lb, want_q=False)
-            n = int(lb.n_next.item())
-            rows.append(S)
-            S = lb.S_next[:n]
-        r = int(lbs[M - 1].remote_total.item())
-        X_remote = Xd[lbs[M - 1].remote_ids[:r].long()]      # stands in for the exchange of remote rows
-        H = None
-        for l in range(M - 1, -1, -1):
-            lb = lbs[l]
-            nS = rows[l].numel()
-            Z, Hn = Zs[l][:nS], Hs[l][:nS]
-            if l == M - 1:
-                pipeline.compute_step(lb, nS, X_local, X_remote, True, False, Wd[M - 1 - l], Z, Hn)
-            else:
-                pipeline.compute_step(lb, nS, H, None, False, True, Wd[M - 1 - l], Z, Hn)
-            H = Hn
-        if sizes is not None:
-            torch.cuda.synchronize()
-            for l in range(M):
-                st = lbs[l].stats_host()
-                sizes.append(dict(layer=l, nS=rows[l].numel(), E=st.edges_scanned, nc=st.n_cand,
-                                  n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
-                                  remote=int(lbs[l].remote_total.item()), F_in=dims[M - 1 - l][0],
-                                  F_out=dims[M - 1 - l][1], elt=elt if l == M - 1 else 4,
-                                  status=int(lbs[l].status.item())))
-        return H
-
-    for it in range(args.warmup):
-        step(it)
+    # copy-kernel yardstick (also the known-size kernel for calibrating byte counters)
+    cbytes = 512 * 2 ** 20
+    ca = torch.zeros(cbytes // 8, dtype=torch.int64, device=dev)
+    cb = torch.empty_like(ca)
+    for _ in range(3):
+        csgs.csgs_calib_copy(cb, ca)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for it in range(args.warmup, n_batches):
-        step(it)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
-
-    # same steps again with every kernel launch bracketed by HIP events (on the launch stream)
-    sizes = []
     csgs.csgs_profile_enable(True)
-    for it in range(args.warmup, n_batches):
-        step(it, sizes)
+    for _ in range(5):
+        csgs.csgs_calib_copy(cb, ca)
     torch.cuda.synchronize()
     csgs.csgs_profile_enable(False)
-    prof = csgs.csgs_profile_collect()
-    assert all(s["status"] == 0 for s in sizes), "a status bit was set"
+    cms, ccnt = csgs.csgs_profile_collect()["copy"]
+    copy_GBps = 2 * cbytes * ccnt / (cms * 1e-3) / 1e9
+    del ca, cb
+    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write)")
 
-    # algorithmic bytes / flops per kernel, summed over the launches of the profiled region
-    N = g.n_nodes
-    alg = {k: 0.0 for k in prof}
-    flops = 0.0
-    for s in sizes:
-        nS, E, nc, n2, nnz, Fi, Fo, el = s["nS"], s["E"], s["nc"], s["n_next"], s["nnz"], s["F_in"], s["F_out"], s["elt"]
-        add = lambda k, b: alg.__setitem__(k, alg.get(k, 0.0) + b)
-        add("scan_edges", 8 * E + 20 * nS + 8 * nc)
-        add("cand_fused", N / 64 + 8 * nc + 20 * nc)
-        add("adj_fused", 4 * E + 16 * nS + 4 * nS + 20 * nnz)
-        add("aggregate", n2 * Fi * el + 8 * nnz + 4 * (nS + 1) + 4 * nS * Fi)
-        add("layer_gemm", 4 * (nS * Fi + Fi * Fo + nS * Fo))
-        flops += 2.0 * nS * Fi * Fo
-    kernels = {}
-    for k, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
-        kernels[k] = dict(avg_us=ms / cnt * 1e3, launches_per_step=cnt / args.steps, ms_per_step=ms / args.steps)
-        if alg.get(k):
-            kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
-    kernels["layer_gemm"]["TFLOPs"] = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
-    dominant = next(iter(kernels))
-    if dominant == "layer_gemm":
-        ach = kernels[dominant]["TFLOPs"]
-        roofline = dict(bound="mfma", kernel=dominant, achieved=ach, peak=MFMA_F32_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=ach / MFMA_F32_PEAK_TFLOPS, traffic=None)
-    else:
-        ach = kernels[dominant].get("alg_GBps", 0.0)
-        roofline = dict(bound="hbm", kernel=dominant, achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=ach / HBM_PEAK_GBS, traffic=None)
-    roofline["avg_launch_us"] = kernels[dominant]["avg_us"]
-    roofline["alg_bytes_per_launch"] = alg.get(dominant, 0.0) / max(prof[dominant][1], 1)
-
-    tot = lambda key: sum(s[key] for s in sizes) / args.steps
-    sampled_edges_per_step = tot("nnz")
-    value = sampled_edges_per_step / (ms_per_step * 1e-3)
+    wl = mk(cfg, args.steps + args.warmup)
+    log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
+    res = wl.measure(args.steps, args.warmup)
+    ms_per_step = res["ms_per_step"]
+    log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
+    dominant = next(iter(res["kernels"]))
+    roofline = roofline_of(res["kernels"], dominant, load_traffic(name))
+    roofline["copy_kernel_GBps"] = copy_GBps
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import chain
-        n_cpu = 2
+        n_cpu = 4
         t0 = time.perf_counter()
         cpu_nnz = 0
         for it in range(args.warmup, args.warmup + n_cpu):
-            osteps = chain.oracle_chain(g, X, Ws, batches[it], cfg.skew, B, seed, it, bf16)
+            osteps = chain.oracle_chain(g, X, wl.Ws, wl.batches[it], cfg.skew, wl.B, wl.seed, it, bf16)
             cpu_nnz += sum(o.sm.adj_nnz for o in osteps)
             if it == args.warmup:   # spot check: the GPU step of the same batch drew the same nodes
-                want = [s for s in sizes if True][:M]
                 for l, o in enumerate(osteps):
-                    assert want[l]["n_next"] == o.sm.n_next and want[l]["nnz"] == o.sm.adj_nnz
-                    assert want[l]["remote"] == o.rc.remote_total
+                    got = res["sizes"][l]
+                    assert got["n_next"] == o.sm.n_next and got["nnz"] == o.sm.adj_nnz and got["remote"] == o.rc.remote_total
         cpu_s = time.perf_counter() - t0
         cpu_baseline = dict(value=cpu_nnz / cpu_s, unit="sampled edges/s", cores=1, kind="oracle",
                             sample=f"{n_cpu} whole steps of the same workload ({cpu_s:.1f} s)",
                             ms_per_step=cpu_s / n_cpu * 1e3)
+        log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
+    scaled = None
+    if not args.no_scaled and args.scale == 1:
+        del wl
+        torch.cuda.empty_cache()
+        sc = 16
+        cfg_s = dataclasses.replace(cfg, batch=cfg.batch * sc, samples=cfg.samples * sc)
+        rs = mk(cfg_s, 8).measure(6, 2)
+        tr = load_traffic(f"{cfg.name}_x{sc}")
+        shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_fused")
+        scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
+                      ms_per_step=rs["ms_per_step"],
+                      sampled_edges_per_s=rs["per_step"]["sampled_edges"] / (rs["ms_per_step"] * 1e-3),
+                      per_step=rs["per_step"], aggregate_GBps=rs["aggregate_GBps"], gemm_TFLOPs=rs["gemm_TFLOPs"],
+                      rooflines=[roofline_of(rs["kernels"], k, tr) for k in rs["kernels"] if k in shown],
+                      kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in rs["kernels"].items()})
+        log(f"scaled x{sc}: {rs['ms_per_step']:.3f} ms/step, aggregate {rs['aggregate_GBps']:.0f} GB/s, "
+            f"gemm {rs['gemm_TFLOPs']:.1f} TFLOP/s")
+
+    dims = synth.layer_dims(cfg)
     out = dict(
         metric="sampled-aggregation HBM GB/s + sampled edges/s per GCN layer; step time",
-        value=value, unit="sampled edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
-        ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
-        dtype="bf16 features, f32 accumulate" if bf16 else "f32", data="synthetic",
-        config=dict(workload=f"{cfg.name}: N={g.n_nodes}, nnz={g.nnz}, {cfg.n_parts} partitions, batch {cfg.batch}, "
-                             f"{B} samples/layer, {M} layers {dims}, skew {cfg.skew}",
-                    per_step=dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
-                                  sampled_edges=sampled_edges_per_step, remote_nodes=tot("remote"))),
-        aggregate_GBps=kernels.get("aggregate", {}).get("alg_GBps"),
-        gemm_TFLOPs=kernels["layer_gemm"]["TFLOPs"],
-        scanned_edges_per_s=tot("E") / (ms_per_step * 1e-3),
-        roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels)
+        value=res["per_step"]["sampled_edges"] / (ms_per_step * 1e-3), unit="sampled edges/s",
+        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
+        scaling="weak", vs_baseline=None,
+        dtype="bf16 features, f64 accumulate, f32 out" if bf16 else "f32 in/out, f64 accumulate", data="synthetic",
+        config=dict(workload=f"{name}: N={g.n_nodes}, nnz={g.nnz}, {cfg.n_parts} partitions, batch {cfg.batch}, "
+                             f"{cfg.samples} samples/layer, {len(dims)} layers {dims}, skew {cfg.skew}",
+                    per_step=res["per_step"]),
+        aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
+        scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
+        roofline=roofline, cpu_baseline=cpu_baseline,
+        kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
     print(json.dumps(out))
 
 

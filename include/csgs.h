@@ -224,6 +224,11 @@ int csgs_profile_kernel_count(void);
 const char *csgs_profile_kernel_name(int kernel);
 int csgs_profile_collect(double *ms_sum /*host*/, int64_t *launches /*host*/);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned)
+ * with an ordinary streaming kernel: the yardstick for achievable HBM bandwidth, and the
+ * known-size kernel against which hardware byte counters are calibrated. */
+int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Static string for a CSGS_E* code. */
 const char *csgs_strerror(int code);
 

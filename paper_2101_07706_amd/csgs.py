@@ -22,7 +22,8 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
            "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
-           "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect"]
+           "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
+           "csgs_calib_copy"]
 
 
 class CsgsError(RuntimeError):
@@ -77,6 +78,7 @@ def lib():
         L.csgs_layer_gemm.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, i64, vp]
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
+        L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
         L.csgs_profile_enable.argtypes = [C.c_int]
         L.csgs_profile_kernel_name.restype = C.c_char_p
         L.csgs_profile_kernel_name.argtypes = [C.c_int]
@@ -195,3 +197,8 @@ def csgs_profile_collect():
     cnt = (C.c_int64 * n)()
     _chk(lib().csgs_profile_collect(ms, cnt), "csgs_profile_collect")
     return {lib().csgs_profile_kernel_name(k).decode(): (ms[k], cnt[k]) for k in range(n) if cnt[k]}
+
+
+def csgs_calib_copy(dst, src, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _chk(lib().csgs_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "csgs_calib_copy")

@@ -46,7 +46,28 @@ void record(int kid, hipStream_t st, bool start)
 }  // namespace prof
 }  // namespace csgs
 
+namespace csgs {
+// Plain streaming copy, 16 bytes per thread and step: the yardstick for achievable HBM bandwidth
+// and the known-size kernel against which byte counters are calibrated.
+__global__ __launch_bounds__(256) void copy_k(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace csgs
+
 using namespace csgs::prof;
+
+extern "C" int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || bytes == 0 || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return CSGS_EINVAL;
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
+    CSGS_LAUNCH(K_COPY, csgs::copy_k, dim3(blocks), dim3(256), (hipStream_t)stream, (const uint4 *)src, (uint4 *)dst, n16);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
 
 extern "C" int csgs_profile_enable(int on)
 {

@@ -1,0 +1,93 @@
+"""C-ABI checks that need no GPU: the library loads, exports every function include/csgs.h
+declares, and its host-side logic (argument validation, fixed-point parameters, workspace sizing)
+behaves as documented.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2101_07706_amd import csgs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "csgs.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(csgs_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported():
+    names = declared_functions()
+    assert {"csgs_build_probs", "csgs_sample_layer", "csgs_aggregate", "csgs_layer_gemm",
+            "csgs_remote_count"} <= set(names)
+    L = csgs.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/csgs.h but not exported by libcsgs.so"
+    # and the binding knows each of them
+    assert set(names) <= set(csgs.EXPORTS), set(names) - set(csgs.EXPORTS)
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
+    assert C.sizeof(csgs.Graph) == 56
+    assert C.sizeof(csgs.Workspace) == 48
+    assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48
+    assert csgs.Workspace.epoch.offset == 40
+
+
+@pytest.mark.parametrize("nS,skew,rmax", [(8192, 16.0, 1.0), (256, 4.0, 1.0), (1, 1.0, 1.0), (3000, 2.5, 1.0),
+                                          (8192, 16.0, 4.0), (5, 1.0, 0.25), (100000, 1000.0, 1.0)])
+def test_fixed_point_matches_the_oracle_rule(nS, skew, rmax):
+    rc, shift, s_fx = csgs.csgs_fixed_point(nS, skew, rmax)
+    assert rc == csgs.OK
+    assert shift == oracle.shift_for(nS, skew, rmax)
+    assert s_fx == round(skew * 16)
+
+
+def test_fixed_point_rejects():
+    assert csgs.csgs_fixed_point(0, 2.0)[0] == csgs.EINVAL
+    assert csgs.csgs_fixed_point(10, 0.99)[0] == csgs.EINVAL
+    assert csgs.csgs_fixed_point(10, float("nan"))[0] == csgs.EINVAL
+    assert csgs.csgs_fixed_point(10, 2.0, 0.0)[0] == csgs.EINVAL
+    assert csgs.csgs_fixed_point(2 ** 30, 2.0 ** 20, 1.0)[0] == csgs.ERANGE     # fewer than 24 fraction bits
+
+
+def test_workspace_sizing():
+    b = csgs.csgs_workspace_bytes
+    assert b(0, 1, 1, 1) == 0 and b(10, 0, 1, 1) == 0 and b(10, 1, 0, 1) == 0 and b(10, 1, 1, 0) == 0
+    small, big = b(1000, 64, 64, 5000), b(2_449_029, 8192, 8192, 127_511_871)
+    assert 0 < small < big < 200 * 2 ** 20
+    assert small % 256 == 0 and big % 256 == 0
+    assert b(1000, 64, 64, 5000) <= b(1000, 128, 64, 5000) <= b(1000, 128, 128, 5000) <= b(1000, 128, 128, 50000)
+    assert 0 < csgs.csgs_workspace_clean_bytes(1000) < small
+
+
+def test_null_arguments_are_rejected_before_any_launch():
+    L = csgs.lib()
+    z = C.c_void_p(0)
+    assert L.csgs_build_probs(None, z, 1, 2.0, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
+    assert L.csgs_sample_layer(None, z, 1, z, z, 1, z, 1, 0, 0, 0, z, z, z, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
+    assert L.csgs_remote_count(z, z, 0, 1, z, 0, z, z, z, z, z) == csgs.EINVAL
+    assert L.csgs_aggregate(z, z, z, 1, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm(z, 1, 1, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
+    assert L.csgs_workspace_init(None, z) == csgs.EINVAL
+    ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0)
+    assert L.csgs_workspace_init(C.byref(ws), z) == csgs.EINVAL           # null base
+
+
+def test_error_strings():
+    assert csgs.strerror(csgs.OK) == "ok"
+    for code in (csgs.EINVAL, csgs.EWORKSPACE, csgs.EUNSUPPORTED, csgs.ERANGE, csgs.ELAUNCH):
+        assert csgs.strerror(code) not in ("ok", "unknown error")
+    assert csgs.strerror(-99) == "unknown error"
+
+
+def test_profile_interface_without_launches():
+    L = csgs.lib()
+    n = L.csgs_profile_kernel_count()
+    names = [L.csgs_profile_kernel_name(k).decode() for k in range(n)]
+    assert len(set(names)) == n and "aggregate" in names and "layer_gemm" in names
+    assert csgs.csgs_profile_collect() == {}
