@@ -38,7 +38,9 @@ def algorithmic_bytes(s, N):
     return {
         "row_prefix": 28 * nS,                              # S, two row pointers, prefix + start written
         "scan_edges": 8 * E + 16 * nS + 8 * nc,             # col + val per edge, row slices, accumulators
-        "cand_fused": N / 64 + 8 * nc + 20 * nc,            # flags, accumulators read, id + weight + cdf written
+        "cand_partials": N / 64 + 8 * nc,                   # flags, accumulators read
+        "cand_groups": 0.0,
+        "cand_emit": N / 64 + 8 * nc + 20 * nc,             # the same again, id + weight + cdf written
         "draw": 12 * B,                                     # cdf probes are cache traffic
         "hits_fused": nc / 8 + 36 * n2,                     # position bitmap, per hit: count, 2 cdf, id, 4 outputs
         "adj_fused": 4 * E + 16 * nS + 4 * nS + 20 * nnz,   # col per edge, row slices, row pointers, kept edges
@@ -259,7 +261,7 @@ def main():
         cfg_s = dataclasses.replace(cfg, batch=cfg.batch * sc, samples=cfg.samples * sc)
         rs = mk(cfg_s, 8).measure(6, 2)
         tr = load_traffic(f"{cfg.name}_x{sc}")
-        shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_fused")
+        shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_emit")
         scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
                       ms_per_step=rs["ms_per_step"],
                       sampled_edges_per_s=rs["per_step"]["sampled_edges"] / (rs["ms_per_step"] * 1e-3),

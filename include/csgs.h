@@ -82,7 +82,8 @@ typedef struct csgs_prob_stats {
     uint64_t w_remote;     /* sum_{k in R} ||w_*k||^2 */
     uint64_t total;        /* denominator of Eq. 10 in fixed point = cdf[n_cand - 1] */
     int32_t shift;         /* fraction bits of the fixed-point weights */
-    int32_t pad_;
+    int32_t skew_fx;       /* multiplier of local weights that was used, in 1/16 units (remote: 16);
+                              negative when remote candidates were given weight zero */
 } csgs_prob_stats;
 
 /* Scratch memory of the sampling calls: a host descriptor of a caller-owned device buffer.
@@ -126,7 +127,9 @@ int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift,
  * weight * s_fx for local j, weight * 16 for remote j.
  *
  *   S        [nS] distinct node ids, any order
- *   skew     s >= 1 (s = 1 is linear weighted sampling, Eq. 7); used in 1/16 steps
+ *   skew     s >= 1 (s = 1 is linear weighted sampling, Eq. 7); used in 1/16 steps.  +infinity
+ *            selects the "Local" version of Section 5.1: remote candidates keep their place in
+ *            the list but get probability zero
  *   cand_id  [cap] out: candidate ids ascending
  *   cand_w   [cap] out: fixed-point ||w_*j||^2 (unskewed)
  *   cdf      [cap] out: inclusive running sum of the skewed weights (cdf[n_cand-1] = total)
@@ -139,6 +142,19 @@ int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
                      int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
                      csgs_prob_stats *stats, csgs_workspace *ws /*host*/, int32_t *status,
                      void *stream);
+
+/*
+ * Same, with the skew chosen by Theorem 1 (Eq. 12) from the candidate counts of this very call:
+ *   s = D (|N(S_l)| - B) / |R| + 1/2,  raised to 1 when smaller, 1 when there is no remote
+ * candidate, cut at skew_max, rounded to 1/16 (half up); evaluated on the device in double.
+ * The fixed-point shift is the one of skew = skew_max, whatever s turns out to be.  The s that
+ * was used is reported in stats->skew_fx.  D >= 0 is the constant of the theorem (the paper
+ * sweeps 4, 8, 16, 32), B the sampling budget.
+ */
+int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float D, int32_t B,
+                          float skew_max, int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q,
+                          int64_t cap, csgs_prob_stats *stats, csgs_workspace *ws /*host*/,
+                          int32_t *status, void *stream);
 
 /*
  * B independent draws from q (Section 4.1: the sampling is run B times), deduplicated into

@@ -37,7 +37,7 @@ def build(force: bool = True) -> str:
 class _Stats(C.Structure):
     _fields_ = [("n_cand", C.c_int64), ("n_local", C.c_int64), ("n_remote", C.c_int64),
                 ("edges_scanned", C.c_int64), ("w_local", C.c_uint64), ("w_remote", C.c_uint64),
-                ("total", C.c_uint64), ("shift", C.c_int32)]
+                ("total", C.c_uint64), ("shift", C.c_int32), ("skew_fx", C.c_int32)]
 
 
 _lib = None
@@ -82,8 +82,15 @@ def shift_for(nS, skew, rownorm2_max=1.0):
     return int(lib().orc_shift(nS, skew, rownorm2_max))
 
 
-def build_probs(g, S, skew, cap=None):
-    """g: synth.Graph-like (n_nodes,rowptr,colidx,val,local_lo,local_hi,rownorm2_max)."""
+def theorem1_skew_fx(n_cand, n_remote, B, D, s_fx_max):
+    lib().orc_theorem1_skew_fx.restype = C.c_int64
+    return int(lib().orc_theorem1_skew_fx(C.c_int64(n_cand), C.c_int64(n_remote), C.c_int32(B), C.c_double(D),
+                                          C.c_int64(s_fx_max)))
+
+
+def build_probs(g, S, skew, cap=None, auto=None):
+    """g: synth.Graph-like (n_nodes,rowptr,colidx,val,local_lo,local_hi,rownorm2_max).
+    skew = inf: "Local" version.  auto = (D, B): skew from Theorem 1, `skew` is then its upper bound."""
     S = np.ascontiguousarray(S, dtype=np.int32)
     cap = int(g.n_nodes if cap is None else cap)
     cand_id = np.zeros(cap, np.int32)
@@ -91,16 +98,18 @@ def build_probs(g, S, skew, cap=None):
     cdf = np.zeros(cap, np.uint64)
     q = np.zeros(cap, np.float32)
     st = _Stats()
-    rc = lib().orc_build_probs(C.c_int64(g.n_nodes), _p(g.rowptr), _p(g.colidx), _p(g.val),
-                               C.c_int32(g.local_lo), C.c_int32(g.local_hi), C.c_float(g.rownorm2_max),
-                               _p(S), C.c_int32(len(S)), C.c_float(skew),
-                               _p(cand_id), _p(cand_w), _p(cdf), _p(q), C.c_int64(cap), C.byref(st))
+    mode = 1 if auto is not None else (2 if skew == float("inf") else 0)
+    D, B = auto if auto is not None else (0.0, 0)
+    rc = lib().orc_build_probs_ex(C.c_int64(g.n_nodes), _p(g.rowptr), _p(g.colidx), _p(g.val),
+                                  C.c_int32(g.local_lo), C.c_int32(g.local_hi), C.c_float(g.rownorm2_max),
+                                  _p(S), C.c_int32(len(S)), C.c_int(mode), C.c_float(skew), C.c_float(D), C.c_int32(B),
+                                  _p(cand_id), _p(cand_w), _p(cdf), _p(q), C.c_int64(cap), C.byref(st))
     _chk(rc)
     n = st.n_cand
     return SimpleNamespace(cand_id=cand_id[:n], cand_w=cand_w[:n], cdf=cdf[:n], q=q[:n],
                            n_cand=n, n_local=st.n_local, n_remote=st.n_remote,
                            edges_scanned=st.edges_scanned, w_local=st.w_local, w_remote=st.w_remote,
-                           total=st.total, shift=st.shift)
+                           total=st.total, shift=st.shift, skew_fx=st.skew_fx)
 
 
 def _sample_common(fn_name, g, S, probs, B, tail_args, adj_cap):

@@ -110,7 +110,24 @@ typedef struct {
     int64_t n_cand, n_local, n_remote, edges_scanned;
     uint64_t w_local, w_remote, total;
     int32_t shift;
+    int32_t skew_fx;   /* local multiplier used, in 1/16 units; negative: remote weight was zero */
 } orc_stats;
+
+/*
+ * Skew by Theorem 1 (Eq. 12): s = D (|N(S_l)| - B) / |R| + 1/2.  Readings: the text wants s > 1,
+ * so smaller values are raised to 1 (s = 1 is the unskewed sampler); |R| = 0 leaves nothing to
+ * skew against, s = 1; s is cut at the bound the fixed-point format was sized for and rounded
+ * to 1/16 (half up).  Returns s in 1/16 units.
+ */
+int64_t orc_theorem1_skew_fx(int64_t n_cand, int64_t n_remote, int32_t B, double D, int64_t s_fx_max)
+{
+    double sk = 1.0;
+    if (n_remote > 0) sk = D * (double)(n_cand - (int64_t)B) / (double)n_remote + 0.5;
+    if (!(sk >= 1.0)) sk = 1.0;
+    double fx = floor(sk * 16.0 + 0.5);
+    if (fx > (double)s_fx_max) fx = (double)s_fx_max;
+    return (int64_t)fx;
+}
 
 /*
  * Sampling distribution over N(S_l), the union of the neighbors of the nodes
@@ -119,18 +136,26 @@ typedef struct {
  * out: cand_id ascending, cand_w = fixed-point ||w_*j||^2 (unskewed),
  *      cdf = inclusive running sum of the skewed weights, q = Eq. 10 as float.
  */
-int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
-                    int32_t local_lo, int32_t local_hi, float rownorm2_max,
-                    const int32_t *S, int32_t nS, float skew,
-                    int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
-                    orc_stats *st)
+/*
+ * mode 0: skew s given (Eq. 10).  mode 1: s from Theorem 1 with constants D, B, the fixed-point
+ * format sized for `skew` as the upper bound of s.  mode 2: the "Local" version of Section 5.1,
+ * remote candidates get weight zero (they stay in the list and can never be drawn).
+ */
+int orc_build_probs_ex(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                       int32_t local_lo, int32_t local_hi, float rownorm2_max,
+                       const int32_t *S, int32_t nS, int mode, float skew, float D, int32_t B,
+                       int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
+                       orc_stats *st)
 {
+    if (mode == 2) skew = 1.0f;
     if (!rowptr || !colidx || !val || !S || !st || nS <= 0 || !(skew >= 1.0f) || skew > 1048576.0f ||
-        local_lo > local_hi || !(rownorm2_max > 0.0f))
+        local_lo > local_hi || !(rownorm2_max > 0.0f) || mode < 0 || mode > 2 ||
+        (mode == 1 && (!(D >= 0.0f) || B <= 0)))
         return ORC_EINVAL;
     int shift = orc_shift(nS, skew, rownorm2_max);
     if (shift < 24) return ORC_ERANGE;
     uint64_t s_fx = (uint64_t)orc_skew_fx(skew);
+    uint64_t s_remote = 16u;
 
     uint64_t *acc = (uint64_t *)calloc((size_t)n_nodes, sizeof(uint64_t));
     if (!acc) return ORC_ECAP;
@@ -151,6 +176,14 @@ int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colid
             st->edges_scanned++;
         }
     }
+    if (mode == 1) {   /* the counts |N(S_l)| and |R| of this very candidate set choose s */
+        int64_t nc = 0, nr = 0;
+        for (int64_t j = 0; j < n_nodes; ++j)
+            if (acc[j]) { ++nc; if (!(j >= local_lo && j < local_hi)) ++nr; }
+        s_fx = (uint64_t)orc_theorem1_skew_fx(nc, nr, B, (double)D, (int64_t)s_fx);
+    }
+    if (mode == 2) { s_fx = 16u; s_remote = 0u; }
+    st->skew_fx = (int32_t)s_fx * (s_remote ? 1 : -1);
     {
         uint64_t running = 0;
         int64_t n = 0;
@@ -158,7 +191,7 @@ int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colid
             if (!acc[j]) continue;
             if (n >= cap) { rc = ORC_ECAP; goto done; }
             int is_local = (j >= local_lo && j < local_hi);
-            uint64_t wskew = acc[j] * (is_local ? s_fx : 16u);   /* Eq. 10 numerator */
+            uint64_t wskew = acc[j] * (is_local ? s_fx : s_remote);   /* Eq. 10 numerator */
             running += wskew;
             cand_id[n] = (int32_t)j;
             cand_w[n] = acc[j];
@@ -169,7 +202,7 @@ int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colid
         }
         st->n_cand = n;
         st->total = running;
-        if (n == 0) { rc = ORC_EEMPTY; goto done; }
+        if (n == 0 || running == 0) { rc = ORC_EEMPTY; goto done; }
         if (q) {
             uint64_t prev = 0;
             for (int64_t k = 0; k < n; ++k) {
@@ -181,6 +214,17 @@ int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colid
 done:
     free(acc);
     return rc;
+}
+
+int orc_build_probs(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                    int32_t local_lo, int32_t local_hi, float rownorm2_max,
+                    const int32_t *S, int32_t nS, float skew,
+                    int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
+                    orc_stats *st)
+{
+    const int local_only = isinf(skew) && skew > 0;
+    return orc_build_probs_ex(n_nodes, rowptr, colidx, val, local_lo, local_hi, rownorm2_max, S, nS,
+                              local_only ? 2 : 0, skew, 0.0f, 0, cand_id, cand_w, cdf, q, cap, st);
 }
 
 /* -------------------------------------------------------- sample_layer */

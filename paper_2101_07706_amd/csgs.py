@@ -20,7 +20,7 @@ ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BA
 ST_EDGE_OVERFLOW, ST_INTERNAL = 32, 64
 F32, BF16 = 0, 1
 
-EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs",
+EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
            "csgs_calib_copy"]
@@ -49,7 +49,7 @@ class ProbStats(C.Structure):
     """csgs_prob_stats as laid out on the device (64 bytes)."""
     _fields_ = [("n_cand", C.c_int64), ("n_local", C.c_int64), ("n_remote", C.c_int64),
                 ("edges_scanned", C.c_int64), ("w_local", C.c_uint64), ("w_remote", C.c_uint64),
-                ("total", C.c_uint64), ("shift", C.c_int32), ("pad_", C.c_int32)]
+                ("total", C.c_uint64), ("shift", C.c_int32), ("skew_fx", C.c_int32)]
 
 
 _lib = None
@@ -70,6 +70,8 @@ def lib():
         L.csgs_workspace_init.argtypes = [C.POINTER(Workspace), vp]
         L.csgs_fixed_point.argtypes = [i32, f32, f32, C.POINTER(i32), C.POINTER(i64)]
         L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, f32, i32, f32, vp, vp, vp, vp, i64, vp,
+                                            C.POINTER(Workspace), vp, vp]
         L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
                                         vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
@@ -144,6 +146,12 @@ def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, str
     _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
                                 _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream)),
          "csgs_build_probs")
+
+
+def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, ws, status, stream=None):
+    _chk(lib().csgs_build_probs_auto(C.byref(g), _ptr(S), S.numel(), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
+                                     _ptr(cdf), _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status),
+                                     _stream(stream)), "csgs_build_probs_auto")
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,

@@ -40,7 +40,8 @@ struct Workspace {
     // persistent: zeroed once, then never cleared; an entry counts only if it carries the tag of
     // the current call
     uint64_t *rank;      // [n_nodes]  (tag << 32) | (position in S_next + 1)
-    uint64_t *cand_ts;   // scan state of the candidate tiles (4 sums per tile)
+    uint64_t *partial;   // [4 * n_tiles] per-tile candidate counts and weight sums
+    uint64_t *gtot;      // [4 * ceil(n_tiles / 64)] the same per group of 64 tiles
     uint64_t *hit_ts;    // scan state of the hit tiles (1 sum per tile)
     // per call
     int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows of S
@@ -76,7 +77,8 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.cbitmap = (uint64_t *)take(words * 8);
     w.clean_bytes = off;
     w.rank = (uint64_t *)take((size_t)n_nodes * 8);
-    w.cand_ts = (uint64_t *)take(scan_state_words(w.n_tiles, 4) * 8);
+    w.partial = (uint64_t *)take((size_t)w.n_tiles * 4 * 8);
+    w.gtot = (uint64_t *)take((size_t)((w.n_tiles + 63) / 64) * 4 * 8);
     w.hit_ts = (uint64_t *)take(scan_state_words(w.hit_tiles, 1) * 8);
     w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
     w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);

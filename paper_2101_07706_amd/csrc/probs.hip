@@ -9,15 +9,18 @@
 //                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
 //                  with fire-and-forget integer atomics (order-independent); flag the 64-node
 //                  word of the target with a plain byte store
-//   cand_fused     per tile of 1024 node ids, single pass: candidate count and weight sums of the
-//                  flagged words, prefix over earlier tiles by decoupled look-back, positions by
-//                  ballot popcount, inclusive wave scan of the skewed weights -> cand_id / cand_w /
-//                  cdf; restores accumulator and flags to zero; the last tile writes the stats
-//   fill_q         only when q is requested: skewed weight / total (the total is known only after
-//                  the last tile)
+//   cand_partials  per tile of 1024 node ids: candidate count, local count, local and remote
+//                  weight sums of the flagged words (unskewed, so they do not depend on s)
+//   cand_groups    one wavefront per 64 tiles: sums of the tile partials
+//   cand_emit      per tile: prefix = group sums before my group + tile sums before me in my
+//                  group (plain loads: the producers are earlier kernels); the skew multiplier is
+//                  fixed by the caller, or taken from the grand totals by the rule of Theorem 1
+//                  (Eq. 12), or zero for remote nodes ("Local" version of Section 5.1); positions
+//                  by ballot popcount, inclusive wave scan of the skewed weights -> cand_id /
+//                  cand_w / cdf / q; restores accumulator and flags to zero; the last tile writes
+//                  the stats
 #include <math.h>
 #include "common.hpp"
-#include "lookback.hpp"
 
 namespace csgs {
 
@@ -120,112 +123,187 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
 }
 
-__global__ __launch_bounds__(256) void cand_fused(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
-                                                  int32_t hi, uint64_t s_fx, unsigned long long tag,
-                                                  uint64_t *__restrict__ ts_mem, int32_t shift,
-                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
-                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
-                                                  uint64_t *__restrict__ cdf, int64_t cap)
+// Skew policy, resolved on the device once the candidate counts are known.
+struct SkewPolicy {
+    int mode;          // 0: s_fx given; 1: Theorem 1 from (D, B), clamped to [16, s_fx_max]; 2: remote weight 0
+    uint64_t s_fx;     // mode 0: local multiplier in 1/16 units
+    double D;          // mode 1
+    int64_t B;         // mode 1
+    uint64_t s_fx_max; // mode 1
+};
+
+// Multipliers of local and remote weights (Eq. 10 numerators in 1/16 units).
+__device__ inline void resolve_skew(const SkewPolicy &pol, uint64_t n_cand, uint64_t n_remote, uint64_t *m_local,
+                                    uint64_t *m_remote)
 {
-    constexpr int WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
-    __shared__ uint32_t s_cnt[WORDS];
-    __shared__ uint64_t s_w[WORDS];
-    __shared__ uint64_t s_aux[4][3];
-    __shared__ unsigned long long s_lb[4];
-    const int lane = lane_id();
-    const int wave = (int)(threadIdx.x >> 6);
-    const TileState<4> ts(ts_mem, n_tiles);
-    // one tile per block (the loop also covers a smaller, fully resident grid)
-    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint64_t words[WORDS / 4], w[WORDS / 4], wsk_incl[WORDS / 4];
-        uint64_t nloc = 0, wl = 0, wr = 0;
-#pragma unroll
-        for (int k = 0; k < WORDS / 4; ++k) {
-            const int slot = wave * (WORDS / 4) + k;
-            const int64_t word_idx = t * WORDS + slot;
-            const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
-            const int64_t id = word_idx * 64 + lane;
-            const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
-            const bool local = id >= lo && id < hi;
-            const uint64_t wsk = wv * (local ? s_fx : 16ull);
-            if (wv) {
-                if (local) { nloc += 1; wl += wv; } else { wr += wv; }
-            }
-            words[k] = __ballot(wv != 0);
-            w[k] = wv;
-            wsk_incl[k] = wave_inclusive_scan(wsk);
-            if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
-            if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
-        }
-        nloc = wave_sum(nloc); wl = wave_sum(wl); wr = wave_sum(wr);
-        if (lane == 0) { s_aux[wave][0] = nloc; s_aux[wave][1] = wl; s_aux[wave][2] = wr; }
-        __syncthreads();
-        // tile totals (tiny: computed redundantly by every thread)
-        uint64_t tile_cnt = 0, tile_w = 0, my_cnt = 0, my_w = 0;
-        for (int sl = 0; sl < WORDS; ++sl) {
-            if (sl == wave * (WORDS / 4)) { my_cnt = tile_cnt; my_w = tile_w; }
-            tile_cnt += s_cnt[sl]; tile_w += s_w[sl];
-        }
-        unsigned long long local[4], excl[4];
-        local[0] = (tile_cnt << 32) | (s_aux[0][0] + s_aux[1][0] + s_aux[2][0] + s_aux[3][0]);  // both halves stay below 2^31
-        local[1] = tile_w;
-        local[2] = s_aux[0][1] + s_aux[1][1] + s_aux[2][1] + s_aux[3][1];
-        local[3] = s_aux[0][2] + s_aux[1][2] + s_aux[2][2] + s_aux[3][2];
-        lookback<4>(ts, tag, t, n_tiles, local, excl, s_lb, status);
-        uint64_t base_cnt = (excl[0] >> 32) + my_cnt;
-        uint64_t base_w = excl[1] + my_w;
-#pragma unroll
-        for (int k = 0; k < WORDS / 4; ++k) {
-            const int slot = wave * (WORDS / 4) + k;
-            const int64_t word_idx = t * WORDS + slot;
-            const uint64_t word = words[k];
-            if (word) {
-                const int64_t id = word_idx * 64 + lane;
-                const bool set = (word >> lane) & 1ull;
-                const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
-                if (set) {
-                    wtable[id] = 0ull;  // back to the clean state
-                    if (pos < cap) {
-                        cand_id[pos] = (int32_t)id;
-                        cand_w[pos] = w[k];
-                        cdf[pos] = base_w + wsk_incl[k];
-                    }
-                }
-            }
-            base_cnt += s_cnt[slot];
-            base_w += s_w[slot];
-        }
-        if (t == n_tiles - 1 && threadIdx.x == 0) {
-            const uint64_t tot_cnt = (excl[0] >> 32) + tile_cnt;
-            const uint64_t tot_loc = (excl[0] & 0xFFFFFFFFull) + (local[0] & 0xFFFFFFFFull);
-            stats->n_cand = (int64_t)tot_cnt;
-            stats->n_local = (int64_t)tot_loc;
-            stats->n_remote = (int64_t)(tot_cnt - tot_loc);
-            stats->w_local = excl[2] + local[2];
-            stats->w_remote = excl[3] + local[3];
-            stats->total = excl[1] + tile_w;
-            stats->shift = shift;
-            stats->pad_ = 0;
-            int32_t st = 0;
-            if (tot_cnt == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
-            if ((int64_t)tot_cnt > cap) st |= CSGS_ST_CAND_OVERFLOW;
-            if (st) atomicOr(status, st);
-        }
-        __syncthreads();  // the shared arrays are reused by the next tile
+    *m_remote = 16ull;
+    if (pol.mode == 0) {
+        *m_local = pol.s_fx;
+    } else if (pol.mode == 1) {
+        // s = D (|N(S_l)| - B) / |R| + 1/2 (Eq. 12), at least 1, no remote candidates -> 1
+        double sk = 1.0;
+        if (n_remote > 0) sk = pol.D * (double)((int64_t)n_cand - pol.B) / (double)n_remote + 0.5;
+        if (!(sk >= 1.0)) sk = 1.0;
+        double fx = floor(sk * 16.0 + 0.5);
+        if (fx > (double)pol.s_fx_max) fx = (double)pol.s_fx_max;
+        *m_local = (uint64_t)fx;
+    } else {
+        *m_local = 16ull;
+        *m_remote = 0ull;
     }
 }
 
-__global__ __launch_bounds__(256) void fill_q(const uint64_t *__restrict__ cdf,
-                                              const csgs_prob_stats *__restrict__ stats, int64_t cap,
-                                              float *__restrict__ q)
+constexpr int CAND_WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
+
+__global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
+                                                     const uint8_t *__restrict__ tileflag, int64_t n_words,
+                                                     int64_t n_nodes, int32_t lo, int32_t hi,
+                                                     uint64_t *__restrict__ partial)
 {
-    int64_t n = stats->n_cand;
-    if (n > cap) n = cap;
-    const double total = (double)stats->total;
-    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (int64_t)gridDim.x * blockDim.x) {
-        const uint64_t wsk = cdf[k] - (k ? cdf[k - 1] : 0ull);
-        q[k] = (float)((double)wsk / total);
+    __shared__ uint64_t lds[4][3];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t word_idx = (int64_t)blockIdx.x * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
+        if (word_idx >= n_words || tileflag[word_idx] == 0) continue;
+        const int64_t id = word_idx * 64 + lane;
+        const uint64_t w = id < n_nodes ? wtable[id] : 0ull;
+        if (w) {
+            const bool local = id >= lo && id < hi;
+            cn += (1ull << 32) | (local ? 1ull : 0ull);
+            if (local) wl += w; else wr += w;
+        }
+    }
+    cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
+    if (lane == 0) { lds[wave][0] = cn; lds[wave][1] = wl; lds[wave][2] = wr; }
+    __syncthreads();
+    if (threadIdx.x < 3)  // packed count halves cannot carry: each is at most 1024 per tile
+        partial[(int64_t)blockIdx.x * 4 + threadIdx.x] = lds[0][threadIdx.x] + lds[1][threadIdx.x] + lds[2][threadIdx.x] + lds[3][threadIdx.x];
+}
+
+__global__ __launch_bounds__(64) void cand_groups(const uint64_t *__restrict__ partial, int64_t n_tiles,
+                                                  uint64_t *__restrict__ gtot)
+{
+    const int64_t t = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    uint64_t v[3] = {0, 0, 0};
+    if (t < n_tiles) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) v[i] = partial[t * 4 + i];
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) v[i] = wave_sum(v[i]);
+    if (threadIdx.x < 3) gtot[(int64_t)blockIdx.x * 4 + threadIdx.x] = v[threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
+                                                 int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
+                                                 int32_t hi, SkewPolicy pol, const uint64_t *__restrict__ partial,
+                                                 const uint64_t *__restrict__ gtot, int32_t shift,
+                                                 csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
+                                                 int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
+                                                 uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
+{
+    __shared__ uint32_t s_cnt[CAND_WORDS];
+    __shared__ uint64_t s_w[CAND_WORDS];
+    __shared__ uint64_t s_red[4][6];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t t = blockIdx.x;
+    const int64_t g = t / 64, n_groups = (n_tiles + 63) / 64;
+    // sums over everything (tot) and over what lies before this tile (pre): group sums before my
+    // group, then tile sums before me inside my group
+    uint64_t tot[3] = {0, 0, 0}, pre[3] = {0, 0, 0};
+    for (int64_t j = threadIdx.x; j < n_groups; j += blockDim.x) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint64_t v = gtot[j * 4 + i];
+            tot[i] += v;
+            if (j < g) pre[i] += v;
+        }
+    }
+    {
+        const int64_t j = g * 64 + threadIdx.x;
+        if (threadIdx.x < 64 && j < t) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) pre[i] += partial[j * 4 + i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) { tot[i] = wave_sum(tot[i]); pre[i] = wave_sum(pre[i]); }
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) { s_red[wave][i] = tot[i]; s_red[wave][3 + i] = pre[i]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        tot[i] = s_red[0][i] + s_red[1][i] + s_red[2][i] + s_red[3][i];
+        pre[i] = s_red[0][3 + i] + s_red[1][3 + i] + s_red[2][3 + i] + s_red[3][3 + i];
+    }
+    const uint64_t n_cand = tot[0] >> 32, n_local = tot[0] & 0xFFFFFFFFull;
+    uint64_t m_local, m_remote;
+    resolve_skew(pol, n_cand, n_cand - n_local, &m_local, &m_remote);
+    const uint64_t total_w = tot[1] * m_local + tot[2] * m_remote;
+    const double total_d = (double)total_w;
+
+    uint64_t words[CAND_WORDS / 4], w[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int slot = wave * (CAND_WORDS / 4) + k;
+        const int64_t word_idx = t * CAND_WORDS + slot;
+        const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
+        const int64_t id = word_idx * 64 + lane;
+        const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
+        const bool local = id >= lo && id < hi;
+        const uint64_t wsk = wv * (local ? m_local : m_remote);
+        words[k] = __ballot(wv != 0);
+        w[k] = wv;
+        wsk_incl[k] = wave_inclusive_scan(wsk);
+        if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
+        if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
+    }
+    __syncthreads();
+    uint64_t base_cnt = pre[0] >> 32;
+    uint64_t base_w = pre[1] * m_local + pre[2] * m_remote;
+    for (int sl = 0; sl < wave * (CAND_WORDS / 4); ++sl) { base_cnt += s_cnt[sl]; base_w += s_w[sl]; }
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int slot = wave * (CAND_WORDS / 4) + k;
+        const int64_t word_idx = t * CAND_WORDS + slot;
+        const uint64_t word = words[k];
+        if (word) {
+            const int64_t id = word_idx * 64 + lane;
+            const bool set = (word >> lane) & 1ull;
+            const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
+            if (set) {
+                wtable[id] = 0ull;  // back to the clean state
+                if (pos < cap) {
+                    const bool local = id >= lo && id < hi;
+                    cand_id[pos] = (int32_t)id;
+                    cand_w[pos] = w[k];
+                    cdf[pos] = base_w + wsk_incl[k];
+                    if (q) q[pos] = (float)((double)(w[k] * (local ? m_local : m_remote)) / total_d);
+                }
+            }
+        }
+        base_cnt += s_cnt[slot];
+        base_w += s_w[slot];
+    }
+    if (t == n_tiles - 1 && threadIdx.x == 0) {
+        stats->n_cand = (int64_t)n_cand;
+        stats->n_local = (int64_t)n_local;
+        stats->n_remote = (int64_t)(n_cand - n_local);
+        stats->w_local = tot[1];
+        stats->w_remote = tot[2];
+        stats->total = total_w;
+        stats->shift = shift;
+        stats->skew_fx = (int32_t)m_local * (m_remote ? 1 : -1);
+        int32_t st = 0;
+        if (n_cand == 0 || total_w == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
+        if ((int64_t)n_cand > cap) st |= CSGS_ST_CAND_OVERFLOW;
+        if (st) atomicOr(status, st);
     }
 }
 
@@ -289,22 +367,25 @@ extern "C" int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int3
     return sh < 24 ? CSGS_ERANGE : CSGS_OK;
 }
 
-extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t nS, float skew, int32_t *cand_id,
-                                uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap, csgs_prob_stats *stats,
-                                csgs_workspace *ws, int32_t *status, void *stream)
+static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, float shift_skew, SkewPolicy pol,
+                            int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
+                            csgs_prob_stats *stats, csgs_workspace *ws, int32_t *status, void *stream)
 {
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll ||
         g->local_lo > g->local_hi || !S || nS <= 0 || !cand_id || !cand_w || !cdf || cap <= 0 || !stats || !ws || !status)
         return CSGS_EINVAL;
     int32_t shift;
     int64_t s_fx;
-    int rc = csgs_fixed_point(nS, skew, g->rownorm2_max, &shift, &s_fx);
+    int rc = csgs_fixed_point(nS, shift_skew, g->rownorm2_max, &shift, &s_fx);
     if (rc != CSGS_OK) return rc;
+    if (pol.mode == 0) pol.s_fx = (uint64_t)s_fx;
+    if (pol.mode == 1) pol.s_fx_max = (uint64_t)s_fx;
     Workspace w;
     rc = open_workspace(ws, g->n_nodes, nS, 1, &w);
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int64_t n_words = (g->n_nodes + 63) / 64;
+    const unsigned n_groups = (unsigned)((w.n_tiles + 63) / 64);
 
     CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, g->rowptr, g->n_nodes, S, nS, w.eoff, w.rowstart,
                 w.chunk_cap * EDGE_TILE, stats, status);
@@ -312,17 +393,37 @@ extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t n
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, nS, w.eoff,
                 w.rowstart, ldexp(1.0, shift), w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
-    const unsigned long long tag = ++ws->epoch;
-    const int64_t cand_grid = w.n_tiles;  // one tile per block, dispatched in ascending order
-    CSGS_LAUNCH(K_CAND_FUSED, cand_fused, dim3((unsigned)cand_grid), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, (uint64_t)s_fx, tag, w.cand_ts, shift, stats, status,
-                cand_id, cand_w, cdf, cap);
+    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+                g->n_nodes, g->local_lo, g->local_hi, w.partial);
     CSGS_LAUNCH_CHECK();
-    if (q) {
-        const int64_t qn = cap < g->n_nodes ? cap : g->n_nodes;
-        const unsigned qb = (unsigned)((qn + 255) / 256 < 2048 ? (qn + 255) / 256 : 2048);
-        CSGS_LAUNCH(K_FILL_Q, fill_q, dim3(qb), dim3(256), st, cdf, stats, cap, q);
-        CSGS_LAUNCH_CHECK();
-    }
+    CSGS_LAUNCH(K_CAND_GROUPS, cand_groups, dim3(n_groups), dim3(64), st, w.partial, w.n_tiles, w.gtot);
+    CSGS_LAUNCH_CHECK();
+    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, shift, stats, status, cand_id,
+                cand_w, cdf, q, cap);
+    CSGS_LAUNCH_CHECK();
     return CSGS_OK;
+}
+
+extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t nS, float skew, int32_t *cand_id,
+                                uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap, csgs_prob_stats *stats,
+                                csgs_workspace *ws, int32_t *status, void *stream)
+{
+    SkewPolicy pol = {0, 0, 0.0, 0, 0};
+    float shift_skew = skew;
+    if (isinf(skew) && skew > 0) {   // "Local" version: remote candidates get probability zero
+        pol.mode = 2;
+        shift_skew = 1.0f;
+    }
+    return build_probs_impl(g, S, nS, shift_skew, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
+}
+
+extern "C" int csgs_build_probs_auto(const csgs_graph *g, const int32_t *S, int32_t nS, float D, int32_t B,
+                                     float skew_max, int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q,
+                                     int64_t cap, csgs_prob_stats *stats, csgs_workspace *ws, int32_t *status,
+                                     void *stream)
+{
+    if (!(D >= 0.0f) || !isfinite(D) || B <= 0) return CSGS_EINVAL;
+    SkewPolicy pol = {1, 0, (double)D, (int64_t)B, 0};
+    return build_probs_impl(g, S, nS, skew_max, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
 }

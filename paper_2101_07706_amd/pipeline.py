@@ -63,14 +63,19 @@ class LayerBuffers:
         s = csgs.ProbStats.from_buffer_copy(raw)
         return SimpleNamespace(n_cand=s.n_cand, n_local=s.n_local, n_remote=s.n_remote,
                                edges_scanned=s.edges_scanned, w_local=s.w_local, w_remote=s.w_remote,
-                               total=s.total, shift=s.shift)
+                               total=s.total, shift=s.shift, skew_fx=s.skew_fx)
 
 
-def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True):
-    """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32)."""
+def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None):
+    """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32).
+    auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound."""
     nS = S.numel()
-    csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, lb.q if want_q else None, lb.stats, ws.desc,
-                          lb.status, stream)
+    q = lb.q if want_q else None
+    if auto_D is None:
+        csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc, lb.status, stream)
+    else:
+        csgs.csgs_build_probs_auto(dg.c, S, auto_D, B, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc,
+                                   lb.status, stream)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
                            ws.desc, lb.status, stream)

@@ -13,13 +13,14 @@ RTOL, ATOL = 1e-4, 1e-5          # fp32 aggregation and GEMM outputs (stated tar
 P_RTOL = 2.5e-7                  # p_incl, adj_val: fp64 results rounded to fp32, libm differences <= 2 ulp
 
 
-def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False):
-    """Top-down sampling then bottom-up compute.  Ws: bottom layer first.  Returns per-step records."""
+def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, auto_D=None):
+    """Top-down sampling then bottom-up compute.  Ws: bottom layer first.  Returns per-step records.
+    skew = inf: "Local" version.  auto_D: skew by Theorem 1 with this constant, `skew` its upper bound."""
     M = len(Ws)
     steps = []
     S = np.ascontiguousarray(S0, np.int32)
     for l in range(M):
-        pr = oracle.build_probs(g, S, skew)
+        pr = oracle.build_probs(g, S, skew, auto=None if auto_D is None else (auto_D, B))
         sm = oracle.sample_layer(g, S, pr, B, seed, it, l)
         rc = oracle.remote_count(sm.S_next, g.local_lo, g.local_hi, g.part_bounds)
         steps.append(SimpleNamespace(S=S, pr=pr, sm=sm, rc=rc))
@@ -40,7 +41,7 @@ def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False):
     return steps
 
 
-def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None):
+def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None, auto_D=None):
     import torch
     from paper_2101_07706_amd import pipeline
     dev = torch.device("cuda:0")
@@ -59,7 +60,7 @@ def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None
         Sh = S.cpu().numpy().astype(np.int64)
         cap = adj_cap or int((g.rowptr[Sh + 1] - g.rowptr[Sh]).sum())
         lb = pipeline.LayerBuffers(S.numel(), B, g.n_nodes, cap, dg.n_parts, dev)
-        pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lb)
+        pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lb, auto_D=auto_D)
         n = int(lb.n_next.item())
         steps.append(SimpleNamespace(S=S, lb=lb, n_next=n, status=int(lb.status.item())))
         S = lb.S_next[:n].clone()
@@ -113,7 +114,7 @@ def compare_chain(osteps, gsteps, check_compute=True):
         assert gs.status == 0, f"layer {l}: status {gs.status}"
         st = lb.stats_host()
         pr, sm, rc = o.pr, o.sm, o.rc
-        for k in ("n_cand", "n_local", "n_remote", "edges_scanned", "w_local", "w_remote", "total", "shift"):
+        for k in ("n_cand", "n_local", "n_remote", "edges_scanned", "w_local", "w_remote", "total", "shift", "skew_fx"):
             assert int(getattr(st, k)) == int(getattr(pr, k)), f"layer {l}: stats.{k}"
         n = pr.n_cand
         np.testing.assert_array_equal(lb.cand_id[:n].cpu().numpy(), pr.cand_id, err_msg=f"layer {l} cand_id")

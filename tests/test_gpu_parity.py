@@ -150,6 +150,44 @@ def test_small_graphs(dev, n, avg_deg, nS, B, skew, lo, hi):
     chain.compare_chain(osteps, gsteps)
 
 
+@pytest.mark.parametrize("policy", ["auto_D4", "auto_D32", "auto_D0", "local"])
+@pytest.mark.parametrize("n,avg_deg,nS,B,lo,hi", [(1000, 8, 65, 64, 300, 600), (5000, 40, 333, 257, 0, 1250),
+                                                  (3000, 5, 17, 4100, 1000, 1000), (70, 3, 70, 500, 0, 70)])
+def test_skew_policies(dev, policy, n, avg_deg, nS, B, lo, hi):
+    """Skew chosen on the device by Theorem 1 (Eq. 12), and the Local version, against the oracle."""
+    g = SmallGraph(n, avg_deg, seed=n + nS, lo=lo, hi=hi)
+    rng = np.random.default_rng(11)
+    S0 = rng.choice(n, size=nS, replace=False).astype(np.int32)
+    X = rng.standard_normal((n, 12)).astype(np.float32)
+    Ws = [synth.glorot_uniform(12, 9, 1), synth.glorot_uniform(9, 6, 2)]
+    if policy == "local":
+        kw = dict(skew=float("inf"))
+    else:
+        kw = dict(skew=1024.0, auto_D=float(policy[6:]))
+    say(f"[policy] {policy} n={n} nS={nS} B={B}")
+    if policy == "local" and lo == hi:
+        with pytest.raises(oracle.OracleError):      # no local candidate at all: nothing can be drawn
+            chain.oracle_chain(g, X, Ws, S0, B=B, seed=42, it=7, **kw)
+        return
+    osteps = chain.oracle_chain(g, X, Ws, S0, B=B, seed=42, it=7, **kw)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, B=B, seed=42, it=7, **kw)
+    chain.compare_chain(osteps, gsteps)
+    say(f"[policy] skew_fx per layer: {[o.pr.skew_fx for o in osteps]} remote: {[o.rc.remote_total for o in osteps]}")
+
+
+def test_tiny_config_theorem1_sweep(dev):
+    """The paper's sweep of D (Section 5.2: 4, 8, 16, 32) on the Tiny configuration."""
+    cfg, g, X, Ws, S0 = chain.config_inputs("tiny")
+    remote = []
+    for D in (4.0, 8.0, 16.0, 32.0):
+        osteps = chain.oracle_chain(g, X, Ws, S0, 4096.0, cfg.samples, 77, 0, auto_D=D)
+        gsteps, _ = chain.gpu_chain(g, X, Ws, S0, 4096.0, cfg.samples, 77, 0, auto_D=D)
+        chain.compare_chain(osteps, gsteps)
+        remote.append(sum(o.rc.remote_total for o in osteps))
+        say(f"[tiny] D={D}: skew_fx {[o.pr.skew_fx for o in osteps]} remote {remote[-1]}")
+    assert remote[-1] < remote[0]
+
+
 def _drop_rows(g, rows):
     """Remove every edge of the given rows (they become empty rows; P is no longer symmetric, which
     the method does not need)."""

@@ -197,6 +197,60 @@ def test_variance_closed_forms():
         assert math.isclose(got, line2, rel_tol=1e-11)
 
 
+# ----------------------------------------------- Theorem 1 (Eq. 12) and the "Local" version
+
+@pytest.mark.parametrize("n_c,n_r,B,D,cap,want", [
+    (1000, 200, 100, 4.0, 10 ** 6, 296),      # 4 * 900 / 200 + 0.5 = 18.5
+    (1000, 200, 100, 0.0, 10 ** 6, 16),       # D = 0 gives 1/2, raised to 1
+    (50, 40, 100, 8.0, 10 ** 6, 16),          # budget above the candidate count: negative, raised to 1
+    (1000, 0, 100, 8.0, 10 ** 6, 16),         # no remote candidates
+    (1000, 1, 100, 32.0, 4096, 4096),         # cut at the bound
+    (700, 300, 256, 1.0, 10 ** 6, 32),        # 444 / 300 + 0.5 = 1.98 -> 31.68 -> 32
+])
+def test_theorem1_skew_values(n_c, n_r, B, D, cap, want):
+    assert oracle.theorem1_skew_fx(n_c, n_r, B, D, cap) == want
+
+
+@pytest.mark.parametrize("D", [0.5, 4.0, 32.0])
+def test_theorem1_keeps_the_variance_bound(D):
+    # the theorem's s = T1 / 2 satisfies V_skewed <= D1 V_lnr with D1 = 2 D + 1 (proof of Theorem 1)
+    tg = TinyGraph(16, 0.45, 21, lo=3, hi=9)
+    S = np.array([1, 4, 8, 12], np.int32)
+    B = 4
+    lin = oracle.build_probs(tg, S, 1.0)
+    sk = oracle.build_probs(tg, S, 4096.0, auto=(D, B))
+    assert sk.skew_fx == oracle.theorem1_skew_fx(lin.n_cand, lin.n_remote, B, D, 4096 * 16)
+    s = sk.skew_fx / 16.0
+    w = sk.cand_w.astype(np.float64)    # same weights as the unskewed run, on a coarser fixed-point grid
+    np.testing.assert_allclose(w, lin.cand_w.astype(np.float64) * 2.0 ** (sk.shift - lin.shift), rtol=1e-9)
+    q_lin = np.diff(np.concatenate([[0], lin.cdf.astype(np.float64)])) / float(lin.total)
+    q_sk = np.diff(np.concatenate([[0], sk.cdf.astype(np.float64)])) / float(sk.total)
+    v_lnr, v_sk = _upper_bound_variance(w, q_lin, B), _upper_bound_variance(w, q_sk, B)
+    assert v_lnr > 0
+    assert v_sk <= (2 * D + 1) * v_lnr * (1 + 1e-9)
+    # and it is the skewed distribution of Eq. 10 with that s
+    loc = (sk.cand_id >= 3) & (sk.cand_id < 9)
+    num = np.where(loc, s, 1.0) * w
+    np.testing.assert_allclose(q_sk, num / num.sum(), rtol=1e-12)
+
+
+def test_local_version_never_draws_remote_nodes():
+    tg = TinyGraph(16, 0.4, 9, lo=5, hi=12)
+    S = np.array([0, 6, 11, 15], np.int32)
+    full = oracle.build_probs(tg, S, 1.0)
+    loc = oracle.build_probs(tg, S, float("inf"))
+    assert loc.cand_id.tolist() == full.cand_id.tolist() and loc.skew_fx == -16
+    is_loc = (loc.cand_id >= 5) & (loc.cand_id < 12)
+    assert np.all(loc.q[~is_loc] == 0) and abs(float(loc.q[is_loc].astype(np.float64).sum()) - 1) < 1e-6
+    # restricted to the local candidates it is linear weighted sampling (Eq. 7)
+    w = full.cand_w.astype(np.float64)
+    np.testing.assert_allclose(loc.q[is_loc], w[is_loc] / w[is_loc].sum(), rtol=1e-6)
+    for it in range(20):
+        sm = oracle.sample_layer(tg, S, loc, 8, seed=3, it=it, layer=0)
+        assert np.all((sm.S_next >= 5) & (sm.S_next < 12))
+        assert oracle.remote_count(sm.S_next, 5, 12).remote_total == 0
+
+
 # ------------------------------------------- exhaustive unbiasedness (Eq. 3 + Eq. 8)
 
 def _word_for_candidate(cdf, k):
