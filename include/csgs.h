@@ -97,7 +97,11 @@ typedef struct csgs_workspace {
     int64_t n_nodes;
     int32_t nS_max, B_max;
     int64_t edges_max;
-    uint64_t epoch; /* owned by the library: calls made with this workspace; set to 0 before init */
+    /* owned by the library (csgs_workspace_init resets them): */
+    uint64_t epoch;      /* kernels tagged so far */
+    uint64_t draw_epoch; /* tag of the latest csgs_draw_nodes, 0 = none */
+    int32_t draw_B;      /* its B */
+    int32_t pad_;
 } csgs_workspace;
 
 /* Bytes needed for a workspace of these sizes; 0 on bad input. */
@@ -182,6 +186,28 @@ int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS
                       int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
                       int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
                       void *stream);
+
+/*
+ * The two halves of csgs_sample_layer, for samplers that draw once and then need the sampled
+ * operator for other rows than the ones the distribution was built from (the subgraph sampler of
+ * Section 5.1 takes all training nodes as candidates, draws the subgraph's nodes, and runs the
+ * full convolution on the subgraph: rows = the drawn nodes themselves).
+ *
+ * csgs_draw_nodes: the B draws, S_next / mult / p_incl / n_next as in csgs_sample_layer.  It
+ * leaves the node -> position table and the double inclusion probabilities in the workspace.
+ * csgs_sampled_adjacency: CSR of P~ (Eq. 3) for `rows` (n_rows node ids, device) against the node
+ * set of the latest csgs_draw_nodes on the same workspace; outputs as in csgs_sample_layer.
+ * Host errors: CSGS_EINVAL (also: no draw has run), CSGS_EWORKSPACE (n_rows above nS_max).
+ * Status bits: ADJ_OVERFLOW, EDGE_OVERFLOW, BAD_NODE_ID.
+ */
+int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
+                    const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter,
+                    uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
+                    csgs_workspace *ws /*host*/, int32_t *status, void *stream);
+int csgs_sampled_adjacency(const csgs_graph *g /*host*/, const int32_t *rows, int32_t n_rows,
+                           int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
+                           int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
+                           void *stream);
 
 /*
  * Communication volume of the step (Eq. 4; Section 5.2 reports the number of nodes whose

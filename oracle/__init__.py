@@ -153,6 +153,38 @@ def sample_from_words(g, S, probs, words, adj_cap=None):
     return out
 
 
+def draw_nodes(probs, B, seed, it, layer):
+    """Draws only (no adjacency): S_next, mult, p_incl and the inclusion probabilities in double."""
+    cand_id = np.ascontiguousarray(probs.cand_id, np.int32)
+    cdf = np.ascontiguousarray(probs.cdf, np.uint64)
+    S_next, mult = np.zeros(B, np.int32), np.zeros(B, np.int32)
+    p_incl, pd = np.zeros(B, np.float32), np.zeros(B, np.float64)
+    n = C.c_int32(0)
+    _chk(lib().orc_draw_nodes(_p(cand_id), _p(cdf), C.c_int64(len(cand_id)), C.c_int32(B), C.c_uint64(seed),
+                              C.c_uint64(it), C.c_uint32(layer), _p(S_next), _p(mult), _p(p_incl), _p(pd), C.byref(n)))
+    n = n.value
+    return SimpleNamespace(S_next=S_next[:n], mult=mult[:n], p_incl=p_incl[:n], pd=pd[:n], n_next=n)
+
+
+def sampled_adjacency(g, rows, draw, adj_cap=None):
+    """Eq. 3 adjacency of the given rows against the drawn set `draw` (from draw_nodes)."""
+    rows = np.ascontiguousarray(rows, np.int32)
+    if adj_cap is None:
+        r64 = rows.astype(np.int64)
+        adj_cap = int((g.rowptr[r64 + 1] - g.rowptr[r64]).sum())
+    adj_rowptr = np.zeros(len(rows) + 1, np.int32)
+    adj_col = np.zeros(max(adj_cap, 1), np.int32)
+    adj_val = np.zeros(max(adj_cap, 1), np.float32)
+    nnz = C.c_int64(0)
+    S_next = np.ascontiguousarray(draw.S_next, np.int32)
+    pd = np.ascontiguousarray(draw.pd, np.float64)
+    _chk(lib().orc_sampled_adjacency(C.c_int64(g.n_nodes), _p(g.rowptr), _p(g.colidx), _p(g.val), _p(rows),
+                                     C.c_int32(len(rows)), _p(S_next), C.c_int32(len(S_next)), _p(pd),
+                                     _p(adj_rowptr), _p(adj_col), _p(adj_val), C.c_int64(adj_cap), C.byref(nnz)))
+    nnz = nnz.value
+    return SimpleNamespace(adj_rowptr=adj_rowptr, adj_col=adj_col[:nnz], adj_val=adj_val[:nnz], adj_nnz=nnz)
+
+
 def draw_positions(cdf, B, seed, it, layer):
     cdf = np.ascontiguousarray(cdf, np.uint64)
     pos = np.zeros(B, np.int64)

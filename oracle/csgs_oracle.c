@@ -246,29 +246,19 @@ static int64_t first_greater(const uint64_t *cdf, int64_t n, uint64_t u)
 }
 
 /*
- * Draws given as explicit 64-bit words (so that tests can enumerate them).
- * B draws with replacement from q (Section 4.1, "run the sampling for B
- * times"), deduplicated to the ascending node set S_next with multiplicities;
- * p_incl from Eq. 8; sampled adjacency from Eq. 3: rows in S order, columns =
- * position in S_next ascending, value w_ij / p_j.
+ * B draws with replacement from q (Section 4.1, "run the sampling for B times"), the draws given
+ * as explicit 64-bit words so that tests can enumerate them; deduplicated to the ascending node
+ * set S_next with multiplicities; inclusion probability from Eq. 8 (pd in double, p_incl as float).
  */
-int orc_sample_from_words(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
-                          const int32_t *S, int32_t nS,
-                          const int32_t *cand_id, const uint64_t *cdf, int64_t n_cand,
-                          const uint64_t *words, int32_t B,
-                          int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
-                          int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
-                          int64_t *adj_nnz)
+int orc_draw_from_words(const int32_t *cand_id, const uint64_t *cdf, int64_t n_cand,
+                        const uint64_t *words, int32_t B,
+                        int32_t *S_next, int32_t *mult, float *p_incl, double *pd, int32_t *n_next)
 {
-    if (!cand_id || !cdf || n_cand <= 0 || B <= 0 || !words || nS <= 0) return ORC_EINVAL;
+    if (!cand_id || !cdf || n_cand <= 0 || B <= 0 || !words) return ORC_EINVAL;
     uint64_t total = cdf[n_cand - 1];
     if (total == 0) return ORC_EEMPTY;
     int32_t *cnt = (int32_t *)calloc((size_t)n_cand, sizeof(int32_t));
-    int32_t *rank = (int32_t *)malloc((size_t)n_nodes * sizeof(int32_t));
-    double *pd = (double *)malloc((size_t)B * sizeof(double));
-    if (!cnt || !rank || !pd) { free(cnt); free(rank); free(pd); return ORC_ECAP; }
-    for (int64_t j = 0; j < n_nodes; ++j) rank[j] = -1;
-
+    if (!cnt) return ORC_ECAP;
     for (int32_t t = 0; t < B; ++t) {
         uint64_t u = mulhi64(words[t], total);
         cnt[first_greater(cdf, n_cand, u)]++;
@@ -283,16 +273,34 @@ int orc_sample_from_words(int64_t n_nodes, const int64_t *rowptr, const int32_t 
         mult[n] = cnt[k];
         pd[n] = pk;
         p_incl[n] = (float)pk;
-        rank[cand_id[k]] = n;
         ++n;
     }
     *n_next = n;
+    free(cnt);
+    return ORC_OK;
+}
 
+/*
+ * Sampled adjacency of Eq. 3 for an arbitrary row set: rows in the given order, columns =
+ * position in S_next ascending, value w_ij / p_j.  With rows = S_l it is the layer operator P~;
+ * with rows = S_next it is the sampled subgraph on which a subgraph sampler runs the full
+ * convolution (Section 5.1, second sampler).
+ */
+int orc_sampled_adjacency(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                          const int32_t *rows, int32_t n_rows, const int32_t *S_next, int32_t n_next,
+                          const double *pd, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
+                          int64_t adj_cap, int64_t *adj_nnz)
+{
+    if (!rows || n_rows <= 0 || !S_next || n_next < 0 || !pd) return ORC_EINVAL;
+    int32_t *rank = (int32_t *)malloc((size_t)n_nodes * sizeof(int32_t));
+    if (!rank) return ORC_ECAP;
+    for (int64_t j = 0; j < n_nodes; ++j) rank[j] = -1;
+    for (int32_t k = 0; k < n_next; ++k) rank[S_next[k]] = k;
     int rc = ORC_OK;
     int64_t nnz = 0;
     adj_rowptr[0] = 0;
-    for (int32_t a = 0; a < nS; ++a) {
-        int32_t i = S[a];
+    for (int32_t a = 0; a < n_rows; ++a) {
+        int32_t i = rows[a];
         for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
             int32_t r = rank[colidx[e]];
             if (r < 0) continue;
@@ -305,7 +313,40 @@ int orc_sample_from_words(int64_t n_nodes, const int64_t *rowptr, const int32_t 
     }
     *adj_nnz = nnz;
 done:
-    free(cnt); free(rank); free(pd);
+    free(rank);
+    return rc;
+}
+
+int orc_sample_from_words(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                          const int32_t *S, int32_t nS,
+                          const int32_t *cand_id, const uint64_t *cdf, int64_t n_cand,
+                          const uint64_t *words, int32_t B,
+                          int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
+                          int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
+                          int64_t *adj_nnz)
+{
+    if (B <= 0 || nS <= 0) return ORC_EINVAL;
+    double *pd = (double *)malloc((size_t)B * sizeof(double));
+    if (!pd) return ORC_ECAP;
+    int rc = orc_draw_from_words(cand_id, cdf, n_cand, words, B, S_next, mult, p_incl, pd, n_next);
+    if (rc == ORC_OK)
+        rc = orc_sampled_adjacency(n_nodes, rowptr, colidx, val, S, nS, S_next, *n_next, pd, adj_rowptr, adj_col,
+                                   adj_val, adj_cap, adj_nnz);
+    free(pd);
+    return rc;
+}
+
+/* The draws of csgs: word t from the counter-based generator. */
+int orc_draw_nodes(const int32_t *cand_id, const uint64_t *cdf, int64_t n_cand, int32_t B,
+                   uint64_t seed, uint64_t iter, uint32_t layer,
+                   int32_t *S_next, int32_t *mult, float *p_incl, double *pd, int32_t *n_next)
+{
+    if (B <= 0) return ORC_EINVAL;
+    uint64_t *words = (uint64_t *)malloc((size_t)B * sizeof(uint64_t));
+    if (!words) return ORC_ECAP;
+    for (int32_t t = 0; t < B; ++t) words[t] = orc_draw_word(seed, iter, layer, (uint32_t)t);
+    int rc = orc_draw_from_words(cand_id, cdf, n_cand, words, B, S_next, mult, p_incl, pd, n_next);
+    free(words);
     return rc;
 }
 

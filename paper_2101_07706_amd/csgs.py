@@ -21,7 +21,7 @@ ST_EDGE_OVERFLOW, ST_INTERNAL = 32, 64
 F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
-           "csgs_sample_layer", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
+           "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
            "csgs_calib_copy"]
 
@@ -42,7 +42,8 @@ class Graph(C.Structure):
 class Workspace(C.Structure):
     """csgs_workspace: host descriptor of the caller-owned scratch buffer."""
     _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("n_nodes", C.c_int64),
-                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("epoch", C.c_uint64)]
+                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("epoch", C.c_uint64),
+                ("draw_epoch", C.c_uint64), ("draw_B", C.c_int32), ("pad_", C.c_int32)]
 
 
 class ProbStats(C.Structure):
@@ -74,6 +75,8 @@ def lib():
                                             C.POINTER(Workspace), vp, vp]
         L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
                                         vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_draw_nodes.argtypes = [i64, vp, vp, i64, vp, i32, u64, u64, u32, vp, vp, vp, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_sampled_adjacency.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
         L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
                                      C.c_int, vp, i64, vp]
@@ -127,7 +130,7 @@ def csgs_workspace_clean_bytes(n_nodes) -> int:
 
 def make_workspace(buf, n_nodes, nS_max, B_max, edges_max) -> Workspace:
     """Descriptor for `buf` (a torch tensor of at least csgs_workspace_bytes(...) bytes)."""
-    ws = Workspace(buf.data_ptr(), buf.numel() * buf.element_size(), n_nodes, nS_max, B_max, edges_max, 0)
+    ws = Workspace(buf.data_ptr(), buf.numel() * buf.element_size(), n_nodes, nS_max, B_max, edges_max, 0, 0, 0, 0)
     ws._keep = buf
     return ws
 
@@ -160,6 +163,19 @@ def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mul
                                  _ptr(stats), B, seed, it, layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
                                  _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream)), "csgs_sample_layer")
+
+
+def csgs_draw_nodes(n_nodes, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next, ws, status,
+                    stream=None):
+    _chk(lib().csgs_draw_nodes(n_nodes, _ptr(cand_id), _ptr(cdf), cand_id.numel(), _ptr(stats), B, seed, it, layer,
+                               _ptr(S_next), _ptr(mult), _ptr(p_incl), _ptr(n_next), C.byref(ws), _ptr(status),
+                               _stream(stream)), "csgs_draw_nodes")
+
+
+def csgs_sampled_adjacency(g, rows, adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None):
+    _chk(lib().csgs_sampled_adjacency(C.byref(g), _ptr(rows), rows.numel(), _ptr(adj_rowptr), _ptr(adj_col),
+                                      _ptr(adj_val), adj_col.numel(), _ptr(adj_nnz), C.byref(ws), _ptr(status),
+                                      _stream(stream)), "csgs_sampled_adjacency")
 
 
 def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_total, per_part=None,

@@ -115,6 +115,11 @@ __host__ inline int resident_grid()
     return cached[dev];
 }
 
+// Degrees of the rows S, their exclusive prefix (w.eoff) and CSR starts (w.rowstart); stats may be
+// null.  Defined with the weight scan.
+int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const Workspace &w,
+                      csgs_prob_stats *stats, int32_t *status, hipStream_t st);
+
 // ---------------------------------------------------------------- wave helpers
 __device__ inline int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
 

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ r
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);
     if (threadIdx.x == 0) {
-        stats->edges_scanned = base;
+        if (stats) stats->edges_scanned = base;
         // an edge count the workspace cannot hold is reported and treated as empty
         if (base > edge_cap) {
             atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
@@ -323,6 +323,15 @@ static int ceil_log2_u64(uint64_t n)
 
 }  // namespace csgs
 
+int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const Workspace &w,
+                            csgs_prob_stats *stats, int32_t *status, hipStream_t st)
+{
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, rowptr, n_nodes, S, nS, w.eoff, w.rowstart,
+                w.chunk_cap * EDGE_TILE, stats, status);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
 using namespace csgs;
 
 extern "C" size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max)
@@ -341,6 +350,8 @@ extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
 {
     if (!ws) return CSGS_EINVAL;
     ws->epoch = 0;
+    ws->draw_epoch = 0;
+    ws->draw_B = 0;
     Workspace w;
     const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
     if (rc != CSGS_OK) return rc;
@@ -387,9 +398,8 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, f
     const int64_t n_words = (g->n_nodes + 63) / 64;
     const unsigned n_groups = (unsigned)((w.n_tiles + 63) / 64);
 
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, g->rowptr, g->n_nodes, S, nS, w.eoff, w.rowstart,
-                w.chunk_cap * EDGE_TILE, stats, status);
-    CSGS_LAUNCH_CHECK();
+    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, w, stats, status, st);
+    if (rc != CSGS_OK) return rc;
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, nS, w.eoff,
                 w.rowstart, ldexp(1.0, shift), w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();

@@ -322,25 +322,21 @@ __global__ __launch_bounds__(1024) void remote_count_k(const int32_t *__restrict
 }
 
 }  // namespace csgs
-
 using namespace csgs;
 
-extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
-                                 const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
-                                 uint64_t iter, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
-                                 int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
-                                 int64_t adj_cap, int64_t *adj_nnz, csgs_workspace *ws, int32_t *status,
-                                 void *stream)
+extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
+                               const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter, uint32_t layer,
+                               int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next, csgs_workspace *ws,
+                               int32_t *status, void *stream)
 {
-    if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !S || nS <= 0 ||
-        !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next || !mult || !p_incl || !n_next || !adj_rowptr || !adj_col ||
-        !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
+    if (n_nodes <= 0 || n_nodes > 0x7FFFFFFFll || !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next ||
+        !mult || !p_incl || !n_next || !ws || !status)
         return CSGS_EINVAL;
     Workspace w;
-    const int rc = open_workspace(ws, g->n_nodes, nS, B, &w);
+    const int rc = open_workspace(ws, n_nodes, 1, B, &w);
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (cand_cap > g->n_nodes) cand_cap = g->n_nodes;  // there are never more candidates than nodes
+    if (cand_cap > n_nodes) cand_cap = n_nodes;  // there are never more candidates than nodes
 
     CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), st, cdf, stats,
                 cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32), layer, w.hit,
@@ -350,7 +346,7 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
     // current, so the table is wiped once every 2^32 calls
     const unsigned long long hits_tag = ++ws->epoch;
     if ((hits_tag & 0xFFFFFFFFull) == 0) {
-        const size_t n = (size_t)g->n_nodes;
+        const size_t n = (size_t)n_nodes;
         const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
         CSGS_LAUNCH(K_FILL_ZERO, fill_zero_u64, dim3(blocks), dim3(256), st, w.rank, n);
         CSGS_LAUNCH_CHECK();
@@ -358,15 +354,59 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
     const int64_t cap_words = (cand_cap + 63) / 64;
     const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
     const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid() ? hit_tiles : resident_grid());
-    CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, g->n_nodes, B,
+    CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
                 hits_tag, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
     CSGS_LAUNCH_CHECK();
+    ws->draw_epoch = hits_tag;
+    ws->draw_B = B;
+    return CSGS_OK;
+}
+
+// rows == nullptr: reuse the row offsets that csgs_build_probs left in the workspace for the same rows
+static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int32_t n_rows, bool reuse_offsets,
+                                  int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
+                                  int64_t *adj_nnz, csgs_workspace *ws, int32_t *status, void *stream)
+{
+    if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !rows || n_rows <= 0 ||
+        !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
+        return CSGS_EINVAL;
+    if (ws->draw_epoch == 0) return CSGS_EINVAL;  // no csgs_draw_nodes has run on this workspace
+    Workspace w;
+    const int rc = open_workspace(ws, g->n_nodes, n_rows, ws->draw_B, &w);
+    if (rc != CSGS_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (!reuse_offsets) {
+        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, w, nullptr, status, st);
+        if (rc2 != CSGS_OK) return rc2;
+    }
     const unsigned long long adj_tag = ++ws->epoch;
-    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes, nS,
-                w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, hits_tag, w.adj_ts, w.chunk_cap, adj_rowptr, adj_col, adj_val,
-                adj_cap, adj_nnz, status);
+    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes,
+                n_rows, w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, (unsigned long long)ws->draw_epoch, w.adj_ts, w.chunk_cap,
+                adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
+}
+
+extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, int32_t n_rows, int32_t *adj_rowptr,
+                                      int32_t *adj_col, float *adj_val, int64_t adj_cap, int64_t *adj_nnz,
+                                      csgs_workspace *ws, int32_t *status, void *stream)
+{
+    return sampled_adjacency_impl(g, rows, n_rows, false, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status,
+                                  stream);
+}
+
+extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
+                                 const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
+                                 uint64_t iter, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
+                                 int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
+                                 int64_t adj_cap, int64_t *adj_nnz, csgs_workspace *ws, int32_t *status,
+                                 void *stream)
+{
+    if (!g || !S || nS <= 0 || !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz) return CSGS_EINVAL;
+    const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, layer, S_next, mult, p_incl,
+                                   n_next, ws, status, stream);
+    if (rc != CSGS_OK) return rc;
+    return sampled_adjacency_impl(g, S, nS, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, stream);
 }
 
 extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo, int32_t local_hi,

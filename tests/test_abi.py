@@ -33,7 +33,7 @@ def test_every_declared_function_is_exported():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
     assert C.sizeof(csgs.Graph) == 56
-    assert C.sizeof(csgs.Workspace) == 48
+    assert C.sizeof(csgs.Workspace) == 64
     assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48
     assert csgs.Workspace.epoch.offset == 40
 
@@ -74,7 +74,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.csgs_aggregate(z, z, z, 1, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
     assert L.csgs_layer_gemm(z, 1, 1, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_workspace_init(None, z) == csgs.EINVAL
-    ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0)
+    ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0, 0, 0, 0)
     assert L.csgs_workspace_init(C.byref(ws), z) == csgs.EINVAL           # null base
 
 
