@@ -213,7 +213,8 @@ int csgs_sampled_adjacency(const csgs_graph *g /*host*/, const int32_t *rows, in
  * Communication volume of the step (Eq. 4; Section 5.2 reports the number of nodes whose
  * feature vectors are transferred): sampled ids outside [local_lo, local_hi).
  *
- *   S_next [*n_next] ascending (device), n_next device
+ *   S_next [*n_next] ascending (device; the order csgs_sample_layer produces -- the kernel
+ *   relies on it), n_next device
  *   part_bounds [P+1] nullable: partition p owns [b[p], b[p+1]); per_part [P] nullable out
  *   remote_total out (device int64)
  *   src_row [*n_next] nullable out: where the aggregation finds the feature row of S_next[k]:

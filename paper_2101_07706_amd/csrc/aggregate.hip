@@ -50,7 +50,7 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
                    __uint_as_float(v.y & 0xFFFF0000u)}};
 }
 
-constexpr int LONG_ROW = 128;   // rows with more kept edges than this go to the block-cooperative kernel
+constexpr int LONG_ROW = 32;    // rows with more kept edges than this go to the block-cooperative kernel
 constexpr int UNR = 8;          // gathered rows in flight per lane
 
 // Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.

@@ -50,8 +50,8 @@ __device__ inline uint64_t philox_word(uint32_t c0, uint32_t c1, uint32_t c2, ui
     return (uint64_t)c0 | ((uint64_t)c1 << 32);
 }
 
-constexpr int DRAW_BLOCK = 1024;
-constexpr int TOP = 4096;  // CDF samples staged in LDS per block (32 KB)
+constexpr int DRAW_BLOCK = 256;
+constexpr int TOP = 2048;  // CDF samples staged in LDS per block (16 KB)
 
 __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ cdf,
                                                    const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
@@ -81,10 +81,31 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
         if (top[m] > u) b = m; else a = m + 1;
     }
     int64_t lo = a * stride;
-    int64_t hi = (a < n_top) ? (a + 1) * stride - 1 : n - 1;  // cdf[hi] > u is known
-    while (lo < hi) {
-        const int64_t m = (lo + hi) >> 1;
-        if (cdf[m] > u) hi = m; else lo = m + 1;
+    int64_t hi = (a < n_top) ? (a + 1) * stride - 1 : n - 1;  // cdf[hi] > u is known; the answer is in [lo, hi]
+    // 8-ary search on the global array: 7 independent probes per round instead of one
+    while (hi - lo >= 8) {
+        const int64_t len = hi - lo;  // candidates lo .. hi, hi already known to be above u
+        uint64_t pv[7];
+#pragma unroll
+        for (int i = 0; i < 7; ++i) pv[i] = cdf[lo + (len * (i + 1)) / 8];
+        int below = 0;                // pivots that are <= u (they ascend, so these are the first ones)
+#pragma unroll
+        for (int i = 0; i < 7; ++i) below += pv[i] <= u ? 1 : 0;
+        const int64_t new_lo = below ? lo + (len * below) / 8 + 1 : lo;
+        const int64_t new_hi = below < 7 ? lo + (len * (below + 1)) / 8 : hi;
+        lo = new_lo;
+        hi = new_hi;
+    }
+    {
+        // at most 8 entries left: fetch them together, take the first above u
+        uint64_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (lo + i < hi) ? cdf[lo + i] : ~0ull;
+        int skip = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) skip += v[i] <= u ? 1 : 0;
+        lo += skip;  // entries ascend; cdf[hi] > u bounds the result by hi
+        if (lo > hi) lo = hi;
     }
     const uint32_t old = atomicAdd(&hit[lo], 1u);
     if (old == 0) atomicOr((unsigned long long *)&cbitmap[lo >> 6], 1ull << (lo & 63));
@@ -270,53 +291,72 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     }
 }
 
-__global__ __launch_bounds__(1024) void remote_count_k(const int32_t *__restrict__ S_next,
-                                                       const int32_t *__restrict__ n_next, int32_t lo, int32_t hi,
-                                                       const int32_t *__restrict__ part_bounds, int32_t P,
-                                                       int64_t *__restrict__ remote_total,
-                                                       int64_t *__restrict__ per_part, int32_t *__restrict__ src_row,
-                                                       int32_t *__restrict__ remote_ids)
+// First index in [0, n) with a[idx] >= key, found by the whole wavefront: every round the 64 lanes
+// probe the ends of 64 equal segments at once, so an array of 8192 entries takes 3 dependent loads
+// instead of 13.  All lanes must call it with the same arguments; all get the result.
+__device__ inline int32_t wave_lower_bound(const int32_t *__restrict__ a, int32_t n, int32_t key)
 {
-    __shared__ uint32_t lds[17];
-    const int32_t n = *n_next;
-    // every thread owns a contiguous run of the (ascending) sampled ids: one block scan in total
-    const int32_t per = (n + (int32_t)blockDim.x - 1) / (int32_t)blockDim.x;
-    const int32_t k0 = (int32_t)threadIdx.x * per;
-    const int32_t k1 = (k0 + per < n) ? k0 + per : n;
-    uint32_t rem = 0;
-    for (int32_t k = k0; k < k1; ++k) {
-        const int32_t j = S_next[k];
-        rem += (j < lo || j >= hi) ? 1u : 0u;
+    const int lane = lane_id();
+    int32_t lo = 0, hi = n;
+    while (hi > lo) {
+        const int32_t len = hi - lo;
+        const int32_t step = (len + WAVE - 1) / WAVE;
+        const int32_t seg_end = lo + ((lane + 1) * step < len ? (lane + 1) * step : len);  // exclusive
+        const int32_t seg_beg = lo + (lane * step < len ? lane * step : len);
+        bool ge = true;  // empty segments sit past the end: treat as "all remaining entries are >= key"
+        if (seg_end > seg_beg) ge = a[seg_end - 1] >= key;
+        const uint64_t m = __ballot(ge);
+        const int first = m ? __ffsll((unsigned long long)m) - 1 : WAVE;
+        const int32_t fb = lo + (first * step < len ? first * step : len);
+        const int32_t fe = lo + ((first + 1) * step < len ? (first + 1) * step : len);
+        if (fe <= fb) {          // no segment ends at or above key: every entry is below it
+            lo = hi;
+        } else if (step == 1) {  // segments are single entries: entry fb is the first >= key
+            return fb;
+        } else {                 // a[fe - 1] >= key and everything before fb is below key
+            lo = fb;
+            hi = fe;
+        }
     }
-    uint32_t tot;
-    uint32_t ex = block_exclusive_scan<uint32_t>(rem, lds, &tot);
+    return lo;
+}
+
+// S_next ascends and the local partition is one id range, so the sampled remote nodes are the
+// entries before the first id >= lo and from the first id >= hi on: two searches give every
+// element its place, no scan needed.
+__global__ __launch_bounds__(256) void remote_count_k(const int32_t *__restrict__ S_next,
+                                                      const int32_t *__restrict__ n_next, int32_t lo, int32_t hi,
+                                                      const int32_t *__restrict__ part_bounds, int32_t P,
+                                                      int64_t *__restrict__ remote_total,
+                                                      int64_t *__restrict__ per_part, int32_t *__restrict__ src_row,
+                                                      int32_t *__restrict__ remote_ids)
+{
+    const int32_t n = *n_next;
+    const int32_t a = wave_lower_bound(S_next, n, lo);   // ids below the local range
+    const int32_t b = wave_lower_bound(S_next, n, hi);   // first id above it
+    const int32_t n_local = b - a;
+    const int32_t tid = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    const int32_t stride = (int32_t)(gridDim.x * blockDim.x);
+    if (tid == 0) *remote_total = (int64_t)(n - n_local);
     if (src_row || remote_ids) {
-        for (int32_t k = k0; k < k1; ++k) {
+        for (int32_t k = tid; k < n; k += stride) {
             const int32_t j = S_next[k];
-            if (j < lo || j >= hi) {
-                if (src_row) src_row[k] = -1 - (int32_t)ex;
-                if (remote_ids) remote_ids[ex] = j;
-                ++ex;
-            } else if (src_row) {
-                src_row[k] = j - lo;
+            if (k >= a && k < b) {
+                if (src_row) src_row[k] = j - lo;
+            } else {
+                const int32_t r = k < a ? k : k - n_local;
+                if (src_row) src_row[k] = -1 - r;
+                if (remote_ids) remote_ids[r] = j;
             }
         }
     }
-    if (threadIdx.x == 0) *remote_total = (int64_t)tot;
-    // S_next ascends, so partition p holds the ids between two lower bounds
+    // partition p holds the ids between two lower bounds; one wavefront per partition
     if (per_part) {
-        for (int p = threadIdx.x; p < P; p += blockDim.x) {
-            int32_t cut[2];
-            for (int s = 0; s < 2; ++s) {
-                const int32_t key = part_bounds[p + s];
-                int32_t a = 0, b = n;
-                while (a < b) {
-                    const int32_t m = (a + b) >> 1;
-                    if (S_next[m] >= key) b = m; else a = m + 1;
-                }
-                cut[s] = a;
-            }
-            per_part[p] = (int64_t)(cut[1] > cut[0] ? cut[1] - cut[0] : 0);
+        const int32_t wave = tid >> 6, n_waves = stride >> 6;
+        for (int32_t p = wave; p < P; p += n_waves) {
+            const int32_t c0 = wave_lower_bound(S_next, n, part_bounds[p]);
+            const int32_t c1 = wave_lower_bound(S_next, n, part_bounds[p + 1]);
+            if (lane_id() == 0) per_part[p] = (int64_t)(c1 > c0 ? c1 - c0 : 0);
         }
     }
 }
@@ -415,7 +455,9 @@ extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, i
 {
     if (!S_next || !n_next || local_lo > local_hi || !remote_total) return CSGS_EINVAL;
     if (per_part && (!part_bounds || P <= 0)) return CSGS_EINVAL;
-    CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(1), dim3(1024), (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
+    // the element count is known only on the device; 64 blocks of 256 cover the usual budgets in one
+    // sweep and stride over larger ones
+    CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(64), dim3(256), (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
                        part_bounds, per_part ? P : 0, remote_total, per_part, src_row, remote_ids);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
