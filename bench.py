@@ -47,6 +47,7 @@ def algorithmic_bytes(s, N):
         "remote_count": 12 * n2,
         "aggregate": agg, "aggregate_long": 0.0,            # long rows are part of the same algorithmic volume
         "layer_gemm": 4 * (nS * Fi + Fi * Fo + nS * Fo),
+        "gather_rows": 0.0,                                 # filled in by the caller (remote rows, bottom layer only)
     }
 
 
@@ -72,36 +73,35 @@ class Workload:
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
         self.elt = 2 if self.bf16 else 4
+        self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
 
     def step(self, it, sizes=None):
-        """One whole mini-batch.  The host learns each layer's sampled-set size (it sizes the next launch)."""
+        """One whole mini-batch, enqueued without the host waiting for anything: each layer's row
+        count stays on the device (the n_dev arguments), launches are sized for the capacities."""
         cfg, M, B, lbs, pipeline = self.cfg, self.M, self.B, self.lbs, self.pipeline
-        S = self.Sd[it]
-        rows = []
+        S0 = self.Sd[it]
+        n0 = S0.numel()
         for l in range(M):
-            lb = lbs[l]
-            pipeline.sample_step(self.dg, self.ws, S, cfg.skew, B, self.seed, it, l, lb, want_q=False)
-            n = int(lb.n_next.item())
-            rows.append(S)
-            S = lb.S_next[:n]
-        r = int(lbs[M - 1].remote_total.item())
-        X_remote = self.Xd[lbs[M - 1].remote_ids[:r].long()]      # stands in for the exchange of remote rows
+            S = S0 if l == 0 else lbs[l - 1].S_next
+            pipeline.sample_step(self.dg, self.ws, S, cfg.skew, B, self.seed, it, l, lbs[l], want_q=False,
+                                 nS_dev=None if l == 0 else lbs[l - 1].n_next)
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.staged)      # stands in for the exchange of remote rows
         H = None
         for l in range(M - 1, -1, -1):
-            lb = lbs[l]
-            nS = rows[l].numel()
+            nS = n0 if l == 0 else B
+            nS_dev = None if l == 0 else lbs[l - 1].n_next
             Z, Hn = self.Zs[l][:nS], self.Hs[l][:nS]
             if l == M - 1:
-                pipeline.compute_step(lb, nS, self.X_local, X_remote, True, False, self.Wd[M - 1 - l], Z, Hn)
+                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev)
             else:
-                pipeline.compute_step(lb, nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn)
+                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev)
             H = Hn
         if sizes is not None:
             self.torch.cuda.synchronize()
             for l in range(M):
                 st = lbs[l].stats_host()
-                sizes.append(dict(layer=l, nS=rows[l].numel(), E=st.edges_scanned, nc=st.n_cand, B=B,
-                                  n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
+                sizes.append(dict(layer=l, nS=n0 if l == 0 else int(lbs[l - 1].n_next.item()), E=st.edges_scanned,
+                                  nc=st.n_cand, B=B, n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
                                   remote=int(lbs[l].remote_total.item()), F_in=self.dims[M - 1 - l][0],
                                   F_out=self.dims[M - 1 - l][1], elt=self.elt if l == M - 1 else 4,
                                   status=int(lbs[l].status.item())))
@@ -131,6 +131,8 @@ class Workload:
         for s in sizes:
             for k, b in algorithmic_bytes(s, self.g.n_nodes).items():
                 alg[k] = alg.get(k, 0.0) + b
+            if s["layer"] == self.M - 1:    # staged remote rows: read once, written once
+                alg["gather_rows"] = alg.get("gather_rows", 0.0) + 2.0 * s["remote"] * s["F_in"] * s["elt"]
             flops += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
         kernels = {}
         for k, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):

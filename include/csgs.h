@@ -22,6 +22,13 @@
  *     out of range, an empty candidate set) OR the matching CSGS_ST_* bit into the int32 word
  *     `status` (device).  The caller zeroes it and reads it when it next synchronises.  When a
  *     bit is set the outputs of that call are unspecified but every access stayed in bounds.
+ *   - Row counts that exist only on the device.  In a multi-layer step the rows of one call are
+ *     the node set the previous call sampled, whose size the host does not know without waiting.
+ *     Every entry point that takes a row count n (nS, n_rows, M) therefore also takes n_dev, a
+ *     nullable DEVICE pointer to an int32.  NULL: n is the count.  Otherwise the kernels use
+ *     min(max(*n_dev, 0), n), read when they run, and n is only the capacity: host-side checks,
+ *     launch sizes and array extents ("[nS + 1]") refer to it, entries past the device count are
+ *     left untouched.  A whole step can so be enqueued without the host ever waiting.
  *   - `ws` describes scratch memory (see csgs_workspace), prepared once with
  *     csgs_workspace_init().  Every call leaves it ready for the next.  Calls that share one
  *     workspace must be ordered on one stream.
@@ -39,7 +46,7 @@ extern "C" {
 enum {
     CSGS_OK = 0,
     CSGS_EINVAL = -1,       /* null pointer, non-positive size, skew < 1, lo > hi, bad alignment */
-    CSGS_EWORKSPACE = -2,   /* ws_bytes too small */
+    CSGS_EWORKSPACE = -2,   /* the workspace is smaller than this call's sizes need */
     CSGS_EUNSUPPORTED = -3, /* dtype or dimension outside what the kernels cover */
     CSGS_ERANGE = -4,       /* fixed-point format would keep fewer than 24 fraction bits */
     CSGS_ELAUNCH = -5       /* the HIP runtime refused a launch */
@@ -139,10 +146,10 @@ int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift,
  *   cdf      [cap] out: inclusive running sum of the skewed weights (cdf[n_cand-1] = total)
  *   q        [cap] out, nullable: Eq. 10 as float = skewed weight / total
  *   stats    out, see above
- * Host errors: CSGS_EINVAL, CSGS_ERANGE (shift < 24), CSGS_EWORKSPACE.
+ * Host errors: CSGS_EINVAL, CSGS_ERANGE (shift < 24 for nS rows), CSGS_EWORKSPACE.
  * Status bits: CAND_OVERFLOW, BAD_EDGE_VALUE, EMPTY_CANDIDATES, BAD_NODE_ID, EDGE_OVERFLOW.
  */
-int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float skew,
+int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, const int32_t *nS_dev, float skew,
                      int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
                      csgs_prob_stats *stats, csgs_workspace *ws /*host*/, int32_t *status,
                      void *stream);
@@ -155,7 +162,8 @@ int csgs_build_probs(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
  * was used is reported in stats->skew_fx.  D >= 0 is the constant of the theorem (the paper
  * sweeps 4, 8, 16, 32), B the sampling budget.
  */
-int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, float D, int32_t B,
+int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS, const int32_t *nS_dev,
+                          float D, int32_t B,
                           float skew_max, int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q,
                           int64_t cap, csgs_prob_stats *stats, csgs_workspace *ws /*host*/,
                           int32_t *status, void *stream);
@@ -170,7 +178,9 @@ int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_
  *
  *   cand_id, cdf, stats   as written by csgs_build_probs for the same S (device);
  *            cand_cap = the capacity those arrays were given there.  The call must follow that
- *            csgs_build_probs call on the same workspace: it reuses the row offsets left there.
+ *            csgs_build_probs call on the same workspace: it reuses the row offsets left there,
+ *            and with them the row count that call used (so there is no nS_dev here; nS is the
+ *            same capacity).
  *   S_next   [B] out: distinct sampled ids ascending; *n_next of them
  *   mult     [B] out: how many of the B draws hit each
  *   p_incl   [B] out: p_j as float
@@ -205,6 +215,7 @@ int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const uint64_t *cdf
                     uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
                     csgs_workspace *ws /*host*/, int32_t *status, void *stream);
 int csgs_sampled_adjacency(const csgs_graph *g /*host*/, const int32_t *rows, int32_t n_rows,
+                           const int32_t *n_rows_dev,
                            int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
                            int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
                            void *stream);
@@ -243,15 +254,29 @@ int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t loca
  * outside the tables contributes nothing (no status word here; every load stays in bounds).
  */
 int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val,
-                   int32_t nS, const int32_t *n_next, const void *X_local, int64_t ld_local,
+                   int32_t nS, const int32_t *nS_dev, const int32_t *n_next, const void *X_local, int64_t ld_local,
                    int64_t rows_local, const void *X_remote, int64_t ld_remote, int64_t rows_remote,
                    const int32_t *src_row, int32_t F, int dtype, int relu_on_input, float *Z,
                    int64_t ldz, void *stream);
 
+/*
+ * out[k, 0..F) = X[ids[k], 0..F) for k < n: fills the staged buffer of sampled remote feature rows
+ * that csgs_aggregate reads (X_remote) from the request list csgs_remote_count wrote (remote_ids).
+ * On one GPU that holds the whole feature table this takes the place of the exchange of feature
+ * vectors between partitions (Section 3, "Communication of Feature Vectors").
+ *
+ *   X [rows x F], leading dimension ld (elements of dtype CSGS_F32 or CSGS_BF16; rows are copied
+ *   bit for bit); ids [cap] device; n = min(*n_dev, cap) when n_dev (device int64, e.g.
+ *   remote_total) is given, else cap; out [cap x F], leading dimension ldo.  An id outside
+ *   [0, rows) yields a zero row.  Rows k >= n are left untouched.
+ */
+int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t F, int dtype, const int32_t *ids,
+                     int64_t cap, const int64_t *n_dev, void *out, int64_t ldo, void *stream);
+
 /* H [M x Nout] = Z [M x K] W [K x Nout], all row-major fp32 (Eq. 1).  Operands are widened to
  * double, products accumulate in double on the matrix cores, one rounding to float.
  * Host errors: CSGS_EINVAL; CSGS_EUNSUPPORTED when the tile count exceeds 2^30. */
-int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const float *W,
+int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev, int32_t K, const float *W,
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
 
 /*

@@ -21,7 +21,8 @@ ST_EDGE_OVERFLOW, ST_INTERNAL = 32, 64
 F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
-           "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_layer_gemm", "csgs_strerror",
+           "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
+           "csgs_layer_gemm", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
            "csgs_calib_copy"]
 
@@ -70,17 +71,18 @@ def lib():
         L.csgs_workspace_clean_bytes.argtypes = [i64]
         L.csgs_workspace_init.argtypes = [C.POINTER(Workspace), vp]
         L.csgs_fixed_point.argtypes = [i32, f32, f32, C.POINTER(i32), C.POINTER(i64)]
-        L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
-        L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, f32, i32, f32, vp, vp, vp, vp, i64, vp,
+        L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, i32, f32, vp, vp, vp, vp, i64, vp,
                                             C.POINTER(Workspace), vp, vp]
         L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
                                         vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_draw_nodes.argtypes = [i64, vp, vp, i64, vp, i32, u64, u64, u32, vp, vp, vp, vp, C.POINTER(Workspace), vp, vp]
-        L.csgs_sampled_adjacency.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_sampled_adjacency.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
-        L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
+        L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
                                      C.c_int, vp, i64, vp]
-        L.csgs_layer_gemm.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, i64, vp]
+        L.csgs_layer_gemm.argtypes = [vp, i64, i32, vp, i32, vp, i64, i32, vp, i64, vp]
+        L.csgs_gather_rows.argtypes = [vp, i64, i64, i32, C.c_int, vp, i64, vp, vp, i64, vp]
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
         L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
@@ -145,14 +147,16 @@ def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
     return rc, sh.value, sfx.value
 
 
-def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None):
-    _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
+def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None, nS_dev=None):
+    """nS_dev: device int32 holding the number of rows of S to use (S.numel() is then the capacity)."""
+    _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
                                 _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream)),
          "csgs_build_probs")
 
 
-def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, ws, status, stream=None):
-    _chk(lib().csgs_build_probs_auto(C.byref(g), _ptr(S), S.numel(), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
+def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, ws, status, stream=None,
+                          nS_dev=None):
+    _chk(lib().csgs_build_probs_auto(C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
                                      _ptr(cdf), _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status),
                                      _stream(stream)), "csgs_build_probs_auto")
 
@@ -172,8 +176,9 @@ def csgs_draw_nodes(n_nodes, cand_id, cdf, stats, B, seed, it, layer, S_next, mu
                                _stream(stream)), "csgs_draw_nodes")
 
 
-def csgs_sampled_adjacency(g, rows, adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None):
-    _chk(lib().csgs_sampled_adjacency(C.byref(g), _ptr(rows), rows.numel(), _ptr(adj_rowptr), _ptr(adj_col),
+def csgs_sampled_adjacency(g, rows, adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None,
+                           n_rows_dev=None):
+    _chk(lib().csgs_sampled_adjacency(C.byref(g), _ptr(rows), rows.numel(), _ptr(n_rows_dev), _ptr(adj_rowptr), _ptr(adj_col),
                                       _ptr(adj_val), adj_col.numel(), _ptr(adj_nnz), C.byref(ws), _ptr(status),
                                       _stream(stream)), "csgs_sampled_adjacency")
 
@@ -187,7 +192,7 @@ def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_to
 
 
 def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_row, relu_on_input, Z,
-                   stream=None):
+                   stream=None, nS_dev=None):
     """X_* are 2-D float32 tensors or int16/uint16/bfloat16 tensors holding bfloat16 rows."""
     dtype = F32 if X_local.dtype == torch.float32 else BF16
     F = X_local.shape[1]
@@ -197,17 +202,25 @@ def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_
         X_remote = None
     Xl_ptr = _ptr(X_local) if X_local.shape[0] > 0 else None
     _chk(lib().csgs_aggregate(_ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
-                              _ptr(n_next), Xl_ptr, X_local.stride(0), X_local.shape[0], _ptr(X_remote),
+                              _ptr(nS_dev), _ptr(n_next), Xl_ptr, X_local.stride(0), X_local.shape[0], _ptr(X_remote),
                               ld_r, rows_r, _ptr(src_row), F, dtype, 1 if relu_on_input else 0, _ptr(Z),
                               Z.stride(0), _stream(stream)), "csgs_aggregate")
 
 
-def csgs_layer_gemm(Z, W, H, stream=None):
+def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None):
     M, K = Z.shape
     K2, N = W.shape
     assert K == K2 and H.shape == (M, N)
-    _chk(lib().csgs_layer_gemm(_ptr(Z), Z.stride(0), M, K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
+    _chk(lib().csgs_layer_gemm(_ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
                                _stream(stream)), "csgs_layer_gemm")
+
+
+def csgs_gather_rows(X, ids, n_dev, out, stream=None):
+    """out[k] = X[ids[k]] for k < *n_dev (device int64; None = all of ids)."""
+    assert X.dtype == out.dtype and X.shape[1] == out.shape[1] and out.shape[0] >= ids.numel()
+    dtype = F32 if X.dtype == torch.float32 else BF16
+    _chk(lib().csgs_gather_rows(_ptr(X), X.stride(0), X.shape[0], X.shape[1], dtype, _ptr(ids), ids.numel(),
+                                _ptr(n_dev), _ptr(out), out.stride(0), _stream(stream)), "csgs_gather_rows")
 
 
 def csgs_profile_enable(on: bool):

@@ -126,13 +126,15 @@ __device__ inline void store_row(float *z, const double (&acc)[V])
 template <typename T, int V, int G, bool RELU>
 __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                    const int32_t *__restrict__ adj_col,
-                                                   const float *__restrict__ adj_val, int32_t nS,
+                                                   const float *__restrict__ adj_val, int32_t nS_bound,
+                                                   const int32_t *__restrict__ nS_dev,
                                                    const int32_t *__restrict__ n_cols_p, const T *__restrict__ Xl,
                                                    int64_t ldl, int64_t rows_l, const T *__restrict__ Xr, int64_t ldr,
                                                    int64_t rows_r, const int32_t *__restrict__ src_row, int32_t F,
                                                    float *__restrict__ Z, int64_t ldz)
 {
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+    const int32_t nS = resolve_count(nS_bound, nS_dev);
     const int tid = (int)threadIdx.x;
     const int g = tid & (G - 1);  // lane within the row group
     const int gbase = tid & (WAVE - 1) & ~(G - 1);
@@ -179,7 +181,8 @@ __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ a
 template <typename T, int V, bool RELU>
 __global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restrict__ adj_rowptr,
                                                          const int32_t *__restrict__ adj_col,
-                                                         const float *__restrict__ adj_val, int32_t nS,
+                                                         const float *__restrict__ adj_val, int32_t nS_bound,
+                                                         const int32_t *__restrict__ nS_dev,
                                                          const int32_t *__restrict__ n_cols_p,
                                                          const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
                                                          const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
@@ -190,10 +193,11 @@ __global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restri
     __shared__ int32_t long_rows[1024];
     __shared__ int32_t n_long;
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+    const int32_t nS = resolve_count(nS_bound, nS_dev);
     const int tid = (int)threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     // this block's share of the rows, searched in parallel for long ones
-    const int32_t per = (nS + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;
+    const int32_t per = (nS_bound + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;
     const int32_t r0 = (int32_t)blockIdx.x * per;
     if (tid == 0) n_long = 0;
     __syncthreads();
@@ -243,7 +247,7 @@ __global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restri
 }
 
 template <typename T, int V, int G>
-static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                       hipStream_t st)
 {
@@ -253,16 +257,16 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     unsigned lblocks = 512;
     if ((nS + 1023) / 1024 > (int)lblocks) lblocks = (unsigned)((nS + 1023) / 1024);
     if (relu) {
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp, (const T *)Xl,
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), st, rp, col, val, nS, nsd, ncp, (const T *)Xl,
                     ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
         CSGS_LAUNCH_CHECK();
-        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, true>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, ncp,
+        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, true>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, nsd, ncp,
                     (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
     } else {
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), st, rp, col, val, nS, ncp,
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), st, rp, col, val, nS, nsd, ncp,
                     (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
         CSGS_LAUNCH_CHECK();
-        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, false>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, ncp,
+        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, false>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, nsd, ncp,
                     (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
     }
     CSGS_LAUNCH_CHECK();
@@ -270,17 +274,17 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 }
 
 template <typename T, int V>
-static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                       hipStream_t st)
 {
-    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    return launch_agg<T, V, 64>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
 }
 
 template <typename T>
-static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *ncp, const void *Xl,
+static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                     int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                     hipStream_t st)
 {
@@ -291,17 +295,70 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
                (!Xr || (ldr % v == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % v == 0 &&
                ((uintptr_t)Z % ((uintptr_t)v * sizeof(float))) == 0;
     };
-    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    return pick_group<T, 1>(rp, col, val, nS, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+}
+
+// out[k, :] = X[ids[k], :] in units of U (the widest type every row start is aligned to); one
+// wavefront per row, rows strided over the grid.  An id outside the table gives a zero row.
+template <typename U>
+__global__ __launch_bounds__(256) void gather_rows_k(const U *__restrict__ X, int64_t ld_u, int64_t rows, int32_t row_u,
+                                                     const int32_t *__restrict__ ids, int64_t cap,
+                                                     const int64_t *__restrict__ n_dev, U *__restrict__ out,
+                                                     int64_t ldo_u)
+{
+    int64_t n = cap;
+    if (n_dev) {
+        const int64_t d = *n_dev;
+        n = d < 0 ? 0 : (d < cap ? d : cap);
+    }
+    const int lane = lane_id();
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t k = wave; k < n; k += n_waves) {
+        const int64_t id = ids[k];
+        const bool ok = id >= 0 && id < rows;
+        for (int32_t f = lane; f < row_u; f += WAVE) out[k * ldo_u + f] = ok ? X[id * ld_u + f] : U{};
+    }
+}
+
+template <typename U>
+static void launch_gather(const void *X, int64_t ld_b, int64_t rows, int64_t row_b, const int32_t *ids, int64_t cap,
+                          const int64_t *n_dev, void *out, int64_t ldo_b, hipStream_t st)
+{
+    const int64_t waves = cap < 8192 ? cap : 8192;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    CSGS_LAUNCH(K_GATHER_ROWS, gather_rows_k<U>, dim3(blocks), dim3(256), st, (const U *)X, ld_b / (int64_t)sizeof(U), rows,
+                (int32_t)(row_b / (int64_t)sizeof(U)), ids, cap, n_dev, (U *)out, ldo_b / (int64_t)sizeof(U));
 }
 
 }  // namespace csgs
 
 using namespace csgs;
 
+extern "C" int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t F, int dtype, const int32_t *ids,
+                                int64_t cap, const int64_t *n_dev, void *out, int64_t ldo, void *stream)
+{
+    if (!X || !ids || !out || rows <= 0 || F <= 0 || ld < F || ldo < F || cap <= 0) return CSGS_EINVAL;
+    if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
+    const int64_t elt = dtype == CSGS_F32 ? 4 : 2;
+    const int64_t row_b = (int64_t)F * elt, ld_b = ld * elt, ldo_b = ldo * elt;
+    hipStream_t st = (hipStream_t)stream;
+    auto aligned = [&](int64_t a) {
+        return row_b % a == 0 && ld_b % a == 0 && ldo_b % a == 0 && ((uintptr_t)X % (uintptr_t)a) == 0 &&
+               ((uintptr_t)out % (uintptr_t)a) == 0;
+    };
+    if (aligned(16)) launch_gather<uint4>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
+    else if (aligned(8)) launch_gather<uint2>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
+    else if (aligned(4)) launch_gather<uint32_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
+    else launch_gather<uint16_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
 extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int32_t nS,
-                              const int32_t *n_next, const void *X_local, int64_t ld_local, int64_t rows_local,
+                              const int32_t *nS_dev, const int32_t *n_next, const void *X_local, int64_t ld_local, int64_t rows_local,
                               const void *X_remote, int64_t ld_remote, int64_t rows_remote, const int32_t *src_row,
                               int32_t F, int dtype, int relu_on_input, float *Z, int64_t ldz, void *stream)
 {
@@ -313,8 +370,8 @@ extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col,
     if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     if (dtype == CSGS_F32)
-        return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, n_next, X_local, ld_local, rows_local, X_remote,
+        return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
                                ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
-    return pick_vec<uint16_t>(adj_rowptr, adj_col, adj_val, nS, n_next, X_local, ld_local, rows_local, X_remote,
+    return pick_vec<uint16_t>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
 }

@@ -23,6 +23,9 @@ constexpr int CAND_TILE = 1024;   // node ids per block in the candidate scan
 constexpr int EDGE_TILE = 1024;   // edges per chunk in the flat edge passes
 constexpr int EDGE_GRID = 2048;   // blocks of the weight scan (grid-stride over chunks, no waits between blocks)
 constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in the hit compaction
+constexpr int META_WORDS = 4;
+constexpr int META_ROWS = 0;          // rows the latest row_prefix covered (the count behind eoff / rowstart)
+constexpr int META_SHIFT = 1;         // fraction bits of the fixed-point weights for that count
 
 // Words of workspace a single-pass scan over at most `tiles` tiles with nv sums per tile needs
 // (one tag word and nv sums per tile, and twice that per group of 64 tiles).
@@ -48,6 +51,7 @@ struct Workspace {
     int64_t *rowstart;   // [nS]     rowptr[S[a]]
     uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
     double *pdbl;        // [B]      inclusion probabilities in double
+    int32_t *meta;       // [META_WORDS] what row_prefix resolved on the device: row count, weight shift
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
     int64_t n_tiles, hit_tiles;
     size_t clean_bytes;  // size of the clean part
@@ -84,6 +88,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
     w.rowstart = (int64_t *)take((size_t)nS_max * 8);
     w.pdbl = (double *)take((size_t)B_max * 8);
+    w.meta = (int32_t *)take(META_WORDS * 4);
     w.bytes = off;
     return w;
 }
@@ -116,9 +121,19 @@ __host__ inline int resident_grid()
 }
 
 // Degrees of the rows S, their exclusive prefix (w.eoff) and CSR starts (w.rowstart); stats may be
-// null.  Defined with the weight scan.
-int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const Workspace &w,
-                      csgs_prob_stats *stats, int32_t *status, hipStream_t st);
+// null.  The row count is min(*nS_dev, nS) when nS_dev is given; the kernel leaves it, and
+// min(52, shift_base - ceil(log2 count)), in w.meta for the kernels that follow.  Defined with the
+// weight scan.
+int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
+                      int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status, hipStream_t st);
+
+// A row count given on the host (n) or, when n_dev is not null, on the device with n as its bound.
+__device__ inline int32_t resolve_count(int32_t n, const int32_t *__restrict__ n_dev)
+{
+    if (!n_dev) return n;
+    const int32_t d = *n_dev;
+    return d < 0 ? 0 : (d < n ? d : n);
+}
 
 // ---------------------------------------------------------------- wave helpers
 __device__ inline int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }

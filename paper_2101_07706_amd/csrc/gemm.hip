@@ -102,7 +102,8 @@ __device__ inline void stash(float *As, float *Bs, int tid, const float4 (&ra)[4
 template <int BN, int VA, bool FULL>
 __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
-                                                  int64_t ldc, int M, int N, int K, int n_tiles_n, int n_tiles)
+                                                  int64_t ldc, int M_bound, const int32_t *__restrict__ M_dev, int N,
+                                                  int K, int n_tiles_n, int n_tiles)
 {
     constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront (times 2 row tiles)
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_STRIDE];
@@ -116,6 +117,8 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int tile = (bid & 7) * per_xcd + (bid >> 3);
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM, n0 = (int64_t)(tile % n_tiles_n) * BN;
+    const int M = resolve_count(M_bound, M_dev);
+    if (m0 >= M) return;  // the whole block leaves together, before any barrier
 
     doublex4 acc[2][NT];
 #pragma unroll
@@ -190,29 +193,29 @@ static int widest(const float *p, int64_t ld)
 }
 
 template <int BN>
-static void launch_gemm(const float *Z, int64_t ldz, int M, int K, const float *W, int64_t ldw, int N, float *H,
+static void launch_gemm(const float *Z, int64_t ldz, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *H,
                         int64_t ldh, hipStream_t st)
 {
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8));
     const int va = widest(Z, ldz);
-    const bool full = M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;
+    const bool full = !M_dev && M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;
     if (full)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
     else if (va == 4)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
     else if (va == 2)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
     else
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
 }
 
 }  // namespace csgs
 
 using namespace csgs;
 
-extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const float *W, int64_t ldw,
+extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev, int32_t K, const float *W, int64_t ldw,
                                int32_t Nout, float *H, int64_t ldh, void *stream)
 {
     if (!Z || !W || !H || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldw < Nout || ldh < Nout) return CSGS_EINVAL;
@@ -222,9 +225,9 @@ extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K
     // narrow column tiles when wide ones would leave fewer than two blocks per compute unit
     const int64_t wide_tiles = tm * (((int64_t)Nout + 63) / 64);
     if (wide_tiles >= 512 && Nout > 32)
-        launch_gemm<64>(Z, ldz, M, K, W, ldw, Nout, H, ldh, st);
+        launch_gemm<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
     else
-        launch_gemm<32>(Z, ldz, M, K, W, ldw, Nout, H, ldh, st);
+        launch_gemm<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -27,13 +27,15 @@ namespace csgs {
 constexpr int RP_ITEMS = 8;  // rows per thread and round in row_prefix
 
 __global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
-                                                   const int32_t *__restrict__ S, int32_t nS,
+                                                   const int32_t *__restrict__ S, int32_t nS_bound,
+                                                   const int32_t *__restrict__ nS_dev, int32_t shift_base,
                                                    int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
-                                                   int64_t edge_cap, csgs_prob_stats *__restrict__ stats,
-                                                   int32_t *__restrict__ status)
+                                                   int32_t *__restrict__ meta, int64_t edge_cap,
+                                                   csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status)
 {
     __shared__ int64_t lds[17];
     __shared__ int32_t s_deg[1024 * RP_ITEMS];
+    const int32_t nS = resolve_count(nS_bound, nS_dev);
     bool bad = false;
     int64_t base = 0;
     // rounds of 8192 rows: degrees are fetched striped (coalesced, all loads independent), handed
@@ -84,16 +86,25 @@ __global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ r
             base = 0;
         }
         eoff[nS] = base;
+        // fraction bits for this many rows: the sum of nS weights must stay below 2^61 / (s_fx rmax)
+        int32_t lg = 0;
+        while (lg < 31 && (1ll << lg) < (int64_t)nS) ++lg;
+        const int32_t shift = shift_base - lg;
+        meta[META_ROWS] = nS;
+        meta[META_SHIFT] = shift > 52 ? 52 : shift;
     }
 }
 
 __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                  int64_t n_nodes, int32_t nS, const int64_t *__restrict__ eoff,
-                                                  const int64_t *__restrict__ rowstart, double scale,
+                                                  int64_t n_nodes, const int32_t *__restrict__ meta,
+                                                  const int64_t *__restrict__ eoff,
+                                                  const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
                                                   int32_t *__restrict__ status)
 {
     __shared__ RowSlice slice;
+    const int32_t nS = meta[META_ROWS];
+    const double scale = ldexp(1.0, meta[META_SHIFT]);
     const int64_t E = eoff[nS];
     bool bad = false;
     for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
@@ -200,8 +211,8 @@ __global__ __launch_bounds__(64) void cand_groups(const uint64_t *__restrict__ p
 __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
                                                  int32_t hi, SkewPolicy pol, const uint64_t *__restrict__ partial,
-                                                 const uint64_t *__restrict__ gtot, int32_t shift,
-                                                 csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
+                                                 const uint64_t *__restrict__ gtot,
+                                                 const int32_t *__restrict__ meta, csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
                                                  uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
 {
@@ -298,7 +309,7 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
         stats->w_local = tot[1];
         stats->w_remote = tot[2];
         stats->total = total_w;
-        stats->shift = shift;
+        stats->shift = meta[META_SHIFT];
         stats->skew_fx = (int32_t)m_local * (m_remote ? 1 : -1);
         int32_t st = 0;
         if (n_cand == 0 || total_w == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
@@ -321,13 +332,22 @@ static int ceil_log2_u64(uint64_t n)
     return e;
 }
 
+// 61 - ceil(log2 s_fx) - ceil(log2 rmax): the fraction bits a single row could use
+static int shift_base_for(int64_t s_fx, float rownorm2_max)
+{
+    int e_r = 0;
+    while (e_r < 64 && ldexp(1.0, e_r) < (double)rownorm2_max) ++e_r;
+    return 61 - ceil_log2_u64((uint64_t)s_fx) - e_r;
+}
+
 }  // namespace csgs
 
-int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const Workspace &w,
-                            csgs_prob_stats *stats, int32_t *status, hipStream_t st)
+int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
+                            int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status,
+                            hipStream_t st)
 {
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, rowptr, n_nodes, S, nS, w.eoff, w.rowstart,
-                w.chunk_cap * EDGE_TILE, stats, status);
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, w.eoff,
+                w.rowstart, w.meta, w.chunk_cap * EDGE_TILE, stats, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -369,16 +389,15 @@ extern "C" int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int3
     if (nS <= 0 || !(skew >= 1.0f) || skew > 1048576.0f || !(rownorm2_max > 0.0f) || !isfinite(rownorm2_max))
         return CSGS_EINVAL;
     const int64_t sfx = llround((double)skew * 16.0);
-    int e_r = 0;
-    while (e_r < 64 && ldexp(1.0, e_r) < (double)rownorm2_max) ++e_r;
-    int sh = 61 - ceil_log2_u64((uint64_t)nS) - ceil_log2_u64((uint64_t)sfx) - e_r;
+    int sh = shift_base_for(sfx, rownorm2_max) - ceil_log2_u64((uint64_t)nS);
     if (sh > 52) sh = 52;
     if (shift) *shift = sh;
     if (s_fx) *s_fx = sfx;
     return sh < 24 ? CSGS_ERANGE : CSGS_OK;
 }
 
-static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, float shift_skew, SkewPolicy pol,
+static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *nS_dev,
+                            float shift_skew, SkewPolicy pol,
                             int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap,
                             csgs_prob_stats *stats, csgs_workspace *ws, int32_t *status, void *stream)
 {
@@ -398,10 +417,12 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, f
     const int64_t n_words = (g->n_nodes + 63) / 64;
     const unsigned n_groups = (unsigned)((w.n_tiles + 63) / 64);
 
-    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, w, stats, status, st);
+    // the shift for nS rows has passed the range check; fewer rows on the device only widen it
+    const int32_t shift_base = shift_base_for(s_fx, g->rownorm2_max);
+    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
     if (rc != CSGS_OK) return rc;
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, nS, w.eoff,
-                w.rowstart, ldexp(1.0, shift), w.wtable, w.tileflag, status);
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, w.meta, w.eoff,
+                w.rowstart, w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, g->local_lo, g->local_hi, w.partial);
@@ -409,13 +430,14 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, f
     CSGS_LAUNCH(K_CAND_GROUPS, cand_groups, dim3(n_groups), dim3(64), st, w.partial, w.n_tiles, w.gtot);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, shift, stats, status, cand_id,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, w.meta, stats, status, cand_id,
                 cand_w, cdf, q, cap);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
 
-extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t nS, float skew, int32_t *cand_id,
+extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *nS_dev, float skew,
+                                int32_t *cand_id,
                                 uint64_t *cand_w, uint64_t *cdf, float *q, int64_t cap, csgs_prob_stats *stats,
                                 csgs_workspace *ws, int32_t *status, void *stream)
 {
@@ -425,15 +447,16 @@ extern "C" int csgs_build_probs(const csgs_graph *g, const int32_t *S, int32_t n
         pol.mode = 2;
         shift_skew = 1.0f;
     }
-    return build_probs_impl(g, S, nS, shift_skew, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
+    return build_probs_impl(g, S, nS, nS_dev, shift_skew, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
 }
 
-extern "C" int csgs_build_probs_auto(const csgs_graph *g, const int32_t *S, int32_t nS, float D, int32_t B,
+extern "C" int csgs_build_probs_auto(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *nS_dev, float D,
+                                     int32_t B,
                                      float skew_max, int32_t *cand_id, uint64_t *cand_w, uint64_t *cdf, float *q,
                                      int64_t cap, csgs_prob_stats *stats, csgs_workspace *ws, int32_t *status,
                                      void *stream)
 {
     if (!(D >= 0.0f) || !isfinite(D) || B <= 0) return CSGS_EINVAL;
     SkewPolicy pol = {1, 0, (double)D, (int64_t)B, 0};
-    return build_probs_impl(g, S, nS, skew_max, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
+    return build_probs_impl(g, S, nS, nS_dev, skew_max, pol, cand_id, cand_w, cdf, q, cap, stats, ws, status, stream);
 }

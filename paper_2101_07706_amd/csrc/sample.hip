@@ -186,7 +186,8 @@ __device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, 
 }
 
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                 int64_t n_nodes, int32_t nS, const int64_t *__restrict__ eoff,
+                                                 int64_t n_nodes, const int32_t *__restrict__ meta,
+                                                 const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
                                                  const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
                                                  unsigned long long tag, unsigned long long hits_tag,
@@ -203,6 +204,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     const int wave = (int)(threadIdx.x >> 6);
     const TileState<1> ts(ts_mem, chunk_cap);
     const uint64_t rank_tag = (hits_tag & 0xFFFFFFFFull) << 32;
+    const int32_t nS = meta[META_ROWS];
     int64_t E = eoff[nS];
     int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
     bool overflow = false;
@@ -403,7 +405,8 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
 }
 
 // rows == nullptr: reuse the row offsets that csgs_build_probs left in the workspace for the same rows
-static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int32_t n_rows, bool reuse_offsets,
+static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int32_t n_rows, const int32_t *n_rows_dev,
+                                  bool reuse_offsets,
                                   int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
                                   int64_t *adj_nnz, csgs_workspace *ws, int32_t *status, void *stream)
 {
@@ -416,22 +419,22 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (!reuse_offsets) {
-        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, w, nullptr, status, st);
+        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
     const unsigned long long adj_tag = ++ws->epoch;
     CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes,
-                n_rows, w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, (unsigned long long)ws->draw_epoch, w.adj_ts, w.chunk_cap,
+                w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, (unsigned long long)ws->draw_epoch, w.adj_ts, w.chunk_cap,
                 adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
 
-extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, int32_t n_rows, int32_t *adj_rowptr,
-                                      int32_t *adj_col, float *adj_val, int64_t adj_cap, int64_t *adj_nnz,
+extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, int32_t n_rows,
+                                      const int32_t *n_rows_dev, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap, int64_t *adj_nnz,
                                       csgs_workspace *ws, int32_t *status, void *stream)
 {
-    return sampled_adjacency_impl(g, rows, n_rows, false, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status,
+    return sampled_adjacency_impl(g, rows, n_rows, n_rows_dev, false, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status,
                                   stream);
 }
 
@@ -446,7 +449,7 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
     const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, layer, S_next, mult, p_incl,
                                    n_next, ws, status, stream);
     if (rc != CSGS_OK) return rc;
-    return sampled_adjacency_impl(g, S, nS, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, stream);
+    return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, stream);
 }
 
 extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo, int32_t local_hi,

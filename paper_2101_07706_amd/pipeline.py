@@ -66,16 +66,19 @@ class LayerBuffers:
                                total=s.total, shift=s.shift, skew_fx=s.skew_fx)
 
 
-def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None):
+def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None, nS_dev=None):
     """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32).
-    auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound."""
+    auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound.
+    nS_dev: device int32 with the number of rows of S to use (the previous layer's n_next), so that
+    the host need not wait for it; S is then the whole capacity-sized array."""
     nS = S.numel()
     q = lb.q if want_q else None
     if auto_D is None:
-        csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc, lb.status, stream)
+        csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc, lb.status, stream,
+                              nS_dev=nS_dev)
     else:
         csgs.csgs_build_probs_auto(dg.c, S, auto_D, B, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc,
-                                   lb.status, stream)
+                                   lb.status, stream, nS_dev=nS_dev)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
                            ws.desc, lb.status, stream)
@@ -83,8 +86,15 @@ def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=Tru
                            lb.per_part, lb.src_row, lb.remote_ids, stream)
 
 
-def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None):
-    """csgs_aggregate -> csgs_layer_gemm for one layer; Z and H are preallocated [nS, F] / [nS, F_out]."""
+def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None):
+    """csgs_aggregate -> csgs_layer_gemm for one layer; Z and H are preallocated [nS, F] / [nS, F_out].
+    nS_dev: as in sample_step (nS is then the capacity)."""
     csgs.csgs_aggregate(lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.n_next, X_local, X_remote,
-                        lb.src_row if use_src_row else None, relu, Z, stream)
-    csgs.csgs_layer_gemm(Z, W, H, stream)
+                        lb.src_row if use_src_row else None, relu, Z, stream, nS_dev=nS_dev)
+    csgs.csgs_layer_gemm(Z, W, H, stream, M_dev=nS_dev)
+
+
+def stage_remote_rows(lb, X, staged, stream=None):
+    """Fills `staged` [B, F] with the feature rows of the sampled remote nodes (csgs_gather_rows over the
+    request list): the one-GPU stand-in for the exchange between partitions."""
+    csgs.csgs_gather_rows(X, lb.remote_ids, lb.remote_total, staged, stream)

@@ -41,7 +41,9 @@ def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, auto_D=None):
     return steps
 
 
-def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None, auto_D=None):
+def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None, auto_D=None, device_counts=False):
+    if device_counts:
+        return gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D)
     import torch
     from paper_2101_07706_amd import pipeline
     dev = torch.device("cuda:0")
@@ -84,6 +86,56 @@ def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None
     torch.cuda.synchronize()
     # workspace must be back in its prepared (all-zero) state
     from paper_2101_07706_amd import csgs
+    clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0, "workspace not restored"
+    return steps, ws
+
+
+def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D):
+    """The same chain enqueued without the host reading anything back in between: every layer's
+    row count stays on the device (the previous layer's n_next), arrays have their capacity
+    sizes, the staged remote rows come from csgs_gather_rows."""
+    import torch
+    from paper_2101_07706_amd import csgs, pipeline
+    dev = torch.device("cuda:0")
+    dg = dg or pipeline.DeviceGraph(g, dev)
+    M = len(Ws)
+    nS_max = max(len(S0), B)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
+    Xd = torch.from_numpy(synth.to_bf16_bits(X).view(np.int16) if bf16 else X).to(dev)
+    Wd = [torch.from_numpy(W).to(dev) for W in Ws]
+    cap = adj_cap or min(g.nnz, 1 << 26)
+    lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, cap, dg.n_parts, dev) for _ in range(M)]
+    Zs = [torch.full((len(S0) if l == 0 else B, Wd[M - 1 - l].shape[0]), float("nan"), dtype=torch.float32, device=dev)
+          for l in range(M)]
+    Hs = [torch.full((len(S0) if l == 0 else B, Wd[M - 1 - l].shape[1]), float("nan"), dtype=torch.float32, device=dev)
+          for l in range(M)]
+    staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
+    S0d = torch.from_numpy(np.ascontiguousarray(S0, np.int32)).to(dev)
+    torch.cuda.synchronize()
+    # ---- nothing below reads device memory on the host until the final synchronize
+    for l in range(M):
+        S = S0d if l == 0 else lbs[l - 1].S_next
+        nS_dev = None if l == 0 else lbs[l - 1].n_next
+        pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lbs[l], auto_D=auto_D, nS_dev=nS_dev)
+    pipeline.stage_remote_rows(lbs[M - 1], Xd, staged)
+    X_local = Xd[g.local_lo:g.local_hi]
+    for l in range(M - 1, -1, -1):
+        nS = len(S0) if l == 0 else B
+        nS_dev = None if l == 0 else lbs[l - 1].n_next
+        if l == M - 1:
+            pipeline.compute_step(lbs[l], nS, X_local, staged, True, False, Wd[0], Zs[l], Hs[l], nS_dev=nS_dev)
+        else:
+            pipeline.compute_step(lbs[l], nS, Hs[l + 1], None, False, True, Wd[M - 1 - l], Zs[l], Hs[l], nS_dev=nS_dev)
+    torch.cuda.synchronize()
+    steps = []
+    for l in range(M):
+        n_rows = len(S0) if l == 0 else int(lbs[l - 1].n_next.item())
+        S = S0d if l == 0 else lbs[l - 1].S_next[:n_rows]
+        # rows past the device count must be untouched
+        assert bool(torch.isnan(Zs[l][n_rows:]).all()) and bool(torch.isnan(Hs[l][n_rows:]).all()), f"layer {l}: wrote past the row count"
+        steps.append(SimpleNamespace(S=S, lb=lbs[l], n_next=int(lbs[l].n_next.item()), status=int(lbs[l].status.item()),
+                                     Z=Zs[l][:n_rows], H=Hs[l][:n_rows]))
     clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
     assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0, "workspace not restored"
     return steps, ws

@@ -68,11 +68,12 @@ def test_workspace_sizing():
 def test_null_arguments_are_rejected_before_any_launch():
     L = csgs.lib()
     z = C.c_void_p(0)
-    assert L.csgs_build_probs(None, z, 1, 2.0, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
+    assert L.csgs_build_probs(None, z, 1, z, 2.0, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
     assert L.csgs_sample_layer(None, z, 1, z, z, 1, z, 1, 0, 0, 0, z, z, z, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
     assert L.csgs_remote_count(z, z, 0, 1, z, 0, z, z, z, z, z) == csgs.EINVAL
-    assert L.csgs_aggregate(z, z, z, 1, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
-    assert L.csgs_layer_gemm(z, 1, 1, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
+    assert L.csgs_aggregate(z, z, z, 1, z, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
+    assert L.csgs_gather_rows(z, 1, 1, 1, 0, z, 1, z, z, 1, z) == csgs.EINVAL
     assert L.csgs_workspace_init(None, z) == csgs.EINVAL
     ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0, 0, 0, 0)
     assert L.csgs_workspace_init(C.byref(ws), z) == csgs.EINVAL           # null base

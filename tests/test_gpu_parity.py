@@ -404,3 +404,128 @@ def test_layer_gemm_shapes(dev, M, K, N):
     csgs.csgs_layer_gemm(torch.from_numpy(Z).to(dev), torch.from_numpy(W).to(dev), H)
     torch.cuda.synchronize()
     chain.assert_close(H.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"gemm {M}x{K}x{N}")
+
+
+# ---------------------------------------------------------------- row counts that stay on the device
+def run_config_device_counts(name, it=0, auto_D=None):
+    cfg, g, X, Ws, S0 = chain.config_inputs(name, it)
+    bf16 = cfg.feat_dtype == "bf16"
+    say(f"[{name}] device-side row counts, it={it} auto_D={auto_D}")
+    osteps = chain.oracle_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
+                                device_counts=True)
+    worst = chain.compare_chain(osteps, gsteps)
+    say(f"[{name}] n' per layer {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium", "mid"])
+def test_chain_without_host_reads(dev, name):
+    """The whole step enqueued with every layer's row count left on the device (n_dev arguments,
+    capacity-sized arrays, staged remote rows by csgs_gather_rows): same results as the oracle."""
+    run_config_device_counts(name)
+    if name == "tiny":
+        run_config_device_counts(name, it=2, auto_D=8.0)
+
+
+def test_chain_without_host_reads_large(dev):
+    cfg, g, X, Ws, _ = cached_inputs("large")
+    S0 = synth.make_batch(g, cfg.batch, cfg.seed, 3)
+    osteps = chain.oracle_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, 3, True)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, 3, True, device_counts=True)
+    worst = chain.compare_chain(osteps, gsteps)
+    say(f"[large] device-side row counts: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+
+
+def test_device_row_count_small_and_zero(dev):
+    """A device count below the capacity gives exactly the result of a call with that many rows;
+    a device count of zero gives an empty candidate set (status bit) and writes nothing else."""
+    from paper_2101_07706_amd import csgs, pipeline
+    g = SmallGraph(2000, 10, seed=11, lo=400, hi=900)
+    rng = np.random.default_rng(4)
+    S_full = rng.permutation(2000)[:300].astype(np.int32)
+    B = 128
+    dg = pipeline.DeviceGraph(g, dev)
+    ws = pipeline.Workspace(g.n_nodes, 300, B, g.nnz, dev)
+    Sd = torch.from_numpy(S_full).to(dev)
+    for n_rows in (300, 77, 1):
+        pr = oracle.build_probs(g, S_full[:n_rows], 3.0)
+        sm = oracle.sample_layer(g, S_full[:n_rows], pr, B, 5, 1, 0)
+        lb = pipeline.LayerBuffers(300, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+        lb.adj_rowptr.fill_(-7)
+        cnt = torch.tensor([n_rows], dtype=torch.int32, device=dev)
+        pipeline.sample_step(dg, ws, Sd, 3.0, B, 5, 1, 0, lb, nS_dev=cnt)
+        torch.cuda.synchronize()
+        assert int(lb.status.item()) == 0
+        st = lb.stats_host()
+        assert (st.n_cand, st.total, st.shift) == (pr.n_cand, pr.total, pr.shift)
+        np.testing.assert_array_equal(chain.u64(lb.cdf[:pr.n_cand]), pr.cdf)
+        m = int(lb.n_next.item())
+        assert m == sm.n_next
+        np.testing.assert_array_equal(lb.S_next[:m].cpu().numpy(), sm.S_next)
+        np.testing.assert_array_equal(lb.adj_rowptr[:n_rows + 1].cpu().numpy(), sm.adj_rowptr)
+        assert bool((lb.adj_rowptr[n_rows + 1:] == -7).all()), "row pointers past the device count were written"
+        np.testing.assert_array_equal(lb.adj_col[:sm.adj_nnz].cpu().numpy(), sm.adj_col)
+    lb = pipeline.LayerBuffers(300, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    csgs.csgs_build_probs(dg.c, Sd, 3.0, lb.cand_id, lb.cand_w, lb.cdf, lb.q, lb.stats, ws.desc, lb.status, nS_dev=cnt)
+    torch.cuda.synchronize()
+    assert int(lb.status.item()) == csgs.ST_EMPTY_CANDIDATES
+    assert lb.stats_host().n_cand == 0 and lb.stats_host().edges_scanned == 0
+    clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
+    assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0
+
+
+@pytest.mark.parametrize("F,bf16,off", [(64, False, 0), (100, True, 0), (602, True, 0), (33, False, 0), (7, True, 1),
+                                        (256, False, 2)])
+def test_gather_rows(dev, F, bf16, off):
+    """csgs_gather_rows against plain indexing, for every vector width the alignment allows."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(F)
+    rows, cap, n = 500, 200, 137
+    ld = F + off
+    if bf16:
+        Xh = rng.integers(-30000, 30000, (rows, ld)).astype(np.int16)
+    else:
+        Xh = rng.standard_normal((rows, ld)).astype(np.float32)
+    ids = rng.integers(0, rows, cap).astype(np.int32)
+    ids[5], ids[6] = -1, rows      # outside the table: zero rows
+    Xd = torch.from_numpy(Xh).to(dev)[:, :F]
+    out = torch.full((cap, ld), 99, dtype=Xd.dtype, device=dev)[:, :F]
+    csgs.csgs_gather_rows(Xd, torch.from_numpy(ids).to(dev), torch.tensor([n], dtype=torch.int64, device=dev), out)
+    torch.cuda.synchronize()
+    want = Xh[:, :F][np.clip(ids[:n], 0, rows - 1)].copy()
+    want[5] = 0
+    want[6] = 0
+    got = out.cpu().numpy()
+    np.testing.assert_array_equal(got[:n], want)
+    assert (got[n:] == 99).all(), "rows past the device count were written"
+
+
+def test_layer_gemm_and_aggregate_device_row_count(dev):
+    """M_dev / nS_dev below the capacity: the first rows equal a call of that size, the rest stay untouched."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(8)
+    M, K, N, m = 700, 96, 80, 389
+    Z = rng.standard_normal((M, K)).astype(np.float32)
+    W = rng.standard_normal((K, N)).astype(np.float32)
+    Zd, Wd = torch.from_numpy(Z).to(dev), torch.from_numpy(W).to(dev)
+    H = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    cnt = torch.tensor([m], dtype=torch.int32, device=dev)
+    csgs.csgs_layer_gemm(Zd, Wd, H, M_dev=cnt)
+    torch.cuda.synchronize()
+    chain.assert_close(H[:m].cpu().numpy(), oracle.layer_gemm(Z[:m], W), chain.RTOL, chain.ATOL, "H with M_dev")
+    assert bool(torch.isnan(H[m:]).all())
+    # aggregation: random CSR with M rows over 300 input rows
+    deg = rng.integers(0, 70, M)
+    rp = np.zeros(M + 1, np.int32)
+    np.cumsum(deg, out=rp[1:])
+    col = np.concatenate([np.sort(rng.choice(300, d, replace=False)) for d in deg]).astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    X = rng.standard_normal((300, K)).astype(np.float32)
+    Zo = torch.full((M, K), float("nan"), dtype=torch.float32, device=dev)
+    csgs.csgs_aggregate(torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), torch.from_numpy(val).to(dev),
+                        None, torch.from_numpy(X).to(dev), None, None, True, Zo, nS_dev=cnt)
+    torch.cuda.synchronize()
+    want = oracle.aggregate(rp[:m + 1], col[:rp[m]], val[:rp[m]], X, relu_on_input=True)
+    chain.assert_close(Zo[:m].cpu().numpy(), want, chain.RTOL, chain.ATOL, "Z with nS_dev")
+    assert bool(torch.isnan(Zo[m:]).all())
