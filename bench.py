@@ -45,7 +45,7 @@ def algorithmic_bytes(s, N):
         "hits_fused": nc / 8 + 36 * n2,                     # position bitmap, per hit: count, 2 cdf, id, 4 outputs
         "adj_fused": 4 * E + 16 * nS + 4 * nS + 20 * nnz,   # col per edge, row slices, row pointers, kept edges
         "remote_count": 12 * n2,
-        "aggregate": agg, "aggregate_long": 0.0,            # long rows are part of the same algorithmic volume
+        "aggregate": agg,
         "layer_gemm": 4 * (nS * Fi + Fi * Fo + nS * Fo),
         "gather_rows": 0.0,                                 # filled in by the caller (remote rows, bottom layer only)
     }
@@ -140,8 +140,7 @@ class Workload:
                               alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
             if alg.get(k):
                 kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
-        # the aggregation is two launches (ordinary rows, long rows) over one algorithmic volume
-        agg_ms = prof.get("aggregate", (0, 1))[0] + prof.get("aggregate_long", (0, 1))[0]
+        agg_ms = prof["aggregate"][0]
         agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
         gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
         kernels["layer_gemm"]["TFLOPs"] = gemm_TF

@@ -52,6 +52,7 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
 
 constexpr int LONG_ROW = 32;    // rows with more kept edges than this go to the block-cooperative kernel
 constexpr int UNR = 8;          // gathered rows in flight per lane
+constexpr int AGG_BLOCK = 1024; // threads per block: 16 wavefronts
 
 // Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.
 template <typename T>
@@ -123,23 +124,19 @@ __device__ inline void store_row(float *z, const double (&acc)[V])
         z[0] = (float)acc[0];
 }
 
+// Ordinary rows: block `bid` of AGG_BLOCK threads owns AGG_BLOCK / G consecutive rows.
 template <typename T, int V, int G, bool RELU>
-__global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
-                                                   const int32_t *__restrict__ adj_col,
-                                                   const float *__restrict__ adj_val, int32_t nS_bound,
-                                                   const int32_t *__restrict__ nS_dev,
-                                                   const int32_t *__restrict__ n_cols_p, const T *__restrict__ Xl,
-                                                   int64_t ldl, int64_t rows_l, const T *__restrict__ Xr, int64_t ldr,
-                                                   int64_t rows_r, const int32_t *__restrict__ src_row, int32_t F,
-                                                   float *__restrict__ Z, int64_t ldz)
+__device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ adj_rowptr,
+                                      const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
+                                      int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
+                                      const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                      const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z, int64_t ldz)
 {
-    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
-    const int32_t nS = resolve_count(nS_bound, nS_dev);
     const int tid = (int)threadIdx.x;
     const int g = tid & (G - 1);  // lane within the row group
     const int gbase = tid & (WAVE - 1) & ~(G - 1);
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + tid) / G;
-    // Rows past the end, and long rows (left to aggregate_long_k), take part in the lane broadcasts of
+    const int64_t row = (bid * AGG_BLOCK + tid) / G;
+    // Rows past the end, and long rows (left to the long-row blocks), take part in the lane broadcasts of
     // their wavefront with an empty range.
     int32_t beg = 0, end = 0;
     if (row < nS) { beg = adj_rowptr[row]; end = adj_rowptr[row + 1]; }
@@ -175,33 +172,28 @@ __global__ __launch_bounds__(256) void aggregate_k(const int32_t *__restrict__ a
     }
 }
 
-// Rows with more than LONG_ROW kept edges (hubs among the rows of S): one block of 16 wavefronts
-// per row, each wavefront takes a contiguous sixteenth of the row's edges, partial sums are added
-// in wavefront order through LDS (fixed order: the result does not depend on timing).
+// Rows with more than LONG_ROW kept edges (hubs among the rows of S): the block's 16 wavefronts
+// work on one such row at a time, each wavefront takes a contiguous sixteenth of the row's edges,
+// partial sums are added in wavefront order through LDS (fixed order: the result does not depend
+// on timing).  Block `bid` of `n_blocks` looks for long rows among its share of `per` rows.
 template <typename T, int V, bool RELU>
-__global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restrict__ adj_rowptr,
-                                                         const int32_t *__restrict__ adj_col,
-                                                         const float *__restrict__ adj_val, int32_t nS_bound,
-                                                         const int32_t *__restrict__ nS_dev,
-                                                         const int32_t *__restrict__ n_cols_p,
-                                                         const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
-                                                         const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
-                                                         const int32_t *__restrict__ src_row, int32_t F,
-                                                         float *__restrict__ Z, int64_t ldz)
+__device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32_t *__restrict__ adj_rowptr,
+                                           const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
+                                           int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl,
+                                           int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                           const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z,
+                                           int64_t ldz)
 {
     __shared__ double part[16][WAVE * V];
     __shared__ int32_t long_rows[1024];
     __shared__ int32_t n_long;
-    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
-    const int32_t nS = resolve_count(nS_bound, nS_dev);
     const int tid = (int)threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     // this block's share of the rows, searched in parallel for long ones
-    const int32_t per = (nS_bound + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;
-    const int32_t r0 = (int32_t)blockIdx.x * per;
+    const int32_t r0 = bid * per;
     if (tid == 0) n_long = 0;
     __syncthreads();
-    for (int32_t i = tid; i < per; i += 1024) {   // per <= 1024 is arranged by the host
+    for (int32_t i = tid; i < per; i += AGG_BLOCK) {   // per <= 1024 is arranged by the host
         const int32_t row = r0 + i;
         if (row < nS && adj_rowptr[row + 1] - adj_rowptr[row] > LONG_ROW) long_rows[atomicAdd(&n_long, 1)] = row;
     }
@@ -246,29 +238,49 @@ __global__ __launch_bounds__(1024) void aggregate_long_k(const int32_t *__restri
     }
 }
 
+// One launch: the first n_long_blocks blocks take the long rows (they start first, so the slowest
+// work is not left for the end), the others the ordinary rows.
+template <typename T, int V, int G, bool RELU>
+__global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
+                                                         const int32_t *__restrict__ adj_col,
+                                                         const float *__restrict__ adj_val, int32_t nS_bound,
+                                                         const int32_t *__restrict__ nS_dev,
+                                                         const int32_t *__restrict__ n_cols_p,
+                                                         const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
+                                                         const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                                         const int32_t *__restrict__ src_row, int32_t F,
+                                                         float *__restrict__ Z, int64_t ldz, int32_t n_long_blocks,
+                                                         int32_t per)
+{
+    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+    const int32_t nS = resolve_count(nS_bound, nS_dev);
+    if ((int32_t)blockIdx.x < n_long_blocks)
+        aggregate_long_rows<T, V, RELU>((int32_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl, rows_l,
+                                        Xr, ldr, rows_r, src_row, F, Z, ldz);
+    else
+        aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x - n_long_blocks, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl,
+                                      ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz);
+}
+
 template <typename T, int V, int G>
 static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                       hipStream_t st)
 {
-    const int rows_per_block = 256 / G;
-    const unsigned blocks = (unsigned)((nS + rows_per_block - 1) / rows_per_block);
-    // long-row kernel: every block looks at no more than 1024 rows
-    unsigned lblocks = 512;
-    if ((nS + 1023) / 1024 > (int)lblocks) lblocks = (unsigned)((nS + 1023) / 1024);
-    if (relu) {
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), dim3(blocks), dim3(256), st, rp, col, val, nS, nsd, ncp, (const T *)Xl,
-                    ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
-        CSGS_LAUNCH_CHECK();
-        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, true>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
-    } else {
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), dim3(blocks), dim3(256), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
-        CSGS_LAUNCH_CHECK();
-        CSGS_LAUNCH(K_AGG_LONG, (aggregate_long_k<T, V, false>), dim3(lblocks), dim3(1024), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz);
-    }
+    const int rows_per_block = AGG_BLOCK / G;
+    const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
+    // long-row blocks: about 128 rows each to look through, never more than 1024
+    int64_t lblocks = ((int64_t)nS + 127) / 128;
+    if (lblocks > 256) lblocks = 256;
+    if (lblocks < ((int64_t)nS + 1023) / 1024) lblocks = ((int64_t)nS + 1023) / 1024;
+    const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
+    const dim3 grid((unsigned)(blocks + lblocks));
+    if (relu)
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per);
+    else
+        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

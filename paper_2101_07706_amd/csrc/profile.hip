@@ -20,7 +20,7 @@ static bool g_open = false;
 static const size_t kMaxPairs = 1 << 16;
 
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_groups", "cand_emit", "draw", "hits_fused",
-                                            "adj_fused", "remote_count", "aggregate", "aggregate_long",
+                                            "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "fill_zero", "copy"};
 
 void record(int kid, hipStream_t st, bool start)

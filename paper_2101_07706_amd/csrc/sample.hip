@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             // rows that start at or after the last edge (trailing empty rows, and the end pointer)
             const int64_t total = base + tile_cnt;
             const int32_t clamp = (int32_t)(total < 0x7FFFFFFFll ? total : 0x7FFFFFFFll);
-            const int64_t first_tail = lower_bound_i64(eoff, (int64_t)nS + 1, E);
+            const int64_t first_tail = wave_lower_bound(eoff, (int64_t)nS + 1, E);
             for (int64_t a = first_tail + threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = clamp;
             if (threadIdx.x == 0) {
                 *adj_nnz = total;
@@ -291,36 +291,6 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             }
         }
     }
-}
-
-// First index in [0, n) with a[idx] >= key, found by the whole wavefront: every round the 64 lanes
-// probe the ends of 64 equal segments at once, so an array of 8192 entries takes 3 dependent loads
-// instead of 13.  All lanes must call it with the same arguments; all get the result.
-__device__ inline int32_t wave_lower_bound(const int32_t *__restrict__ a, int32_t n, int32_t key)
-{
-    const int lane = lane_id();
-    int32_t lo = 0, hi = n;
-    while (hi > lo) {
-        const int32_t len = hi - lo;
-        const int32_t step = (len + WAVE - 1) / WAVE;
-        const int32_t seg_end = lo + ((lane + 1) * step < len ? (lane + 1) * step : len);  // exclusive
-        const int32_t seg_beg = lo + (lane * step < len ? lane * step : len);
-        bool ge = true;  // empty segments sit past the end: treat as "all remaining entries are >= key"
-        if (seg_end > seg_beg) ge = a[seg_end - 1] >= key;
-        const uint64_t m = __ballot(ge);
-        const int first = m ? __ffsll((unsigned long long)m) - 1 : WAVE;
-        const int32_t fb = lo + (first * step < len ? first * step : len);
-        const int32_t fe = lo + ((first + 1) * step < len ? (first + 1) * step : len);
-        if (fe <= fb) {          // no segment ends at or above key: every entry is below it
-            lo = hi;
-        } else if (step == 1) {  // segments are single entries: entry fb is the first >= key
-            return fb;
-        } else {                 // a[fe - 1] >= key and everything before fb is below key
-            lo = fb;
-            hi = fe;
-        }
-    }
-    return lo;
 }
 
 // S_next ascends and the local partition is one id range, so the sampled remote nodes are the

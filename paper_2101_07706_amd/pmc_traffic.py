@@ -19,10 +19,11 @@ import os
 
 CALIB_BYTES = 512 * 2 ** 20
 
-NAMES = [("aggregate_long_k", "aggregate_long"), ("aggregate_k", "aggregate"), ("gemm_f32_k", "layer_gemm"),
-         ("remote_count_k", "remote_count"), ("csgs::scan_edges", "scan_edges"), ("csgs::cand_fused", "cand_fused"),
+NAMES = [("aggregate_k", "aggregate"), ("gemm_f32_k", "layer_gemm"), ("gather_rows_k", "gather_rows"),
+         ("remote_count_k", "remote_count"), ("csgs::scan_edges", "scan_edges"), ("csgs::cand_partials", "cand_partials"),
+         ("csgs::cand_groups", "cand_groups"), ("csgs::cand_emit", "cand_emit"),
          ("csgs::row_prefix", "row_prefix"), ("csgs::draw", "draw"), ("csgs::hits_fused", "hits_fused"),
-         ("csgs::adj_fused", "adj_fused"), ("csgs::fill_q", "fill_q"), ("csgs::copy_k", "copy")]
+         ("csgs::adj_fused", "adj_fused"), ("csgs::copy_k", "copy")]
 
 
 def short_name(kernel: str):
