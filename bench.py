@@ -39,7 +39,6 @@ def algorithmic_bytes(s, N):
         "row_prefix": 28 * nS,                              # S, two row pointers, prefix + start written
         "scan_edges": 8 * E + 16 * nS + 8 * nc,             # col + val per edge, row slices, accumulators
         "cand_partials": N / 64 + 8 * nc,                   # flags, accumulators read
-        "cand_groups": 0.0,
         "cand_emit": N / 64 + 8 * nc + 20 * nc,             # the same again, id + weight + cdf written
         "draw": 12 * B,                                     # cdf probes are cache traffic
         "hits_fused": nc / 8 + 36 * n2,                     # position bitmap, per hit: count, 2 cdf, id, 4 outputs
@@ -117,8 +116,10 @@ class Workload:
         t0 = time.perf_counter()
         for it in range(warmup, warmup + steps):
             self.step(it)
+        enqueue_ms = (time.perf_counter() - t0) / steps * 1e3     # host time to enqueue a step (no waiting in it)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+        log(f"host enqueue {enqueue_ms:.3f} ms/step, wall {ms_per_step:.3f} ms/step")
         sizes = []
         csgs.csgs_profile_enable(True)
         for it in range(warmup, warmup + steps):

@@ -23,9 +23,11 @@ constexpr int CAND_TILE = 1024;   // node ids per block in the candidate scan
 constexpr int EDGE_TILE = 1024;   // edges per chunk in the flat edge passes
 constexpr int EDGE_GRID = 2048;   // blocks of the weight scan (grid-stride over chunks, no waits between blocks)
 constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in the hit compaction
+constexpr int ROW_TILE = 1024;    // rows of S per block in the degree prefix
 constexpr int META_WORDS = 4;
 constexpr int META_ROWS = 0;          // rows the latest row_prefix covered (the count behind eoff / rowstart)
 constexpr int META_SHIFT = 1;         // fraction bits of the fixed-point weights for that count
+constexpr int META_EDGES = 2;         // eoff[rows]: edges of those rows (0 when above the workspace's capacity)
 
 // Words of workspace a single-pass scan over at most `tiles` tiles with nv sums per tile needs
 // (one tag word and nv sums per tile, and twice that per group of 64 tiles).
@@ -45,15 +47,17 @@ struct Workspace {
     uint64_t *rank;      // [n_nodes]  (tag << 32) | (position in S_next + 1)
     uint64_t *partial;   // [4 * n_tiles] per-tile candidate counts and weight sums
     uint64_t *gtot;      // [4 * ceil(n_tiles / 64)] the same per group of 64 tiles
+    uint64_t *cand_flag; // [n_tiles] tag of the call whose partial sums a tile holds
     uint64_t *hit_ts;    // scan state of the hit tiles (1 sum per tile)
     // per call
     int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows of S
     int64_t *rowstart;   // [nS]     rowptr[S[a]]
     uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
+    uint64_t *rp_ts;     // scan state of the row tiles (1 sum per tile of ROW_TILE rows)
     double *pdbl;        // [B]      inclusion probabilities in double
-    int32_t *meta;       // [META_WORDS] what row_prefix resolved on the device: row count, weight shift
+    int64_t *meta;       // [META_WORDS] what row_prefix resolved on the device: row count, weight shift, edge count
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
-    int64_t n_tiles, hit_tiles;
+    int64_t n_tiles, hit_tiles, rp_tiles;
     size_t clean_bytes;  // size of the clean part
     size_t bytes;
 };
@@ -83,12 +87,15 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.rank = (uint64_t *)take((size_t)n_nodes * 8);
     w.partial = (uint64_t *)take((size_t)w.n_tiles * 4 * 8);
     w.gtot = (uint64_t *)take((size_t)((w.n_tiles + 63) / 64) * 4 * 8);
+    w.cand_flag = (uint64_t *)take((size_t)w.n_tiles * 8);
     w.hit_ts = (uint64_t *)take(scan_state_words(w.hit_tiles, 1) * 8);
     w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
+    w.rp_tiles = (nS_max + ROW_TILE - 1) / ROW_TILE;
+    w.rp_ts = (uint64_t *)take(scan_state_words(w.rp_tiles, 1) * 8);
     w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
     w.rowstart = (int64_t *)take((size_t)nS_max * 8);
     w.pdbl = (double *)take((size_t)B_max * 8);
-    w.meta = (int32_t *)take(META_WORDS * 4);
+    w.meta = (int64_t *)take(META_WORDS * 8);
     w.bytes = off;
     return w;
 }
@@ -125,7 +132,8 @@ __host__ inline int resident_grid()
 // min(52, shift_base - ceil(log2 count)), in w.meta for the kernels that follow.  Defined with the
 // weight scan.
 int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                      int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status, hipStream_t st);
+                      int32_t shift_base, const Workspace &w, csgs_workspace *ws, csgs_prob_stats *stats,
+                      int32_t *status, hipStream_t st);
 
 // A row count given on the host (n) or, when n_dev is not null, on the device with n as its bound.
 __device__ inline int32_t resolve_count(int32_t n, const int32_t *__restrict__ n_dev)
@@ -156,6 +164,23 @@ __device__ inline T wave_inclusive_scan(T v)
         if (lane >= off) v += t;
     }
     return v;
+}
+
+// K independent inclusive scans at once: the lane exchanges of the K chains are interleaved, so
+// their latencies overlap instead of adding up.
+template <typename T, int K>
+__device__ inline void wave_inclusive_scan_multi(T (&v)[K])
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        T t[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) t[k] = __shfl_up(v[k], off, WAVE);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (lane >= off) v[k] += t[k];
+    }
 }
 
 // Exclusive scan over the threads of a block (blockDim.x a multiple of 64, at most 1024).

@@ -11,7 +11,8 @@
 //   3. the first tile of a group adds the totals of all earlier groups and publishes that prefix
 //      for its group; the other tiles of the group read just this one value.
 //
-// Every wait ends.  A tile publishes its own sum before it waits for anything; a group total
+// Every wait ends.  A tile publishes its own sum (lookback_publish) before it waits for anything
+// (lookback_resolve), and nothing a block does between the two halves waits for another block; a group total
 // depends only on sums of lower tiles, the prefix only on group totals and sums of lower tiles.
 // So a block makes progress as long as the blocks that own lower tiles run, which holds in both
 // ways these kernels are launched:
@@ -91,24 +92,34 @@ __device__ inline bool wait_tag(const unsigned long long *p, unsigned long long 
     return f == tag;
 }
 
-// Publishes `local` (block-uniform sums of tile t of n_tiles) and returns in `excl` the sums over
-// tiles 0..t-1 (block-uniform).  Called by all threads; `lds` holds NV words.
+// First half: publishes `local` (the block-uniform sums of tile t).  Called by all threads; what a
+// block does between the two halves (issuing loads that do not depend on the prefix, arithmetic in
+// wavefronts other than the first) overlaps with the hops of the second half.
 template <int NV>
-__device__ inline void lookback(const TileState<NV> &ts, unsigned long long tag, long long t, long long n_tiles,
-                                const unsigned long long (&local)[NV], unsigned long long (&excl)[NV],
-                                unsigned long long *lds, int32_t *status)
+__device__ inline void lookback_publish(const TileState<NV> &ts, unsigned long long tag, long long t,
+                                        const unsigned long long (&local)[NV])
+{
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) st_relaxed(&ts.agg[t * NV + v], local[v]);
+        st_flag(&ts.flag[t], tag);
+    }
+}
+
+// Second half: returns in `excl` the sums over tiles 0..t-1 (block-uniform).  Called by all threads
+// after lookback_publish of the same tile; the first wavefront does the hops, the block meets at
+// a barrier at the end.  `lds` holds NV words; between two calls that use the same `lds` the block
+// must pass a barrier of its own.
+template <int NV>
+__device__ inline void lookback_resolve(const TileState<NV> &ts, unsigned long long tag, long long t, long long n_tiles,
+                                        const unsigned long long (&local)[NV], unsigned long long (&excl)[NV],
+                                        unsigned long long *lds, int32_t *status)
 {
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    __syncthreads();
     if (wave == 0) {
         const long long g = t / LB_GROUP;
         const int r = (int)(t % LB_GROUP);
-        if (lane == 0) {
-#pragma unroll
-            for (int v = 0; v < NV; ++v) st_relaxed(&ts.agg[t * NV + v], local[v]);
-            st_flag(&ts.flag[t], tag);
-        }
         bool ok = true;
         unsigned long long run[NV];
         // hop 1: earlier tiles of my group

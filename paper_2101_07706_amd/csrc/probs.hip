@@ -2,16 +2,19 @@
 // linear weighted sampling distribution (Section 4.2, Eq. 10) as an integer CDF.
 //
 // Kernels:
-//   row_prefix     one block: degrees of the rows of S, their exclusive prefix (the flat edge
-//                  numbering), CSR start of every row, total edges
+//   row_prefix     per tile of 1024 rows of S: degrees, their exclusive prefix (the flat edge
+//                  numbering; tile offsets by the single-pass scan across blocks), CSR start of
+//                  every row; the last tile leaves row count, edge count and weight shift for
+//                  the kernels that follow
 //   scan_edges     flat over the edges of S (chunks of 1024, rows of a chunk staged in LDS, so
 //                  hub rows and short rows cost the same per edge): square each edge value
 //                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
 //                  with fire-and-forget integer atomics (order-independent); flag the 64-node
 //                  word of the target with a plain byte store
 //   cand_partials  per tile of 1024 node ids: candidate count, local count, local and remote
-//                  weight sums of the flagged words (unskewed, so they do not depend on s)
-//   cand_groups    one wavefront per 64 tiles: sums of the tile partials
+//                  weight sums of the flagged words (unskewed, so they do not depend on s); the
+//                  last tile of each group of 64 adds up its group (it waits for the other
+//                  tiles' flags)
 //   cand_emit      per tile: prefix = group sums before my group + tile sums before me in my
 //                  group (plain loads: the producers are earlier kernels); the skew multiplier is
 //                  fixed by the caller, or taken from the grand totals by the rule of Theorem 1
@@ -21,91 +24,105 @@
 //                  the stats
 #include <math.h>
 #include "common.hpp"
+#include "lookback.hpp"
 
 namespace csgs {
 
-constexpr int RP_ITEMS = 8;  // rows per thread and round in row_prefix
+constexpr int RP_ITEMS = 4;                  // rows per thread in row_prefix
+constexpr int RP_TILE = ROW_TILE;           // rows per block
+static_assert(RP_TILE == 256 * RP_ITEMS, "row tile");
 
-__global__ __launch_bounds__(1024) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
-                                                   const int32_t *__restrict__ S, int32_t nS_bound,
-                                                   const int32_t *__restrict__ nS_dev, int32_t shift_base,
-                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
-                                                   int32_t *__restrict__ meta, int64_t edge_cap,
-                                                   csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status)
+// Tile t = rows [t * RP_TILE, ...): degrees fetched striped (coalesced, all loads independent), handed
+// through LDS to a blocked arrangement, block scan, offset of the tile by the single-pass scan
+// across blocks.  One tile per block, grid = tiles of the row capacity; with a device-side count
+// the blocks past it leave at once.
+__global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
+                                                  const int32_t *__restrict__ S, int32_t nS_bound,
+                                                  const int32_t *__restrict__ nS_dev, int32_t shift_base,
+                                                  unsigned long long tag, uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
+                                                  int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
+                                                  int64_t *__restrict__ meta, int64_t edge_cap,
+                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status)
 {
     __shared__ int64_t lds[17];
-    __shared__ int32_t s_deg[1024 * RP_ITEMS];
+    __shared__ int32_t s_deg[RP_TILE];
+    __shared__ unsigned long long s_lb[1];
+    const TileState<1> ts(ts_mem, ts_tiles);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
+    int64_t n_tiles = ((int64_t)nS + RP_TILE - 1) / RP_TILE;
+    if (n_tiles < 1) n_tiles = 1;   // an empty row set still gets its end markers written
+    const int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    const int32_t r0 = (int32_t)(t * RP_TILE);
     bool bad = false;
-    int64_t base = 0;
-    // rounds of 8192 rows: degrees are fetched striped (coalesced, all loads independent), handed
-    // through LDS to a blocked arrangement, and scanned with one block scan per round
-    for (int32_t r0 = 0; r0 < nS; r0 += 1024 * RP_ITEMS) {
-        __syncthreads();
 #pragma unroll
-        for (int k = 0; k < RP_ITEMS; ++k) {
-            const int32_t a = r0 + k * 1024 + (int32_t)threadIdx.x;
-            int64_t deg = 0, beg = 0;
-            if (a < nS) {
-                const int32_t i = S[a];
-                if (i >= 0 && i < n_nodes) {
-                    beg = rowptr[i];
-                    deg = rowptr[i + 1] - beg;
-                    if (deg < 0 || deg > 0x7FFFFFFFll) deg = 0;
-                } else {
-                    bad = true;
-                }
-                rowstart[a] = beg;
+    for (int k = 0; k < RP_ITEMS; ++k) {
+        const int32_t a = r0 + k * 256 + (int32_t)threadIdx.x;
+        int64_t deg = 0, beg = 0;
+        if (a < nS) {
+            const int32_t i = S[a];
+            if (i >= 0 && i < n_nodes) {
+                beg = rowptr[i];
+                deg = rowptr[i + 1] - beg;
+                if (deg < 0 || deg > 0x7FFFFFFFll) deg = 0;
+            } else {
+                bad = true;
             }
-            s_deg[k * 1024 + threadIdx.x] = (int32_t)deg;
+            rowstart[a] = beg;
         }
-        __syncthreads();
-        int32_t d[RP_ITEMS];
-        int64_t sum = 0;
+        s_deg[k * 256 + threadIdx.x] = (int32_t)deg;
+    }
+    __syncthreads();
+    int32_t d[RP_ITEMS];
+    int64_t sum = 0;
 #pragma unroll
-        for (int k = 0; k < RP_ITEMS; ++k) {
-            d[k] = s_deg[threadIdx.x * RP_ITEMS + k];
-            sum += d[k];
-        }
-        int64_t total;
-        int64_t ex = base + block_exclusive_scan<int64_t>(sum, lds, &total);
+    for (int k = 0; k < RP_ITEMS; ++k) {
+        d[k] = s_deg[threadIdx.x * RP_ITEMS + k];
+        sum += d[k];
+    }
+    int64_t tile_total;
+    int64_t ex = block_exclusive_scan<int64_t>(sum, lds, &tile_total);
+    unsigned long long local[1] = {(unsigned long long)tile_total}, excl[1];
+    lookback_publish<1>(ts, tag, t, local);
+    lookback_resolve<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);
+    ex += (int64_t)excl[0];
 #pragma unroll
-        for (int k = 0; k < RP_ITEMS; ++k) {
-            const int32_t a = r0 + (int32_t)threadIdx.x * RP_ITEMS + k;
-            if (a < nS) eoff[a] = ex;
-            ex += d[k];
-        }
-        base += total;
+    for (int k = 0; k < RP_ITEMS; ++k) {
+        const int32_t a = r0 + (int32_t)threadIdx.x * RP_ITEMS + k;
+        if (a < nS) eoff[a] = ex;
+        ex += d[k];
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);
-    if (threadIdx.x == 0) {
-        if (stats) stats->edges_scanned = base;
+    if (t == n_tiles - 1 && threadIdx.x == 0) {
+        int64_t total = (int64_t)excl[0] + tile_total;
+        if (stats) stats->edges_scanned = total;
         // an edge count the workspace cannot hold is reported and treated as empty
-        if (base > edge_cap) {
+        if (total > edge_cap) {
             atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
-            base = 0;
+            total = 0;
         }
-        eoff[nS] = base;
+        eoff[nS] = total;
         // fraction bits for this many rows: the sum of nS weights must stay below 2^61 / (s_fx rmax)
         int32_t lg = 0;
         while (lg < 31 && (1ll << lg) < (int64_t)nS) ++lg;
         const int32_t shift = shift_base - lg;
         meta[META_ROWS] = nS;
         meta[META_SHIFT] = shift > 52 ? 52 : shift;
+        meta[META_EDGES] = total;
     }
 }
 
 __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                  int64_t n_nodes, const int32_t *__restrict__ meta,
+                                                  int64_t n_nodes, const int64_t *__restrict__ meta,
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
                                                   int32_t *__restrict__ status)
 {
     __shared__ RowSlice slice;
-    const int32_t nS = meta[META_ROWS];
-    const double scale = ldexp(1.0, meta[META_SHIFT]);
-    const int64_t E = eoff[nS];
+    const int32_t nS = (int32_t)meta[META_ROWS];
+    const double scale = ldexp(1.0, (int)meta[META_SHIFT]);
+    const int64_t E = meta[META_EDGES];
     bool bad = false;
     for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
@@ -166,18 +183,24 @@ __device__ inline void resolve_skew(const SkewPolicy &pol, uint64_t n_cand, uint
 
 constexpr int CAND_WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
 
+// Tile sums, and -- by the last tile of every group of 64 -- the group's sums.  That tile waits
+// for the flags of the (at most 63) lower tiles of its group, which were dispatched before it
+// (one tile per block, ascending block ids) and wait for nobody, so the wait ends.
 __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
                                                      const uint8_t *__restrict__ tileflag, int64_t n_words,
-                                                     int64_t n_nodes, int32_t lo, int32_t hi,
-                                                     uint64_t *__restrict__ partial)
+                                                     int64_t n_nodes, int64_t n_tiles, int32_t lo, int32_t hi,
+                                                     unsigned long long tag, unsigned long long *__restrict__ cand_flag,
+                                                     unsigned long long *__restrict__ partial,
+                                                     uint64_t *__restrict__ gtot, int32_t *__restrict__ status)
 {
     __shared__ uint64_t lds[4][3];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
+    const int64_t t = blockIdx.x;
     uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t word_idx = (int64_t)blockIdx.x * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
+        const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
         if (word_idx >= n_words || tileflag[word_idx] == 0) continue;
         const int64_t id = word_idx * 64 + lane;
         const uint64_t w = id < n_nodes ? wtable[id] : 0ull;
@@ -190,29 +213,31 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
     cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
     if (lane == 0) { lds[wave][0] = cn; lds[wave][1] = wl; lds[wave][2] = wr; }
     __syncthreads();
-    if (threadIdx.x < 3)  // packed count halves cannot carry: each is at most 1024 per tile
-        partial[(int64_t)blockIdx.x * 4 + threadIdx.x] = lds[0][threadIdx.x] + lds[1][threadIdx.x] + lds[2][threadIdx.x] + lds[3][threadIdx.x];
-}
-
-__global__ __launch_bounds__(64) void cand_groups(const uint64_t *__restrict__ partial, int64_t n_tiles,
-                                                  uint64_t *__restrict__ gtot)
-{
-    const int64_t t = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    uint64_t v[3] = {0, 0, 0};
-    if (t < n_tiles) {
+    if (wave != 0) return;
+    // packed count halves cannot carry: each is at most 1024 per tile
+    const unsigned long long mine = lane < 3 ? lds[0][lane] + lds[1][lane] + lds[2][lane] + lds[3][lane] : 0ull;
+    if (lane < 3) st_relaxed(&partial[t * 4 + lane], mine);
+    if (lane == 0) st_flag(&cand_flag[t], tag);   // after the wavefront's value stores have been acknowledged
+    const int r = (int)(t % LB_GROUP);
+    if (r != LB_GROUP - 1 && t != n_tiles - 1) return;
+    const int64_t g = t / LB_GROUP;
+    bool ok = true;
+    if (lane < r) ok = wait_tag(&cand_flag[g * LB_GROUP + lane], tag);
+    unsigned long long sum[3];
 #pragma unroll
-        for (int i = 0; i < 3; ++i) v[i] = partial[t * 4 + i];
+    for (int i = 0; i < 3; ++i) {
+        const unsigned long long own = __shfl(mine, i, WAVE);
+        sum[i] = own + wave_sum((lane < r && ok) ? ld_relaxed(&partial[(g * LB_GROUP + lane) * 4 + i]) : 0ull);
     }
-#pragma unroll
-    for (int i = 0; i < 3; ++i) v[i] = wave_sum(v[i]);
-    if (threadIdx.x < 3) gtot[(int64_t)blockIdx.x * 4 + threadIdx.x] = v[threadIdx.x];
+    if (__ballot(!ok) && lane == 0) atomicOr(status, CSGS_ST_INTERNAL);
+    if (lane < 3) gtot[g * 4 + lane] = lane == 0 ? sum[0] : (lane == 1 ? sum[1] : sum[2]);
 }
 
 __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
                                                  int32_t hi, SkewPolicy pol, const uint64_t *__restrict__ partial,
                                                  const uint64_t *__restrict__ gtot,
-                                                 const int32_t *__restrict__ meta, csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
+                                                 const int64_t *__restrict__ meta, csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
                                                  uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
 {
@@ -223,22 +248,46 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     const int wave = (int)(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;
     const int64_t g = t / 64, n_groups = (n_tiles + 63) / 64;
+    // Loads are issued in the order flags, prefix inputs, accumulators, and consumed only after
+    // all are in flight, so the tile's own data travels while the prefix is being summed.
+    bool flagged[CAND_WORDS / 4];
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
+        flagged[k] = word_idx < n_words && tileflag[word_idx] != 0;
+    }
     // sums over everything (tot) and over what lies before this tile (pre): group sums before my
     // group, then tile sums before me inside my group
-    uint64_t tot[3] = {0, 0, 0}, pre[3] = {0, 0, 0};
-    for (int64_t j = threadIdx.x; j < n_groups; j += blockDim.x) {
+    uint64_t gv[3] = {0, 0, 0}, pv[3] = {0, 0, 0};
+    if ((int64_t)threadIdx.x < n_groups) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const uint64_t v = gtot[j * 4 + i];
-            tot[i] += v;
-            if (j < g) pre[i] += v;
-        }
+        for (int i = 0; i < 3; ++i) gv[i] = gtot[(int64_t)threadIdx.x * 4 + i];
     }
     {
         const int64_t j = g * 64 + threadIdx.x;
         if (threadIdx.x < 64 && j < t) {
 #pragma unroll
-            for (int i = 0; i < 3; ++i) pre[i] += partial[j * 4 + i];
+            for (int i = 0; i < 3; ++i) pv[i] = partial[j * 4 + i];
+        }
+    }
+    uint64_t w[CAND_WORDS / 4];
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
+        w[k] = (flagged[k] && id < n_nodes) ? wtable[id] : 0ull;
+    }
+    uint64_t tot[3], pre[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        tot[i] = gv[i];
+        pre[i] = ((int64_t)threadIdx.x < g ? gv[i] : 0ull) + pv[i];
+    }
+    for (int64_t j = (int64_t)threadIdx.x + blockDim.x; j < n_groups; j += blockDim.x) {  // more than 256 groups
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint64_t v = gtot[j * 4 + i];
+            tot[i] += v;
+            if (j < g) pre[i] += v;
         }
     }
 #pragma unroll
@@ -259,21 +308,20 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     const uint64_t total_w = tot[1] * m_local + tot[2] * m_remote;
     const double total_d = (double)total_w;
 
-    uint64_t words[CAND_WORDS / 4], w[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
+    uint64_t words[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
+        const bool local = id >= lo && id < hi;
+        wsk_incl[k] = w[k] * (local ? m_local : m_remote);
+        words[k] = __ballot(w[k] != 0);
+    }
+    wave_inclusive_scan_multi(wsk_incl);
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int slot = wave * (CAND_WORDS / 4) + k;
-        const int64_t word_idx = t * CAND_WORDS + slot;
-        const bool flagged = word_idx < n_words && tileflag[word_idx] != 0;
-        const int64_t id = word_idx * 64 + lane;
-        const uint64_t wv = (flagged && id < n_nodes) ? wtable[id] : 0ull;
-        const bool local = id >= lo && id < hi;
-        const uint64_t wsk = wv * (local ? m_local : m_remote);
-        words[k] = __ballot(wv != 0);
-        w[k] = wv;
-        wsk_incl[k] = wave_inclusive_scan(wsk);
         if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
-        if (flagged && lane == 0) tileflag[word_idx] = 0;  // back to the clean state
+        if (flagged[k] && lane == 0) tileflag[t * CAND_WORDS + slot] = 0;  // back to the clean state
     }
     __syncthreads();
     uint64_t base_cnt = pre[0] >> 32;
@@ -309,7 +357,7 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
         stats->w_local = tot[1];
         stats->w_remote = tot[2];
         stats->total = total_w;
-        stats->shift = meta[META_SHIFT];
+        stats->shift = (int32_t)meta[META_SHIFT];
         stats->skew_fx = (int32_t)m_local * (m_remote ? 1 : -1);
         int32_t st = 0;
         if (n_cand == 0 || total_w == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
@@ -343,11 +391,13 @@ static int shift_base_for(int64_t s_fx, float rownorm2_max)
 }  // namespace csgs
 
 int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                            int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status,
-                            hipStream_t st)
+                            int32_t shift_base, const Workspace &w, csgs_workspace *ws, csgs_prob_stats *stats,
+                            int32_t *status, hipStream_t st)
 {
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(1), dim3(1024), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, w.eoff,
-                w.rowstart, w.meta, w.chunk_cap * EDGE_TILE, stats, status);
+    const unsigned tiles = (unsigned)(((int64_t)nS + RP_TILE - 1) / RP_TILE);
+    const unsigned long long tag = ++ws->epoch;
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, tag,
+                w.rp_ts, w.rp_tiles, w.eoff, w.rowstart, w.meta, w.chunk_cap * EDGE_TILE, stats, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -415,19 +465,18 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int64_t n_words = (g->n_nodes + 63) / 64;
-    const unsigned n_groups = (unsigned)((w.n_tiles + 63) / 64);
 
     // the shift for nS rows has passed the range check; fewer rows on the device only widen it
     const int32_t shift_base = shift_base_for(s_fx, g->rownorm2_max);
-    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
+    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, ws, stats, status, st);
     if (rc != CSGS_OK) return rc;
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, w.meta, w.eoff,
                 w.rowstart, w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
+    const unsigned long long cand_tag = ++ws->epoch;
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, g->local_lo, g->local_hi, w.partial);
-    CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_GROUPS, cand_groups, dim3(n_groups), dim3(64), st, w.partial, w.n_tiles, w.gtot);
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, cand_tag, (unsigned long long *)w.cand_flag,
+                (unsigned long long *)w.partial, w.gtot, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, w.meta, stats, status, cand_id,

@@ -19,7 +19,7 @@ static size_t g_used = 0;
 static bool g_open = false;
 static const size_t kMaxPairs = 1 << 16;
 
-static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_groups", "cand_emit", "draw", "hits_fused",
+static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "fill_zero", "copy"};
 

@@ -6,7 +6,7 @@ namespace csgs {
 namespace prof {
 
 enum Kid {
-    K_ROW_PREFIX = 0, K_SCAN_EDGES, K_CAND_PARTIALS, K_CAND_GROUPS, K_CAND_EMIT, K_DRAW, K_HITS_FUSED, K_ADJ_FUSED, K_REMOTE_COUNT,
+    K_ROW_PREFIX = 0, K_SCAN_EDGES, K_CAND_PARTIALS, K_CAND_EMIT, K_DRAW, K_HITS_FUSED, K_ADJ_FUSED, K_REMOTE_COUNT,
     K_AGGREGATE, K_GEMM, K_GATHER_ROWS, K_FILL_ZERO, K_COPY, K_COUNT
 };
 

@@ -151,14 +151,42 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
             s_list[ex++] = (uint16_t)(threadIdx.x * 64 + bit);
         }
         unsigned long long local[1] = {tile_total}, excl[1];
-        lookback<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);   // its barriers also publish s_list
-        // one thread per distinct hit
-        for (uint32_t i = threadIdx.x; i < tile_total; i += blockDim.x) {
+        lookback_publish<1>(ts, tag, t, local);
+        __syncthreads();  // s_list complete
+        // One thread per distinct hit.  Everything except the output position is ready before the
+        // prefix is: fetch and compute it now.  The tile's first hits go to the last threads, so
+        // that the arithmetic runs in other wavefronts than the one that does the hops.
+        const uint32_t i0 = (uint32_t)(blockDim.x - 1 - threadIdx.x);
+        int64_t kpos0 = 0;
+        uint32_t m0 = 0;
+        int32_t id0 = -1;
+        double pk0 = 0.0;
+        if (i0 < tile_total) {
+            kpos0 = t * (HIT_TILE_WORDS * 64) + s_list[i0];
+            m0 = hit[kpos0];
+            hit[kpos0] = 0u;
+            const uint64_t wk = cdf[kpos0] - (kpos0 ? cdf[kpos0 - 1] : 0ull);
+            const double qk = (double)wk / total;
+            pk0 = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
+            id0 = cand_id[kpos0];
+        }
+        lookback_resolve<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);
+        if (i0 < tile_total) {
+            const uint64_t pos = excl[0] + i0;
+            if (pos < (uint64_t)B) {  // at most B distinct hits exist; the guard keeps stores in bounds regardless
+                S_next[pos] = id0;
+                mult[pos] = (int32_t)m0;
+                p_incl[pos] = (float)pk0;
+                pdbl[pos] = pk0;
+                if (id0 >= 0 && id0 < n_nodes) rank[id0] = rank_tag | (pos + 1);
+            }
+        }
+        for (uint32_t i = blockDim.x + threadIdx.x; i < tile_total; i += blockDim.x) {  // crowded tiles
             const int64_t kpos = t * (HIT_TILE_WORDS * 64) + s_list[i];
             const uint64_t pos = excl[0] + i;
             const uint32_t m = hit[kpos];
             hit[kpos] = 0u;
-            if (pos < (uint64_t)B) {  // at most B distinct hits exist; the guard keeps stores in bounds regardless
+            if (pos < (uint64_t)B) {
                 const uint64_t wk = cdf[kpos] - (kpos ? cdf[kpos - 1] : 0ull);
                 const double qk = (double)wk / total;
                 const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
@@ -186,7 +214,7 @@ __device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, 
 }
 
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                 int64_t n_nodes, const int32_t *__restrict__ meta,
+                                                 int64_t n_nodes, const int64_t *__restrict__ meta,
                                                  const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
                                                  const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
@@ -204,8 +232,8 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     const int wave = (int)(threadIdx.x >> 6);
     const TileState<1> ts(ts_mem, chunk_cap);
     const uint64_t rank_tag = (hits_tag & 0xFFFFFFFFull) << 32;
-    const int32_t nS = meta[META_ROWS];
-    int64_t E = eoff[nS];
+    const int32_t nS = (int32_t)meta[META_ROWS];
+    int64_t E = meta[META_EDGES];
     int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
     bool overflow = false;
     if (n_chunks > chunk_cap) {  // the workspace cannot describe this many chunks: report, emit nothing
@@ -255,7 +283,12 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         __syncthreads();
         const int32_t tile_cnt = s_pre[EDGE_TILE / 64];
         unsigned long long local[1] = {(unsigned long long)tile_cnt}, excl[1];
-        lookback<1>(ts, tag, t, n_chunks, local, excl, s_lb, status);
+        lookback_publish<1>(ts, tag, t, local);
+        // values of the kept edges do not depend on the prefix: fetch and divide while it is resolved
+        float pv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) pv[k] = rk[k] > 0 ? (float)((double)val[ea[k]] / pdbl[rk[k] - 1]) : 0.f;
+        lookback_resolve<1>(ts, tag, t, n_chunks, local, excl, s_lb, status);
         const int64_t base = (int64_t)excl[0];
         // row pointers of the rows that start inside this chunk: kept edges before the row start
         const int32_t R = slice.R;
@@ -275,7 +308,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                 const int64_t pos = base + s_pre[word] + __popcll(s_mask[word] & ((1ull << lane) - 1ull));
                 if (pos < adj_cap) {
                     adj_col[pos] = rk[k] - 1;
-                    adj_val[pos] = (float)((double)val[ea[k]] / pdbl[rk[k] - 1]);
+                    adj_val[pos] = pv[k];
                 }
             }
         }
@@ -389,7 +422,7 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (!reuse_offsets) {
-        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
+        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, ws, nullptr, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
     const unsigned long long adj_tag = ++ws->epoch;

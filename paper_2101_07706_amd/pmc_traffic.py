@@ -21,7 +21,7 @@ CALIB_BYTES = 512 * 2 ** 20
 
 NAMES = [("aggregate_k", "aggregate"), ("gemm_f32_k", "layer_gemm"), ("gather_rows_k", "gather_rows"),
          ("remote_count_k", "remote_count"), ("csgs::scan_edges", "scan_edges"), ("csgs::cand_partials", "cand_partials"),
-         ("csgs::cand_groups", "cand_groups"), ("csgs::cand_emit", "cand_emit"),
+         ("csgs::cand_emit", "cand_emit"),
          ("csgs::row_prefix", "row_prefix"), ("csgs::draw", "draw"), ("csgs::hits_fused", "hits_fused"),
          ("csgs::adj_fused", "adj_fused"), ("csgs::copy_k", "copy")]
 
