@@ -146,41 +146,67 @@ __device__ inline int32_t resolve_count(int32_t n, const int32_t *__restrict__ n
 // ---------------------------------------------------------------- wave helpers
 __device__ inline int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
 
-template <typename T>
-__device__ inline T wave_sum(T v)
+// Lane exchanges of the wave-wide scan run on the data-parallel-primitive path of the vector ALU
+// (no LDS round trip): shifts by 1, 2, 4, 8 inside each row of 16 lanes with zero fill, then lane
+// 15 of a row broadcast to the next row (rows 1 and 3), then lane 31 to rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ inline uint32_t dpp_move(uint32_t v)
 {
-#pragma unroll
-    for (int off = WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
-    return v;
+    // old = 0: lanes outside ROW_MASK, and lanes whose source falls outside the row, receive 0
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+
+template <typename T, int CTRL, int ROW_MASK>
+__device__ inline T dpp_move_t(T v)
+{
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit integers");
+    if (sizeof(T) == 4) return (T)dpp_move<CTRL, ROW_MASK>((uint32_t)v);
+    const uint64_t x = (uint64_t)v;
+    const uint32_t lo = dpp_move<CTRL, ROW_MASK>((uint32_t)x), hi = dpp_move<CTRL, ROW_MASK>((uint32_t)(x >> 32));
+    return (T)(((uint64_t)hi << 32) | lo);
 }
 
 template <typename T>
 __device__ inline T wave_inclusive_scan(T v)
 {
-    const int lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-        T t = __shfl_up(v, off, WAVE);
-        if (lane >= off) v += t;
-    }
+    v += dpp_move_t<T, 0x111, 0xF>(v);  // row_shr:1
+    v += dpp_move_t<T, 0x112, 0xF>(v);  // row_shr:2
+    v += dpp_move_t<T, 0x114, 0xF>(v);  // row_shr:4
+    v += dpp_move_t<T, 0x118, 0xF>(v);  // row_shr:8
+    v += dpp_move_t<T, 0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_move_t<T, 0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
     return v;
 }
 
-// K independent inclusive scans at once: the lane exchanges of the K chains are interleaved, so
-// their latencies overlap instead of adding up.
+// Sum over the wavefront, the same value in every lane.
+template <typename T>
+__device__ inline T wave_sum(T v)
+{
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit integers");
+    const T s = wave_inclusive_scan(v);
+    if (sizeof(T) == 4) return (T)__builtin_amdgcn_readlane((int)s, WAVE - 1);
+    const uint64_t x = (uint64_t)s;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, WAVE - 1);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), WAVE - 1);
+    return (T)(((uint64_t)hi << 32) | lo);
+}
+
+// K independent inclusive scans; written step by step across the chains so that they interleave.
 template <typename T, int K>
 __device__ inline void wave_inclusive_scan_multi(T (&v)[K])
 {
-    const int lane = lane_id();
 #pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-        T t[K];
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x111, 0xF>(v[k]);
 #pragma unroll
-        for (int k = 0; k < K; ++k) t[k] = __shfl_up(v[k], off, WAVE);
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x112, 0xF>(v[k]);
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            if (lane >= off) v[k] += t[k];
-    }
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x114, 0xF>(v[k]);
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x118, 0xF>(v[k]);
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x142, 0xA>(v[k]);
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x143, 0xC>(v[k]);
 }
 
 // Exclusive scan over the threads of a block (blockDim.x a multiple of 64, at most 1024).
