@@ -281,11 +281,12 @@ int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev
 
 /*
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the
- * library is bracketed by two HIP events on its stream.  csgs_profile_collect, called after the
- * caller has synchronised, fills ms_sum[k] / launches[k] (host arrays of
- * csgs_profile_kernel_count() entries) with the summed elapsed milliseconds and the number of
- * launches per kernel since the last collect, and resets.  Process-wide, not thread-safe;
- * creates HIP events on first use, so it is not for callers that may not allocate.
+ * library carries two HIP events that the runtime stamps with the start and the end of that
+ * dispatch.  csgs_profile_collect, called after the caller has synchronised, fills ms_sum[k] /
+ * launches[k] (host arrays of csgs_profile_kernel_count() entries) with the summed kernel
+ * durations in milliseconds and the number of launches per kernel since the last collect, and
+ * resets.  Process-wide, not thread-safe; creates HIP events on first use, so it is not for
+ * callers that may not allocate.
  */
 int csgs_profile_enable(int on);
 int csgs_profile_kernel_count(void);

@@ -1,6 +1,8 @@
-// Per-kernel timing: every launch made while timing is enabled is bracketed by a pair of HIP
-// events on the launch stream; csgs_profile_collect() (after the caller synchronised) sums the
-// elapsed times per kernel.  Process-wide state, one thread at a time.
+// Per-kernel timing: every launch made while timing is enabled carries a pair of HIP events that
+// the runtime stamps with the start and the end of that very dispatch (hipExtLaunchKernelGGL), so
+// the elapsed time is the kernel's own duration as the command processor sees it, without the
+// cost of separate event packets; csgs_profile_collect() (after the caller synchronised) sums
+// the elapsed times per kernel.  Process-wide state, one thread at a time.
 #include <vector>
 #include "common.hpp"
 #include "profile.hpp"
@@ -16,31 +18,26 @@ struct Pair {
 };
 static std::vector<Pair> g_pool;   // created once, reused
 static size_t g_used = 0;
-static bool g_open = false;
 static const size_t kMaxPairs = 1 << 16;
 
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "fill_zero", "copy"};
 
-void record(int kid, hipStream_t st, bool start)
+bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {
-    if (start) {
-        g_open = false;
-        if (g_used >= kMaxPairs) return;
-        if (g_used == g_pool.size()) {
-            Pair p;
-            if (hipEventCreate(&p.a) != hipSuccess) return;
-            if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return; }
-            g_pool.push_back(p);
-        }
-        g_pool[g_used].kid = kid;
-        if (hipEventRecord(g_pool[g_used].a, st) == hipSuccess) g_open = true;
-    } else if (g_open) {
-        (void)hipEventRecord(g_pool[g_used].b, st);
-        ++g_used;
-        g_open = false;
+    if (g_used >= kMaxPairs) return false;
+    if (g_used == g_pool.size()) {
+        Pair p;
+        if (hipEventCreate(&p.a) != hipSuccess) return false;
+        if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return false; }
+        g_pool.push_back(p);
     }
+    g_pool[g_used].kid = kid;
+    *start = g_pool[g_used].a;
+    *stop = g_pool[g_used].b;
+    ++g_used;
+    return true;
 }
 
 }  // namespace prof

@@ -1,6 +1,7 @@
 // Optional per-kernel timing with HIP events (off by default; a measuring aid for benchmarks).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 namespace csgs {
 namespace prof {
@@ -11,21 +12,19 @@ enum Kid {
 };
 
 extern bool g_enabled;
-void record(int kid, hipStream_t st, bool start);
-
-struct Scope {
-    int kid;
-    hipStream_t st;
-    Scope(int k, hipStream_t s) : kid(k), st(s) { if (g_enabled) record(kid, st, true); }
-    ~Scope() { if (g_enabled) record(kid, st, false); }
-};
+// Hands out the next pooled event pair for a launch of kernel `kid`; false when none is available.
+bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop);
 
 }  // namespace prof
 }  // namespace csgs
 
-// Launch `kernel` on `stream`; when timing is enabled the launch is bracketed by two events.
-#define CSGS_LAUNCH(kid, kernel, grid, block, stream, ...)                     \
-    do {                                                                       \
-        ::csgs::prof::Scope scope_(::csgs::prof::kid, stream);                 \
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);       \
+// Launch `kernel` on `stream`; when timing is enabled the dispatch is stamped with two events.
+#define CSGS_LAUNCH(kid, kernel, grid, block, stream, ...)                                          \
+    do {                                                                                            \
+        hipEvent_t ev0_ = nullptr, ev1_ = nullptr;                                                  \
+        if (::csgs::prof::g_enabled && !::csgs::prof::next_pair(::csgs::prof::kid, &ev0_, &ev1_)) { \
+            ev0_ = nullptr;                                                                         \
+            ev1_ = nullptr;                                                                         \
+        }                                                                                           \
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev0_, ev1_, 0, __VA_ARGS__);          \
     } while (0)
