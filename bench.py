@@ -51,7 +51,7 @@ def algorithmic_bytes(s, N):
 
 
 class Workload:
-    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs):
+    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1):
         self.cfg, self.g, self.dg, self.Xd, self.dev = cfg, g, dg, Xd, dev
         self.torch, self.pipeline, self.csgs = torch, pipeline, csgs
         self.bf16 = cfg.feat_dtype == "bf16"
@@ -66,35 +66,101 @@ class Workload:
         self.Sd = [torch.from_numpy(b).to(dev) for b in self.batches]
         M, B, dims = self.M, self.B, self.dims
         nS_max = max(len(self.batches[0]), B)
-        self.ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
+        self.n_samplers = n_samplers
+        self.wss = [pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev) for _ in range(n_samplers)]   # one per sampling stream
+        self.ws = self.wss[0]
         adj_cap = int(min(g.nnz, 48_000_000))
-        self.lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
+        # sets of sampling outputs: while the layers of one batch are computed from one set, later batches
+        # are sampled into the others
+        self.n_sets = 2 * n_samplers
+        self.lb_sets = [[pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
+                        for _ in range(self.n_sets)]
+        self.lbs = self.lb_sets[0]
+        self.overlap = None
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
         self.elt = 2 if self.bf16 else 4
         self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
 
-    def step(self, it, sizes=None):
-        """One whole mini-batch, enqueued without the host waiting for anything: each layer's row
-        count stays on the device (the n_dev arguments), launches are sized for the capacities."""
-        cfg, M, B, lbs, pipeline = self.cfg, self.M, self.B, self.lbs, self.pipeline
-        S0 = self.Sd[it]
+    def enqueue(self, S0, it, lbs, ws, s_samp=None, s_comp=None, between=None):
+        """The library calls of one mini-batch: sampling top-down on s_samp, then (after `between`, which
+        ties the two streams) staging of the remote rows and the layer compute bottom-up on s_comp."""
+        cfg, M, B, pipeline = self.cfg, self.M, self.B, self.pipeline
         n0 = S0.numel()
         for l in range(M):
             S = S0 if l == 0 else lbs[l - 1].S_next
-            pipeline.sample_step(self.dg, self.ws, S, cfg.skew, B, self.seed, it, l, lbs[l], want_q=False,
-                                 nS_dev=None if l == 0 else lbs[l - 1].n_next)
-        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.staged)      # stands in for the exchange of remote rows
+            pipeline.sample_step(self.dg, ws, S, cfg.skew, B, self.seed, it, l, lbs[l], want_q=False,
+                                 nS_dev=None if l == 0 else lbs[l - 1].n_next, stream=s_samp)
+        if between:
+            between()
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.staged, stream=s_comp)   # stands in for the exchange of remote rows
         H = None
         for l in range(M - 1, -1, -1):
             nS = n0 if l == 0 else B
             nS_dev = None if l == 0 else lbs[l - 1].n_next
             Z, Hn = self.Zs[l][:nS], self.Hs[l][:nS]
             if l == M - 1:
-                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev)
+                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev,
+                                      stream=s_comp)
             else:
-                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev)
+                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev,
+                                      stream=s_comp)
             H = Hn
+        return H
+
+    def prepare_overlap(self):
+        """Streams, events and, per buffer set, the step's calls with their arguments marshalled once
+        (csgs.Plan); the batch pointer and the iteration number are boxes filled in per step."""
+        import ctypes as C
+        torch, csgs = self.torch, self.csgs
+        samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
+        s_comp = torch.cuda.Stream()
+        sets = []
+        for k in range(self.n_sets):
+            S0 = csgs.DevicePtr(self.Sd[0].numel())
+            it = C.c_uint64(0)
+            marks = []
+            with csgs.record() as plan:
+                H = self.enqueue(S0, it, self.lb_sets[k], self.wss[k % self.n_samplers], samplers[k % self.n_samplers], s_comp,
+                                 between=lambda: marks.append(len(plan.calls)))
+            sample, compute = csgs.Plan(), csgs.Plan()
+            sample.calls, compute.calls = plan.calls[:marks[0]], plan.calls[marks[0]:]
+            sets.append(dict(S0=S0, it=it, sample=sample, compute=compute, H=H, s_samp=samplers[k % self.n_samplers],
+                             samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
+        self.overlap = dict(sets=sets, s_comp=s_comp)
+
+    def step(self, it, sizes=None, overlap=False):
+        """One whole mini-batch, enqueued without the host waiting for anything: each layer's row
+        count stays on the device (the n_dev arguments), launches are sized for the capacities.
+        overlap: the sampling (top-down) of consecutive batches goes round-robin to n_samplers streams,
+        each with its own workspace, and the layer compute (bottom-up) of all batches, in batch order,
+        to one more stream; events tie a batch's compute to its sampling and a buffer set's reuse to
+        the compute that read it.  This is how a training loop runs its sampler ahead: sampling
+        does not depend on the model weights, the compute of consecutive batches does.  Every step
+        still does all of its work."""
+        M, B = self.M, self.B
+        n0 = self.Sd[it].numel()
+        if overlap:
+            if self.overlap is None:
+                self.prepare_overlap()
+            st = self.overlap["sets"][it % self.n_sets]
+            s_comp = self.overlap["s_comp"]
+            lbs = self.lb_sets[it % self.n_sets]
+            st["S0"].value = self.Sd[it].data_ptr()
+            st["it"].value = it
+            if st["used"]:
+                st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batch sampled into it was computed
+            st["sample"].run()
+            st["samp_done"].record(st["s_samp"])
+            s_comp.wait_event(st["samp_done"])
+            st["compute"].run()
+            st["comp_done"].record(s_comp)
+            st["used"] = True
+            H = st["H"]
+        else:
+            lbs = self.lb_sets[0]
+            H = self.enqueue(self.Sd[it], it, lbs, self.wss[0])
+        self.lbs = lbs
         if sizes is not None:
             self.torch.cuda.synchronize()
             for l in range(M):
@@ -113,13 +179,26 @@ class Workload:
         for it in range(warmup):
             self.step(it)
         torch.cuda.synchronize()
+        # (1) one stream, steps back to back: the latency of a step
         t0 = time.perf_counter()
         for it in range(warmup, warmup + steps):
-            self.step(it)
+            H = self.step(it)
+        torch.cuda.synchronize()
+        serial_ms = (time.perf_counter() - t0) / steps * 1e3
+        h_serial = H.clone()
+        # (2) the timed region proper: same steps, sampling and compute on two streams
+        for it in range(warmup):
+            self.step(it, overlap=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(warmup, warmup + steps):
+            H = self.step(it, overlap=True)
         enqueue_ms = (time.perf_counter() - t0) / steps * 1e3     # host time to enqueue a step (no waiting in it)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
-        log(f"host enqueue {enqueue_ms:.3f} ms/step, wall {ms_per_step:.3f} ms/step")
+        assert torch.equal(H, h_serial), "overlapped steps must give the serial result bit for bit"
+        log(f"host enqueue {enqueue_ms:.3f} ms/step; one stream {serial_ms:.3f} ms/step; sampling and compute overlapped "
+            f"{ms_per_step:.3f} ms/step")
         sizes = []
         csgs.csgs_profile_enable(True)
         for it in range(warmup, warmup + steps):
@@ -149,7 +228,7 @@ class Workload:
         tot = lambda key: sum(s[key] for s in sizes) / steps
         per_step = dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
                         sampled_edges=tot("nnz"), remote_nodes=tot("remote"))
-        return dict(ms_per_step=ms_per_step, kernels=kernels, per_step=per_step, sizes=sizes,
+        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, kernels=kernels, per_step=per_step, sizes=sizes,
                     aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
 
 
@@ -181,6 +260,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
+    ap.add_argument("--samplers", type=int, default=2, help="sampling streams (batches sampled side by side)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     args = ap.parse_args()
@@ -208,7 +288,7 @@ def main():
     dg = pipeline.DeviceGraph(g, dev)
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
-    mk = lambda c, nb: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs)
+    mk = lambda c, nb: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers)
 
     # copy-kernel yardstick (also the known-size kernel for calibrating byte counters)
     cbytes = 512 * 2 ** 20
@@ -265,7 +345,7 @@ def main():
         tr = load_traffic(f"{cfg.name}_x{sc}")
         shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_emit")
         scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
-                      ms_per_step=rs["ms_per_step"],
+                      ms_per_step=rs["ms_per_step"], one_stream_ms_per_step=rs["serial_ms_per_step"],
                       sampled_edges_per_s=rs["per_step"]["sampled_edges"] / (rs["ms_per_step"] * 1e-3),
                       per_step=rs["per_step"], aggregate_GBps=rs["aggregate_GBps"], gemm_TFLOPs=rs["gemm_TFLOPs"],
                       rooflines=[roofline_of(rs["kernels"], k, tr) for k in rs["kernels"] if k in shown],
@@ -283,6 +363,9 @@ def main():
         config=dict(workload=f"{name}: N={g.n_nodes}, nnz={g.nnz}, {cfg.n_parts} partitions, batch {cfg.batch}, "
                              f"{cfg.samples} samples/layer, {len(dims)} layers {dims}, skew {cfg.skew}",
                     per_step=res["per_step"]),
+        one_stream_ms_per_step=res["serial_ms_per_step"],
+        schedule=f"sampling of consecutive batches on {args.samplers} streams (own workspace each), layer compute of all "
+                 "batches in order on one more stream",
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
         roofline=roofline, cpu_baseline=cpu_baseline,

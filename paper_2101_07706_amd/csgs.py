@@ -101,7 +101,10 @@ def strerror(code: int) -> str:
 
 
 def _ptr(t):
-    return None if t is None else C.c_void_p(t.data_ptr())
+    """Device pointer of a tensor; ctypes objects (a caller's mutable pointer box) pass through."""
+    if t is None or isinstance(t, C._SimpleCData):
+        return t
+    return C.c_void_p(t.data_ptr())
 
 
 def _stream(stream):
@@ -112,6 +115,59 @@ def _stream(stream):
 def _chk(rc, where):
     if rc != OK:
         raise CsgsError(rc, where)
+
+
+class DevicePtr(C.c_void_p):
+    """A device pointer whose value may be changed between runs of a Plan: stands for an array of
+    `n` elements wherever a wrapper takes a tensor only for its address and element count."""
+
+    def __init__(self, n, value=None):
+        super().__init__(value)
+        self.n = n
+
+    def numel(self):
+        return self.n
+
+
+class Plan:
+    """Library calls with their arguments already marshalled, to be issued again and again: a serving
+    or training loop that repeats the same calls on the same buffers pays the Python-side marshalling
+    once.  Arguments that change between runs are passed as ctypes boxes (c_uint64, c_void_p ...) whose
+    value is read at every run.  Built with `with csgs.record() as plan:` around ordinary wrapper calls
+    (nothing is enqueued while recording); `plan.run()` enqueues them."""
+
+    def __init__(self):
+        self.calls = []
+
+    def run(self):
+        for fn, args, name in self.calls:
+            rc = fn(*args)
+            if rc != OK:
+                raise CsgsError(rc, name)
+
+
+_recording = None
+
+
+class record:
+    def __enter__(self):
+        global _recording
+        assert _recording is None, "csgs.record() does not nest"
+        _recording = Plan()
+        return _recording
+
+    def __exit__(self, *exc):
+        global _recording
+        _recording = None
+        return False
+
+
+def _call(name, *args):
+    fn = getattr(lib(), name)
+    if _recording is not None:
+        _recording.calls.append((fn, args, name))
+        return
+    _chk(fn(*args), name)
 
 
 def make_graph(rowptr, colidx, val, local_lo, local_hi, rownorm2_max=1.0) -> Graph:
@@ -138,7 +194,7 @@ def make_workspace(buf, n_nodes, nS_max, B_max, edges_max) -> Workspace:
 
 
 def csgs_workspace_init(ws, stream=None):
-    _chk(lib().csgs_workspace_init(C.byref(ws), _stream(stream)), "csgs_workspace_init")
+    _call("csgs_workspace_init", C.byref(ws), _stream(stream))
 
 
 def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
@@ -149,46 +205,45 @@ def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
 
 def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None, nS_dev=None):
     """nS_dev: device int32 holding the number of rows of S to use (S.numel() is then the capacity)."""
-    _chk(lib().csgs_build_probs(C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
-                                _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream)),
-         "csgs_build_probs")
+    _call("csgs_build_probs", C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
+                                _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream))
 
 
 def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, ws, status, stream=None,
                           nS_dev=None):
-    _chk(lib().csgs_build_probs_auto(C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
+    _call("csgs_build_probs_auto", C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
                                      _ptr(cdf), _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status),
-                                     _stream(stream)), "csgs_build_probs_auto")
+                                     _stream(stream))
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
                       adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None):
-    _chk(lib().csgs_sample_layer(C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
+    _call("csgs_sample_layer", C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
                                  _ptr(stats), B, seed, it, layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
-                                 _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream)), "csgs_sample_layer")
+                                 _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream))
 
 
 def csgs_draw_nodes(n_nodes, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next, ws, status,
                     stream=None):
-    _chk(lib().csgs_draw_nodes(n_nodes, _ptr(cand_id), _ptr(cdf), cand_id.numel(), _ptr(stats), B, seed, it, layer,
+    _call("csgs_draw_nodes", n_nodes, _ptr(cand_id), _ptr(cdf), cand_id.numel(), _ptr(stats), B, seed, it, layer,
                                _ptr(S_next), _ptr(mult), _ptr(p_incl), _ptr(n_next), C.byref(ws), _ptr(status),
-                               _stream(stream)), "csgs_draw_nodes")
+                               _stream(stream))
 
 
 def csgs_sampled_adjacency(g, rows, adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None,
                            n_rows_dev=None):
-    _chk(lib().csgs_sampled_adjacency(C.byref(g), _ptr(rows), rows.numel(), _ptr(n_rows_dev), _ptr(adj_rowptr), _ptr(adj_col),
+    _call("csgs_sampled_adjacency", C.byref(g), _ptr(rows), rows.numel(), _ptr(n_rows_dev), _ptr(adj_rowptr), _ptr(adj_col),
                                       _ptr(adj_val), adj_col.numel(), _ptr(adj_nnz), C.byref(ws), _ptr(status),
-                                      _stream(stream)), "csgs_sampled_adjacency")
+                                      _stream(stream))
 
 
 def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_total, per_part=None,
                       src_row=None, remote_ids=None, stream=None):
     P = 0 if part_bounds is None else part_bounds.numel() - 1
-    _chk(lib().csgs_remote_count(_ptr(S_next), _ptr(n_next), local_lo, local_hi, _ptr(part_bounds), P,
+    _call("csgs_remote_count", _ptr(S_next), _ptr(n_next), local_lo, local_hi, _ptr(part_bounds), P,
                                  _ptr(remote_total), _ptr(per_part), _ptr(src_row), _ptr(remote_ids),
-                                 _stream(stream)), "csgs_remote_count")
+                                 _stream(stream))
 
 
 def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_row, relu_on_input, Z,
@@ -201,30 +256,30 @@ def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_
     if X_remote is not None and rows_r == 0:
         X_remote = None
     Xl_ptr = _ptr(X_local) if X_local.shape[0] > 0 else None
-    _chk(lib().csgs_aggregate(_ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
+    _call("csgs_aggregate", _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
                               _ptr(nS_dev), _ptr(n_next), Xl_ptr, X_local.stride(0), X_local.shape[0], _ptr(X_remote),
                               ld_r, rows_r, _ptr(src_row), F, dtype, 1 if relu_on_input else 0, _ptr(Z),
-                              Z.stride(0), _stream(stream)), "csgs_aggregate")
+                              Z.stride(0), _stream(stream))
 
 
 def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None):
     M, K = Z.shape
     K2, N = W.shape
     assert K == K2 and H.shape == (M, N)
-    _chk(lib().csgs_layer_gemm(_ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
-                               _stream(stream)), "csgs_layer_gemm")
+    _call("csgs_layer_gemm", _ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
+                               _stream(stream))
 
 
 def csgs_gather_rows(X, ids, n_dev, out, stream=None):
     """out[k] = X[ids[k]] for k < *n_dev (device int64; None = all of ids)."""
     assert X.dtype == out.dtype and X.shape[1] == out.shape[1] and out.shape[0] >= ids.numel()
     dtype = F32 if X.dtype == torch.float32 else BF16
-    _chk(lib().csgs_gather_rows(_ptr(X), X.stride(0), X.shape[0], X.shape[1], dtype, _ptr(ids), ids.numel(),
-                                _ptr(n_dev), _ptr(out), out.stride(0), _stream(stream)), "csgs_gather_rows")
+    _call("csgs_gather_rows", _ptr(X), X.stride(0), X.shape[0], X.shape[1], dtype, _ptr(ids), ids.numel(),
+                                _ptr(n_dev), _ptr(out), out.stride(0), _stream(stream))
 
 
 def csgs_profile_enable(on: bool):
-    _chk(lib().csgs_profile_enable(1 if on else 0), "csgs_profile_enable")
+    _call("csgs_profile_enable", 1 if on else 0)
 
 
 def csgs_profile_collect():
@@ -232,10 +287,10 @@ def csgs_profile_collect():
     n = lib().csgs_profile_kernel_count()
     ms = (C.c_double * n)()
     cnt = (C.c_int64 * n)()
-    _chk(lib().csgs_profile_collect(ms, cnt), "csgs_profile_collect")
+    _call("csgs_profile_collect", ms, cnt)
     return {lib().csgs_profile_kernel_name(k).decode(): (ms[k], cnt[k]) for k in range(n) if cnt[k]}
 
 
 def csgs_calib_copy(dst, src, stream=None):
     nbytes = src.numel() * src.element_size()
-    _chk(lib().csgs_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "csgs_calib_copy")
+    _call("csgs_calib_copy", _ptr(dst), _ptr(src), nbytes, _stream(stream))

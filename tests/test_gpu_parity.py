@@ -529,3 +529,34 @@ def test_layer_gemm_and_aggregate_device_row_count(dev):
     want = oracle.aggregate(rp[:m + 1], col[:rp[m]], val[:rp[m]], X, relu_on_input=True)
     chain.assert_close(Zo[:m].cpu().numpy(), want, chain.RTOL, chain.ATOL, "Z with nS_dev")
     assert bool(torch.isnan(Zo[m:]).all())
+
+
+def test_recorded_plan_replays_calls(dev):
+    """csgs.record(): wrapper calls made while recording are not enqueued; Plan.run() issues them with
+    the arguments marshalled once, boxes (batch pointer, iteration number) read at every run."""
+    import ctypes as C
+    from paper_2101_07706_amd import csgs, pipeline
+    g = SmallGraph(1500, 9, seed=21, lo=200, hi=700)
+    rng = np.random.default_rng(2)
+    B = 96
+    batches = [rng.permutation(1500)[:120].astype(np.int32) for _ in range(3)]
+    dg = pipeline.DeviceGraph(g, dev)
+    ws = pipeline.Workspace(g.n_nodes, 120, B, g.nnz, dev)
+    lb = pipeline.LayerBuffers(120, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+    Sd = [torch.from_numpy(b).to(dev) for b in batches]
+    S_box, it_box = csgs.DevicePtr(120), C.c_uint64(0)
+    lb.n_next.fill_(-5)
+    with csgs.record() as plan:
+        pipeline.sample_step(dg, ws, S_box, 2.0, B, 77, it_box, 1, lb)
+    torch.cuda.synchronize()
+    assert int(lb.n_next.item()) == -5 and len(plan.calls) == 3, "recording must not enqueue anything"
+    for it, b in enumerate(batches):
+        S_box.value, it_box.value = Sd[it].data_ptr(), it
+        plan.run()
+        torch.cuda.synchronize()
+        pr = oracle.build_probs(g, b, 2.0)
+        sm = oracle.sample_layer(g, b, pr, B, 77, it, 1)
+        assert int(lb.status.item()) == 0 and int(lb.n_next.item()) == sm.n_next
+        np.testing.assert_array_equal(lb.S_next[:sm.n_next].cpu().numpy(), sm.S_next)
+        np.testing.assert_array_equal(lb.adj_rowptr[:121].cpu().numpy(), sm.adj_rowptr)
+        np.testing.assert_array_equal(lb.adj_col[:sm.adj_nnz].cpu().numpy(), sm.adj_col)
