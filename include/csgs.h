@@ -32,6 +32,11 @@
  *   - `ws` describes scratch memory (see csgs_workspace), prepared once with
  *     csgs_workspace_init().  Every call leaves it ready for the next.  Calls that share one
  *     workspace must be ordered on one stream.
+ *   - Replay.  Nothing a kernel needs to tell one call from the next is fixed at launch time
+ *     (the call counter behind the inter-block flags lives in the workspace and is advanced by
+ *     the kernels), and no entry point records a memset.  A sequence of calls captured into a
+ *     HIP graph can therefore be replayed; what changes between replays (the batch, the
+ *     iteration number) is passed through device memory: see nS_dev / iter_dev.
  */
 #ifndef CSGS_H
 #define CSGS_H
@@ -105,8 +110,8 @@ typedef struct csgs_workspace {
     int32_t nS_max, B_max;
     int64_t edges_max;
     /* owned by the library (csgs_workspace_init resets them): */
-    uint64_t epoch;      /* kernels tagged so far */
-    uint64_t draw_epoch; /* tag of the latest csgs_draw_nodes, 0 = none */
+    uint64_t reserved_;
+    uint64_t has_draw;   /* a csgs_draw_nodes has been enqueued on this workspace */
     int32_t draw_B;      /* its B */
     int32_t pad_;
 } csgs_workspace;
@@ -172,7 +177,8 @@ int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_
  * B independent draws from q (Section 4.1: the sampling is run B times), deduplicated into
  * the next layer's node set, and the sampled adjacency of Eq. 3.
  *
- * Draw t uses Philox4x32-10 with key (seed_lo, seed_hi) and counter (t, layer, iter_lo, iter_hi);
+ * Draw t uses Philox4x32-10 with key (seed_lo, seed_hi) and counter (t, layer, iter_lo, iter_hi)
+ * (iter = *iter_dev, a device uint64 read when the kernel runs, if iter_dev is not NULL);
  * r = x0 | x1 << 32;  u = floor(r * total / 2^64);  the draw is the first candidate k with
  * cdf[k] > u.  Inclusion probability p_j = 1 - (1 - q_j)^B (Eq. 8) in double.
  *
@@ -191,8 +197,8 @@ int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_
  */
 int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
                       const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
-                      const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter, uint32_t layer,
-                      int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
+                      const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter,
+                      const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
                       int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
                       int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
                       void *stream);
@@ -212,7 +218,7 @@ int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS
  */
 int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
                     const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter,
-                    uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
+                    const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
                     csgs_workspace *ws /*host*/, int32_t *status, void *stream);
 int csgs_sampled_adjacency(const csgs_graph *g /*host*/, const int32_t *rows, int32_t n_rows,
                            const int32_t *n_rows_dev,

@@ -43,8 +43,8 @@ class Graph(C.Structure):
 class Workspace(C.Structure):
     """csgs_workspace: host descriptor of the caller-owned scratch buffer."""
     _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("n_nodes", C.c_int64),
-                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("epoch", C.c_uint64),
-                ("draw_epoch", C.c_uint64), ("draw_B", C.c_int32), ("pad_", C.c_int32)]
+                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("reserved_", C.c_uint64),
+                ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("pad_", C.c_int32)]
 
 
 class ProbStats(C.Structure):
@@ -74,9 +74,9 @@ def lib():
         L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, i32, f32, vp, vp, vp, vp, i64, vp,
                                             C.POINTER(Workspace), vp, vp]
-        L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, u32,
+        L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, vp, u32,
                                         vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
-        L.csgs_draw_nodes.argtypes = [i64, vp, vp, i64, vp, i32, u64, u64, u32, vp, vp, vp, vp, C.POINTER(Workspace), vp, vp]
+        L.csgs_draw_nodes.argtypes = [i64, vp, vp, i64, vp, i32, u64, u64, vp, u32, vp, vp, vp, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_sampled_adjacency.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
         L.csgs_aggregate.argtypes = [vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int,
@@ -217,16 +217,17 @@ def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, 
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
-                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None):
+                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None, iter_dev=None):
+    """iter_dev: device uint64 tensor holding the iteration number (then `it` is ignored)."""
     _call("csgs_sample_layer", C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
-                                 _ptr(stats), B, seed, it, layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
+                                 _ptr(stats), B, seed, it, _ptr(iter_dev), layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
                                  _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream))
 
 
 def csgs_draw_nodes(n_nodes, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next, ws, status,
-                    stream=None):
-    _call("csgs_draw_nodes", n_nodes, _ptr(cand_id), _ptr(cdf), cand_id.numel(), _ptr(stats), B, seed, it, layer,
+                    stream=None, iter_dev=None):
+    _call("csgs_draw_nodes", n_nodes, _ptr(cand_id), _ptr(cdf), cand_id.numel(), _ptr(stats), B, seed, it, _ptr(iter_dev), layer,
                                _ptr(S_next), _ptr(mult), _ptr(p_incl), _ptr(n_next), C.byref(ws), _ptr(status),
                                _stream(stream))
 

@@ -48,6 +48,7 @@ struct Workspace {
     uint64_t *partial;   // [4 * n_tiles] per-tile candidate counts and weight sums
     uint64_t *gtot;      // [4 * ceil(n_tiles / 64)] the same per group of 64 tiles
     uint64_t *cand_flag; // [n_tiles] tag of the call whose partial sums a tile holds
+    uint64_t *epoch;     // [4] call counter and draw tag (see lookback.hpp); advanced on the device
     uint64_t *hit_ts;    // scan state of the hit tiles (1 sum per tile)
     // per call
     int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows of S
@@ -88,6 +89,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.partial = (uint64_t *)take((size_t)w.n_tiles * 4 * 8);
     w.gtot = (uint64_t *)take((size_t)((w.n_tiles + 63) / 64) * 4 * 8);
     w.cand_flag = (uint64_t *)take((size_t)w.n_tiles * 8);
+    w.epoch = (uint64_t *)take(4 * 8);
     w.hit_ts = (uint64_t *)take(scan_state_words(w.hit_tiles, 1) * 8);
     w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
     w.rp_tiles = (nS_max + ROW_TILE - 1) / ROW_TILE;
@@ -132,8 +134,7 @@ __host__ inline int resident_grid()
 // min(52, shift_base - ceil(log2 count)), in w.meta for the kernels that follow.  Defined with the
 // weight scan.
 int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                      int32_t shift_base, const Workspace &w, csgs_workspace *ws, csgs_prob_stats *stats,
-                      int32_t *status, hipStream_t st);
+                      int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status, hipStream_t st);
 
 // A row count given on the host (n) or, when n_dev is not null, on the device with n as its bound.
 __device__ inline int32_t resolve_count(int32_t n, const int32_t *__restrict__ n_dev)

@@ -32,14 +32,26 @@
 // and invalidate the whole L2 of the XCD on every use, which was measured to cost tens of
 // microseconds per tile.  Everything else a tile writes is consumed by later kernels only.
 //
-// The flags live in the caller's workspace and are never cleared: every launch gets a fresh tag
-// (a host-side counter in the workspace descriptor), and a flag counts only if it carries it.
+// The flags live in the caller's workspace and are never cleared: a flag counts only if it carries
+// the tag of the current call.  Tags come from a call counter that lives in the workspace itself
+// (device memory): a kernel reads it when it starts, and the last kernel of every library call
+// advances it at its very end, when all blocks that use the tag have read it.  Nothing about a
+// tag is fixed at launch time, so a captured sequence of calls can be replayed.
 #pragma once
 #include "common.hpp"
 
 namespace csgs {
 
 constexpr int LOOKBACK_SPIN_LIMIT = 1 << 22;
+
+// words of Workspace::epoch
+constexpr int EPOCH_CALLS = 0;   // library calls completed on this workspace
+constexpr int EPOCH_DRAW = 1;    // value of (calls + 1) during the latest draw: tags the rank table
+// one tag space per scan-state region, so the kernels of one call never mistake each other's flags
+enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4 };
+
+__device__ inline unsigned long long call_number(const uint64_t *epoch) { return epoch[EPOCH_CALLS] + 1ull; }
+__device__ inline unsigned long long call_tag(unsigned long long call, int slot) { return call * 16ull + (unsigned long long)slot; }
 
 __device__ inline unsigned long long ld_relaxed(const unsigned long long *p)
 {

@@ -39,7 +39,7 @@ static_assert(RP_TILE == 256 * RP_ITEMS, "row tile");
 __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
                                                   const int32_t *__restrict__ S, int32_t nS_bound,
                                                   const int32_t *__restrict__ nS_dev, int32_t shift_base,
-                                                  unsigned long long tag, uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
+                                                  const uint64_t *__restrict__ epoch, uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
                                                   int64_t *__restrict__ meta, int64_t edge_cap,
                                                   csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status)
@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
     __shared__ int32_t s_deg[RP_TILE];
     __shared__ unsigned long long s_lb[1];
     const TileState<1> ts(ts_mem, ts_tiles);
+    const unsigned long long tag = call_tag(call_number(epoch), SLOT_ROWS);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
     int64_t n_tiles = ((int64_t)nS + RP_TILE - 1) / RP_TILE;
     if (n_tiles < 1) n_tiles = 1;   // an empty row set still gets its end markers written
@@ -189,7 +190,7 @@ constexpr int CAND_WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
 __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
                                                      const uint8_t *__restrict__ tileflag, int64_t n_words,
                                                      int64_t n_nodes, int64_t n_tiles, int32_t lo, int32_t hi,
-                                                     unsigned long long tag, unsigned long long *__restrict__ cand_flag,
+                                                     const uint64_t *__restrict__ epoch, unsigned long long *__restrict__ cand_flag,
                                                      unsigned long long *__restrict__ partial,
                                                      uint64_t *__restrict__ gtot, int32_t *__restrict__ status)
 {
@@ -197,6 +198,7 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;
+    const unsigned long long tag = call_tag(call_number(epoch), SLOT_CAND);
     uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
@@ -237,7 +239,8 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
                                                  int32_t hi, SkewPolicy pol, const uint64_t *__restrict__ partial,
                                                  const uint64_t *__restrict__ gtot,
-                                                 const int64_t *__restrict__ meta, csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
+                                                 const int64_t *__restrict__ meta, uint64_t *__restrict__ epoch,
+                                                 csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
                                                  uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
 {
@@ -363,6 +366,7 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
         if (n_cand == 0 || total_w == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
         if ((int64_t)n_cand > cap) st |= CSGS_ST_CAND_OVERFLOW;
         if (st) atomicOr(status, st);
+        epoch[EPOCH_CALLS] += 1ull;  // last kernel of the call; no block of this kernel reads the counter
     }
 }
 
@@ -391,12 +395,11 @@ static int shift_base_for(int64_t s_fx, float rownorm2_max)
 }  // namespace csgs
 
 int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                            int32_t shift_base, const Workspace &w, csgs_workspace *ws, csgs_prob_stats *stats,
-                            int32_t *status, hipStream_t st)
+                            int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status,
+                            hipStream_t st)
 {
     const unsigned tiles = (unsigned)(((int64_t)nS + RP_TILE - 1) / RP_TILE);
-    const unsigned long long tag = ++ws->epoch;
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, tag,
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, w.epoch,
                 w.rp_ts, w.rp_tiles, w.eoff, w.rowstart, w.meta, w.chunk_cap * EDGE_TILE, stats, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
@@ -419,8 +422,8 @@ extern "C" size_t csgs_workspace_clean_bytes(int64_t n_nodes)
 extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
 {
     if (!ws) return CSGS_EINVAL;
-    ws->epoch = 0;
-    ws->draw_epoch = 0;
+    ws->reserved_ = 0;
+    ws->has_draw = 0;
     ws->draw_B = 0;
     Workspace w;
     const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
@@ -468,18 +471,17 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
 
     // the shift for nS rows has passed the range check; fewer rows on the device only widen it
     const int32_t shift_base = shift_base_for(s_fx, g->rownorm2_max);
-    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, ws, stats, status, st);
+    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
     if (rc != CSGS_OK) return rc;
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, w.meta, w.eoff,
                 w.rowstart, w.wtable, w.tileflag, status);
     CSGS_LAUNCH_CHECK();
-    const unsigned long long cand_tag = ++ws->epoch;
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, cand_tag, (unsigned long long *)w.cand_flag,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,
                 (unsigned long long *)w.partial, w.gtot, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, w.meta, stats, status, cand_id,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, w.meta, w.epoch, stats, status, cand_id,
                 cand_w, cdf, q, cap);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;

@@ -19,12 +19,11 @@ bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop);
 }  // namespace csgs
 
 // Launch `kernel` on `stream`; when timing is enabled the dispatch is stamped with two events.
-#define CSGS_LAUNCH(kid, kernel, grid, block, stream, ...)                                          \
-    do {                                                                                            \
-        hipEvent_t ev0_ = nullptr, ev1_ = nullptr;                                                  \
-        if (::csgs::prof::g_enabled && !::csgs::prof::next_pair(::csgs::prof::kid, &ev0_, &ev1_)) { \
-            ev0_ = nullptr;                                                                         \
-            ev1_ = nullptr;                                                                         \
-        }                                                                                           \
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev0_, ev1_, 0, __VA_ARGS__);          \
+#define CSGS_LAUNCH(kid, kernel, grid, block, stream, ...)                                         \
+    do {                                                                                           \
+        hipEvent_t ev0_ = nullptr, ev1_ = nullptr;                                                 \
+        if (::csgs::prof::g_enabled && ::csgs::prof::next_pair(::csgs::prof::kid, &ev0_, &ev1_))   \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev0_, ev1_, 0, __VA_ARGS__);     \
+        else                                                                                       \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                       \
     } while (0)

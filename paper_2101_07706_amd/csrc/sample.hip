@@ -25,13 +25,6 @@
 
 namespace csgs {
 
-__global__ void fill_zero_u64(uint64_t *p, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = 0ull;
-}
-
 // Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): each round multiplies two
 // counter words by fixed odd constants, swaps halves around and xors in the key, then the key
 // advances by two Weyl increments.
@@ -55,11 +48,22 @@ constexpr int TOP = 2048;  // CDF samples staged in LDS per block (16 KB)
 
 __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ cdf,
                                                    const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
-                                                   int32_t B, uint32_t seed_lo, uint32_t seed_hi, uint32_t iter_lo,
-                                                   uint32_t iter_hi, uint32_t layer, uint32_t *__restrict__ hit,
-                                                   uint64_t *__restrict__ cbitmap)
+                                                   int32_t B, uint32_t seed_lo, uint32_t seed_hi, uint64_t iter,
+                                                   const uint64_t *__restrict__ iter_dev, uint32_t layer,
+                                                   uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
+                                                   const uint64_t *__restrict__ epoch, uint64_t *__restrict__ rank,
+                                                   int64_t n_nodes)
 {
     __shared__ uint64_t top[TOP];
+    // rank entries carry the low 32 bits of the call number; when those wrap, stale entries could
+    // look current, so the table is wiped once every 2^32 calls (the compaction kernel that follows
+    // writes the new entries)
+    if ((call_number(epoch) & 0xFFFFFFFFull) == 0) {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_nodes; i += (int64_t)gridDim.x * blockDim.x)
+            rank[i] = 0ull;
+    }
+    if (iter_dev) iter = *iter_dev;
+    const uint32_t iter_lo = (uint32_t)iter, iter_hi = (uint32_t)(iter >> 32);
     int64_t n = stats->n_cand;
     if (n > cand_cap) n = cand_cap;
     if (n <= 0) return;
@@ -114,7 +118,7 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
 __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ cand_id,
                                                   const uint64_t *__restrict__ cdf,
                                                   const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
-                                                  int64_t n_nodes, int32_t B, unsigned long long tag,
+                                                  int64_t n_nodes, int32_t B, uint64_t *__restrict__ epoch,
                                                   uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
                                                   uint64_t *__restrict__ rank, int32_t *__restrict__ S_next,
@@ -126,17 +130,23 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
     __shared__ unsigned long long s_lb[1];
     __shared__ uint16_t s_list[HIT_TILE_WORDS * 64];   // drawn positions of the tile, ascending
     const TileState<1> ts(ts_mem, ts_tiles);
+    const unsigned long long call = call_number(epoch);
+    const unsigned long long tag = call_tag(call, SLOT_HITS);
     int64_t n = stats->n_cand;
     if (n > cand_cap) n = cand_cap;
     if (n < 0) n = 0;
     const int64_t n_words = (n + 63) / 64;
     const int64_t n_tiles = (n_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
     if (n_tiles == 0) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) *n_next = 0;  // no candidates at all
+        if (blockIdx.x == 0 && threadIdx.x == 0) {  // no candidates at all
+            *n_next = 0;
+            epoch[EPOCH_DRAW] = call;
+            epoch[EPOCH_CALLS] = call;
+        }
         return;
     }
     const double total = (double)cdf[n - 1];
-    const uint64_t rank_tag = (tag & 0xFFFFFFFFull) << 32;
+    const uint64_t rank_tag = (call & 0xFFFFFFFFull) << 32;
     for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         // one bitmap word per thread -> ordered list of the tile's drawn positions in LDS
         const int64_t wi = t * HIT_TILE_WORDS + threadIdx.x;
@@ -201,6 +211,10 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
         if (t == n_tiles - 1 && threadIdx.x == 0) {
             const uint64_t tot = excl[0] + tile_total;
             *n_next = (int32_t)(tot < (uint64_t)B ? tot : (uint64_t)B);
+            // Last kernel of the draw: advance the call counter.  Every block that owns a tile has
+            // read it by now (this tile's prefix needed all their sums), the others never use it.
+            epoch[EPOCH_DRAW] = call;
+            epoch[EPOCH_CALLS] = call;
         }
         __syncthreads();  // s_list is reused by the next tile
     }
@@ -218,8 +232,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                                                  const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
                                                  const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
-                                                 unsigned long long tag, unsigned long long hits_tag,
-                                                 uint64_t *__restrict__ ts_mem, int64_t chunk_cap,
+                                                 uint64_t *__restrict__ epoch, uint64_t *__restrict__ ts_mem, int64_t chunk_cap,
                                                  int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
                                                  float *__restrict__ adj_val, int64_t adj_cap,
                                                  int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
@@ -231,7 +244,9 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const TileState<1> ts(ts_mem, chunk_cap);
-    const uint64_t rank_tag = (hits_tag & 0xFFFFFFFFull) << 32;
+    const unsigned long long call = call_number(epoch);
+    const unsigned long long tag = call_tag(call, SLOT_ADJ);
+    const uint64_t rank_tag = (epoch[EPOCH_DRAW] & 0xFFFFFFFFull) << 32;
     const int32_t nS = (int32_t)meta[META_ROWS];
     int64_t E = meta[META_EDGES];
     int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
@@ -247,6 +262,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             if (threadIdx.x == 0) {
                 *adj_nnz = 0;
                 if (overflow) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
+                epoch[EPOCH_CALLS] = call;
             }
         }
         return;
@@ -321,6 +337,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             if (threadIdx.x == 0) {
                 *adj_nnz = total;
                 if (total > adj_cap || total > 0x7FFFFFFFll) atomicOr(status, CSGS_ST_ADJ_OVERFLOW);
+                epoch[EPOCH_CALLS] = call;  // last kernel of the call, last chunk: all chunk owners have read the counter
             }
         }
     }
@@ -370,9 +387,9 @@ __global__ __launch_bounds__(256) void remote_count_k(const int32_t *__restrict_
 using namespace csgs;
 
 extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
-                               const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter, uint32_t layer,
-                               int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next, csgs_workspace *ws,
-                               int32_t *status, void *stream)
+                               const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter,
+                               const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
+                               int32_t *n_next, csgs_workspace *ws, int32_t *status, void *stream)
 {
     if (n_nodes <= 0 || n_nodes > 0x7FFFFFFFll || !cand_id || !cdf || cand_cap <= 0 || !stats || B <= 0 || !S_next ||
         !mult || !p_incl || !n_next || !ws || !status)
@@ -384,25 +401,16 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
     if (cand_cap > n_nodes) cand_cap = n_nodes;  // there are never more candidates than nodes
 
     CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), st, cdf, stats,
-                cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)iter, (uint32_t)(iter >> 32), layer, w.hit,
-                w.cbitmap);
+                cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), iter, iter_dev, layer, w.hit, w.cbitmap, w.epoch, w.rank,
+                n_nodes);
     CSGS_LAUNCH_CHECK();
-    // rank entries carry the low 32 bits of the tag; when those wrap, stale entries could look
-    // current, so the table is wiped once every 2^32 calls
-    const unsigned long long hits_tag = ++ws->epoch;
-    if ((hits_tag & 0xFFFFFFFFull) == 0) {
-        const size_t n = (size_t)n_nodes;
-        const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-        CSGS_LAUNCH(K_FILL_ZERO, fill_zero_u64, dim3(blocks), dim3(256), st, w.rank, n);
-        CSGS_LAUNCH_CHECK();
-    }
     const int64_t cap_words = (cand_cap + 63) / 64;
     const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
     const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid() ? hit_tiles : resident_grid());
     CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
-                hits_tag, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
+                w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
     CSGS_LAUNCH_CHECK();
-    ws->draw_epoch = hits_tag;
+    ws->has_draw = 1;
     ws->draw_B = B;
     return CSGS_OK;
 }
@@ -416,18 +424,17 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !rows || n_rows <= 0 ||
         !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
         return CSGS_EINVAL;
-    if (ws->draw_epoch == 0) return CSGS_EINVAL;  // no csgs_draw_nodes has run on this workspace
+    if (!ws->has_draw) return CSGS_EINVAL;  // no csgs_draw_nodes has run on this workspace
     Workspace w;
     const int rc = open_workspace(ws, g->n_nodes, n_rows, ws->draw_B, &w);
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (!reuse_offsets) {
-        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, ws, nullptr, status, st);
+        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
-    const unsigned long long adj_tag = ++ws->epoch;
     CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes,
-                w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, adj_tag, (unsigned long long)ws->draw_epoch, w.adj_ts, w.chunk_cap,
+                w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap,
                 adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
@@ -443,13 +450,13 @@ extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, 
 
 extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
                                  const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
-                                 uint64_t iter, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
+                                 uint64_t iter, const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
                                  int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
                                  int64_t adj_cap, int64_t *adj_nnz, csgs_workspace *ws, int32_t *status,
                                  void *stream)
 {
     if (!g || !S || nS <= 0 || !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz) return CSGS_EINVAL;
-    const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, layer, S_next, mult, p_incl,
+    const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, iter_dev, layer, S_next, mult, p_incl,
                                    n_next, ws, status, stream);
     if (rc != CSGS_OK) return rc;
     return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, stream);

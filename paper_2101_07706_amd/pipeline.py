@@ -66,11 +66,13 @@ class LayerBuffers:
                                total=s.total, shift=s.shift, skew_fx=s.skew_fx)
 
 
-def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None, nS_dev=None):
+def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None, nS_dev=None,
+                iter_dev=None):
     """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32).
     auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound.
     nS_dev: device int32 with the number of rows of S to use (the previous layer's n_next), so that
-    the host need not wait for it; S is then the whole capacity-sized array."""
+    the host need not wait for it; S is then the whole capacity-sized array.
+    iter_dev: device uint64 with the iteration number (for replayed call sequences)."""
     nS = S.numel()
     q = lb.q if want_q else None
     if auto_D is None:
@@ -81,7 +83,7 @@ def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=Tru
                                    lb.status, stream, nS_dev=nS_dev)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
-                           ws.desc, lb.status, stream)
+                           ws.desc, lb.status, stream, iter_dev=iter_dev)
     csgs.csgs_remote_count(lb.S_next, lb.n_next, dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total,
                            lb.per_part, lb.src_row, lb.remote_ids, stream)
 

@@ -560,3 +560,69 @@ def test_recorded_plan_replays_calls(dev):
         np.testing.assert_array_equal(lb.S_next[:sm.n_next].cpu().numpy(), sm.S_next)
         np.testing.assert_array_equal(lb.adj_rowptr[:121].cpu().numpy(), sm.adj_rowptr)
         np.testing.assert_array_equal(lb.adj_col[:sm.adj_nnz].cpu().numpy(), sm.adj_col)
+
+
+def test_step_replayed_from_a_hip_graph(dev):
+    """A two-layer step captured once into a HIP graph and replayed for several batches and iteration
+    numbers (passed through device memory), with eager library work on the same workspace and
+    synchronisations between the replays: every replay equals the oracle."""
+    from paper_2101_07706_amd import pipeline
+    g = SmallGraph(4000, 14, seed=31, lo=1000, hi=2400)
+    rng = np.random.default_rng(6)
+    F, Fh, B, nS0, seed = 32, 24, 200, 150, 4321
+    X = rng.standard_normal((g.n_nodes, F)).astype(np.float32)
+    Ws = [synth.glorot_uniform(F, Fh, 1), synth.glorot_uniform(Fh, 8, 2)]
+    dg = pipeline.DeviceGraph(g, dev)
+    ws = pipeline.Workspace(g.n_nodes, max(nS0, B), B, g.nnz, dev)
+    lbs = [pipeline.LayerBuffers(max(nS0, B), B, g.n_nodes, g.nnz, dg.n_parts, dev) for _ in range(2)]
+    Xd = torch.from_numpy(X).to(dev)
+    Wd = [torch.from_numpy(W).to(dev) for W in Ws]
+    S0buf = torch.zeros(nS0, dtype=torch.int32, device=dev)
+    iter_dev = torch.zeros(1, dtype=torch.int64, device=dev)
+    staged = torch.zeros((B, F), dtype=torch.float32, device=dev)
+    Z = [torch.zeros((nS0, Fh), dtype=torch.float32, device=dev), torch.zeros((B, F), dtype=torch.float32, device=dev)]
+    H = [torch.zeros((nS0, 8), dtype=torch.float32, device=dev), torch.zeros((B, Fh), dtype=torch.float32, device=dev)]
+
+    def enqueue():
+        pipeline.sample_step(dg, ws, S0buf, 3.0, B, seed, 0, 0, lbs[0], iter_dev=iter_dev)
+        pipeline.sample_step(dg, ws, lbs[0].S_next, 3.0, B, seed, 0, 1, lbs[1], nS_dev=lbs[0].n_next, iter_dev=iter_dev)
+        pipeline.stage_remote_rows(lbs[1], Xd, staged)
+        pipeline.compute_step(lbs[1], B, Xd[g.local_lo:g.local_hi], staged, True, False, Wd[0], Z[1], H[1], nS_dev=lbs[0].n_next)
+        pipeline.compute_step(lbs[0], nS0, H[1], None, False, True, Wd[1], Z[0], H[0])
+
+    batches = [rng.permutation(np.arange(g.local_lo, g.local_hi))[:nS0].astype(np.int32) for _ in range(4)]
+    S0buf.copy_(torch.from_numpy(batches[0]).to(dev))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):      # one eager pass before capture
+        enqueue()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    torch.cuda.synchronize()
+    for rep, (b, it) in enumerate(zip(batches, [5, 5, 9, 2 ** 33 + 1])):
+        S0buf.copy_(torch.from_numpy(b).to(dev))
+        iter_dev.fill_(it)
+        for lb in lbs:
+            lb.status.zero_()
+        if rep % 2 == 1:   # eager library work on the same workspace between replays
+            scratch = pipeline.LayerBuffers(max(nS0, B), B, g.n_nodes, g.nnz, dg.n_parts, dev)
+            pipeline.sample_step(dg, ws, S0buf, 1.0, B, 1, 0, 0, scratch)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        osteps = chain.oracle_chain(g, X, Ws, b, 3.0, B, seed, it)
+        n1 = osteps[0].sm.n_next
+        gsteps = [SimpleNamespaceLike(S=S0buf, lb=lbs[0], n_next=int(lbs[0].n_next.item()), status=int(lbs[0].status.item()),
+                                      Z=Z[0], H=H[0]),
+                  SimpleNamespaceLike(S=lbs[0].S_next[:n1], lb=lbs[1], n_next=int(lbs[1].n_next.item()),
+                                      status=int(lbs[1].status.item()), Z=Z[1][:n1], H=H[1][:n1])]
+        worst = chain.compare_chain(osteps, gsteps)
+        say(f"[graph] replay {rep}: iter {it}, n' {[o.sm.n_next for o in osteps]}, worst err/tol {max(worst.values()):.3f}")
+
+
+class SimpleNamespaceLike:
+    def __init__(self, **kw):
+        self.__dict__.update(kw)
