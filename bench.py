@@ -77,56 +77,79 @@ class Workload:
                         for _ in range(self.n_sets)]
         self.lbs = self.lb_sets[0]
         self.overlap = None
+        self.use_graphs = True
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
         self.elt = 2 if self.bf16 else 4
         self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
 
-    def enqueue(self, S0, it, lbs, ws, s_samp=None, s_comp=None, between=None):
-        """The library calls of one mini-batch: sampling top-down on s_samp, then (after `between`, which
-        ties the two streams) staging of the remote rows and the layer compute bottom-up on s_comp."""
+    def enqueue_sampling(self, S0, it, lbs, ws):
+        """Top-down sampling calls of one mini-batch on the current stream; `it` is a number or a
+        device uint64 tensor."""
         cfg, M, B, pipeline = self.cfg, self.M, self.B, self.pipeline
-        n0 = S0.numel()
+        it_num, it_dev = (0, it) if hasattr(it, "data_ptr") else (it, None)
         for l in range(M):
             S = S0 if l == 0 else lbs[l - 1].S_next
-            pipeline.sample_step(self.dg, ws, S, cfg.skew, B, self.seed, it, l, lbs[l], want_q=False,
-                                 nS_dev=None if l == 0 else lbs[l - 1].n_next, stream=s_samp)
-        if between:
-            between()
-        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.staged, stream=s_comp)   # stands in for the exchange of remote rows
+            pipeline.sample_step(self.dg, ws, S, cfg.skew, B, self.seed, it_num, l, lbs[l], want_q=False,
+                                 nS_dev=None if l == 0 else lbs[l - 1].n_next, iter_dev=it_dev)
+
+    def enqueue_compute(self, lbs, n0):
+        """Staging of the sampled remote rows (stands in for their exchange) and the bottom-up layer
+        compute of one mini-batch on the current stream."""
+        M, B, pipeline = self.M, self.B, self.pipeline
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.staged)
         H = None
         for l in range(M - 1, -1, -1):
             nS = n0 if l == 0 else B
             nS_dev = None if l == 0 else lbs[l - 1].n_next
             Z, Hn = self.Zs[l][:nS], self.Hs[l][:nS]
             if l == M - 1:
-                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev,
-                                      stream=s_comp)
+                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev)
             else:
-                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev,
-                                      stream=s_comp)
+                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev)
             H = Hn
         return H
 
     def prepare_overlap(self):
-        """Streams, events and, per buffer set, the step's calls with their arguments marshalled once
-        (csgs.Plan); the batch pointer and the iteration number are boxes filled in per step."""
-        import ctypes as C
-        torch, csgs = self.torch, self.csgs
+        """Streams, events and, per buffer set, the step's library calls captured into two HIP graphs
+        (sampling, compute).  What differs from step to step goes through device memory: the batch
+        is copied into the set's batch buffer and the iteration number into a device word before
+        the sampling graph is replayed.  A kernel launch costs the host 4-5 us and a step has 34,
+        so launching them one by one cannot keep three streams fed; a replay is one call."""
+        torch = self.torch
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
         s_comp = torch.cuda.Stream()
         sets = []
         for k in range(self.n_sets):
-            S0 = csgs.DevicePtr(self.Sd[0].numel())
-            it = C.c_uint64(0)
-            marks = []
-            with csgs.record() as plan:
-                H = self.enqueue(S0, it, self.lb_sets[k], self.wss[k % self.n_samplers], samplers[k % self.n_samplers], s_comp,
-                                 between=lambda: marks.append(len(plan.calls)))
-            sample, compute = csgs.Plan(), csgs.Plan()
-            sample.calls, compute.calls = plan.calls[:marks[0]], plan.calls[marks[0]:]
-            sets.append(dict(S0=S0, it=it, sample=sample, compute=compute, H=H, s_samp=samplers[k % self.n_samplers],
+            s_samp = samplers[k % self.n_samplers]
+            S0 = torch.zeros_like(self.Sd[0])
+            it_dev = torch.zeros(1, dtype=torch.int64, device=self.dev)
+            # one eager pass on the streams the graphs will run on, then capture
+            S0.copy_(self.Sd[0])
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s_samp):
+                self.enqueue_sampling(S0, it_dev, self.lb_sets[k], self.wss[k % self.n_samplers])
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s_comp):
+                self.enqueue_compute(self.lb_sets[k], S0.numel())
+            torch.cuda.synchronize()
+            g_samp = g_comp = None
+            H = self.Hs[0][:S0.numel()]
+            if self.use_graphs:
+                try:
+                    g_samp, g_comp = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g_samp, stream=s_samp):
+                        self.enqueue_sampling(S0, it_dev, self.lb_sets[k], self.wss[k % self.n_samplers])
+                    with torch.cuda.graph(g_comp, stream=s_comp):
+                        self.enqueue_compute(self.lb_sets[k], S0.numel())
+                except Exception as e:      # said out loud and recorded in the JSON line; the calls are then issued one by one
+                    log(f"graph capture failed ({e!r}); launching the calls directly")
+                    self.use_graphs = False
+                    g_samp = g_comp = None
+            torch.cuda.synchronize()
+            sets.append(dict(S0=S0, it=it_dev, sample=g_samp, compute=g_comp, H=H, s_samp=s_samp,
                              samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
+        self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=self.dev)   # iteration numbers, resident
         self.overlap = dict(sets=sets, s_comp=s_comp)
 
     def step(self, it, sizes=None, overlap=False):
@@ -146,20 +169,30 @@ class Workload:
             st = self.overlap["sets"][it % self.n_sets]
             s_comp = self.overlap["s_comp"]
             lbs = self.lb_sets[it % self.n_sets]
-            st["S0"].value = self.Sd[it].data_ptr()
-            st["it"].value = it
-            if st["used"]:
-                st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batch sampled into it was computed
-            st["sample"].run()
-            st["samp_done"].record(st["s_samp"])
-            s_comp.wait_event(st["samp_done"])
-            st["compute"].run()
-            st["comp_done"].record(s_comp)
+            torch = self.torch
+            with torch.cuda.stream(st["s_samp"]):
+                if st["used"]:
+                    st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batch sampled into it was computed
+                st["S0"].copy_(self.Sd[it], non_blocking=True)
+                st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
+                if st["sample"] is not None:
+                    st["sample"].replay()
+                else:
+                    self.enqueue_sampling(st["S0"], st["it"], lbs, self.wss[(it % self.n_sets) % self.n_samplers])
+                st["samp_done"].record(st["s_samp"])
+            with torch.cuda.stream(s_comp):
+                s_comp.wait_event(st["samp_done"])
+                if st["compute"] is not None:
+                    st["compute"].replay()
+                else:
+                    self.enqueue_compute(lbs, n0)
+                st["comp_done"].record(s_comp)
             st["used"] = True
             H = st["H"]
         else:
             lbs = self.lb_sets[0]
-            H = self.enqueue(self.Sd[it], it, lbs, self.wss[0])
+            self.enqueue_sampling(self.Sd[it], it, lbs, self.wss[0])
+            H = self.enqueue_compute(lbs, n0)
         self.lbs = lbs
         if sizes is not None:
             self.torch.cuda.synchronize()
@@ -186,7 +219,9 @@ class Workload:
         torch.cuda.synchronize()
         serial_ms = (time.perf_counter() - t0) / steps * 1e3
         h_serial = H.clone()
-        # (2) the timed region proper: same steps, sampling and compute on two streams
+        # (2) the timed region proper: same steps in the overlapped schedule
+        if self.overlap is None:
+            self.prepare_overlap()
         for it in range(warmup):
             self.step(it, overlap=True)
         torch.cuda.synchronize()
@@ -228,7 +263,7 @@ class Workload:
         tot = lambda key: sum(s[key] for s in sizes) / steps
         per_step = dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
                         sampled_edges=tot("nnz"), remote_nodes=tot("remote"))
-        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, kernels=kernels, per_step=per_step, sizes=sizes,
+        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes,
                     aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
 
 
@@ -365,7 +400,8 @@ def main():
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
         schedule=f"sampling of consecutive batches on {args.samplers} streams (own workspace each), layer compute of all "
-                 "batches in order on one more stream",
+                 "batches in order on one more stream; each part " +
+                 ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
         roofline=roofline, cpu_baseline=cpu_baseline,
