@@ -31,7 +31,10 @@
  *     left untouched.  A whole step can so be enqueued without the host ever waiting.
  *   - `ws` describes scratch memory (see csgs_workspace), prepared once with
  *     csgs_workspace_init().  Every call leaves it ready for the next.  Calls that share one
- *     workspace must be ordered on one stream.
+ *     workspace must be ordered on one stream.  Calls on DIFFERENT workspaces may run side by
+ *     side on different streams; at most four such call sequences per device at a time (two
+ *     kernels hold all their blocks resident while they wait for each other, and four of them
+ *     fit a compute unit together).
  *   - Replay.  Nothing a kernel needs to tell one call from the next is fixed at launch time
  *     (the call counter behind the inter-block flags lives in the workspace and is advanced by
  *     the kernels), and no entry point records a memset.  A sequence of calls captured into a

@@ -113,20 +113,25 @@ __host__ inline int open_workspace(csgs_workspace *d, int64_t n_nodes, int64_t n
     return out->bytes <= d->bytes ? CSGS_OK : CSGS_EWORKSPACE;
 }
 
-// Blocks of 256 threads that are certainly resident at the same time on the current device: two
-// per compute unit (far below what registers and LDS of these kernels allow).  Kernels whose blocks
-// wait for each other never launch more.
-__host__ inline int resident_grid()
+// Grid of a kernel whose blocks wait for each other and stride over a tile count known only on
+// the device: resident_grid(per_cu) blocks of 256 threads, per_cu per compute unit.  Such a kernel
+// must have all its blocks resident at once.  Alone on the device that is certain (registers and
+// LDS allow several times as many).  Beside kernels of other streams it still holds as long as the
+// waiting kernels in flight fit together, because every other kernel drains by itself: the
+// compaction of drawn positions (33 KB of LDS) runs 1 block per unit and the adjacency filter
+// (13 KB) 2, so four call sequences on four workspaces can be in flight on one device within the
+// 2048 threads and 160 KB of a compute unit.  That is the documented limit.
+__host__ inline int resident_grid(int per_cu)
 {
     static int cached[64] = {0};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 64;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 32 * per_cu;
     if (cached[dev] == 0) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 32;
-        cached[dev] = 2 * cus;
+        cached[dev] = cus;
     }
-    return cached[dev];
+    return per_cu * cached[dev];
 }
 
 // Degrees of the rows S, their exclusive prefix (w.eoff) and CSR starts (w.rowstart); stats may be

@@ -406,7 +406,7 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
     CSGS_LAUNCH_CHECK();
     const int64_t cap_words = (cand_cap + 63) / 64;
     const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
-    const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid() ? hit_tiles : resident_grid());
+    const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid(1) ? hit_tiles : resident_grid(1));
     CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
                 w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
     CSGS_LAUNCH_CHECK();
@@ -433,7 +433,7 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
         const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
-    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid()), dim3(256), st, g->colidx, g->val, g->n_nodes,
+    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
                 w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap,
                 adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
