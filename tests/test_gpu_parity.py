@@ -626,3 +626,82 @@ def test_step_replayed_from_a_hip_graph(dev):
 class SimpleNamespaceLike:
     def __init__(self, **kw):
         self.__dict__.update(kw)
+
+
+def test_subgraph_sampler_without_host_reads(dev):
+    """Subgraph sampler with the number of drawn nodes left on the device: rows of the sampled operator
+    = S_next at its capacity B, n_rows_dev = n_next; aggregation and GEMM with the same device count."""
+    from paper_2101_07706_amd import csgs, pipeline
+    g = SmallGraph(2500, 11, seed=8, lo=300, hi=1300)
+    rng = np.random.default_rng(3)
+    F, B, seed, skew = 24, 380, 17, 2.0
+    X = rng.standard_normal((g.n_nodes, F)).astype(np.float32)
+    W = synth.glorot_uniform(F, 12, 5)
+    n = g.n_nodes
+    rows_all = np.arange(n, dtype=np.int32)
+    pr = oracle.build_probs(g, rows_all, skew)
+    dr = oracle.draw_nodes(pr, B, seed, 4, 0)
+    adj = oracle.sampled_adjacency(g, dr.S_next, dr)
+    rc = oracle.remote_count(dr.S_next, g.local_lo, g.local_hi, g.part_bounds)
+    Zo = oracle.aggregate(adj.adj_rowptr, adj.adj_col, adj.adj_val, X[g.local_lo:g.local_hi], X[rc.remote_ids], rc.src_row)
+    Ho = oracle.layer_gemm(Zo, W)
+
+    dg = pipeline.DeviceGraph(g, dev)
+    ws = pipeline.Workspace(n, n, B, g.nnz, dev)
+    lb = pipeline.LayerBuffers(n, B, n, int(g.nnz), dg.n_parts, dev)
+    Xd, Wd = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev)
+    staged = torch.zeros((B, F), dtype=torch.float32, device=dev)
+    Zd = torch.full((B, F), float("nan"), dtype=torch.float32, device=dev)
+    Hd = torch.full((B, 12), float("nan"), dtype=torch.float32, device=dev)
+    lb.adj_rowptr.fill_(-3)
+    csgs.csgs_build_probs(dg.c, torch.from_numpy(rows_all).to(dev), skew, lb.cand_id, lb.cand_w, lb.cdf, lb.q, lb.stats, ws.desc,
+                          lb.status)
+    csgs.csgs_draw_nodes(n, lb.cand_id, lb.cdf, lb.stats, B, seed, 4, 0, lb.S_next, lb.mult, lb.p_incl, lb.n_next, ws.desc, lb.status)
+    csgs.csgs_sampled_adjacency(dg.c, lb.S_next, lb.adj_rowptr[:B + 1], lb.adj_col, lb.adj_val, lb.adj_nnz, ws.desc, lb.status,
+                                n_rows_dev=lb.n_next)
+    csgs.csgs_remote_count(lb.S_next, lb.n_next, g.local_lo, g.local_hi, dg.part_bounds, lb.remote_total, lb.per_part,
+                           lb.src_row, lb.remote_ids)
+    pipeline.stage_remote_rows(lb, Xd, staged)
+    pipeline.compute_step(lb, B, Xd[g.local_lo:g.local_hi], staged, True, False, Wd, Zd, Hd, nS_dev=lb.n_next)
+    torch.cuda.synchronize()
+    m = int(lb.n_next.item())
+    assert int(lb.status.item()) == 0 and m == dr.n_next and m < B
+    np.testing.assert_array_equal(lb.adj_rowptr[:m + 1].cpu().numpy(), adj.adj_rowptr)
+    assert bool((lb.adj_rowptr[m + 1:B + 1] == -3).all())
+    np.testing.assert_array_equal(lb.adj_col[:adj.adj_nnz].cpu().numpy(), adj.adj_col)
+    chain.assert_close(lb.adj_val[:adj.adj_nnz].cpu().numpy(), adj.adj_val, chain.P_RTOL, 0.0, "adj_val")
+    chain.assert_close(Zd[:m].cpu().numpy(), Zo, chain.RTOL, chain.ATOL, "Z")
+    chain.assert_close(Hd[:m].cpu().numpy(), Ho, chain.RTOL, chain.ATOL, "H")
+    assert bool(torch.isnan(Zd[m:]).all()) and bool(torch.isnan(Hd[m:]).all())
+
+
+def test_four_call_sequences_side_by_side(dev):
+    """Four sampling call sequences on four workspaces and four streams at once (the documented limit
+    of concurrent sequences): each gives the result of running alone."""
+    from paper_2101_07706_amd import pipeline
+    cfg, g, X, Ws, _ = chain.config_inputs("medium")
+    dg = pipeline.DeviceGraph(g, dev)
+    B = cfg.samples
+    batches = [synth.make_batch(g, cfg.batch, cfg.seed, it) for it in range(4)]
+    Sd = [torch.from_numpy(b).to(dev) for b in batches]
+    wss = [pipeline.Workspace(g.n_nodes, max(cfg.batch, B), B, g.nnz, dev) for _ in range(4)]
+    lbs = [[pipeline.LayerBuffers(max(cfg.batch, B), B, g.n_nodes, 4_000_000, dg.n_parts, dev) for _ in range(2)] for _ in range(4)]
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for j in range(4):
+            pipeline.sample_step(dg, wss[j], Sd[j], cfg.skew, B, 99, rep, 0, lbs[j][0], stream=streams[j])
+            pipeline.sample_step(dg, wss[j], lbs[j][0].S_next, cfg.skew, B, 99, rep, 1, lbs[j][1], stream=streams[j],
+                                 nS_dev=lbs[j][0].n_next)
+    torch.cuda.synchronize()
+    for j in range(4):
+        S = batches[j]
+        for l in range(2):
+            pr = oracle.build_probs(g, S, cfg.skew)
+            sm = oracle.sample_layer(g, S, pr, B, 99, 2, l)
+            lb = lbs[j][l]
+            assert int(lb.status.item()) == 0 and int(lb.n_next.item()) == sm.n_next
+            np.testing.assert_array_equal(lb.S_next[:sm.n_next].cpu().numpy(), sm.S_next)
+            np.testing.assert_array_equal(lb.adj_rowptr[:len(S) + 1].cpu().numpy(), sm.adj_rowptr)
+            np.testing.assert_array_equal(lb.adj_col[:sm.adj_nnz].cpu().numpy(), sm.adj_col)
+            S = sm.S_next
