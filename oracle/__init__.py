@@ -241,3 +241,44 @@ def layer_gemm(Z, W):
     _chk(lib().orc_layer_gemm(_p(Z), C.c_int64(K), C.c_int32(M), C.c_int32(K), _p(W), C.c_int64(N),
                               C.c_int32(N), _p(H), C.c_int64(N)))
     return H
+
+
+def layer_gemm_grad_w(Z, G):
+    """dW = Z^T G."""
+    Z = np.ascontiguousarray(Z, np.float32)
+    G = np.ascontiguousarray(G, np.float32)
+    M, K = Z.shape
+    M2, N = G.shape
+    assert M == M2
+    dW = np.zeros((K, N), np.float32)
+    _chk(lib().orc_layer_gemm_grad_w(_p(Z), C.c_int64(K), _p(G), C.c_int64(N), C.c_int32(M), C.c_int32(K), C.c_int32(N),
+                                     _p(dW), C.c_int64(N)))
+    return dW
+
+
+def layer_gemm_grad_z(G, W):
+    """dZ = G W^T (W stored [K x N])."""
+    G = np.ascontiguousarray(G, np.float32)
+    W = np.ascontiguousarray(W, np.float32)
+    M, N = G.shape
+    K, N2 = W.shape
+    assert N == N2
+    dZ = np.zeros((M, K), np.float32)
+    _chk(lib().orc_layer_gemm_grad_z(_p(G), C.c_int64(N), C.c_int32(M), C.c_int32(N), _p(W), C.c_int64(N), C.c_int32(K),
+                                     _p(dZ), C.c_int64(K)))
+    return dZ
+
+
+def aggregate_grad(adj_rowptr, adj_col, adj_val, n_cols, dZ, H_prev=None):
+    """dH_prev = (P~^T dZ) .* [H_prev > 0]; H_prev None: no mask."""
+    adj_rowptr = np.ascontiguousarray(adj_rowptr, np.int32)
+    adj_col = np.ascontiguousarray(adj_col, np.int32)
+    adj_val = np.ascontiguousarray(adj_val, np.float32)
+    dZ = np.ascontiguousarray(dZ, np.float32)
+    nS, F = dZ.shape
+    assert len(adj_rowptr) == nS + 1
+    Hp = None if H_prev is None else np.ascontiguousarray(H_prev, np.float32)
+    dH = np.zeros((n_cols, F), np.float32)
+    _chk(lib().orc_aggregate_grad(_p(adj_rowptr), _p(adj_col), _p(adj_val), C.c_int32(nS), C.c_int32(n_cols), _p(dZ),
+                                  C.c_int64(F), C.c_int32(F), _p(Hp), C.c_int64(F), _p(dH), C.c_int64(F)))
+    return dH

@@ -480,3 +480,68 @@ int orc_layer_gemm(const float *Z, int64_t ldz, int32_t M, int32_t K, const floa
     free(acc);
     return ORC_OK;
 }
+
+/* -------------------------------------------------------- gradients of one layer
+ *
+ * Each GPU obtains a stochastic gradient of the loss through its sampled layers (Section 3,
+ * Eq. 1 and Eq. 2).  For one layer H = Z W, Z = P~ sigma(H_prev), with G = dL/dH given, the chain
+ * rule is written out as it stands:
+ *     dL/dW      = Z^T G
+ *     dL/dZ      = G W^T
+ *     dL/dH_prev = (P~^T dL/dZ) .* sigma'(H_prev),   sigma = ReLU: sigma'(x) = [x > 0]
+ * Double accumulation, one rounding to float.  Pinned by central finite differences of the
+ * forward functions in double.
+ */
+
+/* dW [K x N] = Z^T [K x M] G [M x N] */
+int orc_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M, int32_t K, int32_t N,
+                          float *dW, int64_t lddw)
+{
+    if (!Z || !G || !dW || M < 0 || K <= 0 || N <= 0) return ORC_EINVAL;
+    for (int32_t k = 0; k < K; ++k)
+        for (int32_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int32_t m = 0; m < M; ++m) acc += (double)Z[(int64_t)m * ldz + k] * (double)G[(int64_t)m * ldg + n];
+            dW[(int64_t)k * lddw + n] = (float)acc;
+        }
+    return ORC_OK;
+}
+
+/* dZ [M x K] = G [M x N] W^T [N x K],  W stored [K x N] */
+int orc_layer_gemm_grad_z(const float *G, int64_t ldg, int32_t M, int32_t N, const float *W, int64_t ldw, int32_t K,
+                          float *dZ, int64_t lddz)
+{
+    if (!G || !W || !dZ || M < 0 || K <= 0 || N <= 0) return ORC_EINVAL;
+    for (int32_t m = 0; m < M; ++m)
+        for (int32_t k = 0; k < K; ++k) {
+            double acc = 0.0;
+            for (int32_t n = 0; n < N; ++n) acc += (double)G[(int64_t)m * ldg + n] * (double)W[(int64_t)k * ldw + n];
+            dZ[(int64_t)m * lddz + k] = (float)acc;
+        }
+    return ORC_OK;
+}
+
+/* dH_prev [n_cols x F] = (P~^T dZ) .* [H_prev > 0]   (H_prev NULL: no activation, no mask).
+ * P~ is the CSR of the forward step: nS rows, columns < n_cols. */
+int orc_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int32_t nS,
+                       int32_t n_cols, const float *dZ, int64_t lddz, int32_t F, const float *H_prev, int64_t ldh,
+                       float *dH, int64_t ldd)
+{
+    if (!adj_rowptr || !dZ || !dH || nS < 0 || n_cols < 0 || F <= 0) return ORC_EINVAL;
+    double *acc = (double *)calloc((size_t)(n_cols > 0 ? n_cols : 1) * (size_t)F, sizeof(double));
+    if (!acc) return ORC_ECAP;
+    for (int32_t r = 0; r < nS; ++r)
+        for (int32_t e = adj_rowptr[r]; e < adj_rowptr[r + 1]; ++e) {
+            const int32_t c = adj_col[e];
+            if (c < 0 || c >= n_cols) { free(acc); return ORC_EINVAL; }
+            for (int32_t f = 0; f < F; ++f) acc[(size_t)c * F + f] += (double)adj_val[e] * (double)dZ[(int64_t)r * lddz + f];
+        }
+    for (int32_t c = 0; c < n_cols; ++c)
+        for (int32_t f = 0; f < F; ++f) {
+            double v = acc[(size_t)c * F + f];
+            if (H_prev && !(H_prev[(int64_t)c * ldh + f] > 0.0f)) v = 0.0;
+            dH[(int64_t)c * ldd + f] = (float)v;
+        }
+    free(acc);
+    return ORC_OK;
+}

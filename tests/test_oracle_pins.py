@@ -518,3 +518,73 @@ def test_layer_gemm_is_matmul():
                                rtol=1e-6, atol=1e-7)
     # not the transposed product
     assert H.shape == (17, 11)
+
+
+# ---------------------------------------------------------------- gradients of one layer
+def _dense_forward(Pd, Hprev, W, relu):
+    """The layer of Eq. 1 in float64 with a dense sampled operator."""
+    X = np.maximum(Hprev, 0.0) if relu else Hprev
+    return Pd @ X @ W
+
+
+@pytest.mark.parametrize("relu", [True, False])
+def test_layer_gradients_match_finite_differences(relu):
+    """orc_layer_gemm_grad_w / _grad_z / orc_aggregate_grad against central finite differences of the
+    forward layer (dense, float64) for the scalar loss L = sum(R .* H): the chain rule of Eq. 1 is not
+    retyped here, only the forward pass is."""
+    rng = np.random.default_rng(11 + relu)
+    nS, nc, F, N = 7, 9, 5, 4
+    deg = rng.integers(0, 5, nS)
+    rp = np.zeros(nS + 1, np.int32)
+    np.cumsum(deg, out=rp[1:])
+    col = np.concatenate([np.sort(rng.choice(nc, d, replace=False)) for d in deg]).astype(np.int32)
+    val = (rng.standard_normal(len(col)) * 3).astype(np.float32)
+    Hprev = rng.standard_normal((nc, F)).astype(np.float32)
+    Hprev[np.abs(Hprev) < 0.05] = 0.3          # keep the ReLU kink away from the difference step
+    W = rng.standard_normal((F, N)).astype(np.float32)
+    R = rng.standard_normal((nS, N)).astype(np.float32)
+    Pd = np.zeros((nS, nc))
+    for r in range(nS):
+        Pd[r, col[rp[r]:rp[r + 1]]] = val[rp[r]:rp[r + 1]]
+    loss = lambda Hp, Wm: float((R.astype(np.float64) * _dense_forward(Pd, Hp, Wm, relu)).sum())
+    h = 1e-4
+    Hp64, W64 = Hprev.astype(np.float64), W.astype(np.float64)
+    fd_W = np.zeros_like(W64)
+    for i in range(F):
+        for j in range(N):
+            d = np.zeros_like(W64); d[i, j] = h
+            fd_W[i, j] = (loss(Hp64, W64 + d) - loss(Hp64, W64 - d)) / (2 * h)
+    fd_H = np.zeros_like(Hp64)
+    for i in range(nc):
+        for j in range(F):
+            d = np.zeros_like(Hp64); d[i, j] = h
+            fd_H[i, j] = (loss(Hp64 + d, W64) - loss(Hp64 - d, W64)) / (2 * h)
+    # oracle chain: forward Z, then the three gradient functions with G = R
+    Z = oracle.aggregate(rp, col, val, Hprev, relu_on_input=relu)
+    dW = oracle.layer_gemm_grad_w(Z, R)
+    dZ = oracle.layer_gemm_grad_z(R, W)
+    dH = oracle.aggregate_grad(rp, col, val, nc, dZ, Hprev if relu else None)
+    np.testing.assert_allclose(dW, fd_W, rtol=2e-5, atol=2e-5)
+    np.testing.assert_allclose(dH, fd_H, rtol=2e-5, atol=2e-5)
+    # and dZ alone: L as a function of Z is linear, so the difference quotient is exact up to rounding
+    fd_Z = R.astype(np.float64) @ W64.T
+    np.testing.assert_allclose(dZ, fd_Z, rtol=1e-6, atol=1e-6)
+
+
+def test_gradient_functions_reduce_to_dense_products():
+    rng = np.random.default_rng(5)
+    Z = rng.standard_normal((33, 17)).astype(np.float32)
+    G = rng.standard_normal((33, 6)).astype(np.float32)
+    W = rng.standard_normal((17, 6)).astype(np.float32)
+    np.testing.assert_allclose(oracle.layer_gemm_grad_w(Z, G), Z.astype(np.float64).T @ G, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(oracle.layer_gemm_grad_z(G, W), G.astype(np.float64) @ W.T, rtol=1e-6, atol=1e-6)
+    # empty rows and an unused column
+    rp = np.array([0, 0, 2, 2, 3], np.int32)
+    col = np.array([1, 3, 3], np.int32)
+    val = np.array([2.0, -1.0, 0.5], np.float32)
+    dZ = rng.standard_normal((4, 3)).astype(np.float32)
+    dH = oracle.aggregate_grad(rp, col, val, 5, dZ)
+    want = np.zeros((5, 3))
+    want[1] = 2.0 * dZ[1]
+    want[3] = -1.0 * dZ[1] + 0.5 * dZ[3]
+    np.testing.assert_allclose(dH, want, rtol=1e-6, atol=1e-7)
