@@ -289,6 +289,40 @@ int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
 
 /*
+ * Gradients of one sampled layer.  Every GPU obtains a stochastic gradient of the loss (Section 3,
+ * Eq. 2) through its sampled layers (Eq. 1): for H = Z W, Z = P~ sigma(H_prev) and G = dL/dH,
+ *     dW      = Z^T G                                  csgs_layer_gemm_grad_w
+ *     dZ      = G W^T                                  csgs_layer_gemm_grad_z
+ *     dH_prev = (P~^T dZ) .* [H_prev > 0]              csgs_aggregate_grad   (sigma = ReLU)
+ * Same conventions as the forward calls: row-major fp32, double accumulation (fp64 matrix cores
+ * for the two products), one rounding to float, M / nS / n_cols with nullable *_dev counterparts.
+ *
+ * csgs_layer_gemm_grad_w: Z [M x K], G [M x Nout] -> dW [K x Nout].  The sum over the M rows is
+ *   split into parts that are added in a fixed order; `scratch` (device, 8-byte aligned) holds the
+ *   parts: at least csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout) bytes.
+ * csgs_layer_gemm_grad_z: G [M x Nout], W [K x Nout] (as in the forward call) -> dZ [M x K].
+ * csgs_aggregate_grad: P~ as written by csgs_sample_layer (nS rows, n_cols = *n_next columns,
+ *   adj_cap = capacity of adj_col / adj_val), dZ [nS x F] -> dH_prev [n_cols x F].  H_prev
+ *   [n_cols x F] is the layer's input (NULL: no activation, no mask).  The transpose of P~ is built
+ *   in `scratch` (256-byte aligned, csgs_aggregate_grad_scratch_bytes(n_cols, adj_cap) bytes);
+ *   inside a column the summation order is the arrival order of integer atomics, which moves a
+ *   double sum by parts in 1e16, far below the float result's last bit in all but tie cases.
+ * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE (scratch too small), CSGS_EUNSUPPORTED.
+ */
+size_t csgs_layer_gemm_grad_w_scratch_bytes(int32_t M, int32_t K, int32_t Nout);
+int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M,
+                           const int32_t *M_dev, int32_t K, int32_t Nout, float *dW, int64_t lddw,
+                           void *scratch, size_t scratch_bytes, void *stream);
+int csgs_layer_gemm_grad_z(const float *G, int64_t ldg, int32_t M, const int32_t *M_dev, int32_t Nout,
+                           const float *W, int64_t ldw, int32_t K, float *dZ, int64_t lddz, void *stream);
+size_t csgs_aggregate_grad_scratch_bytes(int32_t n_cols, int64_t adj_cap);
+int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val,
+                        int64_t adj_cap, int32_t nS, const int32_t *nS_dev, int32_t n_cols,
+                        const int32_t *n_cols_dev, const float *dZ, int64_t lddz, int32_t F,
+                        const float *H_prev, int64_t ldh, float *dH_prev, int64_t ldd, void *scratch,
+                        size_t scratch_bytes, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the
  * library carries two HIP events that the runtime stamps with the start and the end of that
  * dispatch.  csgs_profile_collect, called after the caller has synchronised, fills ms_sum[k] /

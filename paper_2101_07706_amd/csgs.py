@@ -22,7 +22,8 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
-           "csgs_layer_gemm", "csgs_strerror",
+           "csgs_layer_gemm", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
+           "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
            "csgs_calib_copy"]
 
@@ -83,6 +84,13 @@ def lib():
                                      C.c_int, vp, i64, vp]
         L.csgs_layer_gemm.argtypes = [vp, i64, i32, vp, i32, vp, i64, i32, vp, i64, vp]
         L.csgs_gather_rows.argtypes = [vp, i64, i64, i32, C.c_int, vp, i64, vp, vp, i64, vp]
+        L.csgs_layer_gemm_grad_w_scratch_bytes.restype = sz
+        L.csgs_layer_gemm_grad_w_scratch_bytes.argtypes = [i32, i32, i32]
+        L.csgs_layer_gemm_grad_w.argtypes = [vp, i64, vp, i64, i32, vp, i32, i32, vp, i64, vp, sz, vp]
+        L.csgs_layer_gemm_grad_z.argtypes = [vp, i64, i32, vp, i32, vp, i64, i32, vp, i64, vp]
+        L.csgs_aggregate_grad_scratch_bytes.restype = sz
+        L.csgs_aggregate_grad_scratch_bytes.argtypes = [i32, i64]
+        L.csgs_aggregate_grad.argtypes = [vp, vp, vp, i64, i32, vp, i32, vp, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp]
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
         L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
@@ -269,6 +277,42 @@ def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None):
     assert K == K2 and H.shape == (M, N)
     _call("csgs_layer_gemm", _ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
                                _stream(stream))
+
+
+def csgs_layer_gemm_grad_w_scratch_bytes(M, K, N) -> int:
+    return int(lib().csgs_layer_gemm_grad_w_scratch_bytes(M, K, N))
+
+
+def csgs_layer_gemm_grad_w(Z, G, dW, scratch, stream=None, M_dev=None):
+    """dW [K x N] = Z^T G; scratch: a tensor of at least csgs_layer_gemm_grad_w_scratch_bytes(M, K, N) bytes."""
+    M, K = Z.shape
+    M2, N = G.shape
+    assert M == M2 and dW.shape == (K, N)
+    _call("csgs_layer_gemm_grad_w", _ptr(Z), Z.stride(0), _ptr(G), G.stride(0), M, _ptr(M_dev), K, N, _ptr(dW), dW.stride(0),
+          _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream))
+
+
+def csgs_layer_gemm_grad_z(G, W, dZ, stream=None, M_dev=None):
+    """dZ [M x K] = G W^T with W [K x N] as in the forward call."""
+    M, N = G.shape
+    K, N2 = W.shape
+    assert N == N2 and dZ.shape == (M, K)
+    _call("csgs_layer_gemm_grad_z", _ptr(G), G.stride(0), M, _ptr(M_dev), N, _ptr(W), W.stride(0), K, _ptr(dZ), dZ.stride(0),
+          _stream(stream))
+
+
+def csgs_aggregate_grad_scratch_bytes(n_cols, adj_cap) -> int:
+    return int(lib().csgs_aggregate_grad_scratch_bytes(n_cols, adj_cap))
+
+
+def csgs_aggregate_grad(adj_rowptr, adj_col, adj_val, n_next, dZ, H_prev, dH_prev, scratch, stream=None, nS_dev=None):
+    """dH_prev [n_cols x F] = (P~^T dZ) .* [H_prev > 0]; n_cols = dH_prev.shape[0] (capacity), n_next its device count."""
+    nS, F = dZ.shape
+    n_cols = dH_prev.shape[0]
+    assert adj_rowptr.numel() == nS + 1 and dH_prev.shape[1] == F and (H_prev is None or H_prev.shape[1] == F)
+    _call("csgs_aggregate_grad", _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(), nS, _ptr(nS_dev), n_cols,
+          _ptr(n_next), _ptr(dZ), dZ.stride(0), F, _ptr(H_prev), 0 if H_prev is None else H_prev.stride(0), _ptr(dH_prev),
+          dH_prev.stride(0), _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream))
 
 
 def csgs_gather_rows(X, ids, n_dev, out, stream=None):

@@ -112,6 +112,15 @@ __device__ inline void accumulate_staged(double (&acc)[V], const T *src, float w
     }
 }
 
+// Zeroes the components whose mask entry is not positive (the derivative of ReLU at the layer's input).
+template <int V>
+__device__ inline void apply_mask(double (&acc)[V], const float *__restrict__ m)
+{
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+        if (!(m[v] > 0.f)) acc[v] = 0.0;
+}
+
 template <int V>
 __device__ inline void store_row(float *z, const double (&acc)[V])
 {
@@ -130,7 +139,8 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
                                       const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
                                       int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
                                       const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
-                                      const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z, int64_t ldz)
+                                      const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z, int64_t ldz,
+                                      const float *__restrict__ mask, int64_t ldm)
 {
     const int tid = (int)threadIdx.x;
     const int g = tid & (G - 1);  // lane within the row group
@@ -168,7 +178,10 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
             const int32_t n_max = (maxlen - c0) < G ? (maxlen - c0) : G;
             accumulate_staged<T, V, RELU>(acc, src, w, gbase, n_here, n_max, active, f);
         }
-        if (active && mine) store_row<V>(Z + row * ldz + f, acc);
+        if (active && mine) {
+            if (mask) apply_mask<V>(acc, mask + row * ldm + f);
+            store_row<V>(Z + row * ldz + f, acc);
+        }
     }
 }
 
@@ -182,7 +195,7 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
                                            int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl,
                                            int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
                                            const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z,
-                                           int64_t ldz)
+                                           int64_t ldz, const float *__restrict__ mask, int64_t ldm)
 {
     __shared__ double part[16][WAVE * V];
     __shared__ int32_t long_rows[1024];
@@ -232,6 +245,7 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
 #pragma unroll
                     for (int v = 0; v < V; ++v) sum[v] += part[w2][lane * V + v];
                 }
+                if (mask) apply_mask<V>(sum, mask + (int64_t)row * ldm + f);
                 store_row<V>(Z + (int64_t)row * ldz + f, sum);
             }
         }
@@ -250,22 +264,22 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
                                                          const int32_t *__restrict__ src_row, int32_t F,
                                                          float *__restrict__ Z, int64_t ldz, int32_t n_long_blocks,
-                                                         int32_t per)
+                                                         int32_t per, const float *__restrict__ mask, int64_t ldm)
 {
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
     if ((int32_t)blockIdx.x < n_long_blocks)
         aggregate_long_rows<T, V, RELU>((int32_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl, rows_l,
-                                        Xr, ldr, rows_r, src_row, F, Z, ldz);
+                                        Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
     else
         aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x - n_long_blocks, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl,
-                                      ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz);
+                                      ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
 }
 
 template <typename T, int V, int G>
 static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                      hipStream_t st)
+                      const float *mask, int64_t ldm, int kid, hipStream_t st)
 {
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
@@ -276,11 +290,11 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
     const dim3 grid((unsigned)(blocks + lblocks));
     if (relu)
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per);
+        CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm);
     else
-        CSGS_LAUNCH(K_AGGREGATE, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per);
+        CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -288,17 +302,17 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 template <typename T, int V>
 static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                      hipStream_t st)
+                      const float *mask, int64_t ldm, int kid, hipStream_t st)
 {
-    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
 }
 
 template <typename T>
 static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                     int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                    hipStream_t st)
+                    const float *mask, int64_t ldm, int kid, hipStream_t st)
 {
     // widest vector for which every row start and F are aligned
     auto ok = [&](int v) {
@@ -307,9 +321,124 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
                (!Xr || (ldr % v == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % v == 0 &&
                ((uintptr_t)Z % ((uintptr_t)v * sizeof(float))) == 0;
     };
-    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
-    return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, st);
+    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+}
+
+// ------------------------------------------------------------------ gradient of the aggregation
+// dH_prev = (P~^T dZ) .* [H_prev > 0].  P~ is held by rows; its transpose is built per call in the
+// caller's scratch: entries per column counted with integer atomics, a block scan turns the
+// counts into column offsets, a second pass drops every entry into its column (order inside a
+// column is arrival order).  Then the forward kernel runs on the transposed structure with dZ as
+// the gathered table and the ReLU derivative as an output mask.  Sums are in double, so the
+// arrival order moves the result by parts in 1e16 before the single rounding to float.
+
+// one wavefront per row of P~: counts[c] += 1 for every entry of the row
+__global__ __launch_bounds__(256) void adjT_count(const int32_t *__restrict__ adj_rowptr,
+                                                  const int32_t *__restrict__ adj_col, int32_t nS_bound,
+                                                  const int32_t *__restrict__ nS_dev, int32_t n_cols_bound,
+                                                  const int32_t *__restrict__ n_cols_dev, int32_t *__restrict__ counts)
+{
+    const int32_t nS = resolve_count(nS_bound, nS_dev), n_cols = resolve_count(n_cols_bound, n_cols_dev);
+    const int lane = lane_id();
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r = wave; r < nS; r += n_waves) {
+        const int32_t beg = adj_rowptr[r], end = adj_rowptr[r + 1];
+        for (int32_t e = beg + lane; e < end; e += WAVE) {
+            const int32_t c = adj_col[e];
+            if (c >= 0 && c < n_cols) atomicAdd(&counts[c], 1);
+        }
+    }
+}
+
+// one block: colptr = exclusive prefix of counts (rounds of 8192), counts reset to zero so that the
+// fill pass can use them as per-column cursors
+__global__ __launch_bounds__(1024) void adjT_prefix(int32_t *__restrict__ counts, int32_t n_cols_bound,
+                                                    const int32_t *__restrict__ n_cols_dev,
+                                                    int32_t *__restrict__ colptr)
+{
+    __shared__ int32_t lds[17];
+    const int32_t n_cols = resolve_count(n_cols_bound, n_cols_dev);
+    int32_t base = 0;
+    for (int32_t c0 = 0; c0 < n_cols; c0 += 8192) {
+        int32_t v[8], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int32_t c = c0 + (int32_t)threadIdx.x * 8 + k;
+            v[k] = c < n_cols ? counts[c] : 0;
+            sum += v[k];
+        }
+        int32_t total;
+        int32_t ex = base + block_exclusive_scan<int32_t>(sum, lds, &total);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int32_t c = c0 + (int32_t)threadIdx.x * 8 + k;
+            if (c < n_cols) {
+                colptr[c] = ex;
+                counts[c] = 0;
+            }
+            ex += v[k];
+        }
+        base += total;
+    }
+    if (threadIdx.x == 0) colptr[n_cols] = base;
+}
+
+// one wavefront per row of P~: entry (r, c, v) goes to slot colptr[c] + cursor[c]++
+__global__ __launch_bounds__(256) void adjT_fill(const int32_t *__restrict__ adj_rowptr,
+                                                 const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
+                                                 int32_t nS_bound, const int32_t *__restrict__ nS_dev,
+                                                 int32_t n_cols_bound, const int32_t *__restrict__ n_cols_dev,
+                                                 const int32_t *__restrict__ colptr, int32_t *__restrict__ cursor,
+                                                 int32_t *__restrict__ rowT, float *__restrict__ valT, int64_t cap)
+{
+    const int32_t nS = resolve_count(nS_bound, nS_dev), n_cols = resolve_count(n_cols_bound, n_cols_dev);
+    const int lane = lane_id();
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r = wave; r < nS; r += n_waves) {
+        const int32_t beg = adj_rowptr[r], end = adj_rowptr[r + 1];
+        for (int32_t e = beg + lane; e < end; e += WAVE) {
+            const int32_t c = adj_col[e];
+            if (c >= 0 && c < n_cols) {
+                const int64_t slot = (int64_t)colptr[c] + atomicAdd(&cursor[c], 1);
+                if (slot < cap) {
+                    rowT[slot] = (int32_t)r;
+                    valT[slot] = adj_val[e];
+                }
+            }
+        }
+    }
+}
+
+__global__ void fill_zero_i32(int32_t *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+struct GradScratch {
+    int32_t *counts, *colptr, *rowT;
+    float *valT;
+    size_t bytes;
+};
+
+__host__ inline GradScratch carve_grad(void *base, int32_t n_cols_cap, int64_t adj_cap)
+{
+    GradScratch g;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return (char *)base + o;
+    };
+    g.counts = (int32_t *)take((size_t)n_cols_cap * 4);
+    g.colptr = (int32_t *)take(((size_t)n_cols_cap + 1) * 4);
+    g.rowT = (int32_t *)take((size_t)adj_cap * 4);
+    g.valT = (float *)take((size_t)adj_cap * 4);
+    g.bytes = off;
+    return g;
 }
 
 // out[k, :] = X[ids[k], :] in units of U (the widest type every row start is aligned to); one
@@ -383,7 +512,41 @@ extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col,
     hipStream_t st = (hipStream_t)stream;
     if (dtype == CSGS_F32)
         return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
-                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
+                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st);
     return pick_vec<uint16_t>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
-                              ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, st);
+                              ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st);
+}
+
+extern "C" size_t csgs_aggregate_grad_scratch_bytes(int32_t n_cols, int64_t adj_cap)
+{
+    if (n_cols <= 0 || adj_cap <= 0) return 0;
+    return carve_grad(nullptr, n_cols, adj_cap).bytes;
+}
+
+extern "C" int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int64_t adj_cap,
+                                   int32_t nS, const int32_t *nS_dev, int32_t n_cols, const int32_t *n_cols_dev, const float *dZ,
+                                   int64_t lddz, int32_t F, const float *H_prev, int64_t ldh, float *dH_prev, int64_t ldd,
+                                   void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (!adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || adj_cap > 0x7FFFFFFFll || nS <= 0 || n_cols <= 0 || !dZ ||
+        lddz < F || F <= 0 || (H_prev && ldh < F) || !dH_prev || ldd < F || !scratch || ((uintptr_t)scratch & 255))
+        return CSGS_EINVAL;
+    const GradScratch g = carve_grad(scratch, n_cols, adj_cap);
+    if (scratch_bytes < g.bytes) return CSGS_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const unsigned zb = (unsigned)(((int64_t)n_cols + 255) / 256 < 1024 ? ((int64_t)n_cols + 255) / 256 : 1024);
+    CSGS_LAUNCH(K_FILL_ZERO, fill_zero_i32, dim3(zb), dim3(256), st, g.counts, (int64_t)n_cols);
+    CSGS_LAUNCH_CHECK();
+    const unsigned rb = (unsigned)(((int64_t)nS + 3) / 4 < 4096 ? ((int64_t)nS + 3) / 4 : 4096);   // 4 rows (wavefronts) per block
+    CSGS_LAUNCH(K_ADJT_COUNT, adjT_count, dim3(rb), dim3(256), st, adj_rowptr, adj_col, nS, nS_dev, n_cols, n_cols_dev, g.counts);
+    CSGS_LAUNCH_CHECK();
+    CSGS_LAUNCH(K_ADJT_PREFIX, adjT_prefix, dim3(1), dim3(1024), st, g.counts, n_cols, n_cols_dev, g.colptr);
+    CSGS_LAUNCH_CHECK();
+    CSGS_LAUNCH(K_ADJT_FILL, adjT_fill, dim3(rb), dim3(256), st, adj_rowptr, adj_col, adj_val, nS, nS_dev, n_cols, n_cols_dev,
+                (const int32_t *)g.colptr, g.counts, g.rowT, g.valT, adj_cap);
+    CSGS_LAUNCH_CHECK();
+    // the forward kernel on the transposed structure: rows = columns of P~, gathered table = dZ
+    // (its rows are bounded by the row count of P~), output mask = [H_prev > 0]
+    return pick_vec<float>(g.colptr, g.rowT, g.valT, n_cols, n_cols_dev, nS_dev, dZ, lddz, (int64_t)nS, nullptr, (int64_t)F, 0,
+                           nullptr, F, 0, dH_prev, ldd, H_prev, ldh, prof::K_AGGREGATE_GRAD, st);
 }

@@ -41,71 +41,80 @@ __device__ inline float4 load4(const float *__restrict__ p)
     return make_float4(p[0], p[1], p[2], p[3]);
 }
 
-// A chunk: 128 rows x 32 k = 1024 groups of 4 consecutive k; thread t takes groups t + 256 i.
-template <int VA, bool FULL>
-__device__ inline void fetch_a(const float *__restrict__ A, int64_t lda, int M, int K, int64_t m0, int k0, int tid,
-                               float4 (&ra)[4])
+// The same kernel serves the layer's forward product and its two gradient products; they differ in
+// how the operands lie in memory and in where the result goes:
+//   FWD  H  = Z W        A(m,k) = Z[m][k]           B(k,n) = W[k][n]      C float [M x N]
+//   DZ   dZ = G W^T      A(m,k) = G[m][k]           B(k,n) = W[n][k]      C float [M x N]
+//   DW   dW = Z^T G      A(m,k) = Z[k][m]           B(k,n) = G[k][n]      partial sums in double,
+//        the reduction dimension (the rows of the sampled layer) split over blockIdx.y; a second
+//        kernel adds the parts in a fixed order.
+enum { MODE_FWD = 0, MODE_DZ = 1, MODE_DW = 2 };
+
+// Tile [ROWS][BK] of a matrix whose element (r, k) sits at P[r * ld + k] (k contiguous): ROWS * 8
+// groups of 4 consecutive k; thread t takes groups t + 256 i.
+template <int ROWS, int V, bool FULL>
+__device__ inline void fetch_kmajor(const float *__restrict__ P, int64_t ld, int R, int K, int64_t r0, int k0, int tid,
+                                    float4 (&reg)[ROWS / 32])
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < ROWS / 32; ++i) {
         const int idx = tid + i * 256;
         const int r = idx >> 3, kq = (idx & 7) * 4;
-        const int64_t gm = m0 + r;
+        const int64_t gr = r0 + r;
         const int gk = k0 + kq;
-        if (FULL || (gm < M && gk + 3 < K)) {
-            ra[i] = load4<VA>(A + gm * lda + gk);
+        if (FULL || (gr < R && gk + 3 < K)) {
+            reg[i] = load4<V>(P + gr * ld + gk);
         } else {
             float t[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) t[j] = (gm < M && gk + j < K) ? A[gm * lda + gk + j] : 0.f;
-            ra[i] = make_float4(t[0], t[1], t[2], t[3]);
+            for (int j = 0; j < 4; ++j) t[j] = (gr < R && gk + j < K) ? P[gr * ld + gk + j] : 0.f;
+            reg[i] = make_float4(t[0], t[1], t[2], t[3]);
         }
     }
 }
 
-// B chunk: 32 k x BN columns.  Lane <-> column (coalesced across lanes), each thread takes runs of
-// 4 consecutive k of one column, which become one 128-bit store into the transposed LDS tile.
-template <int BN, bool FULL>
-__device__ inline void fetch_b(const float *__restrict__ Bm, int64_t ldb, int K, int N, int k0, int64_t n0, int tid,
-                               float4 (&rb)[BN / 32])
+// Tile [ROWS][BK] of a matrix whose element (r, k) sits at P[k * ld + r] (r contiguous).  Lane <-> r
+// (coalesced across lanes), each thread takes runs of 4 consecutive k of one r, which become one
+// 128-bit store into the LDS tile.
+template <int ROWS, bool FULL>
+__device__ inline void fetch_rmajor(const float *__restrict__ P, int64_t ld, int R, int K, int64_t r0, int k0, int tid,
+                                    float4 (&reg)[ROWS / 32])
 {
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) {
-        const int idx = tid + i * 256;          // BN * 8 groups
-        const int n = idx % BN, kg = (idx / BN) * 4;
-        const int64_t gn = n0 + n;
+    for (int i = 0; i < ROWS / 32; ++i) {
+        const int idx = tid + i * 256;          // ROWS * 8 groups
+        const int r = idx % ROWS, kg = (idx / ROWS) * 4;
+        const int64_t gr = r0 + r;
         const int gk = k0 + kg;
         float t[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t[j] = (FULL || (gn < N && gk + j < K)) ? Bm[(int64_t)(gk + j) * ldb + gn] : 0.f;
-        rb[i] = make_float4(t[0], t[1], t[2], t[3]);
+        for (int j = 0; j < 4; ++j) t[j] = (FULL || (gr < R && gk + j < K)) ? P[(int64_t)(gk + j) * ld + gr] : 0.f;
+        reg[i] = make_float4(t[0], t[1], t[2], t[3]);
     }
 }
 
-template <int BN>
-__device__ inline void stash(float *As, float *Bs, int tid, const float4 (&ra)[4], const float4 (&rb)[BN / 32])
+// Registers -> LDS tile [ROWS][LDS_STRIDE], with the (r, k) of each group as the fetch above had it.
+template <int ROWS, bool KMAJOR>
+__device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 32])
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < ROWS / 32; ++i) {
         const int idx = tid + i * 256;
-        const int r = idx >> 3, kq = (idx & 7) * 4;
-        *reinterpret_cast<float4 *>(&As[r * LDS_STRIDE + kq]) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < BN / 32; ++i) {
-        const int idx = tid + i * 256;
-        const int n = idx % BN, kg = (idx / BN) * 4;
-        *reinterpret_cast<float4 *>(&Bs[n * LDS_STRIDE + kg]) = rb[i];
+        const int r = KMAJOR ? (idx >> 3) : (idx % ROWS);
+        const int k = KMAJOR ? (idx & 7) * 4 : (idx / ROWS) * 4;
+        *reinterpret_cast<float4 *>(&S[r * LDS_STRIDE + k]) = reg[i];
     }
 }
 
-template <int BN, int VA, bool FULL>
+template <int BN, int MODE, int V, bool FULL>
 __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
-                                                  int64_t ldc, int M_bound, const int32_t *__restrict__ M_dev, int N,
-                                                  int K, int n_tiles_n, int n_tiles)
+                                                  int64_t ldc, double *__restrict__ partial, int M_bound, int N,
+                                                  int K_bound, const int32_t *__restrict__ rows_dev, int n_tiles_n,
+                                                  int n_tiles, int k_split)
 {
     constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront (times 2 row tiles)
+    constexpr bool A_KMAJOR = MODE != MODE_DW, B_KMAJOR = MODE == MODE_DZ;
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDS_STRIDE];
     const int tid = (int)threadIdx.x;
@@ -117,28 +126,40 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int tile = (bid & 7) * per_xcd + (bid >> 3);
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM, n0 = (int64_t)(tile % n_tiles_n) * BN;
-    const int M = resolve_count(M_bound, M_dev);
+    // the row count of the sampled layer may live on the device: it bounds M, or K for dW
+    const int M = MODE == MODE_DW ? M_bound : resolve_count(M_bound, rows_dev);
+    const int K = MODE == MODE_DW ? resolve_count(K_bound, rows_dev) : K_bound;
     if (m0 >= M) return;  // the whole block leaves together, before any barrier
+    const int k_begin = MODE == MODE_DW ? (int)blockIdx.y * k_split : 0;
+    const int k_end = MODE == MODE_DW ? (k_begin + k_split < K ? k_begin + k_split : K) : K;
+    const int n_chunks = k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0;
 
     doublex4 acc[2][NT];
 #pragma unroll
     for (int r = 0; r < 2; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = doublex4{0.0, 0.0, 0.0, 0.0};
-    float4 ra[4], rb[BN / 32];
-    const int n_chunks = (K + BK - 1) / BK;
-    fetch_a<VA, FULL>(A, lda, M, K, m0, 0, tid, ra);
-    fetch_b<BN, FULL>(Bm, ldb, K, N, 0, n0, tid, rb);
-    stash<BN>(As[0], Bs[0], tid, ra, rb);
+    float4 ra[BM / 32], rb[BN / 32];
+    auto fetch = [&](int k0) {
+        if (A_KMAJOR) fetch_kmajor<BM, V, FULL>(A, lda, M, k_end, m0, k0, tid, ra);
+        else fetch_rmajor<BM, FULL>(A, lda, M, k_end, m0, k0, tid, ra);
+        if (B_KMAJOR) fetch_kmajor<BN, V, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb);
+        else fetch_rmajor<BN, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb);
+    };
+    auto stash = [&](int buf) {
+        stash_tile<BM, A_KMAJOR>(As[buf], tid, ra);
+        stash_tile<BN, B_KMAJOR>(Bs[buf], tid, rb);
+    };
+    if (n_chunks > 0) {
+        fetch(k_begin);
+        stash(0);
+    }
     __syncthreads();
     const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
     for (int c = 0; c < n_chunks; ++c) {
         const int cur = c & 1;
-        if (c + 1 < n_chunks) {
-            fetch_a<VA, FULL>(A, lda, M, K, m0, (c + 1) * BK, tid, ra);
-            fetch_b<BN, FULL>(Bm, ldb, K, N, (c + 1) * BK, n0, tid, rb);
-        }
+        if (c + 1 < n_chunks) fetch(k_begin + (c + 1) * BK);
         float av[2][8], bv[NT][8];
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
@@ -165,7 +186,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
             }
         }
         if (c + 1 < n_chunks) {
-            stash<BN>(As[cur ^ 1], Bs[cur ^ 1], tid, ra, rb);
+            stash(cur ^ 1);
             __syncthreads();
         }
     }
@@ -179,10 +200,26 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     const int64_t col = n0 + t * 16 + l16;
-                    if (FULL || col < N) C[row * ldc + col] = (float)acc[r][t][i];
+                    if (FULL || col < N) {
+                        if (MODE == MODE_DW)
+                            partial[((int64_t)blockIdx.y * M_bound + row) * N + col] = acc[r][t][i];
+                        else
+                            C[row * ldc + col] = (float)acc[r][t][i];
+                    }
                 }
             }
         }
+}
+
+// dW[i] = sum over the K parts, in ascending part order (fixed: the result does not depend on timing)
+__global__ __launch_bounds__(256) void gemm_reduce_parts(const double *__restrict__ partial, int parts, int64_t count,
+                                                         int N, float *__restrict__ C, int64_t ldc)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    double s = 0.0;
+    for (int p = 0; p < parts; ++p) s += partial[(int64_t)p * count + i];
+    C[(i / N) * ldc + (i % N)] = (float)s;
 }
 
 static int widest(const float *p, int64_t ld)
@@ -193,22 +230,53 @@ static int widest(const float *p, int64_t ld)
 }
 
 template <int BN>
-static void launch_gemm(const float *Z, int64_t ldz, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *H,
-                        int64_t ldh, hipStream_t st)
+static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *H,
+                       int64_t ldh, hipStream_t st)
 {
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8));
     const int va = widest(Z, ldz);
     const bool full = !M_dev && M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;
+    double *none = nullptr;
     if (full)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
     else if (va == 4)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
     else if (va == 2)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
     else
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, M, M_dev, N, K, tn, n_tiles);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
+}
+
+template <int BN>
+static void launch_dz(const float *G, int64_t ldg, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *dZ,
+                      int64_t lddz, hipStream_t st)
+{
+    const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    const int n_tiles = tm * tn;
+    const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8));
+    const int v = widest(G, ldg) == 4 && widest(W, ldw) == 4 ? 4 : 1;
+    double *none = nullptr;
+    if (v == 4)
+        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 4, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0);
+    else
+        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 1, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0);
+}
+
+// Parts of the reduction dimension for dW = Z^T G with `rows` rows: enough blocks to fill the device,
+// each part a multiple of the K chunk.
+static void dw_split(int rows, int tiles, int *parts, int *k_split)
+{
+    int want = (512 + tiles - 1) / tiles;
+    const int max_parts = (rows + BK - 1) / BK;
+    if (want > max_parts) want = max_parts;
+    if (want < 1) want = 1;
+    int ks = ((rows + want - 1) / want + BK - 1) / BK * BK;
+    if (ks < BK) ks = BK;
+    *k_split = ks;
+    *parts = (rows + ks - 1) / ks;
+    if (*parts < 1) *parts = 1;
 }
 
 }  // namespace csgs
@@ -225,9 +293,61 @@ extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int
     // narrow column tiles when wide ones would leave fewer than two blocks per compute unit
     const int64_t wide_tiles = tm * (((int64_t)Nout + 63) / 64);
     if (wide_tiles >= 512 && Nout > 32)
-        launch_gemm<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
+        launch_fwd<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
     else
-        launch_gemm<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
+        launch_fwd<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+extern "C" int csgs_layer_gemm_grad_z(const float *G, int64_t ldg, int32_t M, const int32_t *M_dev, int32_t Nout, const float *W,
+                                      int64_t ldw, int32_t K, float *dZ, int64_t lddz, void *stream)
+{
+    if (!G || !W || !dZ || M <= 0 || K <= 0 || Nout <= 0 || ldg < Nout || ldw < Nout || lddz < K) return CSGS_EINVAL;
+    const int64_t tm = ((int64_t)M + BM - 1) / BM;
+    if (tm * (((int64_t)K + 31) / 32) > 0x3FFFFFFF) return CSGS_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    // output [M x K]; the reduction runs over the Nout columns of G
+    const int64_t wide_tiles = tm * (((int64_t)K + 63) / 64);
+    if (wide_tiles >= 512 && K > 32)
+        launch_dz<64>(G, ldg, M, M_dev, Nout, W, ldw, K, dZ, lddz, st);
+    else
+        launch_dz<32>(G, ldg, M, M_dev, Nout, W, ldw, K, dZ, lddz, st);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+extern "C" size_t csgs_layer_gemm_grad_w_scratch_bytes(int32_t M, int32_t K, int32_t Nout)
+{
+    if (M <= 0 || K <= 0 || Nout <= 0) return 0;
+    const int tiles = ((K + BM - 1) / BM) * ((Nout + 31) / 32);
+    int parts, ks;
+    dw_split(M, tiles, &parts, &ks);
+    return (size_t)parts * (size_t)K * (size_t)Nout * sizeof(double);
+}
+
+extern "C" int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M, const int32_t *M_dev,
+                                      int32_t K, int32_t Nout, float *dW, int64_t lddw, void *scratch, size_t scratch_bytes,
+                                      void *stream)
+{
+    if (!Z || !G || !dW || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldg < Nout || lddw < Nout || !scratch ||
+        ((uintptr_t)scratch & 7))
+        return CSGS_EINVAL;
+    if (scratch_bytes < csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout)) return CSGS_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // kernel terms: output [K x Nout], reduction over the M rows (their count may live on the device)
+    const int tm = (K + BM - 1) / BM, tn = (Nout + 31) / 32;
+    const int n_tiles = tm * tn;
+    int parts, ks;
+    dw_split(M, n_tiles, &parts, &ks);
+    const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), (unsigned)parts);
+    float *none = nullptr;
+    CSGS_LAUNCH(K_GEMM_DW, (gemm_f32_k<32, MODE_DW, 1, false>), grid, dim3(256), st, Z, ldz, G, ldg, none, (int64_t)0,
+                (double *)scratch, K, Nout, M, M_dev, tn, n_tiles, ks);
+    CSGS_LAUNCH_CHECK();
+    const int64_t count = (int64_t)K * Nout;
+    CSGS_LAUNCH(K_GEMM_DW_REDUCE, gemm_reduce_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), st,
+                (const double *)scratch, parts, count, Nout, dW, lddw);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

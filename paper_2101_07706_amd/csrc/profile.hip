@@ -22,7 +22,8 @@ static const size_t kMaxPairs = 1 << 16;
 
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
-                                            "layer_gemm", "gather_rows", "fill_zero", "copy"};
+                                            "layer_gemm", "gather_rows", "gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce",
+                                            "adjT_count", "adjT_prefix", "adjT_fill", "aggregate_grad", "fill_zero", "copy"};
 
 bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {

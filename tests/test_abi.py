@@ -74,9 +74,21 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.csgs_aggregate(z, z, z, 1, z, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
     assert L.csgs_layer_gemm(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_gather_rows(z, 1, 1, 1, 0, z, 1, z, z, 1, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm_grad_w(z, 1, z, 1, 1, z, 1, 1, z, 1, z, 0, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm_grad_z(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
+    assert L.csgs_aggregate_grad(z, z, z, 1, 1, z, 1, z, z, 1, 1, z, 1, z, 1, z, 0, z) == csgs.EINVAL
     assert L.csgs_workspace_init(None, z) == csgs.EINVAL
     ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0, 0, 0, 0)
     assert L.csgs_workspace_init(C.byref(ws), z) == csgs.EINVAL           # null base
+
+
+def test_gradient_scratch_sizing():
+    w = csgs.csgs_layer_gemm_grad_w_scratch_bytes
+    assert w(0, 1, 1) == 0 and w(1, 0, 1) == 0
+    assert w(8192, 256, 256) % (256 * 256 * 8) == 0 and 0 < w(8192, 256, 256) <= 64 * 256 * 256 * 8
+    assert w(10, 256, 256) == 256 * 256 * 8                     # fewer rows than one K chunk: a single part
+    a = csgs.csgs_aggregate_grad_scratch_bytes
+    assert a(0, 10) == 0 and a(10, 0) == 0 and 0 < a(8192, 1000) < a(8192, 100000) and a(100, 1000) % 256 == 0
 
 
 def test_error_strings():

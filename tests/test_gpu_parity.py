@@ -705,3 +705,136 @@ def test_four_call_sequences_side_by_side(dev):
             np.testing.assert_array_equal(lb.adj_rowptr[:len(S) + 1].cpu().numpy(), sm.adj_rowptr)
             np.testing.assert_array_equal(lb.adj_col[:sm.adj_nnz].cpu().numpy(), sm.adj_col)
             S = sm.S_next
+
+
+# ---------------------------------------------------------------- gradients of a layer
+def _scratch(nbytes, dev):
+    return torch.empty(max(nbytes, 256) // 8 + 32, dtype=torch.int64, device=dev)
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (33, 17, 5), (700, 96, 80), (4096, 300, 512), (8192, 256, 256), (7001, 100, 256),
+                                   (5000, 256, 47)])
+def test_layer_gemm_gradients(dev, M, K, N):
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(M + K + N)
+    Z = rng.standard_normal((M, K)).astype(np.float32)
+    G = rng.standard_normal((M, N)).astype(np.float32)
+    W = rng.standard_normal((K, N)).astype(np.float32)
+    Zd, Gd, Wd = (torch.from_numpy(a).to(dev) for a in (Z, G, W))
+    dW = torch.full((K, N), float("nan"), dtype=torch.float32, device=dev)
+    dZ = torch.full((M, K), float("nan"), dtype=torch.float32, device=dev)
+    scratch = _scratch(csgs.csgs_layer_gemm_grad_w_scratch_bytes(M, K, N), dev)
+    csgs.csgs_layer_gemm_grad_w(Zd, Gd, dW, scratch)
+    csgs.csgs_layer_gemm_grad_z(Gd, Wd, dZ)
+    torch.cuda.synchronize()
+    # tolerances as for the forward product, scaled to the length of the sums (dW adds M terms of O(1))
+    chain.assert_close(dW.cpu().numpy(), oracle.layer_gemm_grad_w(Z, G), chain.RTOL, chain.ATOL * max(1.0, M ** 0.5 / 8), "dW")
+    chain.assert_close(dZ.cpu().numpy(), oracle.layer_gemm_grad_z(G, W), chain.RTOL, chain.ATOL, "dZ")
+    if M > 40:   # device row count below the capacity
+        m = M - 37
+        cnt = torch.tensor([m], dtype=torch.int32, device=dev)
+        dW.fill_(float("nan"))
+        dZ.fill_(float("nan"))
+        csgs.csgs_layer_gemm_grad_w(Zd, Gd, dW, scratch, M_dev=cnt)
+        csgs.csgs_layer_gemm_grad_z(Gd, Wd, dZ, M_dev=cnt)
+        torch.cuda.synchronize()
+        chain.assert_close(dW.cpu().numpy(), oracle.layer_gemm_grad_w(Z[:m], G[:m]), chain.RTOL,
+                           chain.ATOL * max(1.0, M ** 0.5 / 8), "dW with M_dev")
+        chain.assert_close(dZ[:m].cpu().numpy(), oracle.layer_gemm_grad_z(G[:m], W), chain.RTOL, chain.ATOL, "dZ with M_dev")
+        assert bool(torch.isnan(dZ[m:]).all())
+
+
+@pytest.mark.parametrize("nS,nc,F,maxdeg,relu", [(1, 1, 4, 1, False), (300, 257, 64, 9, True), (2048, 1500, 256, 40, True),
+                                                 (500, 64, 100, 64, False), (3000, 3000, 33, 6, True)])
+def test_aggregate_gradient(dev, nS, nc, F, maxdeg, relu):
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(nS + nc + F)
+    deg = rng.integers(0, min(maxdeg, nc) + 1, nS)
+    if nS > 100:
+        deg[7] = min(nc, 700)                # a hub row
+    rp = np.zeros(nS + 1, np.int32)
+    np.cumsum(deg, out=rp[1:])
+    col = np.concatenate([np.sort(rng.choice(nc, d, replace=False)) for d in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    dZ = rng.standard_normal((nS, F)).astype(np.float32)
+    Hp = rng.standard_normal((nc, F)).astype(np.float32)
+    cap = max(len(col), 1) + 5
+    rpd, cold, vald = torch.from_numpy(rp).to(dev), torch.zeros(cap, dtype=torch.int32, device=dev), torch.zeros(cap, device=dev)
+    cold[:len(col)] = torch.from_numpy(col).to(dev)
+    vald[:len(col)] = torch.from_numpy(val).to(dev)
+    dH = torch.full((nc, F), float("nan"), dtype=torch.float32, device=dev)
+    scratch = _scratch(csgs.csgs_aggregate_grad_scratch_bytes(nc, cap), dev)
+    n_next = torch.tensor([nc], dtype=torch.int32, device=dev)
+    csgs.csgs_aggregate_grad(rpd, cold, vald, n_next, torch.from_numpy(dZ).to(dev), torch.from_numpy(Hp).to(dev) if relu else None,
+                             dH, scratch)
+    torch.cuda.synchronize()
+    want = oracle.aggregate_grad(rp, col, val, nc, dZ, Hp if relu else None)
+    chain.assert_close(dH.cpu().numpy(), want, chain.RTOL, chain.ATOL, "dH_prev")
+    # twice in a row on the same scratch (the counters are re-zeroed by the call itself)
+    dH.fill_(float("nan"))
+    csgs.csgs_aggregate_grad(rpd, cold, vald, n_next, torch.from_numpy(dZ).to(dev), torch.from_numpy(Hp).to(dev) if relu else None,
+                             dH, scratch)
+    torch.cuda.synchronize()
+    chain.assert_close(dH.cpu().numpy(), want, chain.RTOL, chain.ATOL, "dH_prev, second call")
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium"])
+def test_backward_chain(dev, name):
+    """Forward with device-side row counts, then the gradients of every layer bottom-up from a random
+    dL/dH of the top layer, all row counts left on the device; against the oracle's chain."""
+    from paper_2101_07706_amd import csgs
+    cfg, g, X, Ws, S0 = chain.config_inputs(name)
+    B, M = cfg.samples, len(Ws)
+    osteps = chain.oracle_chain(g, X, Ws, S0, cfg.skew, B, 1234 + cfg.seed, 0)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, cfg.skew, B, 1234 + cfg.seed, 0, device_counts=True)
+    chain.compare_chain(osteps, gsteps)
+    rng = np.random.default_rng(9)
+    G0 = rng.standard_normal(osteps[0].H.shape).astype(np.float32)
+    # oracle: layer 0 is the top (its rows are the batch); dL/dH of layer l+1 comes from layer l's input gradient
+    Go, want = G0, []
+    for l in range(M):
+        o = osteps[l]
+        W = Ws[M - 1 - l]
+        dW = oracle.layer_gemm_grad_w(o.Z, Go)
+        dZ = oracle.layer_gemm_grad_z(Go, W)
+        dH = None
+        if l < M - 1:
+            dH = oracle.aggregate_grad(o.sm.adj_rowptr, o.sm.adj_col, o.sm.adj_val, o.sm.n_next, dZ, osteps[l + 1].H)
+        want.append((dW, dZ, dH))
+        Go = dH
+    # GPU: capacity-sized arrays, device counts
+    Gd = torch.from_numpy(G0).to(dev)
+    for l in range(M):
+        gs, lb = gsteps[l], gsteps[l].lb
+        nS_cap = len(S0) if l == 0 else B
+        nS_dev = None if l == 0 else gsteps[l - 1].lb.n_next
+        Wd = torch.from_numpy(Ws[M - 1 - l]).to(dev)
+        K, N = Wd.shape
+        Zfull = gs.Z._base if gs.Z._base is not None else gs.Z          # the capacity-sized buffer behind the view
+        Zfull = Zfull[:nS_cap]
+        Gfull = torch.zeros((nS_cap, N), dtype=torch.float32, device=dev)
+        Gfull[:Gd.shape[0]] = Gd
+        dW = torch.full((K, N), float("nan"), dtype=torch.float32, device=dev)
+        dZ = torch.full((nS_cap, K), float("nan"), dtype=torch.float32, device=dev)
+        sw = _scratch(csgs.csgs_layer_gemm_grad_w_scratch_bytes(nS_cap, K, N), dev)
+        csgs.csgs_layer_gemm_grad_w(Zfull, Gfull, dW, sw, M_dev=nS_dev)
+        csgs.csgs_layer_gemm_grad_z(Gfull, Wd, dZ, M_dev=nS_dev)
+        torch.cuda.synchronize()
+        n_rows = len(osteps[l].S)
+        tol_scale = max(1.0, n_rows ** 0.5 / 8) * max(1.0, float(np.abs(want[l][0]).max()))
+        chain.assert_close(dW.cpu().numpy(), want[l][0], chain.RTOL, chain.ATOL * tol_scale, f"layer {l} dW")
+        chain.assert_close(dZ[:n_rows].cpu().numpy(), want[l][1], chain.RTOL, chain.ATOL * max(1.0, float(np.abs(want[l][1]).max())),
+                           f"layer {l} dZ")
+        if l < M - 1:
+            Hp = gsteps[l + 1].H
+            Hp = (Hp._base if Hp._base is not None else Hp)[:B]
+            dH = torch.full((B, K), float("nan"), dtype=torch.float32, device=dev)
+            sa = _scratch(csgs.csgs_aggregate_grad_scratch_bytes(B, lb.adj_col.numel()), dev)
+            csgs.csgs_aggregate_grad(lb.adj_rowptr[:nS_cap + 1], lb.adj_col, lb.adj_val, lb.n_next, dZ, Hp, dH, sa, nS_dev=nS_dev)
+            torch.cuda.synchronize()
+            m = osteps[l].sm.n_next
+            chain.assert_close(dH[:m].cpu().numpy(), want[l][2], chain.RTOL,
+                               chain.ATOL * max(1.0, float(np.abs(want[l][2]).max())), f"layer {l} dH_prev")
+            assert bool(torch.isnan(dH[m:]).all())
+            Gd = dH[:m]
+    say(f"[{name}] backward chain: {M} layers, |dW| max {[float(np.abs(w[0]).max()) for w in want]}")
