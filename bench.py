@@ -110,6 +110,65 @@ class Workload:
             H = Hn
         return H
 
+    def prepare_backward(self):
+        """Buffers for the gradients of every layer (dW, dZ, dH_prev, scratch), sized for the capacities."""
+        torch, csgs, M, B, dims = self.torch, self.csgs, self.M, self.B, self.dims
+        dev, n0 = self.dev, self.Sd[0].numel()
+        i8 = lambda nbytes: torch.empty(max(nbytes, 256) // 8 + 32, dtype=torch.int64, device=dev)
+        self.bw = []
+        for l in range(M):
+            K, N = dims[M - 1 - l]
+            cap = n0 if l == 0 else B
+            self.bw.append(dict(
+                cap=cap, dW=torch.empty((K, N), device=dev), dZ=torch.empty((cap, K), device=dev),
+                dH=torch.empty((B, K), device=dev) if l < M - 1 else None,
+                sw=i8(csgs.csgs_layer_gemm_grad_w_scratch_bytes(cap, K, N)),
+                sa=i8(csgs.csgs_aggregate_grad_scratch_bytes(B, self.lb_sets[0][l].adj_col.numel())) if l < M - 1 else None))
+        g = torch.Generator(device="cpu").manual_seed(5)
+        self.G_top = torch.randn((n0, dims[0][1] if M == 1 else dims[M - 1][1]), generator=g).to(dev)
+
+    def backward(self):
+        """Gradients of all layers for the batch whose forward pass is in lb_sets[0] / Zs / Hs: top layer
+        first, each layer's dH_prev is the next one's dL/dH; row counts stay on the device."""
+        csgs, M, B, lbs = self.csgs, self.M, self.B, self.lb_sets[0]
+        G = self.G_top
+        for l in range(M):
+            bw, lb = self.bw[l], lbs[l]
+            nS_dev = None if l == 0 else lbs[l - 1].n_next
+            Z, W = self.Zs[l][:bw["cap"]], self.Wd[M - 1 - l]
+            csgs.csgs_layer_gemm_grad_w(Z, G, bw["dW"], bw["sw"], M_dev=nS_dev)
+            csgs.csgs_layer_gemm_grad_z(G, W, bw["dZ"], M_dev=nS_dev)
+            if l < M - 1:
+                csgs.csgs_aggregate_grad(lb.adj_rowptr[:bw["cap"] + 1], lb.adj_col, lb.adj_val, lb.n_next, bw["dZ"],
+                                         self.Hs[l + 1][:B], bw["dH"], bw["sa"], nS_dev=nS_dev)
+                G = bw["dH"]
+
+    def measure_backward(self, steps):
+        """Backward pass alone, back to back on one stream, after one forward step; then per-kernel times."""
+        torch, csgs = self.torch, self.csgs
+        self.prepare_backward()
+        self.step(0)
+        for _ in range(3):
+            self.backward()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.backward()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        csgs.csgs_profile_enable(True)
+        for _ in range(steps):
+            self.backward()
+        torch.cuda.synchronize()
+        csgs.csgs_profile_enable(False)
+        prof = csgs.csgs_profile_collect()
+        sizes = [int(self.Sd[0].numel())] + [int(self.lb_sets[0][l].n_next.item()) for l in range(self.M - 1)]
+        flops = sum(4.0 * sizes[l] * self.dims[self.M - 1 - l][0] * self.dims[self.M - 1 - l][1] for l in range(self.M))
+        gemm_ms = sum(prof[k][0] for k in ("gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce") if k in prof)
+        return dict(ms_per_step=ms, gemm_TFLOPs=flops * steps / (gemm_ms * 1e-3) / 1e12,
+                    kernels={k: dict(avg_us=round(v[0] / v[1] * 1e3, 3), launches_per_step=v[1] / steps)
+                             for k, v in sorted(prof.items(), key=lambda kv: -kv[1][0])})
+
     def prepare_overlap(self):
         """Streams, events and, per buffer set, the step's library calls captured into two HIP graphs
         (sampling, compute).  What differs from step to step goes through device memory: the batch
@@ -370,6 +429,9 @@ def main():
                             ms_per_step=cpu_s / n_cpu * 1e3)
         log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
+    backward = wl.measure_backward(args.steps)
+    log(f"backward pass alone: {backward['ms_per_step']:.3f} ms/step, gradient GEMMs {backward['gemm_TFLOPs']:.1f} TFLOP/s")
+
     scaled = None
     if not args.no_scaled and args.scale == 1:
         del wl
@@ -404,7 +466,7 @@ def main():
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
-        roofline=roofline, cpu_baseline=cpu_baseline,
+        roofline=roofline, cpu_baseline=cpu_baseline, backward=backward,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
     print(json.dumps(out))
 

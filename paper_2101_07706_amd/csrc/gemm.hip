@@ -218,7 +218,15 @@ __global__ __launch_bounds__(256) void gemm_reduce_parts(const double *__restric
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
     double s = 0.0;
-    for (int p = 0; p < parts; ++p) s += partial[(int64_t)p * count + i];
+    int p = 0;
+    for (; p + 8 <= parts; p += 8) {   // eight loads in flight, added in ascending part order
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(p + u) * count + i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; p < parts; ++p) s += partial[(int64_t)p * count + i];
     C[(i / N) * ldc + (i % N)] = (float)s;
 }
 
