@@ -6,7 +6,11 @@
 // lane, and broadcast lane-to-lane.  Products are accumulated in double, in ascending edge order,
 // and rounded to float once: sampled rows carry 1/p_j discounts of 10^2..10^3, so near-cancelling
 // outputs would lose the 1e-5 absolute tolerance with a float accumulator; the kernel is bound
-// by memory traffic, so the wider adds are free.
+// by memory traffic, so the wider adds are free.  Rows with many kept edges (hubs) are taken by
+// whole blocks, dispatched first in the same launch.
+//
+// Also here: csgs_gather_rows (staging of the sampled remote feature rows) and csgs_aggregate_grad
+// (dH_prev = (P~^T dZ) .* [H_prev > 0]: the same kernel on a per-call transpose of P~).
 #include "common.hpp"
 
 namespace csgs {

@@ -238,17 +238,6 @@ __device__ inline T block_exclusive_scan(T v, T *lds /*[17]*/, T *block_total)
     return incl - v + lds[wave];
 }
 
-// first index in [0, n) with a[idx] >= key (n if none)
-__device__ inline int64_t lower_bound_i64(const int64_t *a, int64_t n, int64_t key)
-{
-    int64_t lo = 0, hi = n;
-    while (lo < hi) {
-        const int64_t m = (lo + hi) >> 1;
-        if (a[m] >= key) hi = m; else lo = m + 1;
-    }
-    return lo;
-}
-
 // First index in [0, n) with a[idx] >= key, found by the whole wavefront: every round the 64 lanes
 // probe the ends of 64 equal segments at once, so an array of 8192 entries takes 3 dependent loads
 // instead of 13.  All lanes must call it with the same arguments; all get the result.

@@ -1,4 +1,4 @@
-// csgs_sample_layer and csgs_remote_count.
+// csgs_draw_nodes, csgs_sampled_adjacency, csgs_sample_layer and csgs_remote_count.
 //
 // B draws with replacement from the skewed distribution (Section 4.1: the sampling is run B
 // times), deduplicated; inclusion probability p_j = 1 - (1 - q_j)^B (Eq. 8); sampled adjacency
@@ -7,18 +7,22 @@
 // Kernels:
 //   draw          one thread per draw: Philox4x32-10 word -> u = mulhi(r, total) -> first cdf
 //                 entry above u.  The top levels of the search run on a strided sample of the
-//                 CDF staged in LDS, the rest on the global array.  Hits are counted per
-//                 candidate position with integer atomics; first hits set a position bitmap.
-//   hits_fused    single pass over the position bitmap (tiles of 1024 words): per-tile count,
-//                 prefix over earlier tiles by decoupled look-back, then every thread emits the
-//                 hits of its words: S_next ascending, mult, p_incl, node -> rank table
+//                 CDF staged in LDS, the rest is an 8-ary search on the global array (seven
+//                 independent probes per round).  Hits are counted per candidate position with
+//                 integer atomics; first hits set a position bitmap.
+//   hits_fused    single pass over the position bitmap (tiles of 256 words): ordered list of
+//                 the tile's hits in LDS, prefix over earlier tiles by the single-pass scan
+//                 across blocks, then one thread per distinct hit: S_next ascending, mult,
+//                 p_incl, node -> rank table.  Everything but the output position is fetched
+//                 and computed while the prefix is being resolved.
 //   adj_fused     flat over the edges of S (same chunking as the weight scan), single pass: keep
 //                 = the target was sampled; the kept edges in flat order ARE the CSR of P~ (rows
-//                 in the order of S, columns ascending), so position = look-back prefix of the
-//                 chunk + popcount of earlier keep bits, and the row pointers are the positions
-//                 at the row starts.  The node -> rank table is never cleared: its entries carry the
-//                 tag of the call that wrote them
-//   remote_count  one block
+//                 in the order of S, columns ascending), so position = prefix of the chunk +
+//                 popcount of earlier keep bits, and the row pointers are the positions at the
+//                 row starts.  The node -> rank table is never cleared: its entries carry the
+//                 tag of the draw that wrote them.
+//   remote_count_k  S_next ascends and the local partition is one id range: two searches by a
+//                 whole wavefront place every element (see the kernel)
 #include <math.h>
 #include "common.hpp"
 #include "lookback.hpp"
