@@ -54,7 +54,7 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
                    __uint_as_float(v.y & 0xFFFF0000u)}};
 }
 
-constexpr int LONG_ROW = 32;    // rows with more kept edges than this go to the block-cooperative kernel
+constexpr int LONG_ROW = 32;    // rows with more kept edges than this are taken by whole blocks
 constexpr int UNR = 8;          // gathered rows in flight per lane
 constexpr int AGG_BLOCK = 1024; // threads per block: 16 wavefronts
 
@@ -166,7 +166,8 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
             maxlen = o > maxlen ? o : maxlen;
         }
     }
-    for (int32_t f0 = 0; f0 < F; f0 += G * V) {
+    {   // feature chunk blockIdx.y: wide rows are spread over several blocks instead of walked chunk by chunk
+        const int32_t f0 = (int32_t)blockIdx.y * G * V;
         const int32_t f = f0 + g * V;
         const bool active = f < F;  // F is a multiple of V (checked on the host)
         double acc[V];
@@ -223,7 +224,8 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
         const int32_t wbeg = beg + wave * share;
         const int32_t wend = (wbeg + share < end) ? wbeg + share : end;
         const int32_t len = wend > wbeg ? wend - wbeg : 0;
-        for (int32_t f0 = 0; f0 < F; f0 += WAVE * V) {
+        {
+            const int32_t f0 = (int32_t)blockIdx.y * WAVE * V;
             const int32_t f = f0 + lane * V;
             const bool active = f < F;
             double acc[V];
@@ -287,12 +289,15 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 {
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
-    // long-row blocks: about 128 rows each to look through, never more than 1024
-    int64_t lblocks = ((int64_t)nS + 127) / 128;
-    if (lblocks > 256) lblocks = 256;
+    // long-row blocks: about 16 rows each to look through (a block works its long rows off one after
+    // the other, so where most rows are long -- dense neighborhoods -- there must be many blocks),
+    // never more than 1024 rows
+    int64_t lblocks = ((int64_t)nS + 15) / 16;
+    if (lblocks > 2048) lblocks = 2048;
     if (lblocks < ((int64_t)nS + 1023) / 1024) lblocks = ((int64_t)nS + 1023) / 1024;
     const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
-    const dim3 grid((unsigned)(blocks + lblocks));
+    // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
+    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)((F + G * V - 1) / (G * V)));
     if (relu)
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
                     (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm);
