@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "csgs.h"
 #include "profile.hpp"
 
@@ -123,15 +124,15 @@ __host__ inline int open_workspace(csgs_workspace *d, int64_t n_nodes, int64_t n
 // 2048 threads and 160 KB of a compute unit.  That is the documented limit.
 __host__ inline int resident_grid(int per_cu)
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];   // compute units per device, 0 = not asked yet (zero-initialised)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 32 * per_cu;
-    if (cached[dev] == 0) {
-        int cus = 0;
+    int cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 32;
-        cached[dev] = cus;
+        cached[dev].store(cus, std::memory_order_relaxed);   // every thread would store the same value
     }
-    return per_cu * cached[dev];
+    return per_cu * cus;
 }
 
 // Degrees of the rows S, their exclusive prefix (w.eoff) and CSR starts (w.rowstart); stats may be

@@ -104,3 +104,33 @@ def test_profile_interface_without_launches():
     names = [L.csgs_profile_kernel_name(k).decode() for k in range(n)]
     assert len(set(names)) == n and "aggregate" in names and "layer_gemm" in names
     assert csgs.csgs_profile_collect() == {}
+
+
+def test_gradient_calls_reject_bad_arguments_before_any_launch():
+    L = csgs.lib()
+    z, p = C.c_void_p(0), C.c_void_p(4096)       # p: a non-null, aligned address that is never dereferenced on the host
+    # scratch too small
+    assert L.csgs_layer_gemm_grad_w(p, 8, p, 8, 64, z, 8, 8, p, 8, p, 16, z) == csgs.EWORKSPACE
+    assert L.csgs_aggregate_grad(p, p, p, 100, 10, z, 10, z, p, 8, 8, z, 0, p, 8, p, 16, z) == csgs.EWORKSPACE
+    # leading dimensions below the row width, misaligned scratch
+    assert L.csgs_layer_gemm_grad_z(p, 4, 16, z, 8, p, 8, 8, p, 8, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm_grad_w(p, 8, p, 8, 64, z, 8, 8, p, 8, C.c_void_p(4100), 1 << 20, z) == csgs.EINVAL
+    assert L.csgs_aggregate_grad(p, p, p, 100, 10, z, 10, z, p, 8, 8, z, 0, p, 8, C.c_void_p(4100), 1 << 20, z) == csgs.EINVAL
+
+
+def test_sampling_calls_reject_workspace_mismatch():
+    L = csgs.lib()
+    z, p = C.c_void_p(0), C.c_void_p(4096)
+    g = csgs.Graph(1000, 5000, 4096, 4096, 4096, 0, 500, 1.0)
+    ws = csgs.Workspace(4096, 1 << 30, 1000, 64, 64, 5000, 0, 0, 0, 0)
+    st = C.c_void_p(8192)
+    # more rows / draws than the workspace was sized for; a graph of another size
+    assert L.csgs_build_probs(C.byref(g), p, 65, z, 2.0, p, p, p, z, 1000, p, C.byref(ws), st, z) == csgs.EWORKSPACE
+    assert L.csgs_draw_nodes(1000, p, p, 1000, p, 65, 0, 0, z, 0, p, p, p, p, C.byref(ws), st, z) == csgs.EWORKSPACE
+    assert L.csgs_draw_nodes(999, p, p, 1000, p, 64, 0, 0, z, 0, p, p, p, p, C.byref(ws), st, z) == csgs.EINVAL
+    small = csgs.Workspace(4096, 1024, 1000, 64, 64, 5000, 0, 0, 0, 0)
+    assert L.csgs_build_probs(C.byref(g), p, 64, z, 2.0, p, p, p, z, 1000, p, C.byref(small), st, z) == csgs.EWORKSPACE
+    # no draw has run on this workspace yet
+    assert L.csgs_sampled_adjacency(C.byref(g), p, 10, z, p, p, p, 100, p, C.byref(ws), st, z) == csgs.EINVAL
+    # skew below 1, fixed-point range
+    assert L.csgs_build_probs(C.byref(g), p, 64, z, 0.5, p, p, p, z, 1000, p, C.byref(ws), st, z) == csgs.EINVAL
