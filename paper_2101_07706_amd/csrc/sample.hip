@@ -71,7 +71,7 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
     int64_t n = stats->n_cand;
     if (n > cand_cap) n = cand_cap;
     if (n <= 0) return;
-    const uint64_t total = cdf[n - 1];
+    const uint64_t total = stats->total;   // = cdf[n - 1], without waiting for a second dependent load
     if (total == 0) return;
     // top[i] = cdf[(i + 1) * stride - 1] for the i with that index inside the array
     const int64_t stride = (n + TOP - 1) / TOP;
@@ -115,8 +115,10 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
         lo += skip;  // entries ascend; cdf[hi] > u bounds the result by hi
         if (lo > hi) lo = hi;
     }
-    const uint32_t old = atomicAdd(&hit[lo], 1u);
-    if (old == 0) atomicOr((unsigned long long *)&cbitmap[lo >> 6], 1ull << (lo & 63));
+    // both updates are fire-and-forget (no returned value to wait for); setting an already set bit is harmless
+    (void)__hip_atomic_fetch_add(&hit[lo], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    (void)__hip_atomic_fetch_or((unsigned long long *)&cbitmap[lo >> 6], 1ull << (lo & 63), __ATOMIC_RELAXED,
+                                __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ cand_id,
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
         }
         return;
     }
-    const double total = (double)cdf[n - 1];
+    const double total = (double)stats->total;   // = cdf[n - 1]
     const uint64_t rank_tag = (call & 0xFFFFFFFFull) << 32;
     for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         // one bitmap word per thread -> ordered list of the tile's drawn positions in LDS
