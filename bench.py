@@ -357,6 +357,7 @@ def main():
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (batches sampled side by side)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
+    ap.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share); --gpus above 1 is not supported",
@@ -429,8 +430,10 @@ def main():
                             ms_per_step=cpu_s / n_cpu * 1e3)
         log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
-    backward = wl.measure_backward(args.steps)
-    log(f"backward pass alone: {backward['ms_per_step']:.3f} ms/step, gradient GEMMs {backward['gemm_TFLOPs']:.1f} TFLOP/s")
+    backward = None
+    if not args.no_backward:
+        backward = wl.measure_backward(args.steps)
+        log(f"backward pass alone: {backward['ms_per_step']:.3f} ms/step, gradient GEMMs {backward['gemm_TFLOPs']:.1f} TFLOP/s")
 
     scaled = None
     if not args.no_scaled and args.scale == 1:
