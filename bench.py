@@ -178,6 +178,7 @@ class Workload:
         torch = self.torch
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
         s_comp = torch.cuda.Stream()
+        self.S_all = torch.stack(self.Sd)        # all batches, resident: [n_batches, batch]
         sets = []
         for k in range(self.n_sets):
             s_samp = samplers[k % self.n_samplers]
@@ -198,7 +199,11 @@ class Workload:
                 try:
                     g_samp, g_comp = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
                     with torch.cuda.graph(g_samp, stream=s_samp):
+                        # the batch of this replay: row it_dev of the resident batch table; the next replay
+                        # of this set is n_sets batches later
+                        torch.index_select(self.S_all, 0, it_dev, out=S0.view(1, -1))
                         self.enqueue_sampling(S0, it_dev, self.lb_sets[k], self.wss[k % self.n_samplers])
+                        it_dev.add_(self.n_sets)
                     with torch.cuda.graph(g_comp, stream=s_comp):
                         self.enqueue_compute(self.lb_sets[k], S0.numel())
                 except Exception as e:      # said out loud and recorded in the JSON line; the calls are then issued one by one
@@ -209,6 +214,7 @@ class Workload:
             sets.append(dict(S0=S0, it=it_dev, sample=g_samp, compute=g_comp, H=H, s_samp=s_samp,
                              samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
         self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=self.dev)   # iteration numbers, resident
+        self.graph_it = [None] * self.n_sets     # iteration number each set's counter will use at its next replay
         self.overlap = dict(sets=sets, s_comp=s_comp)
 
     def step(self, it, sizes=None, overlap=False):
@@ -232,11 +238,15 @@ class Workload:
             with torch.cuda.stream(st["s_samp"]):
                 if st["used"]:
                     st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batch sampled into it was computed
-                st["S0"].copy_(self.Sd[it], non_blocking=True)
-                st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
+                k = it % self.n_sets
                 if st["sample"] is not None:
+                    if self.graph_it[k] != it:   # (re)seat the set's device counter; consecutive replays advance it themselves
+                        st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
                     st["sample"].replay()
+                    self.graph_it[k] = it + self.n_sets
                 else:
+                    st["S0"].copy_(self.Sd[it], non_blocking=True)
+                    st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
                     self.enqueue_sampling(st["S0"], st["it"], lbs, self.wss[(it % self.n_sets) % self.n_samplers])
                 st["samp_done"].record(st["s_samp"])
             with torch.cuda.stream(s_comp):
