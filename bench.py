@@ -301,6 +301,7 @@ class Workload:
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
         assert torch.equal(H, h_serial), "overlapped steps must give the serial result bit for bit"
+        assert all(int(lb.status.item()) == 0 for lbs in self.lb_sets for lb in lbs), "a status bit was set in the overlapped run"
         log(f"host enqueue {enqueue_ms:.3f} ms/step; one stream {serial_ms:.3f} ms/step; sampling and compute overlapped "
             f"{ms_per_step:.3f} ms/step")
         sizes = []
