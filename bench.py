@@ -411,7 +411,21 @@ def main():
     cms, ccnt = csgs.csgs_profile_collect()["copy"]
     copy_GBps = 2 * cbytes * ccnt / (cms * 1e-3) / 1e9
     del ca, cb
-    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write)")
+    # atomic-update yardstick: 64-bit adds to random entries of a table as large as the weight accumulators
+    table = torch.zeros(g.n_nodes, dtype=torch.int64, device=dev)
+    n_upd = 1 << 24
+    for _ in range(2):
+        csgs.csgs_calib_atomics(table, n_upd)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(True)
+    for _ in range(5):
+        csgs.csgs_calib_atomics(table, n_upd)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(False)
+    ams, acnt = csgs.csgs_profile_collect()["atomics"]
+    atomic_Gups = n_upd * acnt / (ams * 1e-3) / 1e9
+    del table
+    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s")
 
     wl = mk(cfg, args.steps + args.warmup)
     log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
@@ -421,6 +435,10 @@ def main():
     dominant = next(iter(res["kernels"]))
     roofline = roofline_of(res["kernels"], dominant, load_traffic(name))
     roofline["copy_kernel_GBps"] = copy_GBps
+    roofline["atomic_adds_Gps"] = atomic_Gups      # what bounds scan_edges: one such add per scanned edge
+    if "scan_edges" in res["kernels"]:
+        per_launch = res["per_step"]["edges_scanned"] / res["kernels"]["scan_edges"]["launches_per_step"]
+        roofline["scan_edges_adds_Gps"] = per_launch / (res["kernels"]["scan_edges"]["avg_us"] * 1e-6) / 1e9
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -341,6 +341,11 @@ int csgs_profile_collect(double *ms_sum /*host*/, int64_t *launches /*host*/);
  * known-size kernel against which hardware byte counters are calibrated. */
 int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* n_updates fire-and-forget 64-bit integer atomic adds (+1, device scope) to pseudo-random entries of
+ * `table` (n_table entries, device, 8-byte aligned, contents are modified): the yardstick for the
+ * weight scan of csgs_build_probs, which updates its per-node accumulators the same way. */
+int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_updates, void *stream);
+
 /* Static string for a CSGS_E* code. */
 const char *csgs_strerror(int code);
 

@@ -25,7 +25,7 @@ EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace
            "csgs_layer_gemm", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
-           "csgs_calib_copy"]
+           "csgs_calib_copy", "csgs_calib_atomics"]
 
 
 class CsgsError(RuntimeError):
@@ -94,6 +94,7 @@ def lib():
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
         L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.csgs_calib_atomics.argtypes = [vp, sz, sz, vp]
         L.csgs_profile_enable.argtypes = [C.c_int]
         L.csgs_profile_kernel_name.restype = C.c_char_p
         L.csgs_profile_kernel_name.argtypes = [C.c_int]
@@ -339,3 +340,8 @@ def csgs_profile_collect():
 def csgs_calib_copy(dst, src, stream=None):
     nbytes = src.numel() * src.element_size()
     _call("csgs_calib_copy", _ptr(dst), _ptr(src), nbytes, _stream(stream))
+
+
+def csgs_calib_atomics(table, n_updates, stream=None):
+    """n_updates atomic +1 on pseudo-random entries of `table` (an int64 tensor)."""
+    _call("csgs_calib_atomics", _ptr(table), table.numel(), n_updates, _stream(stream))

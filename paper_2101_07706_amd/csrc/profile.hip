@@ -23,7 +23,7 @@ static const size_t kMaxPairs = 1 << 16;
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce",
-                                            "adjT_count", "adjT_prefix", "adjT_fill", "aggregate_grad", "fill_zero", "copy"};
+                                            "adjT_count", "adjT_prefix", "adjT_fill", "aggregate_grad", "fill_zero", "copy", "atomics"};
 
 bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {
@@ -53,6 +53,18 @@ __global__ __launch_bounds__(256) void copy_k(const uint4 *__restrict__ src, uin
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < n16; i += stride) dst[i] = src[i];
 }
+// n fire-and-forget 64-bit integer atomic adds at device scope to pseudo-random entries of a table:
+// the yardstick for the weight scan, whose accumulators are updated the same way.
+__global__ __launch_bounds__(256) void atomics_k(unsigned long long *__restrict__ table, uint64_t n_table, uint64_t n)
+{
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        uint64_t h = (i + 1) * 0x9E3779B97F4A7C15ull;   // Fibonacci hashing: consecutive i land far apart
+        h ^= h >> 29;
+        (void)__hip_atomic_fetch_add(&table[h % n_table], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 }  // namespace csgs
 
 using namespace csgs::prof;
@@ -63,6 +75,17 @@ extern "C" int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *s
     const size_t n16 = bytes / 16;
     const unsigned blocks = (unsigned)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
     CSGS_LAUNCH(K_COPY, csgs::copy_k, dim3(blocks), dim3(256), (hipStream_t)stream, (const uint4 *)src, (uint4 *)dst, n16);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+extern "C" int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_updates, void *stream)
+{
+    if (!table || n_table == 0 || n_updates == 0 || ((uintptr_t)table & 7)) return CSGS_EINVAL;
+    const size_t want = (n_updates + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 16384 ? want : 16384);
+    CSGS_LAUNCH(K_ATOMICS, csgs::atomics_k, dim3(blocks), dim3(256), (hipStream_t)stream, (unsigned long long *)table,
+                (uint64_t)n_table, (uint64_t)n_updates);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
