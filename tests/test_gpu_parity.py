@@ -838,3 +838,16 @@ def test_backward_chain(dev, name):
             assert bool(torch.isnan(dH[m:]).all())
             Gd = dH[:m]
     say(f"[{name}] backward chain: {M} layers, |dW| max {[float(np.abs(w[0]).max()) for w in want]}")
+
+
+def test_calibration_kernels(dev):
+    """The two yardstick kernels do what their byte / update counts assume."""
+    from paper_2101_07706_amd import csgs
+    src = torch.arange(1 << 16, dtype=torch.int64, device=dev)
+    dst = torch.zeros_like(src)
+    csgs.csgs_calib_copy(dst, src)
+    table = torch.zeros(1000, dtype=torch.int64, device=dev)
+    csgs.csgs_calib_atomics(table, 123457)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert int(table.sum().item()) == 123457 and int(table.min().item()) > 0
