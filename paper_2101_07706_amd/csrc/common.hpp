@@ -56,6 +56,7 @@ struct Workspace {
     int64_t *rowstart;   // [nS]     rowptr[S[a]]
     uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
     uint64_t *rp_ts;     // scan state of the row tiles (1 sum per tile of ROW_TILE rows)
+    int2 *chunk_note;    // [chunk_cap] (first row, rows) of every edge chunk, left by the weight scan for the adjacency pass
     double *pdbl;        // [B]      inclusion probabilities in double
     int64_t *meta;       // [META_WORDS] what row_prefix resolved on the device: row count, weight shift, edge count
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
@@ -95,6 +96,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
     w.rp_tiles = (nS_max + ROW_TILE - 1) / ROW_TILE;
     w.rp_ts = (uint64_t *)take(scan_state_words(w.rp_tiles, 1) * 8);
+    w.chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
     w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
     w.rowstart = (int64_t *)take((size_t)nS_max * 8);
     w.pdbl = (double *)take((size_t)B_max * 8);
@@ -287,25 +289,44 @@ struct RowSlice {
 };
 
 // Called by all threads of the block (at least two wavefronts).  c0 < c1 <= eoff[nS].
+// `note` (nullable) points at this chunk's entry of the workspace's chunk table: with FROM_NOTE the
+// first row and row count are read from it (one load) instead of being searched for (four dependent
+// loads); otherwise they are searched for and, if `note` is given, left there for a later pass over
+// the same chunks.
+template <bool FROM_NOTE>
 __device__ inline void stage_slice(RowSlice &s, const int64_t *__restrict__ eoff, const int64_t *__restrict__ rowstart,
-                                   int32_t nS, int64_t c0, int64_t c1)
+                                   int32_t nS, int64_t c0, int64_t c1, int2 *note)
 {
     __syncthreads();  // previous chunk's readers are done
-    // the two searches run side by side, each by one whole wavefront (3 dependent loads for 8192
-    // rows where a per-thread binary search takes 14)
-    const int wave = (int)(threadIdx.x >> 6);
-    if (wave == 0) {
-        const int64_t lb0 = wave_lower_bound(eoff, (int64_t)nS + 1, c0);
-        if (lane_id() == 0) s.a_first = (int32_t)((eoff[lb0] == c0) ? lb0 : lb0 - 1);
-    } else if (wave == 1) {
-        const int64_t lb1 = wave_lower_bound(eoff, (int64_t)nS + 1, c1);
-        if (lane_id() == 0) s.R = (int32_t)lb1;  // turned into a count below
+    int64_t a_first, R;
+    if (FROM_NOTE) {
+        const int2 v = *note;
+        a_first = v.x;
+        R = v.y;
+        // a stale note (the caller skipped the scan that writes it) must not lead outside eoff / rowstart
+        if (a_first < 0) a_first = 0;
+        if (a_first > nS) a_first = nS;
+        if (R < 0) R = 0;
+        if (R > (int64_t)nS + 1 - a_first) R = (int64_t)nS + 1 - a_first;
+    } else {
+        // the two searches run side by side, each by one whole wavefront (3 dependent loads for 8192
+        // rows where a per-thread binary search takes 14)
+        const int wave = (int)(threadIdx.x >> 6);
+        if (wave == 0) {
+            const int64_t lb0 = wave_lower_bound(eoff, (int64_t)nS + 1, c0);
+            if (lane_id() == 0) s.a_first = (int32_t)((eoff[lb0] == c0) ? lb0 : lb0 - 1);
+        } else if (wave == 1) {
+            const int64_t lb1 = wave_lower_bound(eoff, (int64_t)nS + 1, c1);
+            if (lane_id() == 0) s.R = (int32_t)lb1;  // turned into a count below
+        }
+        __syncthreads();
+        a_first = s.a_first;
+        R = (int64_t)s.R - a_first;
+        __syncthreads();  // everyone has read the end index before it is replaced by the count
+        if (note && threadIdx.x == 0) *note = make_int2((int)a_first, (int)R);
     }
-    __syncthreads();
-    const int64_t a_first = s.a_first;
-    const int64_t R = (int64_t)s.R - a_first;
-    __syncthreads();  // everyone has read the end index before it is replaced by the count
     if (threadIdx.x == 0) {
+        s.a_first = (int32_t)a_first;
         s.R = (int32_t)R;
         s.in_lds = R <= SLICE_MAX;
     }

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                  int32_t *__restrict__ status)
+                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status)
 {
     __shared__ RowSlice slice;
     const int32_t nS = (int32_t)meta[META_ROWS];
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
     bool bad = false;
     for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
-        stage_slice(slice, eoff, rowstart, nS, c0, c1);
+        stage_slice<false>(slice, eoff, rowstart, nS, c0, c1, chunk_note + c0 / EDGE_TILE);
         const int32_t len = (int32_t)(c1 - c0);
 #pragma unroll
         for (int k = 0; k < EDGE_TILE / 256; ++k) {
@@ -474,7 +474,7 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
     rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
     if (rc != CSGS_OK) return rc;
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, w.meta, w.eoff,
-                w.rowstart, w.wtable, w.tileflag, status);
+                w.rowstart, w.wtable, w.tileflag, w.chunk_note, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,

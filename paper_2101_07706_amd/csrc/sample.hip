@@ -233,15 +233,17 @@ __device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, 
     return (e & 0xFFFFFFFF00000000ull) == rank_tag ? (int32_t)(e & 0xFFFFFFFFull) : 0;
 }
 
+template <bool FROM_NOTE>
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                  int64_t n_nodes, const int64_t *__restrict__ meta,
                                                  const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
                                                  const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
                                                  uint64_t *__restrict__ epoch, uint64_t *__restrict__ ts_mem, int64_t chunk_cap,
-                                                 int32_t *__restrict__ adj_rowptr, int32_t *__restrict__ adj_col,
-                                                 float *__restrict__ adj_val, int64_t adj_cap,
-                                                 int64_t *__restrict__ adj_nnz, int32_t *__restrict__ status)
+                                                 int2 *__restrict__ chunk_note, int32_t *__restrict__ adj_rowptr,
+                                                 int32_t *__restrict__ adj_col, float *__restrict__ adj_val,
+                                                 int64_t adj_cap, int64_t *__restrict__ adj_nnz,
+                                                 int32_t *__restrict__ status)
 {
     __shared__ RowSlice slice;
     __shared__ uint64_t s_mask[EDGE_TILE / 64];
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     for (int64_t t = blockIdx.x; t < n_chunks; t += gridDim.x) {
         const int64_t c0 = t * EDGE_TILE;
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
-        stage_slice(slice, eoff, rowstart, nS, c0, c1);
+        stage_slice<FROM_NOTE>(slice, eoff, rowstart, nS, c0, c1, FROM_NOTE ? chunk_note + t : nullptr);
         const int32_t len = (int32_t)(c1 - c0);
         // wave w owns positions [w * 256, w * 256 + 256): four 64-edge words
         int32_t rk[4];
@@ -439,9 +441,15 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
         const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
-    CSGS_LAUNCH(K_ADJ_FUSED, adj_fused, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
-                w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap,
-                adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status);
+    // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
+    if (reuse_offsets)
+        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
+                    w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
+                    adj_col, adj_val, adj_cap, adj_nnz, status);
+    else
+        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
+                    w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
+                    adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
