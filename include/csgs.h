@@ -130,6 +130,13 @@ size_t csgs_workspace_clean_bytes(int64_t n_nodes);
  * first use, and again after a call was aborted.  Host errors: CSGS_EINVAL, CSGS_EWORKSPACE. */
 int csgs_workspace_init(csgs_workspace *ws /*host*/, void *stream);
 
+/* Bounds the polls a block may spend waiting for another block's flag (polls < 0: the built-in
+ * limit, large enough for seconds of waiting).  For tests of the timeout path: with a tiny limit a
+ * wait that is not satisfied at once gives up, the call sets CSGS_ST_INTERNAL, its outputs are
+ * unspecified, and every kernel still ends normally with all accesses in bounds.  Afterwards
+ * csgs_workspace_init must be called again.  Host errors: CSGS_EINVAL, CSGS_EWORKSPACE. */
+int csgs_workspace_wait_limit(csgs_workspace *ws /*host*/, int64_t polls, void *stream);
+
 /* Host-only helper: the fixed-point parameters csgs_build_probs will use (see there).
  * shift and s_fx are host pointers, nullable.  Returns CSGS_EINVAL for nS <= 0, skew < 1 or
  * > 2^20, rownorm2_max <= 0; CSGS_ERANGE when fewer than 24 fraction bits would remain. */

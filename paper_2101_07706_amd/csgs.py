@@ -20,7 +20,7 @@ ST_CAND_OVERFLOW, ST_BAD_EDGE_VALUE, ST_EMPTY_CANDIDATES, ST_ADJ_OVERFLOW, ST_BA
 ST_EDGE_OVERFLOW, ST_INTERNAL = 32, 64
 F32, BF16 = 0, 1
 
-EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
+EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_workspace_wait_limit", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
            "csgs_layer_gemm", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
@@ -71,6 +71,7 @@ def lib():
         L.csgs_workspace_clean_bytes.restype = sz
         L.csgs_workspace_clean_bytes.argtypes = [i64]
         L.csgs_workspace_init.argtypes = [C.POINTER(Workspace), vp]
+        L.csgs_workspace_wait_limit.argtypes = [C.POINTER(Workspace), i64, vp]
         L.csgs_fixed_point.argtypes = [i32, f32, f32, C.POINTER(i32), C.POINTER(i64)]
         L.csgs_build_probs.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, i32, f32, vp, vp, vp, vp, i64, vp,
@@ -204,6 +205,10 @@ def make_workspace(buf, n_nodes, nS_max, B_max, edges_max) -> Workspace:
 
 def csgs_workspace_init(ws, stream=None):
     _call("csgs_workspace_init", C.byref(ws), _stream(stream))
+
+
+def csgs_workspace_wait_limit(ws, polls, stream=None):
+    _call("csgs_workspace_wait_limit", C.byref(ws), polls, _stream(stream))
 
 
 def csgs_fixed_point(nS, skew, rownorm2_max=1.0):

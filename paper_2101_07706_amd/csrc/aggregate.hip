@@ -347,14 +347,16 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
 __global__ __launch_bounds__(256) void adjT_count(const int32_t *__restrict__ adj_rowptr,
                                                   const int32_t *__restrict__ adj_col, int32_t nS_bound,
                                                   const int32_t *__restrict__ nS_dev, int32_t n_cols_bound,
-                                                  const int32_t *__restrict__ n_cols_dev, int32_t *__restrict__ counts)
+                                                  const int32_t *__restrict__ n_cols_dev, int64_t cap,
+                                                  int32_t *__restrict__ counts)
 {
     const int32_t nS = resolve_count(nS_bound, nS_dev), n_cols = resolve_count(n_cols_bound, n_cols_dev);
     const int lane = lane_id();
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     for (int64_t r = wave; r < nS; r += n_waves) {
-        const int32_t beg = adj_rowptr[r], end = adj_rowptr[r + 1];
+        const int32_t beg = adj_rowptr[r] < 0 ? 0 : adj_rowptr[r];
+        const int32_t end = adj_rowptr[r + 1] < cap ? adj_rowptr[r + 1] : (int32_t)cap;   // stay inside adj_col whatever the pointers say
         for (int32_t e = beg + lane; e < end; e += WAVE) {
             const int32_t c = adj_col[e];
             if (c >= 0 && c < n_cols) atomicAdd(&counts[c], 1);
@@ -408,7 +410,8 @@ __global__ __launch_bounds__(256) void adjT_fill(const int32_t *__restrict__ adj
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     for (int64_t r = wave; r < nS; r += n_waves) {
-        const int32_t beg = adj_rowptr[r], end = adj_rowptr[r + 1];
+        const int32_t beg = adj_rowptr[r] < 0 ? 0 : adj_rowptr[r];
+        const int32_t end = adj_rowptr[r + 1] < cap ? adj_rowptr[r + 1] : (int32_t)cap;
         for (int32_t e = beg + lane; e < end; e += WAVE) {
             const int32_t c = adj_col[e];
             if (c >= 0 && c < n_cols) {
@@ -547,7 +550,7 @@ extern "C" int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj
     CSGS_LAUNCH(K_FILL_ZERO, fill_zero_i32, dim3(zb), dim3(256), st, g.counts, (int64_t)n_cols);
     CSGS_LAUNCH_CHECK();
     const unsigned rb = (unsigned)(((int64_t)nS + 3) / 4 < 4096 ? ((int64_t)nS + 3) / 4 : 4096);   // 4 rows (wavefronts) per block
-    CSGS_LAUNCH(K_ADJT_COUNT, adjT_count, dim3(rb), dim3(256), st, adj_rowptr, adj_col, nS, nS_dev, n_cols, n_cols_dev, g.counts);
+    CSGS_LAUNCH(K_ADJT_COUNT, adjT_count, dim3(rb), dim3(256), st, adj_rowptr, adj_col, nS, nS_dev, n_cols, n_cols_dev, adj_cap, g.counts);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_ADJT_PREFIX, adjT_prefix, dim3(1), dim3(1024), st, g.counts, n_cols, n_cols_dev, g.colptr);
     CSGS_LAUNCH_CHECK();

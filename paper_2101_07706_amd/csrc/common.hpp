@@ -98,7 +98,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.rp_ts = (uint64_t *)take(scan_state_words(w.rp_tiles, 1) * 8);
     w.chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
     w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
-    w.rowstart = (int64_t *)take((size_t)nS_max * 8);
+    w.rowstart = (int64_t *)take((size_t)(nS_max + 1) * 8);
     w.pdbl = (double *)take((size_t)B_max * 8);
     w.meta = (int64_t *)take(META_WORDS * 8);
     w.bytes = off;
@@ -303,17 +303,13 @@ __device__ inline void stage_slice(RowSlice &s, const int64_t *__restrict__ eoff
         const int2 v = *note;
         a_first = v.x;
         R = v.y;
-        // a stale note (the caller skipped the scan that writes it) must not lead outside eoff / rowstart
-        if (a_first < 0) a_first = 0;
-        if (a_first > nS) a_first = nS;
-        if (R < 0) R = 0;
-        if (R > (int64_t)nS + 1 - a_first) R = (int64_t)nS + 1 - a_first;
     } else {
         // the two searches run side by side, each by one whole wavefront (3 dependent loads for 8192
         // rows where a per-thread binary search takes 14)
         const int wave = (int)(threadIdx.x >> 6);
         if (wave == 0) {
-            const int64_t lb0 = wave_lower_bound(eoff, (int64_t)nS + 1, c0);
+            int64_t lb0 = wave_lower_bound(eoff, (int64_t)nS + 1, c0);
+            if (lb0 > nS) lb0 = nS;   // cannot happen with a sound prefix (c0 < eoff[nS])
             if (lane_id() == 0) s.a_first = (int32_t)((eoff[lb0] == c0) ? lb0 : lb0 - 1);
         } else if (wave == 1) {
             const int64_t lb1 = wave_lower_bound(eoff, (int64_t)nS + 1, c1);
@@ -325,6 +321,12 @@ __device__ inline void stage_slice(RowSlice &s, const int64_t *__restrict__ eoff
         __syncthreads();  // everyone has read the end index before it is replaced by the count
         if (note && threadIdx.x == 0) *note = make_int2((int)a_first, (int)R);
     }
+    // A prefix broken by a failed wait, or a stale note (the caller skipped the scan that writes it),
+    // must not lead outside eoff / rowstart: rows [a_first, a_first + R) stay within [0, nS].
+    if (a_first < 0) a_first = 0;
+    if (a_first > nS) a_first = nS;
+    if (R < 0) R = 0;
+    if (R > (int64_t)nS + 1 - a_first) R = (int64_t)nS + 1 - a_first;
     if (threadIdx.x == 0) {
         s.a_first = (int32_t)a_first;
         s.R = (int32_t)R;

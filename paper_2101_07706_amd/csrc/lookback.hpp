@@ -20,9 +20,10 @@
 //     block id, so the owners of all lower tiles were dispatched earlier and run or have finished;
 //   - a grid of at most resident_grid() blocks, all resident at once, block b taking tiles b,
 //     b + grid, ... in ascending order (used when the tile count is known only on the device).
-// Each poll loop is also bounded by LOOKBACK_SPIN_LIMIT; on a timeout (which would need another
-// workload to keep lower blocks off the device for seconds) the block sets CSGS_ST_INTERNAL and
-// carries on with a zero prefix; all stores are capacity-checked.
+// Each poll loop is also bounded (LOOKBACK_SPIN_LIMIT polls, or what csgs_workspace_wait_limit set);
+// on a timeout (which would need another workload to keep lower blocks off the device for seconds)
+// the block sets CSGS_ST_INTERNAL and carries on with a zero prefix; every store is
+// capacity-checked and every edge address derived from a prefix is checked against the graph.
 //
 // Memory ordering.  Tile sums and flags are exchanged only through device-scope relaxed atomic
 // loads and stores, which the hardware serves at the memory-side cache shared by all XCDs, so they
@@ -47,9 +48,15 @@ constexpr int LOOKBACK_SPIN_LIMIT = 1 << 22;
 // words of Workspace::epoch
 constexpr int EPOCH_CALLS = 0;   // library calls completed on this workspace
 constexpr int EPOCH_DRAW = 1;    // value of (calls + 1) during the latest draw: tags the rank table
+constexpr int EPOCH_WAIT = 2;    // 0, or 1 + the number of polls a wait may take (set through csgs_workspace_wait_limit)
 // one tag space per scan-state region, so the kernels of one call never mistake each other's flags
 enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4 };
 
+__device__ inline int wait_limit(const uint64_t *epoch)
+{
+    const uint64_t v = epoch[EPOCH_WAIT];
+    return v ? (int)(v - 1ull) : LOOKBACK_SPIN_LIMIT;
+}
 __device__ inline unsigned long long call_number(const uint64_t *epoch) { return epoch[EPOCH_CALLS] + 1ull; }
 __device__ inline unsigned long long call_tag(unsigned long long call, int slot) { return call * 16ull + (unsigned long long)slot; }
 
@@ -78,7 +85,8 @@ constexpr int LB_GROUP = 64;
 template <int NV>
 struct TileState {
     unsigned long long *flag, *agg, *gflag, *gagg, *pflag, *gpre;
-    __device__ TileState(uint64_t *mem, int64_t tiles)
+    int limit;   // polls a wait may take
+    __device__ TileState(uint64_t *mem, int64_t tiles, int poll_limit) : limit(poll_limit)
     {
         const int64_t groups = tiles / LB_GROUP + 2;
         flag = (unsigned long long *)mem;
@@ -91,11 +99,11 @@ struct TileState {
 };
 
 // Waits (bounded, with growing pauses) until *p carries `tag`; returns false on a timeout.
-__device__ inline bool wait_tag(const unsigned long long *p, unsigned long long tag)
+__device__ inline bool wait_tag(const unsigned long long *p, unsigned long long tag, int limit)
 {
     unsigned long long f = ld_relaxed(p);
     int spins = 0;
-    while (f != tag && spins < LOOKBACK_SPIN_LIMIT) {
+    while (f != tag && spins < limit) {
         if (spins < 4) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(16);
         f = ld_relaxed(p);
         ++spins;
@@ -138,7 +146,7 @@ __device__ inline void lookback_resolve(const TileState<NV> &ts, unsigned long l
         {
             const bool mine = lane < r;
             const long long j = g * LB_GROUP + lane;
-            if (mine) ok = wait_tag(&ts.flag[j], tag);
+            if (mine) ok = wait_tag(&ts.flag[j], tag, ts.limit);
 #pragma unroll
             for (int v = 0; v < NV; ++v) run[v] = wave_sum((mine && ok) ? ld_relaxed(&ts.agg[j * NV + v]) : 0ull);
         }
@@ -157,7 +165,7 @@ __device__ inline void lookback_resolve(const TileState<NV> &ts, unsigned long l
                 const long long gj = g0 + lane;
                 const bool mine = gj < g;
                 bool okg = true;
-                if (mine) okg = wait_tag(&ts.gflag[gj], tag);
+                if (mine) okg = wait_tag(&ts.gflag[gj], tag, ts.limit);
                 ok = ok && okg;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) pre[v] += wave_sum((mine && okg) ? ld_relaxed(&ts.gagg[gj * NV + v]) : 0ull);
@@ -169,7 +177,7 @@ __device__ inline void lookback_resolve(const TileState<NV> &ts, unsigned long l
             }
         } else {
             bool okp = true;
-            if (lane == 0) okp = wait_tag(&ts.pflag[g], tag);
+            if (lane == 0) okp = wait_tag(&ts.pflag[g], tag, ts.limit);
             ok = ok && okp;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
     __shared__ int64_t lds[17];
     __shared__ int32_t s_deg[RP_TILE];
     __shared__ unsigned long long s_lb[1];
-    const TileState<1> ts(ts_mem, ts_tiles);
+    const TileState<1> ts(ts_mem, ts_tiles, wait_limit(epoch));
     const unsigned long long tag = call_tag(call_number(epoch), SLOT_ROWS);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
     int64_t n_tiles = ((int64_t)nS + RP_TILE - 1) / RP_TILE;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
 }
 
 __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                  int64_t n_nodes, const int64_t *__restrict__ meta,
+                                                  int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
@@ -135,6 +135,10 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
             if (x >= len) break;
             int32_t r;
             const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
+            if (e < 0 || e >= nnz) {   // only after a failed wait in the prefix kernel: stay inside the graph
+                bad = true;
+                continue;
+            }
             const int32_t c = colidx[e];
             const float v = val[e];
             if (!isfinite(v) || c < 0 || c >= n_nodes) {
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
     if (r != LB_GROUP - 1 && t != n_tiles - 1) return;
     const int64_t g = t / LB_GROUP;
     bool ok = true;
-    if (lane < r) ok = wait_tag(&cand_flag[g * LB_GROUP + lane], tag);
+    if (lane < r) ok = wait_tag(&cand_flag[g * LB_GROUP + lane], tag, wait_limit(epoch));
     unsigned long long sum[3];
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
@@ -435,6 +439,22 @@ extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
     return CSGS_OK;
 }
 
+namespace csgs {
+__global__ void set_word(uint64_t *p, uint64_t v) { *p = v; }
+}  // namespace csgs
+
+extern "C" int csgs_workspace_wait_limit(csgs_workspace *ws, int64_t polls, void *stream)
+{
+    if (!ws) return CSGS_EINVAL;
+    Workspace w;
+    const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
+    if (rc != CSGS_OK) return rc;
+    const uint64_t v = polls < 0 ? 0ull : (uint64_t)(polls > 0x7FFFFFF0ll ? 0x7FFFFFF0ll : polls) + 1ull;
+    CSGS_LAUNCH(K_FILL_ZERO, csgs::set_word, dim3(1), dim3(1), (hipStream_t)stream, w.epoch + EPOCH_WAIT, v);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
 // Fixed-point parameters.  shift = min(52, 61 - ceil(log2 nS) - ceil(log2 s_fx) - ceil(log2 rmax)):
 // the skewed total is at most nS * rmax * 2^shift * s_fx plus rounding slack, below 2^63.
 extern "C" int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift, int64_t *s_fx)
@@ -473,7 +493,7 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
     const int32_t shift_base = shift_base_for(s_fx, g->rownorm2_max);
     rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
     if (rc != CSGS_OK) return rc;
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, w.meta, w.eoff,
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, w.meta, w.eoff,
                 w.rowstart, w.wtable, w.tileflag, w.chunk_note, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,

@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
     __shared__ uint32_t lds[17];
     __shared__ unsigned long long s_lb[1];
     __shared__ uint16_t s_list[HIT_TILE_WORDS * 64];   // drawn positions of the tile, ascending
-    const TileState<1> ts(ts_mem, ts_tiles);
+    const TileState<1> ts(ts_mem, ts_tiles, wait_limit(epoch));
     const unsigned long long call = call_number(epoch);
     const unsigned long long tag = call_tag(call, SLOT_HITS);
     int64_t n = stats->n_cand;
@@ -235,7 +235,7 @@ __device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, 
 
 template <bool FROM_NOTE>
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                 int64_t n_nodes, const int64_t *__restrict__ meta,
+                                                 int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
                                                  const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
                                                  const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
@@ -251,11 +251,14 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     __shared__ unsigned long long s_lb[1];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    const TileState<1> ts(ts_mem, chunk_cap);
+    const TileState<1> ts(ts_mem, chunk_cap, wait_limit(epoch));
     const unsigned long long call = call_number(epoch);
     const unsigned long long tag = call_tag(call, SLOT_ADJ);
     const uint64_t rank_tag = (epoch[EPOCH_DRAW] & 0xFFFFFFFFull) << 32;
     const int32_t nS = (int32_t)meta[META_ROWS];
+    // Row pointers never exceed what adj_col / adj_val can hold: when the kept edges overflow the
+    // capacity (status bit), later kernels that walk the rows still stay inside the arrays.
+    const int64_t ptr_max = adj_cap < 0x7FFFFFFFll ? adj_cap : 0x7FFFFFFFll;
     int64_t E = meta[META_EDGES];
     int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
     bool overflow = false;
@@ -292,8 +295,12 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             if (x < len) {
                 int32_t r;
                 ea[k] = edge_address(slice, eoff, rowstart, c0, x, &r);
-                const int32_t c = colidx[ea[k]];
-                if (c >= 0 && c < n_nodes) rk[k] = rank_of(rank, c, rank_tag);
+                if (ea[k] >= 0 && ea[k] < nnz) {   // (an address outside the graph can only follow a failed wait)
+                    const int32_t c = colidx[ea[k]];
+                    if (c >= 0 && c < n_nodes) rk[k] = rank_of(rank, c, rank_tag);
+                } else {
+                    ea[k] = 0;
+                }
             }
             const uint64_t m = __ballot(rk[k] > 0);
             if (lane == 0) s_mask[wave * 4 + k] = m;
@@ -321,7 +328,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
             const int64_t off = slice.in_lds ? (int64_t)slice.off[r] : eoff[a_first + r] - c0;
             if (off >= 0 && off < len) {
                 const int64_t v = base + s_pre[off >> 6] + __popcll(s_mask[off >> 6] & ((1ull << (off & 63)) - 1ull));
-                adj_rowptr[a_first + r] = (int32_t)(v < 0x7FFFFFFFll ? v : 0x7FFFFFFFll);
+                adj_rowptr[a_first + r] = (int32_t)(v < ptr_max ? v : ptr_max);
             }
         }
         if (tile_cnt) {
@@ -339,7 +346,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         if (t == n_chunks - 1) {
             // rows that start at or after the last edge (trailing empty rows, and the end pointer)
             const int64_t total = base + tile_cnt;
-            const int32_t clamp = (int32_t)(total < 0x7FFFFFFFll ? total : 0x7FFFFFFFll);
+            const int32_t clamp = (int32_t)(total < ptr_max ? total : ptr_max);
             const int64_t first_tail = wave_lower_bound(eoff, (int64_t)nS + 1, E);
             for (int64_t a = first_tail + threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = clamp;
             if (threadIdx.x == 0) {
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(256) void remote_count_k(const int32_t *__restrict_
             } else {
                 const int32_t r = k < a ? k : k - n_local;
                 if (src_row) src_row[k] = -1 - r;
-                if (remote_ids) remote_ids[r] = j;
+                if (remote_ids && r >= 0 && r < n) remote_ids[r] = j;   // (r leaves [0, n) only if S_next does not ascend)
             }
         }
     }
@@ -444,11 +451,11 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
     if (reuse_offsets)
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
+                    g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
                     adj_col, adj_val, adj_cap, adj_nnz, status);
     else
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
+                    g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
                     adj_col, adj_val, adj_cap, adj_nnz, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;

@@ -851,3 +851,56 @@ def test_calibration_kernels(dev):
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     assert int(table.sum().item()) == 123457 and int(table.min().item()) > 0
+
+
+def test_failed_waits_end_normally_and_are_reported(dev):
+    """Timeout path of the waits between blocks, forced from the host: with a poll limit of zero a
+    wait that is not satisfied at once gives up.  Every kernel must still end (no hang, all accesses
+    in bounds), the status word must say so, and after csgs_workspace_init the same workspace must
+    give exact results again."""
+    from paper_2101_07706_amd import csgs, pipeline
+    cfg, g, X, Ws, S0 = chain.config_inputs("medium")
+    dg = pipeline.DeviceGraph(g, dev)
+    B = cfg.samples
+    ws = pipeline.Workspace(g.n_nodes, max(len(S0), B), B, g.nnz, dev)
+    lbs = [pipeline.LayerBuffers(max(len(S0), B), B, g.n_nodes, 4_000_000, dg.n_parts, dev) for _ in range(2)]
+    Sd = torch.from_numpy(S0).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    Z = torch.zeros((B, X.shape[1]), dtype=torch.float32, device=dev)
+    staged = torch.zeros((B, X.shape[1]), dtype=torch.float32, device=dev)
+
+    def run(it):
+        for lb in lbs:
+            lb.status.zero_()
+        pipeline.sample_step(dg, ws, Sd, cfg.skew, B, 7, it, 0, lbs[0])
+        pipeline.sample_step(dg, ws, lbs[0].S_next, cfg.skew, B, 7, it, 1, lbs[1], nS_dev=lbs[0].n_next)
+        pipeline.stage_remote_rows(lbs[1], Xd, staged)
+        csgs.csgs_aggregate(lbs[1].adj_rowptr[:B + 1], lbs[1].adj_col, lbs[1].adj_val, lbs[1].n_next,
+                            Xd[g.local_lo:g.local_hi], staged, lbs[1].src_row, False, Z, nS_dev=lbs[0].n_next)
+        torch.cuda.synchronize()
+        return [int(lb.status.item()) for lb in lbs]
+
+    def check_exact(it):
+        S = S0
+        for l in range(2):
+            pr = oracle.build_probs(g, S, cfg.skew)
+            sm = oracle.sample_layer(g, S, pr, B, 7, it, l)
+            assert int(lbs[l].n_next.item()) == sm.n_next
+            np.testing.assert_array_equal(lbs[l].S_next[:sm.n_next].cpu().numpy(), sm.S_next)
+            np.testing.assert_array_equal(lbs[l].adj_rowptr[:len(S) + 1].cpu().numpy(), sm.adj_rowptr)
+            S = sm.S_next
+
+    assert run(0) == [0, 0]
+    check_exact(0)
+    csgs.csgs_workspace_wait_limit(ws.desc, 0)
+    seen = 0
+    for it in range(1, 4):
+        st = run(it)            # must return: that is the test
+        seen |= st[0] | st[1]
+        csgs.csgs_workspace_init(ws.desc)
+        csgs.csgs_workspace_wait_limit(ws.desc, 0)
+    say(f"[waits] status bits seen with a poll limit of zero: {seen:#x}")
+    assert seen & csgs.ST_INTERNAL, "no wait gave up although none may poll"
+    csgs.csgs_workspace_init(ws.desc)            # also puts the built-in limit back
+    assert run(9) == [0, 0]
+    check_exact(9)
