@@ -488,9 +488,10 @@ def main():
         value=res["per_step"]["sampled_edges"] / (ms_per_step * 1e-3), unit="sampled edges/s",
         n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
         scaling="weak", vs_baseline=None,
-        dtype="bf16 features, f64 accumulate, f32 out" if bf16 else "f32 in/out, f64 accumulate", data="synthetic",
+        dtype="f64", data="synthetic",     # sums and products in double (vector ALU, fp64 matrix cores); weights and CDF in u64
         config=dict(workload=f"{name}: N={g.n_nodes}, nnz={g.nnz}, {cfg.n_parts} partitions, batch {cfg.batch}, "
                              f"{cfg.samples} samples/layer, {len(dims)} layers {dims}, skew {cfg.skew}",
+                    precision=("bf16 features, " if bf16 else "f32 features, ") + "u64 fixed-point weights and CDF, f64 accumulation, f32 outputs",
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
         schedule=f"sampling of consecutive batches on {args.samplers} streams (own workspace each), layer compute of all "
