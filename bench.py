@@ -173,7 +173,7 @@ class Workload:
         """Streams, events and, per buffer set, the step's library calls captured into two HIP graphs
         (sampling, compute).  What differs from step to step goes through device memory: the batch
         is copied into the set's batch buffer and the iteration number into a device word before
-        the sampling graph is replayed.  A kernel launch costs the host 4-5 us and a step has 31,
+        the sampling graph is replayed.  A kernel launch costs the host 4-5 us and a step has 28,
         so launching them one by one cannot keep three streams fed; a replay is one call."""
         torch = self.torch
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]

@@ -203,15 +203,29 @@ int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_
  *   adj_rowptr [nS+1], adj_col [adj_cap], adj_val [adj_cap], adj_nnz: out, CSR of P~ with rows in
  *            the order of S, adj_col = position in S_next (ascending within a row),
  *            adj_val = (float)((double)P_ij / p_j)
+ *   remote   nullable: also write the remote split of S_next (see csgs_remote_out)
  * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE.  Status bits: ADJ_OVERFLOW, EDGE_OVERFLOW.
  */
+/* Optional extra outputs of csgs_sample_layer: what csgs_remote_count (below) computes, produced by
+ * spare blocks of the adjacency kernel, so that a layer step is one launch shorter.  Host struct
+ * of device pointers; fields as the parameters of csgs_remote_count. */
+typedef struct csgs_remote_out {
+    int32_t local_lo, local_hi;
+    const int32_t *part_bounds; /* nullable */
+    int32_t P;
+    int64_t *remote_total;
+    int64_t *per_part;  /* nullable */
+    int32_t *src_row;   /* nullable */
+    int32_t *remote_ids; /* nullable */
+} csgs_remote_out;
+
 int csgs_sample_layer(const csgs_graph *g /*host*/, const int32_t *S, int32_t nS,
                       const int32_t *cand_id, const uint64_t *cdf, int64_t cand_cap,
                       const csgs_prob_stats *stats, int32_t B, uint64_t seed, uint64_t iter,
                       const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl, int32_t *n_next,
                       int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
-                      int64_t *adj_nnz, csgs_workspace *ws /*host*/, int32_t *status,
-                      void *stream);
+                      int64_t *adj_nnz, const csgs_remote_out *remote /*host, nullable*/,
+                      csgs_workspace *ws /*host*/, int32_t *status, void *stream);
 
 /*
  * The two halves of csgs_sample_layer, for samplers that draw once and then need the sampled

@@ -48,6 +48,13 @@ class Workspace(C.Structure):
                 ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("pad_", C.c_int32)]
 
 
+class RemoteOut(C.Structure):
+    """csgs_remote_out: where csgs_sample_layer leaves the remote split of the new node set."""
+    _fields_ = [("local_lo", C.c_int32), ("local_hi", C.c_int32), ("part_bounds", C.c_void_p), ("P", C.c_int32),
+                ("remote_total", C.c_void_p), ("per_part", C.c_void_p), ("src_row", C.c_void_p),
+                ("remote_ids", C.c_void_p)]
+
+
 class ProbStats(C.Structure):
     """csgs_prob_stats as laid out on the device (64 bytes)."""
     _fields_ = [("n_cand", C.c_int64), ("n_local", C.c_int64), ("n_remote", C.c_int64),
@@ -77,7 +84,7 @@ def lib():
         L.csgs_build_probs_auto.argtypes = [C.POINTER(Graph), vp, i32, vp, f32, i32, f32, vp, vp, vp, vp, i64, vp,
                                             C.POINTER(Workspace), vp, vp]
         L.csgs_sample_layer.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, i64, vp, i32, u64, u64, vp, u32,
-                                        vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
+                                        vp, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(RemoteOut), C.POINTER(Workspace), vp, vp]
         L.csgs_draw_nodes.argtypes = [i64, vp, vp, i64, vp, i32, u64, u64, vp, u32, vp, vp, vp, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_sampled_adjacency.argtypes = [C.POINTER(Graph), vp, i32, vp, vp, vp, vp, i64, vp, C.POINTER(Workspace), vp, vp]
         L.csgs_remote_count.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
@@ -231,12 +238,21 @@ def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, 
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
-                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None, iter_dev=None):
-    """iter_dev: device uint64 tensor holding the iteration number (then `it` is ignored)."""
+                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None, iter_dev=None, remote=None):
+    """iter_dev: device uint64 tensor holding the iteration number (then `it` is ignored).
+    remote: a RemoteOut (see make_remote_out): also write the remote split of S_next."""
     _call("csgs_sample_layer", C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
                                  _ptr(stats), B, seed, it, _ptr(iter_dev), layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
-                                 _ptr(adj_nnz), C.byref(ws), _ptr(status), _stream(stream))
+                                 _ptr(adj_nnz), None if remote is None else C.byref(remote), C.byref(ws), _ptr(status), _stream(stream))
+
+
+def make_remote_out(local_lo, local_hi, part_bounds, remote_total, per_part=None, src_row=None, remote_ids=None) -> RemoteOut:
+    dp = lambda t: None if t is None else t.data_ptr()
+    r = RemoteOut(local_lo, local_hi, dp(part_bounds), 0 if part_bounds is None else part_bounds.numel() - 1, dp(remote_total),
+                  dp(per_part), dp(src_row), dp(remote_ids))
+    r._keep = (part_bounds, remote_total, per_part, src_row, remote_ids)
+    return r
 
 
 def csgs_draw_nodes(n_nodes, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next, ws, status,

@@ -233,6 +233,62 @@ __device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, 
     return (e & 0xFFFFFFFF00000000ull) == rank_tag ? (int32_t)(e & 0xFFFFFFFFull) : 0;
 }
 
+// S_next ascends and the local partition is one id range, so the sampled remote nodes are the
+// entries before the first id >= lo and from the first id >= hi on: two searches give every
+// element its place, no scan needed.
+constexpr int REMOTE_BLOCKS = 64;
+
+struct RemoteArgs {
+    const int32_t *S_next, *n_next;
+    int32_t lo, hi;
+    const int32_t *part_bounds;
+    int32_t P;
+    int64_t *remote_total, *per_part;
+    int32_t *src_row, *remote_ids;
+    int32_t blocks;   // blocks of 256 threads that do this work (as leading blocks of another kernel: 0 = none)
+};
+
+// `block` of `n_blocks` blocks of 256 threads
+__device__ inline void remote_count_body(const RemoteArgs &r_, int32_t block, int32_t n_blocks)
+{
+    const int32_t *__restrict__ S_next = r_.S_next;
+    const int32_t lo = r_.lo, hi = r_.hi, P = r_.P;
+    const int32_t *__restrict__ part_bounds = r_.part_bounds;
+    int64_t *__restrict__ remote_total = r_.remote_total, *__restrict__ per_part = r_.per_part;
+    int32_t *__restrict__ src_row = r_.src_row, *__restrict__ remote_ids = r_.remote_ids;
+    int32_t n = *r_.n_next;
+    if (n < 0) n = 0;
+    const int32_t a = wave_lower_bound(S_next, n, lo);   // ids below the local range
+    const int32_t b = wave_lower_bound(S_next, n, hi);   // first id above it
+    const int32_t n_local = b - a;
+    const int32_t tid = (int32_t)(block * blockDim.x + threadIdx.x);
+    const int32_t stride = (int32_t)(n_blocks * blockDim.x);
+    if (tid == 0) *remote_total = (int64_t)(n - n_local);
+    if (src_row || remote_ids) {
+        for (int32_t k = tid; k < n; k += stride) {
+            const int32_t j = S_next[k];
+            if (k >= a && k < b) {
+                if (src_row) src_row[k] = j - lo;
+            } else {
+                const int32_t r = k < a ? k : k - n_local;
+                if (src_row) src_row[k] = -1 - r;
+                if (remote_ids && r >= 0 && r < n) remote_ids[r] = j;   // (r leaves [0, n) only if S_next does not ascend)
+            }
+        }
+    }
+    // partition p holds the ids between two lower bounds; one wavefront per partition
+    if (per_part) {
+        const int32_t wave = tid >> 6, n_waves = stride >> 6;
+        for (int32_t p = wave; p < P; p += n_waves) {
+            const int32_t c0 = wave_lower_bound(S_next, n, part_bounds[p]);
+            const int32_t c1 = wave_lower_bound(S_next, n, part_bounds[p + 1]);
+            if (lane_id() == 0) per_part[p] = (int64_t)(c1 > c0 ? c1 - c0 : 0);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void remote_count_k(RemoteArgs r) { remote_count_body(r, (int32_t)blockIdx.x, (int32_t)gridDim.x); }
+
 template <bool FROM_NOTE>
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                  int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
@@ -243,8 +299,16 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ adj_rowptr,
                                                  int32_t *__restrict__ adj_col, float *__restrict__ adj_val,
                                                  int64_t adj_cap, int64_t *__restrict__ adj_nnz,
-                                                 int32_t *__restrict__ status)
+                                                 int32_t *__restrict__ status, RemoteArgs rem)
 {
+    // The leading rem.blocks blocks split the new node set into local and remote (what
+    // csgs_remote_count does: it needs only S_next / n_next, complete since the previous kernel) so
+    // that a layer step is one launch shorter; they wait for nobody and nobody waits for them.
+    if ((int32_t)blockIdx.x < rem.blocks) {
+        remote_count_body(rem, (int32_t)blockIdx.x, rem.blocks);
+        return;
+    }
+    const int64_t bid = (int64_t)blockIdx.x - rem.blocks, n_bids = (int64_t)gridDim.x - rem.blocks;
     __shared__ RowSlice slice;
     __shared__ uint64_t s_mask[EDGE_TILE / 64];
     __shared__ int32_t s_pre[EDGE_TILE / 64 + 1];
@@ -268,7 +332,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         n_chunks = 0;
     }
     if (n_chunks == 0) {
-        if (blockIdx.x == 0) {
+        if (bid == 0) {
             for (int32_t a = threadIdx.x; a <= nS; a += blockDim.x) adj_rowptr[a] = 0;
             if (threadIdx.x == 0) {
                 *adj_nnz = 0;
@@ -279,7 +343,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         return;
     }
     // all blocks are resident; block b takes chunks b, b + grid, ... in ascending order
-    for (int64_t t = blockIdx.x; t < n_chunks; t += gridDim.x) {
+    for (int64_t t = bid; t < n_chunks; t += n_bids) {
         const int64_t c0 = t * EDGE_TILE;
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
         stage_slice<FROM_NOTE>(slice, eoff, rowstart, nS, c0, c1, FROM_NOTE ? chunk_note + t : nullptr);
@@ -358,46 +422,6 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     }
 }
 
-// S_next ascends and the local partition is one id range, so the sampled remote nodes are the
-// entries before the first id >= lo and from the first id >= hi on: two searches give every
-// element its place, no scan needed.
-__global__ __launch_bounds__(256) void remote_count_k(const int32_t *__restrict__ S_next,
-                                                      const int32_t *__restrict__ n_next, int32_t lo, int32_t hi,
-                                                      const int32_t *__restrict__ part_bounds, int32_t P,
-                                                      int64_t *__restrict__ remote_total,
-                                                      int64_t *__restrict__ per_part, int32_t *__restrict__ src_row,
-                                                      int32_t *__restrict__ remote_ids)
-{
-    const int32_t n = *n_next;
-    const int32_t a = wave_lower_bound(S_next, n, lo);   // ids below the local range
-    const int32_t b = wave_lower_bound(S_next, n, hi);   // first id above it
-    const int32_t n_local = b - a;
-    const int32_t tid = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    const int32_t stride = (int32_t)(gridDim.x * blockDim.x);
-    if (tid == 0) *remote_total = (int64_t)(n - n_local);
-    if (src_row || remote_ids) {
-        for (int32_t k = tid; k < n; k += stride) {
-            const int32_t j = S_next[k];
-            if (k >= a && k < b) {
-                if (src_row) src_row[k] = j - lo;
-            } else {
-                const int32_t r = k < a ? k : k - n_local;
-                if (src_row) src_row[k] = -1 - r;
-                if (remote_ids && r >= 0 && r < n) remote_ids[r] = j;   // (r leaves [0, n) only if S_next does not ascend)
-            }
-        }
-    }
-    // partition p holds the ids between two lower bounds; one wavefront per partition
-    if (per_part) {
-        const int32_t wave = tid >> 6, n_waves = stride >> 6;
-        for (int32_t p = wave; p < P; p += n_waves) {
-            const int32_t c0 = wave_lower_bound(S_next, n, part_bounds[p]);
-            const int32_t c1 = wave_lower_bound(S_next, n, part_bounds[p + 1]);
-            if (lane_id() == 0) per_part[p] = (int64_t)(c1 > c0 ? c1 - c0 : 0);
-        }
-    }
-}
-
 }  // namespace csgs
 using namespace csgs;
 
@@ -434,7 +458,8 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
 static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int32_t n_rows, const int32_t *n_rows_dev,
                                   bool reuse_offsets,
                                   int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
-                                  int64_t *adj_nnz, csgs_workspace *ws, int32_t *status, void *stream)
+                                  int64_t *adj_nnz, csgs_workspace *ws, int32_t *status, const RemoteArgs &rem,
+                                  void *stream)
 {
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !rows || n_rows <= 0 ||
         !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
@@ -449,14 +474,15 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
         if (rc2 != CSGS_OK) return rc2;
     }
     // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
+    const dim3 grid((unsigned)(resident_grid(2) + rem.blocks));
     if (reuse_offsets)
-        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
+        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
                     g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
-                    adj_col, adj_val, adj_cap, adj_nnz, status);
+                    adj_col, adj_val, adj_cap, adj_nnz, status, rem);
     else
-        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, dim3((unsigned)resident_grid(2)), dim3(256), st, g->colidx, g->val, g->n_nodes,
+        CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
                     g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
-                    adj_col, adj_val, adj_cap, adj_nnz, status);
+                    adj_col, adj_val, adj_cap, adj_nnz, status, rem);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -466,21 +492,30 @@ extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, 
                                       csgs_workspace *ws, int32_t *status, void *stream)
 {
     return sampled_adjacency_impl(g, rows, n_rows, n_rows_dev, false, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status,
-                                  stream);
+                                  RemoteArgs{}, stream);
 }
 
 extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
                                  const uint64_t *cdf, int64_t cand_cap, const csgs_prob_stats *stats, int32_t B, uint64_t seed,
                                  uint64_t iter, const uint64_t *iter_dev, uint32_t layer, int32_t *S_next, int32_t *mult, float *p_incl,
                                  int32_t *n_next, int32_t *adj_rowptr, int32_t *adj_col, float *adj_val,
-                                 int64_t adj_cap, int64_t *adj_nnz, csgs_workspace *ws, int32_t *status,
-                                 void *stream)
+                                 int64_t adj_cap, int64_t *adj_nnz, const csgs_remote_out *remote,
+                                 csgs_workspace *ws, int32_t *status, void *stream)
 {
     if (!g || !S || nS <= 0 || !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz) return CSGS_EINVAL;
+    RemoteArgs rem{};
+    if (remote) {
+        if (!remote->remote_total || remote->local_lo > remote->local_hi ||
+            (remote->per_part && (!remote->part_bounds || remote->P <= 0)))
+            return CSGS_EINVAL;
+        rem = RemoteArgs{S_next, n_next, remote->local_lo, remote->local_hi, remote->part_bounds,
+                         remote->per_part ? remote->P : 0, remote->remote_total, remote->per_part, remote->src_row,
+                         remote->remote_ids, REMOTE_BLOCKS};
+    }
     const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, iter_dev, layer, S_next, mult, p_incl,
                                    n_next, ws, status, stream);
     if (rc != CSGS_OK) return rc;
-    return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, stream);
+    return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, rem, stream);
 }
 
 extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo, int32_t local_hi,
@@ -489,10 +524,11 @@ extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, i
 {
     if (!S_next || !n_next || local_lo > local_hi || !remote_total) return CSGS_EINVAL;
     if (per_part && (!part_bounds || P <= 0)) return CSGS_EINVAL;
-    // the element count is known only on the device; 64 blocks of 256 cover the usual budgets in one
-    // sweep and stride over larger ones
-    CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(64), dim3(256), (hipStream_t)stream, S_next, n_next, local_lo, local_hi,
-                       part_bounds, per_part ? P : 0, remote_total, per_part, src_row, remote_ids);
+    // the element count is known only on the device; REMOTE_BLOCKS blocks of 256 cover the usual budgets
+    // in one sweep and stride over larger ones
+    const RemoteArgs rem{S_next, n_next, local_lo, local_hi, part_bounds, per_part ? P : 0, remote_total, per_part, src_row,
+                         remote_ids, REMOTE_BLOCKS};
+    CSGS_LAUNCH(K_REMOTE_COUNT, remote_count_k, dim3(REMOTE_BLOCKS), dim3(256), (hipStream_t)stream, rem);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

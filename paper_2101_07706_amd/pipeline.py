@@ -57,6 +57,7 @@ class LayerBuffers:
         self.src_row, self.remote_ids = e(B, i32), e(B, i32)
         self.status = torch.zeros(1, dtype=i32, device=device)
         self.B = B
+        self.remote = None     # csgs_remote_out over these buffers, made on first use (needs the partition bounds)
 
     def stats_host(self):
         raw = self.stats.cpu().numpy().tobytes()
@@ -67,12 +68,14 @@ class LayerBuffers:
 
 
 def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=True, auto_D=None, nS_dev=None,
-                iter_dev=None):
-    """csgs_build_probs -> csgs_sample_layer -> csgs_remote_count for the rows S (device int32).
+                iter_dev=None, fuse_remote=True):
+    """csgs_build_probs -> csgs_sample_layer (-> csgs_remote_count) for the rows S (device int32).
     auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound.
     nS_dev: device int32 with the number of rows of S to use (the previous layer's n_next), so that
     the host need not wait for it; S is then the whole capacity-sized array.
-    iter_dev: device uint64 with the iteration number (for replayed call sequences)."""
+    iter_dev: device uint64 with the iteration number (for replayed call sequences).
+    fuse_remote: let csgs_sample_layer write the remote split (one launch less); False: call
+    csgs_remote_count separately."""
     nS = S.numel()
     q = lb.q if want_q else None
     if auto_D is None:
@@ -81,11 +84,15 @@ def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=Tru
     else:
         csgs.csgs_build_probs_auto(dg.c, S, auto_D, B, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc,
                                    lb.status, stream, nS_dev=nS_dev)
+    if fuse_remote and lb.remote is None:
+        lb.remote = csgs.make_remote_out(dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total, lb.per_part, lb.src_row,
+                                         lb.remote_ids)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
-                           ws.desc, lb.status, stream, iter_dev=iter_dev)
-    csgs.csgs_remote_count(lb.S_next, lb.n_next, dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total,
-                           lb.per_part, lb.src_row, lb.remote_ids, stream)
+                           ws.desc, lb.status, stream, iter_dev=iter_dev, remote=lb.remote if fuse_remote else None)
+    if not fuse_remote:
+        csgs.csgs_remote_count(lb.S_next, lb.n_next, dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total,
+                               lb.per_part, lb.src_row, lb.remote_ids, stream)
 
 
 def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None):

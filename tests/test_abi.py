@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
     assert C.sizeof(csgs.Graph) == 56
     assert C.sizeof(csgs.Workspace) == 64
+    assert C.sizeof(csgs.RemoteOut) == 56 and csgs.RemoteOut.remote_total.offset == 24
     assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48
     assert csgs.Workspace.has_draw.offset == 48 and csgs.Workspace.draw_B.offset == 56
 
@@ -69,7 +70,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     L = csgs.lib()
     z = C.c_void_p(0)
     assert L.csgs_build_probs(None, z, 1, z, 2.0, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
-    assert L.csgs_sample_layer(None, z, 1, z, z, 1, z, 1, 0, 0, z, 0, z, z, z, z, z, z, z, 1, z, None, z, z) == csgs.EINVAL
+    assert L.csgs_sample_layer(None, z, 1, z, z, 1, z, 1, 0, 0, z, 0, z, z, z, z, z, z, z, 1, z, None, None, z, z) == csgs.EINVAL
     assert L.csgs_remote_count(z, z, 0, 1, z, 0, z, z, z, z, z) == csgs.EINVAL
     assert L.csgs_aggregate(z, z, z, 1, z, z, z, 1, 1, z, 1, 0, z, 1, 0, 0, z, 1, z) == csgs.EINVAL
     assert L.csgs_layer_gemm(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
