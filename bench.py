@@ -89,9 +89,9 @@ class Workload:
         cfg, M, B, pipeline = self.cfg, self.M, self.B, self.pipeline
         it_num, it_dev = (0, it) if hasattr(it, "data_ptr") else (it, None)
         for l in range(M):
-            S = S0 if l == 0 else lbs[l - 1].S_next
-            pipeline.sample_step(self.dg, ws, S, cfg.skew, B, self.seed, it_num, l, lbs[l], want_q=False,
-                                 nS_dev=None if l == 0 else lbs[l - 1].n_next, iter_dev=it_dev)
+            # layers after the first take the rows the previous layer's sampler prepared (S None)
+            pipeline.sample_step(self.dg, ws, S0 if l == 0 else None, cfg.skew, B, self.seed, it_num, l, lbs[l],
+                                 want_q=False, iter_dev=it_dev)
 
     def enqueue_compute(self, lbs, n0):
         """Staging of the sampled remote rows (stands in for their exchange) and the bottom-up layer

@@ -113,10 +113,10 @@ typedef struct csgs_workspace {
     int32_t nS_max, B_max;
     int64_t edges_max;
     /* owned by the library (csgs_workspace_init resets them): */
-    uint64_t reserved_;
+    uint64_t rows_buf;   /* which of the two sets of row offsets belongs to the current rows */
     uint64_t has_draw;   /* a csgs_draw_nodes has been enqueued on this workspace */
     int32_t draw_B;      /* its B */
-    int32_t pad_;
+    int32_t has_next;    /* the latest csgs_sample_layer prepared the offsets of its S_next */
 } csgs_workspace;
 
 /* Bytes needed for a workspace of these sizes; 0 on bad input. */
@@ -152,7 +152,10 @@ int csgs_fixed_point(int32_t nS, float skew, float rownorm2_max, int32_t *shift,
  * so that the result does not depend on summation order.  Skewed weight (Eq. 10 numerator):
  * weight * s_fx for local j, weight * 16 for remote j.
  *
- *   S        [nS] distinct node ids, any order
+ *   S        [nS] distinct node ids, any order.  NULL: the rows are the node set S_next of the latest
+ *            csgs_sample_layer on this workspace (which has already prepared their offsets, so
+ *            this call is one kernel shorter); nS must be that call's B, nS_dev NULL -- the row
+ *            count is its *n_next
  *   skew     s >= 1 (s = 1 is linear weighted sampling, Eq. 7); used in 1/16 steps.  +infinity
  *            selects the "Local" version of Section 5.1: remote candidates keep their place in
  *            the list but get probability zero
@@ -196,7 +199,9 @@ int csgs_build_probs_auto(const csgs_graph *g /*host*/, const int32_t *S, int32_
  *            cand_cap = the capacity those arrays were given there.  The call must follow that
  *            csgs_build_probs call on the same workspace: it reuses the row offsets left there,
  *            and with them the row count that call used (so there is no nS_dev here; nS is the
- *            same capacity).
+ *            same capacity).  S may be NULL if it was NULL there.  Besides its outputs the call
+ *            prepares the row offsets of S_next for a following csgs_build_probs(S = NULL)
+ *            (only when B <= nS_max of the workspace; otherwise that call returns CSGS_EINVAL).
  *   S_next   [B] out: distinct sampled ids ascending; *n_next of them
  *   mult     [B] out: how many of the B draws hit each
  *   p_incl   [B] out: p_j as float

@@ -44,8 +44,8 @@ class Graph(C.Structure):
 class Workspace(C.Structure):
     """csgs_workspace: host descriptor of the caller-owned scratch buffer."""
     _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("n_nodes", C.c_int64),
-                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("reserved_", C.c_uint64),
-                ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("pad_", C.c_int32)]
+                ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("rows_buf", C.c_uint64),
+                ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("has_next", C.c_int32)]
 
 
 class RemoteOut(C.Structure):
@@ -224,24 +224,30 @@ def csgs_fixed_point(nS, skew, rownorm2_max=1.0):
     return rc, sh.value, sfx.value
 
 
-def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None, nS_dev=None):
-    """nS_dev: device int32 holding the number of rows of S to use (S.numel() is then the capacity)."""
-    _call("csgs_build_probs", C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
+def _rows(S, nS):
+    """Row capacity of a call: the length of S, or nS when S is None (rows = the latest sampled set)."""
+    return S.numel() if S is not None else nS
+
+
+def csgs_build_probs(g, S, skew, cand_id, cand_w, cdf, q, stats, ws, status, stream=None, nS_dev=None, nS=None):
+    """nS_dev: device int32 holding the number of rows of S to use (S.numel() is then the capacity).
+    S None: rows = the node set of the latest csgs_sample_layer on `ws`; nS = that call's B."""
+    _call("csgs_build_probs", C.byref(g), _ptr(S), _rows(S, nS), _ptr(nS_dev), skew, _ptr(cand_id), _ptr(cand_w), _ptr(cdf),
                                 _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status), _stream(stream))
 
 
 def csgs_build_probs_auto(g, S, D, B, skew_max, cand_id, cand_w, cdf, q, stats, ws, status, stream=None,
-                          nS_dev=None):
-    _call("csgs_build_probs_auto", C.byref(g), _ptr(S), S.numel(), _ptr(nS_dev), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
+                          nS_dev=None, nS=None):
+    _call("csgs_build_probs_auto", C.byref(g), _ptr(S), _rows(S, nS), _ptr(nS_dev), D, B, skew_max, _ptr(cand_id), _ptr(cand_w),
                                      _ptr(cdf), _ptr(q), cand_id.numel(), _ptr(stats), C.byref(ws), _ptr(status),
                                      _stream(stream))
 
 
 def csgs_sample_layer(g, S, cand_id, cdf, stats, B, seed, it, layer, S_next, mult, p_incl, n_next,
-                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None, iter_dev=None, remote=None):
+                      adj_rowptr, adj_col, adj_val, adj_nnz, ws, status, stream=None, iter_dev=None, remote=None, nS=None):
     """iter_dev: device uint64 tensor holding the iteration number (then `it` is ignored).
     remote: a RemoteOut (see make_remote_out): also write the remote split of S_next."""
-    _call("csgs_sample_layer", C.byref(g), _ptr(S), S.numel(), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
+    _call("csgs_sample_layer", C.byref(g), _ptr(S), _rows(S, nS), _ptr(cand_id), _ptr(cdf), cand_id.numel(),
                                  _ptr(stats), B, seed, it, _ptr(iter_dev), layer, _ptr(S_next), _ptr(mult), _ptr(p_incl),
                                  _ptr(n_next), _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_col.numel(),
                                  _ptr(adj_nnz), None if remote is None else C.byref(remote), C.byref(ws), _ptr(status), _stream(stream))

@@ -27,8 +27,8 @@ constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in t
 constexpr int ROW_TILE = 1024;    // rows of S per block in the degree prefix
 constexpr int META_WORDS = 4;
 constexpr int META_ROWS = 0;          // rows the latest row_prefix covered (the count behind eoff / rowstart)
-constexpr int META_SHIFT = 1;         // fraction bits of the fixed-point weights for that count
-constexpr int META_EDGES = 2;         // eoff[rows]: edges of those rows (0 when above the workspace's capacity)
+constexpr int META_EDGES = 1;         // eoff[rows]: edges of those rows (0 when above the workspace's capacity)
+constexpr int META_EDGES_TRUE = 2;    // their true number
 
 // Words of workspace a single-pass scan over at most `tiles` tiles with nv sums per tile needs
 // (one tag word and nv sums per tile, and twice that per group of 64 tiles).
@@ -36,6 +36,13 @@ __host__ __device__ inline size_t scan_state_words(int64_t tiles, int nv)
 {
     return (size_t)(1 + nv) * (size_t)(tiles + 2 * (tiles / 64 + 2));
 }
+
+struct RowOffsets {
+    int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows
+    int64_t *rowstart;   // [nS + 1] rowptr[S[a]]
+    int64_t *meta;       // [META_WORDS] resolved on the device: row count, edge count, true edge count
+    int2 *chunk_note;    // [chunk_cap] (first row, rows) of every edge chunk, left by the weight scan for the adjacency pass
+};
 
 struct Workspace {
     // clean: all-zero whenever no call is in flight
@@ -51,14 +58,12 @@ struct Workspace {
     uint64_t *cand_flag; // [n_tiles] tag of the call whose partial sums a tile holds
     uint64_t *epoch;     // [4] call counter and draw tag (see lookback.hpp); advanced on the device
     uint64_t *hit_ts;    // scan state of the hit tiles (1 sum per tile)
-    // per call
-    int64_t *eoff;       // [nS + 1] exclusive prefix of the degrees of the rows of S
-    int64_t *rowstart;   // [nS]     rowptr[S[a]]
+    // per call.  The row offsets exist twice: while the adjacency pass of one layer reads one set,
+    // its spare blocks prepare the other for the next layer (rows = the node set just sampled).
+    RowOffsets rows[2];
     uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
     uint64_t *rp_ts;     // scan state of the row tiles (1 sum per tile of ROW_TILE rows)
-    int2 *chunk_note;    // [chunk_cap] (first row, rows) of every edge chunk, left by the weight scan for the adjacency pass
     double *pdbl;        // [B]      inclusion probabilities in double
-    int64_t *meta;       // [META_WORDS] what row_prefix resolved on the device: row count, weight shift, edge count
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
     int64_t n_tiles, hit_tiles, rp_tiles;
     size_t clean_bytes;  // size of the clean part
@@ -96,11 +101,13 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.adj_ts = (uint64_t *)take(scan_state_words(w.chunk_cap, 1) * 8);
     w.rp_tiles = (nS_max + ROW_TILE - 1) / ROW_TILE;
     w.rp_ts = (uint64_t *)take(scan_state_words(w.rp_tiles, 1) * 8);
-    w.chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
-    w.eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
-    w.rowstart = (int64_t *)take((size_t)(nS_max + 1) * 8);
+    for (int b = 0; b < 2; ++b) {
+        w.rows[b].eoff = (int64_t *)take((size_t)(nS_max + 1) * 8);
+        w.rows[b].rowstart = (int64_t *)take((size_t)(nS_max + 1) * 8);
+        w.rows[b].meta = (int64_t *)take(META_WORDS * 8);
+        w.rows[b].chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
+    }
     w.pdbl = (double *)take((size_t)B_max * 8);
-    w.meta = (int64_t *)take(META_WORDS * 8);
     w.bytes = off;
     return w;
 }
@@ -137,12 +144,11 @@ __host__ inline int resident_grid(int per_cu)
     return per_cu * cus;
 }
 
-// Degrees of the rows S, their exclusive prefix (w.eoff) and CSR starts (w.rowstart); stats may be
-// null.  The row count is min(*nS_dev, nS) when nS_dev is given; the kernel leaves it, and
-// min(52, shift_base - ceil(log2 count)), in w.meta for the kernels that follow.  Defined with the
-// weight scan.
+// Degrees of the rows S, their exclusive prefix and CSR starts into `rows`.  The row count is
+// min(*nS_dev, nS) when nS_dev is given; the kernel leaves it, and the edge count, in rows.meta for
+// the kernels that follow.  Defined with the weight scan.
 int launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                      int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status, hipStream_t st);
+                      const Workspace &w, const RowOffsets &rows, int32_t *status, hipStream_t st);
 
 // A row count given on the host (n) or, when n_dev is not null, on the device with n as its bound.
 __device__ inline int32_t resolve_count(int32_t n, const int32_t *__restrict__ n_dev)

@@ -50,7 +50,7 @@ constexpr int EPOCH_CALLS = 0;   // library calls completed on this workspace
 constexpr int EPOCH_DRAW = 1;    // value of (calls + 1) during the latest draw: tags the rank table
 constexpr int EPOCH_WAIT = 2;    // 0, or 1 + the number of polls a wait may take (set through csgs_workspace_wait_limit)
 // one tag space per scan-state region, so the kernels of one call never mistake each other's flags
-enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4 };
+enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4, SLOT_ROWS_NEXT = 5 };
 
 __device__ inline int wait_limit(const uint64_t *epoch)
 {

@@ -25,96 +25,31 @@
 #include <math.h>
 #include "common.hpp"
 #include "lookback.hpp"
+#include "row_prefix.hpp"
 
 namespace csgs {
 
-constexpr int RP_ITEMS = 4;                  // rows per thread in row_prefix
-constexpr int RP_TILE = ROW_TILE;           // rows per block
-static_assert(RP_TILE == 256 * RP_ITEMS, "row tile");
-
-// Tile t = rows [t * RP_TILE, ...): degrees fetched striped (coalesced, all loads independent), handed
-// through LDS to a blocked arrangement, block scan, offset of the tile by the single-pass scan
-// across blocks.  One tile per block, grid = tiles of the row capacity; with a device-side count
-// the blocks past it leave at once.
+// Rows given by the caller: one tile per block, grid = tiles of the row capacity; with a device-side
+// count the blocks past it leave at once.
 __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ rowptr, int64_t n_nodes,
                                                   const int32_t *__restrict__ S, int32_t nS_bound,
-                                                  const int32_t *__restrict__ nS_dev, int32_t shift_base,
-                                                  const uint64_t *__restrict__ epoch, uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
+                                                  const int32_t *__restrict__ nS_dev, const uint64_t *__restrict__ epoch,
+                                                  uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
                                                   int64_t *__restrict__ meta, int64_t edge_cap,
-                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status)
+                                                  int32_t *__restrict__ status)
 {
-    __shared__ int64_t lds[17];
-    __shared__ int32_t s_deg[RP_TILE];
-    __shared__ unsigned long long s_lb[1];
     const TileState<1> ts(ts_mem, ts_tiles, wait_limit(epoch));
-    const unsigned long long tag = call_tag(call_number(epoch), SLOT_ROWS);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
-    int64_t n_tiles = ((int64_t)nS + RP_TILE - 1) / RP_TILE;
-    if (n_tiles < 1) n_tiles = 1;   // an empty row set still gets its end markers written
-    const int64_t t = blockIdx.x;
-    if (t >= n_tiles) return;
-    const int32_t r0 = (int32_t)(t * RP_TILE);
-    bool bad = false;
-#pragma unroll
-    for (int k = 0; k < RP_ITEMS; ++k) {
-        const int32_t a = r0 + k * 256 + (int32_t)threadIdx.x;
-        int64_t deg = 0, beg = 0;
-        if (a < nS) {
-            const int32_t i = S[a];
-            if (i >= 0 && i < n_nodes) {
-                beg = rowptr[i];
-                deg = rowptr[i + 1] - beg;
-                if (deg < 0 || deg > 0x7FFFFFFFll) deg = 0;
-            } else {
-                bad = true;
-            }
-            rowstart[a] = beg;
-        }
-        s_deg[k * 256 + threadIdx.x] = (int32_t)deg;
-    }
-    __syncthreads();
-    int32_t d[RP_ITEMS];
-    int64_t sum = 0;
-#pragma unroll
-    for (int k = 0; k < RP_ITEMS; ++k) {
-        d[k] = s_deg[threadIdx.x * RP_ITEMS + k];
-        sum += d[k];
-    }
-    int64_t tile_total;
-    int64_t ex = block_exclusive_scan<int64_t>(sum, lds, &tile_total);
-    unsigned long long local[1] = {(unsigned long long)tile_total}, excl[1];
-    lookback_publish<1>(ts, tag, t, local);
-    lookback_resolve<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);
-    ex += (int64_t)excl[0];
-#pragma unroll
-    for (int k = 0; k < RP_ITEMS; ++k) {
-        const int32_t a = r0 + (int32_t)threadIdx.x * RP_ITEMS + k;
-        if (a < nS) eoff[a] = ex;
-        ex += d[k];
-    }
-    if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);
-    if (t == n_tiles - 1 && threadIdx.x == 0) {
-        int64_t total = (int64_t)excl[0] + tile_total;
-        if (stats) stats->edges_scanned = total;
-        // an edge count the workspace cannot hold is reported and treated as empty
-        if (total > edge_cap) {
-            atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
-            total = 0;
-        }
-        eoff[nS] = total;
-        // fraction bits for this many rows: the sum of nS weights must stay below 2^61 / (s_fx rmax)
-        int32_t lg = 0;
-        while (lg < 31 && (1ll << lg) < (int64_t)nS) ++lg;
-        const int32_t shift = shift_base - lg;
-        meta[META_ROWS] = nS;
-        meta[META_SHIFT] = shift > 52 ? 52 : shift;
-        meta[META_EDGES] = total;
-    }
+    const int64_t n_tiles = row_tiles(nS);
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+    row_prefix_tile(rowptr, n_nodes, S, nS, blockIdx.x, n_tiles, ts, call_tag(call_number(epoch), SLOT_ROWS), eoff, rowstart,
+                    meta, edge_cap, status);
 }
 
 __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
-                                                  int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
+                                                  int64_t n_nodes, int64_t nnz, int32_t shift_base,
+                                                  const int64_t *__restrict__ meta, int64_t edge_cap,
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
@@ -122,8 +57,9 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
 {
     __shared__ RowSlice slice;
     const int32_t nS = (int32_t)meta[META_ROWS];
-    const double scale = ldexp(1.0, (int)meta[META_SHIFT]);
+    const double scale = ldexp(1.0, shift_for_rows(shift_base, nS));
     const int64_t E = meta[META_EDGES];
+    if (blockIdx.x == 0 && threadIdx.x == 0 && meta[META_EDGES_TRUE] > edge_cap) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
     bool bad = false;
     for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
@@ -243,7 +179,8 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
                                                  int64_t n_words, int64_t n_nodes, int64_t n_tiles, int32_t lo,
                                                  int32_t hi, SkewPolicy pol, const uint64_t *__restrict__ partial,
                                                  const uint64_t *__restrict__ gtot,
-                                                 const int64_t *__restrict__ meta, uint64_t *__restrict__ epoch,
+                                                 const int64_t *__restrict__ meta, int32_t shift_base,
+                                                 uint64_t *__restrict__ epoch,
                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
                                                  uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
@@ -364,7 +301,8 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
         stats->w_local = tot[1];
         stats->w_remote = tot[2];
         stats->total = total_w;
-        stats->shift = (int32_t)meta[META_SHIFT];
+        stats->shift = shift_for_rows(shift_base, meta[META_ROWS]);
+        stats->edges_scanned = meta[META_EDGES_TRUE];
         stats->skew_fx = (int32_t)m_local * (m_remote ? 1 : -1);
         int32_t st = 0;
         if (n_cand == 0 || total_w == 0) st |= CSGS_ST_EMPTY_CANDIDATES;
@@ -399,12 +337,11 @@ static int shift_base_for(int64_t s_fx, float rownorm2_max)
 }  // namespace csgs
 
 int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_t *S, int32_t nS, const int32_t *nS_dev,
-                            int32_t shift_base, const Workspace &w, csgs_prob_stats *stats, int32_t *status,
-                            hipStream_t st)
+                            const Workspace &w, const RowOffsets &rows, int32_t *status, hipStream_t st)
 {
-    const unsigned tiles = (unsigned)(((int64_t)nS + RP_TILE - 1) / RP_TILE);
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, shift_base, w.epoch,
-                w.rp_ts, w.rp_tiles, w.eoff, w.rowstart, w.meta, w.chunk_cap * EDGE_TILE, stats, status);
+    const unsigned tiles = (unsigned)(((int64_t)nS + ROW_TILE - 1) / ROW_TILE);
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, w.epoch, w.rp_ts,
+                w.rp_tiles, rows.eoff, rows.rowstart, rows.meta, w.chunk_cap * EDGE_TILE, status);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -426,8 +363,9 @@ extern "C" size_t csgs_workspace_clean_bytes(int64_t n_nodes)
 extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
 {
     if (!ws) return CSGS_EINVAL;
-    ws->reserved_ = 0;
+    ws->rows_buf = 0;
     ws->has_draw = 0;
+    ws->has_next = 0;
     ws->draw_B = 0;
     Workspace w;
     const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
@@ -475,8 +413,12 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
                             csgs_prob_stats *stats, csgs_workspace *ws, int32_t *status, void *stream)
 {
     if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll ||
-        g->local_lo > g->local_hi || !S || nS <= 0 || !cand_id || !cand_w || !cdf || cap <= 0 || !stats || !ws || !status)
+        g->local_lo > g->local_hi || nS <= 0 || !cand_id || !cand_w || !cdf || cap <= 0 || !stats || !ws || !status)
         return CSGS_EINVAL;
+    // S == NULL: the rows are the node set of the latest csgs_sample_layer on this workspace, whose
+    // offsets that call has prepared; nS must be its capacity (the B of that draw)
+    const bool chained = S == nullptr;
+    if (chained && (!ws->has_next || nS_dev || nS != ws->draw_B)) return CSGS_EINVAL;
     int32_t shift;
     int64_t s_fx;
     int rc = csgs_fixed_point(nS, shift_skew, g->rownorm2_max, &shift, &s_fx);
@@ -491,17 +433,23 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
 
     // the shift for nS rows has passed the range check; fewer rows on the device only widen it
     const int32_t shift_base = shift_base_for(s_fx, g->rownorm2_max);
-    rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, shift_base, w, stats, status, st);
-    if (rc != CSGS_OK) return rc;
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, w.meta, w.eoff,
-                w.rowstart, w.wtable, w.tileflag, w.chunk_note, status);
+    if (chained) {
+        ws->rows_buf ^= 1;      // the set the adjacency pass prepared
+    } else {
+        rc = launch_row_prefix(g->rowptr, g->n_nodes, S, nS, nS_dev, w, w.rows[ws->rows_buf & 1], status, st);
+        if (rc != CSGS_OK) return rc;
+    }
+    ws->has_next = 0;
+    const RowOffsets &rows = w.rows[ws->rows_buf & 1];
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, shift_base,
+                rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable, w.tileflag, rows.chunk_note, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,
                 (unsigned long long *)w.partial, w.gtot, status);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
-                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, w.meta, w.epoch, stats, status, cand_id,
+                g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, rows.meta, shift_base, w.epoch, stats, status, cand_id,
                 cand_w, cdf, q, cap);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;

@@ -26,6 +26,7 @@
 #include <math.h>
 #include "common.hpp"
 #include "lookback.hpp"
+#include "row_prefix.hpp"
 
 namespace csgs {
 
@@ -289,6 +290,20 @@ __device__ inline void remote_count_body(const RemoteArgs &r_, int32_t block, in
 
 __global__ __launch_bounds__(256) void remote_count_k(RemoteArgs r) { remote_count_body(r, (int32_t)blockIdx.x, (int32_t)gridDim.x); }
 
+// Work of the adjacency kernel's second group of spare blocks: the row offsets of the node set just
+// sampled, for a following csgs_build_probs on those rows (one tile of rows per block).
+struct NextRows {
+    const int64_t *rowptr;
+    int64_t n_nodes;
+    const int32_t *S_next, *n_next;
+    int32_t bound;        // capacity of S_next (the B of the draw)
+    uint64_t *ts_mem;
+    int64_t ts_tiles;
+    int64_t *eoff, *rowstart, *meta;
+    int64_t edge_cap;
+    int32_t blocks;       // 0 = none
+};
+
 template <bool FROM_NOTE>
 __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                  int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
@@ -299,7 +314,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ adj_rowptr,
                                                  int32_t *__restrict__ adj_col, float *__restrict__ adj_val,
                                                  int64_t adj_cap, int64_t *__restrict__ adj_nnz,
-                                                 int32_t *__restrict__ status, RemoteArgs rem)
+                                                 int32_t *__restrict__ status, RemoteArgs rem, NextRows nxt)
 {
     // The leading rem.blocks blocks split the new node set into local and remote (what
     // csgs_remote_count does: it needs only S_next / n_next, complete since the previous kernel) so
@@ -308,7 +323,21 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         remote_count_body(rem, (int32_t)blockIdx.x, rem.blocks);
         return;
     }
-    const int64_t bid = (int64_t)blockIdx.x - rem.blocks, n_bids = (int64_t)gridDim.x - rem.blocks;
+    // The next nxt.blocks blocks lay out the rows of the new node set.  They wait only for each other
+    // (lower tiles, dispatched before them); their flags are tagged with the draw's call number,
+    // which the previous kernel wrote, so the counter this kernel advances at its end does not matter.
+    if ((int32_t)blockIdx.x < rem.blocks + nxt.blocks) {
+        const int32_t n = resolve_count(nxt.bound, nxt.n_next);
+        const int64_t t = (int64_t)blockIdx.x - rem.blocks, n_tiles = row_tiles(n);
+        if (t < n_tiles) {
+            const TileState<1> rts(nxt.ts_mem, nxt.ts_tiles, wait_limit(epoch));
+            row_prefix_tile(nxt.rowptr, nxt.n_nodes, nxt.S_next, n, t, n_tiles, rts, call_tag(epoch[EPOCH_DRAW], SLOT_ROWS_NEXT),
+                            nxt.eoff, nxt.rowstart, nxt.meta, nxt.edge_cap, status);
+        }
+        return;
+    }
+    const int64_t bid = (int64_t)blockIdx.x - rem.blocks - nxt.blocks;
+    const int64_t n_bids = (int64_t)gridDim.x - rem.blocks - nxt.blocks;
     __shared__ RowSlice slice;
     __shared__ uint64_t s_mask[EDGE_TILE / 64];
     __shared__ int32_t s_pre[EDGE_TILE / 64 + 1];
@@ -451,6 +480,7 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
     CSGS_LAUNCH_CHECK();
     ws->has_draw = 1;
     ws->draw_B = B;
+    ws->has_next = 0;   // offsets prepared for an earlier node set are void
     return CSGS_OK;
 }
 
@@ -459,9 +489,10 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
                                   bool reuse_offsets,
                                   int32_t *adj_rowptr, int32_t *adj_col, float *adj_val, int64_t adj_cap,
                                   int64_t *adj_nnz, csgs_workspace *ws, int32_t *status, const RemoteArgs &rem,
-                                  void *stream)
+                                  const int32_t *S_next, const int32_t *n_next, void *stream)
 {
-    if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || !rows || n_rows <= 0 ||
+    if (!g || !g->rowptr || !g->colidx || !g->val || g->n_nodes <= 0 || g->n_nodes > 0x7FFFFFFFll || (!rows && !reuse_offsets) ||
+        n_rows <= 0 ||
         !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz || !ws || !status)
         return CSGS_EINVAL;
     if (!ws->has_draw) return CSGS_EINVAL;  // no csgs_draw_nodes has run on this workspace
@@ -469,20 +500,29 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     const int rc = open_workspace(ws, g->n_nodes, n_rows, ws->draw_B, &w);
     if (rc != CSGS_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
+    const RowOffsets &cur = w.rows[ws->rows_buf & 1];
     if (!reuse_offsets) {
-        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, 52, w, nullptr, status, st);
+        const int rc2 = launch_row_prefix(g->rowptr, g->n_nodes, rows, n_rows, n_rows_dev, w, cur, status, st);
         if (rc2 != CSGS_OK) return rc2;
     }
+    // prepare the other set of row offsets for the new node set, if it fits there
+    NextRows nxt{};
+    if (S_next && ws->draw_B <= ws->nS_max) {
+        const RowOffsets &o = w.rows[(ws->rows_buf & 1) ^ 1];
+        nxt = NextRows{g->rowptr, g->n_nodes, S_next, n_next, ws->draw_B, w.rp_ts, w.rp_tiles, o.eoff, o.rowstart, o.meta,
+                       w.chunk_cap * EDGE_TILE, (int32_t)((ws->draw_B + ROW_TILE - 1) / ROW_TILE)};
+    }
+    ws->has_next = nxt.blocks > 0;
     // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
-    const dim3 grid((unsigned)(resident_grid(2) + rem.blocks));
+    const dim3 grid((unsigned)(resident_grid(2) + rem.blocks + nxt.blocks));
     if (reuse_offsets)
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
-                    adj_col, adj_val, adj_cap, adj_nnz, status, rem);
+                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
+                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt);
     else
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    g->nnz, w.meta, w.eoff, w.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, w.chunk_note, adj_rowptr,
-                    adj_col, adj_val, adj_cap, adj_nnz, status, rem);
+                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
+                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -492,7 +532,7 @@ extern "C" int csgs_sampled_adjacency(const csgs_graph *g, const int32_t *rows, 
                                       csgs_workspace *ws, int32_t *status, void *stream)
 {
     return sampled_adjacency_impl(g, rows, n_rows, n_rows_dev, false, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status,
-                                  RemoteArgs{}, stream);
+                                  RemoteArgs{}, nullptr, nullptr, stream);
 }
 
 extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t nS, const int32_t *cand_id,
@@ -502,7 +542,7 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
                                  int64_t adj_cap, int64_t *adj_nnz, const csgs_remote_out *remote,
                                  csgs_workspace *ws, int32_t *status, void *stream)
 {
-    if (!g || !S || nS <= 0 || !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz) return CSGS_EINVAL;
+    if (!g || nS <= 0 || !adj_rowptr || !adj_col || !adj_val || adj_cap <= 0 || !adj_nnz) return CSGS_EINVAL;
     RemoteArgs rem{};
     if (remote) {
         if (!remote->remote_total || remote->local_lo > remote->local_hi ||
@@ -515,7 +555,7 @@ extern "C" int csgs_sample_layer(const csgs_graph *g, const int32_t *S, int32_t 
     const int rc = csgs_draw_nodes(g->n_nodes, cand_id, cdf, cand_cap, stats, B, seed, iter, iter_dev, layer, S_next, mult, p_incl,
                                    n_next, ws, status, stream);
     if (rc != CSGS_OK) return rc;
-    return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, rem, stream);
+    return sampled_adjacency_impl(g, S, nS, nullptr, true, adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, ws, status, rem, S_next, n_next, stream);
 }
 
 extern "C" int csgs_remote_count(const int32_t *S_next, const int32_t *n_next, int32_t local_lo, int32_t local_hi,

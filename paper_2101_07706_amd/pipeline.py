@@ -73,23 +73,25 @@ def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=Tru
     auto_D: take the skew from Theorem 1 with this constant; `skew` is then its upper bound.
     nS_dev: device int32 with the number of rows of S to use (the previous layer's n_next), so that
     the host need not wait for it; S is then the whole capacity-sized array.
+    S None: the rows are the node set the previous csgs_sample_layer on `ws` sampled (it has prepared
+    their offsets); B must be the same as in that call.
     iter_dev: device uint64 with the iteration number (for replayed call sequences).
     fuse_remote: let csgs_sample_layer write the remote split (one launch less); False: call
     csgs_remote_count separately."""
-    nS = S.numel()
+    nS = S.numel() if S is not None else B       # S None: rows = the previous layer's sampled set, capacity B
     q = lb.q if want_q else None
     if auto_D is None:
         csgs.csgs_build_probs(dg.c, S, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc, lb.status, stream,
-                              nS_dev=nS_dev)
+                              nS_dev=nS_dev, nS=nS)
     else:
         csgs.csgs_build_probs_auto(dg.c, S, auto_D, B, skew, lb.cand_id, lb.cand_w, lb.cdf, q, lb.stats, ws.desc,
-                                   lb.status, stream, nS_dev=nS_dev)
+                                   lb.status, stream, nS_dev=nS_dev, nS=nS)
     if fuse_remote and lb.remote is None:
         lb.remote = csgs.make_remote_out(dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total, lb.per_part, lb.src_row,
                                          lb.remote_ids)
     csgs.csgs_sample_layer(dg.c, S, lb.cand_id, lb.cdf, lb.stats, B, seed, it, layer, lb.S_next, lb.mult,
                            lb.p_incl, lb.n_next, lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.adj_nnz,
-                           ws.desc, lb.status, stream, iter_dev=iter_dev, remote=lb.remote if fuse_remote else None)
+                           ws.desc, lb.status, stream, iter_dev=iter_dev, remote=lb.remote if fuse_remote else None, nS=nS)
     if not fuse_remote:
         csgs.csgs_remote_count(lb.S_next, lb.n_next, dg.local_lo, dg.local_hi, dg.part_bounds, lb.remote_total,
                                lb.per_part, lb.src_row, lb.remote_ids, stream)

@@ -41,9 +41,10 @@ def oracle_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, auto_D=None):
     return steps
 
 
-def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None, auto_D=None, device_counts=False):
-    if device_counts:
-        return gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D)
+def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None, auto_D=None, device_counts=False,
+              chained=False):
+    if device_counts or chained:
+        return gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D, chained)
     import torch
     from paper_2101_07706_amd import pipeline
     dev = torch.device("cuda:0")
@@ -91,10 +92,11 @@ def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None
     return steps, ws
 
 
-def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D):
+def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, auto_D, chained=False):
     """The same chain enqueued without the host reading anything back in between: every layer's
     row count stays on the device (the previous layer's n_next), arrays have their capacity
-    sizes, the staged remote rows come from csgs_gather_rows."""
+    sizes, the staged remote rows come from csgs_gather_rows.  chained: layers after the first
+    pass no row array at all, their rows are the set the previous csgs_sample_layer produced."""
     import torch
     from paper_2101_07706_amd import csgs, pipeline
     dev = torch.device("cuda:0")
@@ -115,8 +117,8 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
     torch.cuda.synchronize()
     # ---- nothing below reads device memory on the host until the final synchronize
     for l in range(M):
-        S = S0d if l == 0 else lbs[l - 1].S_next
-        nS_dev = None if l == 0 else lbs[l - 1].n_next
+        S = S0d if l == 0 else (None if chained else lbs[l - 1].S_next)
+        nS_dev = None if (l == 0 or chained) else lbs[l - 1].n_next
         pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lbs[l], auto_D=auto_D, nS_dev=nS_dev)
     pipeline.stage_remote_rows(lbs[M - 1], Xd, staged)
     X_local = Xd[g.local_lo:g.local_hi]

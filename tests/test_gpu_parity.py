@@ -436,6 +436,66 @@ def test_chain_without_host_reads_large(dev):
     say(f"[large] device-side row counts: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
 
 
+@pytest.mark.parametrize("name", ["tiny", "medium", "mid", "large"])
+def test_chain_on_prepared_rows(dev, name):
+    """Layers after the first pass no row array: csgs_build_probs(S = NULL) takes the node set the
+    previous csgs_sample_layer sampled, whose offsets that call prepared.  Same results as the oracle."""
+    if name == "large":
+        cfg, g, X, Ws, _ = cached_inputs("large")
+        S0 = synth.make_batch(g, cfg.batch, cfg.seed, 5)
+        it = 5
+    else:
+        it = 1
+        cfg, g, X, Ws, S0 = chain.config_inputs(name, it)
+    bf16 = cfg.feat_dtype == "bf16"
+    say(f"[{name}] rows prepared by the previous layer")
+    for auto_D in (None, 8.0) if name == "tiny" else (None,):
+        osteps = chain.oracle_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D)
+        gsteps, _ = chain.gpu_chain(g, X, Ws, S0, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
+                                    chained=True)
+        worst = chain.compare_chain(osteps, gsteps)
+        say(f"[{name}] n' per layer {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+
+
+def test_prepared_rows_need_a_matching_sample_layer(dev):
+    """csgs_build_probs(S = NULL) is refused on the host when no csgs_sample_layer has prepared rows,
+    when nS is not that call's B, when a device count is given, and after the rows were consumed."""
+    from paper_2101_07706_amd import csgs, pipeline
+    cfg, g, X, Ws, S0 = chain.config_inputs("tiny", 0)
+    B = cfg.samples
+    dg = pipeline.DeviceGraph(g, dev)
+    nS_max = max(len(S0), B)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
+    lb0 = pipeline.LayerBuffers(nS_max, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+    lb1 = pipeline.LayerBuffers(nS_max, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+    S0d = torch.from_numpy(np.ascontiguousarray(S0, np.int32)).to(dev)
+
+    def chained(lb, nS, nS_dev=None):
+        csgs.csgs_build_probs(dg.c, None, cfg.skew, lb.cand_id, lb.cand_w, lb.cdf, None, lb.stats, ws.desc, lb.status,
+                              nS_dev=nS_dev, nS=nS)
+
+    with pytest.raises(csgs.CsgsError):
+        chained(lb1, B)                                   # nothing prepared yet
+    pipeline.sample_step(dg, ws, S0d, cfg.skew, B, 7, 0, 0, lb0)
+    with pytest.raises(csgs.CsgsError):
+        chained(lb1, B - 1)                               # not the capacity of the draw
+    with pytest.raises(csgs.CsgsError):
+        chained(lb1, B, nS_dev=lb0.n_next)                # the count is already known
+    chained(lb1, B)                                       # accepted
+    with pytest.raises(csgs.CsgsError):
+        chained(lb1, B)                                   # consumed
+    torch.cuda.synchronize()
+    assert int(lb0.status.item()) == 0 and int(lb1.status.item()) == 0
+    # the accepted call equals the explicit form
+    lb2 = pipeline.LayerBuffers(nS_max, B, g.n_nodes, g.nnz, dg.n_parts, dev)
+    csgs.csgs_build_probs(dg.c, lb0.S_next, cfg.skew, lb2.cand_id, lb2.cand_w, lb2.cdf, None, lb2.stats, ws.desc,
+                          lb2.status, nS_dev=lb0.n_next)
+    torch.cuda.synchronize()
+    n = int(lb2.stats_host().n_cand)
+    assert n == int(lb1.stats_host().n_cand) and n > 0
+    assert torch.equal(lb1.cand_id[:n], lb2.cand_id[:n]) and torch.equal(lb1.cdf[:n], lb2.cdf[:n])
+
+
 def test_device_row_count_small_and_zero(dev):
     """A device count below the capacity gives exactly the result of a call with that many rows;
     a device count of zero gives an empty candidate set (status bit) and writes nothing else."""
