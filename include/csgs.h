@@ -117,7 +117,24 @@ typedef struct csgs_workspace {
     uint64_t has_draw;   /* a csgs_draw_nodes has been enqueued on this workspace */
     int32_t draw_B;      /* its B */
     int32_t has_next;    /* the latest csgs_sample_layer prepared the offsets of its S_next */
+    /* several instances per call, set by the caller (see below); 0 or 1 = one instance */
+    int32_t n_inst;
+    int32_t reserved;
+    int64_t inst_stride; /* bytes between consecutive instances' arrays; a multiple of 256 */
 } csgs_workspace;
+
+/* Several instances per call.  Consecutive training iterations sample independent mini-batches
+ * against the same graph (Section 5.1: a new mini-batch, newly sampled, per iteration); at the
+ * paper's batch sizes one of them is too little work to fill the device.  With n_inst = K > 1 the
+ * buffer holds K workspaces back to back (bytes >= K * csgs_workspace_bytes(...)), and every call
+ * that takes this descriptor -- csgs_build_probs, csgs_build_probs_auto, csgs_draw_nodes,
+ * csgs_sampled_adjacency, csgs_sample_layer -- processes K independent instances in the same kernel
+ * launches.  Instance k reads and writes every device-pointer argument of the call (S, nS_dev, the
+ * candidate arrays, stats, S_next, mult, p_incl, n_next, the adjacency arrays, adj_nnz, status, and
+ * remote_total / per_part / src_row / remote_ids of csgs_remote_out) at the given address plus
+ * k * inst_stride bytes; null arguments are null for all.  Shared by all instances: the graph's
+ * arrays, part_bounds, iter_dev, and all scalar arguments, except that instance k's draws use
+ * iteration number iter + k (*iter_dev + k).  Results are those of K separate calls.  At most 64. */
 
 /* Bytes needed for a workspace of these sizes; 0 on bad input. */
 size_t csgs_workspace_bytes(int64_t n_nodes, int32_t nS_max, int32_t B_max, int64_t edges_max);

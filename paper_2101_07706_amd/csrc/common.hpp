@@ -67,8 +67,24 @@ struct Workspace {
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
     int64_t n_tiles, hit_tiles, rp_tiles;
     size_t clean_bytes;  // size of the clean part
-    size_t bytes;
+    size_t bytes;        // size of one instance's workspace (a multiple of 256)
+    int32_t n_inst;      // instances a call on this workspace processes (set by open_workspace)
+    int64_t buf_stride;  // bytes between consecutive instances' caller buffers
 };
+
+// Several independent instances of a call run in the same launches: blockIdx.z selects the
+// instance, and every per-instance pointer moves by that instance's stride in bytes -- `ws` for
+// what lives in the workspace (instance k's workspace follows instance k - 1's), `buf` for the
+// caller's arrays.  The graph is shared.  With one instance blockIdx.z is 0 and nothing moves.
+struct InstStride {
+    int64_t ws, buf;
+};
+template <typename T>
+__device__ inline T *inst_ptr(T *p, int64_t stride)
+{
+    return p ? (T *)((uintptr_t)p + (uintptr_t)((int64_t)blockIdx.z * stride)) : p;   // null stays null
+}
+constexpr int MAX_INSTANCES = 64;
 
 // Layout of a workspace sized for (n_nodes, nS_max, B_max, edges_max).  Every call carves with the
 // same four numbers (they travel in the caller's csgs_workspace descriptor), so the persistent
@@ -109,6 +125,8 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     }
     w.pdbl = (double *)take((size_t)B_max * 8);
     w.bytes = off;
+    w.n_inst = 1;
+    w.buf_stride = 0;
     return w;
 }
 
@@ -119,9 +137,15 @@ __host__ inline int open_workspace(csgs_workspace *d, int64_t n_nodes, int64_t n
         d->edges_max <= 0)
         return CSGS_EINVAL;
     if (nS > d->nS_max || B > d->B_max) return CSGS_EWORKSPACE;
+    const int32_t n_inst = d->n_inst > 1 ? d->n_inst : 1;
+    if (n_inst > MAX_INSTANCES || (n_inst > 1 && (d->inst_stride <= 0 || (d->inst_stride & 255)))) return CSGS_EINVAL;
     *out = carve(d->base, d->n_nodes, d->nS_max, d->B_max, d->edges_max);
-    return out->bytes <= d->bytes ? CSGS_OK : CSGS_EWORKSPACE;
+    out->n_inst = n_inst;
+    out->buf_stride = n_inst > 1 ? d->inst_stride : 0;
+    return out->bytes * (size_t)n_inst <= d->bytes ? CSGS_OK : CSGS_EWORKSPACE;
 }
+
+__host__ inline InstStride inst_stride(const Workspace &w) { return InstStride{(int64_t)w.bytes, w.buf_stride}; }
 
 // Grid of a kernel whose blocks wait for each other and stride over a tile count known only on
 // the device: resident_grid(per_cu) blocks of 256 threads, per_cu per compute unit.  Such a kernel

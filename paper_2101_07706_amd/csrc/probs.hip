@@ -37,8 +37,11 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
                                                   uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
                                                   int64_t *__restrict__ meta, int64_t edge_cap,
-                                                  int32_t *__restrict__ status)
+                                                  int32_t *__restrict__ status, InstStride is)
 {
+    S = inst_ptr(S, is.buf); nS_dev = inst_ptr(nS_dev, is.buf); status = inst_ptr(status, is.buf);
+    epoch = inst_ptr(epoch, is.ws); ts_mem = inst_ptr(ts_mem, is.ws); eoff = inst_ptr(eoff, is.ws);
+    rowstart = inst_ptr(rowstart, is.ws); meta = inst_ptr(meta, is.ws);
     const TileState<1> ts(ts_mem, ts_tiles, wait_limit(epoch));
     const int32_t nS = resolve_count(nS_bound, nS_dev);
     const int64_t n_tiles = row_tiles(nS);
@@ -53,9 +56,12 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status)
+                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status, InstStride is)
 {
     __shared__ RowSlice slice;
+    meta = inst_ptr(meta, is.ws); eoff = inst_ptr(eoff, is.ws); rowstart = inst_ptr(rowstart, is.ws);
+    wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); chunk_note = inst_ptr(chunk_note, is.ws);
+    status = inst_ptr(status, is.buf);
     const int32_t nS = (int32_t)meta[META_ROWS];
     const double scale = ldexp(1.0, shift_for_rows(shift_base, nS));
     const int64_t E = meta[META_EDGES];
@@ -132,9 +138,12 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
                                                      int64_t n_nodes, int64_t n_tiles, int32_t lo, int32_t hi,
                                                      const uint64_t *__restrict__ epoch, unsigned long long *__restrict__ cand_flag,
                                                      unsigned long long *__restrict__ partial,
-                                                     uint64_t *__restrict__ gtot, int32_t *__restrict__ status)
+                                                     uint64_t *__restrict__ gtot, int32_t *__restrict__ status, InstStride is)
 {
     __shared__ uint64_t lds[4][3];
+    wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); epoch = inst_ptr(epoch, is.ws);
+    cand_flag = inst_ptr(cand_flag, is.ws); partial = inst_ptr(partial, is.ws); gtot = inst_ptr(gtot, is.ws);
+    status = inst_ptr(status, is.buf);
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;
@@ -183,9 +192,13 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
                                                  uint64_t *__restrict__ epoch,
                                                  csgs_prob_stats *__restrict__ stats, int32_t *__restrict__ status,
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
-                                                 uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap)
+                                                 uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap, InstStride is)
 {
     __shared__ uint32_t s_cnt[CAND_WORDS];
+    wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); partial = inst_ptr(partial, is.ws);
+    gtot = inst_ptr(gtot, is.ws); meta = inst_ptr(meta, is.ws); epoch = inst_ptr(epoch, is.ws);
+    stats = inst_ptr(stats, is.buf); status = inst_ptr(status, is.buf); cand_id = inst_ptr(cand_id, is.buf);
+    cand_w = inst_ptr(cand_w, is.buf); cdf = inst_ptr(cdf, is.buf); q = inst_ptr(q, is.buf);
     __shared__ uint64_t s_w[CAND_WORDS];
     __shared__ uint64_t s_red[4][6];
     const int lane = lane_id();
@@ -340,8 +353,9 @@ int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_
                             const Workspace &w, const RowOffsets &rows, int32_t *status, hipStream_t st)
 {
     const unsigned tiles = (unsigned)(((int64_t)nS + ROW_TILE - 1) / ROW_TILE);
-    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev, w.epoch, w.rp_ts,
-                w.rp_tiles, rows.eoff, rows.rowstart, rows.meta, w.chunk_cap * EDGE_TILE, status);
+    CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles, 1, (unsigned)w.n_inst), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev,
+                w.epoch, w.rp_ts, w.rp_tiles, rows.eoff, rows.rowstart, rows.meta, w.chunk_cap * EDGE_TILE, status,
+                inst_stride(w));
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -370,7 +384,7 @@ extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
     Workspace w;
     const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
     if (rc != CSGS_OK) return rc;
-    const size_t n = w.bytes / 8;
+    const size_t n = w.bytes * (size_t)w.n_inst / 8;
     const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
     CSGS_LAUNCH(K_FILL_ZERO, fill_zero, dim3(blocks), dim3(256), (hipStream_t)stream, (uint64_t *)ws->base, n);
     CSGS_LAUNCH_CHECK();
@@ -378,7 +392,8 @@ extern "C" int csgs_workspace_init(csgs_workspace *ws, void *stream)
 }
 
 namespace csgs {
-__global__ void set_word(uint64_t *p, uint64_t v) { *p = v; }
+// one block per instance
+__global__ void set_word(uint64_t *p, uint64_t v, int64_t stride) { *(uint64_t *)((char *)p + (int64_t)blockIdx.x * stride) = v; }
 }  // namespace csgs
 
 extern "C" int csgs_workspace_wait_limit(csgs_workspace *ws, int64_t polls, void *stream)
@@ -388,7 +403,8 @@ extern "C" int csgs_workspace_wait_limit(csgs_workspace *ws, int64_t polls, void
     const int rc = open_workspace(ws, ws->n_nodes, 1, 1, &w);
     if (rc != CSGS_OK) return rc;
     const uint64_t v = polls < 0 ? 0ull : (uint64_t)(polls > 0x7FFFFFF0ll ? 0x7FFFFFF0ll : polls) + 1ull;
-    CSGS_LAUNCH(K_FILL_ZERO, csgs::set_word, dim3(1), dim3(1), (hipStream_t)stream, w.epoch + EPOCH_WAIT, v);
+    CSGS_LAUNCH(K_FILL_ZERO, csgs::set_word, dim3((unsigned)w.n_inst), dim3(1), (hipStream_t)stream, w.epoch + EPOCH_WAIT, v,
+                (int64_t)w.bytes);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -441,16 +457,18 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
     }
     ws->has_next = 0;
     const RowOffsets &rows = w.rows[ws->rows_buf & 1];
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, shift_base,
-                rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable, w.tileflag, rows.chunk_note, status);
+    const unsigned nz = (unsigned)w.n_inst;
+    const InstStride is = inst_stride(w);
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID, 1, nz), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, shift_base,
+                rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable, w.tileflag, rows.chunk_note, status, is);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles, 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,
-                (unsigned long long *)w.partial, w.gtot, status);
+                (unsigned long long *)w.partial, w.gtot, status, is);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles), dim3(256), st, w.wtable, w.tileflag, n_words,
+    CSGS_LAUNCH(K_CAND_EMIT, cand_emit, dim3((unsigned)w.n_tiles, 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, pol, w.partial, w.gtot, rows.meta, shift_base, w.epoch, stats, status, cand_id,
-                cand_w, cdf, q, cap);
+                cand_w, cdf, q, cap, is);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

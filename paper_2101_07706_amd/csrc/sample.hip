@@ -57,9 +57,11 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
                                                    const uint64_t *__restrict__ iter_dev, uint32_t layer,
                                                    uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
                                                    const uint64_t *__restrict__ epoch, uint64_t *__restrict__ rank,
-                                                   int64_t n_nodes)
+                                                   int64_t n_nodes, InstStride is)
 {
     __shared__ uint64_t top[TOP];
+    cdf = inst_ptr(cdf, is.buf); stats = inst_ptr(stats, is.buf);
+    hit = inst_ptr(hit, is.ws); cbitmap = inst_ptr(cbitmap, is.ws); epoch = inst_ptr(epoch, is.ws); rank = inst_ptr(rank, is.ws);
     // rank entries carry the low 32 bits of the call number; when those wrap, stale entries could
     // look current, so the table is wiped once every 2^32 calls (the compaction kernel that follows
     // writes the new entries)
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
             rank[i] = 0ull;
     }
     if (iter_dev) iter = *iter_dev;
+    iter += blockIdx.z;   // consecutive instances are consecutive iterations
     const uint32_t iter_lo = (uint32_t)iter, iter_hi = (uint32_t)(iter >> 32);
     int64_t n = stats->n_cand;
     if (n > cand_cap) n = cand_cap;
@@ -131,9 +134,14 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
                                                   uint64_t *__restrict__ rank, int32_t *__restrict__ S_next,
                                                   int32_t *__restrict__ mult, float *__restrict__ p_incl,
                                                   double *__restrict__ pdbl, int32_t *__restrict__ n_next,
-                                                  int32_t *__restrict__ status)
+                                                  int32_t *__restrict__ status, InstStride is)
 {
     __shared__ uint32_t lds[17];
+    cand_id = inst_ptr(cand_id, is.buf); cdf = inst_ptr(cdf, is.buf); stats = inst_ptr(stats, is.buf);
+    S_next = inst_ptr(S_next, is.buf); mult = inst_ptr(mult, is.buf); p_incl = inst_ptr(p_incl, is.buf);
+    n_next = inst_ptr(n_next, is.buf); status = inst_ptr(status, is.buf);
+    epoch = inst_ptr(epoch, is.ws); ts_mem = inst_ptr(ts_mem, is.ws); hit = inst_ptr(hit, is.ws);
+    cbitmap = inst_ptr(cbitmap, is.ws); rank = inst_ptr(rank, is.ws); pdbl = inst_ptr(pdbl, is.ws);
     __shared__ unsigned long long s_lb[1];
     __shared__ uint16_t s_list[HIT_TILE_WORDS * 64];   // drawn positions of the tile, ascending
     const TileState<1> ts(ts_mem, ts_tiles, wait_limit(epoch));
@@ -314,12 +322,17 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ adj_rowptr,
                                                  int32_t *__restrict__ adj_col, float *__restrict__ adj_val,
                                                  int64_t adj_cap, int64_t *__restrict__ adj_nnz,
-                                                 int32_t *__restrict__ status, RemoteArgs rem, NextRows nxt)
+                                                 int32_t *__restrict__ status, RemoteArgs rem, NextRows nxt, InstStride is)
 {
+    status = inst_ptr(status, is.buf);
+    epoch = inst_ptr(epoch, is.ws);
     // The leading rem.blocks blocks split the new node set into local and remote (what
     // csgs_remote_count does: it needs only S_next / n_next, complete since the previous kernel) so
     // that a layer step is one launch shorter; they wait for nobody and nobody waits for them.
     if ((int32_t)blockIdx.x < rem.blocks) {
+        rem.S_next = inst_ptr(rem.S_next, is.buf); rem.n_next = inst_ptr(rem.n_next, is.buf);
+        rem.remote_total = inst_ptr(rem.remote_total, is.buf); rem.per_part = inst_ptr(rem.per_part, is.buf);
+        rem.src_row = inst_ptr(rem.src_row, is.buf); rem.remote_ids = inst_ptr(rem.remote_ids, is.buf);
         remote_count_body(rem, (int32_t)blockIdx.x, rem.blocks);
         return;
     }
@@ -327,6 +340,9 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
     // (lower tiles, dispatched before them); their flags are tagged with the draw's call number,
     // which the previous kernel wrote, so the counter this kernel advances at its end does not matter.
     if ((int32_t)blockIdx.x < rem.blocks + nxt.blocks) {
+        nxt.S_next = inst_ptr(nxt.S_next, is.buf); nxt.n_next = inst_ptr(nxt.n_next, is.buf);
+        nxt.ts_mem = inst_ptr(nxt.ts_mem, is.ws); nxt.eoff = inst_ptr(nxt.eoff, is.ws);
+        nxt.rowstart = inst_ptr(nxt.rowstart, is.ws); nxt.meta = inst_ptr(nxt.meta, is.ws);
         const int32_t n = resolve_count(nxt.bound, nxt.n_next);
         const int64_t t = (int64_t)blockIdx.x - rem.blocks, n_tiles = row_tiles(n);
         if (t < n_tiles) {
@@ -336,6 +352,11 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         }
         return;
     }
+    meta = inst_ptr(meta, is.ws); eoff = inst_ptr(eoff, is.ws); rowstart = inst_ptr(rowstart, is.ws);
+    rank = inst_ptr(rank, is.ws); pdbl = inst_ptr(pdbl, is.ws); ts_mem = inst_ptr(ts_mem, is.ws);
+    chunk_note = inst_ptr(chunk_note, is.ws);
+    adj_rowptr = inst_ptr(adj_rowptr, is.buf); adj_col = inst_ptr(adj_col, is.buf); adj_val = inst_ptr(adj_val, is.buf);
+    adj_nnz = inst_ptr(adj_nnz, is.buf);
     const int64_t bid = (int64_t)blockIdx.x - rem.blocks - nxt.blocks;
     const int64_t n_bids = (int64_t)gridDim.x - rem.blocks - nxt.blocks;
     __shared__ RowSlice slice;
@@ -468,15 +489,17 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
     hipStream_t st = (hipStream_t)stream;
     if (cand_cap > n_nodes) cand_cap = n_nodes;  // there are never more candidates than nodes
 
-    CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK)), dim3(DRAW_BLOCK), st, cdf, stats,
+    const unsigned nz = (unsigned)w.n_inst;
+    const InstStride is = inst_stride(w);
+    CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK), 1, nz), dim3(DRAW_BLOCK), st, cdf, stats,
                 cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), iter, iter_dev, layer, w.hit, w.cbitmap, w.epoch, w.rank,
-                n_nodes);
+                n_nodes, is);
     CSGS_LAUNCH_CHECK();
     const int64_t cap_words = (cand_cap + 63) / 64;
     const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
     const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid(1) ? hit_tiles : resident_grid(1));
-    CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
-                w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status);
+    CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks, 1, nz), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
+                w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status, is);
     CSGS_LAUNCH_CHECK();
     ws->has_draw = 1;
     ws->draw_B = B;
@@ -514,15 +537,16 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     }
     ws->has_next = nxt.blocks > 0;
     // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
-    const dim3 grid((unsigned)(resident_grid(2) + rem.blocks + nxt.blocks));
+    const dim3 grid((unsigned)(resident_grid(2) + rem.blocks + nxt.blocks), 1, (unsigned)w.n_inst);
+    const InstStride is = inst_stride(w);
     if (reuse_offsets)
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
                     g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
-                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt);
+                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt, is);
     else
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
                     g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
-                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt);
+                    adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt, is);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -31,33 +31,56 @@ class DeviceGraph:
 
 
 class Workspace:
-    def __init__(self, n_nodes, nS_max, B_max, edges_max, device):
+    """Scratch memory of the sampling calls.  n_inst > 1: one workspace per instance back to back;
+    calls through it process n_inst instances whose arrays lie inst_stride bytes apart (the layout
+    LayerBuffers(n_inst=...) gives them)."""
+
+    def __init__(self, n_nodes, nS_max, B_max, edges_max, device, n_inst=1, inst_stride=0):
         nbytes = csgs.csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max)
-        assert nbytes > 0
-        self.buf = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
+        assert nbytes > 0 and nbytes % 256 == 0
+        self.bytes_per_inst = nbytes
+        self.buf = torch.empty(n_inst * nbytes // 8, dtype=torch.int64, device=device)
         assert self.buf.data_ptr() % 256 == 0
-        self.desc = csgs.make_workspace(self.buf, n_nodes, nS_max, B_max, edges_max)
+        self.desc = csgs.make_workspace(self.buf, n_nodes, nS_max, B_max, edges_max, n_inst, inst_stride)
         csgs.csgs_workspace_init(self.desc)
 
 
 class LayerBuffers:
-    """Outputs of one sampling step (one GCN layer)."""
+    """Outputs of one sampling step (one GCN layer), and S0, a place for the rows of the first layer.
 
-    def __init__(self, nS_max, B, cand_cap, adj_cap, n_parts, device):
+    n_inst > 1: the arrays of n_inst instances, every instance's in one contiguous block of
+    `stride` bytes with the same layout, so that one library call can fill all of them; the
+    attributes are instance 0's arrays (what the calls take), inst(k) gives instance k's."""
+
+    def __init__(self, nS_max, B, cand_cap, adj_cap, n_parts, device, n_inst=1, _share=None, _k=0):
         i32, i64, f32 = torch.int32, torch.int64, torch.float32
-        e = lambda n, dt: torch.empty(max(int(n), 1), dtype=dt, device=device)
-        self.cand_id, self.cand_w, self.cdf, self.q = e(cand_cap, i32), e(cand_cap, i64), e(cand_cap, i64), e(cand_cap, f32)
-        self.stats = torch.zeros(8, dtype=i64, device=device)
-        self.S_next, self.mult, self.p_incl = e(B, i32), e(B, i32), e(B, f32)
-        self.n_next = torch.zeros(1, dtype=i32, device=device)
-        self.adj_rowptr, self.adj_col, self.adj_val = e(nS_max + 1, i32), e(adj_cap, i32), e(adj_cap, f32)
-        self.adj_nnz = torch.zeros(1, dtype=i64, device=device)
-        self.remote_total = torch.zeros(1, dtype=i64, device=device)
-        self.per_part = torch.zeros(n_parts, dtype=i64, device=device)
-        self.src_row, self.remote_ids = e(B, i32), e(B, i32)
-        self.status = torch.zeros(1, dtype=i32, device=device)
+        cand_cap, adj_cap = max(int(cand_cap), 1), max(int(adj_cap), 1)
+        fields = [("cand_id", cand_cap, i32), ("cand_w", cand_cap, i64), ("cdf", cand_cap, i64), ("q", cand_cap, f32),
+                  ("stats", 8, i64), ("S_next", B, i32), ("mult", B, i32), ("p_incl", B, f32), ("n_next", 1, i32),
+                  ("adj_rowptr", nS_max + 1, i32), ("adj_col", adj_cap, i32), ("adj_val", adj_cap, f32), ("adj_nnz", 1, i64),
+                  ("remote_total", 1, i64), ("per_part", max(n_parts, 1), i64), ("src_row", B, i32), ("remote_ids", B, i32),
+                  ("status", 1, i32), ("S0", nS_max, i32)]
+        off = 0
+        layout = []
+        for name, n, dt in fields:
+            nbytes = n * torch.empty(0, dtype=dt).element_size()
+            layout.append((name, off, nbytes, dt))
+            off = (off + nbytes + 255) // 256 * 256
+        self.stride = off
+        self.n_inst = n_inst
+        self._args = (nS_max, B, cand_cap, adj_cap, n_parts, device)
+        self.raw = _share if _share is not None else torch.zeros((n_inst, off), dtype=torch.uint8, device=device)
+        assert self.raw.data_ptr() % 256 == 0
+        row = self.raw[_k]
+        for name, o, nbytes, dt in layout:
+            setattr(self, name, row[o:o + nbytes].view(dt))
         self.B = B
         self.remote = None     # csgs_remote_out over these buffers, made on first use (needs the partition bounds)
+
+    def inst(self, k):
+        """The arrays of instance k (views of the same memory)."""
+        assert 0 <= k < self.n_inst
+        return LayerBuffers(*self._args, n_inst=self.n_inst, _share=self.raw, _k=k)
 
     def stats_host(self):
         raw = self.stats.cpu().numpy().tobytes()

@@ -143,6 +143,68 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
     return steps, ws
 
 
+def gpu_chain_instances(g, X, Ws, S0s, skew, B, seed, it, bf16, auto_D=None, chained=True):
+    """len(S0s) mini-batches sampled by the same library calls (instance k: rows S0s[k], iteration
+    it + k), then the layer compute of every instance.  Returns one list of steps per instance."""
+    import torch
+    from paper_2101_07706_amd import pipeline
+    dev = torch.device("cuda:0")
+    dg = pipeline.DeviceGraph(g, dev)
+    M, K, n0 = len(Ws), len(S0s), len(S0s[0])
+    assert all(len(s) == n0 for s in S0s)
+    nS_max = max(n0, B)
+    cap = min(g.nnz, 1 << 24)
+    lbs = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, cap, dg.n_parts, dev, n_inst=K) for _ in range(M)]
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev, n_inst=K, inst_stride=lbs[0].stride)
+    Xd = torch.from_numpy(synth.to_bf16_bits(X).view(np.int16) if bf16 else X).to(dev)
+    Wd = [torch.from_numpy(W).to(dev) for W in Ws]
+    for k in range(K):
+        lbs[0].inst(k).S0[:n0].copy_(torch.from_numpy(np.ascontiguousarray(S0s[k], np.int32)))
+    torch.cuda.synchronize()
+    for l in range(M):
+        if l == 0:
+            S, nS_dev = lbs[0].S0[:n0], None
+        elif chained:
+            S, nS_dev = None, None
+        else:
+            S, nS_dev = lbs[l - 1].S_next, lbs[l - 1].n_next
+        pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lbs[l], auto_D=auto_D, nS_dev=nS_dev)
+    X_local = Xd[g.local_lo:g.local_hi]
+    staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
+    out = []
+    for k in range(K):
+        lk = [lb.inst(k) for lb in lbs]
+        Zs = [torch.full((n0 if l == 0 else B, Wd[M - 1 - l].shape[0]), float("nan"), dtype=torch.float32, device=dev)
+              for l in range(M)]
+        Hs = [torch.full((n0 if l == 0 else B, Wd[M - 1 - l].shape[1]), float("nan"), dtype=torch.float32, device=dev)
+              for l in range(M)]
+        pipeline.stage_remote_rows(lk[M - 1], Xd, staged)
+        for l in range(M - 1, -1, -1):
+            nS = n0 if l == 0 else B
+            nS_dev = None if l == 0 else lk[l - 1].n_next
+            if l == M - 1:
+                pipeline.compute_step(lk[l], nS, X_local, staged, True, False, Wd[0], Zs[l], Hs[l], nS_dev=nS_dev)
+            else:
+                pipeline.compute_step(lk[l], nS, Hs[l + 1], None, False, True, Wd[M - 1 - l], Zs[l], Hs[l], nS_dev=nS_dev)
+        torch.cuda.synchronize()
+        steps = []
+        for l in range(M):
+            n_rows = n0 if l == 0 else int(lk[l - 1].n_next.item())
+            steps.append(SimpleNamespace(S=None, lb=lk[l], n_next=int(lk[l].n_next.item()), status=int(lk[l].status.item()),
+                                         Z=Zs[l][:n_rows], H=Hs[l][:n_rows]))
+        out.append(steps)
+    clean = csgs_clean_words(g.n_nodes)
+    per = ws.bytes_per_inst // 8
+    for k in range(K):
+        assert int(torch.count_nonzero(ws.buf[k * per:k * per + clean]).item()) == 0, f"workspace {k} not restored"
+    return out
+
+
+def csgs_clean_words(n_nodes):
+    from paper_2101_07706_amd import csgs
+    return csgs.csgs_workspace_clean_bytes(n_nodes) // 8
+
+
 def u64(t):
     return t.cpu().numpy().view(np.uint64)
 

@@ -33,7 +33,7 @@ def test_every_declared_function_is_exported():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
     assert C.sizeof(csgs.Graph) == 56
-    assert C.sizeof(csgs.Workspace) == 64
+    assert C.sizeof(csgs.Workspace) == 80 and csgs.Workspace.n_inst.offset == 64 and csgs.Workspace.inst_stride.offset == 72
     assert C.sizeof(csgs.RemoteOut) == 56 and csgs.RemoteOut.remote_total.offset == 24
     assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48
     assert csgs.Workspace.has_draw.offset == 48 and csgs.Workspace.draw_B.offset == 56
@@ -135,3 +135,25 @@ def test_sampling_calls_reject_workspace_mismatch():
     assert L.csgs_sampled_adjacency(C.byref(g), p, 10, z, p, p, p, 100, p, C.byref(ws), st, z) == csgs.EINVAL
     # skew below 1, fixed-point range
     assert L.csgs_build_probs(C.byref(g), p, 64, z, 0.5, p, p, p, z, 1000, p, C.byref(ws), st, z) == csgs.EINVAL
+
+
+def test_instance_descriptors_are_checked():
+    """Several instances per call: the count, the stride and the buffer size are checked on the host."""
+    L = csgs.lib()
+    z, p = C.c_void_p(0), C.c_void_p(4096)
+    g = csgs.Graph(1000, 5000, 4096, 4096, 4096, 0, 500, 1.0)
+    st = C.c_void_p(8192)
+    per = csgs.csgs_workspace_bytes(1000, 64, 64, 5000)
+
+    def probs(ws):
+        return L.csgs_build_probs(C.byref(g), p, 65, z, 2.0, p, p, p, z, 1000, p, C.byref(ws), st, z)
+
+    def desc(nbytes, n_inst, stride):
+        return csgs.Workspace(4096, nbytes, 1000, 64, 64, 5000, 0, 0, 0, 0, n_inst, 0, stride)
+
+    # (nS = 65 exceeds nS_max, so a descriptor that passes the instance checks ends in EWORKSPACE, before any launch)
+    assert probs(desc(4 * per, 4, 1 << 20)) == csgs.EWORKSPACE
+    assert L.csgs_workspace_init(C.byref(desc(4 * per - 256, 4, 1 << 20)), z) == csgs.EWORKSPACE   # room for three only
+    assert L.csgs_workspace_init(C.byref(desc(4 * per, 4, 0)), z) == csgs.EINVAL                   # no stride
+    assert L.csgs_workspace_init(C.byref(desc(4 * per, 4, 1000)), z) == csgs.EINVAL                # not a multiple of 256
+    assert L.csgs_workspace_init(C.byref(desc(100 * per, 65, 1 << 20)), z) == csgs.EINVAL          # too many

@@ -457,6 +457,29 @@ def test_chain_on_prepared_rows(dev, name):
         say(f"[{name}] n' per layer {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
 
 
+# ---------------------------------------------------------------- several mini-batches per call
+@pytest.mark.parametrize("name,K,chained", [("tiny", 3, True), ("tiny", 2, False), ("medium", 4, True), ("mid", 2, True),
+                                             ("large", 3, True)])
+def test_instances_per_call(dev, name, K, chained):
+    """K mini-batches of consecutive iterations through the same sampling calls (n_inst = K in the
+    workspace descriptor): every instance equals the oracle's chain for its batch and iteration."""
+    it = 4
+    if name == "large":
+        cfg, g, X, Ws, _ = cached_inputs("large")
+    else:
+        cfg, g, X, Ws, _ = chain.config_inputs(name, it)
+    S0s = [synth.make_batch(g, cfg.batch, cfg.seed, it + k) for k in range(K)]
+    bf16 = cfg.feat_dtype == "bf16"
+    say(f"[{name}] {K} instances per call, chained={chained}")
+    auto_D = 8.0 if (name == "tiny" and not chained) else None
+    got = chain.gpu_chain_instances(g, X, Ws, S0s, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
+                                    chained=chained)
+    for k in range(K):
+        osteps = chain.oracle_chain(g, X, Ws, S0s[k], cfg.skew, cfg.samples, 1234 + cfg.seed, it + k, bf16, auto_D=auto_D)
+        worst = chain.compare_chain(osteps, got[k])
+        say(f"[{name}] instance {k}: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+
+
 def test_prepared_rows_need_a_matching_sample_layer(dev):
     """csgs_build_probs(S = NULL) is refused on the host when no csgs_sample_layer has prepared rows,
     when nS is not that call's B, when a device count is given, and after the rows were consumed."""
