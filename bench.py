@@ -51,7 +51,7 @@ def algorithmic_bytes(s, N):
 
 
 class Workload:
-    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1):
+    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1, n_inst=1):
         self.cfg, self.g, self.dg, self.Xd, self.dev = cfg, g, dg, Xd, dev
         self.torch, self.pipeline, self.csgs = torch, pipeline, csgs
         self.bf16 = cfg.feat_dtype == "bf16"
@@ -66,16 +66,20 @@ class Workload:
         self.Sd = [torch.from_numpy(b).to(dev) for b in self.batches]
         M, B, dims = self.M, self.B, self.dims
         nS_max = max(len(self.batches[0]), B)
-        self.n_samplers = n_samplers
-        self.wss = [pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev) for _ in range(n_samplers)]   # one per sampling stream
-        self.ws = self.wss[0]
-        adj_cap = int(min(g.nnz, 48_000_000))
-        # sets of sampling outputs: while the layers of one batch are computed from one set, later batches
-        # are sampled into the others
+        self.n_samplers, self.n_inst = n_samplers, n_inst
+        adj_cap = int(min(g.nnz, 16_000_000))
+        # one mini-batch per call: the one-stream (latency) measurement and the backward pass
+        self.lbs1 = [pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
+        self.ws1 = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev)
+        # the timed schedule: n_inst mini-batches per sampling call.  Sets of sampling outputs: while the
+        # layers of one group of batches are computed from one set, later groups are sampled into the others
         self.n_sets = 2 * n_samplers
-        self.lb_sets = [[pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev) for _ in range(M)]
+        self.lb_sets = [[pipeline.LayerBuffers(nS_max, B, g.n_nodes, adj_cap, dg.n_parts, dev, n_inst=n_inst) for _ in range(M)]
                         for _ in range(self.n_sets)]
-        self.lbs = self.lb_sets[0]
+        self.wss = [pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev, n_inst=n_inst, inst_stride=self.lb_sets[0][0].stride)
+                    for _ in range(n_samplers)]   # one per sampling stream
+        self.lb_inst = [[[lb.inst(k) for lb in lbs] for k in range(n_inst)] for lbs in self.lb_sets]   # [set][instance][layer]
+        self.lbs = self.lbs1
         self.overlap = None
         self.use_graphs = True
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
@@ -84,8 +88,9 @@ class Workload:
         self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
 
     def enqueue_sampling(self, S0, it, lbs, ws):
-        """Top-down sampling calls of one mini-batch on the current stream; `it` is a number or a
-        device uint64 tensor."""
+        """Top-down sampling calls on the current stream, for one mini-batch or, when `ws` and `lbs`
+        hold several instances, for that many at once (instance k: the rows at S0 + k strides, iteration
+        it + k); `it` is a number or a device uint64 tensor."""
         cfg, M, B, pipeline = self.cfg, self.M, self.B, self.pipeline
         it_num, it_dev = (0, it) if hasattr(it, "data_ptr") else (it, None)
         for l in range(M):
@@ -123,14 +128,14 @@ class Workload:
                 cap=cap, dW=torch.empty((K, N), device=dev), dZ=torch.empty((cap, K), device=dev),
                 dH=torch.empty((B, K), device=dev) if l < M - 1 else None,
                 sw=i8(csgs.csgs_layer_gemm_grad_w_scratch_bytes(cap, K, N)),
-                sa=i8(csgs.csgs_aggregate_grad_scratch_bytes(B, self.lb_sets[0][l].adj_col.numel())) if l < M - 1 else None))
+                sa=i8(csgs.csgs_aggregate_grad_scratch_bytes(B, self.lbs1[l].adj_col.numel())) if l < M - 1 else None))
         g = torch.Generator(device="cpu").manual_seed(5)
         self.G_top = torch.randn((n0, dims[0][1] if M == 1 else dims[M - 1][1]), generator=g).to(dev)
 
     def backward(self):
-        """Gradients of all layers for the batch whose forward pass is in lb_sets[0] / Zs / Hs: top layer
+        """Gradients of all layers for the batch whose forward pass is in lbs1 / Zs / Hs: top layer
         first, each layer's dH_prev is the next one's dL/dH; row counts stay on the device."""
-        csgs, M, B, lbs = self.csgs, self.M, self.B, self.lb_sets[0]
+        csgs, M, B, lbs = self.csgs, self.M, self.B, self.lbs1
         G = self.G_top
         for l in range(M):
             bw, lb = self.bw[l], lbs[l]
@@ -162,7 +167,7 @@ class Workload:
         torch.cuda.synchronize()
         csgs.csgs_profile_enable(False)
         prof = csgs.csgs_profile_collect()
-        sizes = [int(self.Sd[0].numel())] + [int(self.lb_sets[0][l].n_next.item()) for l in range(self.M - 1)]
+        sizes = [int(self.Sd[0].numel())] + [int(self.lbs1[l].n_next.item()) for l in range(self.M - 1)]
         flops = sum(4.0 * sizes[l] * self.dims[self.M - 1 - l][0] * self.dims[self.M - 1 - l][1] for l in range(self.M))
         gemm_ms = sum(prof[k][0] for k in ("gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce") if k in prof)
         return dict(ms_per_step=ms, gemm_TFLOPs=flops * steps / (gemm_ms * 1e-3) / 1e12,
@@ -170,146 +175,177 @@ class Workload:
                              for k, v in sorted(prof.items(), key=lambda kv: -kv[1][0])})
 
     def prepare_overlap(self):
-        """Streams, events and, per buffer set, the step's library calls captured into two HIP graphs
-        (sampling, compute).  What differs from step to step goes through device memory: the batch
-        is copied into the set's batch buffer and the iteration number into a device word before
-        the sampling graph is replayed.  A kernel launch costs the host 4-5 us and a step has 28,
-        so launching them one by one cannot keep three streams fed; a replay is one call."""
-        torch = self.torch
+        """Streams, events and, per buffer set, the library calls of a group of n_inst mini-batches
+        captured into two HIP graphs (sampling of all of them at once, layer compute one after the
+        other).  What differs from replay to replay goes through device memory: the set's iteration
+        numbers select its batches from the resident batch table, and the sampling graph advances
+        them itself.  A kernel launch costs the host 4-5 us, so launching a step's kernels one by one
+        cannot keep three streams fed; a replay is one call."""
+        torch, K, dev = self.torch, self.n_inst, self.dev
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
         s_comp = torch.cuda.Stream()
         self.S_all = torch.stack(self.Sd)        # all batches, resident: [n_batches, batch]
+        n0 = self.Sd[0].numel()
         sets = []
         for k in range(self.n_sets):
             s_samp = samplers[k % self.n_samplers]
-            S0 = torch.zeros_like(self.Sd[0])
-            it_dev = torch.zeros(1, dtype=torch.int64, device=self.dev)
+            lbs, ws = self.lb_sets[k], self.wss[k % self.n_samplers]
+            lb0 = lbs[0]
+            # first-layer rows of all instances: the S0 arrays of the set, one stride apart
+            S0_all = torch.as_strided(lb0.S0, (K, n0), (lb0.stride // 4, 1))
+            idx = torch.arange(K, dtype=torch.int64, device=dev)      # iteration number of every instance
+            tmp = torch.zeros((K, n0), dtype=self.S_all.dtype, device=dev)
+
+            def fill(idx=idx, tmp=tmp, S0_all=S0_all):
+                torch.index_select(self.S_all, 0, idx, out=tmp)       # the batches of these iterations
+                S0_all.copy_(tmp)
+
+            def sample(idx=idx, lbs=lbs, ws=ws, lb0=lb0, fill=fill):
+                fill()
+                self.enqueue_sampling(lb0.S0[:n0], idx, lbs, ws)      # the library reads idx[0]; instance k uses idx[0] + k
+
+            def compute(k=k):
+                H = None
+                for lk in self.lb_inst[k]:
+                    H = self.enqueue_compute(lk, n0)
+                return H
+
             # one eager pass on the streams the graphs will run on, then capture
-            S0.copy_(self.Sd[0])
             torch.cuda.synchronize()
             with torch.cuda.stream(s_samp):
-                self.enqueue_sampling(S0, it_dev, self.lb_sets[k], self.wss[k % self.n_samplers])
+                sample()
             torch.cuda.synchronize()
             with torch.cuda.stream(s_comp):
-                self.enqueue_compute(self.lb_sets[k], S0.numel())
+                compute()
             torch.cuda.synchronize()
             g_samp = g_comp = None
-            H = self.Hs[0][:S0.numel()]
             if self.use_graphs:
                 try:
                     g_samp, g_comp = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
                     with torch.cuda.graph(g_samp, stream=s_samp):
-                        # the batch of this replay: row it_dev of the resident batch table; the next replay
-                        # of this set is n_sets batches later
-                        torch.index_select(self.S_all, 0, it_dev, out=S0.view(1, -1))
-                        self.enqueue_sampling(S0, it_dev, self.lb_sets[k], self.wss[k % self.n_samplers])
-                        it_dev.add_(self.n_sets)
+                        sample()
+                        idx.add_(K * self.n_sets)     # the next replay of this set is n_sets groups later
                     with torch.cuda.graph(g_comp, stream=s_comp):
-                        self.enqueue_compute(self.lb_sets[k], S0.numel())
+                        compute()
                 except Exception as e:      # said out loud and recorded in the JSON line; the calls are then issued one by one
                     log(f"graph capture failed ({e!r}); launching the calls directly")
                     self.use_graphs = False
                     g_samp = g_comp = None
             torch.cuda.synchronize()
-            sets.append(dict(S0=S0, it=it_dev, sample=g_samp, compute=g_comp, H=H, s_samp=s_samp,
-                             samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
-        self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=self.dev)   # iteration numbers, resident
-        self.graph_it = [None] * self.n_sets     # iteration number each set's counter will use at its next replay
+            sets.append(dict(idx=idx, sample=g_samp, compute=g_comp, sample_fn=sample, compute_fn=compute,
+                             H=self.Hs[0][:n0], s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(),
+                             used=False))
+        self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=dev)   # iteration numbers, resident
+        self.graph_it = [None] * self.n_sets     # first iteration number each set's counters hold for its next replay
         self.overlap = dict(sets=sets, s_comp=s_comp)
 
-    def step(self, it, sizes=None, overlap=False):
-        """One whole mini-batch, enqueued without the host waiting for anything: each layer's row
-        count stays on the device (the n_dev arguments), launches are sized for the capacities.
-        overlap: the sampling (top-down) of consecutive batches goes round-robin to n_samplers streams,
-        each with its own workspace, and the layer compute (bottom-up) of all batches, in batch order,
-        to one more stream; events tie a batch's compute to its sampling and a buffer set's reuse to
-        the compute that read it.  This is how a training loop runs its sampler ahead: sampling
-        does not depend on the model weights, the compute of consecutive batches does.  Every step
-        still does all of its work."""
-        M, B = self.M, self.B
-        n0 = self.Sd[it].numel()
-        if overlap:
-            if self.overlap is None:
-                self.prepare_overlap()
-            st = self.overlap["sets"][it % self.n_sets]
-            s_comp = self.overlap["s_comp"]
-            lbs = self.lb_sets[it % self.n_sets]
-            torch = self.torch
-            with torch.cuda.stream(st["s_samp"]):
-                if st["used"]:
-                    st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batch sampled into it was computed
-                k = it % self.n_sets
-                if st["sample"] is not None:
-                    if self.graph_it[k] != it:   # (re)seat the set's device counter; consecutive replays advance it themselves
-                        st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
-                    st["sample"].replay()
-                    self.graph_it[k] = it + self.n_sets
-                else:
-                    st["S0"].copy_(self.Sd[it], non_blocking=True)
-                    st["it"].copy_(self.it_host[it:it + 1], non_blocking=True)
-                    self.enqueue_sampling(st["S0"], st["it"], lbs, self.wss[(it % self.n_sets) % self.n_samplers])
-                st["samp_done"].record(st["s_samp"])
-            with torch.cuda.stream(s_comp):
-                s_comp.wait_event(st["samp_done"])
-                if st["compute"] is not None:
-                    st["compute"].replay()
-                else:
-                    self.enqueue_compute(lbs, n0)
-                st["comp_done"].record(s_comp)
-            st["used"] = True
-            H = st["H"]
-        else:
-            lbs = self.lb_sets[0]
-            self.enqueue_sampling(self.Sd[it], it, lbs, self.wss[0])
-            H = self.enqueue_compute(lbs, n0)
-        self.lbs = lbs
-        if sizes is not None:
-            self.torch.cuda.synchronize()
-            for l in range(M):
-                st = lbs[l].stats_host()
-                sizes.append(dict(layer=l, nS=n0 if l == 0 else int(lbs[l - 1].n_next.item()), E=st.edges_scanned,
-                                  nc=st.n_cand, B=B, n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
-                                  remote=int(lbs[l].remote_total.item()), F_in=self.dims[M - 1 - l][0],
-                                  F_out=self.dims[M - 1 - l][1], elt=self.elt if l == M - 1 else 4,
-                                  status=int(lbs[l].status.item())))
-        return H
-
-    def measure(self, steps, warmup):
-        """Timed region, then the same steps again with every kernel launch bracketed by HIP events
-        (recorded on the launch stream)."""
-        torch, csgs = self.torch, self.csgs
-        for it in range(warmup):
-            self.step(it)
-        torch.cuda.synchronize()
-        # (1) one stream, steps back to back: the latency of a step
-        t0 = time.perf_counter()
-        for it in range(warmup, warmup + steps):
-            H = self.step(it)
-        torch.cuda.synchronize()
-        serial_ms = (time.perf_counter() - t0) / steps * 1e3
-        h_serial = H.clone()
-        # (2) the timed region proper: same steps in the overlapped schedule
+    def group(self, p):
+        """Mini-batches p * n_inst .. (p + 1) * n_inst - 1, enqueued without the host waiting for
+        anything.  Their sampling (top-down) is ONE sequence of library calls over n_inst instances;
+        consecutive groups go round-robin to n_samplers streams, each with its own workspace.  The
+        layer compute (bottom-up) of all batches runs in batch order on one more stream; events tie a
+        group's compute to its sampling and a buffer set's reuse to the compute that read it.  This is
+        how a training loop runs its sampler ahead: sampling does not depend on the model weights,
+        the compute of consecutive batches does.  Every step still does all of its work."""
+        torch, K = self.torch, self.n_inst
         if self.overlap is None:
             self.prepare_overlap()
-        for it in range(warmup):
-            self.step(it, overlap=True)
+        k = p % self.n_sets
+        st = self.overlap["sets"][k]
+        s_comp = self.overlap["s_comp"]
+        it0 = p * K
+        with torch.cuda.stream(st["s_samp"]):
+            if st["used"]:
+                st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batches sampled into it were computed
+            if st["sample"] is None or self.graph_it[k] != it0:   # (re)seat the set's counters; consecutive replays advance them
+                st["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
+            if st["sample"] is not None:
+                st["sample"].replay()
+                self.graph_it[k] = it0 + K * self.n_sets
+            else:
+                st["sample_fn"]()
+            st["samp_done"].record(st["s_samp"])
+        with torch.cuda.stream(s_comp):
+            s_comp.wait_event(st["samp_done"])
+            if st["compute"] is not None:
+                st["compute"].replay()
+            else:
+                st["compute_fn"]()
+            st["comp_done"].record(s_comp)
+        st["used"] = True
+        return st["H"]
+
+    def sizes_of(self, lbs, n0, sizes):
+        M, B = self.M, self.B
+        for l in range(M):
+            st = lbs[l].stats_host()
+            sizes.append(dict(layer=l, nS=n0 if l == 0 else int(lbs[l - 1].n_next.item()), E=st.edges_scanned,
+                              nc=st.n_cand, B=B, n_next=int(lbs[l].n_next.item()), nnz=int(lbs[l].adj_nnz.item()),
+                              remote=int(lbs[l].remote_total.item()), F_in=self.dims[M - 1 - l][0],
+                              F_out=self.dims[M - 1 - l][1], elt=self.elt if l == M - 1 else 4,
+                              status=int(lbs[l].status.item())))
+
+    def step(self, it, sizes=None):
+        """One whole mini-batch on the current stream, one instance per call, enqueued without the
+        host waiting for anything: each layer's row count stays on the device (the n_dev
+        arguments), launches are sized for the capacities."""
+        n0 = self.Sd[it].numel()
+        self.enqueue_sampling(self.Sd[it], it, self.lbs1, self.ws1)
+        H = self.enqueue_compute(self.lbs1, n0)
+        if sizes is not None:
+            self.torch.cuda.synchronize()
+            self.sizes_of(self.lbs1, n0, sizes)
+        return H
+
+    def measure(self, steps, warmup, serial=True):
+        """Timed region (steps and warmup are multiples of n_inst), then the same groups again on
+        one stream with every kernel launch bracketed by HIP events (recorded on the launch stream)."""
+        torch, csgs, K = self.torch, self.csgs, self.n_inst
+        assert steps % K == 0 and warmup % K == 0 and len(self.Sd) >= steps + warmup
+        n0 = self.Sd[0].numel()
+        # (1) one stream, one mini-batch per call, steps back to back: the latency of a step
+        serial_ms, h_serial = None, None
+        if serial:
+            for it in range(warmup):
+                self.step(it)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for it in range(warmup, warmup + steps):
+                H = self.step(it)
+            torch.cuda.synchronize()
+            serial_ms = (time.perf_counter() - t0) / steps * 1e3
+            h_serial = H.clone()
+        # (2) the timed region proper: the same steps, n_inst per sampling call, sampling and compute overlapped
+        if self.overlap is None:
+            self.prepare_overlap()
+        for p in range(warmup // K):
+            self.group(p)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for it in range(warmup, warmup + steps):
-            H = self.step(it, overlap=True)
+        for p in range(warmup // K, (warmup + steps) // K):
+            H = self.group(p)
         enqueue_ms = (time.perf_counter() - t0) / steps * 1e3     # host time to enqueue a step (no waiting in it)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
-        assert torch.equal(H, h_serial), "overlapped steps must give the serial result bit for bit"
-        assert all(int(lb.status.item()) == 0 for lbs in self.lb_sets for lb in lbs), "a status bit was set in the overlapped run"
-        log(f"host enqueue {enqueue_ms:.3f} ms/step; one stream {serial_ms:.3f} ms/step; sampling and compute overlapped "
-            f"{ms_per_step:.3f} ms/step")
+        if serial:
+            assert torch.equal(H, h_serial), "the timed schedule must give the one-stream result bit for bit"
+        assert all(int(lb.status.item()) == 0 for set_ in self.lb_inst for lk in set_ for lb in lk), \
+            "a status bit was set in the timed run"
+        log(f"host enqueue {enqueue_ms:.3f} ms/step; " + (f"one stream, one batch per call {serial_ms:.3f} ms/step; " if serial else "") +
+            f"{K} batches per sampling call, sampling and compute overlapped {ms_per_step:.3f} ms/step")
+        # (3) per-kernel durations in the timed configuration: the same groups, call by call on one stream
         sizes = []
+        st0 = self.overlap["sets"][0]
         csgs.csgs_profile_enable(True)
-        for it in range(warmup, warmup + steps):
-            self.step(it, sizes)
-        torch.cuda.synchronize()
+        for p in range(warmup // K, (warmup + steps) // K):
+            st0["idx"].copy_(self.it_host[p * K:(p + 1) * K])
+            st0["sample_fn"]()
+            st0["compute_fn"]()
+            torch.cuda.synchronize()
+            for lk in self.lb_inst[0]:
+                self.sizes_of(lk, n0, sizes)
         csgs.csgs_profile_enable(False)
+        self.graph_it[0] = None
         prof = csgs.csgs_profile_collect()
         assert all(s["status"] == 0 for s in sizes), "a status bit was set"
         alg, flops = {}, 0.0
@@ -321,6 +357,8 @@ class Workload:
             flops += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
         kernels = {}
         for k, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            if k == "fill_zero":
+                continue
             kernels[k] = dict(avg_us=ms / cnt * 1e3, launches_per_step=cnt / steps, ms_per_step=ms / steps,
                               alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
             if alg.get(k):
@@ -365,7 +403,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
-    ap.add_argument("--samplers", type=int, default=2, help="sampling streams (batches sampled side by side)")
+    ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
+    ap.add_argument("--instances", type=int, default=1, help="mini-batches per sampling call (one is fastest at the named sizes: the sampling kernels are bound by throughput, not by launches)")
+    ap.add_argument("--no-serial", action="store_true", help="skip the one-stream, one-batch-per-call measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     ap.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
@@ -394,7 +434,13 @@ def main():
     dg = pipeline.DeviceGraph(g, dev)
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
-    mk = lambda c, nb: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers)
+    mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K)
+    # a step is one mini-batch; the timed schedule samples K of them per call, so both counts become multiples of K
+    K = max(1, args.instances)
+    up = lambda n: (n + K - 1) // K * K
+    if up(args.steps) != args.steps or up(args.warmup) != args.warmup:
+        log(f"steps {args.steps} -> {up(args.steps)}, warmup {args.warmup} -> {up(args.warmup)} (multiples of {K} batches per call)")
+    args.steps, args.warmup = up(args.steps), up(args.warmup)
 
     # copy-kernel yardstick (also the known-size kernel for calibrating byte counters)
     cbytes = 512 * 2 ** 20
@@ -427,9 +473,9 @@ def main():
     del table
     log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s")
 
-    wl = mk(cfg, args.steps + args.warmup)
+    wl = mk(cfg, args.steps + args.warmup, K)
     log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
-    res = wl.measure(args.steps, args.warmup)
+    res = wl.measure(args.steps, args.warmup, serial=not args.no_serial)
     ms_per_step = res["ms_per_step"]
     log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
     dominant = next(iter(res["kernels"]))
@@ -470,7 +516,7 @@ def main():
         torch.cuda.empty_cache()
         sc = 16
         cfg_s = dataclasses.replace(cfg, batch=cfg.batch * sc, samples=cfg.samples * sc)
-        rs = mk(cfg_s, 8).measure(6, 2)
+        rs = mk(cfg_s, 8, 1).measure(6, 2)
         tr = load_traffic(f"{cfg.name}_x{sc}")
         shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_emit")
         scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
@@ -494,8 +540,8 @@ def main():
                     precision=("bf16 features, " if bf16 else "f32 features, ") + "u64 fixed-point weights and CDF, f64 accumulation, f32 outputs",
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
-        schedule=f"sampling of consecutive batches on {args.samplers} streams (own workspace each), layer compute of all "
-                 "batches in order on one more stream; each part " +
+        schedule=f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
+                 "workspace each), layer compute of all batches in order on one more stream; each part " +
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
