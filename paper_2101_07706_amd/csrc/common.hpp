@@ -47,7 +47,7 @@ struct RowOffsets {
 struct Workspace {
     // clean: all-zero whenever no call is in flight
     uint64_t *wtable;    // [n_nodes]  per-node fixed-point weight accumulator
-    uint8_t *tileflag;   // [ceil(n_nodes/64)] 1 = some node of this 64-id word was touched
+    uint8_t *tileflag;   // [8 * ceil(n_nodes/64)] byte g = 1: some node of ids 8g .. 8g+7 was touched (read 8 at a time: one 64-id word)
     uint32_t *hit;       // [n_nodes]  draws per candidate position
     uint64_t *cbitmap;   // [ceil(n_nodes/64)] bit set = candidate position was drawn
     // persistent: zeroed once, then never cleared; an entry counts only if it carries the tag of
@@ -104,7 +104,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.chunk_cap = (edges_max + EDGE_TILE - 1) / EDGE_TILE;
     if (w.chunk_cap < 1) w.chunk_cap = 1;
     w.wtable = (uint64_t *)take((size_t)n_nodes * 8);
-    w.tileflag = (uint8_t *)take(words);
+    w.tileflag = (uint8_t *)take(words * 8);
     w.hit = (uint32_t *)take((size_t)n_nodes * 4);
     w.cbitmap = (uint64_t *)take(words * 8);
     w.clean_bytes = off;

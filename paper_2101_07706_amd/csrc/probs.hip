@@ -9,8 +9,9 @@
 //   scan_edges     flat over the edges of S (chunks of 1024, rows of a chunk staged in LDS, so
 //                  hub rows and short rows cost the same per edge): square each edge value
 //                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
-//                  with fire-and-forget integer atomics (order-independent); flag the 64-node
-//                  word of the target with a plain byte store
+//                  with fire-and-forget integer atomics (order-independent); flag the group of 8
+//                  node ids of the target (one 64-byte piece of the accumulator table) with a
+//                  plain byte store, so that the candidate kernels fetch only touched pieces
 //   cand_partials  per tile of 1024 node ids: candidate count, local count, local and remote
 //                  weight sums of the flagged words (unskewed, so they do not depend on s); the
 //                  last tile of each group of 64 adds up its group (it waits for the other
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
             if (q < 1) q = 1;                             // every candidate stays drawable
             (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)q, __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
-            tileflag[c >> 6] = 1;  // same value from every writer
+            tileflag[c >> 3] = 1;  // same value from every writer
         }
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
@@ -152,9 +153,12 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
-        if (word_idx >= n_words || tileflag[word_idx] == 0) continue;
+        if (word_idx >= n_words) continue;
+        const uint64_t f8 = reinterpret_cast<const uint64_t *>(tileflag)[word_idx];   // the word's eight group flags
+        if (f8 == 0) continue;
         const int64_t id = word_idx * 64 + lane;
-        const uint64_t w = id < n_nodes ? wtable[id] : 0ull;
+        // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
+        const uint64_t w = (((f8 >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
         if (w) {
             const bool local = id >= lo && id < hi;
             cn += (1ull << 32) | (local ? 1ull : 0ull);
@@ -207,11 +211,11 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     const int64_t g = t / 64, n_groups = (n_tiles + 63) / 64;
     // Loads are issued in the order flags, prefix inputs, accumulators, and consumed only after
     // all are in flight, so the tile's own data travels while the prefix is being summed.
-    bool flagged[CAND_WORDS / 4];
+    uint64_t flagged[CAND_WORDS / 4];   // the eight group flags of each 64-id word (one byte per 8 ids)
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
-        flagged[k] = word_idx < n_words && tileflag[word_idx] != 0;
+        flagged[k] = word_idx < n_words ? reinterpret_cast<const uint64_t *>(tileflag)[word_idx] : 0ull;
     }
     // sums over everything (tot) and over what lies before this tile (pre): group sums before my
     // group, then tile sums before me inside my group
@@ -231,7 +235,7 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
-        w[k] = (flagged[k] && id < n_nodes) ? wtable[id] : 0ull;
+        w[k] = (((flagged[k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
     }
     uint64_t tot[3], pre[3];
 #pragma unroll
@@ -278,7 +282,7 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int slot = wave * (CAND_WORDS / 4) + k;
         if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
-        if (flagged[k] && lane == 0) tileflag[t * CAND_WORDS + slot] = 0;  // back to the clean state
+        if (flagged[k] && lane == 0) reinterpret_cast<uint64_t *>(tileflag)[t * CAND_WORDS + slot] = 0ull;  // back to the clean state
     }
     __syncthreads();
     uint64_t base_cnt = pre[0] >> 32;
