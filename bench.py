@@ -196,9 +196,12 @@ class Workload:
             idx = torch.arange(K, dtype=torch.int64, device=dev)      # iteration number of every instance
             tmp = torch.zeros((K, n0), dtype=self.S_all.dtype, device=dev)
 
-            def fill(idx=idx, tmp=tmp, S0_all=S0_all):
-                torch.index_select(self.S_all, 0, idx, out=tmp)       # the batches of these iterations
-                S0_all.copy_(tmp)
+            def fill(idx=idx, tmp=tmp, S0_all=S0_all, lb0=lb0):
+                if K == 1:      # straight into the row array
+                    torch.index_select(self.S_all, 0, idx, out=lb0.S0[:n0].view(1, -1))
+                else:
+                    torch.index_select(self.S_all, 0, idx, out=tmp)   # the batches of these iterations
+                    S0_all.copy_(tmp)
 
             def sample(idx=idx, lbs=lbs, ws=ws, lb0=lb0, fill=fill):
                 fill()
