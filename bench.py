@@ -409,6 +409,8 @@ def main():
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
     ap.add_argument("--instances", type=int, default=1, help="mini-batches per sampling call (one is fastest at the named sizes: the sampling kernels are bound by throughput, not by launches)")
     ap.add_argument("--no-serial", action="store_true", help="skip the one-stream, one-batch-per-call measurement")
+    ap.add_argument("--sweep-instances", default="", help="comma-separated K: also time the schedule with K mini-batches per "
+                    "sampling call and report step time and the weight scan's rate under \"instances_sweep\"")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     ap.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
@@ -476,7 +478,8 @@ def main():
     del table
     log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s")
 
-    wl = mk(cfg, args.steps + args.warmup, K)
+    N_CPU = 20      # whole steps the oracle is timed on (about 11 s on one core at Large)
+    wl = mk(cfg, max(args.steps, 0 if args.no_cpu_baseline else N_CPU) + args.warmup, K)
     log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
     res = wl.measure(args.steps, args.warmup, serial=not args.no_serial)
     ms_per_step = res["ms_per_step"]
@@ -492,7 +495,7 @@ def main():
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import chain
-        n_cpu = 4
+        n_cpu = N_CPU
         t0 = time.perf_counter()
         cpu_nnz = 0
         for it in range(args.warmup, args.warmup + n_cpu):
@@ -512,6 +515,23 @@ def main():
     if not args.no_backward:
         backward = wl.measure_backward(args.steps)
         log(f"backward pass alone: {backward['ms_per_step']:.3f} ms/step, gradient GEMMs {backward['gemm_TFLOPs']:.1f} TFLOP/s")
+
+    sweep = None
+    if args.sweep_instances:
+        sweep = []
+        for Ks in [int(x) for x in args.sweep_instances.split(",") if x]:
+            n_st = (48 + Ks - 1) // Ks * Ks
+            n_wu = (8 + Ks - 1) // Ks * Ks
+            ws_ = mk(cfg, n_st + n_wu, Ks)
+            rk = ws_.measure(n_st, n_wu, serial=False)
+            se = rk["kernels"]["scan_edges"]
+            sweep.append(dict(instances=Ks, ms_per_step=rk["ms_per_step"], scan_edges_us_per_launch=se["avg_us"],
+                              scan_edges_alg_GBps=se.get("alg_GBps"),
+                              scan_edges_adds_Gps=rk["per_step"]["edges_scanned"] / se["launches_per_step"] / (se["avg_us"] * 1e-6) / 1e9,
+                              kernels_us_per_launch={k: round(v["avg_us"], 2) for k, v in rk["kernels"].items()}))
+            log(f"{Ks} instances per call: {rk['ms_per_step']:.3f} ms/step, scan_edges {se['avg_us']:.1f} us per launch")
+            del ws_
+            torch.cuda.empty_cache()
 
     scaled = None
     if not args.no_scaled and args.scale == 1:
@@ -548,7 +568,7 @@ def main():
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
-        roofline=roofline, cpu_baseline=cpu_baseline, backward=backward,
+        roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, instances_sweep=sweep,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
     print(json.dumps(out))
 

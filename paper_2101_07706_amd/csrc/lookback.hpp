@@ -156,9 +156,14 @@ __device__ inline void lookback_resolve(const TileState<NV> &ts, unsigned long l
             for (int v = 0; v < NV; ++v) st_relaxed(&ts.gagg[g * NV + v], run[v] + local[v]);
             st_flag(&ts.gflag[g], tag);
         }
-        // hop 3: the first tile of a group sums the totals of the earlier groups for everyone in it
+        // hop 3: the first tile of a group sums the totals of the earlier groups for everyone in it.
+        // Nothing lies before the first group: its tiles neither wait nor publish here, so scans of
+        // at most 64 tiles are done after one hop.
         unsigned long long pre[NV];
-        if (r == 0) {
+        if (g == 0) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) pre[v] = 0ull;
+        } else if (r == 0) {
 #pragma unroll
             for (int v = 0; v < NV; ++v) pre[v] = 0ull;
             for (long long g0 = 0; g0 < g; g0 += WAVE) {
