@@ -402,8 +402,8 @@ def load_traffic(key):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
