@@ -51,7 +51,7 @@ def algorithmic_bytes(s, N):
 
 
 class Workload:
-    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1, n_inst=1):
+    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1, n_inst=1, batch_compute=False):
         self.cfg, self.g, self.dg, self.Xd, self.dev = cfg, g, dg, Xd, dev
         self.torch, self.pipeline, self.csgs = torch, pipeline, csgs
         self.bf16 = cfg.feat_dtype == "bf16"
@@ -86,6 +86,12 @@ class Workload:
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
         self.elt = 2 if self.bf16 else 4
         self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
+        # all instances of a group through the same compute launches: per-instance Z, H and staged rows
+        self.batch_compute = batch_compute and n_inst > 1
+        if self.batch_compute:
+            self.ZsK = [torch.empty((n_inst, nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
+            self.HsK = [torch.empty((n_inst, nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
+            self.stagedK = torch.zeros((n_inst, B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
 
     def enqueue_sampling(self, S0, it, lbs, ws):
         """Top-down sampling calls on the current stream, for one mini-batch or, when `ws` and `lbs`
@@ -114,6 +120,23 @@ class Workload:
                 pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev)
             H = Hn
         return H
+
+    def enqueue_compute_group(self, lbs, n0):
+        """The same for all instances of a buffer set in the same launches (the _n forms of the calls)."""
+        M, B, pipeline = self.M, self.B, self.pipeline
+        nb = lambda t: t.stride(0) * t.element_size()
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.stagedK[0], out_stride=nb(self.stagedK))
+        for l in range(M - 1, -1, -1):
+            nS = n0 if l == 0 else B
+            nS_dev = None if l == 0 else lbs[l - 1].n_next
+            Z, H = self.ZsK[l], self.HsK[l]
+            if l == M - 1:
+                pipeline.compute_step(lbs[l], nS, self.X_local, self.stagedK[0], True, False, self.Wd[0], Z[0, :nS], H[0, :nS],
+                                      nS_dev=nS_dev, strides=(0, nb(self.stagedK), nb(Z), nb(H)))
+            else:
+                pipeline.compute_step(lbs[l], nS, self.HsK[l + 1][0, :B], None, False, True, self.Wd[M - 1 - l], Z[0, :nS], H[0, :nS],
+                                      nS_dev=nS_dev, strides=(nb(self.HsK[l + 1]), 0, nb(Z), nb(H)))
+        return self.HsK[0][self.n_inst - 1, :n0]
 
     def prepare_backward(self):
         """Buffers for the gradients of every layer (dW, dZ, dH_prev, scratch), sized for the capacities."""
@@ -207,7 +230,9 @@ class Workload:
                 fill()
                 self.enqueue_sampling(lb0.S0[:n0], idx, lbs, ws)      # the library reads idx[0]; instance k uses idx[0] + k
 
-            def compute(k=k):
+            def compute(k=k, lbs=lbs):
+                if self.batch_compute:
+                    return self.enqueue_compute_group(lbs, n0)
                 H = None
                 for lk in self.lb_inst[k]:
                     H = self.enqueue_compute(lk, n0)
@@ -236,7 +261,7 @@ class Workload:
                     g_samp = g_comp = None
             torch.cuda.synchronize()
             sets.append(dict(idx=idx, sample=g_samp, compute=g_comp, sample_fn=sample, compute_fn=compute,
-                             H=self.Hs[0][:n0], s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(),
+                             H=self.HsK[0][K - 1, :n0] if self.batch_compute else self.Hs[0][:n0], s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(),
                              used=False))
         self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=dev)   # iteration numbers, resident
         self.graph_it = [None] * self.n_sets     # first iteration number each set's counters hold for its next replay
@@ -408,6 +433,8 @@ def main():
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
     ap.add_argument("--instances", type=int, default=1, help="mini-batches per sampling call (one is fastest at the named sizes: the sampling kernels are bound by throughput, not by launches)")
+    ap.add_argument("--batch-compute", action="store_true", help="with --instances K: also the layer compute of the K "
+                    "mini-batches in the same launches (forward passes are independent; a training loop's are not)")
     ap.add_argument("--no-serial", action="store_true", help="skip the one-stream, one-batch-per-call measurement")
     ap.add_argument("--sweep-instances", default="", help="comma-separated K: also time the schedule with K mini-batches per "
                     "sampling call and report step time and the weight scan's rate under \"instances_sweep\"")
@@ -439,7 +466,8 @@ def main():
     dg = pipeline.DeviceGraph(g, dev)
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
-    mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K)
+    mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
+                                   batch_compute=args.batch_compute)
     # a step is one mini-batch; the timed schedule samples K of them per call, so both counts become multiples of K
     K = max(1, args.instances)
     up = lambda n: (n + K - 1) // K * K
@@ -564,7 +592,8 @@ def main():
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
         schedule=f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
-                 "workspace each), layer compute of all batches in order on one more stream; each part " +
+                 "workspace each), layer compute of all batches " + ("of a group in the same launches" if args.batch_compute and K > 1
+                                                                     else "in order") + " on one more stream; each part " +
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),

@@ -332,6 +332,39 @@ int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
 
 /*
+ * Several instances per launch for the layer compute (the counterpart of n_inst in csgs_workspace:
+ * the forward passes of the mini-batches sampled by one group of sampling calls are independent of
+ * each other).  The _n forms below take the arguments of csgs_aggregate, csgs_layer_gemm and
+ * csgs_gather_rows plus a host struct of strides; instance k of n_inst uses each device pointer at
+ * its address + k * the stride of its group, in bytes (multiples of 16; 0 = the same array for all):
+ *   adj       what the sampling calls wrote: adj_rowptr, adj_col, adj_val, nS_dev / M_dev, n_next,
+ *             src_row (csgs_aggregate); M_dev (csgs_layer_gemm); ids, n_dev (csgs_gather_rows)
+ *   x         the input matrix: X_local (csgs_aggregate), Z (csgs_layer_gemm), X (csgs_gather_rows)
+ *   x_remote  X_remote (csgs_aggregate)
+ *   out       the output matrix: Z (csgs_aggregate), H (csgs_layer_gemm), out (csgs_gather_rows)
+ * Everything else (W, all sizes and leading dimensions) is shared.  inst NULL = one instance.
+ * Results are those of n_inst separate calls.  Host errors as the plain forms, CSGS_EINVAL also
+ * for n_inst outside [1, 64] and negative or misaligned strides.
+ */
+typedef struct csgs_inst_strides {
+    int32_t n_inst;
+    int32_t reserved;
+    int64_t adj, x, x_remote, out;
+} csgs_inst_strides;
+
+int csgs_aggregate_n(const csgs_inst_strides *inst /*host*/, const int32_t *adj_rowptr, const int32_t *adj_col,
+                     const float *adj_val, int32_t nS, const int32_t *nS_dev, const int32_t *n_next,
+                     const void *X_local, int64_t ld_local, int64_t rows_local, const void *X_remote,
+                     int64_t ld_remote, int64_t rows_remote, const int32_t *src_row, int32_t F, int dtype,
+                     int relu_on_input, float *Z, int64_t ldz, void *stream);
+int csgs_layer_gemm_n(const csgs_inst_strides *inst /*host*/, const float *Z, int64_t ldz, int32_t M,
+                      const int32_t *M_dev, int32_t K, const float *W, int64_t ldw, int32_t Nout, float *H,
+                      int64_t ldh, void *stream);
+int csgs_gather_rows_n(const csgs_inst_strides *inst /*host*/, const void *X, int64_t ld, int64_t rows, int32_t F,
+                       int dtype, const int32_t *ids, int64_t cap, const int64_t *n_dev, void *out, int64_t ldo,
+                       void *stream);
+
+/*
  * Gradients of one sampled layer.  Every GPU obtains a stochastic gradient of the loss (Section 3,
  * Eq. 2) through its sampled layers (Eq. 1): for H = Z W, Z = P~ sigma(H_prev) and G = dL/dH,
  *     dW      = Z^T G                                  csgs_layer_gemm_grad_w

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_workspace_wait_limit", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
-           "csgs_layer_gemm", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
+           "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
            "csgs_calib_copy", "csgs_calib_atomics"]
@@ -47,6 +47,12 @@ class Workspace(C.Structure):
                 ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("rows_buf", C.c_uint64),
                 ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("has_next", C.c_int32),
                 ("n_inst", C.c_int32), ("reserved", C.c_int32), ("inst_stride", C.c_int64)]
+
+
+class InstStrides(C.Structure):
+    """csgs_inst_strides: byte strides between the instances of the _n compute calls."""
+    _fields_ = [("n_inst", C.c_int32), ("reserved", C.c_int32), ("adj", C.c_int64), ("x", C.c_int64),
+                ("x_remote", C.c_int64), ("out", C.c_int64)]
 
 
 class RemoteOut(C.Structure):
@@ -93,6 +99,10 @@ def lib():
                                      C.c_int, vp, i64, vp]
         L.csgs_layer_gemm.argtypes = [vp, i64, i32, vp, i32, vp, i64, i32, vp, i64, vp]
         L.csgs_gather_rows.argtypes = [vp, i64, i64, i32, C.c_int, vp, i64, vp, vp, i64, vp]
+        strides = [C.POINTER(InstStrides)]
+        L.csgs_aggregate_n.argtypes = strides + L.csgs_aggregate.argtypes
+        L.csgs_layer_gemm_n.argtypes = strides + L.csgs_layer_gemm.argtypes
+        L.csgs_gather_rows_n.argtypes = strides + L.csgs_gather_rows.argtypes
         L.csgs_layer_gemm_grad_w_scratch_bytes.restype = sz
         L.csgs_layer_gemm_grad_w_scratch_bytes.argtypes = [i32, i32, i32]
         L.csgs_layer_gemm_grad_w.argtypes = [vp, i64, vp, i64, i32, vp, i32, i32, vp, i64, vp, sz, vp]
@@ -109,7 +119,10 @@ def lib():
         L.csgs_profile_kernel_name.argtypes = [C.c_int]
         L.csgs_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in EXPORTS:
-            getattr(L, name)
+            fn = getattr(L, name)
+            # without declared argument types ctypes would pass Python integers as 32-bit values, whose
+            # upper half is undefined once they travel on the stack into a 64-bit parameter
+            assert fn.argtypes is not None or name in ("csgs_profile_kernel_count",), f"{name}: argument types not declared"
         _lib = L
     return _lib
 
@@ -286,9 +299,16 @@ def csgs_remote_count(S_next, n_next, local_lo, local_hi, part_bounds, remote_to
                                  _stream(stream))
 
 
+def _inst(inst):
+    """Leading arguments of a compute call: the _n form with its strides, or the plain form."""
+    return ("_n", (C.byref(inst),)) if inst is not None else ("", ())
+
+
 def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_row, relu_on_input, Z,
-                   stream=None, nS_dev=None):
-    """X_* are 2-D float32 tensors or int16/uint16/bfloat16 tensors holding bfloat16 rows."""
+                   stream=None, nS_dev=None, inst=None):
+    """X_* are 2-D float32 tensors or int16/uint16/bfloat16 tensors holding bfloat16 rows.
+    inst (InstStrides): several instances per launch; the tensors are instance 0's."""
+    suffix, lead = _inst(inst)
     dtype = F32 if X_local.dtype == torch.float32 else BF16
     F = X_local.shape[1]
     rows_r = 0 if X_remote is None else X_remote.shape[0]
@@ -296,17 +316,18 @@ def csgs_aggregate(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_
     if X_remote is not None and rows_r == 0:
         X_remote = None
     Xl_ptr = _ptr(X_local) if X_local.shape[0] > 0 else None
-    _call("csgs_aggregate", _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
+    _call("csgs_aggregate" + suffix, *lead, _ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1,
                               _ptr(nS_dev), _ptr(n_next), Xl_ptr, X_local.stride(0), X_local.shape[0], _ptr(X_remote),
                               ld_r, rows_r, _ptr(src_row), F, dtype, 1 if relu_on_input else 0, _ptr(Z),
                               Z.stride(0), _stream(stream))
 
 
-def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None):
+def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None, inst=None):
     M, K = Z.shape
     K2, N = W.shape
     assert K == K2 and H.shape == (M, N)
-    _call("csgs_layer_gemm", _ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
+    suffix, lead = _inst(inst)
+    _call("csgs_layer_gemm" + suffix, *lead, _ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
                                _stream(stream))
 
 
@@ -346,11 +367,12 @@ def csgs_aggregate_grad(adj_rowptr, adj_col, adj_val, n_next, dZ, H_prev, dH_pre
           dH_prev.stride(0), _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream))
 
 
-def csgs_gather_rows(X, ids, n_dev, out, stream=None):
+def csgs_gather_rows(X, ids, n_dev, out, stream=None, inst=None):
     """out[k] = X[ids[k]] for k < *n_dev (device int64; None = all of ids)."""
     assert X.dtype == out.dtype and X.shape[1] == out.shape[1] and out.shape[0] >= ids.numel()
     dtype = F32 if X.dtype == torch.float32 else BF16
-    _call("csgs_gather_rows", _ptr(X), X.stride(0), X.shape[0], X.shape[1], dtype, _ptr(ids), ids.numel(),
+    suffix, lead = _inst(inst)
+    _call("csgs_gather_rows" + suffix, *lead, _ptr(X), X.stride(0), X.shape[0], X.shape[1], dtype, _ptr(ids), ids.numel(),
                                 _ptr(n_dev), _ptr(out), out.stride(0), _stream(stream))
 
 

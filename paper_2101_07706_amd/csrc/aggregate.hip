@@ -270,8 +270,12 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
                                                          const int32_t *__restrict__ src_row, int32_t F,
                                                          float *__restrict__ Z, int64_t ldz, int32_t n_long_blocks,
-                                                         int32_t per, const float *__restrict__ mask, int64_t ldm)
+                                                         int32_t per, const float *__restrict__ mask, int64_t ldm,
+                                                         CompStride cs)
 {
+    adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
+    nS_dev = inst_ptr(nS_dev, cs.adj); n_cols_p = inst_ptr(n_cols_p, cs.adj); src_row = inst_ptr(src_row, cs.adj);
+    Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
     if ((int32_t)blockIdx.x < n_long_blocks)
@@ -285,7 +289,7 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
 template <typename T, int V, int G>
 static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                      const float *mask, int64_t ldm, int kid, hipStream_t st)
+                      const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
@@ -297,13 +301,13 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     if (lblocks < ((int64_t)nS + 1023) / 1024) lblocks = ((int64_t)nS + 1023) / 1024;
     const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
     // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
-    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)((F + G * V - 1) / (G * V)));
+    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)((F + G * V - 1) / (G * V)), (unsigned)ci.n);
     if (relu)
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm, ci.cs);
     else
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm, ci.cs);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -311,17 +315,17 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 template <typename T, int V>
 static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                      const float *mask, int64_t ldm, int kid, hipStream_t st)
+                      const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
-    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
-    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
-    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
+    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
+    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
 }
 
 template <typename T>
 static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                     int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
-                    const float *mask, int64_t ldm, int kid, hipStream_t st)
+                    const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
     // widest vector for which every row start and F are aligned
     auto ok = [&](int v) {
@@ -330,9 +334,9 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
                (!Xr || (ldr % v == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % v == 0 &&
                ((uintptr_t)Z % ((uintptr_t)v * sizeof(float))) == 0;
     };
-    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
-    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
-    return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st);
+    if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
+    if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
+    return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
 }
 
 // ------------------------------------------------------------------ gradient of the aggregation
@@ -459,8 +463,9 @@ template <typename U>
 __global__ __launch_bounds__(256) void gather_rows_k(const U *__restrict__ X, int64_t ld_u, int64_t rows, int32_t row_u,
                                                      const int32_t *__restrict__ ids, int64_t cap,
                                                      const int64_t *__restrict__ n_dev, U *__restrict__ out,
-                                                     int64_t ldo_u)
+                                                     int64_t ldo_u, CompStride cs)
 {
+    X = inst_ptr(X, cs.x); ids = inst_ptr(ids, cs.adj); n_dev = inst_ptr(n_dev, cs.adj); out = inst_ptr(out, cs.out);
     int64_t n = cap;
     if (n_dev) {
         const int64_t d = *n_dev;
@@ -478,22 +483,25 @@ __global__ __launch_bounds__(256) void gather_rows_k(const U *__restrict__ X, in
 
 template <typename U>
 static void launch_gather(const void *X, int64_t ld_b, int64_t rows, int64_t row_b, const int32_t *ids, int64_t cap,
-                          const int64_t *n_dev, void *out, int64_t ldo_b, hipStream_t st)
+                          const int64_t *n_dev, void *out, int64_t ldo_b, hipStream_t st, const CompInst &ci)
 {
     const int64_t waves = cap < 8192 ? cap : 8192;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
-    CSGS_LAUNCH(K_GATHER_ROWS, gather_rows_k<U>, dim3(blocks), dim3(256), st, (const U *)X, ld_b / (int64_t)sizeof(U), rows,
-                (int32_t)(row_b / (int64_t)sizeof(U)), ids, cap, n_dev, (U *)out, ldo_b / (int64_t)sizeof(U));
+    CSGS_LAUNCH(K_GATHER_ROWS, gather_rows_k<U>, dim3(blocks, 1, (unsigned)ci.n), dim3(256), st, (const U *)X,
+                ld_b / (int64_t)sizeof(U), rows, (int32_t)(row_b / (int64_t)sizeof(U)), ids, cap, n_dev, (U *)out,
+                ldo_b / (int64_t)sizeof(U), ci.cs);
 }
 
 }  // namespace csgs
 
 using namespace csgs;
 
-extern "C" int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t F, int dtype, const int32_t *ids,
-                                int64_t cap, const int64_t *n_dev, void *out, int64_t ldo, void *stream)
+extern "C" int csgs_gather_rows_n(const csgs_inst_strides *inst, const void *X, int64_t ld, int64_t rows, int32_t F, int dtype,
+                                  const int32_t *ids, int64_t cap, const int64_t *n_dev, void *out, int64_t ldo, void *stream)
 {
     if (!X || !ids || !out || rows <= 0 || F <= 0 || ld < F || ldo < F || cap <= 0) return CSGS_EINVAL;
+    CompInst ci;
+    if (open_instances(inst, &ci) != CSGS_OK) return CSGS_EINVAL;
     if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
     const int64_t elt = dtype == CSGS_F32 ? 4 : 2;
     const int64_t row_b = (int64_t)F * elt, ld_b = ld * elt, ldo_b = ldo * elt;
@@ -502,12 +510,18 @@ extern "C" int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t
         return row_b % a == 0 && ld_b % a == 0 && ldo_b % a == 0 && ((uintptr_t)X % (uintptr_t)a) == 0 &&
                ((uintptr_t)out % (uintptr_t)a) == 0;
     };
-    if (aligned(16)) launch_gather<uint4>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
-    else if (aligned(8)) launch_gather<uint2>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
-    else if (aligned(4)) launch_gather<uint32_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
-    else launch_gather<uint16_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st);
+    if (aligned(16)) launch_gather<uint4>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st, ci);
+    else if (aligned(8)) launch_gather<uint2>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st, ci);
+    else if (aligned(4)) launch_gather<uint32_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st, ci);
+    else launch_gather<uint16_t>(X, ld_b, rows, row_b, ids, cap, n_dev, out, ldo_b, st, ci);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
+}
+
+extern "C" int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t F, int dtype, const int32_t *ids,
+                                int64_t cap, const int64_t *n_dev, void *out, int64_t ldo, void *stream)
+{
+    return csgs_gather_rows_n(nullptr, X, ld, rows, F, dtype, ids, cap, n_dev, out, ldo, stream);
 }
 
 extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int32_t nS,
@@ -515,6 +529,18 @@ extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col,
                               const void *X_remote, int64_t ld_remote, int64_t rows_remote, const int32_t *src_row,
                               int32_t F, int dtype, int relu_on_input, float *Z, int64_t ldz, void *stream)
 {
+    return csgs_aggregate_n(nullptr, adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
+                            ld_remote, rows_remote, src_row, F, dtype, relu_on_input, Z, ldz, stream);
+}
+
+extern "C" int csgs_aggregate_n(const csgs_inst_strides *inst, const int32_t *adj_rowptr, const int32_t *adj_col,
+                                const float *adj_val, int32_t nS, const int32_t *nS_dev, const int32_t *n_next,
+                                const void *X_local, int64_t ld_local, int64_t rows_local, const void *X_remote,
+                                int64_t ld_remote, int64_t rows_remote, const int32_t *src_row, int32_t F, int dtype,
+                                int relu_on_input, float *Z, int64_t ldz, void *stream)
+{
+    CompInst ci;
+    if (open_instances(inst, &ci) != CSGS_OK) return CSGS_EINVAL;
     if (!adj_rowptr || !adj_col || !adj_val || nS <= 0 || F <= 0 || rows_local < 0 || (rows_local > 0 && !X_local) ||
         (X_local && ld_local < F) || !Z || ldz < F || (X_remote && (ld_remote < F || rows_remote < 0)))
         return CSGS_EINVAL;
@@ -524,9 +550,9 @@ extern "C" int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col,
     hipStream_t st = (hipStream_t)stream;
     if (dtype == CSGS_F32)
         return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
-                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st);
+                               ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st, ci);
     return pick_vec<uint16_t>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,
-                              ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st);
+                              ld_remote, rows_remote, src_row, F, relu_on_input, Z, ldz, nullptr, 0, prof::K_AGGREGATE, st, ci);
 }
 
 extern "C" size_t csgs_aggregate_grad_scratch_bytes(int32_t n_cols, int64_t adj_cap)

@@ -86,6 +86,30 @@ __device__ inline T *inst_ptr(T *p, int64_t stride)
 }
 constexpr int MAX_INSTANCES = 64;
 
+// The same for the layer compute calls, whose arrays come in four groups with a stride each.
+struct CompStride {
+    int64_t adj;   // what the sampling calls wrote: adjacency arrays, row counts, source-row map, id lists
+    int64_t x;     // the input matrix (0: one table shared by all instances)
+    int64_t xr;    // staged remote rows
+    int64_t out;   // the output matrix
+};
+struct CompInst {
+    int32_t n = 1;
+    CompStride cs = {0, 0, 0, 0};
+};
+// Checks a caller's csgs_inst_strides (null: one instance).
+__host__ inline int open_instances(const csgs_inst_strides *d, CompInst *out)
+{
+    *out = CompInst{};
+    if (!d) return CSGS_OK;
+    if (d->n_inst < 1 || d->n_inst > MAX_INSTANCES || d->adj < 0 || d->x < 0 || d->x_remote < 0 || d->out < 0 ||
+        ((d->adj | d->x | d->x_remote | d->out) & 15))
+        return CSGS_EINVAL;
+    out->n = d->n_inst;
+    out->cs = CompStride{d->adj, d->x, d->x_remote, d->out};
+    return CSGS_OK;
+}
+
 // Layout of a workspace sized for (n_nodes, nS_max, B_max, edges_max).  Every call carves with the
 // same four numbers (they travel in the caller's csgs_workspace descriptor), so the persistent
 // parts never move.

@@ -111,8 +111,9 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, double *__restrict__ partial, int M_bound, int N,
                                                   int K_bound, const int32_t *__restrict__ rows_dev, int n_tiles_n,
-                                                  int n_tiles, int k_split)
+                                                  int n_tiles, int k_split, CompStride cs)
 {
+    A = inst_ptr(A, cs.x); C = inst_ptr(C, cs.out); rows_dev = inst_ptr(rows_dev, cs.adj);   // B (the weights) is shared
     constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront (times 2 row tiles)
     constexpr bool A_KMAJOR = MODE != MODE_DW, B_KMAJOR = MODE == MODE_DZ;
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_STRIDE];
@@ -239,22 +240,22 @@ static int widest(const float *p, int64_t ld)
 
 template <int BN>
 static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *H,
-                       int64_t ldh, hipStream_t st)
+                       int64_t ldh, hipStream_t st, const CompInst &ci)
 {
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
-    const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8));
+    const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), 1, (unsigned)ci.n);
     const int va = widest(Z, ldz);
     const bool full = !M_dev && M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;
     double *none = nullptr;
     if (full)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
     else if (va == 4)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
     else if (va == 2)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
     else
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
 }
 
 template <int BN>
@@ -267,9 +268,9 @@ static void launch_dz(const float *G, int64_t ldg, int M, const int32_t *M_dev, 
     const int v = widest(G, ldg) == 4 && widest(W, ldw) == 4 ? 4 : 1;
     double *none = nullptr;
     if (v == 4)
-        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 4, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 4, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0, CompStride{0, 0, 0, 0});
     else
-        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 1, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0);
+        CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 1, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0, CompStride{0, 0, 0, 0});
 }
 
 // Parts of the reduction dimension for dW = Z^T G with `rows` rows: enough blocks to fill the device,
@@ -294,16 +295,24 @@ using namespace csgs;
 extern "C" int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev, int32_t K, const float *W, int64_t ldw,
                                int32_t Nout, float *H, int64_t ldh, void *stream)
 {
+    return csgs_layer_gemm_n(nullptr, Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, stream);
+}
+
+extern "C" int csgs_layer_gemm_n(const csgs_inst_strides *inst, const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev,
+                                 int32_t K, const float *W, int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream)
+{
     if (!Z || !W || !H || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldw < Nout || ldh < Nout) return CSGS_EINVAL;
+    CompInst ci;
+    if (open_instances(inst, &ci) != CSGS_OK) return CSGS_EINVAL;
     const int64_t tm = ((int64_t)M + BM - 1) / BM;
     if (tm * (((int64_t)Nout + 31) / 32) > 0x3FFFFFFF) return CSGS_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     // narrow column tiles when wide ones would leave fewer than two blocks per compute unit
     const int64_t wide_tiles = tm * (((int64_t)Nout + 63) / 64);
-    if (wide_tiles >= 512 && Nout > 32)
-        launch_fwd<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
+    if (wide_tiles * ci.n >= 512 && Nout > 32)
+        launch_fwd<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
     else
-        launch_fwd<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st);
+        launch_fwd<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
@@ -351,7 +360,7 @@ extern "C" int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), (unsigned)parts);
     float *none = nullptr;
     CSGS_LAUNCH(K_GEMM_DW, (gemm_f32_k<32, MODE_DW, 1, false>), grid, dim3(256), st, Z, ldz, G, ldg, none, (int64_t)0,
-                (double *)scratch, K, Nout, M, M_dev, tn, n_tiles, ks);
+                (double *)scratch, K, Nout, M, M_dev, tn, n_tiles, ks, CompStride{0, 0, 0, 0});
     CSGS_LAUNCH_CHECK();
     const int64_t count = (int64_t)K * Nout;
     CSGS_LAUNCH(K_GEMM_DW_REDUCE, gemm_reduce_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), st,

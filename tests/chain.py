@@ -143,9 +143,11 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
     return steps, ws
 
 
-def gpu_chain_instances(g, X, Ws, S0s, skew, B, seed, it, bf16, auto_D=None, chained=True):
+def gpu_chain_instances(g, X, Ws, S0s, skew, B, seed, it, bf16, auto_D=None, chained=True, batched_compute=False):
     """len(S0s) mini-batches sampled by the same library calls (instance k: rows S0s[k], iteration
-    it + k), then the layer compute of every instance.  Returns one list of steps per instance."""
+    it + k), then the layer compute of every instance -- instance by instance, or, with
+    batched_compute, all instances in the same launches (the _n forms).  Returns one list of steps
+    per instance."""
     import torch
     from paper_2101_07706_amd import pipeline
     dev = torch.device("cuda:0")
@@ -170,6 +172,8 @@ def gpu_chain_instances(g, X, Ws, S0s, skew, B, seed, it, bf16, auto_D=None, cha
             S, nS_dev = lbs[l - 1].S_next, lbs[l - 1].n_next
         pipeline.sample_step(dg, ws, S, skew, B, seed, it, l, lbs[l], auto_D=auto_D, nS_dev=nS_dev)
     X_local = Xd[g.local_lo:g.local_hi]
+    if batched_compute:
+        return _instances_batched_compute(g, lbs, ws, Xd, X_local, Wd, n0, B, K, dev)
     staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
     out = []
     for k in range(K):
@@ -197,6 +201,39 @@ def gpu_chain_instances(g, X, Ws, S0s, skew, B, seed, it, bf16, auto_D=None, cha
     per = ws.bytes_per_inst // 8
     for k in range(K):
         assert int(torch.count_nonzero(ws.buf[k * per:k * per + clean]).item()) == 0, f"workspace {k} not restored"
+    return out
+
+
+def _instances_batched_compute(g, lbs, ws, Xd, X_local, Wd, n0, B, K, dev):
+    import torch
+    from paper_2101_07706_amd import pipeline
+    M = len(Wd)
+    rows = [n0 if l == 0 else B for l in range(M)]
+    Zs = [torch.full((K, rows[l], Wd[M - 1 - l].shape[0]), float("nan"), dtype=torch.float32, device=dev) for l in range(M)]
+    Hs = [torch.full((K, rows[l], Wd[M - 1 - l].shape[1]), float("nan"), dtype=torch.float32, device=dev) for l in range(M)]
+    staged = torch.zeros((K, B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
+    nbytes = lambda t: t.stride(0) * t.element_size()
+    pipeline.stage_remote_rows(lbs[M - 1], Xd, staged[0], out_stride=nbytes(staged))
+    for l in range(M - 1, -1, -1):
+        nS_dev = None if l == 0 else lbs[l - 1].n_next
+        if l == M - 1:
+            pipeline.compute_step(lbs[l], rows[l], X_local, staged[0], True, False, Wd[0], Zs[l][0], Hs[l][0], nS_dev=nS_dev,
+                                  strides=(0, nbytes(staged), nbytes(Zs[l]), nbytes(Hs[l])))
+        else:
+            pipeline.compute_step(lbs[l], rows[l], Hs[l + 1][0], None, False, True, Wd[M - 1 - l], Zs[l][0], Hs[l][0], nS_dev=nS_dev,
+                                  strides=(nbytes(Hs[l + 1]), 0, nbytes(Zs[l]), nbytes(Hs[l])))
+    torch.cuda.synchronize()
+    out = []
+    for k in range(K):
+        lk = [lb.inst(k) for lb in lbs]
+        steps = []
+        for l in range(M):
+            n_rows = n0 if l == 0 else int(lk[l - 1].n_next.item())
+            assert bool(torch.isnan(Zs[l][k, n_rows:]).all()) and bool(torch.isnan(Hs[l][k, n_rows:]).all()), \
+                f"instance {k} layer {l}: wrote past the row count"
+            steps.append(SimpleNamespace(S=None, lb=lk[l], n_next=int(lk[l].n_next.item()), status=int(lk[l].status.item()),
+                                         Z=Zs[l][k, :n_rows], H=Hs[l][k, :n_rows]))
+        out.append(steps)
     return out
 
 

@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
     assert C.sizeof(csgs.Graph) == 56
     assert C.sizeof(csgs.Workspace) == 80 and csgs.Workspace.n_inst.offset == 64 and csgs.Workspace.inst_stride.offset == 72
+    assert C.sizeof(csgs.InstStrides) == 40 and csgs.InstStrides.adj.offset == 8
     assert C.sizeof(csgs.RemoteOut) == 56 and csgs.RemoteOut.remote_total.offset == 24
     assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48
     assert csgs.Workspace.has_draw.offset == 48 and csgs.Workspace.draw_B.offset == 56
@@ -157,3 +158,14 @@ def test_instance_descriptors_are_checked():
     assert L.csgs_workspace_init(C.byref(desc(4 * per, 4, 0)), z) == csgs.EINVAL                   # no stride
     assert L.csgs_workspace_init(C.byref(desc(4 * per, 4, 1000)), z) == csgs.EINVAL                # not a multiple of 256
     assert L.csgs_workspace_init(C.byref(desc(100 * per, 65, 1 << 20)), z) == csgs.EINVAL          # too many
+
+
+def test_compute_instance_strides_are_checked():
+    L = csgs.lib()
+    z, p = C.c_void_p(0), C.c_void_p(4096)
+    bad = [csgs.InstStrides(0, 0, 256, 0, 0, 256), csgs.InstStrides(65, 0, 256, 0, 0, 256), csgs.InstStrides(2, 0, 8, 0, 0, 256),
+           csgs.InstStrides(2, 0, 256, -16, 0, 256)]
+    for inst in bad:
+        assert L.csgs_aggregate_n(C.byref(inst), p, p, p, 4, z, z, p, 8, 4, z, 0, 0, z, 8, 0, 0, p, 8, z) == csgs.EINVAL
+        assert L.csgs_layer_gemm_n(C.byref(inst), p, 8, 4, z, 8, p, 8, 8, p, 8, z) == csgs.EINVAL
+        assert L.csgs_gather_rows_n(C.byref(inst), p, 8, 4, 8, 0, p, 4, z, p, 8, z) == csgs.EINVAL

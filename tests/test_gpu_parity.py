@@ -458,11 +458,13 @@ def test_chain_on_prepared_rows(dev, name):
 
 
 # ---------------------------------------------------------------- several mini-batches per call
-@pytest.mark.parametrize("name,K,chained", [("tiny", 3, True), ("tiny", 2, False), ("medium", 4, True), ("mid", 2, True),
-                                             ("large", 3, True)])
-def test_instances_per_call(dev, name, K, chained):
+@pytest.mark.parametrize("name,K,chained,batched", [("tiny", 3, True, False), ("tiny", 2, False, True), ("medium", 4, True, True),
+                                                     ("mid", 2, True, False), ("mid", 3, True, True), ("large", 3, True, False),
+                                                     ("large", 2, True, True)])
+def test_instances_per_call(dev, name, K, chained, batched):
     """K mini-batches of consecutive iterations through the same sampling calls (n_inst = K in the
-    workspace descriptor): every instance equals the oracle's chain for its batch and iteration."""
+    workspace descriptor) and, with `batched`, through the same compute launches (the _n forms):
+    every instance equals the oracle's chain for its batch and iteration."""
     it = 4
     if name == "large":
         cfg, g, X, Ws, _ = cached_inputs("large")
@@ -470,10 +472,10 @@ def test_instances_per_call(dev, name, K, chained):
         cfg, g, X, Ws, _ = chain.config_inputs(name, it)
     S0s = [synth.make_batch(g, cfg.batch, cfg.seed, it + k) for k in range(K)]
     bf16 = cfg.feat_dtype == "bf16"
-    say(f"[{name}] {K} instances per call, chained={chained}")
+    say(f"[{name}] {K} instances per call, chained={chained}, compute batched={batched}")
     auto_D = 8.0 if (name == "tiny" and not chained) else None
     got = chain.gpu_chain_instances(g, X, Ws, S0s, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
-                                    chained=chained)
+                                    chained=chained, batched_compute=batched)
     for k in range(K):
         osteps = chain.oracle_chain(g, X, Ws, S0s[k], cfg.skew, cfg.samples, 1234 + cfg.seed, it + k, bf16, auto_D=auto_D)
         worst = chain.compare_chain(osteps, got[k])
