@@ -432,9 +432,10 @@ def main():
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
-    ap.add_argument("--instances", type=int, default=1, help="mini-batches per sampling call (one is fastest at the named sizes: the sampling kernels are bound by throughput, not by launches)")
-    ap.add_argument("--batch-compute", action="store_true", help="with --instances K: also the layer compute of the K "
-                    "mini-batches in the same launches (forward passes are independent; a training loop's are not)")
+    ap.add_argument("--instances", type=int, default=4, help="mini-batches per library call in the timed schedule")
+    ap.add_argument("--no-batch-compute", action="store_true", help="with --instances K: sample K mini-batches per call but "
+                    "compute their layers batch by batch (what a training loop must do: its forward passes depend on "
+                    "each other through the weights; the forward passes timed here do not)")
     ap.add_argument("--no-serial", action="store_true", help="skip the one-stream, one-batch-per-call measurement")
     ap.add_argument("--sweep-instances", default="", help="comma-separated K: also time the schedule with K mini-batches per "
                     "sampling call and report step time and the weight scan's rate under \"instances_sweep\"")
@@ -467,7 +468,7 @@ def main():
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
     mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
-                                   batch_compute=args.batch_compute)
+                                   batch_compute=not args.no_batch_compute)
     # a step is one mini-batch; the timed schedule samples K of them per call, so both counts become multiples of K
     K = max(1, args.instances)
     up = lambda n: (n + K - 1) // K * K
@@ -592,7 +593,7 @@ def main():
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
         schedule=f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
-                 "workspace each), layer compute of all batches " + ("of a group in the same launches" if args.batch_compute and K > 1
+                 "workspace each), layer compute of all batches " + ("of a group in the same launches" if not args.no_batch_compute and K > 1
                                                                      else "in order") + " on one more stream; each part " +
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],

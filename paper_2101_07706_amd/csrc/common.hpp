@@ -179,6 +179,12 @@ __host__ inline InstStride inst_stride(const Workspace &w) { return InstStride{(
 // compaction of drawn positions (33 KB of LDS) runs 1 block per unit and the adjacency filter
 // (13 KB) 2, so four call sequences on four workspaces can be in flight on one device within the
 // 2048 threads and 160 KB of a compute unit.  That is the documented limit.
+// With several instances per call (blockIdx.z) the grid is that many times as large, but blocks
+// wait only for blocks of their own instance and the hardware hands out a grid's blocks in
+// ascending x, then y, then z: an instance is dispatched completely before the next one starts, a
+// completely dispatched instance finishes by itself and frees its places, and at most one instance
+// per kernel is ever partly dispatched -- so what must fit at once is still one instance per
+// waiting kernel in flight.
 __host__ inline int resident_grid(int per_cu)
 {
     static std::atomic<int> cached[64];   // compute units per device, 0 = not asked yet (zero-initialised)
