@@ -55,7 +55,8 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
 }
 
 constexpr int LONG_ROW = 32;    // rows with more kept edges than this are taken by whole blocks
-constexpr int UNR = 8;          // gathered rows in flight per lane
+constexpr int UNR = 4;          // gathered rows in flight per lane: with 8 the kernel needs more than 64 registers, which
+                                // halves the blocks a compute unit holds, and the rows in flight on the device set its rate
 constexpr int AGG_BLOCK = 1024; // threads per block: 16 wavefronts
 
 // Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.
