@@ -119,7 +119,10 @@ typedef struct csgs_workspace {
     int32_t has_next;    /* the latest csgs_sample_layer prepared the offsets of its S_next */
     /* several instances per call, set by the caller (see below); 0 or 1 = one instance */
     int32_t n_inst;
-    int32_t reserved;
+    int32_t scan_mode;   /* how csgs_build_probs adds up the weights of local candidates: 0 = the library
+                            chooses (through owner blocks when a launch scans a million edges or more,
+                            else with device-scope atomics like the remote ones), 1 = always atomics,
+                            2 = owner blocks whenever the local range allows.  Same results. */
     int64_t inst_stride; /* bytes between consecutive instances' arrays; a multiple of 256 */
 } csgs_workspace;
 

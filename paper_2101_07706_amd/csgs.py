@@ -46,7 +46,7 @@ class Workspace(C.Structure):
     _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("n_nodes", C.c_int64),
                 ("nS_max", C.c_int32), ("B_max", C.c_int32), ("edges_max", C.c_int64), ("rows_buf", C.c_uint64),
                 ("has_draw", C.c_uint64), ("draw_B", C.c_int32), ("has_next", C.c_int32),
-                ("n_inst", C.c_int32), ("reserved", C.c_int32), ("inst_stride", C.c_int64)]
+                ("n_inst", C.c_int32), ("scan_mode", C.c_int32), ("inst_stride", C.c_int64)]
 
 
 class InstStrides(C.Structure):
@@ -217,11 +217,11 @@ def csgs_workspace_clean_bytes(n_nodes) -> int:
     return int(lib().csgs_workspace_clean_bytes(n_nodes))
 
 
-def make_workspace(buf, n_nodes, nS_max, B_max, edges_max, n_inst=1, inst_stride=0) -> Workspace:
+def make_workspace(buf, n_nodes, nS_max, B_max, edges_max, n_inst=1, inst_stride=0, scan_mode=0) -> Workspace:
     """Descriptor for `buf` (a torch tensor of at least n_inst * csgs_workspace_bytes(...) bytes).
     n_inst > 1: calls through it process that many instances, whose arrays lie inst_stride bytes apart."""
     ws = Workspace(buf.data_ptr(), buf.numel() * buf.element_size(), n_nodes, nS_max, B_max, edges_max, 0, 0, 0, 0,
-                   n_inst, 0, inst_stride)
+                   n_inst, scan_mode, inst_stride)
     ws._keep = buf
     return ws
 

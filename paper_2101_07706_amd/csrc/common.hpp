@@ -25,6 +25,11 @@ constexpr int EDGE_TILE = 1024;   // edges per chunk in the flat edge passes
 constexpr int EDGE_GRID = 2048;   // blocks of the weight scan (grid-stride over chunks, no waits between blocks)
 constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in the hit compaction
 constexpr int ROW_TILE = 1024;    // rows of S per block in the degree prefix
+// Weight scan through owners: edges that end in the local id range are handed, chunk by chunk, to
+// blocks that each own SUB_IDS consecutive local ids and add them up in LDS.
+constexpr int SUB_IDS = 2048;                     // ids per owner block (16 KB of 64-bit sums)
+constexpr int SUB_MAX = 128;                      // most owner blocks: local ranges up to SUB_IDS * SUB_MAX ids
+constexpr int64_t STAGE_EDGES_MAX = 8ll << 20;    // most edges of a call that are handed over this way
 constexpr int META_WORDS = 4;
 constexpr int META_ROWS = 0;          // rows the latest row_prefix covered (the count behind eoff / rowstart)
 constexpr int META_EDGES = 1;         // eoff[rows]: edges of those rows (0 when above the workspace's capacity)
@@ -64,6 +69,12 @@ struct Workspace {
     uint64_t *adj_ts;    // scan state of the edge chunks (1 sum per chunk of 1024 edges)
     uint64_t *rp_ts;     // scan state of the row tiles (1 sum per tile of ROW_TILE rows)
     double *pdbl;        // [B]      inclusion probabilities in double
+    // hand-over of local-range edges from the chunk blocks of the weight scan to the owner blocks
+    uint64_t *stage_w;   // [stage_chunks * EDGE_TILE] fixed-point weight of a handed-over edge
+    uint32_t *stage_c;   // [stage_chunks * EDGE_TILE] its target id; a chunk's edges lie grouped by owner
+    uint32_t *stage_off; // [stage_chunks * SUB_MAX]   per chunk and owner: begin | end << 16 of its group
+    uint64_t *stage_done;// [stage_chunks] persistent: tag of the call whose hand-over of this chunk is complete
+    int64_t stage_chunks;
     int64_t chunk_cap;   // chunks of EDGE_TILE edges the adjacency scan can describe
     int64_t n_tiles, hit_tiles, rp_tiles;
     size_t clean_bytes;  // size of the clean part
@@ -148,6 +159,11 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
         w.rows[b].chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
     }
     w.pdbl = (double *)take((size_t)B_max * 8);
+    w.stage_chunks = w.chunk_cap < STAGE_EDGES_MAX / EDGE_TILE ? w.chunk_cap : STAGE_EDGES_MAX / EDGE_TILE;
+    w.stage_w = (uint64_t *)take((size_t)w.stage_chunks * EDGE_TILE * 8);
+    w.stage_c = (uint32_t *)take((size_t)w.stage_chunks * EDGE_TILE * 4);
+    w.stage_off = (uint32_t *)take((size_t)w.stage_chunks * SUB_MAX * 4);
+    w.stage_done = (uint64_t *)take((size_t)w.stage_chunks * 8);
     w.bytes = off;
     w.n_inst = 1;
     w.buf_stride = 0;

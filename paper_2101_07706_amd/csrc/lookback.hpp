@@ -50,7 +50,7 @@ constexpr int EPOCH_CALLS = 0;   // library calls completed on this workspace
 constexpr int EPOCH_DRAW = 1;    // value of (calls + 1) during the latest draw: tags the rank table
 constexpr int EPOCH_WAIT = 2;    // 0, or 1 + the number of polls a wait may take (set through csgs_workspace_wait_limit)
 // one tag space per scan-state region, so the kernels of one call never mistake each other's flags
-enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4, SLOT_ROWS_NEXT = 5 };
+enum TagSlot { SLOT_ROWS = 1, SLOT_CAND = 2, SLOT_HITS = 3, SLOT_ADJ = 4, SLOT_ROWS_NEXT = 5, SLOT_STAGE = 6 };
 
 __device__ inline int wait_limit(const uint64_t *epoch)
 {
@@ -68,6 +68,8 @@ __device__ inline void st_relaxed(unsigned long long *p, unsigned long long v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline uint32_t ld_relaxed32(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ inline void st_relaxed32(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 // Blocks until every earlier load and store of this wavefront has been acknowledged.
 __device__ inline void wait_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

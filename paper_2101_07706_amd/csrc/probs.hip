@@ -51,31 +51,152 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
                     meta, edge_cap, status);
 }
 
+// Arguments of the hand-over inside the weight scan (see scan_edges).
+struct Stage {
+    uint64_t *w;
+    uint32_t *c, *off;
+    unsigned long long *done;
+    int64_t chunks;     // chunks the hand-over arrays can hold
+    int32_t lo, hi;     // local id range
+    int32_t owners;     // owner blocks at the end of the grid (0: every edge goes through device-scope atomics)
+    int32_t mode;       // 0: hand over when the launch has enough chunks to be bound by the atomic rate; 1: never; 2: always
+};
+// chunks (over all instances of the launch) from which the hand-over pays: below, the launch is
+// bound by latency and the owners' last round only adds to it
+constexpr int64_t STAGE_MIN_CHUNKS = 1024;
+
+// The weight scan.  Two kinds of blocks in one grid:
+//  * chunk blocks (the first gridDim.x - owners, grid-stride over chunks of EDGE_TILE edges): stage the
+//    rows of the chunk, fetch column and value of every edge, square and round.  An edge whose
+//    target lies outside the local id range is added to the per-node accumulator with a
+//    device-scope atomic.  The others -- most edges: the partition holds most neighbors -- are
+//    counting-sorted by owner inside the block and written to the chunk's piece of the hand-over
+//    arrays, then the chunk's flag is raised.  Scattered device-scope atomics run at about 23 G/s on
+//    this part whatever their scope or target range; LDS atomics are two orders faster.
+//  * owner blocks (the last `owners` of the grid): block r owns local ids [lo + r SUB_IDS, + SUB_IDS),
+//    sums in LDS what the chunks hand it (64 chunks at a time per wavefront, one per lane, as their
+//    flags come up), and stores the non-zero sums and their touch flags with plain stores: nobody
+//    else writes those entries.
+// Owners wait only for chunk blocks, which have lower block ids and wait for nobody.  Integer sums:
+// the result does not depend on which way an edge went or in what order.  The hand-over is used
+// when the call's edges fit its arrays and are many enough (see STAGE_MIN_CHUNKS); all blocks take
+// that decision from the same words.
 __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ colidx, const float *__restrict__ val,
                                                   int64_t n_nodes, int64_t nnz, int32_t shift_base,
                                                   const int64_t *__restrict__ meta, int64_t edge_cap,
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status, InstStride is)
+                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status,
+                                                  const uint64_t *__restrict__ epoch, Stage stg, InstStride is)
 {
     __shared__ RowSlice slice;
+    __shared__ unsigned long long acc[SUB_IDS];
+    __shared__ uint32_t hist[SUB_MAX + 1];
     meta = inst_ptr(meta, is.ws); eoff = inst_ptr(eoff, is.ws); rowstart = inst_ptr(rowstart, is.ws);
     wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); chunk_note = inst_ptr(chunk_note, is.ws);
+    epoch = inst_ptr(epoch, is.ws);
+    stg.w = inst_ptr(stg.w, is.ws); stg.c = inst_ptr(stg.c, is.ws); stg.off = inst_ptr(stg.off, is.ws);
+    stg.done = inst_ptr(stg.done, is.ws);
     status = inst_ptr(status, is.buf);
     const int32_t nS = (int32_t)meta[META_ROWS];
     const double scale = ldexp(1.0, shift_for_rows(shift_base, nS));
     const int64_t E = meta[META_EDGES];
+    const int64_t n_chunks = (E + EDGE_TILE - 1) / EDGE_TILE;
+    const bool staged = stg.owners > 0 && n_chunks <= stg.chunks && stg.mode != 1 &&
+                        (stg.mode == 2 || n_chunks * (int64_t)gridDim.z >= STAGE_MIN_CHUNKS);
+    const unsigned long long tag = call_tag(call_number(epoch), SLOT_STAGE);
+    const int32_t chunk_blocks = (int32_t)gridDim.x - stg.owners;
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+
+    if ((int32_t)blockIdx.x >= chunk_blocks) {   // ---------------- owner
+        if (!staged) return;
+        const int32_t r = (int32_t)blockIdx.x - chunk_blocks;
+        const int32_t base_id = stg.lo + r * SUB_IDS;
+        const int limit = wait_limit(epoch);
+        for (int i = threadIdx.x; i < SUB_IDS; i += blockDim.x) acc[i] = 0ull;
+        __syncthreads();
+        bool timed_out = false;
+        for (int64_t cb = (int64_t)wave * WAVE; cb < n_chunks; cb += (int64_t)(blockDim.x >> 6) * WAVE) {
+            // one chunk per lane: where my group lies in its piece
+            const int64_t c = cb + lane;
+            int32_t beg = 0, end = 0;
+            if (c < n_chunks) {
+                if (wait_tag(&stg.done[c], tag, limit)) {
+                    const uint32_t pr = ld_relaxed32(&stg.off[c * SUB_MAX + r]);
+                    beg = (int32_t)(pr & 0xFFFFu);
+                    end = (int32_t)(pr >> 16);
+                    if (end > EDGE_TILE || beg > end) beg = end = 0;   // (only after a failed wait elsewhere)
+                } else {
+                    timed_out = true;
+                }
+            }
+            // the 64 groups as one sequence, one entry per lane and step: entry j belongs to the first
+            // lane whose running count exceeds j
+            const int32_t n = end - beg;
+            const int32_t incl = wave_inclusive_scan<int32_t>(n);
+            const int32_t excl = incl - n;
+            const int32_t total = __builtin_amdgcn_readlane(incl, WAVE - 1);
+            for (int32_t j0 = 0; j0 < total; j0 += 4 * WAVE) {
+                unsigned long long wv[4];
+                uint32_t cv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t j = j0 + u * WAVE + lane;
+                    int lo_l = 0, hi_l = WAVE - 1;
+#pragma unroll
+                    for (int it = 0; it < 6; ++it) {
+                        const int mid = (lo_l + hi_l) >> 1;
+                        if (__shfl(incl, mid, WAVE) > j) hi_l = mid; else lo_l = mid + 1;
+                    }
+                    const int src = lo_l < WAVE ? lo_l : WAVE - 1;
+                    const int64_t pos = (cb + src) * EDGE_TILE + __shfl(beg, src, WAVE) + (j - __shfl(excl, src, WAVE));
+                    const bool on = j < total;
+                    wv[u] = on ? ld_relaxed((const unsigned long long *)&stg.w[pos]) : 0ull;
+                    cv[u] = on ? ld_relaxed32(&stg.c[pos]) : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t x = (int64_t)cv[u] - base_id;
+                    if (j0 + u * WAVE + lane < total && x >= 0 && x < SUB_IDS) atomicAdd(&acc[x], wv[u]);
+                }
+            }
+        }
+        if (timed_out) atomicOr(status, CSGS_ST_INTERNAL);
+        __syncthreads();
+        for (int i = threadIdx.x; i < SUB_IDS; i += blockDim.x) {
+            const unsigned long long v = acc[i];
+            const int64_t id = (int64_t)base_id + i;
+            if (v && id < stg.hi && id < n_nodes) {
+                wtable[id] = v;
+                tileflag[id >> 3] = 1;
+            }
+        }
+        return;
+    }
+
+    // ---------------- chunk blocks
     if (blockIdx.x == 0 && threadIdx.x == 0 && meta[META_EDGES_TRUE] > edge_cap) atomicOr(status, CSGS_ST_EDGE_OVERFLOW);
     bool bad = false;
-    for (int64_t c0 = (int64_t)blockIdx.x * EDGE_TILE; c0 < E; c0 += (int64_t)gridDim.x * EDGE_TILE) {
+    for (int64_t t = blockIdx.x; t < n_chunks; t += chunk_blocks) {
+        const int64_t c0 = t * EDGE_TILE;
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
-        stage_slice<false>(slice, eoff, rowstart, nS, c0, c1, chunk_note + c0 / EDGE_TILE);
+        stage_slice<false>(slice, eoff, rowstart, nS, c0, c1, chunk_note + t);   // (starts with a barrier)
+        if (staged) {
+            for (int i = threadIdx.x; i <= SUB_MAX; i += blockDim.x) hist[i] = 0u;
+            __syncthreads();
+        }
         const int32_t len = (int32_t)(c1 - c0);
+        unsigned long long hq[EDGE_TILE / 256];
+        int32_t hc[EDGE_TILE / 256], hb[EDGE_TILE / 256];
+        uint32_t hr[EDGE_TILE / 256];
 #pragma unroll
         for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            hb[k] = -1;
+            hq[k] = 0ull; hc[k] = 0; hr[k] = 0u;
             const int32_t x = (int32_t)threadIdx.x + k * 256;
-            if (x >= len) break;
+            if (x >= len) continue;
             int32_t r;
             const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
             if (e < 0 || e >= nnz) {   // only after a failed wait in the prefix kernel: stay inside the graph
@@ -91,9 +212,52 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
             const double sq = (double)v * (double)v;      // exact: 24 x 24 bit product
             long long q = __double2ll_rn(sq * scale);     // scale is a power of two: exact, then RNE
             if (q < 1) q = 1;                             // every candidate stays drawable
-            (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)q, __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-            tileflag[c >> 3] = 1;  // same value from every writer
+            if (staged && c >= stg.lo && c < stg.hi) {
+                hb[k] = (c - stg.lo) / SUB_IDS;           // < owners <= SUB_MAX
+                hq[k] = (unsigned long long)q;
+                hc[k] = c;
+                hr[k] = atomicAdd(&hist[hb[k]], 1u);      // place inside the owner's group (any order)
+            } else {
+                (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)q, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+                tileflag[c >> 3] = 1;  // same value from every writer
+            }
+        }
+        if (staged) {
+            __syncthreads();
+            if (wave == 0) {   // counts -> begin of every owner's group; two owners per lane
+                const uint32_t a = hist[2 * lane], b = (2 * lane + 1 <= SUB_MAX) ? hist[2 * lane + 1] : 0u;
+                const uint32_t incl = wave_inclusive_scan<uint32_t>(a + b);
+                const uint32_t ex = incl - (a + b);
+                hist[2 * lane] = ex;
+                hist[2 * lane + 1] = ex + a;
+                if (lane == WAVE - 1) hist[SUB_MAX] = incl;   // edges handed over by this chunk
+                // begin | end << 16 for the owners' lookups
+                st_relaxed32(&stg.off[t * SUB_MAX + 2 * lane], ex | ((ex + a) << 16));
+                st_relaxed32(&stg.off[t * SUB_MAX + 2 * lane + 1], (ex + a) | ((ex + a + b) << 16));
+            }
+            __syncthreads();
+            // grouped by owner in LDS first (the owner blocks' sum array is free here), then out in
+            // order: full 64-byte pieces instead of one scattered store per edge
+            static_assert(SUB_IDS * 8 >= EDGE_TILE * 12, "the sort buffer lives in the owners' sum array");
+            unsigned long long *s_w = acc;                                           // [EDGE_TILE]
+            uint32_t *s_c = reinterpret_cast<uint32_t *>(acc + EDGE_TILE);           // [EDGE_TILE]
+#pragma unroll
+            for (int k = 0; k < EDGE_TILE / 256; ++k) {
+                if (hb[k] < 0) continue;
+                const uint32_t slot = hist[hb[k]] + hr[k];    // < EDGE_TILE: the groups partition the chunk's local edges
+                s_w[slot] = hq[k];
+                s_c[slot] = (uint32_t)hc[k];
+            }
+            __syncthreads();
+            const uint32_t n_handed = hist[SUB_MAX];
+            for (uint32_t i = threadIdx.x; i < n_handed; i += blockDim.x) {
+                st_relaxed((unsigned long long *)&stg.w[t * EDGE_TILE + i], s_w[i]);
+                st_relaxed32(&stg.c[t * EDGE_TILE + i], s_c[i]);
+            }
+            wait_memory_ops();     // this wavefront's hand-over stores have been acknowledged
+            __syncthreads();
+            if (threadIdx.x == 0) st_flag(&stg.done[t], tag);
         }
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
@@ -437,6 +601,7 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
         return CSGS_EINVAL;
     // S == NULL: the rows are the node set of the latest csgs_sample_layer on this workspace, whose
     // offsets that call has prepared; nS must be its capacity (the B of that draw)
+    if (ws->scan_mode < 0 || ws->scan_mode > 2) return CSGS_EINVAL;
     const bool chained = S == nullptr;
     if (chained && (!ws->has_next || nS_dev || nS != ws->draw_B)) return CSGS_EINVAL;
     int32_t shift;
@@ -463,8 +628,15 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
     const RowOffsets &rows = w.rows[ws->rows_buf & 1];
     const unsigned nz = (unsigned)w.n_inst;
     const InstStride is = inst_stride(w);
-    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3(EDGE_GRID, 1, nz), dim3(256), st, g->colidx, g->val, g->n_nodes, g->nnz, shift_base,
-                rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable, w.tileflag, rows.chunk_note, status, is);
+    // owner blocks for the local id range, when it is one the hand-over can cover
+    const int64_t n_local = (int64_t)g->local_hi - (int64_t)g->local_lo;
+    const int32_t owners = (n_local > 0 && n_local <= (int64_t)SUB_IDS * SUB_MAX && g->local_lo >= 0 && g->local_hi <= g->n_nodes)
+                               ? (int32_t)((n_local + SUB_IDS - 1) / SUB_IDS) : 0;
+    const Stage stg{w.stage_w, w.stage_c, w.stage_off, (unsigned long long *)w.stage_done, w.stage_chunks, g->local_lo,
+                    g->local_hi, owners, ws->scan_mode};
+    CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3((unsigned)(EDGE_GRID + owners), 1, nz), dim3(256), st, g->colidx, g->val,
+                g->n_nodes, g->nnz, shift_base, rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable,
+                w.tileflag, rows.chunk_note, status, w.epoch, stg, is);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles, 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,

@@ -30,18 +30,22 @@ class DeviceGraph:
         self.c = csgs.make_graph(self.rowptr, self.colidx, self.val, g.local_lo, g.local_hi, g.rownorm2_max)
 
 
+DEFAULT_SCAN_MODE = 0    # csgs_workspace.scan_mode of new workspaces (tests force either way of the weight scan through it)
+
+
 class Workspace:
     """Scratch memory of the sampling calls.  n_inst > 1: one workspace per instance back to back;
     calls through it process n_inst instances whose arrays lie inst_stride bytes apart (the layout
     LayerBuffers(n_inst=...) gives them)."""
 
-    def __init__(self, n_nodes, nS_max, B_max, edges_max, device, n_inst=1, inst_stride=0):
+    def __init__(self, n_nodes, nS_max, B_max, edges_max, device, n_inst=1, inst_stride=0, scan_mode=None):
         nbytes = csgs.csgs_workspace_bytes(n_nodes, nS_max, B_max, edges_max)
         assert nbytes > 0 and nbytes % 256 == 0
         self.bytes_per_inst = nbytes
         self.buf = torch.empty(n_inst * nbytes // 8, dtype=torch.int64, device=device)
         assert self.buf.data_ptr() % 256 == 0
-        self.desc = csgs.make_workspace(self.buf, n_nodes, nS_max, B_max, edges_max, n_inst, inst_stride)
+        self.desc = csgs.make_workspace(self.buf, n_nodes, nS_max, B_max, edges_max, n_inst, inst_stride,
+                                        DEFAULT_SCAN_MODE if scan_mode is None else scan_mode)
         csgs.csgs_workspace_init(self.desc)
 
 

@@ -33,7 +33,7 @@ def test_every_declared_function_is_exported():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(csgs.ProbStats) == 64           # 7 x 8 bytes + 2 x 4
     assert C.sizeof(csgs.Graph) == 56
-    assert C.sizeof(csgs.Workspace) == 80 and csgs.Workspace.n_inst.offset == 64 and csgs.Workspace.inst_stride.offset == 72
+    assert C.sizeof(csgs.Workspace) == 80 and csgs.Workspace.n_inst.offset == 64 and csgs.Workspace.scan_mode.offset == 68 and csgs.Workspace.inst_stride.offset == 72
     assert C.sizeof(csgs.InstStrides) == 40 and csgs.InstStrides.adj.offset == 8
     assert C.sizeof(csgs.RemoteOut) == 56 and csgs.RemoteOut.remote_total.offset == 24
     assert csgs.Graph.local_lo.offset == 40 and csgs.Graph.rownorm2_max.offset == 48

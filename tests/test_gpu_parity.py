@@ -84,9 +84,11 @@ def run_full_size(name, skews, its=(0,)):
     return osteps
 
 
-def test_dense_config_skew_sweep(dev):
+def test_dense_config_skew_sweep(dev, monkeypatch):
     """Dense-neighborhood config at full size (114 M edges), every output element by element, over
-    the skew sweep; the bottom layer's remote count must fall as the skew grows."""
+    the skew sweep; the bottom layer's remote count must fall as the skew grows.  Once more with the
+    weight scan forced through owner blocks (left to itself the library scans these sizes with atomics)."""
+    from paper_2101_07706_amd import pipeline
     cfg = synth.CONFIGS["dense"]
     remote = []
     for s in cfg.skews:
@@ -94,6 +96,8 @@ def test_dense_config_skew_sweep(dev):
         remote.append(osteps[-1].rc.remote_total)
     say(f"[dense] remote nodes of the bottom layer over skews {cfg.skews}: {remote}")
     assert remote[0] > remote[-1]
+    monkeypatch.setattr(pipeline, "DEFAULT_SCAN_MODE", 2)
+    run_full_size("dense", [cfg.skews[len(cfg.skews) // 2]])
 
 
 def test_large_config(dev):
@@ -148,6 +152,55 @@ def test_small_graphs(dev, n, avg_deg, nS, B, skew, lo, hi):
     osteps = chain.oracle_chain(g, X, Ws, S0, skew, B, 42, 7)
     gsteps, _ = chain.gpu_chain(g, X, Ws, S0, skew, B, 42, 7)
     chain.compare_chain(osteps, gsteps)
+
+
+# ---------------------------------------------------------------- weight scan through owner blocks
+@pytest.fixture
+def owner_scan(monkeypatch):
+    """Workspaces made during the test ask for the owner-block form of the weight scan whatever the size
+    (left to itself the library takes it only for launches of a million edges or more)."""
+    from paper_2101_07706_amd import pipeline
+    monkeypatch.setattr(pipeline, "DEFAULT_SCAN_MODE", 2)
+
+
+@pytest.mark.parametrize("n,avg_deg,nS,B,skew,lo,hi", [
+    (1, 0, 1, 1, 1.0, 0, 1), (70, 3, 1, 5, 2.0, 10, 40), (70, 3, 70, 500, 16.0, 0, 70), (1000, 8, 65, 64, 4.0, 300, 600),
+    (5000, 40, 333, 257, 8.0, 0, 1250), (5000, 2, 1023, 1025, 2.5, 4000, 5000), (3000, 5, 17, 4100, 1.0, 1000, 1000),
+    (9000, 30, 2000, 700, 4.0, 100, 8900),     # several owner blocks, the last one partly outside the range
+])
+def test_small_graphs_owner_scan(dev, owner_scan, n, avg_deg, nS, B, skew, lo, hi):
+    test_small_graphs(dev, n, avg_deg, nS, B, skew, lo, hi)
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium", "mid"])
+def test_configs_owner_scan(dev, owner_scan, name):
+    run_config(name)
+    run_config_device_counts(name, it=2)
+
+
+def test_weight_scan_modes_agree_and_bad_mode_is_rejected(dev):
+    """The same call with scan_mode 1 (atomics) and 2 (owner blocks) writes identical candidates, weights and CDF."""
+    from paper_2101_07706_amd import csgs, pipeline
+    cfg, g, X, Ws, S0 = chain.config_inputs("medium", 3)
+    dg = pipeline.DeviceGraph(g, dev)
+    S0d = torch.from_numpy(np.ascontiguousarray(S0, np.int32)).to(dev)
+    outs = []
+    for mode in (1, 2):
+        ws = pipeline.Workspace(g.n_nodes, len(S0), cfg.samples, g.nnz, dev, scan_mode=mode)
+        lb = pipeline.LayerBuffers(len(S0), cfg.samples, g.n_nodes, 1, dg.n_parts, dev)
+        csgs.csgs_build_probs(dg.c, S0d, cfg.skew, lb.cand_id, lb.cand_w, lb.cdf, lb.q, lb.stats, ws.desc, lb.status)
+        torch.cuda.synchronize()
+        assert int(lb.status.item()) == 0
+        outs.append(lb)
+    n = int(outs[0].stats_host().n_cand)
+    assert n == int(outs[1].stats_host().n_cand) and n > 0
+    for f in ("cand_id", "cand_w", "cdf", "q", "stats"):
+        a, b = getattr(outs[0], f), getattr(outs[1], f)
+        assert torch.equal(a[:n] if f != "stats" else a, b[:n] if f != "stats" else b), f
+    bad = pipeline.Workspace(g.n_nodes, len(S0), cfg.samples, g.nnz, dev, scan_mode=3)
+    with pytest.raises(csgs.CsgsError):
+        csgs.csgs_build_probs(dg.c, S0d, cfg.skew, outs[0].cand_id, outs[0].cand_w, outs[0].cdf, None, outs[0].stats, bad.desc,
+                              outs[0].status)
 
 
 @pytest.mark.parametrize("policy", ["auto_D4", "auto_D32", "auto_D0", "local"])
