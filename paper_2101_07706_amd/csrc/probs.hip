@@ -4,14 +4,16 @@
 // Kernels:
 //   row_prefix     per tile of 1024 rows of S: degrees, their exclusive prefix (the flat edge
 //                  numbering; tile offsets by the single-pass scan across blocks), CSR start of
-//                  every row; the last tile leaves row count, edge count and weight shift for
+//                  every row; the last tile leaves the row count and the edge counts for
 //                  the kernels that follow
 //   scan_edges     flat over the edges of S (chunks of 1024, rows of a chunk staged in LDS, so
 //                  hub rows and short rows cost the same per edge): square each edge value
 //                  exactly, round to the fixed-point grid, add into a per-node 64-bit accumulator
-//                  with fire-and-forget integer atomics (order-independent); flag the group of 8
-//                  node ids of the target (one 64-byte piece of the accumulator table) with a
-//                  plain byte store, so that the candidate kernels fetch only touched pieces
+//                  -- remote targets with fire-and-forget integer atomics, targets in the local id
+//                  range (in launches large enough to be bound by the atomic rate) through owner
+//                  blocks that sum in LDS (see the kernel); flag the group of 8 node ids of the
+//                  target (one 64-byte piece of the accumulator table) with a plain byte store, so
+//                  that the candidate kernels fetch only touched pieces
 //   cand_partials  per tile of 1024 node ids: candidate count, local count, local and remote
 //                  weight sums of the flagged words (unskewed, so they do not depend on s); the
 //                  last tile of each group of 64 adds up its group (it waits for the other
