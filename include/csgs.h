@@ -34,7 +34,8 @@
  *     workspace must be ordered on one stream.  Calls on DIFFERENT workspaces may run side by
  *     side on different streams; at most four such call sequences per device at a time (two
  *     kernels hold all their blocks resident while they wait for each other, and four of them
- *     fit a compute unit together).
+ *     fit a compute unit together; a sequence that processes several instances per call, see
+ *     csgs_workspace, counts once: its instances are dispatched one after the other).
  *   - Replay.  Nothing a kernel needs to tell one call from the next is fixed at launch time
  *     (the call counter behind the inter-block flags lives in the workspace and is advanced by
  *     the kernels), and no entry point records a memset.  A sequence of calls captured into a
