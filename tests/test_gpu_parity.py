@@ -535,6 +535,40 @@ def test_instances_per_call(dev, name, K, chained, batched):
         say(f"[{name}] instance {k}: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
 
 
+def test_instances_are_isolated(dev):
+    """A fault in one instance's input (a row id outside the graph) is reported in that instance's
+    status word only; the other instances of the same calls are exact."""
+    from paper_2101_07706_amd import csgs, pipeline
+    cfg, g, X, Ws, _ = chain.config_inputs("tiny", 0)
+    B, K, it = cfg.samples, 3, 11
+    S0s = [synth.make_batch(g, cfg.batch, cfg.seed, it + k) for k in range(K)]
+    n0 = len(S0s[0])
+    bad = S0s[1].copy()
+    bad[5] = g.n_nodes + 17
+    dg = pipeline.DeviceGraph(g, dev)
+    nS_max = max(n0, B)
+    lb = pipeline.LayerBuffers(nS_max, B, g.n_nodes, g.nnz, dg.n_parts, dev, n_inst=K)
+    ws = pipeline.Workspace(g.n_nodes, nS_max, B, g.nnz, dev, n_inst=K, inst_stride=lb.stride)
+    for k, S in enumerate([S0s[0], bad, S0s[2]]):
+        lb.inst(k).S0[:n0].copy_(torch.from_numpy(np.ascontiguousarray(S, np.int32)))
+    pipeline.sample_step(dg, ws, lb.S0[:n0], cfg.skew, B, 1234 + cfg.seed, it, 0, lb)
+    torch.cuda.synchronize()
+    st = [int(lb.inst(k).status.item()) for k in range(K)]
+    assert st[0] == 0 and st[2] == 0 and st[1] & csgs.ST_BAD_NODE_ID, st
+    for k in (0, 2):
+        pr = oracle.build_probs(g, S0s[k], cfg.skew)
+        sm = oracle.sample_layer(g, S0s[k], pr, B, 1234 + cfg.seed, it + k, 0)
+        lk = lb.inst(k)
+        assert int(lk.n_next.item()) == sm.n_next
+        np.testing.assert_array_equal(lk.S_next[:sm.n_next].cpu().numpy(), sm.S_next)
+        np.testing.assert_array_equal(chain.u64(lk.cdf[:pr.n_cand]), pr.cdf)
+        np.testing.assert_array_equal(lk.adj_rowptr[:n0 + 1].cpu().numpy(), sm.adj_rowptr)
+    clean = chain.csgs_clean_words(g.n_nodes)
+    per = ws.bytes_per_inst // 8
+    for k in range(K):
+        assert int(torch.count_nonzero(ws.buf[k * per:k * per + clean]).item()) == 0, f"workspace {k} not restored"
+
+
 def test_prepared_rows_need_a_matching_sample_layer(dev):
     """csgs_build_probs(S = NULL) is refused on the host when no csgs_sample_layer has prepared rows,
     when nS is not that call's B, when a device count is given, and after the rows were consumed."""
@@ -991,16 +1025,18 @@ def test_calibration_kernels(dev):
     assert int(table.sum().item()) == 123457 and int(table.min().item()) > 0
 
 
-def test_failed_waits_end_normally_and_are_reported(dev):
+@pytest.mark.parametrize("scan_mode", [1, 2])
+def test_failed_waits_end_normally_and_are_reported(dev, scan_mode):
     """Timeout path of the waits between blocks, forced from the host: with a poll limit of zero a
     wait that is not satisfied at once gives up.  Every kernel must still end (no hang, all accesses
     in bounds), the status word must say so, and after csgs_workspace_init the same workspace must
-    give exact results again."""
+    give exact results again.  Both forms of the weight scan (the owner blocks of the second wait for
+    the chunk blocks)."""
     from paper_2101_07706_amd import csgs, pipeline
     cfg, g, X, Ws, S0 = chain.config_inputs("medium")
     dg = pipeline.DeviceGraph(g, dev)
     B = cfg.samples
-    ws = pipeline.Workspace(g.n_nodes, max(len(S0), B), B, g.nnz, dev)
+    ws = pipeline.Workspace(g.n_nodes, max(len(S0), B), B, g.nnz, dev, scan_mode=scan_mode)
     lbs = [pipeline.LayerBuffers(max(len(S0), B), B, g.n_nodes, 4_000_000, dg.n_parts, dev) for _ in range(2)]
     Sd = torch.from_numpy(S0).to(dev)
     Xd = torch.from_numpy(X).to(dev)
