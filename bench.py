@@ -399,6 +399,14 @@ class Workload:
         tot = lambda key: sum(s[key] for s in sizes) / steps
         per_step = dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
                         sampled_edges=tot("nnz"), remote_nodes=tot("remote"))
+        # the same per layer (layer 0 = the batch's own layer, the last one reads the feature table)
+        per_layer = []
+        for l in range(self.M):
+            ls = [x for x in sizes if x["layer"] == l]
+            avg = lambda key: round(sum(x[key] for x in ls) / len(ls), 1)
+            per_layer.append(dict(layer=l, rows=avg("nS"), edges_scanned=avg("E"), candidates=avg("nc"), sampled_nodes=avg("n_next"),
+                                  sampled_edges=avg("nnz"), remote_nodes=avg("remote"), F_in=ls[0]["F_in"], F_out=ls[0]["F_out"]))
+        per_step["per_layer"] = per_layer
         return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes,
                     aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
 
