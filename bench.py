@@ -374,6 +374,7 @@ class Workload:
                 self.sizes_of(lk, n0, sizes)
         csgs.csgs_profile_enable(False)
         self.graph_it[0] = None
+        samples = csgs.csgs_profile_samples()
         prof = csgs.csgs_profile_collect()
         assert all(s["status"] == 0 for s in sizes), "a status bit was set"
         alg, flops = {}, 0.0
@@ -391,6 +392,10 @@ class Workload:
                               alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
             if alg.get(k):
                 kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
+            sm = sorted(samples.get(k, []))
+            if sm:      # launch by launch: median and the 10th / 90th percentile, in us
+                pick = lambda f: sm[min(len(sm) - 1, int(f * len(sm)))] * 1e3
+                kernels[k].update(p10_us=pick(0.10), p50_us=pick(0.50), p90_us=pick(0.90))
         agg_ms = prof["aggregate"][0]
         agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
         gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12

@@ -415,6 +415,11 @@ int csgs_profile_enable(int on);
 int csgs_profile_kernel_count(void);
 const char *csgs_profile_kernel_name(int kernel);
 int csgs_profile_collect(double *ms_sum /*host*/, int64_t *launches /*host*/);
+/* The same launch by launch, for medians and percentiles: fills ms[i] / kernel[i] (host arrays of
+ * `cap` entries) with the duration and the kernel index of the first min(cap, n) launches since the
+ * last collect, stores n (all launches timed since then) in *n_out, and does NOT reset -- call it
+ * before csgs_profile_collect. */
+int csgs_profile_samples(float *ms /*host*/, int32_t *kernel /*host*/, int64_t cap, int64_t *n_out /*host*/);
 
 /* Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned)
  * with an ordinary streaming kernel: the yardstick for achievable HBM bandwidth, and the

@@ -24,7 +24,7 @@ EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
            "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
-           "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect",
+           "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect", "csgs_profile_samples",
            "csgs_calib_copy", "csgs_calib_atomics"]
 
 
@@ -118,6 +118,7 @@ def lib():
         L.csgs_profile_kernel_name.restype = C.c_char_p
         L.csgs_profile_kernel_name.argtypes = [C.c_int]
         L.csgs_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.csgs_profile_samples.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32), i64, C.POINTER(i64)]
         for name in EXPORTS:
             fn = getattr(L, name)
             # without declared argument types ctypes would pass Python integers as 32-bit values, whose
@@ -387,6 +388,19 @@ def csgs_profile_collect():
     cnt = (C.c_int64 * n)()
     _call("csgs_profile_collect", ms, cnt)
     return {lib().csgs_profile_kernel_name(k).decode(): (ms[k], cnt[k]) for k in range(n) if cnt[k]}
+
+
+def csgs_profile_samples(cap=1 << 16):
+    """{kernel name: [ms of every launch]} since the last collect (does not reset); call after synchronising."""
+    ms = (C.c_float * cap)()
+    kid = (C.c_int32 * cap)()
+    n = C.c_int64(0)
+    _call("csgs_profile_samples", ms, kid, cap, C.byref(n))
+    out = {}
+    for i in range(min(cap, n.value)):
+        if ms[i] >= 0:
+            out.setdefault(lib().csgs_profile_kernel_name(kid[i]).decode(), []).append(ms[i])
+    return out
 
 
 def csgs_calib_copy(dst, src, stream=None):

@@ -100,6 +100,19 @@ extern "C" int csgs_profile_kernel_count(void) { return K_COUNT; }
 
 extern "C" const char *csgs_profile_kernel_name(int kid) { return (kid >= 0 && kid < K_COUNT) ? kNames[kid] : ""; }
 
+extern "C" int csgs_profile_samples(float *ms, int32_t *kernel, int64_t cap, int64_t *n_out)
+{
+    if (!ms || !kernel || cap < 0 || !n_out) return CSGS_EINVAL;
+    *n_out = (int64_t)g_used;
+    for (size_t i = 0; i < g_used && (int64_t)i < cap; ++i) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, g_pool[i].a, g_pool[i].b) != hipSuccess) t = -1.f;   // (not yet complete: the caller did not synchronise)
+        ms[i] = t;
+        kernel[i] = g_pool[i].kid;
+    }
+    return CSGS_OK;
+}
+
 extern "C" int csgs_profile_collect(double *ms_sum, int64_t *launches)
 {
     if (!ms_sum || !launches) return CSGS_EINVAL;

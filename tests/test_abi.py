@@ -105,7 +105,9 @@ def test_profile_interface_without_launches():
     n = L.csgs_profile_kernel_count()
     names = [L.csgs_profile_kernel_name(k).decode() for k in range(n)]
     assert len(set(names)) == n and "aggregate" in names and "layer_gemm" in names
+    assert csgs.csgs_profile_samples() == {}
     assert csgs.csgs_profile_collect() == {}
+    assert L.csgs_profile_samples(None, None, 4, None) == csgs.EINVAL
 
 
 def test_gradient_calls_reject_bad_arguments_before_any_launch():
