@@ -482,12 +482,13 @@ def main():
     Xd = torch.from_numpy(Xh).to(dev)
     mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
                                    batch_compute=not args.no_batch_compute)
-    # a step is one mini-batch; the timed schedule samples K of them per call, so both counts become multiples of K
-    K = max(1, args.instances)
-    up = lambda n: (n + K - 1) // K * K
-    if up(args.steps) != args.steps or up(args.warmup) != args.warmup:
-        log(f"steps {args.steps} -> {up(args.steps)}, warmup {args.warmup} -> {up(args.warmup)} (multiples of {K} batches per call)")
-    args.steps, args.warmup = up(args.steps), up(args.warmup)
+    # a step is one mini-batch; the timed schedule handles K of them per call.  Exactly --steps steps are
+    # timed, so K is the largest count up to --instances that divides them; the (untimed) warm-up is
+    # rounded up to a multiple of K
+    K = max(k for k in range(1, max(1, args.instances) + 1) if args.steps % k == 0)
+    if K != args.instances:
+        log(f"{K} instead of {args.instances} mini-batches per call: the largest count that divides {args.steps} steps")
+    args.warmup = (args.warmup + K - 1) // K * K
 
     # copy-kernel yardstick (also the known-size kernel for calibrating byte counters)
     cbytes = 512 * 2 ** 20
