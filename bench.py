@@ -82,6 +82,7 @@ class Workload:
         self.lbs = self.lbs1
         self.overlap = None
         self.use_graphs = True
+        self.direct = False     # issue the timed schedule call by call (for per-dispatch timing, which a graph replay cannot carry)
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
         self.elt = 2 if self.bf16 else 4
@@ -285,17 +286,19 @@ class Workload:
         with torch.cuda.stream(st["s_samp"]):
             if st["used"]:
                 st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batches sampled into it were computed
-            if st["sample"] is None or self.graph_it[k] != it0:   # (re)seat the set's counters; consecutive replays advance them
+            direct = st["sample"] is None or self.direct     # call by call instead of a graph replay
+            if direct or self.graph_it[k] != it0:   # (re)seat the set's counters; consecutive replays advance them
                 st["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
-            if st["sample"] is not None:
+            if not direct:
                 st["sample"].replay()
                 self.graph_it[k] = it0 + K * self.n_sets
             else:
                 st["sample_fn"]()
+                self.graph_it[k] = None
             st["samp_done"].record(st["s_samp"])
         with torch.cuda.stream(s_comp):
             s_comp.wait_event(st["samp_done"])
-            if st["compute"] is not None:
+            if st["compute"] is not None and not self.direct:
                 st["compute"].replay()
             else:
                 st["compute_fn"]()
@@ -361,7 +364,18 @@ class Workload:
             "a status bit was set in the timed run"
         log(f"host enqueue {enqueue_ms:.3f} ms/step; " + (f"one stream, one batch per call {serial_ms:.3f} ms/step; " if serial else "") +
             f"{K} batches per sampling call, sampling and compute overlapped {ms_per_step:.3f} ms/step")
-        # (3) per-kernel durations in the timed configuration: the same groups, call by call on one stream
+        # (3) per-kernel durations over the timed schedule: the same groups on the same streams, launched call
+        # by call so that every dispatch carries its pair of events (the host stays well ahead of the device)
+        csgs.csgs_profile_enable(True)
+        self.direct = True
+        for p in range(warmup // K, (warmup + steps) // K):
+            self.group(p)
+        torch.cuda.synchronize()
+        self.direct = False
+        csgs.csgs_profile_enable(False)
+        samples = csgs.csgs_profile_samples()
+        prof = csgs.csgs_profile_collect()
+        # (4) the same groups once more, alone on one stream: sizes of every step, and what each kernel takes undisturbed
         sizes = []
         st0 = self.overlap["sets"][0]
         csgs.csgs_profile_enable(True)
@@ -374,8 +388,7 @@ class Workload:
                 self.sizes_of(lk, n0, sizes)
         csgs.csgs_profile_enable(False)
         self.graph_it[0] = None
-        samples = csgs.csgs_profile_samples()
-        prof = csgs.csgs_profile_collect()
+        prof_alone = csgs.csgs_profile_collect()
         assert all(s["status"] == 0 for s in sizes), "a status bit was set"
         alg, flops = {}, 0.0
         for s in sizes:
@@ -392,6 +405,8 @@ class Workload:
                               alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
             if alg.get(k):
                 kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
+            if k in prof_alone:
+                kernels[k]["alone_us"] = prof_alone[k][0] / prof_alone[k][1] * 1e3
             sm = sorted(samples.get(k, []))
             if sm:      # launch by launch: median and the 10th / 90th percentile, in us
                 pick = lambda f: sm[min(len(sm) - 1, int(f * len(sm)))] * 1e3
@@ -399,6 +414,8 @@ class Workload:
         agg_ms = prof["aggregate"][0]
         agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
         gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
+        alone = dict(aggregate_GBps=alg["aggregate"] / (prof_alone["aggregate"][0] * 1e-3) / 1e9,
+                     gemm_TFLOPs=flops / (prof_alone["layer_gemm"][0] * 1e-3) / 1e12)
         kernels["layer_gemm"]["TFLOPs"] = gemm_TF
         kernels["layer_gemm"]["flop_per_launch"] = flops / prof["layer_gemm"][1]
         tot = lambda key: sum(s[key] for s in sizes) / steps
@@ -413,7 +430,7 @@ class Workload:
                                   sampled_edges=avg("nnz"), remote_nodes=avg("remote"), F_in=ls[0]["F_in"], F_out=ls[0]["F_out"]))
         per_step["per_layer"] = per_layer
         return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes,
-                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
+                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF, alone=alone)
 
 
 def roofline_of(kernels, name, traffic):
@@ -445,7 +462,7 @@ def main():
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
-    ap.add_argument("--instances", type=int, default=4, help="mini-batches per library call in the timed schedule")
+    ap.add_argument("--instances", type=int, default=8, help="mini-batches per library call in the timed schedule (at most)")
     ap.add_argument("--no-batch-compute", action="store_true", help="with --instances K: sample K mini-batches per call but "
                     "compute their layers batch by batch (what a training loop must do: its forward passes depend on "
                     "each other through the weights; the forward passes timed here do not)")
@@ -610,7 +627,7 @@ def main():
                  "workspace each), layer compute of all batches " + ("of a group in the same launches" if not args.no_batch_compute and K > 1
                                                                      else "in order") + " on one more stream; each part " +
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
-        aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
+        aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"], kernels_alone=res["alone"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
         roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, instances_sweep=sweep,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)

@@ -57,7 +57,9 @@ __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
 constexpr int LONG_ROW = 32;    // rows with more kept edges than this are taken by whole blocks
 constexpr int UNR = 4;          // gathered rows in flight per lane: with 8 the kernel needs more than 64 registers, which
                                 // halves the blocks a compute unit holds, and the rows in flight on the device set its rate
-constexpr int AGG_BLOCK = 1024; // threads per block: 16 wavefronts
+constexpr int AGG_BLOCK = 256;  // threads per block.  Small blocks on purpose: beside kernels of other streams a 1024-thread
+                                // block waits until one compute unit has 16 wavefront places free at once and the kernel starves
+constexpr int AGG_WAVES = AGG_BLOCK / WAVE;
 
 // Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.
 template <typename T>
@@ -191,8 +193,8 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
     }
 }
 
-// Rows with more than LONG_ROW kept edges (hubs among the rows of S): the block's 16 wavefronts
-// work on one such row at a time, each wavefront takes a contiguous sixteenth of the row's edges,
+// Rows with more than LONG_ROW kept edges (hubs among the rows of S): the block's wavefronts
+// work on one such row at a time, each wavefront takes a contiguous share of the row's edges,
 // partial sums are added in wavefront order through LDS (fixed order: the result does not depend
 // on timing).  Block `bid` of `n_blocks` looks for long rows among its share of `per` rows.
 template <typename T, int V, bool RELU>
@@ -203,7 +205,7 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
                                            const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z,
                                            int64_t ldz, const float *__restrict__ mask, int64_t ldm)
 {
-    __shared__ double part[16][WAVE * V];
+    __shared__ double part[AGG_WAVES][WAVE * V];
     __shared__ int32_t long_rows[1024];
     __shared__ int32_t n_long;
     const int tid = (int)threadIdx.x;
@@ -221,7 +223,7 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
     for (int32_t li = 0; li < cnt; ++li) {
         const int32_t row = long_rows[li];
         const int32_t beg = adj_rowptr[row], end = adj_rowptr[row + 1];
-        const int32_t share = (end - beg + 15) / 16;
+        const int32_t share = (end - beg + AGG_WAVES - 1) / AGG_WAVES;
         const int32_t wbeg = beg + wave * share;
         const int32_t wend = (wbeg + share < end) ? wbeg + share : end;
         const int32_t len = wend > wbeg ? wend - wbeg : 0;
@@ -248,7 +250,7 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
                 double sum[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v) sum[v] = 0.0;
-                for (int w2 = 0; w2 < 16; ++w2) {
+                for (int w2 = 0; w2 < AGG_WAVES; ++w2) {
 #pragma unroll
                     for (int v = 0; v < V; ++v) sum[v] += part[w2][lane * V + v];
                 }
@@ -294,11 +296,11 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 {
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
-    // long-row blocks: about 16 rows each to look through (a block works its long rows off one after
+    // long-row blocks: about 4 rows each to look through (a block works its long rows off one after
     // the other, so where most rows are long -- dense neighborhoods -- there must be many blocks),
     // never more than 1024 rows
-    int64_t lblocks = ((int64_t)nS + 15) / 16;
-    if (lblocks > 2048) lblocks = 2048;
+    int64_t lblocks = ((int64_t)nS + 3) / 4;
+    if (lblocks > 8192) lblocks = 8192;
     if (lblocks < ((int64_t)nS + 1023) / 1024) lblocks = ((int64_t)nS + 1023) / 1024;
     const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
     // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
