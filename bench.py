@@ -82,6 +82,7 @@ class Workload:
         self.lbs = self.lbs1
         self.overlap = None
         self.use_graphs = True
+        self.one_stream = False  # --one-stream: the timed schedule without any overlap (what the profiler summaries are made with)
         self.direct = False     # issue the timed schedule call by call (for per-dispatch timing, which a graph replay cannot carry)
         self.Zs = [torch.empty((nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
         self.Hs = [torch.empty((nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
@@ -283,6 +284,17 @@ class Workload:
         st = self.overlap["sets"][k]
         s_comp = self.overlap["s_comp"]
         it0 = p * K
+        if self.one_stream:     # everything in order on the compute stream: every kernel has the device to itself
+            with torch.cuda.stream(s_comp):
+                st["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
+                if st["sample"] is not None:
+                    st["sample"].replay()
+                    st["compute"].replay()
+                else:
+                    st["sample_fn"]()
+                    st["compute_fn"]()
+                self.graph_it[k] = None
+            return st["H"]
         with torch.cuda.stream(st["s_samp"]):
             if st["used"]:
                 st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batches sampled into it were computed
@@ -363,19 +375,23 @@ class Workload:
         assert all(int(lb.status.item()) == 0 for set_ in self.lb_inst for lk in set_ for lb in lk), \
             "a status bit was set in the timed run"
         log(f"host enqueue {enqueue_ms:.3f} ms/step; " + (f"one stream, one batch per call {serial_ms:.3f} ms/step; " if serial else "") +
-            f"{K} batches per sampling call, sampling and compute overlapped {ms_per_step:.3f} ms/step")
-        # (3) per-kernel durations over the timed schedule: the same groups on the same streams, launched call
-        # by call so that every dispatch carries its pair of events (the host stays well ahead of the device)
-        csgs.csgs_profile_enable(True)
-        self.direct = True
-        for p in range(warmup // K, (warmup + steps) // K):
-            self.group(p)
-        torch.cuda.synchronize()
-        self.direct = False
-        csgs.csgs_profile_enable(False)
-        samples = csgs.csgs_profile_samples()
-        prof = csgs.csgs_profile_collect()
-        # (4) the same groups once more, alone on one stream: sizes of every step, and what each kernel takes undisturbed
+            f"{K} batches per sampling call, " + ("everything in order on one stream" if self.one_stream else "sampling and compute overlapped") +
+            f" {ms_per_step:.3f} ms/step")
+        # (3) how long the kernels take inside the timed schedule, beside the kernels of the other streams: the same
+        # groups on the same streams, launched call by call so that every dispatch carries its pair of events (the
+        # host stays well ahead of the device)
+        prof_sched = {}
+        if not self.one_stream:
+            csgs.csgs_profile_enable(True)
+            self.direct = True
+            for p in range(warmup // K, (warmup + steps) // K):
+                self.group(p)
+            torch.cuda.synchronize()
+            self.direct = False
+            csgs.csgs_profile_enable(False)
+            prof_sched = csgs.csgs_profile_collect()
+        # (4) the same groups once more on one stream: sizes of every step, and every kernel's own duration (the device
+        # to itself) -- what the roofline figures are taken from
         sizes = []
         st0 = self.overlap["sets"][0]
         csgs.csgs_profile_enable(True)
@@ -388,7 +404,8 @@ class Workload:
                 self.sizes_of(lk, n0, sizes)
         csgs.csgs_profile_enable(False)
         self.graph_it[0] = None
-        prof_alone = csgs.csgs_profile_collect()
+        samples = csgs.csgs_profile_samples()
+        prof = csgs.csgs_profile_collect()
         assert all(s["status"] == 0 for s in sizes), "a status bit was set"
         alg, flops = {}, 0.0
         for s in sizes:
@@ -405,8 +422,8 @@ class Workload:
                               alg_bytes_per_launch=alg.get(k, 0.0) / cnt)
             if alg.get(k):
                 kernels[k]["alg_GBps"] = alg[k] / (ms * 1e-3) / 1e9
-            if k in prof_alone:
-                kernels[k]["alone_us"] = prof_alone[k][0] / prof_alone[k][1] * 1e3
+            if k in prof_sched:
+                kernels[k]["in_schedule_us"] = prof_sched[k][0] / prof_sched[k][1] * 1e3
             sm = sorted(samples.get(k, []))
             if sm:      # launch by launch: median and the 10th / 90th percentile, in us
                 pick = lambda f: sm[min(len(sm) - 1, int(f * len(sm)))] * 1e3
@@ -414,8 +431,7 @@ class Workload:
         agg_ms = prof["aggregate"][0]
         agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
         gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
-        alone = dict(aggregate_GBps=alg["aggregate"] / (prof_alone["aggregate"][0] * 1e-3) / 1e9,
-                     gemm_TFLOPs=flops / (prof_alone["layer_gemm"][0] * 1e-3) / 1e12)
+
         kernels["layer_gemm"]["TFLOPs"] = gemm_TF
         kernels["layer_gemm"]["flop_per_launch"] = flops / prof["layer_gemm"][1]
         tot = lambda key: sum(s[key] for s in sizes) / steps
@@ -430,7 +446,7 @@ class Workload:
                                   sampled_edges=avg("nnz"), remote_nodes=avg("remote"), F_in=ls[0]["F_in"], F_out=ls[0]["F_out"]))
         per_step["per_layer"] = per_layer
         return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes,
-                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF, alone=alone)
+                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
 
 
 def roofline_of(kernels, name, traffic):
@@ -466,6 +482,8 @@ def main():
     ap.add_argument("--no-batch-compute", action="store_true", help="with --instances K: sample K mini-batches per call but "
                     "compute their layers batch by batch (what a training loop must do: its forward passes depend on "
                     "each other through the weights; the forward passes timed here do not)")
+    ap.add_argument("--one-stream", action="store_true", help="time the schedule without overlap: sampling and compute of every "
+                    "group in order on one stream (every launch then has the device to itself: what the profiler summaries are made with)")
     ap.add_argument("--no-serial", action="store_true", help="skip the one-stream, one-batch-per-call measurement")
     ap.add_argument("--sweep-instances", default="", help="comma-separated K: also time the schedule with K mini-batches per "
                     "sampling call and report step time and the weight scan's rate under \"instances_sweep\"")
@@ -540,6 +558,7 @@ def main():
 
     N_CPU = 20      # whole steps the oracle is timed on (about 11 s on one core at Large)
     wl = mk(cfg, max(args.steps, 0 if args.no_cpu_baseline else N_CPU) + args.warmup, K)
+    wl.one_stream = args.one_stream
     log(f"inputs resident: {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
     res = wl.measure(args.steps, args.warmup, serial=not args.no_serial)
     ms_per_step = res["ms_per_step"]
@@ -623,11 +642,13 @@ def main():
                     precision=("bf16 features, " if bf16 else "f32 features, ") + "u64 fixed-point weights and CDF, f64 accumulation, f32 outputs",
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
-        schedule=f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
-                 "workspace each), layer compute of all batches " + ("of a group in the same launches" if not args.no_batch_compute and K > 1
-                                                                     else "in order") + " on one more stream; each part " +
+        schedule=(f"{K} consecutive mini-batches per library call, sampling then compute of every group in order on one stream; each part "
+                  if args.one_stream else
+                  f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
+                  "workspace each), layer compute of all batches " + ("of a group in the same launches" if not args.no_batch_compute and K > 1
+                                                                      else "in order") + " on one more stream; each part ") +
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
-        aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"], kernels_alone=res["alone"],
+        aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
         roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, instances_sweep=sweep,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
