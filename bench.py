@@ -5,7 +5,12 @@ A step = the whole hot path over one batch of synthetic input: for every GCN lay
 csgs_build_probs -> csgs_sample_layer -> csgs_remote_count; then, bottom-up, csgs_aggregate ->
 csgs_layer_gemm.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large] [--scale S]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large] [--scale S] [--instances 8]
+
+The timed schedule handles several consecutive mini-batches per library call (--instances), samples
+such groups on two streams and computes their layers on a third; every step still does all of its
+work.  Afterwards every kernel is timed launch by launch, inside that schedule and alone on one
+stream; the roofline figures come from the durations alone.
 
 Besides the named workload the default run also times a scaled-up variant of it (batch and samples
 per layer x16, same graph): the named batch moves only a few MB per kernel, which no kernel can
