@@ -158,6 +158,12 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     __syncthreads();
     const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
+    // 16-column MFMA tiles of this block that hold any real column (47 output classes fill 3 of 4), and
+    // k steps of the last chunk that hold any real k (lane group g feeds k = 8 g + s at step s, so with
+    // k_left <= 8 only the first k_left steps of group 0 are not padding): the rest would multiply zeros
+    const int nt_valid = (int)(N - n0 >= BN ? NT : (N - n0 + 15) / 16);
+    const int k_left = n_chunks > 0 ? (k_end - k_begin) - (n_chunks - 1) * BK : 0;
+    const int s_last = k_left >= 8 ? 8 : k_left;
     for (int c = 0; c < n_chunks; ++c) {
         const int cur = c & 1;
         if (c + 1 < n_chunks) fetch(k_begin + (c + 1) * BK);
@@ -176,14 +182,19 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
             bv[t][0] = x.x; bv[t][1] = x.y; bv[t][2] = x.z; bv[t][3] = x.w;
             bv[t][4] = y.x; bv[t][5] = y.y; bv[t][6] = y.z; bv[t][7] = y.w;
         }
+        const int s_end = c + 1 < n_chunks ? 8 : s_last;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const double a0 = (double)av[0][s], a1 = (double)av[1][s];
+            if (s < s_end) {
+                const double a0 = (double)av[0][s], a1 = (double)av[1][s];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const double b = (double)bv[t][s];
-                acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+                for (int t = 0; t < NT; ++t) {
+                    if (t < nt_valid) {
+                        const double b = (double)bv[t][s];
+                        acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
+                        acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+                    }
+                }
             }
         }
         if (c + 1 < n_chunks) {
