@@ -22,7 +22,7 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 // last; how many edges they can hold follows from the size the caller passed.
 constexpr int CAND_TILE = 1024;   // node ids per block in the candidate scan
 constexpr int EDGE_TILE = 1024;   // edges per chunk in the flat edge passes
-constexpr int EDGE_GRID = 2048;   // blocks of the weight scan (grid-stride over chunks, no waits between blocks)
+constexpr int EDGE_GRID = 512;    // chunk blocks of the weight scan (grid-stride over chunks, they wait for nobody): two per compute unit
 constexpr int HIT_TILE_WORDS = 256;   // 64-position bitmap words per block in the hit compaction
 constexpr int ROW_TILE = 1024;    // rows of S per block in the degree prefix
 // Weight scan through owners: edges that end in the local id range are handed, chunk by chunk, to
