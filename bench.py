@@ -559,7 +559,23 @@ def main():
     ams, acnt = csgs.csgs_profile_collect()["atomics"]
     atomic_Gups = n_upd * acnt / (ams * 1e-3) / 1e9
     del table
-    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s")
+    # matrix-core yardstick: the GEMM's instruction (fp64 16 x 16 x 4) back to back from registers, and the
+    # GEMM's inner loop (operands from LDS, widened) without its global loads and barriers
+    sink = torch.zeros(csgs.CALIB_MFMA_BLOCKS * 256, dtype=torch.float64, device=dev)
+    mfma_TF = {}
+    for from_lds in (False, True):
+        for _ in range(2):
+            csgs.csgs_calib_mfma_f64(sink, 256, from_lds)
+        torch.cuda.synchronize()
+        csgs.csgs_profile_enable(True)
+        flops = sum(csgs.csgs_calib_mfma_f64(sink, 256, from_lds) for _ in range(5))
+        torch.cuda.synchronize()
+        csgs.csgs_profile_enable(False)
+        mms, _ = csgs.csgs_profile_collect()["mfma_f64"]
+        mfma_TF[from_lds] = flops / (mms * 1e-3) / 1e12
+    del sink
+    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s; "
+        f"fp64 matrix instructions back to back: {mfma_TF[False]:.1f} TFLOP/s from registers, {mfma_TF[True]:.1f} with operands from LDS")
 
     N_CPU = 20      # whole steps the oracle is timed on (about 11 s on one core at Large)
     wl = mk(cfg, max(args.steps, 0 if args.no_cpu_baseline else N_CPU) + args.warmup, K)
@@ -572,6 +588,8 @@ def main():
     roofline = roofline_of(res["kernels"], dominant, load_traffic(name))
     roofline["copy_kernel_GBps"] = copy_GBps
     roofline["atomic_adds_Gps"] = atomic_Gups      # what bounds scan_edges: one such add per scanned edge
+    roofline["mfma_f64_loop_TFLOPs"] = mfma_TF[False]       # the GEMM's instruction back to back, operands in registers
+    roofline["mfma_f64_lds_loop_TFLOPs"] = mfma_TF[True]    # the GEMM's inner loop without global loads and barriers
     if "scan_edges" in res["kernels"]:
         per_launch = res["per_step"]["edges_scanned"] / res["kernels"]["scan_edges"]["launches_per_step"]
         roofline["scan_edges_adds_Gps"] = per_launch / (res["kernels"]["scan_edges"]["avg_us"] * 1e-6) / 1e9

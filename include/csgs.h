@@ -331,6 +331,9 @@ int csgs_gather_rows(const void *X, int64_t ld, int64_t rows, int32_t F, int dty
 
 /* H [M x Nout] = Z [M x K] W [K x Nout], all row-major fp32 (Eq. 1).  Operands are widened to
  * double, products accumulate in double on the matrix cores, one rounding to float.
+ * With M_dev (device) only the first min(*M_dev, M) rows of H are computed and written; Z must
+ * still be M rows of readable memory -- rows beyond the count may be read, whatever they hold
+ * reaches no row that is written.
  * Host errors: CSGS_EINVAL; CSGS_EUNSUPPORTED when the tile count exceeds 2^30. */
 int csgs_layer_gemm(const float *Z, int64_t ldz, int32_t M, const int32_t *M_dev, int32_t K, const float *W,
                     int64_t ldw, int32_t Nout, float *H, int64_t ldh, void *stream);
@@ -380,7 +383,8 @@ int csgs_gather_rows_n(const csgs_inst_strides *inst /*host*/, const void *X, in
  * csgs_layer_gemm_grad_w: Z [M x K], G [M x Nout] -> dW [K x Nout].  The sum over the M rows is
  *   split into parts that are added in a fixed order; `scratch` (device, 8-byte aligned) holds the
  *   parts: at least csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout) bytes.
- * csgs_layer_gemm_grad_z: G [M x Nout], W [K x Nout] (as in the forward call) -> dZ [M x K].
+ * csgs_layer_gemm_grad_z: G [M x Nout], W [K x Nout] (as in the forward call) -> dZ [M x K]; as in the
+ *   forward call, rows of G beyond a device count may be read and reach no row that is written.
  * csgs_aggregate_grad: P~ as written by csgs_sample_layer (nS rows, n_cols = *n_next columns,
  *   adj_cap = capacity of adj_col / adj_val), dZ [nS x F] -> dH_prev [n_cols x F].  H_prev
  *   [n_cols x F] is the layer's input (NULL: no activation, no mask).  The transpose of P~ is built
@@ -430,6 +434,16 @@ int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
  * `table` (n_table entries, device, 8-byte aligned, contents are modified): the yardstick for the
  * weight scan of csgs_build_probs, which updates its per-node accumulators the same way. */
 int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_updates, void *stream);
+
+/* Matrix-core yardstick for csgs_layer_gemm: CSGS_CALIB_MFMA_BLOCKS blocks of four wavefronts, each
+ * wavefront issuing 64 * iters double-precision 16 x 16 x 4 matrix instructions (2048 flops each) on
+ * eight independent accumulators, i.e. CSGS_CALIB_MFMA_BLOCKS * 4 * 64 * 2048 * iters flops per call.
+ * from_lds = 0: operands stay in registers (what the matrix cores sustain); from_lds = 1: every 64
+ * instructions the operands are re-read from LDS as floats and widened, which is the inner loop of
+ * the layer GEMM without its global loads and barriers.  `sink` (device, n_sink >=
+ * CSGS_CALIB_MFMA_BLOCKS * 256 doubles) receives one value per thread so that the work is kept. */
+#define CSGS_CALIB_MFMA_BLOCKS 2048
+int csgs_calib_mfma_f64(double *sink, size_t n_sink, int64_t iters, int32_t from_lds, void *stream);
 
 /* Static string for a CSGS_E* code. */
 const char *csgs_strerror(int code);

@@ -25,7 +25,7 @@ EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace
            "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect", "csgs_profile_samples",
-           "csgs_calib_copy", "csgs_calib_atomics"]
+           "csgs_calib_copy", "csgs_calib_atomics", "csgs_calib_mfma_f64"]
 
 
 class CsgsError(RuntimeError):
@@ -114,6 +114,7 @@ def lib():
         L.csgs_strerror.argtypes = [C.c_int]
         L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
         L.csgs_calib_atomics.argtypes = [vp, sz, sz, vp]
+        L.csgs_calib_mfma_f64.argtypes = [vp, sz, i64, i32, vp]
         L.csgs_profile_enable.argtypes = [C.c_int]
         L.csgs_profile_kernel_name.restype = C.c_char_p
         L.csgs_profile_kernel_name.argtypes = [C.c_int]
@@ -411,3 +412,13 @@ def csgs_calib_copy(dst, src, stream=None):
 def csgs_calib_atomics(table, n_updates, stream=None):
     """n_updates atomic +1 on pseudo-random entries of `table` (an int64 tensor)."""
     _call("csgs_calib_atomics", _ptr(table), table.numel(), n_updates, _stream(stream))
+
+
+CALIB_MFMA_BLOCKS = 2048   # CSGS_CALIB_MFMA_BLOCKS
+
+
+def csgs_calib_mfma_f64(sink, iters, from_lds=False, stream=None):
+    """Matrix-core yardstick; returns the flops of the call.  `sink`: float64 tensor of at least
+    CALIB_MFMA_BLOCKS * 256 entries."""
+    _call("csgs_calib_mfma_f64", _ptr(sink), sink.numel(), iters, 1 if from_lds else 0, _stream(stream))
+    return CALIB_MFMA_BLOCKS * 4 * 64 * 2048 * iters

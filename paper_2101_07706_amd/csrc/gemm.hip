@@ -20,6 +20,7 @@
 //
 // Block ids are remapped so that consecutive tiles (same rows of Z, neighbouring column tiles)
 // land on the same XCD and share its L2.
+#include <type_traits>
 #include "common.hpp"
 
 namespace csgs {
@@ -50,24 +51,48 @@ __device__ inline float4 load4(const float *__restrict__ p)
 //        kernel adds the parts in a fixed order.
 enum { MODE_FWD = 0, MODE_DZ = 1, MODE_DW = 2 };
 
+// Loads of a tile never sit in divergent control flow (a wavefront would then wait for each load
+// before it issues the next): a group that is out of range reads a clamped, valid address instead, and
+// a bit of `ok` per loaded piece says whether the value counts; stash_tile() turns the others into
+// zeros on the way to LDS, after the MFMAs of the current chunk.
+//
 // Tile [ROWS][BK] of a matrix whose element (r, k) sits at P[r * ld + k] (k contiguous): ROWS * 8
-// groups of 4 consecutive k; thread t takes groups t + 256 i.
+// groups of 4 consecutive k; thread t takes groups t + 256 i, each as 4 / V pieces of V floats
+// (the host picks V so that K is a multiple of it: a piece is inside the row or outside).  Bit
+// 4 i + j of `ok` belongs to float j of group i.
 template <int ROWS, int V, bool FULL>
 __device__ inline void fetch_kmajor(const float *__restrict__ P, int64_t ld, int R, int K, int64_t r0, int k0, int tid,
-                                    float4 (&reg)[ROWS / 32])
+                                    float4 (&reg)[ROWS / 32], uint32_t &ok)
 {
+    ok = 0;
 #pragma unroll
     for (int i = 0; i < ROWS / 32; ++i) {
         const int idx = tid + i * 256;
         const int r = idx >> 3, kq = (idx & 7) * 4;
         const int64_t gr = r0 + r;
         const int gk = k0 + kq;
-        if (FULL || (gr < R && gk + 3 < K)) {
+        if (FULL) {
             reg[i] = load4<V>(P + gr * ld + gk);
         } else {
+            const bool row_ok = gr < R;
+            const float *row = P + (row_ok ? gr : (int64_t)R - 1) * ld;
             float t[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) t[j] = (gr < R && gk + j < K) ? P[gr * ld + gk + j] : 0.f;
+            for (int j = 0; j < 4; j += V) {
+                const bool k_ok = gk + j + V <= K;
+                const bool in = row_ok && k_ok;
+                const float *q = row + (k_ok ? gk + j : K - V);   // the last whole piece of a real row stands in
+                if (V == 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(q);
+                    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+                } else if (V == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(q);
+                    t[j] = v.x; t[j + 1] = v.y;
+                } else {
+                    t[j] = *q;
+                }
+                if (in) ok |= ((1u << V) - 1u) << (4 * i + j);
+            }
             reg[i] = make_float4(t[0], t[1], t[2], t[3]);
         }
     }
@@ -78,8 +103,9 @@ __device__ inline void fetch_kmajor(const float *__restrict__ P, int64_t ld, int
 // 128-bit store into the LDS tile.
 template <int ROWS, bool FULL>
 __device__ inline void fetch_rmajor(const float *__restrict__ P, int64_t ld, int R, int K, int64_t r0, int k0, int tid,
-                                    float4 (&reg)[ROWS / 32])
+                                    float4 (&reg)[ROWS / 32], uint32_t &ok)
 {
+    ok = 0;
 #pragma unroll
     for (int i = 0; i < ROWS / 32; ++i) {
         const int idx = tid + i * 256;          // ROWS * 8 groups
@@ -88,21 +114,33 @@ __device__ inline void fetch_rmajor(const float *__restrict__ P, int64_t ld, int
         const int gk = k0 + kg;
         float t[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t[j] = (FULL || (gr < R && gk + j < K)) ? P[(int64_t)(gk + j) * ld + gr] : 0.f;
+        for (int j = 0; j < 4; ++j) {
+            const bool r_ok = FULL || gr < R, k_ok = FULL || gk + j < K;
+            t[j] = P[(int64_t)(k_ok ? gk + j : K - 1) * ld + (r_ok ? gr : (int64_t)R - 1)];   // the nearest real element stands in
+            if (r_ok && k_ok) ok |= 1u << (4 * i + j);
+        }
         reg[i] = make_float4(t[0], t[1], t[2], t[3]);
     }
 }
 
-// Registers -> LDS tile [ROWS][LDS_STRIDE], with the (r, k) of each group as the fetch above had it.
-template <int ROWS, bool KMAJOR>
-__device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 32])
+// Registers -> LDS tile [ROWS][LDS_STRIDE], with the (r, k) of each group as the fetch above had it;
+// values whose bit in `ok` is clear become zeros.
+template <int ROWS, bool KMAJOR, bool FULL>
+__device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 32], uint32_t ok, bool whole)
 {
 #pragma unroll
     for (int i = 0; i < ROWS / 32; ++i) {
         const int idx = tid + i * 256;
         const int r = KMAJOR ? (idx >> 3) : (idx % ROWS);
         const int k = KMAJOR ? (idx & 7) * 4 : (idx / ROWS) * 4;
-        *reinterpret_cast<float4 *>(&S[r * LDS_STRIDE + k]) = reg[i];
+        float4 v = reg[i];
+        if (!FULL && !whole) {   // `whole` is the same for the whole block: every bit of `ok` is set
+            v.x = (ok >> (4 * i + 0)) & 1u ? v.x : 0.f;
+            v.y = (ok >> (4 * i + 1)) & 1u ? v.y : 0.f;
+            v.z = (ok >> (4 * i + 2)) & 1u ? v.z : 0.f;
+            v.w = (ok >> (4 * i + 3)) & 1u ? v.w : 0.f;
+        }
+        *reinterpret_cast<float4 *>(&S[r * LDS_STRIDE + k]) = v;
     }
 }
 
@@ -127,10 +165,10 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int tile = (bid & 7) * per_xcd + (bid >> 3);
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM, n0 = (int64_t)(tile % n_tiles_n) * BN;
-    // the row count of the sampled layer may live on the device: it bounds M, or K for dW
-    const int M = MODE == MODE_DW ? M_bound : resolve_count(M_bound, rows_dev);
+    // the row count of the sampled layer may live on the device: it bounds M, or K for dW.  As a bound
+    // of M it is only needed once the first chunk's loads are on their way (see below)
+    const int m_dev = (MODE != MODE_DW && rows_dev) ? *rows_dev : M_bound;
     const int K = MODE == MODE_DW ? resolve_count(K_bound, rows_dev) : K_bound;
-    if (m0 >= M) return;  // the whole block leaves together, before any barrier
     const int k_begin = MODE == MODE_DW ? (int)blockIdx.y * k_split : 0;
     const int k_end = MODE == MODE_DW ? (k_begin + k_split < K ? k_begin + k_split : K) : K;
     const int n_chunks = k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0;
@@ -141,20 +179,27 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = doublex4{0.0, 0.0, 0.0, 0.0};
     float4 ra[BM / 32], rb[BN / 32];
+    uint32_t oka = 0, okb = 0;
+    // Rows of A up to M_bound are the caller's memory whatever the device count says, and a row of A
+    // only reaches its own row of C, which is not stored beyond the count: so the count never masks a
+    // load, and the first chunk's loads need not wait for it.
+    const bool a_whole = m0 + BM <= M_bound, b_whole = n0 + BN <= N;
+    bool k_whole = false;   // of the chunk in the registers
     auto fetch = [&](int k0) {
-        if (A_KMAJOR) fetch_kmajor<BM, V, FULL>(A, lda, M, k_end, m0, k0, tid, ra);
-        else fetch_rmajor<BM, FULL>(A, lda, M, k_end, m0, k0, tid, ra);
-        if (B_KMAJOR) fetch_kmajor<BN, V, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb);
-        else fetch_rmajor<BN, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb);
+        k_whole = k0 + BK <= k_end;
+        if (A_KMAJOR) fetch_kmajor<BM, V, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
+        else fetch_rmajor<BM, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
+        if (B_KMAJOR) fetch_kmajor<BN, V, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb, okb);
+        else fetch_rmajor<BN, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb, okb);
     };
     auto stash = [&](int buf) {
-        stash_tile<BM, A_KMAJOR>(As[buf], tid, ra);
-        stash_tile<BN, B_KMAJOR>(Bs[buf], tid, rb);
+        stash_tile<BM, A_KMAJOR, FULL>(As[buf], tid, ra, oka, a_whole && k_whole);
+        stash_tile<BN, B_KMAJOR, FULL>(Bs[buf], tid, rb, okb, b_whole && k_whole);
     };
-    if (n_chunks > 0) {
-        fetch(k_begin);
-        stash(0);
-    }
+    if (n_chunks > 0) fetch(k_begin);
+    const int M = m_dev < 0 ? 0 : (m_dev < M_bound ? m_dev : M_bound);
+    if (m0 >= M) return;  // the whole block leaves together, before any barrier
+    if (n_chunks > 0) stash(0);
     __syncthreads();
     const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
@@ -203,24 +248,29 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
         }
     }
     // accumulator element i of lane l holds row l / 16 + 4 * i, column l % 16 of its 16 x 16 tile
+    auto store = [&](auto whole) {
+        constexpr bool WHOLE = decltype(whole)::value;
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+        for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t row = m0 + wave * 32 + r * 16 + grp + 4 * i;
-            if (FULL || row < M) {
+            for (int i = 0; i < 4; ++i) {
+                const int64_t row = m0 + wave * 32 + r * 16 + grp + 4 * i;
+                if (WHOLE || row < M) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int64_t col = n0 + t * 16 + l16;
-                    if (FULL || col < N) {
-                        if (MODE == MODE_DW)
-                            partial[((int64_t)blockIdx.y * M_bound + row) * N + col] = acc[r][t][i];
-                        else
-                            C[row * ldc + col] = (float)acc[r][t][i];
+                    for (int t = 0; t < NT; ++t) {
+                        const int64_t col = n0 + t * 16 + l16;
+                        if (WHOLE || col < N) {
+                            if (MODE == MODE_DW)
+                                partial[((int64_t)blockIdx.y * M_bound + row) * N + col] = acc[r][t][i];
+                            else
+                                C[row * ldc + col] = (float)acc[r][t][i];
+                        }
                     }
                 }
             }
-        }
+    };
+    if (m0 + BM <= M && (FULL || n0 + BN <= N)) store(std::true_type{});
+    else store(std::false_type{});
 }
 
 // dW[i] = sum over the K parts, in ascending part order (fixed: the result does not depend on timing)
@@ -242,10 +292,11 @@ __global__ __launch_bounds__(256) void gemm_reduce_parts(const double *__restric
     C[(i / N) * ldc + (i % N)] = (float)s;
 }
 
-static int widest(const float *p, int64_t ld)
+// Widest vector (in floats) that loads rows of `k` floats, `ld` apart, in whole pieces
+static int widest(const float *p, int64_t ld, int k)
 {
-    if (ld % 4 == 0 && ((uintptr_t)p & 15) == 0) return 4;
-    if (ld % 2 == 0 && ((uintptr_t)p & 7) == 0) return 2;
+    if (ld % 4 == 0 && k % 4 == 0 && ((uintptr_t)p & 15) == 0) return 4;
+    if (ld % 2 == 0 && k % 2 == 0 && ((uintptr_t)p & 7) == 0) return 2;
     return 1;
 }
 
@@ -256,8 +307,8 @@ static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev,
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), 1, (unsigned)ci.n);
-    const int va = widest(Z, ldz);
-    const bool full = !M_dev && M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;
+    const int va = widest(Z, ldz, K);
+    const bool full = M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;   // of the bounds: a device count only gates the stores
     double *none = nullptr;
     if (full)
         CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
@@ -276,7 +327,7 @@ static void launch_dz(const float *G, int64_t ldg, int M, const int32_t *M_dev, 
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8));
-    const int v = widest(G, ldg) == 4 && widest(W, ldw) == 4 ? 4 : 1;
+    const int v = widest(G, ldg, K) == 4 && widest(W, ldw, K) == 4 ? 4 : 1;
     double *none = nullptr;
     if (v == 4)
         CSGS_LAUNCH(K_GEMM_DZ, (gemm_f32_k<BN, MODE_DZ, 4, false>), grid, dim3(256), st, G, ldg, W, ldw, dZ, lddz, none, M, N, K, M_dev, tn, n_tiles, 0, CompStride{0, 0, 0, 0});

@@ -23,7 +23,7 @@ static const size_t kMaxPairs = 1 << 16;
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce",
-                                            "adjT_count", "adjT_prefix", "adjT_fill", "aggregate_grad", "fill_zero", "copy", "atomics"};
+                                            "adjT_count", "adjT_prefix", "adjT_fill", "aggregate_grad", "fill_zero", "copy", "atomics", "mfma_f64"};
 
 bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {
@@ -65,9 +65,88 @@ __global__ __launch_bounds__(256) void atomics_k(unsigned long long *__restrict_
         (void)__hip_atomic_fetch_add(&table[h % n_table], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
+// Back-to-back v_mfma_f64_16x16x4_f64 on eight independent accumulators per wavefront, 64 per loop
+// iteration: the yardstick for the layer GEMM, whose inner loop is the same instruction stream.
+// FROM_LDS = false: operands stay in registers (the matrix cores' issue rate under load and at the
+// clock the device sustains).  FROM_LDS = true: per iteration every lane reads 6 x 8 floats from LDS
+// with 128-bit reads and widens them, as the GEMM does per K chunk of 32, without its global loads
+// and barriers.
+typedef double calib_d4 __attribute__((ext_vector_type(4)));
+template <bool FROM_LDS>
+__global__ __launch_bounds__(256) void mfma_f64_k(double *__restrict__ sink, int64_t iters)
+{
+    constexpr int STRIDE = 36;
+    __shared__ __attribute__((aligned(16))) float tile[2][64 * STRIDE];
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < 2 * 64 * STRIDE; i += 256) (&tile[0][0])[i] = 1.0f / (float)(1 + (i & 1023));
+    __syncthreads();
+    calib_d4 acc[2][4];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[r][t] = calib_d4{0.0, 0.0, 0.0, 0.0};
+    double a0 = 1.0 / (double)(lane + 1), a1 = 1.0 / (double)(lane + 65), b = 1.0 / (double)(lane + 129);
+    const int off = (lane & 15) * STRIDE + 8 * (lane >> 4);
+    for (int64_t it = 0; it < iters; ++it) {
+        if (FROM_LDS) {
+            const float *base = &tile[it & 1][off];
+            float av[2][8], bv[4][8];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const float4 x = *reinterpret_cast<const float4 *>(base + r * 16 * STRIDE);
+                const float4 y = *reinterpret_cast<const float4 *>(base + r * 16 * STRIDE + 4);
+                av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
+                av[r][4] = y.x; av[r][5] = y.y; av[r][6] = y.z; av[r][7] = y.w;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float4 x = *reinterpret_cast<const float4 *>(base + t * 16 * STRIDE);   // rows 16 t + lane % 16 < 64
+                const float4 y = *reinterpret_cast<const float4 *>(base + t * 16 * STRIDE + 4);
+                bv[t][0] = x.x; bv[t][1] = x.y; bv[t][2] = x.z; bv[t][3] = x.w;
+                bv[t][4] = y.x; bv[t][5] = y.y; bv[t][6] = y.z; bv[t][7] = y.w;
+            }
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const double x0 = (double)av[0][s], x1 = (double)av[1][s];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const double y = (double)bv[t][s];
+                    acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(x0, y, acc[0][t], 0, 0, 0);
+                    acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, y, acc[1][t], 0, 0, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
+                    acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+                }
+        }
+    }
+    double sum = 0.0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) sum += acc[r][t][0] + acc[r][t][1] + acc[r][t][2] + acc[r][t][3];
+    sink[(size_t)blockIdx.x * 256 + tid] = sum;
+}
 }  // namespace csgs
 
 using namespace csgs::prof;
+
+extern "C" int csgs_calib_mfma_f64(double *sink, size_t n_sink, int64_t iters, int32_t from_lds, void *stream)
+{
+    if (!sink || ((uintptr_t)sink & 7) || iters <= 0 || iters > (1 << 24) || n_sink < (size_t)CSGS_CALIB_MFMA_BLOCKS * 256)
+        return CSGS_EINVAL;
+    if (from_lds)
+        CSGS_LAUNCH(K_MFMA_F64, csgs::mfma_f64_k<true>, dim3(CSGS_CALIB_MFMA_BLOCKS), dim3(256), (hipStream_t)stream, sink, iters);
+    else
+        CSGS_LAUNCH(K_MFMA_F64, csgs::mfma_f64_k<false>, dim3(CSGS_CALIB_MFMA_BLOCKS), dim3(256), (hipStream_t)stream, sink, iters);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
 
 extern "C" int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream)
 {

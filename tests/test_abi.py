@@ -79,6 +79,8 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.csgs_layer_gemm_grad_w(z, 1, z, 1, 1, z, 1, 1, z, 1, z, 0, z) == csgs.EINVAL
     assert L.csgs_layer_gemm_grad_z(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_aggregate_grad(z, z, z, 1, 1, z, 1, z, z, 1, 1, z, 1, z, 1, z, 0, z) == csgs.EINVAL
+    assert L.csgs_calib_mfma_f64(z, 1 << 20, 1, 0, z) == csgs.EINVAL
+    assert L.csgs_calib_mfma_f64(C.c_void_p(4096), 100, 1, 0, z) == csgs.EINVAL     # sink too small
     assert L.csgs_workspace_init(None, z) == csgs.EINVAL
     ws = csgs.Workspace(0, 0, 10, 1, 1, 1, 0, 0, 0, 0)
     assert L.csgs_workspace_init(C.byref(ws), z) == csgs.EINVAL           # null base

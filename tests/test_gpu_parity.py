@@ -681,6 +681,8 @@ def test_layer_gemm_and_aggregate_device_row_count(dev):
     Z = rng.standard_normal((M, K)).astype(np.float32)
     W = rng.standard_normal((K, N)).astype(np.float32)
     Zd, Wd = torch.from_numpy(Z).to(dev), torch.from_numpy(W).to(dev)
+    Zd[m:] = float("nan")          # rows beyond the count may be read; what they hold must reach nothing
+    Zd[m + 1::3] = float("inf")
     H = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
     cnt = torch.tensor([m], dtype=torch.int32, device=dev)
     csgs.csgs_layer_gemm(Zd, Wd, H, M_dev=cnt)
@@ -907,6 +909,8 @@ def test_layer_gemm_gradients(dev, M, K, N):
         cnt = torch.tensor([m], dtype=torch.int32, device=dev)
         dW.fill_(float("nan"))
         dZ.fill_(float("nan"))
+        Zd[m:] = float("nan")      # rows beyond the count: never summed into dW, never reach a written row of dZ
+        Gd[m:] = float("inf")
         csgs.csgs_layer_gemm_grad_w(Zd, Gd, dW, scratch, M_dev=cnt)
         csgs.csgs_layer_gemm_grad_z(Gd, Wd, dZ, M_dev=cnt)
         torch.cuda.synchronize()
@@ -1023,6 +1027,26 @@ def test_calibration_kernels(dev):
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     assert int(table.sum().item()) == 123457 and int(table.min().item()) > 0
+    # matrix-core yardstick: the sums say how many instructions ran.  Lane l feeds A[l % 16][l // 16] and
+    # B[l // 16][l % 16] of a 16 x 16 x 4 product; the kernel adds up every accumulator element
+    iters = 3
+    sink = torch.zeros(csgs.CALIB_MFMA_BLOCKS * 256, dtype=torch.float64, device=dev)
+    flops = csgs.csgs_calib_mfma_f64(sink, iters)
+    torch.cuda.synchronize()
+    assert flops == csgs.CALIB_MFMA_BLOCKS * 4 * 64 * 2048 * iters
+    lane = np.arange(64)
+    m, k = lane % 16, lane // 16
+    A0 = np.zeros((16, 4)); A1 = np.zeros((16, 4)); Bm = np.zeros((4, 16))
+    A0[m, k] = 1.0 / (lane + 1); A1[m, k] = 1.0 / (lane + 65); Bm[k, m] = 1.0 / (lane + 129)
+    per_wave = 4 * 8 * iters * float((A0 @ Bm).sum() + (A1 @ Bm).sum())
+    got = sink.cpu().numpy().reshape(-1, 64).sum(axis=1)
+    np.testing.assert_allclose(got, per_wave, rtol=1e-12)
+    csgs.csgs_calib_mfma_f64(sink, iters, from_lds=True)
+    torch.cuda.synchronize()
+    got = sink.cpu().numpy().reshape(-1, 256)
+    assert np.isfinite(got).all() and (got > 0).all() and (got == got[0]).all()
+    with pytest.raises(RuntimeError):
+        csgs.csgs_calib_mfma_f64(sink[:1000], iters)
 
 
 @pytest.mark.parametrize("scan_mode", [1, 2])
