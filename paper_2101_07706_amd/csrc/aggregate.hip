@@ -7,7 +7,7 @@
 // and rounded to float once: sampled rows carry 1/p_j discounts of 10^2..10^3, so near-cancelling
 // outputs would lose the 1e-5 absolute tolerance with a float accumulator; the kernel is bound
 // by memory traffic, so the wider adds are free.  Rows with many kept edges (hubs) are taken by
-// whole blocks, dispatched first in the same launch.
+// all wavefronts of the block that owns them, after its ordinary rows.
 //
 // Also here: csgs_gather_rows (staging of the sampled remote feature rows) and csgs_aggregate_grad
 // (dH_prev = (P~^T dZ) .* [H_prev > 0]: the same kernel on a per-call transpose of P~).
@@ -142,7 +142,7 @@ __device__ inline void store_row(float *z, const double (&acc)[V])
 
 // Ordinary rows: block `bid` of AGG_BLOCK threads owns AGG_BLOCK / G consecutive rows.
 template <typename T, int V, int G, bool RELU>
-__device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ adj_rowptr,
+__device__ inline bool aggregate_rows(int64_t bid, const int32_t *__restrict__ adj_rowptr,
                                       const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
                                       int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
                                       const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
@@ -153,11 +153,12 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
     const int g = tid & (G - 1);  // lane within the row group
     const int gbase = tid & (WAVE - 1) & ~(G - 1);
     const int64_t row = (bid * AGG_BLOCK + tid) / G;
-    // Rows past the end, and long rows (left to the long-row blocks), take part in the lane broadcasts of
+    // Rows past the end, and long rows (left to the block's second pass), take part in the lane broadcasts of
     // their wavefront with an empty range.
     int32_t beg = 0, end = 0;
     if (row < nS) { beg = adj_rowptr[row]; end = adj_rowptr[row + 1]; }
-    const bool mine = row < nS && (end - beg) <= LONG_ROW;
+    const bool is_long = row < nS && (end - beg) > LONG_ROW;
+    const bool mine = row < nS && !is_long;
     if (!mine) end = beg;
     // trip count of the edge loop must be uniform over the wavefront when G < 64
     const int32_t len = end - beg;
@@ -191,14 +192,15 @@ __device__ inline void aggregate_rows(int64_t bid, const int32_t *__restrict__ a
             store_row<V>(Z + row * ldz + f, acc);
         }
     }
+    return is_long;
 }
 
 // Rows with more than LONG_ROW kept edges (hubs among the rows of S): the block's wavefronts
 // work on one such row at a time, each wavefront takes a contiguous share of the row's edges,
 // partial sums are added in wavefront order through LDS (fixed order: the result does not depend
-// on timing).  Block `bid` of `n_blocks` looks for long rows among its share of `per` rows.
+// on timing).  Block `bid` takes the long ones among its own `per` rows, in row order.
 template <typename T, int V, bool RELU>
-__device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32_t *__restrict__ adj_rowptr,
+__device__ inline void aggregate_long_rows(int64_t bid, int32_t per, const int32_t *__restrict__ adj_rowptr,
                                            const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
                                            int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl,
                                            int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
@@ -206,17 +208,16 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
                                            int64_t ldz, const float *__restrict__ mask, int64_t ldm)
 {
     __shared__ double part[AGG_WAVES][WAVE * V];
-    __shared__ int32_t long_rows[1024];
+    __shared__ int32_t long_rows[AGG_BLOCK / 16];   // per <= AGG_BLOCK / 16 rows
     __shared__ int32_t n_long;
     const int tid = (int)threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
-    // this block's share of the rows, searched in parallel for long ones
-    const int32_t r0 = bid * per;
-    if (tid == 0) n_long = 0;
-    __syncthreads();
-    for (int32_t i = tid; i < per; i += AGG_BLOCK) {   // per <= 1024 is arranged by the host
-        const int32_t row = r0 + i;
-        if (row < nS && adj_rowptr[row + 1] - adj_rowptr[row] > LONG_ROW) long_rows[atomicAdd(&n_long, 1)] = row;
+    if (wave == 0) {   // one lane per row of the block; the list keeps row order
+        const int64_t row = bid * per + lane;
+        const bool is_long = lane < per && row < nS && adj_rowptr[row + 1] - adj_rowptr[row] > LONG_ROW;
+        const uint64_t m = __ballot(is_long);
+        if (is_long) long_rows[__popcll(m & ((1ull << lane) - 1ull))] = (int32_t)row;
+        if (lane == 0) n_long = __popcll(m);
     }
     __syncthreads();
     const int32_t cnt = n_long;
@@ -261,8 +262,8 @@ __device__ inline void aggregate_long_rows(int32_t bid, int32_t per, const int32
     }
 }
 
-// One launch: the first n_long_blocks blocks take the long rows (they start first, so the slowest
-// work is not left for the end), the others the ordinary rows.
+// A block first takes the ordinary ones among its AGG_BLOCK / G rows, one group of lanes each, then,
+// all wavefronts together, the long ones among them (a block-wide vote says whether there are any).
 template <typename T, int V, int G, bool RELU>
 __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                          const int32_t *__restrict__ adj_col,
@@ -272,8 +273,8 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
                                                          const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
                                                          const int32_t *__restrict__ src_row, int32_t F,
-                                                         float *__restrict__ Z, int64_t ldz, int32_t n_long_blocks,
-                                                         int32_t per, const float *__restrict__ mask, int64_t ldm,
+                                                         float *__restrict__ Z, int64_t ldz,
+                                                         const float *__restrict__ mask, int64_t ldm,
                                                          CompStride cs)
 {
     adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
@@ -281,12 +282,11 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
     Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
     const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
     const int32_t nS = resolve_count(nS_bound, nS_dev);
-    if ((int32_t)blockIdx.x < n_long_blocks)
-        aggregate_long_rows<T, V, RELU>((int32_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl, rows_l,
-                                        Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
-    else
-        aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x - n_long_blocks, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl,
-                                      ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
+    const bool is_long = aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl,
+                                                       ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
+    if (__syncthreads_or(is_long ? 1 : 0))
+        aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
+                                        rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
 }
 
 template <typename T, int V, int G>
@@ -296,21 +296,14 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
 {
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
-    // long-row blocks: about 4 rows each to look through (a block works its long rows off one after
-    // the other, so where most rows are long -- dense neighborhoods -- there must be many blocks),
-    // never more than 1024 rows
-    int64_t lblocks = ((int64_t)nS + 3) / 4;
-    if (lblocks > 8192) lblocks = 8192;
-    if (lblocks < ((int64_t)nS + 1023) / 1024) lblocks = ((int64_t)nS + 1023) / 1024;
-    const int32_t per = (int32_t)(((int64_t)nS + lblocks - 1) / lblocks);
     // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
-    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)((F + G * V - 1) / (G * V)), (unsigned)ci.n);
+    const dim3 grid((unsigned)blocks, (unsigned)((F + G * V - 1) / (G * V)), (unsigned)ci.n);
     if (relu)
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm, ci.cs);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, ci.cs);
     else
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, (int32_t)lblocks, per, mask, ldm, ci.cs);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, ci.cs);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -144,7 +144,12 @@ __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 
     }
 }
 
-template <int BN, int MODE, int V, bool FULL>
+// TAIL (forward product only, K = 32 n + 1 .. 4 with n >= 1): the last 1 .. 4 k do not get a chunk of
+// their own, whose loads, barrier and LDS reads would cost as much as a full one (100 input features
+// are three chunks and four k).  They are loaded once, before the first barrier, into the four padding
+// words of the rows of the LDS buffer that will hold the last chunk, and take one MFMA step after it,
+// in which lane group g feeds k = 32 n + g.
+template <int BN, int MODE, int V, bool FULL, bool TAIL = false>
 __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, double *__restrict__ partial, int M_bound, int N,
@@ -171,7 +176,8 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int K = MODE == MODE_DW ? resolve_count(K_bound, rows_dev) : K_bound;
     const int k_begin = MODE == MODE_DW ? (int)blockIdx.y * k_split : 0;
     const int k_end = MODE == MODE_DW ? (k_begin + k_split < K ? k_begin + k_split : K) : K;
-    const int n_chunks = k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0;
+    static_assert(!TAIL || (MODE == MODE_FWD && !FULL), "the folded tail is for ragged forward products");
+    const int n_chunks = TAIL ? (k_end - k_begin) / BK : (k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0);
 
     doublex4 acc[2][NT];
 #pragma unroll
@@ -200,6 +206,25 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int M = m_dev < 0 ? 0 : (m_dev < M_bound ? m_dev : M_bound);
     if (m0 >= M) return;  // the whole block leaves together, before any barrier
     if (n_chunks > 0) stash(0);
+    if (TAIL) {
+        const int kt = k_begin + n_chunks * BK, tail = k_end - kt, last = (n_chunks - 1) & 1;
+        {   // A: 128 rows x 4 k, two floats per thread
+            const int r = tid >> 1, j0 = (tid & 1) * 2;
+            const int64_t gr = m0 + r;
+            const float *row = A + (gr < M_bound ? gr : (int64_t)M_bound - 1) * lda;
+#pragma unroll
+            for (int j = j0; j < j0 + 2; ++j) {
+                const float v = row[j < tail ? kt + j : k_end - 1];
+                As[last][r * LDS_STRIDE + BK + j] = (gr < M_bound && j < tail) ? v : 0.f;
+            }
+        }
+        if (tid < BN * 4) {   // B: 4 k x BN columns, one float per thread
+            const int n = tid % BN, j = tid / BN;
+            const int64_t gn = n0 + n;
+            const float v = Bm[(int64_t)(j < tail ? kt + j : k_end - 1) * ldb + (gn < N ? gn : (int64_t)N - 1)];
+            Bs[last][n * LDS_STRIDE + BK + j] = (gn < N && j < tail) ? v : 0.f;
+        }
+    }
     __syncthreads();
     const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
@@ -245,6 +270,19 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
         if (c + 1 < n_chunks) {
             stash(cur ^ 1);
             __syncthreads();
+        }
+    }
+    if (TAIL) {
+        const int last = (n_chunks - 1) & 1;
+        const double a0 = (double)As[last][(wave * 32 + l16) * LDS_STRIDE + BK + grp];
+        const double a1 = (double)As[last][(wave * 32 + 16 + l16) * LDS_STRIDE + BK + grp];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if (t < nt_valid) {
+                const double b = (double)Bs[last][(t * 16 + l16) * LDS_STRIDE + BK + grp];
+                acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+            }
         }
     }
     // accumulator element i of lane l holds row l / 16 + 4 * i, column l % 16 of its 16 x 16 tile
@@ -310,8 +348,15 @@ static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev,
     const int va = widest(Z, ldz, K);
     const bool full = M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;   // of the bounds: a device count only gates the stores
     double *none = nullptr;
+    const bool fold = K > BK && K % BK >= 1 && K % BK <= 4;   // see TAIL
     if (full)
         CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
+    else if (fold && va == 4)
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
+    else if (fold && va == 2)
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
+    else if (fold)
+        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
     else if (va == 4)
         CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
     else if (va == 2)

@@ -445,7 +445,10 @@ def test_aggregate_shapes(dev, F, bf16, mode):
 
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (33, 17, 5), (256, 64, 64), (1024, 128, 256), (2048, 602, 256),
                                    (2048, 256, 41), (4096, 300, 512), (4096, 512, 100), (8192, 100, 256),
-                                   (8192, 256, 256), (8192, 256, 47), (100, 1000, 70)])
+                                   (8192, 256, 256), (8192, 256, 47), (100, 1000, 70),
+                                   # one to four k beyond whole chunks of 32: folded into the last chunk
+                                   (300, 36, 70), (513, 68, 47), (1000, 33, 64), (257, 66, 33), (129, 99, 20),
+                                   (4096, 132, 256), (640, 35, 300), (77, 34, 16), (128, 37, 64)])
 def test_layer_gemm_shapes(dev, M, K, N):
     from paper_2101_07706_amd import csgs
     rng = np.random.default_rng(M + K + N)
@@ -673,10 +676,26 @@ def test_gather_rows(dev, F, bf16, off):
     assert (got[n:] == 99).all(), "rows past the device count were written"
 
 
+def _gemm_device_row_count(dev, rng, M, K, N, m):
+    from paper_2101_07706_amd import csgs
+    Z = rng.standard_normal((M, K)).astype(np.float32)
+    W = rng.standard_normal((K, N)).astype(np.float32)
+    Zd, Wd = torch.from_numpy(Z).to(dev), torch.from_numpy(W).to(dev)
+    Zd[m:] = float("nan")          # rows beyond the count may be read; what they hold must reach nothing
+    Zd[m + 1::3] = float("inf")
+    H = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    csgs.csgs_layer_gemm(Zd, Wd, H, M_dev=torch.tensor([m], dtype=torch.int32, device=dev))
+    torch.cuda.synchronize()
+    chain.assert_close(H[:m].cpu().numpy(), oracle.layer_gemm(Z[:m], W), chain.RTOL, chain.ATOL, f"H with M_dev {M}x{K}x{N}")
+    assert bool(torch.isnan(H[m:]).all())
+
+
 def test_layer_gemm_and_aggregate_device_row_count(dev):
     """M_dev / nS_dev below the capacity: the first rows equal a call of that size, the rest stay untouched."""
     from paper_2101_07706_amd import csgs
     rng = np.random.default_rng(8)
+    for M, K, N, m in [(700, 96, 80, 389), (700, 100, 80, 389), (1024, 256, 256, 1000), (1024, 68, 256, 3)]:
+        _gemm_device_row_count(dev, rng, M, K, N, m)
     M, K, N, m = 700, 96, 80, 389
     Z = rng.standard_normal((M, K)).astype(np.float32)
     W = rng.standard_normal((K, N)).astype(np.float32)
