@@ -71,15 +71,16 @@ __device__ inline void resolve_edge(int32_t e, const int32_t *__restrict__ adj_c
     *src = nullptr;
     *w = 0.f;
     const int32_t c = adj_col[e];
+    const float val = adj_val[e];   // asked for together with the column: one load latency, not two
     // a column or source row outside the tables contributes nothing (keeps every load in bounds)
     if (c >= 0 && c < n_cols) {
         const int64_t sr = src_row ? (int64_t)src_row[c] : (int64_t)c;
         if (sr >= 0 && sr < rows_l) {
             *src = Xl + sr * ldl;
-            *w = adj_val[e];
+            *w = val;
         } else if (sr < 0 && -1 - sr < rows_r) {
             *src = Xr + (-1 - sr) * ldr;
-            *w = adj_val[e];
+            *w = val;
         }
     }
 }
@@ -144,7 +145,9 @@ __device__ inline void store_row(float *z, const double (&acc)[V])
 template <typename T, int V, int G, bool RELU>
 __device__ inline bool aggregate_rows(int64_t bid, const int32_t *__restrict__ adj_rowptr,
                                       const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
-                                      int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
+                                      int32_t nS_bound, const int32_t *__restrict__ nS_dev,
+                                      const int32_t *__restrict__ n_cols_p, int64_t n_cols_default, int32_t *nS_out,
+                                      int64_t *n_cols_out, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
                                       const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
                                       const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z, int64_t ldz,
                                       const float *__restrict__ mask, int64_t ldm)
@@ -153,10 +156,20 @@ __device__ inline bool aggregate_rows(int64_t bid, const int32_t *__restrict__ a
     const int g = tid & (G - 1);  // lane within the row group
     const int gbase = tid & (WAVE - 1) & ~(G - 1);
     const int64_t row = (bid * AGG_BLOCK + tid) / G;
+    // The two counts that may live on the device and the row's extent are asked for together, before any of
+    // them is used: one load latency instead of three in a row.  The row pointers have nS_bound + 1 entries
+    // whatever the count says; a count that is not given is read from a stand-in address and dropped.
+    const int64_t row_c = row < nS_bound ? row : (int64_t)nS_bound - 1;
+    const int32_t nS_raw = *(nS_dev ? nS_dev : adj_rowptr);
+    const int32_t n_cols_raw = *(n_cols_p ? n_cols_p : adj_rowptr);
+    int32_t beg = adj_rowptr[row_c], end = adj_rowptr[row_c + 1];
+    const int32_t nS = !nS_dev ? nS_bound : (nS_raw < 0 ? 0 : (nS_raw < nS_bound ? nS_raw : nS_bound));
+    const int64_t n_cols = n_cols_p ? (int64_t)n_cols_raw : n_cols_default;
+    *nS_out = nS;
+    *n_cols_out = n_cols;
     // Rows past the end, and long rows (left to the block's second pass), take part in the lane broadcasts of
     // their wavefront with an empty range.
-    int32_t beg = 0, end = 0;
-    if (row < nS) { beg = adj_rowptr[row]; end = adj_rowptr[row + 1]; }
+    if (row >= nS) { beg = 0; end = 0; }
     const bool is_long = row < nS && (end - beg) > LONG_ROW;
     const bool mine = row < nS && !is_long;
     if (!mine) end = beg;
@@ -280,10 +293,11 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
     adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
     nS_dev = inst_ptr(nS_dev, cs.adj); n_cols_p = inst_ptr(n_cols_p, cs.adj); src_row = inst_ptr(src_row, cs.adj);
     Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
-    const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
-    const int32_t nS = resolve_count(nS_bound, nS_dev);
-    const bool is_long = aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl,
-                                                       ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
+    int32_t nS;
+    int64_t n_cols;
+    const bool is_long = aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x, adj_rowptr, adj_col, adj_val, nS_bound, nS_dev,
+                                                       n_cols_p, src_row ? 0x7FFFFFFFll : rows_l, &nS, &n_cols, Xl, ldl,
+                                                       rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
     if (__syncthreads_or(is_long ? 1 : 0))
         aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
                                         rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
