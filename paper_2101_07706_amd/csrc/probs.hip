@@ -193,20 +193,40 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
         unsigned long long hq[EDGE_TILE / 256];
         int32_t hc[EDGE_TILE / 256], hb[EDGE_TILE / 256];
         uint32_t hr[EDGE_TILE / 256];
+        // All of a thread's edges go through each step together -- their addresses, then their columns and
+        // values with unconditional loads (an edge that does not exist reads entry 0 and is dropped) -- so
+        // the loads of the four edges travel at the same time instead of one after the other.
+        int64_t ek[EDGE_TILE / 256];
+        bool live[EDGE_TILE / 256];
+#pragma unroll
+        for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            const int32_t x = (int32_t)threadIdx.x + k * 256;
+            ek[k] = 0;
+            live[k] = x < len;
+            if (live[k]) {
+                int32_t r;
+                ek[k] = edge_address(slice, eoff, rowstart, c0, x, &r);
+                if (ek[k] < 0 || ek[k] >= nnz) {   // only after a failed wait in the prefix kernel: stay inside the graph
+                    bad = true;
+                    ek[k] = 0;
+                    live[k] = false;
+                }
+            }
+        }
+        int32_t ck[EDGE_TILE / 256];
+        float vk[EDGE_TILE / 256];
+#pragma unroll
+        for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            ck[k] = colidx[ek[k]];
+            vk[k] = val[ek[k]];
+        }
 #pragma unroll
         for (int k = 0; k < EDGE_TILE / 256; ++k) {
             hb[k] = -1;
             hq[k] = 0ull; hc[k] = 0; hr[k] = 0u;
-            const int32_t x = (int32_t)threadIdx.x + k * 256;
-            if (x >= len) continue;
-            int32_t r;
-            const int64_t e = edge_address(slice, eoff, rowstart, c0, x, &r);
-            if (e < 0 || e >= nnz) {   // only after a failed wait in the prefix kernel: stay inside the graph
-                bad = true;
-                continue;
-            }
-            const int32_t c = colidx[e];
-            const float v = val[e];
+            if (!live[k]) continue;
+            const int32_t c = ck[k];
+            const float v = vk[k];
             if (!isfinite(v) || c < 0 || c >= n_nodes) {
                 bad = true;
                 continue;
@@ -316,19 +336,28 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
     const int64_t t = blockIdx.x;
     const unsigned long long tag = call_tag(call_number(epoch), SLOT_CAND);
     uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
+    // First the flags of all the wavefront's words, then all its pieces of the table: two load latencies.
+    // (Word by word, with the next word's flags asked for only after this word's pieces have arrived, it
+    // was eight in a row.)
+    uint64_t f8[CAND_WORDS / 4], w[CAND_WORDS / 4];
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
-        if (word_idx >= n_words) continue;
-        const uint64_t f8 = reinterpret_cast<const uint64_t *>(tileflag)[word_idx];   // the word's eight group flags
-        if (f8 == 0) continue;
-        const int64_t id = word_idx * 64 + lane;
+        f8[k] = word_idx < n_words ? reinterpret_cast<const uint64_t *>(tileflag)[word_idx] : 0ull;   // the word's eight group flags
+    }
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
         // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
-        const uint64_t w = (((f8 >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
-        if (w) {
+        w[k] = (((f8[k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
+    }
+#pragma unroll
+    for (int k = 0; k < CAND_WORDS / 4; ++k) {
+        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
+        if (w[k]) {
             const bool local = id >= lo && id < hi;
             cn += (1ull << 32) | (local ? 1ull : 0ull);
-            if (local) wl += w; else wr += w;
+            if (local) wl += w[k]; else wr += w[k];
         }
     }
     cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
