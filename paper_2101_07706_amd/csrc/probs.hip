@@ -154,9 +154,11 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
                     }
                     const int src = lo_l < WAVE ? lo_l : WAVE - 1;
                     const int64_t pos = (cb + src) * EDGE_TILE + __shfl(beg, src, WAVE) + (j - __shfl(excl, src, WAVE));
-                    const bool on = j < total;
-                    wv[u] = on ? ld_relaxed((const unsigned long long *)&stg.w[pos]) : 0ull;
-                    cv[u] = on ? ld_relaxed32(&stg.c[pos]) : 0u;
+                    // unconditional (entry 0 stands in past the end and is dropped below), so that the four
+                    // steps' loads are on their way together
+                    const int64_t at = j < total ? pos : 0;
+                    wv[u] = ld_relaxed((const unsigned long long *)&stg.w[at]);
+                    cv[u] = ld_relaxed32(&stg.c[at]);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -220,27 +222,31 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
             ck[k] = colidx[ek[k]];
             vk[k] = val[ek[k]];
         }
+        // Everything that reads a loaded value comes before the first update: an update issued between two
+        // such reads would have to be acknowledged before the second value counts as arrived.
+        long long qk[EDGE_TILE / 256];
+#pragma unroll
+        for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            const bool sound = isfinite(vk[k]) && ck[k] >= 0 && ck[k] < n_nodes;
+            if (live[k] && !sound) bad = true;
+            live[k] = live[k] && sound;
+            const double sq = (double)vk[k] * (double)vk[k];   // exact: 24 x 24 bit product
+            qk[k] = live[k] ? __double2ll_rn(sq * scale) : 0;  // scale is a power of two: exact, then RNE
+            if (qk[k] < 1) qk[k] = 1;                          // every candidate stays drawable
+        }
 #pragma unroll
         for (int k = 0; k < EDGE_TILE / 256; ++k) {
             hb[k] = -1;
             hq[k] = 0ull; hc[k] = 0; hr[k] = 0u;
             if (!live[k]) continue;
             const int32_t c = ck[k];
-            const float v = vk[k];
-            if (!isfinite(v) || c < 0 || c >= n_nodes) {
-                bad = true;
-                continue;
-            }
-            const double sq = (double)v * (double)v;      // exact: 24 x 24 bit product
-            long long q = __double2ll_rn(sq * scale);     // scale is a power of two: exact, then RNE
-            if (q < 1) q = 1;                             // every candidate stays drawable
             if (staged && c >= stg.lo && c < stg.hi) {
                 hb[k] = (c - stg.lo) / SUB_IDS;           // < owners <= SUB_MAX
-                hq[k] = (unsigned long long)q;
+                hq[k] = (unsigned long long)qk[k];
                 hc[k] = c;
                 hr[k] = atomicAdd(&hist[hb[k]], 1u);      // place inside the owner's group (any order)
             } else {
-                (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)q, __ATOMIC_RELAXED,
+                (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)qk[k], __ATOMIC_RELAXED,
                                              __HIP_MEMORY_SCOPE_AGENT);
                 tileflag[c >> 3] = 1;  // same value from every writer
             }
