@@ -221,7 +221,7 @@ __device__ inline void aggregate_long_rows(int64_t bid, int32_t per, const int32
                                            int64_t ldz, const float *__restrict__ mask, int64_t ldm)
 {
     __shared__ double part[AGG_WAVES][WAVE * V];
-    __shared__ int32_t long_rows[AGG_BLOCK / 16];   // per <= AGG_BLOCK / 16 rows
+    __shared__ int32_t long_rows[WAVE];   // per <= 64 rows, one lane each
     __shared__ int32_t n_long;
     const int tid = (int)threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
@@ -276,7 +276,11 @@ __device__ inline void aggregate_long_rows(int64_t bid, int32_t per, const int32
 }
 
 // A block first takes the ordinary ones among its AGG_BLOCK / G rows, one group of lanes each, then,
-// all wavefronts together, the long ones among them (a block-wide vote says whether there are any).
+// all wavefronts together, the long ones among them (a block-wide vote says whether there are any):
+// no block exists only to look for long rows, which matters when the grid takes many rounds.
+// With n_long_blocks > 0 (the host asks for it when the whole grid is resident at once, where the
+// longest path counts and not the number of blocks) the long rows go to that many leading blocks
+// instead, `per` rows to look through each, and start together with the ordinary ones.
 template <typename T, int V, int G, bool RELU>
 __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                          const int32_t *__restrict__ adj_col,
@@ -288,18 +292,25 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const int32_t *__restrict__ src_row, int32_t F,
                                                          float *__restrict__ Z, int64_t ldz,
                                                          const float *__restrict__ mask, int64_t ldm,
-                                                         CompStride cs)
+                                                         int32_t n_long_blocks, int32_t per, CompStride cs)
 {
     adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
     nS_dev = inst_ptr(nS_dev, cs.adj); n_cols_p = inst_ptr(n_cols_p, cs.adj); src_row = inst_ptr(src_row, cs.adj);
     Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
+    if ((int32_t)blockIdx.x < n_long_blocks) {
+        const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
+        aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, resolve_count(nS_bound, nS_dev),
+                                        n_cols, Xl, ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
+        return;
+    }
+    const int64_t bid = (int64_t)blockIdx.x - n_long_blocks;
     int32_t nS;
     int64_t n_cols;
-    const bool is_long = aggregate_rows<T, V, G, RELU>((int64_t)blockIdx.x, adj_rowptr, adj_col, adj_val, nS_bound, nS_dev,
+    const bool is_long = aggregate_rows<T, V, G, RELU>(bid, adj_rowptr, adj_col, adj_val, nS_bound, nS_dev,
                                                        n_cols_p, src_row ? 0x7FFFFFFFll : rows_l, &nS, &n_cols, Xl, ldl,
                                                        rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
-    if (__syncthreads_or(is_long ? 1 : 0))
-        aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
+    if (n_long_blocks == 0 && __syncthreads_or(is_long ? 1 : 0))
+        aggregate_long_rows<T, V, RELU>(bid, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
                                         rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
 }
 
@@ -311,13 +322,21 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     const int rows_per_block = AGG_BLOCK / G;
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
     // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
-    const dim3 grid((unsigned)blocks, (unsigned)((F + G * V - 1) / (G * V)), (unsigned)ci.n);
+    const int64_t chunks = (F + G * V - 1) / (G * V);
+    // Leading blocks for the long rows (4 rows each to look through) only when the row blocks are resident
+    // at once, or nearly (8 blocks of 256 threads per compute unit; the leading blocks are gone quickly)
+    int64_t lblocks = 0, per = 0;
+    if ((blocks + ((int64_t)nS + 3) / 4) * chunks * ci.n <= 2 * 8 * 256) {
+        lblocks = ((int64_t)nS + 3) / 4;
+        per = ((int64_t)nS + lblocks - 1) / lblocks;
+    }
+    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)chunks, (unsigned)ci.n);
     if (relu)
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, ci.cs);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, ci.cs);
     else
         CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, ci.cs);
+                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, ci.cs);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
