@@ -325,7 +325,10 @@ constexpr int CAND_WORDS = CAND_TILE / WAVE;  // 16 words per tile, 4 per wave
 
 // Tile sums, and -- by the last tile of every group of 64 -- the group's sums.  That tile waits
 // for the flags of the (at most 63) lower tiles of its group, which were dispatched before it
-// (one tile per block, ascending block ids) and wait for nobody, so the wait ends.
+// (ascending block ids) or belong to its own block and are published before the wait, and which
+// wait for nobody, so the wait ends.  A block takes CAND_PART_TILES consecutive tiles and asks for
+// the flags of all their words, then for all their pieces of the table: two load latencies per block.
+constexpr int CAND_PART_TILES = 2;
 __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict__ wtable,
                                                      const uint8_t *__restrict__ tileflag, int64_t n_words,
                                                      int64_t n_nodes, int64_t n_tiles, int32_t lo, int32_t hi,
@@ -333,47 +336,61 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
                                                      unsigned long long *__restrict__ partial,
                                                      uint64_t *__restrict__ gtot, int32_t *__restrict__ status, InstStride is)
 {
-    __shared__ uint64_t lds[4][3];
+    constexpr int TPB = CAND_PART_TILES, W = CAND_WORDS / 4;   // tiles per block, words per wavefront and tile
+    __shared__ uint64_t lds[TPB][4][3];
     wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); epoch = inst_ptr(epoch, is.ws);
     cand_flag = inst_ptr(cand_flag, is.ws); partial = inst_ptr(partial, is.ws); gtot = inst_ptr(gtot, is.ws);
     status = inst_ptr(status, is.buf);
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    const int64_t t = blockIdx.x;
+    const int64_t t0 = (int64_t)blockIdx.x * TPB;
     const unsigned long long tag = call_tag(call_number(epoch), SLOT_CAND);
-    uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
-    // First the flags of all the wavefront's words, then all its pieces of the table: two load latencies.
-    // (Word by word, with the next word's flags asked for only after this word's pieces have arrived, it
-    // was eight in a row.)
-    uint64_t f8[CAND_WORDS / 4], w[CAND_WORDS / 4];
+    uint64_t f8[TPB][W], w[TPB][W];
 #pragma unroll
-    for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t word_idx = t * CAND_WORDS + wave * (CAND_WORDS / 4) + k;
-        f8[k] = word_idx < n_words ? reinterpret_cast<const uint64_t *>(tileflag)[word_idx] : 0ull;   // the word's eight group flags
-    }
+    for (int h = 0; h < TPB; ++h)
 #pragma unroll
-    for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
-        // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
-        w[k] = (((f8[k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
-    }
-#pragma unroll
-    for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
-        if (w[k]) {
-            const bool local = id >= lo && id < hi;
-            cn += (1ull << 32) | (local ? 1ull : 0ull);
-            if (local) wl += w[k]; else wr += w[k];
+        for (int k = 0; k < W; ++k) {
+            const int64_t word_idx = (t0 + h) * CAND_WORDS + wave * W + k;
+            f8[h][k] = word_idx < n_words ? reinterpret_cast<const uint64_t *>(tileflag)[word_idx] : 0ull;   // the word's eight group flags
         }
+#pragma unroll
+    for (int h = 0; h < TPB; ++h)
+#pragma unroll
+        for (int k = 0; k < W; ++k) {
+            const int64_t id = ((t0 + h) * CAND_WORDS + wave * W + k) * 64 + lane;
+            // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
+            w[h][k] = (((f8[h][k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
+        }
+#pragma unroll
+    for (int h = 0; h < TPB; ++h) {
+        uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
+#pragma unroll
+        for (int k = 0; k < W; ++k) {
+            const int64_t id = ((t0 + h) * CAND_WORDS + wave * W + k) * 64 + lane;
+            if (w[h][k]) {
+                const bool local = id >= lo && id < hi;
+                cn += (1ull << 32) | (local ? 1ull : 0ull);
+                if (local) wl += w[h][k]; else wr += w[h][k];
+            }
+        }
+        cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
+        if (lane == 0) { lds[h][wave][0] = cn; lds[h][wave][1] = wl; lds[h][wave][2] = wr; }
     }
-    cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
-    if (lane == 0) { lds[wave][0] = cn; lds[wave][1] = wl; lds[wave][2] = wr; }
     __syncthreads();
     if (wave != 0) return;
     // packed count halves cannot carry: each is at most 1024 per tile
-    const unsigned long long mine = lane < 3 ? lds[0][lane] + lds[1][lane] + lds[2][lane] + lds[3][lane] : 0ull;
-    if (lane < 3) st_relaxed(&partial[t * 4 + lane], mine);
-    if (lane == 0) st_flag(&cand_flag[t], tag);   // after the wavefront's value stores have been acknowledged
+    unsigned long long mine = 0ull;   // of the block's last tile
+    int64_t t = t0;
+#pragma unroll
+    for (int h = 0; h < TPB; ++h) {
+        if (t0 + h >= n_tiles) break;
+        t = t0 + h;
+        mine = lane < 3 ? lds[h][0][lane] + lds[h][1][lane] + lds[h][2][lane] + lds[h][3][lane] : 0ull;
+        if (lane < 3) st_relaxed(&partial[t * 4 + lane], mine);
+        if (lane == 0) st_flag(&cand_flag[t], tag);   // after the wavefront's value stores have been acknowledged
+    }
+    // the last tile of a group (and the last tile of all) is odd-numbered or the last: always a block's last tile
+    static_assert(LB_GROUP % CAND_PART_TILES == 0, "a group's last tile must be a block's last tile");
     const int r = (int)(t % LB_GROUP);
     if (r != LB_GROUP - 1 && t != n_tiles - 1) return;
     const int64_t g = t / LB_GROUP;
@@ -675,7 +692,7 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
                 g->n_nodes, g->nnz, shift_base, rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable,
                 w.tileflag, rows.chunk_note, status, w.epoch, stg, is);
     CSGS_LAUNCH_CHECK();
-    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)w.n_tiles, 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
+    CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)((w.n_tiles + CAND_PART_TILES - 1) / CAND_PART_TILES), 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,
                 (unsigned long long *)w.partial, w.gtot, status, is);
     CSGS_LAUNCH_CHECK();
