@@ -469,8 +469,12 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
             if (j < g) pre[i] += v;
         }
     }
+    // group j's sums are held by thread j and the in-group tile sums by the first 64 threads: with fewer
+    // than 64 groups only the first wavefront has anything to add up (the others hold zeros)
+    if ((int64_t)wave * WAVE < n_groups) {
 #pragma unroll
-    for (int i = 0; i < 3; ++i) { tot[i] = wave_sum(tot[i]); pre[i] = wave_sum(pre[i]); }
+        for (int i = 0; i < 3; ++i) { tot[i] = wave_sum(tot[i]); pre[i] = wave_sum(pre[i]); }
+    }
     if (lane == 0) {
 #pragma unroll
         for (int i = 0; i < 3; ++i) { s_red[wave][i] = tot[i]; s_red[wave][3 + i] = pre[i]; }
