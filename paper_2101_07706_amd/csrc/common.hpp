@@ -251,9 +251,42 @@ __device__ inline T dpp_move_t(T v)
     return (T)(((uint64_t)hi << 32) | lo);
 }
 
+// One step of the scan on a 64-bit value held as two halves: v += (v moved by the step's pattern), as an
+// add with carry whose first operand comes through the DPP path -- two instructions, where a moved copy
+// (two moves, each with its zero fill) and a 64-bit add take five.  Lanes the pattern leaves out are not
+// written and keep v, which is what adding the zero fill gave.  The carry travels in VCC.  A DPP read of a
+// register needs two wait states after the vector instruction that wrote it; inside an asm statement the
+// compiler does not count them, hence the s_nop in front.
+#define CSGS_SCAN_STEP64(lo, hi, PATTERN)                                                      \
+    asm volatile("s_nop 1\n\t"                                                                 \
+                 "v_add_co_u32_dpp %0, vcc, %0, %0 " PATTERN "\n\t"                              \
+                 "v_addc_co_u32_dpp %1, vcc, %1, %1, vcc " PATTERN                               \
+                 : "+v"(lo), "+v"(hi)                                                          \
+                 :                                                                             \
+                 : "vcc")
+template <int STEP>
+__device__ inline void scan_step64(uint32_t &lo, uint32_t &hi)
+{
+    if (STEP == 0) CSGS_SCAN_STEP64(lo, hi, "row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1");
+    if (STEP == 1) CSGS_SCAN_STEP64(lo, hi, "row_shr:2 row_mask:0xf bank_mask:0xf bound_ctrl:1");
+    if (STEP == 2) CSGS_SCAN_STEP64(lo, hi, "row_shr:4 row_mask:0xf bank_mask:0xf bound_ctrl:1");
+    if (STEP == 3) CSGS_SCAN_STEP64(lo, hi, "row_shr:8 row_mask:0xf bank_mask:0xf bound_ctrl:1");
+    if (STEP == 4) CSGS_SCAN_STEP64(lo, hi, "row_bcast:15 row_mask:0xa bank_mask:0xf");
+    if (STEP == 5) CSGS_SCAN_STEP64(lo, hi, "row_bcast:31 row_mask:0xc bank_mask:0xf");
+}
+
+__device__ inline uint64_t wave_inclusive_scan64(uint64_t v)
+{
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    scan_step64<0>(lo, hi); scan_step64<1>(lo, hi); scan_step64<2>(lo, hi);
+    scan_step64<3>(lo, hi); scan_step64<4>(lo, hi); scan_step64<5>(lo, hi);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 template <typename T>
 __device__ inline T wave_inclusive_scan(T v)
 {
+    if (sizeof(T) == 8) return (T)wave_inclusive_scan64((uint64_t)v);
     v += dpp_move_t<T, 0x111, 0xF>(v);  // row_shr:1
     v += dpp_move_t<T, 0x112, 0xF>(v);  // row_shr:2
     v += dpp_move_t<T, 0x114, 0xF>(v);  // row_shr:4
@@ -280,6 +313,26 @@ __device__ inline T wave_sum(T v)
 template <typename T, int K>
 __device__ inline void wave_inclusive_scan_multi(T (&v)[K])
 {
+    if (sizeof(T) == 8) {
+        uint32_t lo[K], hi[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) { lo[k] = (uint32_t)(uint64_t)v[k]; hi[k] = (uint32_t)((uint64_t)v[k] >> 32); }
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<0>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<1>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<2>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<3>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<4>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) scan_step64<5>(lo[k], hi[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] = (T)(((uint64_t)hi[k] << 32) | lo[k]);
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < K; ++k) v[k] += dpp_move_t<T, 0x111, 0xF>(v[k]);
 #pragma unroll
