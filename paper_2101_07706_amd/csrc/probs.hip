@@ -357,18 +357,18 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
     for (int h = 0; h < TPB; ++h)
 #pragma unroll
         for (int k = 0; k < W; ++k) {
-            const int64_t id = ((t0 + h) * CAND_WORDS + wave * W + k) * 64 + lane;
+            const uint32_t id = ((uint32_t)(t0 + h) * CAND_WORDS + wave * W + k) * 64u + lane;   // below 2^31 + 1024
             // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
-            w[h][k] = (((f8[h][k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
+            w[h][k] = (((f8[h][k] >> (8 * (lane >> 3))) & 0xFFull) && id < (uint32_t)n_nodes) ? wtable[id] : 0ull;
         }
 #pragma unroll
     for (int h = 0; h < TPB; ++h) {
         uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
 #pragma unroll
         for (int k = 0; k < W; ++k) {
-            const int64_t id = ((t0 + h) * CAND_WORDS + wave * W + k) * 64 + lane;
+            const uint32_t id = ((uint32_t)(t0 + h) * CAND_WORDS + wave * W + k) * 64u + lane;
             if (w[h][k]) {
-                const bool local = id >= lo && id < hi;
+                const bool local = id >= (lo > 0 ? (uint32_t)lo : 0u) && id < (hi > 0 ? (uint32_t)hi : 0u);
                 cn += (1ull << 32) | (local ? 1ull : 0ull);
                 if (local) wl += w[h][k]; else wr += w[h][k];
             }
@@ -452,8 +452,9 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     uint64_t w[CAND_WORDS / 4];
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
-        w[k] = (((flagged[k] >> (8 * (lane >> 3))) & 0xFFull) && id < n_nodes) ? wtable[id] : 0ull;
+        // node ids are below 2^31 and a tile adds at most 1023: 32-bit arithmetic, half the instructions
+        const uint32_t id = ((uint32_t)t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64u + lane;
+        w[k] = (((flagged[k] >> (8 * (lane >> 3))) & 0xFFull) && id < (uint32_t)n_nodes) ? wtable[id] : 0ull;
     }
     uint64_t tot[3], pre[3];
 #pragma unroll
@@ -491,12 +492,14 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     const uint64_t total_w = tot[1] * m_local + tot[2] * m_remote;
     const double total_d = (double)total_w;
 
-    uint64_t words[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
+    uint64_t words[CAND_WORDS / 4], wsk[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
+    const uint32_t lo_u = lo > 0 ? (uint32_t)lo : 0u, hi_u = hi > 0 ? (uint32_t)hi : 0u;
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int64_t id = (t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64 + lane;
-        const bool local = id >= lo && id < hi;
-        wsk_incl[k] = w[k] * (local ? m_local : m_remote);
+        const uint32_t id = ((uint32_t)t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64u + lane;
+        const bool local = id >= lo_u && id < hi_u;
+        wsk[k] = w[k] * (local ? m_local : m_remote);
+        wsk_incl[k] = wsk[k];
         words[k] = __ballot(w[k] != 0);
     }
     wave_inclusive_scan_multi(wsk_incl);
@@ -513,20 +516,18 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int slot = wave * (CAND_WORDS / 4) + k;
-        const int64_t word_idx = t * CAND_WORDS + slot;
         const uint64_t word = words[k];
         if (word) {
-            const int64_t id = word_idx * 64 + lane;
+            const uint32_t id = ((uint32_t)t * CAND_WORDS + slot) * 64u + lane;
             const bool set = (word >> lane) & 1ull;
             const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
             if (set) {
                 wtable[id] = 0ull;  // back to the clean state
                 if (pos < cap) {
-                    const bool local = id >= lo && id < hi;
                     cand_id[pos] = (int32_t)id;
                     cand_w[pos] = w[k];
                     cdf[pos] = base_w + wsk_incl[k];
-                    if (q) q[pos] = (float)((double)(w[k] * (local ? m_local : m_remote)) / total_d);
+                    if (q) q[pos] = (float)((double)wsk[k] / total_d);
                 }
             }
         }
