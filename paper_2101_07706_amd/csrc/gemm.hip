@@ -149,7 +149,7 @@ __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 
 // are three chunks and four k).  They are loaded once, before the first barrier, into the four padding
 // words of the rows of the LDS buffer that will hold the last chunk, and take one MFMA step after it,
 // in which lane group g feeds k = 32 n + g.
-template <int BN, int MODE, int V, bool FULL, bool TAIL = false>
+template <int BN, int MODE, int V, bool FULL, bool TAIL = false, int BM_ = 128>
 __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, double *__restrict__ partial, int M_bound, int N,
@@ -157,9 +157,11 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
                                                   int n_tiles, int k_split, CompStride cs)
 {
     A = inst_ptr(A, cs.x); C = inst_ptr(C, cs.out); rows_dev = inst_ptr(rows_dev, cs.adj);   // B (the weights) is shared
-    constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront (times 2 row tiles)
+    constexpr int NT = BN / 16;   // 16-column MFMA tiles per wavefront
+    constexpr int RT = BM_ / 64;  // 16-row MFMA tiles per wavefront: the four wavefronts are stacked along M
+    static_assert(BM_ == 128 || BM_ == 64, "block tiles of 128 or 64 rows");
     constexpr bool A_KMAJOR = MODE != MODE_DW, B_KMAJOR = MODE == MODE_DZ;
-    __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) float As[2][BM_ * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDS_STRIDE];
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     const int per_xcd = (n_tiles + 7) / 8;
     const int tile = (bid & 7) * per_xcd + (bid >> 3);
     if (tile >= n_tiles) return;
-    const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM, n0 = (int64_t)(tile % n_tiles_n) * BN;
+    const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM_, n0 = (int64_t)(tile % n_tiles_n) * BN;
     // the row count of the sampled layer may live on the device: it bounds M, or K for dW.  As a bound
     // of M it is only needed once the first chunk's loads are on their way (see below)
     const int m_dev = (MODE != MODE_DW && rows_dev) ? *rows_dev : M_bound;
@@ -179,27 +181,27 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     static_assert(!TAIL || (MODE == MODE_FWD && !FULL), "the folded tail is for ragged forward products");
     const int n_chunks = TAIL ? (k_end - k_begin) / BK : (k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0);
 
-    doublex4 acc[2][NT];
+    doublex4 acc[RT][NT];
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = doublex4{0.0, 0.0, 0.0, 0.0};
-    float4 ra[BM / 32], rb[BN / 32];
+    float4 ra[BM_ / 32], rb[BN / 32];
     uint32_t oka = 0, okb = 0;
     // Rows of A up to M_bound are the caller's memory whatever the device count says, and a row of A
     // only reaches its own row of C, which is not stored beyond the count: so the count never masks a
     // load, and the first chunk's loads need not wait for it.
-    const bool a_whole = m0 + BM <= M_bound, b_whole = n0 + BN <= N;
+    const bool a_whole = m0 + BM_ <= M_bound, b_whole = n0 + BN <= N;
     bool k_whole = false;   // of the chunk in the registers
     auto fetch = [&](int k0) {
         k_whole = k0 + BK <= k_end;
-        if (A_KMAJOR) fetch_kmajor<BM, V, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
-        else fetch_rmajor<BM, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
+        if (A_KMAJOR) fetch_kmajor<BM_, V, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
+        else fetch_rmajor<BM_, FULL>(A, lda, M_bound, k_end, m0, k0, tid, ra, oka);
         if (B_KMAJOR) fetch_kmajor<BN, V, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb, okb);
         else fetch_rmajor<BN, FULL>(Bm, ldb, N, k_end, n0, k0, tid, rb, okb);
     };
     auto stash = [&](int buf) {
-        stash_tile<BM, A_KMAJOR, FULL>(As[buf], tid, ra, oka, a_whole && k_whole);
+        stash_tile<BM_, A_KMAJOR, FULL>(As[buf], tid, ra, oka, a_whole && k_whole);
         stash_tile<BN, B_KMAJOR, FULL>(Bs[buf], tid, rb, okb, b_whole && k_whole);
     };
     if (n_chunks > 0) fetch(k_begin);
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     if (n_chunks > 0) stash(0);
     if (TAIL) {
         const int kt = k_begin + n_chunks * BK, tail = k_end - kt, last = (n_chunks - 1) & 1;
-        {   // A: 128 rows x 4 k, two floats per thread
+        if (tid < BM_ * 2) {   // A: BM_ rows x 4 k, two floats per thread
             const int r = tid >> 1, j0 = (tid & 1) * 2;
             const int64_t gr = m0 + r;
             const float *row = A + (gr < M_bound ? gr : (int64_t)M_bound - 1) * lda;
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
         }
     }
     __syncthreads();
-    const int a_off = (wave * 32 + l16) * LDS_STRIDE + 8 * grp;
+    const int a_off = (wave * (BM_ / 4) + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
     // 16-column MFMA tiles of this block that hold any real column (47 output classes fill 3 of 4), and
     // k steps of the last chunk that hold any real k (lane group g feeds k = 8 g + s at step s, so with
@@ -237,9 +239,9 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     for (int c = 0; c < n_chunks; ++c) {
         const int cur = c & 1;
         if (c + 1 < n_chunks) fetch(k_begin + (c + 1) * BK);
-        float av[2][8], bv[NT][8];
+        float av[RT][8], bv[NT][8];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < RT; ++r) {
             const float *ap = &As[cur][a_off + r * 16 * LDS_STRIDE];
             const float4 x = *reinterpret_cast<const float4 *>(ap), y = *reinterpret_cast<const float4 *>(ap + 4);
             av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
@@ -256,13 +258,15 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             if (s < s_end) {
-                const double a0 = (double)av[0][s], a1 = (double)av[1][s];
+                double a[RT];
+#pragma unroll
+                for (int r = 0; r < RT; ++r) a[r] = (double)av[r][s];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     if (t < nt_valid) {
                         const double b = (double)bv[t][s];
-                        acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
-                        acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) acc[r][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[r][t], 0, 0, 0);
                     }
                 }
             }
@@ -274,14 +278,15 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     }
     if (TAIL) {
         const int last = (n_chunks - 1) & 1;
-        const double a0 = (double)As[last][(wave * 32 + l16) * LDS_STRIDE + BK + grp];
-        const double a1 = (double)As[last][(wave * 32 + 16 + l16) * LDS_STRIDE + BK + grp];
+        double a[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) a[r] = (double)As[last][(wave * (BM_ / 4) + r * 16 + l16) * LDS_STRIDE + BK + grp];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if (t < nt_valid) {
                 const double b = (double)Bs[last][(t * 16 + l16) * LDS_STRIDE + BK + grp];
-                acc[0][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][t], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < RT; ++r) acc[r][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[r][t], 0, 0, 0);
             }
         }
     }
@@ -289,10 +294,10 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     auto store = [&](auto whole) {
         constexpr bool WHOLE = decltype(whole)::value;
 #pragma unroll
-        for (int r = 0; r < 2; ++r)
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int64_t row = m0 + wave * 32 + r * 16 + grp + 4 * i;
+                const int64_t row = m0 + wave * (BM_ / 4) + r * 16 + grp + 4 * i;
                 if (WHOLE || row < M) {
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
@@ -307,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
                 }
             }
     };
-    if (m0 + BM <= M && (FULL || n0 + BN <= N)) store(std::true_type{});
+    if (m0 + BM_ <= M && (FULL || n0 + BN <= N)) store(std::true_type{});
     else store(std::false_type{});
 }
 
@@ -338,31 +343,27 @@ static int widest(const float *p, int64_t ld, int k)
     return 1;
 }
 
-template <int BN>
+template <int BMF, int BN>
 static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev, int K, const float *W, int64_t ldw, int N, float *H,
                        int64_t ldh, hipStream_t st, const CompInst &ci)
 {
-    const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    const int tm = (M + BMF - 1) / BMF, tn = (N + BN - 1) / BN;
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), 1, (unsigned)ci.n);
     const int va = widest(Z, ldz, K);
-    const bool full = M % BM == 0 && N % BN == 0 && K % BK == 0 && va == 4;   // of the bounds: a device count only gates the stores
+    const bool full = M % BMF == 0 && N % BN == 0 && K % BK == 0 && va == 4;   // of the bounds: a device count only gates the stores
     double *none = nullptr;
     const bool fold = K > BK && K % BK >= 1 && K % BK <= 4;   // see TAIL
-    if (full)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else if (fold && va == 4)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else if (fold && va == 2)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else if (fold)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false, true>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else if (va == 4)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 4, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else if (va == 2)
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 2, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
-    else
-        CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, 1, false>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs);
+#define CSGS_GEMM_FWD(V, FULL, TAIL) \
+    CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, V, FULL, TAIL, BMF>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs)
+    if (full) CSGS_GEMM_FWD(4, true, false);
+    else if (fold && va == 4) CSGS_GEMM_FWD(4, false, true);
+    else if (fold && va == 2) CSGS_GEMM_FWD(2, false, true);
+    else if (fold) CSGS_GEMM_FWD(1, false, true);
+    else if (va == 4) CSGS_GEMM_FWD(4, false, false);
+    else if (va == 2) CSGS_GEMM_FWD(2, false, false);
+    else CSGS_GEMM_FWD(1, false, false);
+#undef CSGS_GEMM_FWD
 }
 
 template <int BN>
@@ -414,12 +415,17 @@ extern "C" int csgs_layer_gemm_n(const csgs_inst_strides *inst, const float *Z, 
     const int64_t tm = ((int64_t)M + BM - 1) / BM;
     if (tm * (((int64_t)Nout + 31) / 32) > 0x3FFFFFFF) return CSGS_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
-    // narrow column tiles when wide ones would leave fewer than two blocks per compute unit
+    // Tiles of 128 x 64 where they give at least four blocks per compute unit; else 64 rows (a tile's
+    // prologue and epilogue then overlap with the MFMAs of three other blocks instead of one); narrow
+    // column tiles when even those would leave fewer than two blocks per compute unit
     const int64_t wide_tiles = tm * (((int64_t)Nout + 63) / 64);
-    if (wide_tiles * ci.n >= 512 && Nout > 32)
-        launch_fwd<64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
+    const int64_t tm64 = ((int64_t)M + 63) / 64;
+    if (wide_tiles * ci.n >= 1024 && Nout > 32)
+        launch_fwd<128, 64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
+    else if (tm64 * (((int64_t)Nout + 63) / 64) * ci.n >= 512 && Nout > 32)
+        launch_fwd<64, 64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
     else
-        launch_fwd<32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
+        launch_fwd<64, 32>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
