@@ -415,12 +415,13 @@ extern "C" int csgs_layer_gemm_n(const csgs_inst_strides *inst, const float *Z, 
     const int64_t tm = ((int64_t)M + BM - 1) / BM;
     if (tm * (((int64_t)Nout + 31) / 32) > 0x3FFFFFFF) return CSGS_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
-    // Tiles of 128 x 64 where they give at least four blocks per compute unit; else 64 rows (a tile's
-    // prologue and epilogue then overlap with the MFMAs of three other blocks instead of one); narrow
-    // column tiles when even those would leave fewer than two blocks per compute unit
+    // Tiles of 128 x 64 where they give at least two blocks per compute unit; else 64 rows (twice the
+    // blocks: 18 against 20 us per launch for one mini-batch of the named configuration; with 512 tiles
+    // of 128 rows, the narrow output layer of 8 mini-batches, 64-row tiles are 2 us slower); narrow column
+    // tiles when even those would leave fewer than two blocks per compute unit
     const int64_t wide_tiles = tm * (((int64_t)Nout + 63) / 64);
     const int64_t tm64 = ((int64_t)M + 63) / 64;
-    if (wide_tiles * ci.n >= 1024 && Nout > 32)
+    if (wide_tiles * ci.n >= 512 && Nout > 32)
         launch_fwd<128, 64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
     else if (tm64 * (((int64_t)Nout + 63) / 64) * ci.n >= 512 && Nout > 32)
         launch_fwd<64, 64>(Z, ldz, M, M_dev, K, W, ldw, Nout, H, ldh, st, ci);
