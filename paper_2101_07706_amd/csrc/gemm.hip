@@ -125,7 +125,9 @@ __device__ inline void fetch_rmajor(const float *__restrict__ P, int64_t ld, int
 
 // Registers -> LDS tile [ROWS][LDS_STRIDE], with the (r, k) of each group as the fetch above had it;
 // values whose bit in `ok` is clear become zeros.
-template <int ROWS, bool KMAJOR, bool FULL>
+// SWZ: rows of 32 words without padding; the 16-byte column c of row r sits at column c ^ ((r >> 1) & 7), which
+// spreads 16 consecutive rows' reads of one column over all banks as the padding does, in 8/9 of the space.
+template <int ROWS, bool KMAJOR, bool FULL, bool SWZ = false>
 __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 32], uint32_t ok, bool whole)
 {
 #pragma unroll
@@ -140,7 +142,8 @@ __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 
             v.z = (ok >> (4 * i + 2)) & 1u ? v.z : 0.f;
             v.w = (ok >> (4 * i + 3)) & 1u ? v.w : 0.f;
         }
-        *reinterpret_cast<float4 *>(&S[r * LDS_STRIDE + k]) = v;
+        if (SWZ) *reinterpret_cast<float4 *>(&S[r * BK + (((k >> 2) ^ ((r >> 1) & 7)) << 2)]) = v;
+        else *reinterpret_cast<float4 *>(&S[r * LDS_STRIDE + k]) = v;
     }
 }
 
@@ -150,7 +153,7 @@ __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 
 // words of the rows of the LDS buffer that will hold the last chunk, and take one MFMA step after it,
 // in which lane group g feeds k = 32 n + g.
 template <int BN, int MODE, int V, bool FULL, bool TAIL = false, int BM_ = 128>
-__global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
+__global__ __launch_bounds__(256, 3) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, double *__restrict__ partial, int M_bound, int N,
                                                   int K_bound, const int32_t *__restrict__ rows_dev, int n_tiles_n,
@@ -162,7 +165,13 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     static_assert(BM_ == 128 || BM_ == 64, "block tiles of 128 or 64 rows");
     constexpr bool A_KMAJOR = MODE != MODE_DW, B_KMAJOR = MODE == MODE_DZ;
     __shared__ __attribute__((aligned(16))) float As[2][BM_ * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDS_STRIDE];
+    // The B tile of the forward product's 128 x 64 blocks is swizzled instead of padded: 52-53 KB of LDS per block
+    // instead of 54, which lets a third block onto a compute unit (the launch bound asks the compiler for the
+    // 168 registers that go with it)
+    constexpr bool SWZ = MODE == MODE_FWD && BM_ == 128 && BN == 64;
+    constexpr int B_STRIDE = SWZ ? BK : LDS_STRIDE;
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * B_STRIDE];
+    __shared__ float Bt[(TAIL && SWZ) ? BN * 4 : 1];   // the K tail of B where its rows have no padding
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int grp = lane >> 4, l16 = lane & 15;
@@ -202,7 +211,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
     };
     auto stash = [&](int buf) {
         stash_tile<BM_, A_KMAJOR, FULL>(As[buf], tid, ra, oka, a_whole && k_whole);
-        stash_tile<BN, B_KMAJOR, FULL>(Bs[buf], tid, rb, okb, b_whole && k_whole);
+        stash_tile<BN, B_KMAJOR, FULL, SWZ>(Bs[buf], tid, rb, okb, b_whole && k_whole);
     };
     if (n_chunks > 0) fetch(k_begin);
     const int M = m_dev < 0 ? 0 : (m_dev < M_bound ? m_dev : M_bound);
@@ -224,12 +233,14 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
             const int n = tid % BN, j = tid / BN;
             const int64_t gn = n0 + n;
             const float v = Bm[(int64_t)(j < tail ? kt + j : k_end - 1) * ldb + (gn < N ? gn : (int64_t)N - 1)];
-            Bs[last][n * LDS_STRIDE + BK + j] = (gn < N && j < tail) ? v : 0.f;
+            if (SWZ) Bt[n * 4 + j] = (gn < N && j < tail) ? v : 0.f;
+            else Bs[last][n * LDS_STRIDE + BK + j] = (gn < N && j < tail) ? v : 0.f;
         }
     }
     __syncthreads();
     const int a_off = (wave * (BM_ / 4) + l16) * LDS_STRIDE + 8 * grp;
     const int b_off = l16 * LDS_STRIDE + 8 * grp;
+    const int bx_off = l16 * BK + (((2 * grp) ^ ((l16 >> 1) & 7)) << 2), by_off = l16 * BK + (((2 * grp + 1) ^ ((l16 >> 1) & 7)) << 2);
     // 16-column MFMA tiles of this block that hold any real column (47 output classes fill 3 of 4), and
     // k steps of the last chunk that hold any real k (lane group g feeds k = 8 g + s at step s, so with
     // k_left <= 8 only the first k_left steps of group 0 are not padding): the rest would multiply zeros
@@ -249,8 +260,15 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const float *bp = &Bs[cur][b_off + t * 16 * LDS_STRIDE];
-            const float4 x = *reinterpret_cast<const float4 *>(bp), y = *reinterpret_cast<const float4 *>(bp + 4);
+            float4 x, y;
+            if (SWZ) {   // row 16 t + l16: its swizzle (row >> 1) & 7 does not depend on t
+                x = *reinterpret_cast<const float4 *>(&Bs[cur][bx_off + t * 16 * BK]);
+                y = *reinterpret_cast<const float4 *>(&Bs[cur][by_off + t * 16 * BK]);
+            } else {
+                const float *bp = &Bs[cur][b_off + t * 16 * LDS_STRIDE];
+                x = *reinterpret_cast<const float4 *>(bp);
+                y = *reinterpret_cast<const float4 *>(bp + 4);
+            }
             bv[t][0] = x.x; bv[t][1] = x.y; bv[t][2] = x.z; bv[t][3] = x.w;
             bv[t][4] = y.x; bv[t][5] = y.y; bv[t][6] = y.z; bv[t][7] = y.w;
         }
@@ -284,7 +302,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const float *__restrict__ A, i
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if (t < nt_valid) {
-                const double b = (double)Bs[last][(t * 16 + l16) * LDS_STRIDE + BK + grp];
+                const double b = (double)(SWZ ? Bt[(t * 16 + l16) * 4 + grp] : Bs[last][(t * 16 + l16) * LDS_STRIDE + BK + grp]);
 #pragma unroll
                 for (int r = 0; r < RT; ++r) acc[r][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[r][t], 0, 0, 0);
             }
