@@ -178,7 +178,9 @@ __global__ __launch_bounds__(256, 3) void gemm_f32_k(const float *__restrict__ A
     // XCD-aware tile order: hardware deals consecutive block ids round-robin to the 8 XCDs
     const int bid = (int)blockIdx.x;
     const int per_xcd = (n_tiles + 7) / 8;
-    const int tile = (bid & 7) * per_xcd + (bid >> 3);
+    // (rotated by the instance: the row tiles beyond a mini-batch's row count are the last ones, and with the
+    // same order for every instance they would all fall to the same XCD, which then idles)
+    const int tile = (((bid & 7) + (int)blockIdx.z) & 7) * per_xcd + (bid >> 3);
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / n_tiles_n) * BM_, n0 = (int64_t)(tile % n_tiles_n) * BN;
     // the row count of the sampled layer may live on the device: it bounds M, or K for dW.  As a bound
