@@ -216,27 +216,34 @@ __global__ __launch_bounds__(256, 3) void gemm_f32_k(const float *__restrict__ A
         stash_tile<BN, B_KMAJOR, FULL, SWZ>(Bs[buf], tid, rb, okb, b_whole && k_whole);
     };
     if (n_chunks > 0) fetch(k_begin);
+    // the K tail's loads travel with the first chunk's (unconditional, clamped addresses; threads beyond the
+    // tail's extent read a stand-in and store nothing): one load latency before the first barrier, not two
+    float ta0 = 0.f, ta1 = 0.f, tb = 0.f;
+    const int kt = k_begin + n_chunks * BK, tail = k_end - kt;
+    const int tr = (tid >> 1) < BM_ ? (tid >> 1) : BM_ - 1, tj0 = (tid & 1) * 2;   // A: BM_ rows x 4 k, two floats per thread
+    const int tn = tid % BN, tj = (tid / BN) & 3;                                  // B: 4 k x BN columns, one float per thread
+    if (TAIL) {
+        const int64_t gr = m0 + tr;
+        const float *row = A + (gr < M_bound ? gr : (int64_t)M_bound - 1) * lda;
+        ta0 = row[tj0 < tail ? kt + tj0 : k_end - 1];
+        ta1 = row[tj0 + 1 < tail ? kt + tj0 + 1 : k_end - 1];
+        const int64_t gn = n0 + tn;
+        tb = Bm[(int64_t)(tj < tail ? kt + tj : k_end - 1) * ldb + (gn < N ? gn : (int64_t)N - 1)];
+    }
     const int M = m_dev < 0 ? 0 : (m_dev < M_bound ? m_dev : M_bound);
     if (m0 >= M) return;  // the whole block leaves together, before any barrier
     if (n_chunks > 0) stash(0);
     if (TAIL) {
-        const int kt = k_begin + n_chunks * BK, tail = k_end - kt, last = (n_chunks - 1) & 1;
-        if (tid < BM_ * 2) {   // A: BM_ rows x 4 k, two floats per thread
-            const int r = tid >> 1, j0 = (tid & 1) * 2;
-            const int64_t gr = m0 + r;
-            const float *row = A + (gr < M_bound ? gr : (int64_t)M_bound - 1) * lda;
-#pragma unroll
-            for (int j = j0; j < j0 + 2; ++j) {
-                const float v = row[j < tail ? kt + j : k_end - 1];
-                As[last][r * LDS_STRIDE + BK + j] = (gr < M_bound && j < tail) ? v : 0.f;
-            }
+        const int last = (n_chunks - 1) & 1;
+        if (tid < BM_ * 2) {
+            const bool row_ok = m0 + tr < M_bound;
+            As[last][tr * LDS_STRIDE + BK + tj0] = (row_ok && tj0 < tail) ? ta0 : 0.f;
+            As[last][tr * LDS_STRIDE + BK + tj0 + 1] = (row_ok && tj0 + 1 < tail) ? ta1 : 0.f;
         }
-        if (tid < BN * 4) {   // B: 4 k x BN columns, one float per thread
-            const int n = tid % BN, j = tid / BN;
-            const int64_t gn = n0 + n;
-            const float v = Bm[(int64_t)(j < tail ? kt + j : k_end - 1) * ldb + (gn < N ? gn : (int64_t)N - 1)];
-            if (SWZ) Bt[n * 4 + j] = (gn < N && j < tail) ? v : 0.f;
-            else Bs[last][n * LDS_STRIDE + BK + j] = (gn < N && j < tail) ? v : 0.f;
+        if (tid < BN * 4) {
+            const bool ok = n0 + tn < N && tj < tail;
+            if (SWZ) Bt[tn * 4 + tj] = ok ? tb : 0.f;
+            else Bs[last][tn * LDS_STRIDE + BK + tj] = ok ? tb : 0.f;
         }
     }
     __syncthreads();
