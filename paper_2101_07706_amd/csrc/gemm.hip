@@ -189,7 +189,7 @@ __global__ __launch_bounds__(256, 3) void gemm_f32_k(const float *__restrict__ A
     const int K = MODE == MODE_DW ? resolve_count(K_bound, rows_dev) : K_bound;
     const int k_begin = MODE == MODE_DW ? (int)blockIdx.y * k_split : 0;
     const int k_end = MODE == MODE_DW ? (k_begin + k_split < K ? k_begin + k_split : K) : K;
-    static_assert(!TAIL || (MODE == MODE_FWD && !FULL), "the folded tail is for ragged forward products");
+    static_assert(!TAIL || MODE == MODE_FWD, "the folded tail is for forward products");
     const int n_chunks = TAIL ? (k_end - k_begin) / BK : (k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0);
 
     doublex4 acc[RT][NT];
@@ -378,12 +378,14 @@ static void launch_fwd(const float *Z, int64_t ldz, int M, const int32_t *M_dev,
     const int n_tiles = tm * tn;
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), 1, (unsigned)ci.n);
     const int va = widest(Z, ldz, K);
-    const bool full = M % BMF == 0 && N % BN == 0 && K % BK == 0 && va == 4;   // of the bounds: a device count only gates the stores
-    double *none = nullptr;
     const bool fold = K > BK && K % BK >= 1 && K % BK <= 4;   // see TAIL
+    // regular shape (of the bounds: a device count only gates the stores); a folded tail leaves whole chunks
+    const bool full = M % BMF == 0 && N % BN == 0 && (K % BK == 0 || fold) && va == 4;
+    double *none = nullptr;
 #define CSGS_GEMM_FWD(V, FULL, TAIL) \
     CSGS_LAUNCH(K_GEMM, (gemm_f32_k<BN, MODE_FWD, V, FULL, TAIL, BMF>), grid, dim3(256), st, Z, ldz, W, ldw, H, ldh, none, M, N, K, M_dev, tn, n_tiles, 0, ci.cs)
-    if (full) CSGS_GEMM_FWD(4, true, false);
+    if (full && fold) CSGS_GEMM_FWD(4, true, true);
+    else if (full) CSGS_GEMM_FWD(4, true, false);
     else if (fold && va == 4) CSGS_GEMM_FWD(4, false, true);
     else if (fold && va == 2) CSGS_GEMM_FWD(2, false, true);
     else if (fold) CSGS_GEMM_FWD(1, false, true);
