@@ -8,12 +8,17 @@
 // double, and v_mfma_f64_16x16x4_f64 accumulates in double, so the only rounding is the final
 // conversion to float.
 //
-// Block tile 128 (M) x BN (64 or 32), K chunks of 32, four wavefronts stacked along M, each
-// owning a 32 x BN strip = 2 x BN/16 MFMA tiles of 16 x 16.  Global -> register -> LDS with the
-// next chunk's loads in flight during the current chunk's MFMAs (two LDS buffers).
+// Block tile BM (128, or 64 where that would leave too few blocks) x BN (64 or 32), K chunks of 32,
+// four wavefronts stacked along M, each owning a BM/4 x BN strip = BM/64 x BN/16 MFMA tiles of
+// 16 x 16.  Global -> register -> LDS with the next chunk's loads in flight during the current
+// chunk's MFMAs (two LDS buffers).  Every load of a tile is unconditional (a piece that does not
+// exist reads a clamped address and becomes zero on the way to LDS); a row count that lives on the
+// device gates only the early exit and the stores.
 //
-// LDS layout (fp32): A row-major [128][36], B transposed [BN][36] (k contiguous, 16-byte aligned
-// rows whose stride of 36 words spreads 16 lanes' 128-bit reads over all 64 banks).  The k order
+// LDS layout (fp32): A row-major [BM][36], B transposed [BN][36] (k contiguous, 16-byte aligned
+// rows whose stride of 36 words spreads 16 lanes' 128-bit reads over all 64 banks); in the
+// 128 x 64 blocks of the forward product B has rows of 32 words with the 16-byte columns swizzled
+// instead, which brings a block to 52-53 KB and three blocks onto a compute unit.  The k order
 // inside a chunk is permuted -- the lane group l / 16 = g feeds k = 8 g + s at step s, for both
 // operands alike, which leaves the sum unchanged -- so that every lane fetches the 8 values it
 // needs per operand row with two 128-bit LDS reads.
