@@ -47,6 +47,8 @@ struct RowOffsets {
     int64_t *rowstart;   // [nS + 1] rowptr[S[a]]
     int64_t *meta;       // [META_WORDS] resolved on the device: row count, edge count, true edge count
     int2 *chunk_note;    // [chunk_cap] (first row, rows) of every edge chunk, left by the weight scan for the adjacency pass
+    int2 *bound_note;    // [chunk_cap + 2] for the edge position t * EDGE_TILE: (first row of a chunk that starts there, first row
+                         // whose offset is at or beyond it), left by the row pass for the weight scan
 };
 
 struct Workspace {
@@ -157,6 +159,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
         w.rows[b].rowstart = (int64_t *)take((size_t)(nS_max + 1) * 8);
         w.rows[b].meta = (int64_t *)take(META_WORDS * 8);
         w.rows[b].chunk_note = (int2 *)take((size_t)w.chunk_cap * sizeof(int2));
+        w.rows[b].bound_note = (int2 *)take((size_t)(w.chunk_cap + 2) * sizeof(int2));
     }
     w.pdbl = (double *)take((size_t)B_max * 8);
     w.stage_chunks = w.chunk_cap < STAGE_EDGES_MAX / EDGE_TILE ? w.chunk_cap : STAGE_EDGES_MAX / EDGE_TILE;
@@ -417,6 +420,30 @@ struct RowSlice {
     bool in_lds;                // false: too many (empty) rows for LDS, read eoff / rowstart directly
 };
 
+// Second half of staging a chunk: rows [a_first, a_first + R) into LDS.  Called by all threads.
+__device__ inline void stage_rows(RowSlice &s, const int64_t *__restrict__ eoff, const int64_t *__restrict__ rowstart,
+                                  int32_t nS, int64_t c0, int64_t a_first, int64_t R)
+{
+    // A prefix broken by a failed wait, or a stale note (the caller skipped the scan that writes it),
+    // must not lead outside eoff / rowstart: rows [a_first, a_first + R) stay within [0, nS].
+    if (a_first < 0) a_first = 0;
+    if (a_first > nS) a_first = nS;
+    if (R < 0) R = 0;
+    if (R > (int64_t)nS + 1 - a_first) R = (int64_t)nS + 1 - a_first;
+    if (threadIdx.x == 0) {
+        s.a_first = (int32_t)a_first;
+        s.R = (int32_t)R;
+        s.in_lds = R <= SLICE_MAX;
+    }
+    if (R <= SLICE_MAX) {
+        for (int64_t r = threadIdx.x; r < R; r += blockDim.x) {
+            s.off[r] = (int32_t)(eoff[a_first + r] - c0);
+            s.start[r] = (a_first + r < nS) ? rowstart[a_first + r] : 0;
+        }
+    }
+    __syncthreads();
+}
+
 // Called by all threads of the block (at least two wavefronts).  c0 < c1 <= eoff[nS].
 // `note` (nullable) points at this chunk's entry of the workspace's chunk table: with FROM_NOTE the
 // first row and row count are read from it (one load) instead of being searched for (four dependent
@@ -450,24 +477,35 @@ __device__ inline void stage_slice(RowSlice &s, const int64_t *__restrict__ eoff
         __syncthreads();  // everyone has read the end index before it is replaced by the count
         if (note && threadIdx.x == 0) *note = make_int2((int)a_first, (int)R);
     }
-    // A prefix broken by a failed wait, or a stale note (the caller skipped the scan that writes it),
-    // must not lead outside eoff / rowstart: rows [a_first, a_first + R) stay within [0, nS].
-    if (a_first < 0) a_first = 0;
-    if (a_first > nS) a_first = nS;
-    if (R < 0) R = 0;
-    if (R > (int64_t)nS + 1 - a_first) R = (int64_t)nS + 1 - a_first;
-    if (threadIdx.x == 0) {
-        s.a_first = (int32_t)a_first;
-        s.R = (int32_t)R;
-        s.in_lds = R <= SLICE_MAX;
-    }
-    if (R <= SLICE_MAX) {
-        for (int64_t r = threadIdx.x; r < R; r += blockDim.x) {
-            s.off[r] = (int32_t)(eoff[a_first + r] - c0);
-            s.start[r] = (a_first + r < nS) ? rowstart[a_first + r] : 0;
+    stage_rows(s, eoff, rowstart, nS, c0, a_first, R);
+}
+
+// The same from what the row pass left per chunk boundary (bound[t] belongs to edge position
+// t * EDGE_TILE): chunk t starts at bound[t].x (row 0 for t = 0) and ends before bound[t + 1].y -- two
+// independent loads instead of the searches.  The last chunk, when it ends short of a boundary, still
+// searches for its end.  Leaves (first row, rows) in `note` like the searching form.
+__device__ inline void stage_slice_bounds(RowSlice &s, const int64_t *__restrict__ eoff,
+                                          const int64_t *__restrict__ rowstart, int32_t nS, int64_t t, int64_t c0,
+                                          int64_t c1, const int2 *__restrict__ bound, int2 *note)
+{
+    __syncthreads();  // previous chunk's readers are done
+    const bool ends_on_bound = c1 == c0 + EDGE_TILE;
+    const int64_t a_first = t == 0 ? 0 : (int64_t)bound[t].x;
+    int64_t lb1;
+    if (ends_on_bound) {
+        lb1 = bound[t + 1].y;
+    } else {
+        if (threadIdx.x < WAVE) {
+            const int64_t lb = wave_lower_bound(eoff, (int64_t)nS + 1, c1);
+            if (lane_id() == 0) s.R = (int32_t)lb;
         }
+        __syncthreads();
+        lb1 = s.R;
+        __syncthreads();  // everyone has read the end index before it is replaced by the count
     }
-    __syncthreads();
+    const int64_t R = lb1 - a_first;
+    if (note && threadIdx.x == 0) *note = make_int2((int)a_first, (int)R);
+    stage_rows(s, eoff, rowstart, nS, c0, a_first, R);
 }
 
 // CSR position of chunk-relative edge x (0 <= x < c1 - c0); *r_out = staged row index.

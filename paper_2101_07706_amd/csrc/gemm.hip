@@ -158,7 +158,7 @@ __device__ inline void stash_tile(float *S, int tid, const float4 (&reg)[ROWS / 
 // words of the rows of the LDS buffer that will hold the last chunk, and take one MFMA step after it,
 // in which lane group g feeds k = 32 n + g.
 template <int BN, int MODE, int V, bool FULL, bool TAIL = false, int BM_ = 128>
-__global__ __launch_bounds__(256, 3) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
+__global__ __launch_bounds__(256, (MODE == MODE_FWD && BM_ == 128 && BN == 64) ? 3 : 2) void gemm_f32_k(const float *__restrict__ A, int64_t lda,
                                                   const float *__restrict__ Bm, int64_t ldb, float *__restrict__ C,
                                                   int64_t ldc, double *__restrict__ partial, int M_bound, int N,
                                                   int K_bound, const int32_t *__restrict__ rows_dev, int n_tiles_n,

@@ -40,8 +40,9 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
                                                   uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   int64_t *__restrict__ eoff, int64_t *__restrict__ rowstart,
                                                   int64_t *__restrict__ meta, int64_t edge_cap,
-                                                  int32_t *__restrict__ status, InstStride is)
+                                                  int2 *__restrict__ bound_note, int32_t *__restrict__ status, InstStride is)
 {
+    bound_note = inst_ptr(bound_note, is.ws);
     S = inst_ptr(S, is.buf); nS_dev = inst_ptr(nS_dev, is.buf); status = inst_ptr(status, is.buf);
     epoch = inst_ptr(epoch, is.ws); ts_mem = inst_ptr(ts_mem, is.ws); eoff = inst_ptr(eoff, is.ws);
     rowstart = inst_ptr(rowstart, is.ws); meta = inst_ptr(meta, is.ws);
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(256) void row_prefix(const int64_t *__restrict__ ro
     const int64_t n_tiles = row_tiles(nS);
     if ((int64_t)blockIdx.x >= n_tiles) return;
     row_prefix_tile(rowptr, n_nodes, S, nS, blockIdx.x, n_tiles, ts, call_tag(call_number(epoch), SLOT_ROWS), eoff, rowstart,
-                    meta, edge_cap, status);
+                    meta, edge_cap, bound_note, edge_cap / EDGE_TILE, status);
 }
 
 // Arguments of the hand-over inside the weight scan (see scan_edges).
@@ -89,14 +90,15 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
                                                   const int64_t *__restrict__ eoff,
                                                   const int64_t *__restrict__ rowstart,
                                                   uint64_t *__restrict__ wtable, uint8_t *__restrict__ tileflag,
-                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ status,
+                                                  int2 *__restrict__ chunk_note, const int2 *__restrict__ bound_note,
+                                                  int32_t *__restrict__ status,
                                                   const uint64_t *__restrict__ epoch, Stage stg, InstStride is)
 {
     __shared__ RowSlice slice;
     __shared__ unsigned long long acc[SUB_IDS];
     __shared__ uint32_t hist[SUB_MAX + 1];
     meta = inst_ptr(meta, is.ws); eoff = inst_ptr(eoff, is.ws); rowstart = inst_ptr(rowstart, is.ws);
-    wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); chunk_note = inst_ptr(chunk_note, is.ws);
+    wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); chunk_note = inst_ptr(chunk_note, is.ws); bound_note = inst_ptr(bound_note, is.ws);
     epoch = inst_ptr(epoch, is.ws);
     stg.w = inst_ptr(stg.w, is.ws); stg.c = inst_ptr(stg.c, is.ws); stg.off = inst_ptr(stg.off, is.ws);
     stg.done = inst_ptr(stg.done, is.ws);
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
     for (int64_t t = blockIdx.x; t < n_chunks; t += chunk_blocks) {
         const int64_t c0 = t * EDGE_TILE;
         const int64_t c1 = (c0 + EDGE_TILE < E) ? c0 + EDGE_TILE : E;
-        stage_slice<false>(slice, eoff, rowstart, nS, c0, c1, chunk_note + t);   // (starts with a barrier)
+        stage_slice_bounds(slice, eoff, rowstart, nS, t, c0, c1, bound_note, chunk_note + t);   // (starts with a barrier)
         if (staged) {
             for (int i = threadIdx.x; i <= SUB_MAX; i += blockDim.x) hist[i] = 0u;
             __syncthreads();
@@ -581,7 +583,7 @@ int csgs::launch_row_prefix(const int64_t *rowptr, int64_t n_nodes, const int32_
 {
     const unsigned tiles = (unsigned)(((int64_t)nS + ROW_TILE - 1) / ROW_TILE);
     CSGS_LAUNCH(K_ROW_PREFIX, row_prefix, dim3(tiles, 1, (unsigned)w.n_inst), dim3(256), st, rowptr, n_nodes, S, nS, nS_dev,
-                w.epoch, w.rp_ts, w.rp_tiles, rows.eoff, rows.rowstart, rows.meta, w.chunk_cap * EDGE_TILE, status,
+                w.epoch, w.rp_ts, w.rp_tiles, rows.eoff, rows.rowstart, rows.meta, w.chunk_cap * EDGE_TILE, rows.bound_note, status,
                 inst_stride(w));
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
@@ -695,7 +697,7 @@ static int build_probs_impl(const csgs_graph *g, const int32_t *S, int32_t nS, c
                     g->local_hi, owners, ws->scan_mode};
     CSGS_LAUNCH(K_SCAN_EDGES, scan_edges, dim3((unsigned)(EDGE_GRID + owners), 1, nz), dim3(256), st, g->colidx, g->val,
                 g->n_nodes, g->nnz, shift_base, rows.meta, w.chunk_cap * EDGE_TILE, rows.eoff, rows.rowstart, w.wtable,
-                w.tileflag, rows.chunk_note, status, w.epoch, stg, is);
+                w.tileflag, rows.chunk_note, rows.bound_note, status, w.epoch, stg, is);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_CAND_PARTIALS, cand_partials, dim3((unsigned)((w.n_tiles + CAND_PART_TILES - 1) / CAND_PART_TILES), 1, nz), dim3(256), st, w.wtable, w.tileflag, n_words,
                 g->n_nodes, w.n_tiles, g->local_lo, g->local_hi, w.epoch, (unsigned long long *)w.cand_flag,

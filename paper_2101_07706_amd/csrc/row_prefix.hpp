@@ -12,12 +12,12 @@ static_assert(ROW_TILE == 256 * RP_ITEMS, "row tile");
 
 // Tile t of the rows S[0 .. nS).  Called by all 256 threads of a block; blocks with t >= number of
 // tiles must not call.  Leaves in `meta` (by the last tile): row count, edge count (0 when above
-// edge_cap: treated as empty), true edge count.
+// edge_cap: treated as empty), true edge count; in bound_note [chunk_cap + 2] what stage_slice_bounds() reads.
 __device__ inline void row_prefix_tile(const int64_t *__restrict__ rowptr, int64_t n_nodes,
                                        const int32_t *__restrict__ S, int32_t nS, int64_t t, int64_t n_tiles,
                                        const TileState<1> &ts, unsigned long long tag, int64_t *__restrict__ eoff,
                                        int64_t *__restrict__ rowstart, int64_t *__restrict__ meta, int64_t edge_cap,
-                                       int32_t *__restrict__ status)
+                                       int2 *__restrict__ bound_note, int64_t chunk_cap, int32_t *__restrict__ status)
 {
     __shared__ int64_t lds[17];
     __shared__ int32_t s_deg[ROW_TILE];
@@ -60,7 +60,15 @@ __device__ inline void row_prefix_tile(const int64_t *__restrict__ rowptr, int64
 #pragma unroll
     for (int k = 0; k < RP_ITEMS; ++k) {
         const int32_t a = r0 + (int32_t)threadIdx.x * RP_ITEMS + k;
-        if (a < nS) eoff[a] = ex;
+        if (a < nS) {
+            eoff[a] = ex;
+            // Edge positions t * EDGE_TILE inside (ex, ex + deg]: a chunk that starts there starts in this row --
+            // or, if the row ends exactly there, with the next one -- and the first row whose offset is at
+            // or beyond the position is the next one.  The edge passes read this instead of searching eoff.
+            const int64_t e1 = ex + d[k];
+            for (int64_t tb = ex / EDGE_TILE + 1; tb <= e1 / EDGE_TILE && tb <= chunk_cap; ++tb)
+                bound_note[tb] = make_int2(e1 == tb * EDGE_TILE ? a + 1 : a, a + 1);
+        }
         ex += d[k];
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_NODE_ID);

@@ -308,6 +308,7 @@ struct NextRows {
     uint64_t *ts_mem;
     int64_t ts_tiles;
     int64_t *eoff, *rowstart, *meta;
+    int2 *bound_note;
     int64_t edge_cap;
     int32_t blocks;       // 0 = none
 };
@@ -343,12 +344,13 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         nxt.S_next = inst_ptr(nxt.S_next, is.buf); nxt.n_next = inst_ptr(nxt.n_next, is.buf);
         nxt.ts_mem = inst_ptr(nxt.ts_mem, is.ws); nxt.eoff = inst_ptr(nxt.eoff, is.ws);
         nxt.rowstart = inst_ptr(nxt.rowstart, is.ws); nxt.meta = inst_ptr(nxt.meta, is.ws);
+        nxt.bound_note = inst_ptr(nxt.bound_note, is.ws);
         const int32_t n = resolve_count(nxt.bound, nxt.n_next);
         const int64_t t = (int64_t)blockIdx.x - rem.blocks, n_tiles = row_tiles(n);
         if (t < n_tiles) {
             const TileState<1> rts(nxt.ts_mem, nxt.ts_tiles, wait_limit(epoch));
             row_prefix_tile(nxt.rowptr, nxt.n_nodes, nxt.S_next, n, t, n_tiles, rts, call_tag(epoch[EPOCH_DRAW], SLOT_ROWS_NEXT),
-                            nxt.eoff, nxt.rowstart, nxt.meta, nxt.edge_cap, status);
+                            nxt.eoff, nxt.rowstart, nxt.meta, nxt.edge_cap, nxt.bound_note, nxt.edge_cap / EDGE_TILE, status);
         }
         return;
     }
@@ -533,7 +535,7 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     if (S_next && ws->draw_B <= ws->nS_max) {
         const RowOffsets &o = w.rows[(ws->rows_buf & 1) ^ 1];
         nxt = NextRows{g->rowptr, g->n_nodes, S_next, n_next, ws->draw_B, w.rp_ts, w.rp_tiles, o.eoff, o.rowstart, o.meta,
-                       w.chunk_cap * EDGE_TILE, (int32_t)((ws->draw_B + ROW_TILE - 1) / ROW_TILE)};
+                       o.bound_note, w.chunk_cap * EDGE_TILE, (int32_t)((ws->draw_B + ROW_TILE - 1) / ROW_TILE)};
     }
     ws->has_next = nxt.blocks > 0;
     // after csgs_build_probs on the same rows the weight scan has left every chunk's row slice in the workspace
