@@ -448,7 +448,11 @@ def test_aggregate_shapes(dev, F, bf16, mode):
                                    (8192, 256, 256), (8192, 256, 47), (100, 1000, 70),
                                    # one to four k beyond whole chunks of 32: folded into the last chunk
                                    (300, 36, 70), (513, 68, 47), (1000, 33, 64), (257, 66, 33), (129, 99, 20),
-                                   (4096, 132, 256), (640, 35, 300), (77, 34, 16), (128, 37, 64)])
+                                   (4096, 132, 256), (640, 35, 300), (77, 34, 16), (128, 37, 64),
+                                   # 512 and more blocks of 128 x 64: the block shape of a launch for 8 mini-batches of the
+                                   # largest configuration (regular shape, with and without folded tail, ragged, narrow output)
+                                   (16384, 256, 256), (16384, 100, 256), (16500, 100, 256), (16421, 250, 256),
+                                   (65536, 256, 47), (65541, 256, 47), (32768, 36, 128)])
 def test_layer_gemm_shapes(dev, M, K, N):
     from paper_2101_07706_amd import csgs
     rng = np.random.default_rng(M + K + N)
@@ -516,7 +520,7 @@ def test_chain_on_prepared_rows(dev, name):
 # ---------------------------------------------------------------- several mini-batches per call
 @pytest.mark.parametrize("name,K,chained,batched", [("tiny", 3, True, False), ("tiny", 2, False, True), ("medium", 4, True, True),
                                                      ("mid", 2, True, False), ("mid", 3, True, True), ("large", 3, True, False),
-                                                     ("large", 2, True, True)])
+                                                     ("large", 2, True, True), ("large", 8, True, True)])
 def test_instances_per_call(dev, name, K, chained, batched):
     """K mini-batches of consecutive iterations through the same sampling calls (n_inst = K in the
     workspace descriptor) and, with `batched`, through the same compute launches (the _n forms):
@@ -694,7 +698,8 @@ def test_layer_gemm_and_aggregate_device_row_count(dev):
     """M_dev / nS_dev below the capacity: the first rows equal a call of that size, the rest stay untouched."""
     from paper_2101_07706_amd import csgs
     rng = np.random.default_rng(8)
-    for M, K, N, m in [(700, 96, 80, 389), (700, 100, 80, 389), (1024, 256, 256, 1000), (1024, 68, 256, 3)]:
+    for M, K, N, m in [(700, 96, 80, 389), (700, 100, 80, 389), (1024, 256, 256, 1000), (1024, 68, 256, 3),
+                       (16512, 256, 256, 16001), (16384, 100, 256, 9000)]:
         _gemm_device_row_count(dev, rng, M, K, N, m)
     M, K, N, m = 700, 96, 80, 389
     Z = rng.standard_normal((M, K)).astype(np.float32)
