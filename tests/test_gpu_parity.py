@@ -84,6 +84,27 @@ def run_full_size(name, skews, its=(0,)):
     return osteps
 
 
+def run_instances(name, K, chained, batched):
+    """K mini-batches of consecutive iterations through the same sampling calls (n_inst = K in the
+    workspace descriptor) and, with `batched`, through the same compute launches (the _n forms):
+    every instance equals the oracle's chain for its batch and iteration."""
+    it = 4
+    if name in ("large", "dense"):
+        cfg, g, X, Ws, _ = cached_inputs(name)
+    else:
+        cfg, g, X, Ws, _ = chain.config_inputs(name, it)
+    S0s = [synth.make_batch(g, cfg.batch, cfg.seed, it + k) for k in range(K)]
+    bf16 = cfg.feat_dtype == "bf16"
+    say(f"[{name}] {K} instances per call, chained={chained}, compute batched={batched}")
+    auto_D = 8.0 if (name == "tiny" and not chained) else None
+    got = chain.gpu_chain_instances(g, X, Ws, S0s, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
+                                    chained=chained, batched_compute=batched)
+    for k in range(K):
+        osteps = chain.oracle_chain(g, X, Ws, S0s[k], cfg.skew, cfg.samples, 1234 + cfg.seed, it + k, bf16, auto_D=auto_D)
+        worst = chain.compare_chain(osteps, got[k])
+        say(f"[{name}] instance {k}: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+
+
 def test_dense_config_skew_sweep(dev, monkeypatch):
     """Dense-neighborhood config at full size (114 M edges), every output element by element, over
     the skew sweep; the bottom layer's remote count must fall as the skew grows.  Once more with the
@@ -98,6 +119,11 @@ def test_dense_config_skew_sweep(dev, monkeypatch):
     assert remote[0] > remote[-1]
     monkeypatch.setattr(pipeline, "DEFAULT_SCAN_MODE", 2)
     run_full_size("dense", [cfg.skews[len(cfg.skews) // 2]])
+
+
+def test_dense_config_instances(dev):
+    """Dense-neighborhood config, 8 mini-batches per sampling call and per compute launch (the form bench.py times)."""
+    run_instances("dense", 8, True, True)
 
 
 def test_large_config(dev):
@@ -500,8 +526,8 @@ def test_chain_without_host_reads_large(dev):
 def test_chain_on_prepared_rows(dev, name):
     """Layers after the first pass no row array: csgs_build_probs(S = NULL) takes the node set the
     previous csgs_sample_layer sampled, whose offsets that call prepared.  Same results as the oracle."""
-    if name == "large":
-        cfg, g, X, Ws, _ = cached_inputs("large")
+    if name in ("large", "dense"):
+        cfg, g, X, Ws, _ = cached_inputs(name)
         S0 = synth.make_batch(g, cfg.batch, cfg.seed, 5)
         it = 5
     else:
@@ -522,24 +548,7 @@ def test_chain_on_prepared_rows(dev, name):
                                                      ("mid", 2, True, False), ("mid", 3, True, True), ("large", 3, True, False),
                                                      ("large", 2, True, True), ("large", 8, True, True)])
 def test_instances_per_call(dev, name, K, chained, batched):
-    """K mini-batches of consecutive iterations through the same sampling calls (n_inst = K in the
-    workspace descriptor) and, with `batched`, through the same compute launches (the _n forms):
-    every instance equals the oracle's chain for its batch and iteration."""
-    it = 4
-    if name == "large":
-        cfg, g, X, Ws, _ = cached_inputs("large")
-    else:
-        cfg, g, X, Ws, _ = chain.config_inputs(name, it)
-    S0s = [synth.make_batch(g, cfg.batch, cfg.seed, it + k) for k in range(K)]
-    bf16 = cfg.feat_dtype == "bf16"
-    say(f"[{name}] {K} instances per call, chained={chained}, compute batched={batched}")
-    auto_D = 8.0 if (name == "tiny" and not chained) else None
-    got = chain.gpu_chain_instances(g, X, Ws, S0s, cfg.skew, cfg.samples, 1234 + cfg.seed, it, bf16, auto_D=auto_D,
-                                    chained=chained, batched_compute=batched)
-    for k in range(K):
-        osteps = chain.oracle_chain(g, X, Ws, S0s[k], cfg.skew, cfg.samples, 1234 + cfg.seed, it + k, bf16, auto_D=auto_D)
-        worst = chain.compare_chain(osteps, got[k])
-        say(f"[{name}] instance {k}: n' {[o.sm.n_next for o in osteps]} worst err/tol {max(worst.values()):.3f}")
+    run_instances(name, K, chained, batched)
 
 
 def test_instances_are_isolated(dev):
