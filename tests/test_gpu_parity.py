@@ -131,6 +131,22 @@ def test_large_config(dev):
     run_full_size("large", [synth.CONFIGS["large"].skew], its=(0, 7))
 
 
+def test_large_config_scaled(dev):
+    """Large config with batch and samples per layer times 16 (the scaled-up variant bench.py also times):
+    every output element by element."""
+    from paper_2101_07706_amd import pipeline
+    cfg, g, X, Ws, _ = cached_inputs("large")
+    sc = 16
+    dg = pipeline.DeviceGraph(g, torch.device("cuda:0"))
+    S0 = synth.make_batch(g, cfg.batch * sc, cfg.seed, 0)
+    say(f"[large x{sc}] batch {len(S0)}, {cfg.samples * sc} samples per layer")
+    osteps = chain.oracle_chain(g, X, Ws, S0, cfg.skew, cfg.samples * sc, 1234 + cfg.seed, 0, True)
+    gsteps, _ = chain.gpu_chain(g, X, Ws, S0, cfg.skew, cfg.samples * sc, 1234 + cfg.seed, 0, True, dg=dg)
+    worst = chain.compare_chain(osteps, gsteps)
+    say(f"[large x{sc}] " + ", ".join(f"nS={len(o.S)} E={o.pr.edges_scanned} n'={o.sm.n_next} nnz={o.sm.adj_nnz}" for o in osteps)
+        + f" worst err/tol {max(worst.values()):.3f}")
+
+
 class SmallGraph:
     """Random symmetric-normalised graph with self-loops and a few isolated (self-loop only) nodes."""
 
