@@ -275,13 +275,18 @@ __device__ inline void aggregate_long_rows(int64_t bid, int32_t per, const int32
     }
 }
 
+constexpr int DENSE_AVG = 16;      // kept edges per row, on average, from which on leading blocks take the long rows of a large grid
+constexpr int MANY_ROWS = 32768;   // rows per call (and instance) from which on such a grid has leading blocks at all
+
 // A block first takes the ordinary ones among its AGG_BLOCK / G rows, one group of lanes each, then,
 // all wavefronts together, the long ones among them (a block-wide vote says whether there are any):
-// no block exists only to look for long rows, which matters when the grid takes many rounds.
-// With n_long_blocks > 0 (the host asks for it when the whole grid is resident at once, where the
-// longest path counts and not the number of blocks) the long rows go to that many leading blocks
-// instead, `per` rows to look through each, and start together with the ordinary ones.
-template <typename T, int V, int G, bool RELU>
+// no block has to look for long rows, which matters when the grid takes many rounds and few rows are long.
+// Or the long rows go to n_long_blocks leading blocks instead, `per` rows to look through each, which
+// start together with the ordinary ones: always when the whole grid is resident at once (the longest
+// path counts there, not the number of blocks); in a larger grid when the rows are dense (many blocks
+// would otherwise end with wavefronts that wait for the one with the longest ordinary row before the
+// long rows start), and then the leading blocks of a sparse call return at once.
+template <typename T, int V, int G, bool RELU, bool ADAPT>
 __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                          const int32_t *__restrict__ adj_col,
                                                          const float *__restrict__ adj_val, int32_t nS_bound,
@@ -292,12 +297,20 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const int32_t *__restrict__ src_row, int32_t F,
                                                          float *__restrict__ Z, int64_t ldz,
                                                          const float *__restrict__ mask, int64_t ldm,
-                                                         int32_t n_long_blocks, int32_t per, CompStride cs)
+                                                         int32_t n_long_blocks, int32_t per, int32_t dense_avg, CompStride cs)
 {
     adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
     nS_dev = inst_ptr(nS_dev, cs.adj); n_cols_p = inst_ptr(n_cols_p, cs.adj); src_row = inst_ptr(src_row, cs.adj);
     Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
+    // Who takes the long rows: the leading blocks if there are any and (ADAPT) the rows hold more than
+    // dense_avg kept edges on average; else the blocks that own them.  The same for the whole grid.
+    bool leading = n_long_blocks > 0;
+    if (ADAPT) {
+        const int32_t n = resolve_count(nS_bound, nS_dev);
+        leading = leading && n > 0 && (int64_t)adj_rowptr[n] > (int64_t)dense_avg * n;
+    }
     if ((int32_t)blockIdx.x < n_long_blocks) {
+        if (ADAPT && !leading) return;
         const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
         aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, resolve_count(nS_bound, nS_dev),
                                         n_cols, Xl, ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
     const bool is_long = aggregate_rows<T, V, G, RELU>(bid, adj_rowptr, adj_col, adj_val, nS_bound, nS_dev,
                                                        n_cols_p, src_row ? 0x7FFFFFFFll : rows_l, &nS, &n_cols, Xl, ldl,
                                                        rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
-    if (n_long_blocks == 0 && __syncthreads_or(is_long ? 1 : 0))
+    if ((ADAPT ? !leading : n_long_blocks == 0) && __syncthreads_or(is_long ? 1 : 0))
         aggregate_long_rows<T, V, RELU>(bid, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
                                         rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
 }
@@ -323,20 +336,26 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
     const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
     // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
     const int64_t chunks = (F + G * V - 1) / (G * V);
-    // Leading blocks for the long rows (4 rows each to look through) only when the row blocks are resident
-    // at once, or nearly (8 blocks of 256 threads per compute unit; the leading blocks are gone quickly)
-    int64_t lblocks = 0, per = 0;
-    if ((blocks + ((int64_t)nS + 3) / 4) * chunks * ci.n <= 2 * 8 * 256) {
-        lblocks = ((int64_t)nS + 3) / 4;
-        per = ((int64_t)nS + lblocks - 1) / lblocks;
-    }
+    // Leading blocks for the long rows.  When the row blocks are resident at once, or nearly (8 blocks of
+    // 256 threads per compute unit), 4 rows each to look through, and they always take the long rows.
+    // For a call with very many rows 8 rows each, and the kernel decides by the density of the rows (every
+    // block then reads the edge total first).  In between none: measured, the leading blocks and the extra
+    // read cost more there than they bring (launches for 8 mini-batches of 2 K to 8 K rows each).
+    const bool small_grid = (blocks + ((int64_t)nS + 3) / 4) * chunks * ci.n <= 2 * 8 * 256;
+    const bool many_rows = nS >= MANY_ROWS;
+    const int64_t per = small_grid ? 4 : 8;
+    const int64_t lblocks = (small_grid || many_rows) ? ((int64_t)nS + per - 1) / per : 0;
+    const int32_t dense_avg = (many_rows && !small_grid) ? DENSE_AVG : 0;   // > 0: the kernel decides
     const dim3 grid((unsigned)(blocks + lblocks), (unsigned)chunks, (unsigned)ci.n);
-    if (relu)
-        CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, true>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, ci.cs);
-    else
-        CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, false>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp,
-                    (const T *)Xl, ldl, rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, ci.cs);
+#define CSGS_AGG_LAUNCH(RELU, ADAPT)                                                                                              \
+    CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, RELU, ADAPT>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp, (const T *)Xl, ldl, \
+                   rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, dense_avg, ci.cs)
+    if (dense_avg > 0) {
+        if (relu) CSGS_AGG_LAUNCH(true, true); else CSGS_AGG_LAUNCH(false, true);
+    } else {
+        if (relu) CSGS_AGG_LAUNCH(true, false); else CSGS_AGG_LAUNCH(false, false);
+    }
+#undef CSGS_AGG_LAUNCH
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

@@ -485,6 +485,34 @@ def test_aggregate_shapes(dev, F, bf16, mode):
     chain.assert_close(Z.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"aggregate F={F}")
 
 
+@pytest.mark.parametrize("mean_len,device_count", [(2, False), (2, True), (24, False), (24, True)])
+def test_aggregate_many_rows(dev, mean_len, device_count):
+    """Calls with tens of thousands of rows: the kernel itself decides, by the mean number of kept edges per
+    row, whether leading blocks or the owning blocks take the long rows.  Both outcomes, rows of 0 to 400 edges."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(1000 + mean_len)
+    n_rows, n_cols, F = 40000, 6000, 64
+    lens = rng.poisson(mean_len, n_rows)
+    long_ones = rng.choice(n_rows, 300, replace=False)
+    lens[long_ones] = rng.integers(33, 400, 300)
+    lens[rng.choice(n_rows, 50, replace=False)] = 0
+    rowptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=rowptr[1:])
+    col = rng.integers(0, n_cols, int(rowptr[-1])).astype(np.int32)   # (repeated columns in a row are allowed: they add up)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    m = 39001 if device_count else n_rows
+    say(f"[aggregate] {n_rows} rows, mean {len(col) / n_rows:.1f} edges, device count {device_count}")
+    t = lambda a: torch.from_numpy(a).to(dev)
+    Z = torch.full((n_rows, F), float("nan"), dtype=torch.float32, device=dev)
+    cnt = torch.tensor([m], dtype=torch.int32, device=dev) if device_count else None
+    csgs.csgs_aggregate(t(rowptr), t(col), t(val), None, t(X), None, None, True, Z, nS_dev=cnt)
+    torch.cuda.synchronize()
+    want = oracle.aggregate(rowptr[:m + 1], col[:rowptr[m]], val[:rowptr[m]], X, relu_on_input=True)
+    chain.assert_close(Z[:m].cpu().numpy(), want, chain.RTOL, chain.ATOL, "Z of a call with many rows")
+    assert bool(torch.isnan(Z[m:]).all())
+
+
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (33, 17, 5), (256, 64, 64), (1024, 128, 256), (2048, 602, 256),
                                    (2048, 256, 41), (4096, 300, 512), (4096, 512, 100), (8192, 100, 256),
                                    (8192, 256, 256), (8192, 256, 47), (100, 1000, 70),
