@@ -246,7 +246,7 @@ static int64_t first_greater(const uint64_t *cdf, int64_t n, uint64_t u)
 }
 
 /*
- * B draws with replacement from q (Section 4.1, "run the sampling for B times"), the draws given
+ * B draws with replacement from q (Section 4.1, Eq. 8), the draws given
  * as explicit 64-bit words so that tests can enumerate them; deduplicated to the ascending node
  * set S_next with multiplicities; inclusion probability from Eq. 8 (pd in double, p_incl as float).
  */

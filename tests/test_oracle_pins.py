@@ -321,6 +321,73 @@ def test_inclusion_probability_and_discount_values():
     assert sm.S_next.tolist() == ids.tolist() and sm.mult.tolist() == counts.tolist()
 
 
+# ------------------------------- the two halves of the sampler (subgraph variant, Section 5.1)
+
+@pytest.mark.parametrize("seed,it,layer", [(123, 4, 1), (7, 0, 3), (2 ** 40 + 5, 2 ** 33 + 9, 2)])
+def test_split_draw_and_adjacency_equal_the_fused_call(seed, it, layer):
+    """draw_nodes + sampled_adjacency(rows = S) is sample_layer, bit for bit; the draws themselves are
+    replayed here from the generator word (pinned by the known-answer vectors) and the search rule,
+    with iteration and layer numbers that differ, so that exchanged counter words would show."""
+    tg = TinyGraph(14, 0.4, 17, lo=3, hi=9)
+    S = np.array([0, 4, 8, 13], np.int32)
+    pr = oracle.build_probs(tg, S, 4.0)
+    B = 7
+    dr = oracle.draw_nodes(pr, B, seed, it, layer)
+    total = int(pr.total)
+    cdf = [int(c) for c in pr.cdf]
+    hits = []
+    for t in range(B):
+        u = (oracle.draw_word(seed, it, layer, t) * total) >> 64
+        hits.append(next(k for k, c in enumerate(cdf) if c > u))       # first candidate whose running sum exceeds u
+    ids, counts = np.unique(pr.cand_id[hits], return_counts=True)
+    assert dr.S_next.tolist() == ids.tolist() and dr.mult.tolist() == counts.tolist() and dr.n_next == len(ids)
+    # exchanged counter words give other draws (the case above would not notice a swap if they did not)
+    other = [next(k for k, c in enumerate(cdf) if c > (oracle.draw_word(seed, layer, it, t) * total) >> 64) for t in range(B)]
+    assert other != hits
+    # Eq. 8 in double, and its float rounding
+    q = np.diff(np.concatenate([[0], pr.cdf.astype(np.float64)])) / float(total)
+    pos = np.searchsorted(pr.cand_id, dr.S_next)
+    np.testing.assert_allclose(dr.pd, 1.0 - (1.0 - q[pos]) ** B, rtol=1e-12)
+    assert dr.p_incl.tolist() == dr.pd.astype(np.float32).tolist()
+    # the fused call: same node set, same operator
+    sm = oracle.sample_layer(tg, S, pr, B, seed, it, layer)
+    adj = oracle.sampled_adjacency(tg, S, dr)
+    assert sm.S_next.tolist() == dr.S_next.tolist() and sm.mult.tolist() == dr.mult.tolist()
+    assert sm.p_incl.tobytes() == dr.p_incl.tobytes()
+    assert sm.adj_rowptr.tolist() == adj.adj_rowptr.tolist() and sm.adj_nnz == adj.adj_nnz
+    assert sm.adj_col.tolist() == adj.adj_col.tolist() and sm.adj_val.tobytes() == adj.adj_val.tobytes()
+
+
+def test_induced_sampled_adjacency_is_the_discounted_submatrix():
+    """Subgraph sampler: all nodes are candidates, the rows of the operator are the drawn nodes
+    themselves, so it is the dense P[S_next, S_next] with column j divided by p_j (Eq. 3, Eq. 8)."""
+    n = 12
+    tg = TinyGraph(n, 0.35, 23, lo=2, hi=8)
+    pr = oracle.build_probs(tg, np.arange(n, dtype=np.int32), 2.0)
+    assert pr.n_cand == n                                   # every node has a self-loop, so all are candidates
+    B = 5
+    dr = oracle.draw_nodes(pr, B, seed=11, it=6, layer=0)
+    assert 1 <= dr.n_next <= B and dr.n_next < n
+    adj = oracle.sampled_adjacency(tg, dr.S_next, dr)
+    q = np.diff(np.concatenate([[0], pr.cdf.astype(np.float64)])) / float(pr.total)
+    p = 1.0 - (1.0 - q[dr.S_next]) ** B                     # candidate position = node id here
+    want = tg.dense[np.ix_(dr.S_next, dr.S_next)].astype(np.float64) / p[None, :]
+    got = np.zeros_like(want)
+    for a in range(dr.n_next):
+        cols = adj.adj_col[adj.adj_rowptr[a]:adj.adj_rowptr[a + 1]]
+        assert np.all(np.diff(cols) > 0)                    # ascending, no duplicates
+        got[a, cols] = adj.adj_val[adj.adj_rowptr[a]:adj.adj_rowptr[a + 1]]
+    assert adj.adj_nnz == int((want != 0).sum())
+    np.testing.assert_allclose(got, want, rtol=1e-6, atol=0)
+    # rows in the order given, not sorted: a permuted row list permutes the rows of the operator
+    perm = dr.S_next[::-1].copy()
+    adj2 = oracle.sampled_adjacency(tg, perm, dr)
+    got2 = np.zeros_like(want)
+    for a in range(dr.n_next):
+        got2[a, adj2.adj_col[adj2.adj_rowptr[a]:adj2.adj_rowptr[a + 1]]] = adj2.adj_val[adj2.adj_rowptr[a]:adj2.adj_rowptr[a + 1]]
+    np.testing.assert_array_equal(got2, got[::-1])
+
+
 # --------------------------------------------------------- Tiny config: statistics
 
 @pytest.fixture(scope="module")
