@@ -319,7 +319,7 @@ int csgs_aggregate(const int32_t *adj_rowptr, const int32_t *adj_col, const floa
  * out[k, 0..F) = X[ids[k], 0..F) for k < n: fills the staged buffer of sampled remote feature rows
  * that csgs_aggregate reads (X_remote) from the request list csgs_remote_count wrote (remote_ids).
  * On one GPU that holds the whole feature table this takes the place of the exchange of feature
- * vectors between partitions (Section 3, "Communication of Feature Vectors").
+ * vectors between partitions (Section 3, the paragraph on the transfer of feature vectors).
  *
  *   X [rows x F], leading dimension ld (elements of dtype CSGS_F32 or CSGS_BF16; rows are copied
  *   bit for bit); ids [cap] device; n = min(*n_dev, cap) when n_dev (device int64, e.g.
@@ -388,9 +388,9 @@ int csgs_gather_rows_n(const csgs_inst_strides *inst /*host*/, const void *X, in
  * csgs_aggregate_grad: P~ as written by csgs_sample_layer (nS rows, n_cols = *n_next columns,
  *   adj_cap = capacity of adj_col / adj_val), dZ [nS x F] -> dH_prev [n_cols x F].  H_prev
  *   [n_cols x F] is the layer's input (NULL: no activation, no mask).  The transpose of P~ is built
- *   in `scratch` (256-byte aligned, csgs_aggregate_grad_scratch_bytes(n_cols, adj_cap) bytes);
- *   inside a column the summation order is the arrival order of integer atomics, which moves a
- *   double sum by parts in 1e16, far below the float result's last bit in all but tie cases.
+ *   in `scratch` (256-byte aligned, csgs_aggregate_grad_scratch_bytes(n_cols, adj_cap) bytes),
+ *   every column in ascending row order: the sums are formed in that order, in double, so two calls
+ *   on the same input give the same bits.
  * Host errors: CSGS_EINVAL, CSGS_EWORKSPACE (scratch too small), CSGS_EUNSUPPORTED.
  */
 size_t csgs_layer_gemm_grad_w_scratch_bytes(int32_t M, int32_t K, int32_t Nout);
@@ -405,45 +405,6 @@ int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj_col, const
                         const int32_t *n_cols_dev, const float *dZ, int64_t lddz, int32_t F,
                         const float *H_prev, int64_t ldh, float *dH_prev, int64_t ldd, void *scratch,
                         size_t scratch_bytes, void *stream);
-
-/*
- * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the
- * library carries two HIP events that the runtime stamps with the start and the end of that
- * dispatch.  csgs_profile_collect, called after the caller has synchronised, fills ms_sum[k] /
- * launches[k] (host arrays of csgs_profile_kernel_count() entries) with the summed kernel
- * durations in milliseconds and the number of launches per kernel since the last collect, and
- * resets.  Process-wide, not thread-safe; creates HIP events on first use, so it is not for
- * callers that may not allocate.
- */
-int csgs_profile_enable(int on);
-int csgs_profile_kernel_count(void);
-const char *csgs_profile_kernel_name(int kernel);
-int csgs_profile_collect(double *ms_sum /*host*/, int64_t *launches /*host*/);
-/* The same launch by launch, for medians and percentiles: fills ms[i] / kernel[i] (host arrays of
- * `cap` entries) with the duration and the kernel index of the first min(cap, n) launches since the
- * last collect, stores n (all launches timed since then) in *n_out, and does NOT reset -- call it
- * before csgs_profile_collect. */
-int csgs_profile_samples(float *ms /*host*/, int32_t *kernel /*host*/, int64_t cap, int64_t *n_out /*host*/);
-
-/* Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned)
- * with an ordinary streaming kernel: the yardstick for achievable HBM bandwidth, and the
- * known-size kernel against which hardware byte counters are calibrated. */
-int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/* n_updates fire-and-forget 64-bit integer atomic adds (+1, device scope) to pseudo-random entries of
- * `table` (n_table entries, device, 8-byte aligned, contents are modified): the yardstick for the
- * weight scan of csgs_build_probs, which updates its per-node accumulators the same way. */
-int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_updates, void *stream);
-
-/* Matrix-core yardstick for csgs_layer_gemm: CSGS_CALIB_MFMA_BLOCKS blocks of four wavefronts, each
- * wavefront issuing 64 * iters double-precision 16 x 16 x 4 matrix instructions (2048 flops each) on
- * eight independent accumulators, i.e. CSGS_CALIB_MFMA_BLOCKS * 4 * 64 * 2048 * iters flops per call.
- * from_lds = 0: operands stay in registers (what the matrix cores sustain); from_lds = 1: every 64
- * instructions the operands are re-read from LDS as floats and widened, which is the inner loop of
- * the layer GEMM without its global loads and barriers.  `sink` (device, n_sink >=
- * CSGS_CALIB_MFMA_BLOCKS * 256 doubles) receives one value per thread so that the work is kept. */
-#define CSGS_CALIB_MFMA_BLOCKS 2048
-int csgs_calib_mfma_f64(double *sink, size_t n_sink, int64_t iters, int32_t from_lds, void *stream);
 
 /* Static string for a CSGS_E* code. */
 const char *csgs_strerror(int code);

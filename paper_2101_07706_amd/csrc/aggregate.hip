@@ -390,10 +390,12 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
 // ------------------------------------------------------------------ gradient of the aggregation
 // dH_prev = (P~^T dZ) .* [H_prev > 0].  P~ is held by rows; its transpose is built per call in the
 // caller's scratch: entries per column counted with integer atomics, a block scan turns the
-// counts into column offsets, a second pass drops every entry into its column (order inside a
-// column is arrival order).  Then the forward kernel runs on the transposed structure with dZ as
-// the gathered table and the ReLU derivative as an output mask.  Sums are in double, so the
-// arrival order moves the result by parts in 1e16 before the single rounding to float.
+// counts into column offsets, a second pass drops every entry into its column in arrival order,
+// and a third puts each column's entries into ascending row order (ranks by counting inside a
+// wavefront for columns of up to 64 entries, through a bitmap over the rows in LDS for longer ones).
+// Then the forward kernel runs on the transposed structure with dZ as the gathered table and the
+// ReLU derivative as an output mask.  Every column is summed in ascending row order, in double, with
+// one rounding: the result does not depend on timing.
 
 // one wavefront per row of P~: counts[c] += 1 for every entry of the row
 __global__ __launch_bounds__(256) void adjT_count(const int32_t *__restrict__ adj_rowptr,
@@ -449,13 +451,13 @@ __global__ __launch_bounds__(1024) void adjT_prefix(int32_t *__restrict__ counts
     if (threadIdx.x == 0) colptr[n_cols] = base;
 }
 
-// one wavefront per row of P~: entry (r, c, v) goes to slot colptr[c] + cursor[c]++
+// one wavefront per row of P~: entry (r, c, v) goes to slot colptr[c] + cursor[c]++ of the unordered list
 __global__ __launch_bounds__(256) void adjT_fill(const int32_t *__restrict__ adj_rowptr,
                                                  const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
                                                  int32_t nS_bound, const int32_t *__restrict__ nS_dev,
                                                  int32_t n_cols_bound, const int32_t *__restrict__ n_cols_dev,
                                                  const int32_t *__restrict__ colptr, int32_t *__restrict__ cursor,
-                                                 int32_t *__restrict__ rowT, float *__restrict__ valT, int64_t cap)
+                                                 uint2 *__restrict__ unordered, int64_t cap)
 {
     const int32_t nS = resolve_count(nS_bound, nS_dev), n_cols = resolve_count(n_cols_bound, n_cols_dev);
     const int lane = lane_id();
@@ -468,11 +470,103 @@ __global__ __launch_bounds__(256) void adjT_fill(const int32_t *__restrict__ adj
             const int32_t c = adj_col[e];
             if (c >= 0 && c < n_cols) {
                 const int64_t slot = (int64_t)colptr[c] + atomicAdd(&cursor[c], 1);
-                if (slot < cap) {
-                    rowT[slot] = (int32_t)r;
-                    valT[slot] = adj_val[e];
+                if (slot < cap) unordered[slot] = make_uint2((uint32_t)r, __float_as_uint(adj_val[e]));
+            }
+        }
+    }
+}
+
+// Puts the entries of every column into ascending row order: (row, value) from the unordered list into
+// rowT / valT.  A block owns ORD_COLS consecutive columns.  Columns of up to 64 entries are taken by one
+// wavefront each, an entry's place being the number of entries of its column with a smaller row (rows are
+// distinct inside a column).  Longer columns (hubs among the sampled nodes) are then taken by the whole
+// block one at a time: the rows present are marked in a bitmap in LDS, ORD_TILE_ROWS rows at a time, and an
+// entry's place is the number of marked rows below its own.
+constexpr int ORD_COLS = 64;
+constexpr int ORD_TILE_ROWS = 65536;
+constexpr int ORD_TILE_WORDS = ORD_TILE_ROWS / 32;
+
+__global__ __launch_bounds__(256) void adjT_order(const int32_t *__restrict__ colptr, int32_t n_cols_bound,
+                                                  const int32_t *__restrict__ n_cols_dev, int32_t nS_bound,
+                                                  const int32_t *__restrict__ nS_dev, const uint2 *__restrict__ unordered,
+                                                  int32_t *__restrict__ rowT, float *__restrict__ valT, int64_t cap)
+{
+    __shared__ uint32_t bm[ORD_TILE_WORDS];
+    __shared__ int32_t below[ORD_TILE_WORDS];   // marked rows in the words before this one
+    __shared__ int32_t long_cols[ORD_COLS];
+    __shared__ int32_t n_long;
+    __shared__ int32_t scan_lds[17];
+    const int32_t n_cols = resolve_count(n_cols_bound, n_cols_dev), nS = resolve_count(nS_bound, nS_dev);
+    const int tid = (int)threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    if (tid == 0) n_long = 0;
+    __syncthreads();
+    auto extent = [&](int32_t c, int32_t *beg, int32_t *end) {   // stays inside the lists whatever the offsets say
+        const int32_t b = colptr[c], e = colptr[c + 1];
+        *beg = b < 0 ? 0 : b;
+        *end = e < cap ? e : (int32_t)cap;
+    };
+    for (int k = wave; k < ORD_COLS; k += AGG_WAVES) {
+        const int64_t c = (int64_t)blockIdx.x * ORD_COLS + k;
+        if (c >= n_cols) break;
+        int32_t beg, end;
+        extent((int32_t)c, &beg, &end);
+        const int32_t len = end - beg;
+        if (len <= 0) continue;
+        if (len > WAVE) {
+            if (lane == 0) long_cols[atomicAdd(&n_long, 1)] = (int32_t)c;   // in any order: the columns do not meet
+            continue;
+        }
+        const uint2 v = lane < len ? unordered[beg + lane] : make_uint2(0xFFFFFFFFu, 0u);
+        int32_t place = 0;
+        for (int32_t j = 0; j < len; ++j) place += __shfl(v.x, j, WAVE) < v.x ? 1 : 0;
+        if (lane < len) {
+            rowT[beg + place] = (int32_t)v.x;
+            valT[beg + place] = __uint_as_float(v.y);
+        }
+    }
+    __syncthreads();
+    const int32_t cnt = n_long;
+    for (int32_t li = 0; li < cnt; ++li) {
+        int32_t beg, end;
+        extent(long_cols[li], &beg, &end);
+        int32_t base = 0;   // entries of this column with rows below the tile
+        for (int64_t lo = 0; lo < nS; lo += ORD_TILE_ROWS) {
+            const int32_t words = (int32_t)((nS - lo + 31) / 32 < ORD_TILE_WORDS ? (nS - lo + 31) / 32 : ORD_TILE_WORDS);
+            for (int32_t w = tid; w < words; w += AGG_BLOCK) bm[w] = 0u;
+            __syncthreads();
+            for (int32_t e = beg + tid; e < end; e += AGG_BLOCK) {
+                const int64_t d = (int64_t)unordered[e].x - lo;
+                if (d >= 0 && d < (int64_t)words * 32) atomicOr(&bm[d >> 5], 1u << (d & 31));
+            }
+            __syncthreads();
+            int32_t pc[ORD_TILE_WORDS / AGG_BLOCK], sum = 0;
+#pragma unroll
+            for (int k = 0; k < ORD_TILE_WORDS / AGG_BLOCK; ++k) {
+                const int32_t w = tid * (ORD_TILE_WORDS / AGG_BLOCK) + k;
+                pc[k] = w < words ? __popc(bm[w]) : 0;
+                sum += pc[k];
+            }
+            int32_t total;
+            int32_t ex = block_exclusive_scan<int32_t>(sum, scan_lds, &total);
+#pragma unroll
+            for (int k = 0; k < ORD_TILE_WORDS / AGG_BLOCK; ++k) {
+                below[tid * (ORD_TILE_WORDS / AGG_BLOCK) + k] = ex;
+                ex += pc[k];
+            }
+            __syncthreads();
+            for (int32_t e = beg + tid; e < end; e += AGG_BLOCK) {
+                const uint2 v = unordered[e];
+                const int64_t d = (int64_t)v.x - lo;
+                if (d >= 0 && d < (int64_t)words * 32) {
+                    const int32_t place = base + below[d >> 5] + __popc(bm[d >> 5] & ((1u << (d & 31)) - 1u));
+                    if (place < end - beg) {
+                        rowT[beg + place] = (int32_t)v.x;
+                        valT[beg + place] = __uint_as_float(v.y);
+                    }
                 }
             }
+            base += total;
+            __syncthreads();   // the bitmap is cleared for the next tile or column
         }
     }
 }
@@ -485,6 +579,7 @@ __global__ void fill_zero_i32(int32_t *p, int64_t n)
 struct GradScratch {
     int32_t *counts, *colptr, *rowT;
     float *valT;
+    uint2 *unordered;   // (row, value bits) of every entry, grouped by column, in arrival order inside a column
     size_t bytes;
 };
 
@@ -501,6 +596,7 @@ __host__ inline GradScratch carve_grad(void *base, int32_t n_cols_cap, int64_t a
     g.colptr = (int32_t *)take(((size_t)n_cols_cap + 1) * 4);
     g.rowT = (int32_t *)take((size_t)adj_cap * 4);
     g.valT = (float *)take((size_t)adj_cap * 4);
+    g.unordered = (uint2 *)take((size_t)adj_cap * 8);
     g.bytes = off;
     return g;
 }
@@ -629,7 +725,11 @@ extern "C" int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj
     CSGS_LAUNCH(K_ADJT_PREFIX, adjT_prefix, dim3(1), dim3(1024), st, g.counts, n_cols, n_cols_dev, g.colptr);
     CSGS_LAUNCH_CHECK();
     CSGS_LAUNCH(K_ADJT_FILL, adjT_fill, dim3(rb), dim3(256), st, adj_rowptr, adj_col, adj_val, nS, nS_dev, n_cols, n_cols_dev,
-                (const int32_t *)g.colptr, g.counts, g.rowT, g.valT, adj_cap);
+                (const int32_t *)g.colptr, g.counts, g.unordered, adj_cap);
+    CSGS_LAUNCH_CHECK();
+    const unsigned ob = (unsigned)(((int64_t)n_cols + ORD_COLS - 1) / ORD_COLS);
+    CSGS_LAUNCH(K_ADJT_ORDER, adjT_order, dim3(ob), dim3(AGG_BLOCK), st, (const int32_t *)g.colptr, n_cols, n_cols_dev, nS, nS_dev,
+                (const uint2 *)g.unordered, g.rowT, g.valT, adj_cap);
     CSGS_LAUNCH_CHECK();
     // the forward kernel on the transposed structure: rows = columns of P~, gathered table = dZ
     // (its rows are bounded by the row count of P~), output mask = [H_prev > 0]

@@ -4,7 +4,7 @@ Nothing here computes: it allocates torch tensors as device memory, uploads
 the synthetic inputs, and issues the library calls in the order the method
 prescribes (top-down sampling, Sections 4.1-4.2; bottom-up layer compute,
 Eq. 1).  Staging the feature rows of sampled remote nodes stands in for the
-exchange between GPUs (Section 3, "Communication of Feature Vectors").
+exchange between GPUs (Section 3, the paragraph on the transfer of feature vectors).
 """
 from __future__ import annotations
 
