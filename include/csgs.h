@@ -399,6 +399,24 @@ int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t 
                            void *scratch, size_t scratch_bytes, void *stream);
 int csgs_layer_gemm_grad_z(const float *G, int64_t ldg, int32_t M, const int32_t *M_dev, int32_t Nout,
                            const float *W, int64_t ldw, int32_t K, float *dZ, int64_t lddz, void *stream);
+/*
+ * csgs_layer_gemm_grad_w for callers that cannot allocate device memory and have no scratch buffer to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same results as csgs_layer_gemm_grad_w, but the partial sums go to a
+ * buffer of CSGS_GRAD_W_STATIC_BYTES bytes that is part of the library's device image (every GPU the
+ * library runs on holds one until the process ends).  The call allocates and frees nothing.
+ *   - Shapes whose csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout) exceeds CSGS_GRAD_W_STATIC_BYTES
+ *     are rejected with CSGS_EWORKSPACE before anything is enqueued (the five named configurations
+ *     need at most 16.1 MB).
+ *   - All calls on one GPU share that buffer: calls that overlap on one GPU (different streams, or
+ *     one stream's call still running when another stream's starts) race.  Order them.
+ *   - The first call on a device looks up the buffer's address on that device (no allocation); make
+ *     that first call outside graph capture.  CSGS_ELAUNCH if the lookup fails.
+ */
+#define CSGS_GRAD_W_STATIC_BYTES (32u << 20)
+int csgs_layer_gemm_grad_w_static(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M,
+                                  const int32_t *M_dev, int32_t K, int32_t Nout, float *dW, int64_t lddw,
+                                  void *stream);
 size_t csgs_aggregate_grad_scratch_bytes(int32_t n_cols, int64_t adj_cap);
 int csgs_aggregate_grad(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val,
                         int64_t adj_cap, int32_t nS, const int32_t *nS_dev, int32_t n_cols,

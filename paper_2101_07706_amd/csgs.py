@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_workspace_wait_limit", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
-           "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_z",
+           "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_w_static", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect", "csgs_profile_samples",
            "csgs_calib_copy", "csgs_calib_atomics", "csgs_calib_mfma_f64"]
@@ -106,6 +106,7 @@ def lib():
         L.csgs_layer_gemm_grad_w_scratch_bytes.restype = sz
         L.csgs_layer_gemm_grad_w_scratch_bytes.argtypes = [i32, i32, i32]
         L.csgs_layer_gemm_grad_w.argtypes = [vp, i64, vp, i64, i32, vp, i32, i32, vp, i64, vp, sz, vp]
+        L.csgs_layer_gemm_grad_w_static.argtypes = [vp, i64, vp, i64, i32, vp, i32, i32, vp, i64, vp]
         L.csgs_layer_gemm_grad_z.argtypes = [vp, i64, i32, vp, i32, vp, i64, i32, vp, i64, vp]
         L.csgs_aggregate_grad_scratch_bytes.restype = sz
         L.csgs_aggregate_grad_scratch_bytes.argtypes = [i32, i64]
@@ -344,6 +345,18 @@ def csgs_layer_gemm_grad_w(Z, G, dW, scratch, stream=None, M_dev=None):
     assert M == M2 and dW.shape == (K, N)
     _call("csgs_layer_gemm_grad_w", _ptr(Z), Z.stride(0), _ptr(G), G.stride(0), M, _ptr(M_dev), K, N, _ptr(dW), dW.stride(0),
           _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream))
+
+
+GRAD_W_STATIC_BYTES = 32 << 20     # CSGS_GRAD_W_STATIC_BYTES
+
+
+def csgs_layer_gemm_grad_w_static(Z, G, dW, stream=None, M_dev=None):
+    """dW [K x N] = Z^T G with the partial sums in the library's own static device buffer (nothing is allocated)."""
+    M, K = Z.shape
+    M2, N = G.shape
+    assert M == M2 and dW.shape == (K, N)
+    _call("csgs_layer_gemm_grad_w_static", _ptr(Z), Z.stride(0), _ptr(G), G.stride(0), M, _ptr(M_dev), K, N, _ptr(dW), dW.stride(0),
+          _stream(stream))
 
 
 def csgs_layer_gemm_grad_z(G, W, dZ, stream=None, M_dev=None):

@@ -491,15 +491,10 @@ extern "C" size_t csgs_layer_gemm_grad_w_scratch_bytes(int32_t M, int32_t K, int
     return (size_t)parts * (size_t)K * (size_t)Nout * sizeof(double);
 }
 
-extern "C" int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M, const int32_t *M_dev,
-                                      int32_t K, int32_t Nout, float *dW, int64_t lddw, void *scratch, size_t scratch_bytes,
-                                      void *stream)
+// dW = Z^T G with the partial sums in `parts` (device, at least csgs_layer_gemm_grad_w_scratch_bytes bytes)
+static int grad_w_launch(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M, const int32_t *M_dev, int32_t K,
+                         int32_t Nout, float *dW, int64_t lddw, double *parts_buf, hipStream_t st)
 {
-    if (!Z || !G || !dW || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldg < Nout || lddw < Nout || !scratch ||
-        ((uintptr_t)scratch & 7))
-        return CSGS_EINVAL;
-    if (scratch_bytes < csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout)) return CSGS_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
     // kernel terms: output [K x Nout], reduction over the M rows (their count may live on the device)
     const int tm = (K + BM - 1) / BM, tn = (Nout + 31) / 32;
     const int n_tiles = tm * tn;
@@ -508,13 +503,56 @@ extern "C" int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *
     const dim3 grid((unsigned)(((n_tiles + 7) / 8) * 8), (unsigned)parts);
     float *none = nullptr;
     CSGS_LAUNCH(K_GEMM_DW, (gemm_f32_k<32, MODE_DW, 1, false>), grid, dim3(256), st, Z, ldz, G, ldg, none, (int64_t)0,
-                (double *)scratch, K, Nout, M, M_dev, tn, n_tiles, ks, CompStride{0, 0, 0, 0});
+                parts_buf, K, Nout, M, M_dev, tn, n_tiles, ks, CompStride{0, 0, 0, 0});
     CSGS_LAUNCH_CHECK();
     const int64_t count = (int64_t)K * Nout;
     CSGS_LAUNCH(K_GEMM_DW_REDUCE, gemm_reduce_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), st,
-                (const double *)scratch, parts, count, Nout, dW, lddw);
+                (const double *)parts_buf, parts, count, Nout, dW, lddw);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
+}
+
+extern "C" int csgs_layer_gemm_grad_w(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M, const int32_t *M_dev,
+                                      int32_t K, int32_t Nout, float *dW, int64_t lddw, void *scratch, size_t scratch_bytes,
+                                      void *stream)
+{
+    if (!Z || !G || !dW || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldg < Nout || lddw < Nout || !scratch ||
+        ((uintptr_t)scratch & 7))
+        return CSGS_EINVAL;
+    if (scratch_bytes < csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout)) return CSGS_EWORKSPACE;
+    return grad_w_launch(Z, ldz, G, ldg, M, M_dev, K, Nout, dW, lddw, (double *)scratch, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- the same without any allocation
+// The partial sums of csgs_layer_gemm_grad_w_static live in this array, which is part of the library's
+// device image: every device the library runs on holds its own copy, at its own address, until the
+// process ends.  Host code never uses the array's name as an address; the address on the current
+// device is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[CSGS_GRAD_W_STATIC_BYTES];
+static std::atomic<void *> g_static_scratch[64];   // per device; null = not looked up yet (zero-initialised)
+
+// Address of `scratch` on the current device, or null.
+static void *static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void *p = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_static_scratch[dev].store(p, std::memory_order_release);   // every thread would store the same address
+    }
+    return p;
+}
+
+extern "C" int csgs_layer_gemm_grad_w_static(const float *Z, int64_t ldz, const float *G, int64_t ldg, int32_t M,
+                                             const int32_t *M_dev, int32_t K, int32_t Nout, float *dW, int64_t lddw, void *stream)
+{
+    if (!Z || !G || !dW || M <= 0 || K <= 0 || Nout <= 0 || ldz < K || ldg < Nout || lddw < Nout) return CSGS_EINVAL;
+    if (csgs_layer_gemm_grad_w_scratch_bytes(M, K, Nout) > (size_t)CSGS_GRAD_W_STATIC_BYTES) return CSGS_EWORKSPACE;
+    void *parts_buf = static_scratch_ptr();
+    if (!parts_buf) return CSGS_ELAUNCH;
+    // every part that the reduction reads is written by the product kernel of the same call: nothing to clear
+    return grad_w_launch(Z, ldz, G, ldg, M, M_dev, K, Nout, dW, lddw, (double *)parts_buf, (hipStream_t)stream);
 }
 
 static const char *const kErr[] = {"ok",

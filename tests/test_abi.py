@@ -81,6 +81,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.csgs_layer_gemm(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_gather_rows(z, 1, 1, 1, 0, z, 1, z, z, 1, z) == csgs.EINVAL
     assert L.csgs_layer_gemm_grad_w(z, 1, z, 1, 1, z, 1, 1, z, 1, z, 0, z) == csgs.EINVAL
+    assert L.csgs_layer_gemm_grad_w_static(z, 1, z, 1, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_layer_gemm_grad_z(z, 1, 1, z, 1, z, 1, 1, z, 1, z) == csgs.EINVAL
     assert L.csgs_aggregate_grad(z, z, z, 1, 1, z, 1, z, z, 1, 1, z, 1, z, 1, z, 0, z) == csgs.EINVAL
     assert L.csgs_calib_mfma_f64(z, 1 << 20, 1, 0, z) == csgs.EINVAL
@@ -122,6 +123,9 @@ def test_gradient_calls_reject_bad_arguments_before_any_launch():
     # scratch too small
     assert L.csgs_layer_gemm_grad_w(p, 8, p, 8, 64, z, 8, 8, p, 8, p, 16, z) == csgs.EWORKSPACE
     assert L.csgs_aggregate_grad(p, p, p, 100, 10, z, 10, z, p, 8, 8, z, 0, p, 8, p, 16, z) == csgs.EWORKSPACE
+    # partial sums beyond the static buffer of the form that allocates nothing (checked before anything else runs)
+    assert csgs.csgs_layer_gemm_grad_w_scratch_bytes(65536, 2048, 2304) > csgs.GRAD_W_STATIC_BYTES
+    assert L.csgs_layer_gemm_grad_w_static(p, 2048, p, 2304, 65536, z, 2048, 2304, p, 2304, z) == csgs.EWORKSPACE
     # leading dimensions below the row width, misaligned scratch
     assert L.csgs_layer_gemm_grad_z(p, 4, 16, z, 8, p, 8, 8, p, 8, z) == csgs.EINVAL
     assert L.csgs_layer_gemm_grad_w(p, 8, p, 8, 64, z, 8, 8, p, 8, C.c_void_p(4100), 1 << 20, z) == csgs.EINVAL
