@@ -128,22 +128,24 @@ class Workload:
             H = Hn
         return H
 
-    def enqueue_compute_group(self, lbs, n0):
-        """The same for all instances of a buffer set in the same launches (the _n forms of the calls)."""
+    def enqueue_compute_group(self, lbs, n0, kk=None):
+        """The same for the first kk instances (default: all) of a buffer set in the same launches (the _n
+        forms of the calls)."""
         M, B, pipeline = self.M, self.B, self.pipeline
+        kk = self.n_inst if kk is None else kk
         nb = lambda t: t.stride(0) * t.element_size()
-        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.stagedK[0], out_stride=nb(self.stagedK))
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.stagedK[0], out_stride=nb(self.stagedK), n_inst=kk)
         for l in range(M - 1, -1, -1):
             nS = n0 if l == 0 else B
             nS_dev = None if l == 0 else lbs[l - 1].n_next
             Z, H = self.ZsK[l], self.HsK[l]
             if l == M - 1:
                 pipeline.compute_step(lbs[l], nS, self.X_local, self.stagedK[0], True, False, self.Wd[0], Z[0, :nS], H[0, :nS],
-                                      nS_dev=nS_dev, strides=(0, nb(self.stagedK), nb(Z), nb(H)))
+                                      nS_dev=nS_dev, strides=(0, nb(self.stagedK), nb(Z), nb(H)), n_inst=kk)
             else:
                 pipeline.compute_step(lbs[l], nS, self.HsK[l + 1][0, :B], None, False, True, self.Wd[M - 1 - l], Z[0, :nS], H[0, :nS],
-                                      nS_dev=nS_dev, strides=(nb(self.HsK[l + 1]), 0, nb(Z), nb(H)))
-        return self.HsK[0][self.n_inst - 1, :n0]
+                                      nS_dev=nS_dev, strides=(nb(self.HsK[l + 1]), 0, nb(Z), nb(H)), n_inst=kk)
+        return self.HsK[0][kk - 1, :n0]
 
     def prepare_backward(self):
         """Buffers for the gradients of every layer (dW, dZ, dH_prev, scratch), sized for the capacities."""
@@ -204,18 +206,21 @@ class Workload:
                     kernels={k: dict(avg_us=round(v[0] / v[1] * 1e3, 3), launches_per_step=v[1] / steps)
                              for k, v in sorted(prof.items(), key=lambda kv: -kv[1][0])})
 
-    def prepare_overlap(self):
+    def prepare_overlap(self, rem=0):
         """Streams, events and, per buffer set, the library calls of a group of n_inst mini-batches
         captured into two HIP graphs (sampling of all of them at once, layer compute one after the
-        other).  What differs from replay to replay goes through device memory: the set's iteration
-        numbers select its batches from the resident batch table, and the sampling graph advances
-        them itself.  A kernel launch costs the host 4-5 us, so launching a step's kernels one by one
-        cannot keep three streams fed; a replay is one call."""
+        other), and the same for a last, smaller group of `rem` mini-batches when the step count is
+        no multiple of n_inst (same buffers, fewer instances per call).  What differs from replay to
+        replay goes through device memory: the set's iteration numbers select its batches from the
+        resident batch table, and the sampling graph advances them itself.  A kernel launch costs the
+        host 4-5 us, so launching a step's kernels one by one cannot keep three streams fed; a replay
+        is one call."""
         torch, K, dev = self.torch, self.n_inst, self.dev
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
         s_comp = torch.cuda.Stream()
         self.S_all = torch.stack(self.Sd)        # all batches, resident: [n_batches, batch]
         n0 = self.Sd[0].numel()
+        sizes_k = [K] + ([rem] if 0 < rem < K else [])
         sets = []
         for k in range(self.n_sets):
             s_samp = samplers[k % self.n_samplers]
@@ -226,22 +231,24 @@ class Workload:
             idx = torch.arange(K, dtype=torch.int64, device=dev)      # iteration number of every instance
             tmp = torch.zeros((K, n0), dtype=self.S_all.dtype, device=dev)
 
-            def fill(idx=idx, tmp=tmp, S0_all=S0_all, lb0=lb0):
+            def fill(kk, idx=idx, tmp=tmp, S0_all=S0_all, lb0=lb0):
                 if K == 1:      # straight into the row array
                     torch.index_select(self.S_all, 0, idx, out=lb0.S0[:n0].view(1, -1))
                 else:
-                    torch.index_select(self.S_all, 0, idx, out=tmp)   # the batches of these iterations
-                    S0_all.copy_(tmp)
+                    torch.index_select(self.S_all, 0, idx[:kk], out=tmp[:kk])   # the batches of these iterations
+                    S0_all[:kk].copy_(tmp[:kk])
 
-            def sample(idx=idx, lbs=lbs, ws=ws, lb0=lb0, fill=fill):
-                fill()
+            def sample(kk=K, idx=idx, lbs=lbs, ws=ws, lb0=lb0, fill=fill):
+                fill(kk)
+                ws.desc.n_inst = kk       # instances of this call (the descriptor is read when the call is made)
                 self.enqueue_sampling(lb0.S0[:n0], idx, lbs, ws)      # the library reads idx[0]; instance k uses idx[0] + k
+                ws.desc.n_inst = K
 
-            def compute(k=k, lbs=lbs):
+            def compute(kk=K, k=k, lbs=lbs):
                 if self.batch_compute:
-                    return self.enqueue_compute_group(lbs, n0)
+                    return self.enqueue_compute_group(lbs, n0, kk)
                 H = None
-                for lk in self.lb_inst[k]:
+                for lk in self.lb_inst[k][:kk]:
                     H = self.enqueue_compute(lk, n0)
                 return H
 
@@ -253,75 +260,78 @@ class Workload:
             with torch.cuda.stream(s_comp):
                 compute()
             torch.cuda.synchronize()
-            g_samp = g_comp = None
+            graphs = {}
             if self.use_graphs:
                 try:
-                    g_samp, g_comp = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(g_samp, stream=s_samp):
-                        sample()
-                        idx.add_(K * self.n_sets)     # the next replay of this set is n_sets groups later
-                    with torch.cuda.graph(g_comp, stream=s_comp):
-                        compute()
+                    for kk in sizes_k:
+                        g_samp, g_comp = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(g_samp, stream=s_samp):
+                            sample(kk)
+                            if kk == K:
+                                idx.add_(K * self.n_sets)     # the next replay of this set is n_sets groups later
+                        with torch.cuda.graph(g_comp, stream=s_comp):
+                            compute(kk)
+                        graphs[kk] = (g_samp, g_comp)
                 except Exception as e:      # said out loud and recorded in the JSON line; the calls are then issued one by one
                     log(f"graph capture failed ({e!r}); launching the calls directly")
                     self.use_graphs = False
-                    g_samp = g_comp = None
+                    graphs = {}
             torch.cuda.synchronize()
-            sets.append(dict(idx=idx, sample=g_samp, compute=g_comp, sample_fn=sample, compute_fn=compute,
-                             H=self.HsK[0][K - 1, :n0] if self.batch_compute else self.Hs[0][:n0], s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(),
-                             used=False))
+            H_of = lambda kk: self.HsK[0][kk - 1, :n0] if self.batch_compute else self.Hs[0][:n0]
+            sets.append(dict(idx=idx, graphs=graphs, sample_fn=sample, compute_fn=compute, H_of=H_of,
+                             s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
         self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=dev)   # iteration numbers, resident
         self.graph_it = [None] * self.n_sets     # first iteration number each set's counters hold for its next replay
         self.overlap = dict(sets=sets, s_comp=s_comp)
 
-    def group(self, p):
-        """Mini-batches p * n_inst .. (p + 1) * n_inst - 1, enqueued without the host waiting for
-        anything.  Their sampling (top-down) is ONE sequence of library calls over n_inst instances;
-        consecutive groups go round-robin to n_samplers streams, each with its own workspace.  The
-        layer compute (bottom-up) of all batches runs in batch order on one more stream; events tie a
-        group's compute to its sampling and a buffer set's reuse to the compute that read it.  This is
-        how a training loop runs its sampler ahead: sampling does not depend on the model weights,
-        the compute of consecutive batches does.  Every step still does all of its work."""
+    def group(self, it0, kk=None):
+        """Mini-batches it0 .. it0 + kk - 1 (kk = n_inst unless it is the last, smaller group; it0 a
+        multiple of n_inst), enqueued without the host waiting for anything.  Their sampling (top-down)
+        is ONE sequence of library calls over kk instances; consecutive groups go round-robin to
+        n_samplers streams, each with its own workspace.  The layer compute (bottom-up) of all batches
+        runs in batch order on one more stream; events tie a group's compute to its sampling and a
+        buffer set's reuse to the compute that read it.  This is how a training loop runs its sampler
+        ahead: sampling does not depend on the model weights, the compute of consecutive batches does.
+        Every step still does all of its work."""
         torch, K = self.torch, self.n_inst
-        if self.overlap is None:
-            self.prepare_overlap()
-        k = p % self.n_sets
+        kk = K if kk is None else kk
+        k = (it0 // K) % self.n_sets
         st = self.overlap["sets"][k]
         s_comp = self.overlap["s_comp"]
-        it0 = p * K
+        g_samp, g_comp = st["graphs"].get(kk, (None, None))
         if self.one_stream:     # everything in order on the compute stream: every kernel has the device to itself
             with torch.cuda.stream(s_comp):
-                st["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
-                if st["sample"] is not None:
-                    st["sample"].replay()
-                    st["compute"].replay()
+                st["idx"][:kk].copy_(self.it_host[it0:it0 + kk], non_blocking=True)
+                if g_samp is not None:
+                    g_samp.replay()
+                    g_comp.replay()
                 else:
-                    st["sample_fn"]()
-                    st["compute_fn"]()
+                    st["sample_fn"](kk)
+                    st["compute_fn"](kk)
                 self.graph_it[k] = None
-            return st["H"]
+            return st["H_of"](kk)
         with torch.cuda.stream(st["s_samp"]):
             if st["used"]:
                 st["s_samp"].wait_event(st["comp_done"])     # the set is free once the batches sampled into it were computed
-            direct = st["sample"] is None or self.direct     # call by call instead of a graph replay
-            if direct or self.graph_it[k] != it0:   # (re)seat the set's counters; consecutive replays advance them
-                st["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
+            direct = g_samp is None or self.direct     # call by call instead of a graph replay
+            if direct or kk != K or self.graph_it[k] != it0:   # (re)seat the set's counters; consecutive full replays advance them
+                st["idx"][:kk].copy_(self.it_host[it0:it0 + kk], non_blocking=True)
             if not direct:
-                st["sample"].replay()
-                self.graph_it[k] = it0 + K * self.n_sets
+                g_samp.replay()
+                self.graph_it[k] = it0 + K * self.n_sets if kk == K else None
             else:
-                st["sample_fn"]()
+                st["sample_fn"](kk)
                 self.graph_it[k] = None
             st["samp_done"].record(st["s_samp"])
         with torch.cuda.stream(s_comp):
             s_comp.wait_event(st["samp_done"])
-            if st["compute"] is not None and not self.direct:
-                st["compute"].replay()
+            if g_comp is not None and not self.direct:
+                g_comp.replay()
             else:
-                st["compute_fn"]()
+                st["compute_fn"](kk)
             st["comp_done"].record(s_comp)
         st["used"] = True
-        return st["H"]
+        return st["H_of"](kk)
 
     def sizes_of(self, lbs, n0, sizes):
         M, B = self.M, self.B
@@ -346,11 +356,15 @@ class Workload:
         return H
 
     def measure(self, steps, warmup, serial=True):
-        """Timed region (steps and warmup are multiples of n_inst), then the same groups again on
-        one stream with every kernel launch bracketed by HIP events (recorded on the launch stream)."""
+        """Timed region: exactly `steps` steps in groups of n_inst mini-batches, the last group smaller
+        when n_inst does not divide them (warmup is a multiple of n_inst).  Then the full groups again,
+        launched call by call with every kernel launch bracketed by HIP events (recorded on the launch
+        stream): every launch these passes time handles n_inst mini-batches, whatever `steps` is."""
         torch, csgs, K = self.torch, self.csgs, self.n_inst
-        assert steps % K == 0 and warmup % K == 0 and len(self.Sd) >= steps + warmup
+        assert steps >= K and warmup % K == 0 and len(self.Sd) >= steps + warmup
         n0 = self.Sd[0].numel()
+        chunks = [(it0, min(K, warmup + steps - it0)) for it0 in range(warmup, warmup + steps, K)]
+        full = [c for c in chunks if c[1] == K]
         # (1) one stream, one mini-batch per call, steps back to back: the latency of a step
         serial_ms, h_serial = None, None
         if serial:
@@ -365,13 +379,13 @@ class Workload:
             h_serial = H.clone()
         # (2) the timed region proper: the same steps, n_inst per sampling call, sampling and compute overlapped
         if self.overlap is None:
-            self.prepare_overlap()
-        for p in range(warmup // K):
-            self.group(p)
+            self.prepare_overlap(rem=steps % K)
+        for it0 in range(0, warmup, K):
+            self.group(it0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for p in range(warmup // K, (warmup + steps) // K):
-            H = self.group(p)
+        for it0, kk in chunks:
+            H = self.group(it0, kk)
         enqueue_ms = (time.perf_counter() - t0) / steps * 1e3     # host time to enqueue a step (no waiting in it)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
@@ -380,38 +394,56 @@ class Workload:
         assert all(int(lb.status.item()) == 0 for set_ in self.lb_inst for lk in set_ for lb in lk), \
             "a status bit was set in the timed run"
         log(f"host enqueue {enqueue_ms:.3f} ms/step; " + (f"one stream, one batch per call {serial_ms:.3f} ms/step; " if serial else "") +
-            f"{K} batches per sampling call, " + ("everything in order on one stream" if self.one_stream else "sampling and compute overlapped") +
+            f"{K} batches per sampling call" + (f" (last group {chunks[-1][1]})" if chunks[-1][1] != K else "") + ", " +
+            ("everything in order on one stream" if self.one_stream else "sampling and compute overlapped") +
             f" {ms_per_step:.3f} ms/step")
-        # (3) how long the kernels take inside the timed schedule, beside the kernels of the other streams: the same
+        # (3) how long the kernels take inside the timed schedule, beside the kernels of the other streams: the full
         # groups on the same streams, launched call by call so that every dispatch carries its pair of events (the
         # host stays well ahead of the device)
         prof_sched = {}
+        n_rep = max(1, -(-16 // len(full)))      # at least 16 groups in each per-kernel pass
         if not self.one_stream:
             csgs.csgs_profile_enable(True)
             self.direct = True
-            for p in range(warmup // K, (warmup + steps) // K):
-                self.group(p)
+            for _ in range(n_rep):
+                for it0, kk in full:
+                    self.group(it0, kk)
             torch.cuda.synchronize()
             self.direct = False
             csgs.csgs_profile_enable(False)
             prof_sched = csgs.csgs_profile_collect()
-        # (4) the same groups once more on one stream: sizes of every step, and every kernel's own duration (the device
-        # to itself) -- what the roofline figures are taken from
-        sizes = []
+        # (4) the full groups again on one stream, back to back without the host reading anything in between (the device
+        # stays busy as in the timed region), at least 16 groups: every kernel's own duration with the device to itself
+        # -- what the roofline figures are taken from.  Then once more, untimed, with a wait after every group to read
+        # the sizes of every step (they depend on the iteration numbers only)
         st0 = self.overlap["sets"][0]
+        st0["idx"].copy_(self.it_host[full[0][0]:full[0][0] + K])
+        st0["sample_fn"]()
+        st0["compute_fn"]()
+        torch.cuda.synchronize()
         csgs.csgs_profile_enable(True)
-        for p in range(warmup // K, (warmup + steps) // K):
-            st0["idx"].copy_(self.it_host[p * K:(p + 1) * K])
+        for _ in range(n_rep):
+            for it0, kk in full:
+                st0["idx"].copy_(self.it_host[it0:it0 + K], non_blocking=True)
+                st0["sample_fn"]()
+                st0["compute_fn"]()
+        torch.cuda.synchronize()
+        csgs.csgs_profile_enable(False)
+        samples = csgs.csgs_profile_samples()
+        prof = csgs.csgs_profile_collect()
+        sizes = []
+        for it0, kk in full:
+            st0["idx"].copy_(self.it_host[it0:it0 + K])
             st0["sample_fn"]()
             st0["compute_fn"]()
             torch.cuda.synchronize()
             for lk in self.lb_inst[0]:
                 self.sizes_of(lk, n0, sizes)
-        csgs.csgs_profile_enable(False)
         self.graph_it[0] = None
-        samples = csgs.csgs_profile_samples()
-        prof = csgs.csgs_profile_collect()
         assert all(s["status"] == 0 for s in sizes), "a status bit was set"
+        sizes_once = sizes
+        sizes = sizes * n_rep       # what the timed launches of pass (4) processed
+        steps = n_rep * len(full) * K       # the steps the per-kernel passes covered: what the averages below are over
         alg, flops = {}, 0.0
         for s in sizes:
             for k, b in algorithmic_bytes(s, self.g.n_nodes).items():
@@ -450,29 +482,66 @@ class Workload:
             per_layer.append(dict(layer=l, rows=avg("nS"), edges_scanned=avg("E"), candidates=avg("nc"), sampled_nodes=avg("n_next"),
                                   sampled_edges=avg("nnz"), remote_nodes=avg("remote"), F_in=ls[0]["F_in"], F_out=ls[0]["F_out"]))
         per_step["per_layer"] = per_layer
-        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes,
-                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF)
+        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes_once,
+                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF, last_group=chunks[-1][1])
 
 
-def roofline_of(kernels, name, traffic):
+MFMA_F32_PEAK_TFLOPS = 157.3    # the fp32 matrix peak, for comparison: the GEMM's inputs and outputs are fp32
+
+
+def roofline_of(kernels, name, traffic, k_inst):
+    """Roofline object of one kernel.  traffic: (bytes per launch by kernel name or None, where from / why not)."""
     k = kernels[name]
     if name == "layer_gemm":
         r = dict(bound="mfma", kernel=name, achieved=k["TFLOPs"], peak=MFMA_F64_PEAK_TFLOPS, unit="TFLOP/s",
-                 frac=k["TFLOPs"] / MFMA_F64_PEAK_TFLOPS, alg_per_launch=k["flop_per_launch"])
+                 frac=k["TFLOPs"] / MFMA_F64_PEAK_TFLOPS, alg_per_launch=k["flop_per_launch"],
+                 peak_is="fp64 matrix cores (the kernel multiplies and accumulates in double)",
+                 frac_of_fp32_matrix_peak=k["TFLOPs"] / MFMA_F32_PEAK_TFLOPS)
     else:
         a = k.get("alg_GBps", 0.0)
         r = dict(bound="hbm", kernel=name, achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS,
                  alg_per_launch=k["alg_bytes_per_launch"])
-    r["traffic"] = (traffic or {}).get(name)
+    table, note = traffic
+    r["traffic"] = (table or {}).get(name)
+    r["traffic_source"] = note
     r["avg_launch_us"] = k["avg_us"]
+    r["mini_batches_per_launch"] = k_inst
     return r
 
 
-def load_traffic(key):
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+def load_traffic(workload, k_inst):
+    """HBM bytes per launch and kernel from the committed counter summary profiles/<workload>_step_hbm_traffic.txt,
+    if that summary was taken with the same number of mini-batches per launch; else (None, why)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_step_hbm_traffic.txt")
     if not os.path.exists(path):
-        return None
-    return json.load(open(path)).get(key)
+        return None, f"no counter summary for workload {workload} under profiles/"
+    lines = open(path).read().splitlines()
+    import re
+    m = re.search(r"(\d+) mini-batch(?:es)? per launch", lines[0]) if lines else None
+    if not m:
+        return None, f"{os.path.basename(path)} does not state its mini-batches per launch"
+    if int(m.group(1)) != k_inst:
+        return None, f"{os.path.basename(path)} was taken with {m.group(1)} mini-batches per launch, this run uses {k_inst}"
+    table, in_table = {}, False
+    for ln in lines:
+        f = ln.split()
+        if f[:1] == ["kernel"]:
+            in_table = True
+        elif in_table and len(f) == 5:
+            table[f[0]] = float(f[4]) * 1e6
+        elif in_table and not f:
+            break
+    return table, f"profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on the copy kernel; {k_inst} mini-batches per launch)"
+
+
+def cpu_model():
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.lower().startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main():
@@ -522,12 +591,11 @@ def main():
     Xd = torch.from_numpy(Xh).to(dev)
     mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
                                    batch_compute=not args.no_batch_compute)
-    # a step is one mini-batch; the timed schedule handles K of them per call.  Exactly --steps steps are
-    # timed, so K is the largest count up to --instances that divides them; the (untimed) warm-up is
-    # rounded up to a multiple of K
-    K = max(k for k in range(1, max(1, args.instances) + 1) if args.steps % k == 0)
-    if K != args.instances:
-        log(f"{K} instead of {args.instances} mini-batches per call: the largest count that divides {args.steps} steps")
+    # a step is one mini-batch; the timed schedule handles K of them per call, whatever --steps is: exactly --steps
+    # steps are timed, the last group being smaller when K does not divide them, and the per-kernel timing passes
+    # (what the roofline figures come from) cover the full groups only.  The (untimed) warm-up is rounded up to a
+    # multiple of K
+    K = max(1, min(args.instances, args.steps))
     args.warmup = (args.warmup + K - 1) // K * K
 
     # copy-kernel yardstick (also the known-size kernel for calibrating byte counters)
@@ -585,7 +653,7 @@ def main():
     ms_per_step = res["ms_per_step"]
     log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
     dominant = next(iter(res["kernels"]))
-    roofline = roofline_of(res["kernels"], dominant, load_traffic(name))
+    roofline = roofline_of(res["kernels"], dominant, load_traffic(name, K), K)
     roofline["copy_kernel_GBps"] = copy_GBps
     roofline["atomic_adds_Gps"] = atomic_Gups      # what bounds scan_edges: one such add per scanned edge
     roofline["mfma_f64_loop_TFLOPs"] = mfma_TF[False]       # the GEMM's instruction back to back, operands in registers
@@ -598,6 +666,14 @@ def main():
     if not args.no_cpu_baseline:
         import chain
         n_cpu = N_CPU
+        # the oracle is single-threaded: keep it on one core for the leg (restored afterwards)
+        pinned = None
+        try:
+            allowed = sorted(os.sched_getaffinity(0))
+            pinned = allowed[len(allowed) // 2]
+            os.sched_setaffinity(0, {pinned})
+        except (AttributeError, OSError):
+            allowed = None
         t0 = time.perf_counter()
         cpu_nnz = 0
         for it in range(args.warmup, args.warmup + n_cpu):
@@ -608,9 +684,12 @@ def main():
                     got = res["sizes"][l]
                     assert got["n_next"] == o.sm.n_next and got["nnz"] == o.sm.adj_nnz and got["remote"] == o.rc.remote_total
         cpu_s = time.perf_counter() - t0
+        if pinned is not None:
+            os.sched_setaffinity(0, set(allowed))
         cpu_baseline = dict(value=cpu_nnz / cpu_s, unit="sampled edges/s", cores=1, kind="oracle",
                             sample=f"{n_cpu} whole steps of the same workload ({cpu_s:.1f} s)",
-                            ms_per_step=cpu_s / n_cpu * 1e3)
+                            ms_per_step=cpu_s / n_cpu * 1e3, nproc=os.cpu_count(), cpu_model=cpu_model(),
+                            pinned_to_core=pinned)
         log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
     backward = None
@@ -642,13 +721,13 @@ def main():
         sc = 16
         cfg_s = dataclasses.replace(cfg, batch=cfg.batch * sc, samples=cfg.samples * sc)
         rs = mk(cfg_s, 8, 1).measure(6, 2)
-        tr = load_traffic(f"{cfg.name}_x{sc}")
+        tr = load_traffic(f"{cfg.name}_x{sc}", 1)
         shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_emit")
         scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
                       ms_per_step=rs["ms_per_step"], one_stream_ms_per_step=rs["serial_ms_per_step"],
                       sampled_edges_per_s=rs["per_step"]["sampled_edges"] / (rs["ms_per_step"] * 1e-3),
                       per_step=rs["per_step"], aggregate_GBps=rs["aggregate_GBps"], gemm_TFLOPs=rs["gemm_TFLOPs"],
-                      rooflines=[roofline_of(rs["kernels"], k, tr) for k in rs["kernels"] if k in shown],
+                      rooflines=[roofline_of(rs["kernels"], k, tr, 1) for k in rs["kernels"] if k in shown],
                       kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in rs["kernels"].items()})
         log(f"scaled x{sc}: {rs['ms_per_step']:.3f} ms/step, aggregate {rs['aggregate_GBps']:.0f} GB/s, "
             f"gemm {rs['gemm_TFLOPs']:.1f} TFLOP/s")
@@ -665,6 +744,7 @@ def main():
                     precision=("bf16 features, " if bf16 else "f32 features, ") + "u64 fixed-point weights and CDF, f64 accumulation, f32 outputs",
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
+        mini_batches_per_call=K, last_group=res["last_group"],
         schedule=(f"{K} consecutive mini-batches per library call, sampling then compute of every group in order on one stream; each part "
                   if args.one_stream else
                   f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "

@@ -124,29 +124,31 @@ def sample_step(dg, ws, S, skew, B, seed, it, layer, lb, stream=None, want_q=Tru
                                lb.per_part, lb.src_row, lb.remote_ids, stream)
 
 
-def instance_strides(lb, x, x_remote, out):
-    """csgs_inst_strides for a compute call on all instances of `lb` at once: x / x_remote / out are
-    the byte strides between the instances' input, staged and output matrices (0 = shared)."""
-    return csgs.InstStrides(lb.n_inst, 0, lb.stride, x, x_remote, out)
+def instance_strides(lb, x, x_remote, out, n_inst=None):
+    """csgs_inst_strides for a compute call on all instances of `lb` at once (or on its first n_inst):
+    x / x_remote / out are the byte strides between the instances' input, staged and output matrices
+    (0 = shared)."""
+    return csgs.InstStrides(lb.n_inst if n_inst is None else n_inst, 0, lb.stride, x, x_remote, out)
 
 
-def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None, strides=None):
+def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None, strides=None, n_inst=None):
     """csgs_aggregate -> csgs_layer_gemm for one layer; Z and H are preallocated [nS, F] / [nS, F_out].
     nS_dev: as in sample_step (nS is then the capacity).
-    strides = (x, x_remote, z, h) in bytes: all instances of `lb` in the same two launches; the
-    tensors passed are instance 0's."""
+    strides = (x, x_remote, z, h) in bytes: all instances of `lb` (or its first n_inst) in the same two
+    launches; the tensors passed are instance 0's."""
     agg = gemm = None
     if strides is not None:
         x, xr, z, h = strides
-        agg, gemm = instance_strides(lb, x, xr, z), instance_strides(lb, z, 0, h)
+        agg, gemm = instance_strides(lb, x, xr, z, n_inst), instance_strides(lb, z, 0, h, n_inst)
     csgs.csgs_aggregate(lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.n_next, X_local, X_remote,
                         lb.src_row if use_src_row else None, relu, Z, stream, nS_dev=nS_dev, inst=agg)
     csgs.csgs_layer_gemm(Z, W, H, stream, M_dev=nS_dev, inst=gemm)
 
 
-def stage_remote_rows(lb, X, staged, stream=None, out_stride=None):
+def stage_remote_rows(lb, X, staged, stream=None, out_stride=None, n_inst=None):
     """Fills `staged` [B, F] with the feature rows of the sampled remote nodes (csgs_gather_rows over the
     request list): the one-GPU stand-in for the exchange between partitions.
-    out_stride (bytes): all instances of `lb` in one launch, instance k's rows at staged + k * out_stride."""
-    inst = instance_strides(lb, 0, 0, out_stride) if out_stride is not None else None
+    out_stride (bytes): all instances of `lb` (or its first n_inst) in one launch, instance k's rows at
+    staged + k * out_stride."""
+    inst = instance_strides(lb, 0, 0, out_stride, n_inst) if out_stride is not None else None
     csgs.csgs_gather_rows(X, lb.remote_ids, lb.remote_total, staged, stream, inst=inst)
