@@ -20,46 +20,79 @@ struct Vec {
     float x[V];
 };
 
+// Rows of the gathered tables are read through pointers that come out of LDS or a lane exchange as plain
+// integers; the loads say that they go to global memory (a pointer of unknown kind would be read with the
+// slower flat instructions, which every wait for LDS data would then wait for as well).
+#define CSGS_GLOBAL __attribute__((address_space(1)))
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename U>
+__device__ inline U load_global(const void *p)
+{
+    return *reinterpret_cast<const CSGS_GLOBAL U *>((uintptr_t)p);
+}
+
 template <typename T, int V>
 __device__ inline Vec<V> load_row(const T *p);
 
 template <>
-__device__ inline Vec<1> load_row<float, 1>(const float *p) { return Vec<1>{{p[0]}}; }
+__device__ inline Vec<1> load_row<float, 1>(const float *p) { return Vec<1>{{load_global<float>(p)}}; }
 template <>
 __device__ inline Vec<2> load_row<float, 2>(const float *p)
 {
-    const float2 v = *reinterpret_cast<const float2 *>(p);
+    const f32x2 v = load_global<f32x2>(p);
     return Vec<2>{{v.x, v.y}};
 }
 template <>
 __device__ inline Vec<4> load_row<float, 4>(const float *p)
 {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
+    const f32x4 v = load_global<f32x4>(p);
     return Vec<4>{{v.x, v.y, v.z, v.w}};
+}
+template <>
+__device__ inline Vec<8> load_row<float, 8>(const float *p)   // two 16-byte loads
+{
+    const f32x4 a = load_global<f32x4>(p), b = load_global<f32x4>(p + 4);
+    return Vec<8>{{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
 }
 // bfloat16 bit patterns: widening is a 16-bit left shift
 template <>
-__device__ inline Vec<1> load_row<uint16_t, 1>(const uint16_t *p) { return Vec<1>{{__uint_as_float((uint32_t)p[0] << 16)}}; }
+__device__ inline Vec<1> load_row<uint16_t, 1>(const uint16_t *p) { return Vec<1>{{__uint_as_float((uint32_t)load_global<uint16_t>(p) << 16)}}; }
 template <>
 __device__ inline Vec<2> load_row<uint16_t, 2>(const uint16_t *p)
 {
-    const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+    const uint32_t v = load_global<uint32_t>(p);
     return Vec<2>{{__uint_as_float(v << 16), __uint_as_float(v & 0xFFFF0000u)}};
 }
 template <>
 __device__ inline Vec<4> load_row<uint16_t, 4>(const uint16_t *p)
 {
-    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    const u32x2 v = load_global<u32x2>(p);
     return Vec<4>{{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
                    __uint_as_float(v.y & 0xFFFF0000u)}};
 }
+template <>
+__device__ inline Vec<8> load_row<uint16_t, 8>(const uint16_t *p)
+{
+    const u32x4 v = load_global<u32x4>(p);
+    return Vec<8>{{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                   __uint_as_float(v.y & 0xFFFF0000u), __uint_as_float(v.z << 16), __uint_as_float(v.z & 0xFFFF0000u),
+                   __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xFFFF0000u)}};
+}
 
-constexpr int LONG_ROW = 32;    // rows with more kept edges than this are taken by whole blocks
-constexpr int UNR = 4;          // gathered rows in flight per lane: with 8 the kernel needs more than 64 registers, which
-                                // halves the blocks a compute unit holds, and the rows in flight on the device set its rate
+constexpr int LONG_ROW = 256;   // rows with more kept edges than this are taken by the whole block, after its tiles
+template <int V>
+constexpr int unr() { return V >= 8 ? 2 : 4; }   // gathered row pieces asked for at a time per lane (and as many again before those are used): 64 bytes
 constexpr int AGG_BLOCK = 256;  // threads per block.  Small blocks on purpose: beside kernels of other streams a 1024-thread
                                 // block waits until one compute unit has 16 wavefront places free at once and the kernel starves
 constexpr int AGG_WAVES = AGG_BLOCK / WAVE;
+constexpr int POOL = 256;       // edges a wavefront stages at a time
+
+// Reads that must not count (an edge whose column or source row lies outside the tables, a lane whose share of
+// the edges has ended) go here: zeros, so that they add 0 * 0 without a test.  At least 64 lanes x 8 floats.
+static __device__ __align__(256) uint32_t g_zero_row[512];
 
 // Resolves edge e to (source row pointer, weight); a null pointer marks an edge that must not be read.
 template <typename T>
@@ -91,6 +124,7 @@ template <typename T, int V, bool RELU>
 __device__ inline void accumulate_staged(double (&acc)[V], const T *src, float w, int gbase, int32_t n_here,
                                          int32_t n_max, bool active, int32_t f)
 {
+    constexpr int UNR = unr<V>();
     for (int32_t j0 = 0; j0 < n_max; j0 += UNR) {
         Vec<V> x[UNR];
         float wj[UNR];
@@ -132,161 +166,341 @@ __device__ inline void apply_mask(double (&acc)[V], const float *__restrict__ m)
 template <int V>
 __device__ inline void store_row(float *z, const double (&acc)[V])
 {
-    if (V == 4)
-        *reinterpret_cast<float4 *>(z) = make_float4((float)acc[0], (float)acc[1], (float)acc[V > 2 ? 2 : 0],
-                                                     (float)acc[V > 3 ? 3 : 0]);
-    else if (V == 2)
+    if (V >= 4) {
+#pragma unroll
+        for (int q = 0; q + 4 <= V; q += 4)
+            *reinterpret_cast<float4 *>(z + q) = make_float4((float)acc[q], (float)acc[q + 1 < V ? q + 1 : 0], (float)acc[q + 2 < V ? q + 2 : 0],
+                                                             (float)acc[q + 3 < V ? q + 3 : 0]);
+    } else if (V == 2) {
         *reinterpret_cast<float2 *>(z) = make_float2((float)acc[0], (float)acc[V > 1 ? 1 : 0]);
-    else
+    } else {
         z[0] = (float)acc[0];
+    }
 }
 
-// Ordinary rows: block `bid` of AGG_BLOCK threads owns AGG_BLOCK / G consecutive rows.
+// A staged edge: where its piece of the gathered row starts (source row resolved, the block's feature slice added;
+// a lane adds its own offset inside the slice), its P~ value, and where it stands in its row.
+struct __align__(16) StagedEdge {
+    uint64_t ptr;
+    float w;
+    uint32_t tag;   // row in the tile << 2 | first edge of its row << 1 | last edge of its row
+};
+
+// What a wavefront keeps in LDS about its tile of TR output rows.  The kept edges of the tile's ordinary rows
+// are staged here in row order, already resolved, up to POOL at a time.  The NG lane groups of the wavefront
+// (G lanes each, spread over the slice's features) then take equal shares of the staged edges, whatever rows
+// they belong to, and stream through them; a row whose edges fall into several shares is put together from the
+// groups' partial sums afterwards, in group order.
+template <int TR>
+struct WaveStage {
+    StagedEdge pool[POOL + 1];   // [POOL]: the edge that does not count (zeros, weight 0, ends no row)
+    int32_t beg[TR];             // first edge of the row
+    int32_t len[TR];             // staged edges of the row: 0 for rows past the end and for long rows
+    int32_t xs[TR + 1];          // exclusive prefix of len over the tile
+    int32_t head_state[16];      // per group: how its share begins (see HEAD_*)
+    int32_t carry_row;           // row (in the tile) of the partial sum carried into the next POOL edges, -1: none
+    uint8_t ordinary[TR];        // 1: a row of this call that is not long
+};
+enum { HEAD_NONE = 0,    // the share begins with the first edge of a row
+       HEAD_CLOSED = 1,  // it begins inside a row, and that row's last edge is in the share: head = the row's edges in the share
+       HEAD_OPEN = 2 };  // every edge of the share (possibly none) belongs to a row that began earlier and goes on: head = all of them
+
+constexpr int tile_rows(int G) { return (WAVE / G) * 8 < WAVE ? (WAVE / G) * 8 : WAVE; }   // about 8 rows per lane group
+constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n / 2); }
+
+// One wavefront, one tile of TR output rows, one slice of G * V features starting at feature `slice0`.
+// head: LDS, WAVE * V doubles; carry: LDS, 2 * G * V doubles.
 template <typename T, int V, int G, bool RELU>
-__device__ inline bool aggregate_rows(int64_t bid, const int32_t *__restrict__ adj_rowptr,
-                                      const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
-                                      int32_t nS_bound, const int32_t *__restrict__ nS_dev,
-                                      const int32_t *__restrict__ n_cols_p, int64_t n_cols_default, int32_t *nS_out,
-                                      int64_t *n_cols_out, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
-                                      const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
-                                      const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z, int64_t ldz,
-                                      const float *__restrict__ mask, int64_t ldm)
+__device__ inline bool aggregate_tile(WaveStage<tile_rows(G)> &st, double *__restrict__ head, double *__restrict__ carry, int64_t row0,
+                                      int32_t slice0, int32_t f, bool active, const int32_t *__restrict__ adj_rowptr,
+                                      const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val, int32_t nS_bound,
+                                      int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl, int64_t rows_l,
+                                      const T *__restrict__ Xr, int64_t ldr, int64_t rows_r, const int32_t *__restrict__ src_row,
+                                      float *__restrict__ Z, int64_t ldz, const float *__restrict__ mask, int64_t ldm)
 {
-    const int tid = (int)threadIdx.x;
-    const int g = tid & (G - 1);  // lane within the row group
-    const int gbase = tid & (WAVE - 1) & ~(G - 1);
-    const int64_t row = (bid * AGG_BLOCK + tid) / G;
-    // The two counts that may live on the device and the row's extent are asked for together, before any of
-    // them is used: one load latency instead of three in a row.  The row pointers have nS_bound + 1 entries
-    // whatever the count says; a count that is not given is read from a stand-in address and dropped.
-    const int64_t row_c = row < nS_bound ? row : (int64_t)nS_bound - 1;
-    const int32_t nS_raw = *(nS_dev ? nS_dev : adj_rowptr);
-    const int32_t n_cols_raw = *(n_cols_p ? n_cols_p : adj_rowptr);
-    int32_t beg = adj_rowptr[row_c], end = adj_rowptr[row_c + 1];
-    const int32_t nS = !nS_dev ? nS_bound : (nS_raw < 0 ? 0 : (nS_raw < nS_bound ? nS_raw : nS_bound));
-    const int64_t n_cols = n_cols_p ? (int64_t)n_cols_raw : n_cols_default;
-    *nS_out = nS;
-    *n_cols_out = n_cols;
-    // Rows past the end, and long rows (left to the block's second pass), take part in the lane broadcasts of
-    // their wavefront with an empty range.
-    if (row >= nS) { beg = 0; end = 0; }
-    const bool is_long = row < nS && (end - beg) > LONG_ROW;
-    const bool mine = row < nS && !is_long;
-    if (!mine) end = beg;
-    // trip count of the edge loop must be uniform over the wavefront when G < 64
-    const int32_t len = end - beg;
-    int32_t maxlen = len;
-    if (G < 64) {
+    constexpr int NG = WAVE / G;   // lane groups per wavefront
+    constexpr int TR = tile_rows(G);
+    constexpr int UNR = unr<V>();
+    const int lane = lane_id();
+    // ---- lane l < TR looks at row l of the tile
+    const int64_t row = row0 + lane;
+    const int64_t row_c = row < nS_bound ? row : (int64_t)nS_bound - 1;   // the row pointers have nS_bound + 1 entries
+    const int32_t rbeg = adj_rowptr[row_c], rend = adj_rowptr[row_c + 1];
+    const bool in_call = lane < TR && row < nS;
+    const int32_t full_len = in_call ? rend - rbeg : 0;
+    const bool is_long = full_len > LONG_ROW;
+    const int32_t len = (is_long || full_len < 0) ? 0 : full_len;
+    const int32_t incl = wave_inclusive_scan(len);
+    if (lane < TR) {
+        st.beg[lane] = rbeg;
+        st.len[lane] = len;
+        st.xs[lane + 1] = incl;
+        st.ordinary[lane] = (in_call && !is_long) ? 1 : 0;
+    }
+    if (lane == 0) {
+        st.xs[0] = 0;
+        st.carry_row = -1;
+        st.pool[POOL] = StagedEdge{(uint64_t)(uintptr_t)g_zero_row, 0.f, 0u};
+    }
+    const int32_t total = __builtin_amdgcn_readlane(incl, WAVE - 1);
+    const int grp = lane / G;
+    int par = 0;   // which half of `carry` the next round reads
+    const uint32_t lane_off = active ? (uint32_t)((lane % G) * V * (int)sizeof(T)) : 0u;   // a lane past the last feature reads the slice's start and stores nothing
+    __builtin_amdgcn_wave_barrier();
+    // ---- rows without kept edges are zero rows
+    for (int rr = grp; rr < TR; rr += NG) {
+        if (st.ordinary[rr] && st.len[rr] == 0 && active) {
+            double zero[V];
 #pragma unroll
-        for (int off = G; off < WAVE; off <<= 1) {
-            const int32_t o = __shfl_xor(maxlen, off, WAVE);
-            maxlen = o > maxlen ? o : maxlen;
+            for (int v = 0; v < V; ++v) zero[v] = 0.0;
+            store_row<V>(Z + (row0 + rr) * ldz + f, zero);
         }
     }
-    {   // feature chunk blockIdx.y: wide rows are spread over several blocks instead of walked chunk by chunk
-        const int32_t f0 = (int32_t)blockIdx.y * G * V;
-        const int32_t f = f0 + g * V;
-        const bool active = f < F;  // F is a multiple of V (checked on the host)
+    auto finish_row = [&](double (&sum)[V], int r) {   // rounds and stores row r of the tile
+        const int64_t out = row0 + r;
+        if (active) {
+            if (mask) apply_mask<V>(sum, mask + out * ldm + f);
+            store_row<V>(Z + out * ldz + f, sum);
+        }
+    };
+    for (int32_t cb = 0; cb < total; cb += POOL) {
+        const int32_t S = (total - cb) < POOL ? (total - cb) : POOL;   // edges staged this time: wave-uniform
+        __builtin_amdgcn_wave_barrier();
+        // ---- stage them: one edge per lane and round, two rounds at a time with their loads asked for together
+        // (column and value, then the source row)
+        for (int32_t s0 = 0; s0 < S; s0 += 2 * WAVE) {
+            uint32_t e[2], tg[2];
+            int32_t c[2];
+            float w[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int32_t s = s0 + k * WAVE + lane;
+                const int32_t sa = cb + (s < S ? s : S - 1);   // a lane beyond the end repeats the last edge and stores nothing
+                int lo = 0, hi = TR;   // the row r with xs[r] <= sa < xs[r + 1]
+#pragma unroll
+                for (int step = 0; step < ilog2(TR); ++step) {
+                    const int m = (lo + hi) >> 1;
+                    if (st.xs[m] <= sa) lo = m; else hi = m;
+                }
+                const int32_t d = sa - st.xs[lo];
+                e[k] = (uint32_t)(st.beg[lo] + d);
+                tg[k] = ((uint32_t)lo << 2) | (d == 0 ? 2u : 0u) | (d + 1 == st.len[lo] ? 1u : 0u);
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                c[k] = adj_col[e[k]];
+                w[k] = adj_val[e[k]];
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const bool col_ok = c[k] >= 0 && c[k] < n_cols;
+                const uint32_t cc = col_ok ? (uint32_t)c[k] : 0u;
+                c[k] = src_row ? src_row[cc] : (int32_t)cc;        // from here on: the source row
+                if (!col_ok) c[k] = (int32_t)0x80000000;
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int32_t s = s0 + k * WAVE + lane;
+                if (s < S) {
+                    StagedEdge se;
+                    se.ptr = (uint64_t)(uintptr_t)g_zero_row;
+                    se.w = 0.f;
+                    if (c[k] != (int32_t)0x80000000) {
+                        if (c[k] >= 0 && c[k] < rows_l) {
+                            se.ptr = (uint64_t)(uintptr_t)(Xl + (int64_t)c[k] * ldl + slice0);
+                            se.w = w[k];
+                        } else if (c[k] < 0 && -1 - (int64_t)c[k] < rows_r) {
+                            se.ptr = (uint64_t)(uintptr_t)(Xr + (-1 - (int64_t)c[k]) * ldr + slice0);
+                            se.w = w[k];
+                        }
+                    }
+                    se.tag = tg[k];
+                    st.pool[s] = se;
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- every group streams through its share [lo, hi) of the staged edges: UNR pieces of gathered rows asked for
+        // per lane, and UNR more before those are used; sums in double in edge order
+        const int32_t lo = (int32_t)(((int64_t)grp * S) / NG), hi = (int32_t)(((int64_t)(grp + 1) * S) / NG);
+        const int32_t L = hi - lo;
+        const int32_t Lmax = (S + NG - 1) / NG;   // no share is longer
         double acc[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[v] = 0.0;
-        for (int32_t c0 = 0; c0 < maxlen; c0 += G) {
-            // stage up to G edges of this row: one per lane
-            const int32_t e = beg + c0 + g;
-            const T *src = nullptr;
-            float w = 0.f;
-            if (e < end) resolve_edge<T>(e, adj_col, adj_val, n_cols, src_row, Xl, ldl, rows_l, Xr, ldr, rows_r, &src, &w);
-            const int32_t n_here = (len - c0) < G ? (len - c0) : G;  // edges of my row in this chunk (may be <= 0)
-            const int32_t n_max = (maxlen - c0) < G ? (maxlen - c0) : G;
-            accumulate_staged<T, V, RELU>(acc, src, w, gbase, n_here, n_max, active, f);
+        bool in_head = L == 0 || !(st.pool[lo].tag & 2u);   // my share begins inside a row that an earlier share (or the edges staged before) began
+        int32_t my_head = in_head ? HEAD_OPEN : HEAD_NONE;
+        struct Batch {
+            Vec<V> x[UNR];
+            float w[UNR];
+            uint32_t tg[UNR];
+        };
+        auto issue = [&](int32_t t0, Batch &bt) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int32_t t = t0 + u;
+                const StagedEdge se = st.pool[t < L ? lo + t : POOL];   // beyond my share: the edge that does not count
+                bt.w[u] = se.w;
+                bt.tg[u] = se.tag;
+                bt.x[u] = load_row<T, V>(reinterpret_cast<const T *>((uintptr_t)(se.ptr + lane_off)));
+            }
+        };
+        auto consume = [&](const Batch &bt) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float xv = bt.x[u].x[v];
+                    if (RELU) xv = xv > 0.f ? xv : 0.f;
+                    acc[v] = fma((double)bt.w[u], (double)xv, acc[v]);
+                }
+                if (bt.tg[u] & 1u) {         // the row ends here
+                    if (in_head) {           // its beginning lies in an earlier share: leave my part for whoever holds that
+#pragma unroll
+                        for (int v = 0; v < V; ++v) head[lane * V + v] = acc[v];
+                        in_head = false;
+                        my_head = HEAD_CLOSED;
+                    } else {
+                        finish_row(acc, (int)(bt.tg[u] >> 2));
+                    }
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+                }
+            }
+        };
+        {
+            Batch a, b2;
+            issue(0, a);
+            for (int32_t t0 = 0; t0 < Lmax; t0 += 2 * UNR) {
+                if (t0 + UNR < Lmax) issue(t0 + UNR, b2);
+                consume(a);
+                if (t0 + UNR >= Lmax) break;
+                if (t0 + 2 * UNR < Lmax) issue(t0 + 2 * UNR, a);
+                consume(b2);
+            }
         }
-        if (active && mine) {
-            if (mask) apply_mask<V>(acc, mask + row * ldm + f);
-            store_row<V>(Z + row * ldz + f, acc);
+        if (in_head) {   // the whole share lies inside a row that goes on
+#pragma unroll
+            for (int v = 0; v < V; ++v) head[lane * V + v] = acc[v];
         }
+        if ((lane % G) == 0) st.head_state[grp] = my_head;
+        const uint32_t end_tag = L > 0 ? st.pool[hi - 1].tag : 1u;
+        const bool has_tail = !in_head && !(end_tag & 1u);   // acc holds the beginning of a row that goes on in later shares
+        const int32_t c_row = st.carry_row;                  // a row carried in from the edges staged before
+        double *carry_in = carry + (par ? G * V : 0), *carry_out = carry + (par ? 0 : G * V);
+        par ^= 1;
+        __builtin_amdgcn_wave_barrier();
+        // ---- rows cut by share boundaries: whoever holds a row's beginning adds the later shares' heads, in share
+        // order.  A row that goes on beyond the edges staged this time (at most one) is carried into the next round.
+        auto add_heads = [&](double (&sum)[V], int k, int r) -> bool {   // true: the row was completed and stored
+            for (; k < NG; ++k) {
+                const int32_t hs = st.head_state[k];
+                const int src = k * G + (lane % G);
+#pragma unroll
+                for (int v = 0; v < V; ++v) sum[v] += head[src * V + v];
+                if (hs == HEAD_CLOSED) break;
+            }
+            if (k < NG) {
+                finish_row(sum, r);
+                return true;
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) carry_out[(lane % G) * V + v] = sum[v];
+            return false;
+        };
+        int32_t next_carry = -1;
+        if (has_tail && !add_heads(acc, grp + 1, (int)(end_tag >> 2))) next_carry = (int32_t)(end_tag >> 2);
+        if (grp == 0 && c_row >= 0) {   // the row carried in: group 0's lanes put it together the same way
+            double sum[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) sum[v] = carry_in[(lane % G) * V + v];
+            if (!add_heads(sum, 0, c_row)) next_carry = c_row;
+        }
+        // every lane of the one group that carries on holds the row; all others hold -1
+        int32_t nc = next_carry;
+#pragma unroll
+        for (int off = WAVE / 2; off >= 1; off >>= 1) {
+            const int32_t o = __shfl_xor(nc, off, WAVE);
+            nc = o > nc ? o : nc;
+        }
+        if (lane == 0) st.carry_row = nc;
     }
     return is_long;
 }
 
-// Rows with more than LONG_ROW kept edges (hubs among the rows of S): the block's wavefronts
-// work on one such row at a time, each wavefront takes a contiguous share of the row's edges,
-// partial sums are added in wavefront order through LDS (fixed order: the result does not depend
-// on timing).  Block `bid` takes the long ones among its own `per` rows, in row order.
-template <typename T, int V, bool RELU>
-__device__ inline void aggregate_long_rows(int64_t bid, int32_t per, const int32_t *__restrict__ adj_rowptr,
-                                           const int32_t *__restrict__ adj_col, const float *__restrict__ adj_val,
-                                           int32_t nS, int64_t n_cols, const T *__restrict__ Xl, int64_t ldl,
-                                           int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
-                                           const int32_t *__restrict__ src_row, int32_t F, float *__restrict__ Z,
-                                           int64_t ldz, const float *__restrict__ mask, int64_t ldm)
+// Rows with more than LONG_ROW kept edges (hubs among the rows of S): the whole block works on one such row at
+// a time, each of its 256 / G lane groups takes a contiguous share of the row's edges, and the groups' sums are
+// added in group order through LDS (fixed order: the result does not depend on timing).
+template <typename T, int V, int G, bool RELU>
+__device__ inline void aggregate_long_rows(double *__restrict__ part /* LDS, AGG_BLOCK * V */, int64_t block_row0, bool is_long, int32_t f,
+                                           bool active, const int32_t *__restrict__ adj_rowptr, const int32_t *__restrict__ adj_col,
+                                           const float *__restrict__ adj_val, int64_t n_cols, const T *__restrict__ Xl,
+                                           int64_t ldl, int64_t rows_l, const T *__restrict__ Xr, int64_t ldr, int64_t rows_r,
+                                           const int32_t *__restrict__ src_row, float *__restrict__ Z, int64_t ldz,
+                                           const float *__restrict__ mask, int64_t ldm)
 {
-    __shared__ double part[AGG_WAVES][WAVE * V];
-    __shared__ int32_t long_rows[WAVE];   // per <= 64 rows, one lane each
-    __shared__ int32_t n_long;
+    constexpr int UNITS = AGG_BLOCK / G;
+    constexpr int TR = tile_rows(G);
+    __shared__ int32_t long_rows[AGG_WAVES * TR];   // row in the block, in row order
+    __shared__ int32_t wave_cnt[AGG_WAVES];
     const int tid = (int)threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
-    if (wave == 0) {   // one lane per row of the block; the list keeps row order
-        const int64_t row = bid * per + lane;
-        const bool is_long = lane < per && row < nS && adj_rowptr[row + 1] - adj_rowptr[row] > LONG_ROW;
-        const uint64_t m = __ballot(is_long);
-        if (is_long) long_rows[__popcll(m & ((1ull << lane) - 1ull))] = (int32_t)row;
-        if (lane == 0) n_long = __popcll(m);
-    }
+    const uint64_t m = __ballot(is_long);
+    if (lane == 0) wave_cnt[wave] = __popcll(m);
     __syncthreads();
-    const int32_t cnt = n_long;
+    int32_t base = 0, cnt = 0;
+    for (int w2 = 0; w2 < AGG_WAVES; ++w2) {
+        if (w2 < wave) base += wave_cnt[w2];
+        cnt += wave_cnt[w2];
+    }
+    if (is_long) long_rows[base + __popcll(m & ((1ull << lane) - 1ull))] = wave * TR + lane;
+    __syncthreads();
+    const int unit = tid / G, g = tid % G;
+    const int gbase = lane & ~(G - 1);
     for (int32_t li = 0; li < cnt; ++li) {
-        const int32_t row = long_rows[li];
+        const int64_t row = block_row0 + long_rows[li];
         const int32_t beg = adj_rowptr[row], end = adj_rowptr[row + 1];
-        const int32_t share = (end - beg + AGG_WAVES - 1) / AGG_WAVES;
-        const int32_t wbeg = beg + wave * share;
-        const int32_t wend = (wbeg + share < end) ? wbeg + share : end;
-        const int32_t len = wend > wbeg ? wend - wbeg : 0;
-        {
-            const int32_t f0 = (int32_t)blockIdx.y * WAVE * V;
-            const int32_t f = f0 + lane * V;
-            const bool active = f < F;
-            double acc[V];
+        const int32_t share = (end - beg + UNITS - 1) / UNITS;
+        const int32_t ub = beg + unit * share;
+        const int32_t ue = (ub + share < end) ? ub + share : end;
+        double acc[V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] = 0.0;
-            for (int32_t c0 = 0; c0 < len; c0 += WAVE) {
-                const int32_t e = wbeg + c0 + lane;
-                const T *src = nullptr;
-                float w = 0.f;
-                if (e < wend) resolve_edge<T>(e, adj_col, adj_val, n_cols, src_row, Xl, ldl, rows_l, Xr, ldr, rows_r, &src, &w);
-                const int32_t n_here = (len - c0) < WAVE ? (len - c0) : WAVE;
-                accumulate_staged<T, V, RELU>(acc, src, w, 0, n_here, n_here, active, f);
+        for (int v = 0; v < V; ++v) acc[v] = 0.0;
+        for (int32_t k0 = 0; k0 < share; k0 += G) {   // the same trip count for every group of the block
+            const int32_t e = ub + k0 + g;
+            const T *src = nullptr;
+            float w = 0.f;
+            if (e < ue) resolve_edge<T>(e, adj_col, adj_val, n_cols, src_row, Xl, ldl, rows_l, Xr, ldr, rows_r, &src, &w);
+            const int32_t left = ue - (ub + k0);
+            const int32_t n_here = left < 0 ? 0 : (left < G ? left : G);
+            const int32_t n_max = (share - k0) < G ? (share - k0) : G;
+            accumulate_staged<T, V, RELU>(acc, src, w, gbase, n_here, n_max, active, f);
+        }
+        __syncthreads();  // part[] of the previous row has been read
+#pragma unroll
+        for (int v = 0; v < V; ++v) part[tid * V + v] = acc[v];
+        __syncthreads();
+        if (tid < G && active) {
+            double sum[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) sum[v] = 0.0;
+            for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) sum[v] += part[(u * G + tid) * V + v];
             }
-            __syncthreads();  // part[] of the previous feature chunk / row has been read
-#pragma unroll
-            for (int v = 0; v < V; ++v) part[wave][lane * V + v] = acc[v];
-            __syncthreads();
-            if (wave == 0 && active) {
-                double sum[V];
-#pragma unroll
-                for (int v = 0; v < V; ++v) sum[v] = 0.0;
-                for (int w2 = 0; w2 < AGG_WAVES; ++w2) {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) sum[v] += part[w2][lane * V + v];
-                }
-                if (mask) apply_mask<V>(sum, mask + (int64_t)row * ldm + f);
-                store_row<V>(Z + (int64_t)row * ldz + f, sum);
-            }
+            if (mask) apply_mask<V>(sum, mask + row * ldm + f);
+            store_row<V>(Z + row * ldz + f, sum);
         }
     }
 }
 
-constexpr int DENSE_AVG = 16;      // kept edges per row, on average, from which on leading blocks take the long rows of a large grid
-constexpr int MANY_ROWS = 32768;   // rows per call (and instance) from which on such a grid has leading blocks at all
-
-// A block first takes the ordinary ones among its AGG_BLOCK / G rows, one group of lanes each, then,
-// all wavefronts together, the long ones among them (a block-wide vote says whether there are any):
-// no block has to look for long rows, which matters when the grid takes many rounds and few rows are long.
-// Or the long rows go to n_long_blocks leading blocks instead, `per` rows to look through each, which
-// start together with the ordinary ones: always when the whole grid is resident at once (the longest
-// path counts there, not the number of blocks); in a larger grid when the rows are dense (many blocks
-// would otherwise end with wavefronts that wait for the one with the longest ordinary row before the
-// long rows start), and then the leading blocks of a sparse call return at once.
-template <typename T, int V, int G, bool RELU, bool ADAPT>
+// Block b of the grid: row block b / slots (four tiles of TR consecutive output rows, one per wavefront) and
+// feature slice b % slots (G * V features; slots = the slice count rounded up to a multiple of 8 when there is more
+// than one slice, blocks beyond the slice count leave at once).  The hardware deals consecutive blocks
+// round-robin to the 8 XCDs, so all blocks of slice s run on XCD s mod 8: that XCD's L2 sees only slice s of the
+// gathered table, an eighth of it for rows of 1 KB, and a row that several output rows refer to is fetched
+// from memory once.
+template <typename T, int V, int G, bool RELU>
 __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restrict__ adj_rowptr,
                                                          const int32_t *__restrict__ adj_col,
                                                          const float *__restrict__ adj_val, int32_t nS_bound,
@@ -297,34 +511,35 @@ __global__ __launch_bounds__(AGG_BLOCK) void aggregate_k(const int32_t *__restri
                                                          const int32_t *__restrict__ src_row, int32_t F,
                                                          float *__restrict__ Z, int64_t ldz,
                                                          const float *__restrict__ mask, int64_t ldm,
-                                                         int32_t n_long_blocks, int32_t per, int32_t dense_avg, CompStride cs)
+                                                         int32_t n_slices, int32_t slots, CompStride cs)
 {
+    constexpr int TR = tile_rows(G);
+    __shared__ WaveStage<TR> stage[AGG_WAVES];
+    __shared__ double heads[AGG_WAVES][WAVE * V], carries[AGG_WAVES][2 * G * V];
+    const int32_t slice = (int32_t)(blockIdx.x % (unsigned)slots);
+    if (slice >= n_slices) return;
+    const int64_t block_row0 = (int64_t)(blockIdx.x / (unsigned)slots) * (AGG_WAVES * TR);
     adj_rowptr = inst_ptr(adj_rowptr, cs.adj); adj_col = inst_ptr(adj_col, cs.adj); adj_val = inst_ptr(adj_val, cs.adj);
     nS_dev = inst_ptr(nS_dev, cs.adj); n_cols_p = inst_ptr(n_cols_p, cs.adj); src_row = inst_ptr(src_row, cs.adj);
     Xl = inst_ptr(Xl, cs.x); Xr = inst_ptr(Xr, cs.xr); Z = inst_ptr(Z, cs.out);
-    // Who takes the long rows: the leading blocks if there are any and (ADAPT) the rows hold more than
-    // dense_avg kept edges on average; else the blocks that own them.  The same for the whole grid.
-    bool leading = n_long_blocks > 0;
-    if (ADAPT) {
-        const int32_t n = resolve_count(nS_bound, nS_dev);
-        leading = leading && n > 0 && (int64_t)adj_rowptr[n] > (int64_t)dense_avg * n;
-    }
-    if ((int32_t)blockIdx.x < n_long_blocks) {
-        if (ADAPT && !leading) return;
-        const int64_t n_cols = n_cols_p ? (int64_t)*n_cols_p : (src_row ? 0x7FFFFFFFll : rows_l);
-        aggregate_long_rows<T, V, RELU>((int64_t)blockIdx.x, per, adj_rowptr, adj_col, adj_val, resolve_count(nS_bound, nS_dev),
-                                        n_cols, Xl, ldl, rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
-        return;
-    }
-    const int64_t bid = (int64_t)blockIdx.x - n_long_blocks;
-    int32_t nS;
-    int64_t n_cols;
-    const bool is_long = aggregate_rows<T, V, G, RELU>(bid, adj_rowptr, adj_col, adj_val, nS_bound, nS_dev,
-                                                       n_cols_p, src_row ? 0x7FFFFFFFll : rows_l, &nS, &n_cols, Xl, ldl,
-                                                       rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
-    if ((ADAPT ? !leading : n_long_blocks == 0) && __syncthreads_or(is_long ? 1 : 0))
-        aggregate_long_rows<T, V, RELU>(bid, AGG_BLOCK / G, adj_rowptr, adj_col, adj_val, nS, n_cols, Xl, ldl,
-                                        rows_l, Xr, ldr, rows_r, src_row, F, Z, ldz, mask, ldm);
+    // the two counts that may live on the device are asked for together; a count that is not given is read from a
+    // stand-in address and dropped
+    const int32_t nS_raw = *(nS_dev ? nS_dev : adj_rowptr);
+    const int32_t n_cols_raw = *(n_cols_p ? n_cols_p : adj_rowptr);
+    const int32_t nS = !nS_dev ? nS_bound : (nS_raw < 0 ? 0 : (nS_raw < nS_bound ? nS_raw : nS_bound));
+    const int64_t n_cols = n_cols_p ? (int64_t)n_cols_raw : (src_row ? 0x7FFFFFFFll : rows_l);
+    if (block_row0 >= nS) return;
+    const int tid = (int)threadIdx.x;
+    const int wave = tid >> 6;
+    const int32_t slice0 = slice * G * V;
+    const int32_t f = slice0 + (tid % G) * V;
+    const bool active = f < F;  // F is a multiple of V (checked on the host)
+    const bool is_long = aggregate_tile<T, V, G, RELU>(stage[wave], heads[wave], carries[wave], block_row0 + (int64_t)wave * TR, slice0, f,
+                                                       active, adj_rowptr, adj_col, adj_val, nS_bound, nS, n_cols, Xl, ldl, rows_l,
+                                                       Xr, ldr, rows_r, src_row, Z, ldz, mask, ldm);
+    if (__syncthreads_or(is_long ? 1 : 0))
+        aggregate_long_rows<T, V, G, RELU>(&heads[0][0], block_row0, is_long, f, active, adj_rowptr, adj_col, adj_val, n_cols, Xl, ldl,
+                                           rows_l, Xr, ldr, rows_r, src_row, Z, ldz, mask, ldm);
 }
 
 template <typename T, int V, int G>
@@ -332,42 +547,37 @@ static int launch_agg(const int32_t *rp, const int32_t *col, const float *val, i
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                       const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
-    const int rows_per_block = AGG_BLOCK / G;
-    const int64_t blocks = ((int64_t)nS + rows_per_block - 1) / rows_per_block;
-    // the feature dimension in chunks of G * V (G = 64 whenever there is more than one chunk)
-    const int64_t chunks = (F + G * V - 1) / (G * V);
-    // Leading blocks for the long rows.  When the row blocks are resident at once, or nearly (8 blocks of
-    // 256 threads per compute unit), 4 rows each to look through, and they always take the long rows.
-    // For a call with very many rows 8 rows each, and the kernel decides by the density of the rows (every
-    // block then reads the edge total first).  In between none: measured, the leading blocks and the extra
-    // read cost more there than they bring (launches for 8 mini-batches of 2 K to 8 K rows each).
-    const bool small_grid = (blocks + ((int64_t)nS + 3) / 4) * chunks * ci.n <= 2 * 8 * 256;
-    const bool many_rows = nS >= MANY_ROWS;
-    const int64_t per = small_grid ? 4 : 8;
-    const int64_t lblocks = (small_grid || many_rows) ? ((int64_t)nS + per - 1) / per : 0;
-    const int32_t dense_avg = (many_rows && !small_grid) ? DENSE_AVG : 0;   // > 0: the kernel decides
-    const dim3 grid((unsigned)(blocks + lblocks), (unsigned)chunks, (unsigned)ci.n);
-#define CSGS_AGG_LAUNCH(RELU, ADAPT)                                                                                              \
-    CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, RELU, ADAPT>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp, (const T *)Xl, ldl, \
-                   rl, (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)lblocks, (int32_t)per, dense_avg, ci.cs)
-    if (dense_avg > 0) {
-        if (relu) CSGS_AGG_LAUNCH(true, true); else CSGS_AGG_LAUNCH(false, true);
-    } else {
-        if (relu) CSGS_AGG_LAUNCH(true, false); else CSGS_AGG_LAUNCH(false, false);
-    }
+    constexpr int BLOCK_ROWS = AGG_WAVES * tile_rows(G);
+    const int64_t row_blocks = ((int64_t)nS + BLOCK_ROWS - 1) / BLOCK_ROWS;
+    const int64_t n_slices = (F + G * V - 1) / (G * V);
+    const int64_t slots = n_slices > 1 ? (n_slices + 7) / 8 * 8 : 1;
+    if (row_blocks * slots > 0x7FFFFFFFll) return CSGS_EUNSUPPORTED;
+    const dim3 grid((unsigned)(row_blocks * slots), 1, (unsigned)ci.n);
+#define CSGS_AGG_LAUNCH(RELU)                                                                                                     \
+    CSGS_LAUNCH_ID(kid, (aggregate_k<T, V, G, RELU>), grid, dim3(AGG_BLOCK), st, rp, col, val, nS, nsd, ncp, (const T *)Xl, ldl, rl, \
+                   (const T *)Xr, ldr, rr, src_row, F, Z, ldz, mask, ldm, (int32_t)n_slices, (int32_t)slots, ci.cs)
+    if (relu) CSGS_AGG_LAUNCH(true); else CSGS_AGG_LAUNCH(false);
 #undef CSGS_AGG_LAUNCH
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }
 
+// Lanes per row and slice.  Rows of 1 KB and more are cut into (about) eight slices, one per XCD; shorter rows
+// are taken whole by the smallest group of lanes that covers them.
 template <typename T, int V>
 static int pick_group(const int32_t *rp, const int32_t *col, const float *val, int32_t nS, const int32_t *nsd, const int32_t *ncp, const void *Xl,
                       int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                       const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
-    if (F <= 16 * V) return launch_agg<T, V, 16>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
-    if (F <= 32 * V) return launch_agg<T, V, 32>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
-    return launch_agg<T, V, 64>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
+    const int64_t vecs = (F + V - 1) / V;
+    const int64_t want = (int64_t)F * (int64_t)sizeof(T) >= 1024 ? (vecs + 7) / 8 : vecs;
+#define CSGS_AGG_G(GG) launch_agg<T, V, GG>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci)
+    if (want <= 4) return CSGS_AGG_G(4);
+    if (want <= 8) return CSGS_AGG_G(8);
+    if (want <= 16) return CSGS_AGG_G(16);
+    if (want <= 32) return CSGS_AGG_G(32);
+    return CSGS_AGG_G(64);
+#undef CSGS_AGG_G
 }
 
 template <typename T>
@@ -375,13 +585,16 @@ static int pick_vec(const int32_t *rp, const int32_t *col, const float *val, int
                     int64_t ldl, int64_t rl, const void *Xr, int64_t ldr, int64_t rr, const int32_t *src_row, int32_t F, int relu, float *Z, int64_t ldz,
                     const float *mask, int64_t ldm, int kid, hipStream_t st, const CompInst &ci = CompInst{})
 {
-    // widest vector for which every row start and F are aligned
+    // widest vector for which every row start and F are aligned (8 floats are read as two pieces of 4)
     auto ok = [&](int v) {
-        const uintptr_t bytes = (uintptr_t)v * sizeof(T);
-        return F % v == 0 && (!Xl || (ldl % v == 0 && ((uintptr_t)Xl % bytes) == 0)) &&
-               (!Xr || (ldr % v == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % v == 0 &&
-               ((uintptr_t)Z % ((uintptr_t)v * sizeof(float))) == 0;
+        const int piece = (v == 8 && sizeof(T) == 4) ? 4 : v;
+        const uintptr_t bytes = (uintptr_t)piece * sizeof(T);
+        const int zpiece = v == 8 ? 4 : v;
+        return F % v == 0 && (!Xl || (ldl % piece == 0 && ((uintptr_t)Xl % bytes) == 0)) &&
+               (!Xr || (ldr % piece == 0 && ((uintptr_t)Xr % bytes) == 0)) && ldz % zpiece == 0 &&
+               ((uintptr_t)Z % ((uintptr_t)zpiece * sizeof(float))) == 0 && (!mask || ldm % 1 == 0);
     };
+    if (ok(8)) return pick_group<T, 8>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
     if (ok(4)) return pick_group<T, 4>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
     if (ok(2)) return pick_group<T, 2>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
     return pick_group<T, 1>(rp, col, val, nS, nsd, ncp, Xl, ldl, rl, Xr, ldr, rr, src_row, F, relu, Z, ldz, mask, ldm, kid, st, ci);
@@ -691,6 +904,7 @@ extern "C" int csgs_aggregate_n(const csgs_inst_strides *inst, const int32_t *ad
     if (!X_remote) rows_remote = 0;
     if (!X_local || rows_local == 0) { X_local = nullptr; rows_local = 0; ld_local = F; }
     if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
+    if (rows_remote > 0x7FFFFFFEll) return CSGS_EUNSUPPORTED;   // staged rows are addressed as -1 - row in 32 bits
     hipStream_t st = (hipStream_t)stream;
     if (dtype == CSGS_F32)
         return pick_vec<float>(adj_rowptr, adj_col, adj_val, nS, nS_dev, n_next, X_local, ld_local, rows_local, X_remote,

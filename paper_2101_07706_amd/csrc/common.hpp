@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <atomic>
+#include <type_traits>
 #include "csgs.h"
 #include "profile.hpp"
 
@@ -95,7 +96,9 @@ struct InstStride {
 template <typename T>
 __device__ inline T *inst_ptr(T *p, int64_t stride)
 {
-    return p ? (T *)((uintptr_t)p + (uintptr_t)((int64_t)blockIdx.z * stride)) : p;   // null stays null
+    // (pointer arithmetic, not integer arithmetic: the result is still known to point to global memory, so loads
+    // through it are global loads and not the slower flat ones)
+    return p ? (T *)((char *)const_cast<typename std::remove_const<T>::type *>(p) + (int64_t)blockIdx.z * stride) : p;   // null stays null
 }
 constexpr int MAX_INSTANCES = 64;
 
