@@ -333,6 +333,34 @@ class Workload:
         st["used"] = True
         return st["H_of"](kk)
 
+    def theorem1_sweep(self, Ds=(4.0, 8.0, 16.0, 32.0), it=0):
+        """One mini-batch sampled with the skew chosen on the device by Theorem 1 (Eq. 12) for each D of the
+        paper's sweep (Section 5.2): per layer the skew that was used and the sampled remote nodes, and for the
+        bottom layer (whose remote nodes are the feature vectors that would be transferred) their expectation
+        sum_{j in R} p_j (Eq. 4 with Eq. 8) from the distribution the call wrote."""
+        torch, pipeline, M, B = self.torch, self.pipeline, self.M, self.B
+        out = []
+        for D in Ds:
+            for l in range(M):
+                pipeline.sample_step(self.dg, self.ws1, self.Sd[it] if l == 0 else None, 4096.0, B, self.seed, it, l, self.lbs1[l],
+                                     want_q=False, auto_D=D)
+            torch.cuda.synchronize()
+            layers = []
+            for l in range(M):
+                lb, st = self.lbs1[l], self.lbs1[l].stats_host()
+                assert int(lb.status.item()) == 0
+                layers.append(dict(layer=l, skew=st.skew_fx / 16.0, candidates=st.n_cand, remote_candidates=st.n_remote,
+                                   sampled_nodes=int(lb.n_next.item()), remote_nodes=int(lb.remote_total.item())))
+            lb, st = self.lbs1[M - 1], self.lbs1[M - 1].stats_host()
+            cdf = lb.cdf[:st.n_cand].to(torch.float64)
+            q = torch.diff(cdf, prepend=cdf.new_zeros(1)) / float(st.total)
+            ids = lb.cand_id[:st.n_cand]
+            rem = (ids < self.g.local_lo) | (ids >= self.g.local_hi)
+            expect = float((-torch.expm1(B * torch.log1p(-q[rem]))).sum().item())
+            out.append(dict(D=D, bottom_layer_remote_nodes=layers[-1]["remote_nodes"], bottom_layer_expected_remote_nodes=expect,
+                            layers=layers))
+        return out
+
     def sizes_of(self, lbs, n0, sizes):
         M, B = self.M, self.B
         for l in range(M):
@@ -692,6 +720,10 @@ def main():
                             pinned_to_core=pinned)
         log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
+    t1 = wl.theorem1_sweep()
+    log("Theorem-1 skew, D = 4, 8, 16, 32: remote nodes of the bottom layer " +
+        ", ".join(f"{x['bottom_layer_remote_nodes']} (expected {x['bottom_layer_expected_remote_nodes']:.1f}, s = {x['layers'][-1]['skew']:g})" for x in t1))
+
     backward = None
     if not args.no_backward:
         backward = wl.measure_backward(args.steps)
@@ -753,7 +785,7 @@ def main():
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
-        roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, instances_sweep=sweep,
+        roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, theorem1_sweep=t1, instances_sweep=sweep,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
     print(json.dumps(out))
 

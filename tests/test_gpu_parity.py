@@ -283,6 +283,37 @@ def test_tiny_config_theorem1_sweep(dev):
     assert remote[-1] < remote[0]
 
 
+def test_dense_config_theorem1_sweep(dev):
+    """The paper's sweep of D (Section 5.2: 4, 8, 16, 32) on the Dense-neighbourhood configuration at full
+    size, the skew chosen on the device from the candidate counts of each layer (Theorem 1, Eq. 12).  Every
+    output element by element; the bottom layer's sampled remote nodes (what the method reduces) fall as D
+    grows and agree with their expectation sum_{j in R} p_j (Eq. 4 with Eq. 8) within sampling noise."""
+    from paper_2101_07706_amd import pipeline
+    cfg, g, X, Ws, _ = cached_inputs("dense")
+    dg = pipeline.DeviceGraph(g, torch.device("cuda:0"))
+    S0 = synth.make_batch(g, cfg.batch, cfg.seed, 0)
+    B = cfg.samples
+    remote, expect, skews = [], [], []
+    for D in (4.0, 8.0, 16.0, 32.0):
+        say(f"[dense] Theorem-1 skew, D={D}")
+        osteps = chain.oracle_chain(g, X, Ws, S0, 4096.0, B, 1234 + cfg.seed, 0, auto_D=D)
+        gsteps, _ = chain.gpu_chain(g, X, Ws, S0, 4096.0, B, 1234 + cfg.seed, 0, dg=dg, auto_D=D)
+        chain.compare_chain(osteps, gsteps)
+        bottom = osteps[-1]
+        pr = bottom.pr
+        q = np.diff(np.concatenate([[0], pr.cdf.astype(np.float64)])) / float(pr.total)
+        is_remote = (pr.cand_id < g.local_lo) | (pr.cand_id >= g.local_hi)
+        p = 1.0 - (1.0 - q[is_remote]) ** B
+        mean, sd = float(p.sum()), float(np.sqrt((p * (1 - p)).sum()))     # the draws' inclusion indicators are negatively correlated: sd is an upper bound
+        remote.append(bottom.rc.remote_total)
+        expect.append(mean)
+        skews.append([o.pr.skew_fx / 16 for o in osteps])
+        assert int(gsteps[-1].lb.remote_total.item()) == bottom.rc.remote_total
+        assert abs(bottom.rc.remote_total - mean) <= 5 * sd + 1, (D, bottom.rc.remote_total, mean, sd)
+    say(f"[dense] D = 4, 8, 16, 32: skew per layer {skews}; remote nodes of the bottom layer {remote}, expected {[round(e, 1) for e in expect]}")
+    assert remote[0] > remote[-1] and all(a >= b for a, b in zip(expect, expect[1:]))
+
+
 def _subgraph_variant(dev, g, X, W, skew, B, seed):
     """Subgraph sampler of Section 5.1: candidates = all (training) nodes, one draw of the subgraph's
     node set from the skewed distribution, sampled adjacency restricted to the drawn nodes, one
