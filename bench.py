@@ -592,6 +592,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     ap.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
+    ap.add_argument("--no-theorem1", action="store_true", help="skip the sweep of D with the skew chosen by Theorem 1")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share); --gpus above 1 is not supported",
@@ -655,6 +656,36 @@ def main():
     ams, acnt = csgs.csgs_profile_collect()["atomics"]
     atomic_Gups = n_upd * acnt / (ams * 1e-3) / 1e9
     del table
+    # random-lookup yardstick: 8-byte reads of random entries of the same table (the adjacency pass looks up one per edge)
+    table = torch.zeros(g.n_nodes, dtype=torch.int64, device=dev)
+    lsink = torch.zeros(1 << 22, dtype=torch.int64, device=dev)
+    for _ in range(2):
+        csgs.csgs_calib_lookups(table, n_upd, lsink)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(True)
+    for _ in range(5):
+        csgs.csgs_calib_lookups(table, n_upd, lsink)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(False)
+    lms, lcnt = csgs.csgs_profile_collect()["lookups"]
+    lookup_Gps = n_upd * lcnt / (lms * 1e-3) / 1e9
+    del table, lsink
+    # gather of a known volume: 1 Mi distinct random rows of 256 bytes out of a 1 GiB table through csgs_gather_rows (256 MiB
+    # read, 256 MiB written): the non-streaming kernel of known size against which the byte counters' calibration is checked
+    gt = torch.zeros((1 << 22, 64), dtype=torch.float32, device=dev)
+    gids = torch.randperm(1 << 22, device=dev, generator=torch.Generator(device=dev).manual_seed(7))[:1 << 20].to(torch.int32)
+    gout = torch.empty((1 << 20, 64), dtype=torch.float32, device=dev)
+    for _ in range(2):
+        csgs.csgs_gather_rows(gt, gids, None, gout)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(True)
+    for _ in range(5):
+        csgs.csgs_gather_rows(gt, gids, None, gout)
+    torch.cuda.synchronize()
+    csgs.csgs_profile_enable(False)
+    gms, gcnt = csgs.csgs_profile_collect()["gather_rows"]
+    gather_GBps = 2 * (1 << 28) * gcnt / (gms * 1e-3) / 1e9
+    del gt, gids, gout
     # matrix-core yardstick: the GEMM's instruction (fp64 16 x 16 x 4) back to back from registers, and the
     # GEMM's inner loop (operands from LDS, widened) without its global loads and barriers
     sink = torch.zeros(csgs.CALIB_MFMA_BLOCKS * 256, dtype=torch.float64, device=dev)
@@ -670,7 +701,8 @@ def main():
         mms, _ = csgs.csgs_profile_collect()["mfma_f64"]
         mfma_TF[from_lds] = flops / (mms * 1e-3) / 1e12
     del sink
-    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s; "
+    log(f"copy kernel: {copy_GBps:.0f} GB/s (read + write); gather of random 256-byte rows {gather_GBps:.0f} GB/s (read + write); "
+        f"random 8-byte lookups {lookup_Gps:.1f} G/s; 64-bit atomic adds to random addresses: {atomic_Gups:.1f} G/s; "
         f"fp64 matrix instructions back to back: {mfma_TF[False]:.1f} TFLOP/s from registers, {mfma_TF[True]:.1f} with operands from LDS")
 
     N_CPU = 20      # whole steps the oracle is timed on (about 11 s on one core at Large)
@@ -684,6 +716,8 @@ def main():
     roofline = roofline_of(res["kernels"], dominant, load_traffic(name, K), K)
     roofline["copy_kernel_GBps"] = copy_GBps
     roofline["atomic_adds_Gps"] = atomic_Gups      # what bounds scan_edges: one such add per scanned edge
+    roofline["random_lookups_Gps"] = lookup_Gps    # 8-byte reads of random table entries: the adjacency pass does one per scanned edge
+    roofline["gather_256B_rows_GBps"] = gather_GBps  # csgs_gather_rows on 1 Mi random rows of 256 bytes (read + write)
     roofline["mfma_f64_loop_TFLOPs"] = mfma_TF[False]       # the GEMM's instruction back to back, operands in registers
     roofline["mfma_f64_lds_loop_TFLOPs"] = mfma_TF[True]    # the GEMM's inner loop without global loads and barriers
     if "scan_edges" in res["kernels"]:
@@ -720,9 +754,11 @@ def main():
                             pinned_to_core=pinned)
         log(f"oracle on 1 core: {cpu_s / n_cpu * 1e3:.0f} ms/step")
 
-    t1 = wl.theorem1_sweep()
-    log("Theorem-1 skew, D = 4, 8, 16, 32: remote nodes of the bottom layer " +
-        ", ".join(f"{x['bottom_layer_remote_nodes']} (expected {x['bottom_layer_expected_remote_nodes']:.1f}, s = {x['layers'][-1]['skew']:g})" for x in t1))
+    t1 = None
+    if not args.no_theorem1:
+        t1 = wl.theorem1_sweep()
+        log("Theorem-1 skew, D = 4, 8, 16, 32: remote nodes of the bottom layer " +
+            ", ".join(f"{x['bottom_layer_remote_nodes']} (expected {x['bottom_layer_expected_remote_nodes']:.1f}, s = {x['layers'][-1]['skew']:g})" for x in t1))
 
     backward = None
     if not args.no_backward:

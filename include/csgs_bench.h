@@ -44,6 +44,11 @@ int csgs_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
  * weight scan of csgs_build_probs, which updates its per-node accumulators the same way. */
 int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_updates, void *stream);
 
+/* n_reads independent 8-byte reads of pseudo-random entries of `table` (n_table entries, device, 8-byte aligned): what a
+ * random lookup costs in time and in fetched bytes.  csgs_sample_layer looks up one such entry per scanned edge (the node ->
+ * position table).  `sink` (device, n_sink >= 4 194 304 entries) receives one value per thread so that the reads are kept. */
+int csgs_calib_lookups(const uint64_t *table, size_t n_table, size_t n_reads, uint64_t *sink, size_t n_sink, void *stream);
+
 /* Matrix-core yardstick for csgs_layer_gemm: CSGS_CALIB_MFMA_BLOCKS blocks of four wavefronts, each
  * wavefront issuing 64 * iters double-precision 16 x 16 x 4 matrix instructions (2048 flops each) on
  * eight independent accumulators, i.e. CSGS_CALIB_MFMA_BLOCKS * 4 * 64 * 2048 * iters flops per call.

@@ -25,7 +25,7 @@ EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace
            "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_w_static", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect", "csgs_profile_samples",
-           "csgs_calib_copy", "csgs_calib_atomics", "csgs_calib_mfma_f64"]
+           "csgs_calib_copy", "csgs_calib_atomics", "csgs_calib_mfma_f64", "csgs_calib_lookups"]
 
 
 class CsgsError(RuntimeError):
@@ -114,6 +114,7 @@ def lib():
         L.csgs_strerror.restype = C.c_char_p
         L.csgs_strerror.argtypes = [C.c_int]
         L.csgs_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.csgs_calib_lookups.argtypes = [vp, sz, sz, vp, sz, vp]
         L.csgs_calib_atomics.argtypes = [vp, sz, sz, vp]
         L.csgs_calib_mfma_f64.argtypes = [vp, sz, i64, i32, vp]
         L.csgs_profile_enable.argtypes = [C.c_int]
@@ -425,6 +426,11 @@ def csgs_calib_copy(dst, src, stream=None):
 def csgs_calib_atomics(table, n_updates, stream=None):
     """n_updates atomic +1 on pseudo-random entries of `table` (an int64 tensor)."""
     _call("csgs_calib_atomics", _ptr(table), table.numel(), n_updates, _stream(stream))
+
+
+def csgs_calib_lookups(table, n_reads, sink, stream=None):
+    """n_reads 8-byte reads of pseudo-random entries of `table` (int64 tensor); sink: int64 tensor of >= 4194304 entries."""
+    _call("csgs_calib_lookups", _ptr(table), table.numel(), n_reads, _ptr(sink), sink.numel(), _stream(stream))
 
 
 CALIB_MFMA_BLOCKS = 2048   # CSGS_CALIB_MFMA_BLOCKS

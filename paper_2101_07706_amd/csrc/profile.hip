@@ -24,7 +24,7 @@ static const size_t kMaxPairs = 1 << 16;
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce",
-                                            "adjT_count", "adjT_prefix", "adjT_fill", "adjT_order", "aggregate_grad", "fill_zero", "copy", "atomics", "mfma_f64"};
+                                            "adjT_count", "adjT_prefix", "adjT_fill", "adjT_order", "aggregate_grad", "fill_zero", "copy", "atomics", "mfma_f64", "lookups"};
 
 bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {
@@ -65,6 +65,21 @@ __global__ __launch_bounds__(256) void atomics_k(unsigned long long *__restrict_
         h ^= h >> 29;
         (void)__hip_atomic_fetch_add(&table[h % n_table], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+// n independent 8-byte reads of pseudo-random entries of a table (the same sequence of entries as atomics_k):
+// what one random lookup costs in fetched bytes and time -- the adjacency pass looks up one such entry per edge.
+__global__ __launch_bounds__(256) void lookups_k(const unsigned long long *__restrict__ table, uint64_t n_table, uint64_t n,
+                                                 unsigned long long *__restrict__ sink)
+{
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x, me = i;
+    unsigned long long s = 0;
+    for (; i < n; i += stride) {
+        uint64_t h = (i + 1) * 0x9E3779B97F4A7C15ull;
+        h ^= h >> 29;
+        s += table[h % n_table];
+    }
+    sink[me] = s;   // keeps the reads
 }
 // Back-to-back v_mfma_f64_16x16x4_f64 on eight independent accumulators per wavefront, 64 per loop
 // iteration: the yardstick for the layer GEMM, whose inner loop is the same instruction stream.
@@ -166,6 +181,18 @@ extern "C" int csgs_calib_atomics(uint64_t *table, size_t n_table, size_t n_upda
     const unsigned blocks = (unsigned)(want < 16384 ? want : 16384);
     CSGS_LAUNCH(K_ATOMICS, csgs::atomics_k, dim3(blocks), dim3(256), (hipStream_t)stream, (unsigned long long *)table,
                 (uint64_t)n_table, (uint64_t)n_updates);
+    CSGS_LAUNCH_CHECK();
+    return CSGS_OK;
+}
+
+extern "C" int csgs_calib_lookups(const uint64_t *table, size_t n_table, size_t n_reads, uint64_t *sink, size_t n_sink, void *stream)
+{
+    const size_t want = (n_reads + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 16384 ? want : 16384);
+    if (!table || n_table == 0 || n_reads == 0 || !sink || n_sink < (size_t)blocks * 256 || ((uintptr_t)table & 7) || ((uintptr_t)sink & 7))
+        return CSGS_EINVAL;
+    CSGS_LAUNCH(K_LOOKUPS, csgs::lookups_k, dim3(blocks), dim3(256), (hipStream_t)stream, (const unsigned long long *)table,
+                (uint64_t)n_table, (uint64_t)n_reads, (unsigned long long *)sink);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
 }

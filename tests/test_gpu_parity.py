@@ -1189,6 +1189,18 @@ def test_calibration_kernels(dev):
     assert np.isfinite(got).all() and (got > 0).all() and (got == got[0]).all()
     with pytest.raises(RuntimeError):
         csgs.csgs_calib_mfma_f64(sink[:1000], iters)
+    # random-lookup yardstick: reads the entries the atomic-add yardstick updates, so with table[i] = 1 before ...
+    table = torch.zeros(1000, dtype=torch.int64, device=dev)
+    csgs.csgs_calib_atomics(table, 54321)
+    lsink = torch.zeros(1 << 22, dtype=torch.int64, device=dev)
+    ones = torch.ones(1000, dtype=torch.int64, device=dev)
+    csgs.csgs_calib_lookups(ones, 54321, lsink)
+    torch.cuda.synchronize()
+    assert int(lsink.sum().item()) == 54321                      # ... every read is counted once
+    csgs.csgs_calib_lookups(torch.arange(1000, dtype=torch.int64, device=dev), 54321, lsink)
+    torch.cuda.synchronize()
+    # and the entries read are those the updates went to: sum of index * (updates of that entry)
+    assert int(lsink.sum().item()) == int((table * torch.arange(1000, dtype=torch.int64, device=dev)).sum().item())
 
 
 @pytest.mark.parametrize("scan_mode", [1, 2])
