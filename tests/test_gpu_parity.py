@@ -516,6 +516,70 @@ def test_aggregate_shapes(dev, F, bf16, mode):
     chain.assert_close(Z.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"aggregate F={F}")
 
 
+@pytest.mark.parametrize("F,bf16", [(256, False), (100, True), (512, False), (47, False)])
+def test_aggregate_hub_rows_and_edges_that_do_not_count(dev, F, bf16):
+    """Rows of a few hundred to a few thousand kept edges beside short and empty ones (the block-wide path for the
+    longest, sums carried from one round of staged edges into the next for the others), at the widths of the
+    configurations; and edges whose column or source row lies outside the tables: they contribute nothing, also
+    when the row they would have read holds NaN."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(7 * F)
+    n_rows, n_cols, n_loc, n_rem = 700, 4000, 5000, 300
+    lens = rng.poisson(3, n_rows)
+    lens[rng.choice(n_rows, 12, replace=False)] = rng.integers(200, 3000, 12)
+    lens[[0, 63, 64, 699]] = [257, 256, 0, 1000]
+    rowptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=rowptr[1:])
+    col = np.concatenate([np.sort(rng.choice(n_cols, size=l, replace=False)) for l in lens]).astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    src = np.where(rng.random(n_cols) < 0.85, rng.integers(1, n_loc, n_cols), -1 - rng.integers(0, n_rem, n_cols)).astype(np.int32)
+    Xl = rng.standard_normal((n_loc, F)).astype(np.float32)
+    Xr = rng.standard_normal((n_rem, F)).astype(np.float32)
+    Xl[0] = np.nan          # row 0 of the local table: what a dropped edge's load may touch; no valid edge points at it
+    if bf16:
+        Xl_h, Xr_h = synth.to_bf16_bits(Xl), synth.to_bf16_bits(Xr)
+        Xl_d, Xr_d = torch.from_numpy(Xl_h.view(np.int16)).to(dev), torch.from_numpy(Xr_h.view(np.int16)).to(dev)
+    else:
+        Xl_h, Xr_h = Xl, Xr
+        Xl_d, Xr_d = torch.from_numpy(Xl).to(dev), torch.from_numpy(Xr).to(dev)
+    want = oracle.aggregate(rowptr, col, val, Xl_h, Xr_h, src)
+    # the same operator with edges that must be dropped spliced in: columns beyond the column count, negative columns,
+    # columns whose source row is outside either table
+    bad_src = src.copy()
+    bad_cols = rng.choice(n_cols, 40, replace=False)
+    keep = ~np.isin(col, bad_cols)
+    want_bad = oracle.aggregate(np.concatenate([[0], np.cumsum(np.add.reduceat(keep, rowptr[:-1]) * (lens > 0))]).astype(np.int32),
+                                col[keep], val[keep], Xl_h, Xr_h, src)
+    bad_src[bad_cols[:20]] = n_loc + 5            # beyond the local table
+    bad_src[bad_cols[20:]] = -1 - (n_rem + 3)     # beyond the staged remote rows
+    col2 = col.copy()
+    t = lambda a: torch.from_numpy(a).to(dev)
+    n_next = torch.tensor([n_cols], dtype=torch.int32, device=dev)
+    say(f"[aggregate] hubs: F={F} bf16={bf16} nnz={len(col)} longest rows {np.sort(lens)[-4:]}")
+    Z = torch.full((n_rows, F), float("nan"), dtype=torch.float32, device=dev)
+    csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d, Xr_d, t(src), False, Z)
+    torch.cuda.synchronize()
+    chain.assert_close(Z.cpu().numpy(), want, chain.RTOL, chain.ATOL, f"aggregate with hub rows F={F}")
+    Z.fill_(float("nan"))
+    csgs.csgs_aggregate(t(rowptr), t(col2), t(val), n_next, Xl_d, Xr_d, t(bad_src), False, Z)
+    torch.cuda.synchronize()
+    chain.assert_close(Z.cpu().numpy(), want_bad, chain.RTOL, chain.ATOL, f"source rows outside the tables F={F}")
+    # columns at or beyond the column count, and negative ones
+    n_small = torch.tensor([n_cols - 500], dtype=torch.int32, device=dev)
+    keep = col < n_cols - 500
+    want_cut = oracle.aggregate(np.concatenate([[0], np.cumsum(np.add.reduceat(keep, rowptr[:-1]) * (lens > 0))]).astype(np.int32),
+                                col[keep], val[keep], Xl_h, Xr_h, src)
+    Z.fill_(float("nan"))
+    csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_small, Xl_d, Xr_d, t(src), False, Z)
+    torch.cuda.synchronize()
+    chain.assert_close(Z.cpu().numpy(), want_cut, chain.RTOL, chain.ATOL, f"columns beyond the column count F={F}")
+    # no table at all: every row is a zero row
+    Z.fill_(float("nan"))
+    csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d[:0], None, t(src), False, Z)
+    torch.cuda.synchronize()
+    assert bool((Z == 0).all())
+
+
 @pytest.mark.parametrize("mean_len,device_count", [(2, False), (2, True), (24, False), (24, True)])
 def test_aggregate_many_rows(dev, mean_len, device_count):
     """Calls with tens of thousands of rows: the kernel itself decides, by the mean number of kept edges per
