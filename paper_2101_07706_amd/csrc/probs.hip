@@ -21,10 +21,11 @@
 //   cand_emit      per tile: prefix = group sums before my group + tile sums before me in my
 //                  group (plain loads: the producers are earlier kernels); the skew multiplier is
 //                  fixed by the caller, or taken from the grand totals by the rule of Theorem 1
-//                  (Eq. 12), or zero for remote nodes ("Local" version of Section 5.1); positions
-//                  by ballot popcount, inclusive wave scan of the skewed weights -> cand_id /
-//                  cand_w / cdf / q; restores accumulator and flags to zero; the last tile writes
-//                  the stats
+//                  (Eq. 12), or zero for remote nodes ("Local" version of Section 5.1); the
+//                  tile's candidates are packed into LDS in id order (ballot popcount), then the
+//                  packed list gets its skewed weights, their inclusive running sum and q, and goes
+//                  out as contiguous runs of cand_id / cand_w / cdf / q; restores accumulator and
+//                  flags to zero; the last tile writes the stats
 #include <math.h>
 #include "common.hpp"
 #include "lookback.hpp"
@@ -418,12 +419,14 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
                                                  int32_t *__restrict__ cand_id, uint64_t *__restrict__ cand_w,
                                                  uint64_t *__restrict__ cdf, float *__restrict__ q, int64_t cap, InstStride is)
 {
-    __shared__ uint32_t s_cnt[CAND_WORDS];
+    __shared__ uint32_t s_cnt[4];
+    __shared__ uint32_t s_id[4][CAND_TILE / 4];    // the tile's candidates, packed: ids ...
+    __shared__ uint64_t s_wt[4][CAND_TILE / 4];    // ... and fixed-point weights, per wavefront in id order
     wtable = inst_ptr(wtable, is.ws); tileflag = inst_ptr(tileflag, is.ws); partial = inst_ptr(partial, is.ws);
     gtot = inst_ptr(gtot, is.ws); meta = inst_ptr(meta, is.ws); epoch = inst_ptr(epoch, is.ws);
     stats = inst_ptr(stats, is.buf); status = inst_ptr(status, is.buf); cand_id = inst_ptr(cand_id, is.buf);
     cand_w = inst_ptr(cand_w, is.buf); cdf = inst_ptr(cdf, is.buf); q = inst_ptr(q, is.buf);
-    __shared__ uint64_t s_w[CAND_WORDS];
+    __shared__ uint64_t s_w[4];
     __shared__ uint64_t s_red[4][6];
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
@@ -483,10 +486,13 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
         for (int i = 0; i < 3; ++i) { s_red[wave][i] = tot[i]; s_red[wave][3 + i] = pre[i]; }
     }
     __syncthreads();
+    {   // lanes 0 .. 5 add up one of the six sums each; the others get them by lane broadcast (not every lane all 24 terms)
+        const uint64_t mine = lane < 6 ? s_red[0][lane] + s_red[1][lane] + s_red[2][lane] + s_red[3][lane] : 0ull;
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        tot[i] = s_red[0][i] + s_red[1][i] + s_red[2][i] + s_red[3][i];
-        pre[i] = s_red[0][3 + i] + s_red[1][3 + i] + s_red[2][3 + i] + s_red[3][3 + i];
+        for (int i = 0; i < 3; ++i) {
+            tot[i] = __shfl(mine, i, WAVE);
+            pre[i] = __shfl(mine, 3 + i, WAVE);
+        }
     }
     const uint64_t n_cand = tot[0] >> 32, n_local = tot[0] & 0xFFFFFFFFull;
     uint64_t m_local, m_remote;
@@ -494,47 +500,64 @@ __global__ __launch_bounds__(256) void cand_emit(uint64_t *__restrict__ wtable, 
     const uint64_t total_w = tot[1] * m_local + tot[2] * m_remote;
     const double total_d = (double)total_w;
 
-    uint64_t words[CAND_WORDS / 4], wsk[CAND_WORDS / 4], wsk_incl[CAND_WORDS / 4];
-    const uint32_t lo_u = lo > 0 ? (uint32_t)lo : 0u, hi_u = hi > 0 ? (uint32_t)hi : 0u;
-#pragma unroll
-    for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const uint32_t id = ((uint32_t)t * CAND_WORDS + wave * (CAND_WORDS / 4) + k) * 64u + lane;
-        const bool local = id >= lo_u && id < hi_u;
-        wsk[k] = w[k] * (local ? m_local : m_remote);
-        wsk_incl[k] = wsk[k];
-        words[k] = __ballot(w[k] != 0);
-    }
-    wave_inclusive_scan_multi(wsk_incl);
+    // The tile's candidates (about one id in fifteen in a sparse neighbourhood) are first packed into LDS, every
+    // wavefront its own four words in id order, the accumulators and flags going back to their clean state on the way.
+    // Everything that costs instructions per candidate -- the skewed weight, the 64-bit running sum, q, the five
+    // stores -- is then done on the packed list, by as many wavefronts as it fills, with contiguous stores.
+    uint32_t my_cnt = 0;
 #pragma unroll
     for (int k = 0; k < CAND_WORDS / 4; ++k) {
         const int slot = wave * (CAND_WORDS / 4) + k;
-        if (lane == WAVE - 1) { s_cnt[slot] = (uint32_t)__popcll(words[k]); s_w[slot] = wsk_incl[k]; }
+        const uint32_t id = ((uint32_t)t * CAND_WORDS + slot) * 64u + lane;
+        const uint64_t word = __ballot(w[k] != 0);
+        if (w[k] != 0) {
+            const uint32_t at = my_cnt + (uint32_t)__popcll(word & ((1ull << lane) - 1ull));
+            s_id[wave][at] = id;
+            s_wt[wave][at] = w[k];
+            wtable[id] = 0ull;  // back to the clean state
+        }
+        my_cnt += (uint32_t)__popcll(word);
         if (flagged[k] && lane == 0) reinterpret_cast<uint64_t *>(tileflag)[t * CAND_WORDS + slot] = 0ull;  // back to the clean state
     }
+    if (lane == 0) s_cnt[wave] = my_cnt;
     __syncthreads();
-    uint64_t base_cnt = pre[0] >> 32;
-    uint64_t base_w = pre[1] * m_local + pre[2] * m_remote;
-    for (int sl = 0; sl < wave * (CAND_WORDS / 4); ++sl) { base_cnt += s_cnt[sl]; base_w += s_w[sl]; }
-#pragma unroll
-    for (int k = 0; k < CAND_WORDS / 4; ++k) {
-        const int slot = wave * (CAND_WORDS / 4) + k;
-        const uint64_t word = words[k];
-        if (word) {
-            const uint32_t id = ((uint32_t)t * CAND_WORDS + slot) * 64u + lane;
-            const bool set = (word >> lane) & 1ull;
-            const int64_t pos = (int64_t)base_cnt + __popcll(word & ((1ull << lane) - 1ull));
-            if (set) {
-                wtable[id] = 0ull;  // back to the clean state
-                if (pos < cap) {
-                    cand_id[pos] = (int32_t)id;
-                    cand_w[pos] = w[k];
-                    cdf[pos] = base_w + wsk_incl[k];
-                    if (q) q[pos] = (float)((double)wsk[k] / total_d);
-                }
+    const uint32_t c0 = s_cnt[0], c1 = c0 + s_cnt[1], c2 = c1 + s_cnt[2], n_t = c2 + s_cnt[3];
+    const uint32_t lo_u = lo > 0 ? (uint32_t)lo : 0u, hi_u = hi > 0 ? (uint32_t)hi : 0u;
+    const int64_t base_cnt = (int64_t)(pre[0] >> 32);
+    uint64_t run_w = pre[1] * m_local + pre[2] * m_remote;   // skewed weight before the packed candidate at pass_base
+    for (uint32_t pass_base = 0; pass_base < n_t; pass_base += 256u) {   // one pass unless the tile holds more than 256 candidates
+        const uint32_t i = pass_base + threadIdx.x;
+        const bool have = i < n_t;
+        const bool wave_has = pass_base + (uint32_t)wave * WAVE < n_t;   // the same for the whole wavefront
+        uint32_t id = 0;
+        uint64_t wi = 0, wsk = 0, incl = 0;
+        if (wave_has) {
+            if (have) {
+                const int src = i < c0 ? 0 : (i < c1 ? 1 : (i < c2 ? 2 : 3));
+                const uint32_t at = i - (src == 0 ? 0u : (src == 1 ? c0 : (src == 2 ? c1 : c2)));
+                id = s_id[src][at];
+                wi = s_wt[src][at];
+                wsk = wi * ((id >= lo_u && id < hi_u) ? m_local : m_remote);
+            }
+            incl = wave_inclusive_scan(wsk);
+            if (lane == WAVE - 1) s_w[wave] = incl;
+        } else if (lane == WAVE - 1) {
+            s_w[wave] = 0ull;
+        }
+        __syncthreads();
+        uint64_t before = run_w;
+        for (int w2 = 0; w2 < wave; ++w2) before += s_w[w2];
+        if (have) {
+            const int64_t pos = base_cnt + i;
+            if (pos < cap) {
+                cand_id[pos] = (int32_t)id;
+                cand_w[pos] = wi;
+                cdf[pos] = before + incl;
+                if (q) q[pos] = (float)((double)wsk / total_d);
             }
         }
-        base_cnt += s_cnt[slot];
-        base_w += s_w[slot];
+        run_w += s_w[0] + s_w[1] + s_w[2] + s_w[3];
+        __syncthreads();   // s_w is written again in the next pass
     }
     if (t == n_tiles - 1 && threadIdx.x == 0) {
         stats->n_cand = (int64_t)n_cand;
