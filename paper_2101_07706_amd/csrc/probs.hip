@@ -364,20 +364,22 @@ __global__ __launch_bounds__(256) void cand_partials(const uint64_t *__restrict_
             // only the touched groups of 8 ids (one 64-byte piece of the table each) are fetched
             w[h][k] = (((f8[h][k] >> (8 * (lane >> 3))) & 0xFFull) && id < (uint32_t)n_nodes) ? wtable[id] : 0ull;
         }
+    const uint32_t lo_u = lo > 0 ? (uint32_t)lo : 0u, hi_u = hi > 0 ? (uint32_t)hi : 0u;
 #pragma unroll
     for (int h = 0; h < TPB; ++h) {
-        uint64_t cn = 0, wl = 0, wr = 0;   // cn packs (candidates << 32) | local candidates
+        // counts from the ballots (scalar work), weights as the sum over everything and over the local ids: two
+        // wave-wide 64-bit sums per tile instead of three
+        uint64_t cn = 0, wl = 0, wa = 0;   // cn packs (candidates << 32) | local candidates
 #pragma unroll
         for (int k = 0; k < W; ++k) {
             const uint32_t id = ((uint32_t)(t0 + h) * CAND_WORDS + wave * W + k) * 64u + lane;
-            if (w[h][k]) {
-                const bool local = id >= (lo > 0 ? (uint32_t)lo : 0u) && id < (hi > 0 ? (uint32_t)hi : 0u);
-                cn += (1ull << 32) | (local ? 1ull : 0ull);
-                if (local) wl += w[h][k]; else wr += w[h][k];
-            }
+            const bool local = id >= lo_u && id < hi_u;
+            cn += ((uint64_t)__popcll(__ballot(w[h][k] != 0)) << 32) | (uint64_t)__popcll(__ballot(w[h][k] != 0 && local));
+            wa += w[h][k];
+            wl += local ? w[h][k] : 0ull;
         }
-        cn = wave_sum(cn); wl = wave_sum(wl); wr = wave_sum(wr);
-        if (lane == 0) { lds[h][wave][0] = cn; lds[h][wave][1] = wl; lds[h][wave][2] = wr; }
+        wl = wave_sum(wl); wa = wave_sum(wa);
+        if (lane == 0) { lds[h][wave][0] = cn; lds[h][wave][1] = wl; lds[h][wave][2] = wa - wl; }
     }
     __syncthreads();
     if (wave != 0) return;
