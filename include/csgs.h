@@ -372,6 +372,38 @@ int csgs_gather_rows_n(const csgs_inst_strides *inst /*host*/, const void *X, in
                        void *stream);
 
 /*
+ * H = (P~ sigma?(X)) W  (Eq. 1, both halves of a sampled layer) in one kernel: csgs_aggregate followed by
+ * csgs_layer_gemm without Z passing through memory.  A block aggregates 32 rows of Z into LDS (sums in double in
+ * edge order, one rounding to float: the rounding point of csgs_aggregate) and multiplies them by W on the fp64
+ * matrix cores from there (the arithmetic of csgs_layer_gemm).  H equals that of the two calls up to the order
+ * in which the double sums of a row of Z are formed.
+ *
+ *   adj_*, nS, nS_dev, n_next, X_local .. relu_on_input   as csgs_aggregate (F_in = its F)
+ *   W [F_in x F_out] row-major, leading dimension ldw; H [nS x F_out] float out, leading dimension ldh
+ *   Z         nullable: [nS x F_in] float out, leading dimension ldz, also receives P~ sigma?(X) (a training
+ *             step needs it for dW = Z^T G); NULL: Z is never written
+ *   csgs_layer_forward_n: instances as above (H moves by `out`); z_stride: bytes between the instances' Z
+ *             (a multiple of 16)
+ * Takes F_in <= 64, even F_in <= 128, and F_in <= 256 that are multiples of 4, with rows of X starting on
+ * multiples of 1, 2 and 4 elements: csgs_layer_forward_supported() (host, no device work) returns 1 for a width,
+ * type and pair of leading dimensions (0 = no such table) that the kernel takes, else 0; the calls themselves return
+ * CSGS_EUNSUPPORTED for the others, and the caller uses csgs_aggregate + csgs_layer_gemm.
+ * Host errors: CSGS_EINVAL, CSGS_EUNSUPPORTED.
+ */
+int csgs_layer_forward_supported(int32_t F_in, int dtype, int64_t ld_local, int64_t ld_remote);
+int csgs_layer_forward(const int32_t *adj_rowptr, const int32_t *adj_col, const float *adj_val, int32_t nS,
+                       const int32_t *nS_dev, const int32_t *n_next, const void *X_local, int64_t ld_local,
+                       int64_t rows_local, const void *X_remote, int64_t ld_remote, int64_t rows_remote,
+                       const int32_t *src_row, int32_t F_in, int dtype, int relu_on_input, const float *W,
+                       int64_t ldw, int32_t F_out, float *H, int64_t ldh, float *Z, int64_t ldz, void *stream);
+int csgs_layer_forward_n(const csgs_inst_strides *inst /*host*/, const int32_t *adj_rowptr, const int32_t *adj_col,
+                         const float *adj_val, int32_t nS, const int32_t *nS_dev, const int32_t *n_next,
+                         const void *X_local, int64_t ld_local, int64_t rows_local, const void *X_remote,
+                         int64_t ld_remote, int64_t rows_remote, const int32_t *src_row, int32_t F_in, int dtype,
+                         int relu_on_input, const float *W, int64_t ldw, int32_t F_out, float *H, int64_t ldh,
+                         float *Z, int64_t ldz, int64_t z_stride, void *stream);
+
+/*
  * Gradients of one sampled layer.  Every GPU obtains a stochastic gradient of the loss (Section 3,
  * Eq. 2) through its sampled layers (Eq. 1): for H = Z W, Z = P~ sigma(H_prev) and G = dL/dH,
  *     dW      = Z^T G                                  csgs_layer_gemm_grad_w

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcsgs.so")
-SOURCES = ["probs.hip", "sample.hip", "aggregate.hip", "gemm.hip", "profile.hip"]
+SOURCES = ["probs.hip", "sample.hip", "aggregate.hip", "gemm.hip", "fused.hip", "profile.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["csgs_workspace_bytes", "csgs_workspace_clean_bytes", "csgs_workspace_init", "csgs_workspace_wait_limit", "csgs_fixed_point", "csgs_build_probs", "csgs_build_probs_auto",
            "csgs_sample_layer", "csgs_draw_nodes", "csgs_sampled_adjacency", "csgs_remote_count", "csgs_aggregate", "csgs_gather_rows",
-           "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_w_static", "csgs_layer_gemm_grad_z",
+           "csgs_layer_gemm", "csgs_aggregate_n", "csgs_gather_rows_n", "csgs_layer_gemm_n", "csgs_layer_forward", "csgs_layer_forward_n", "csgs_layer_forward_supported", "csgs_layer_gemm_grad_w_scratch_bytes", "csgs_layer_gemm_grad_w", "csgs_layer_gemm_grad_w_static", "csgs_layer_gemm_grad_z",
            "csgs_aggregate_grad_scratch_bytes", "csgs_aggregate_grad", "csgs_strerror",
            "csgs_profile_enable", "csgs_profile_kernel_count", "csgs_profile_kernel_name", "csgs_profile_collect", "csgs_profile_samples",
            "csgs_calib_copy", "csgs_calib_atomics", "csgs_calib_mfma_f64", "csgs_calib_lookups"]
@@ -103,6 +103,10 @@ def lib():
         L.csgs_aggregate_n.argtypes = strides + L.csgs_aggregate.argtypes
         L.csgs_layer_gemm_n.argtypes = strides + L.csgs_layer_gemm.argtypes
         L.csgs_gather_rows_n.argtypes = strides + L.csgs_gather_rows.argtypes
+        fwd = [vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i64, i64, vp, i32, C.c_int, C.c_int, vp, i64, i32, vp, i64, vp, i64]
+        L.csgs_layer_forward.argtypes = fwd + [vp]
+        L.csgs_layer_forward_n.argtypes = strides + fwd + [i64, vp]
+        L.csgs_layer_forward_supported.argtypes = [i32, C.c_int, i64, i64]
         L.csgs_layer_gemm_grad_w_scratch_bytes.restype = sz
         L.csgs_layer_gemm_grad_w_scratch_bytes.argtypes = [i32, i32, i32]
         L.csgs_layer_gemm_grad_w.argtypes = [vp, i64, vp, i64, i32, vp, i32, i32, vp, i64, vp, sz, vp]
@@ -333,6 +337,35 @@ def csgs_layer_gemm(Z, W, H, stream=None, M_dev=None, inst=None):
     suffix, lead = _inst(inst)
     _call("csgs_layer_gemm" + suffix, *lead, _ptr(Z), Z.stride(0), M, _ptr(M_dev), K, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0),
                                _stream(stream))
+
+
+def csgs_layer_forward_supported(X_local, X_remote=None) -> bool:
+    """Whether csgs_layer_forward takes input rows of this width, type and layout."""
+    dtype = F32 if X_local.dtype == torch.float32 else BF16
+    ld_r = 0 if X_remote is None else X_remote.stride(0)
+    return bool(lib().csgs_layer_forward_supported(X_local.shape[1], dtype, X_local.stride(0), ld_r))
+
+
+def csgs_layer_forward(adj_rowptr, adj_col, adj_val, n_next, X_local, X_remote, src_row, relu_on_input, W, H,
+                       Z=None, stream=None, nS_dev=None, inst=None, z_stride=0):
+    """H = (P~ sigma?(X)) W in one kernel; Z (optional) also receives P~ sigma?(X).  Arguments as csgs_aggregate and
+    csgs_layer_gemm; z_stride: bytes between the instances' Z when inst is given."""
+    dtype = F32 if X_local.dtype == torch.float32 else BF16
+    F_in = X_local.shape[1]
+    K2, N = W.shape
+    assert K2 == F_in and H.shape == (adj_rowptr.numel() - 1, N)
+    rows_r = 0 if X_remote is None else X_remote.shape[0]
+    ld_r = 0 if X_remote is None else X_remote.stride(0)
+    if X_remote is not None and rows_r == 0:
+        X_remote = None
+    Xl_ptr = _ptr(X_local) if X_local.shape[0] > 0 else None
+    args = (_ptr(adj_rowptr), _ptr(adj_col), _ptr(adj_val), adj_rowptr.numel() - 1, _ptr(nS_dev), _ptr(n_next), Xl_ptr,
+            X_local.stride(0), X_local.shape[0], _ptr(X_remote), ld_r, rows_r, _ptr(src_row), F_in, dtype,
+            1 if relu_on_input else 0, _ptr(W), W.stride(0), N, _ptr(H), H.stride(0), _ptr(Z), 0 if Z is None else Z.stride(0))
+    if inst is not None:
+        _call("csgs_layer_forward_n", C.byref(inst), *args, z_stride, _stream(stream))
+    else:
+        _call("csgs_layer_forward", *args, _stream(stream))
 
 
 def csgs_layer_gemm_grad_w_scratch_bytes(M, K, N) -> int:

@@ -24,7 +24,7 @@ static const size_t kMaxPairs = 1 << 16;
 static const char *const kNames[K_COUNT] = {"row_prefix", "scan_edges", "cand_partials", "cand_emit", "draw", "hits_fused",
                                             "adj_fused", "remote_count", "aggregate",
                                             "layer_gemm", "gather_rows", "gemm_grad_z", "gemm_grad_w", "gemm_grad_w_reduce",
-                                            "adjT_count", "adjT_prefix", "adjT_fill", "adjT_order", "aggregate_grad", "fill_zero", "copy", "atomics", "mfma_f64", "lookups"};
+                                            "adjT_count", "adjT_prefix", "adjT_fill", "adjT_order", "aggregate_grad", "fill_zero", "copy", "atomics", "mfma_f64", "lookups", "layer_forward"};
 
 bool next_pair(int kid, hipEvent_t *start, hipEvent_t *stop)
 {

@@ -9,7 +9,7 @@ namespace prof {
 enum Kid {
     K_ROW_PREFIX = 0, K_SCAN_EDGES, K_CAND_PARTIALS, K_CAND_EMIT, K_DRAW, K_HITS_FUSED, K_ADJ_FUSED, K_REMOTE_COUNT,
     K_AGGREGATE, K_GEMM, K_GATHER_ROWS, K_GEMM_DZ, K_GEMM_DW, K_GEMM_DW_REDUCE, K_ADJT_COUNT, K_ADJT_PREFIX, K_ADJT_FILL, K_ADJT_ORDER,
-    K_AGGREGATE_GRAD, K_FILL_ZERO, K_COPY, K_ATOMICS, K_MFMA_F64, K_LOOKUPS, K_COUNT
+    K_AGGREGATE_GRAD, K_FILL_ZERO, K_COPY, K_ATOMICS, K_MFMA_F64, K_LOOKUPS, K_LAYER_FORWARD, K_COUNT
 };
 
 extern bool g_enabled;

@@ -131,18 +131,32 @@ def instance_strides(lb, x, x_remote, out, n_inst=None):
     return csgs.InstStrides(lb.n_inst if n_inst is None else n_inst, 0, lb.stride, x, x_remote, out)
 
 
-def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None, strides=None, n_inst=None):
+def compute_step(lb, nS, X_local, X_remote, use_src_row, relu, W, Z, H, stream=None, nS_dev=None, strides=None, n_inst=None,
+                 fused=None):
     """csgs_aggregate -> csgs_layer_gemm for one layer; Z and H are preallocated [nS, F] / [nS, F_out].
     nS_dev: as in sample_step (nS is then the capacity).
     strides = (x, x_remote, z, h) in bytes: all instances of `lb` (or its first n_inst) in the same two
-    launches; the tensors passed are instance 0's."""
+    launches; the tensors passed are instance 0's.
+    fused: "h" = one csgs_layer_forward call that leaves Z untouched, "hz" = the same and Z written as well, where
+    the input width is one that call takes; the two calls otherwise.  Returns True when the fused call ran."""
     agg = gemm = None
+    if fused and csgs.csgs_layer_forward_supported(X_local, X_remote):
+        assert fused in ("h", "hz")
+        inst, z = None, 0
+        if strides is not None:
+            x, xr, z, h = strides
+            inst = instance_strides(lb, x, xr, h, n_inst)
+        csgs.csgs_layer_forward(lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.n_next, X_local, X_remote,
+                                lb.src_row if use_src_row else None, relu, W, H, Z if fused == "hz" else None, stream,
+                                nS_dev=nS_dev, inst=inst, z_stride=z)
+        return True
     if strides is not None:
         x, xr, z, h = strides
         agg, gemm = instance_strides(lb, x, xr, z, n_inst), instance_strides(lb, z, 0, h, n_inst)
     csgs.csgs_aggregate(lb.adj_rowptr[:nS + 1], lb.adj_col, lb.adj_val, lb.n_next, X_local, X_remote,
                         lb.src_row if use_src_row else None, relu, Z, stream, nS_dev=nS_dev, inst=agg)
     csgs.csgs_layer_gemm(Z, W, H, stream, M_dev=nS_dev, inst=gemm)
+    return False
 
 
 def stage_remote_rows(lb, X, staged, stream=None, out_stride=None, n_inst=None):

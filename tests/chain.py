@@ -79,10 +79,17 @@ def gpu_chain(g, X, Ws, S0, skew, B, seed, it, bf16=False, dg=None, adj_cap=None
             r = int(lb.remote_total.item())
             X_local = Xd[g.local_lo:g.local_hi]
             X_remote = Xd[lb.remote_ids[:r].long()]      # stands in for the exchange of remote rows
-            pipeline.compute_step(lb, nS, X_local, X_remote, True, False, W, Z, Hn)
+            args = (lb, nS, X_local, X_remote, True, False, W)
         else:
-            pipeline.compute_step(lb, nS, H, None, False, True, W, Z, Hn)
+            args = (lb, nS, H, None, False, True, W)
+        pipeline.compute_step(*args, Z, Hn)
         st.Z, st.H = Z, Hn
+        # the same layer through the one-kernel call, on the same inputs: once with Z asked for, once without
+        Zf, Hf, Hf2 = torch.full_like(Z, float("nan")), torch.full_like(Hn, float("nan")), torch.full_like(Hn, float("nan"))
+        st.fused = pipeline.compute_step(*args, Zf, Hf, fused="hz")
+        if st.fused:
+            assert pipeline.compute_step(*args, None, Hf2, fused="h")
+            st.Zf, st.Hf, st.Hf2 = Zf, Hf, Hf2
         H = Hn
     torch.cuda.synchronize()
     # workspace must be back in its prepared (all-zero) state
@@ -112,6 +119,7 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
           for l in range(M)]
     Hs = [torch.full((len(S0) if l == 0 else B, Wd[M - 1 - l].shape[1]), float("nan"), dtype=torch.float32, device=dev)
           for l in range(M)]
+    Zf, Hf, fused = [torch.full_like(z, float("nan")) for z in Zs], [torch.full_like(h, float("nan")) for h in Hs], [False] * M
     staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
     S0d = torch.from_numpy(np.ascontiguousarray(S0, np.int32)).to(dev)
     torch.cuda.synchronize()
@@ -126,9 +134,11 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
         nS = len(S0) if l == 0 else B
         nS_dev = None if l == 0 else lbs[l - 1].n_next
         if l == M - 1:
-            pipeline.compute_step(lbs[l], nS, X_local, staged, True, False, Wd[0], Zs[l], Hs[l], nS_dev=nS_dev)
+            args = (lbs[l], nS, X_local, staged, True, False, Wd[0])
         else:
-            pipeline.compute_step(lbs[l], nS, Hs[l + 1], None, False, True, Wd[M - 1 - l], Zs[l], Hs[l], nS_dev=nS_dev)
+            args = (lbs[l], nS, Hs[l + 1], None, False, True, Wd[M - 1 - l])
+        pipeline.compute_step(*args, Zs[l], Hs[l], nS_dev=nS_dev)
+        fused[l] = pipeline.compute_step(*args, Zf[l], Hf[l], nS_dev=nS_dev, fused="hz")
     torch.cuda.synchronize()
     steps = []
     for l in range(M):
@@ -137,7 +147,10 @@ def gpu_chain_device_counts(g, X, Ws, S0, skew, B, seed, it, bf16, dg, adj_cap, 
         # rows past the device count must be untouched
         assert bool(torch.isnan(Zs[l][n_rows:]).all()) and bool(torch.isnan(Hs[l][n_rows:]).all()), f"layer {l}: wrote past the row count"
         steps.append(SimpleNamespace(S=S, lb=lbs[l], n_next=int(lbs[l].n_next.item()), status=int(lbs[l].status.item()),
-                                     Z=Zs[l][:n_rows], H=Hs[l][:n_rows]))
+                                     Z=Zs[l][:n_rows], H=Hs[l][:n_rows], fused=fused[l]))
+        if fused[l]:
+            assert bool(torch.isnan(Zf[l][n_rows:]).all()) and bool(torch.isnan(Hf[l][n_rows:]).all()), f"layer {l}: the one-kernel call wrote past the row count"
+            steps[-1].Zf, steps[-1].Hf = Zf[l][:n_rows], Hf[l][:n_rows]
     clean = csgs.csgs_workspace_clean_bytes(g.n_nodes) // 8
     assert int(torch.count_nonzero(ws.buf[:clean]).item()) == 0, "workspace not restored"
     return steps, ws
@@ -252,12 +265,17 @@ def assert_close(got, want, rtol, atol, what):
     assert got.shape == want.shape, what
     err = np.abs(got - want)
     tol = atol + rtol * np.abs(want)
-    bad = err > tol
+    bad = ~(err <= tol)    # a NaN on either side is outside every tolerance
     if bad.any():
-        i = np.unravel_index(np.argmax(err - tol), err.shape)
+        i = np.unravel_index(np.argmax(np.where(np.isnan(err), np.inf, err - tol)), err.shape)
         raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst at {i}: "
                              f"got {got[i]!r} want {want[i]!r} err {err[i]:.3e} tol {tol[i]:.3e}")
     return float((err / tol).max()) if err.size else 0.0
+
+
+# (layer, elements of Z, elements of H that differ in any bit between csgs_layer_forward and the two calls, size of Z)
+# of the layers compare_chain() has seen, for the tests' logs
+fused_bit_differences = []
 
 
 def compare_chain(osteps, gsteps, check_compute=True):
@@ -298,6 +316,13 @@ def compare_chain(osteps, gsteps, check_compute=True):
         if check_compute:
             worst[f"Z{l}"] = assert_close(gs.Z.cpu().numpy(), o.Z, RTOL, ATOL, f"layer {l} Z")
             worst[f"H{l}"] = assert_close(gs.H.cpu().numpy(), o.H, RTOL, ATOL, f"layer {l} H")
+            if getattr(gs, "fused", False):   # csgs_layer_forward ran on the same inputs as the two calls
+                worst[f"Zf{l}"] = assert_close(gs.Zf.cpu().numpy(), o.Z, RTOL, ATOL, f"layer {l} Z of the one-kernel call")
+                worst[f"Hf{l}"] = assert_close(gs.Hf.cpu().numpy(), o.H, RTOL, ATOL, f"layer {l} H of the one-kernel call")
+                if hasattr(gs, "Hf2"):
+                    assert bool((gs.Hf2 == gs.Hf).all()), f"layer {l}: H depends on whether Z is asked for"
+                # the two paths round Z at the same point; they differ in the order of the double sums of a row
+                fused_bit_differences.append((l, int((gs.Zf != gs.Z).sum().item()), int((gs.Hf != gs.H).sum().item()), gs.Zf.numel()))
     return worst
 
 

@@ -36,10 +36,12 @@ def run_config(name, it=0, skew=None, bf16=None):
     say(f"[{name}] it={it} skew={skew} bf16={bf16} nnz={g.nnz}")
     osteps = chain.oracle_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16)
     gsteps, _ = chain.gpu_chain(g, X, Ws, S0, skew, cfg.samples, 1234 + cfg.seed, it, bf16)
+    del chain.fused_bit_differences[:]
     worst = chain.compare_chain(osteps, gsteps)
     say(f"[{name}] layers: " + ", ".join(
         f"nS={len(o.S)} E={o.pr.edges_scanned} nc={o.pr.n_cand} n'={o.sm.n_next} nnz={o.sm.adj_nnz} rem={o.rc.remote_total}"
         for o in osteps) + f" worst err/tol {worst}")
+    say(f"[{name}] one-kernel layer call against the two calls, (layer, Z elements, H elements that differ, of): {chain.fused_bit_differences}")
 
 
 def test_tiny_config(dev):
@@ -578,6 +580,138 @@ def test_aggregate_hub_rows_and_edges_that_do_not_count(dev, F, bf16):
     csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d[:0], None, t(src), False, Z)
     torch.cuda.synchronize()
     assert bool((Z == 0).all())
+
+
+@pytest.mark.parametrize("K,N,bf16", [(256, 256, False), (100, 256, True), (256, 47, False), (64, 64, False), (128, 256, False),
+                                      (256, 41, True), (33, 5, False), (7, 100, True), (252, 300, False), (1, 1, False)])
+@pytest.mark.parametrize("mode", ["compact_relu", "src_row"])
+def test_layer_forward_shapes(dev, K, N, bf16, mode):
+    """csgs_layer_forward against the oracle's aggregation followed by its layer product: hub rows (block-wide path,
+    sums carried over rounds of staged edges), empty rows, edges that do not count, a row count that is not a multiple
+    of a block's 32 rows, a device row count below the capacity, Z asked for or not, widths with ragged K chunks and
+    ragged column tiles."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(1000 * K + N)
+    n_rows, n_cols, n_loc, n_rem = 717, 3000, 3500, 200
+    lens = rng.poisson(3, n_rows)
+    lens[rng.choice(n_rows, 10, replace=False)] = rng.integers(60, 1500, 10)
+    lens[[0, 31, 32, 63, 716]] = [257, 256, 0, 65, 700]
+    rowptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=rowptr[1:])
+    col = np.concatenate([np.sort(rng.choice(n_cols, size=l, replace=False)) for l in lens]).astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    compact = mode == "compact_relu"
+    Xl = rng.standard_normal((n_cols if compact else n_loc, K)).astype(np.float32)
+    Xr = rng.standard_normal((n_rem, K)).astype(np.float32)
+    src = np.where(rng.random(n_cols) < 0.85, rng.integers(1, n_loc, n_cols), -1 - rng.integers(0, n_rem, n_cols)).astype(np.int32)
+    bad = rng.choice(n_cols, 30, replace=False)       # columns whose source row lies outside the tables
+    src[bad[:15]] = n_loc + 7
+    src[bad[15:]] = -1 - (n_rem + 2)
+    W = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
+    if bf16:
+        Xl_h, Xr_h = synth.to_bf16_bits(Xl), synth.to_bf16_bits(Xr)
+        Xl_d, Xr_d = torch.from_numpy(Xl_h.view(np.int16)).to(dev), torch.from_numpy(Xr_h.view(np.int16)).to(dev)
+    else:
+        Xl_h, Xr_h = Xl, Xr
+        Xl_d, Xr_d = torch.from_numpy(Xl).to(dev), torch.from_numpy(Xr).to(dev)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    n_small = n_cols - 300                              # columns at or beyond the column count do not count either
+    n_next = torch.tensor([n_small], dtype=torch.int32, device=dev)
+    keep = col < n_small
+    if not compact:
+        keep &= ~np.isin(col, bad)
+    rp_keep = np.concatenate([[0], np.cumsum(np.add.reduceat(keep, rowptr[:-1]) * (lens > 0))]).astype(np.int32)
+    if compact:
+        Z_want = oracle.aggregate(rp_keep, col[keep], val[keep], Xl_h, relu_on_input=True)
+        call = lambda Z, H, nS_dev=None: csgs.csgs_layer_forward(t(rowptr), t(col), t(val), n_next, Xl_d, None, None, True, Wd, H, Z, nS_dev=nS_dev)
+        two = lambda Z: csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d, None, None, True, Z)
+    else:
+        Z_want = oracle.aggregate(rp_keep, col[keep], val[keep], Xl_h, Xr_h, src)
+        call = lambda Z, H, nS_dev=None: csgs.csgs_layer_forward(t(rowptr), t(col), t(val), n_next, Xl_d, Xr_d, t(src), False, Wd, H, Z, nS_dev=nS_dev)
+        two = lambda Z: csgs.csgs_aggregate(t(rowptr), t(col), t(val), n_next, Xl_d, Xr_d, t(src), False, Z)
+    H_want = oracle.layer_gemm(Z_want, W)
+    Wd = t(W)
+    assert csgs.csgs_layer_forward_supported(Xl_d, None if compact else Xr_d)
+    say(f"[layer_forward] K={K} N={N} bf16={bf16} mode={mode} nnz={len(col)} longest rows {np.sort(lens)[-3:]}")
+    nan = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=dev)
+    Z, H, H2 = nan(n_rows, K), nan(n_rows, N), nan(n_rows, N)
+    call(Z, H)
+    call(None, H2)
+    torch.cuda.synchronize()
+    chain.assert_close(Z.cpu().numpy(), Z_want, chain.RTOL, chain.ATOL, f"Z of the one-kernel call K={K}")
+    worst = chain.assert_close(H.cpu().numpy(), H_want, chain.RTOL, chain.ATOL, f"H of the one-kernel call K={K} N={N}")
+    assert bool((H == H2).all()), "H depends on whether Z is asked for"
+    # the product's input is the Z the call reports: the oracle's product of exactly that Z
+    chain.assert_close(H.cpu().numpy(), oracle.layer_gemm(Z.cpu().numpy(), W), chain.RTOL, chain.ATOL, "H against the product of the reported Z")
+    Z2 = nan(n_rows, K)
+    two(Z2)
+    torch.cuda.synchronize()
+    say(f"[layer_forward] worst err/tol {worst:.3f}; elements of Z that differ in any bit from csgs_aggregate: {int((Z2 != Z).sum().item())} of {Z.numel()}")
+    # a device row count below the capacity: rows past it stay untouched
+    for count in (0, 1, 33, 500):
+        Z, H = nan(n_rows, K), nan(n_rows, N)
+        call(Z, H, nS_dev=torch.tensor([count], dtype=torch.int32, device=dev))
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(Z[count:]).all()) and bool(torch.isnan(H[count:]).all()), f"count {count}: wrote past the row count"
+        chain.assert_close(H[:count].cpu().numpy(), H_want[:count], chain.RTOL, chain.ATOL, f"device row count {count}")
+        chain.assert_close(Z[:count].cpu().numpy(), Z_want[:count], chain.RTOL, chain.ATOL, f"device row count {count}, Z")
+
+
+def test_layer_forward_instances_and_unsupported_widths(dev):
+    """Three instances in one launch equal three separate calls bit for bit; widths the kernel does not take are refused
+    before anything is enqueued."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(99)
+    n_inst, n_rows, n_cols, K, N = 3, 300, 400, 128, 96
+    t = lambda a: torch.from_numpy(a).to(dev)
+    cap = 16384
+    # the instances' adjacency arrays, counts and column bounds lie `stride` bytes apart in one buffer
+    stride = (4 * (n_rows + 1) + 8 * cap + 8 + 15) // 16 * 16
+    buf = torch.zeros(n_inst * stride // 4, dtype=torch.int32, device=dev)
+    Xs = rng.standard_normal((n_inst, n_cols, K)).astype(np.float32)
+    W = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
+    Xd, Wd = t(Xs), t(W)
+    views, wants = [], []
+    for k in range(n_inst):
+        rowptr, col, val = _random_adj(rng, n_rows, n_cols, 40)
+        assert len(col) <= cap
+        base = k * stride // 4
+        rp = buf[base:base + n_rows + 1]
+        cl = buf[base + n_rows + 1:base + n_rows + 1 + cap]
+        vl = buf[base + n_rows + 1 + cap:base + n_rows + 1 + 2 * cap].view(torch.float32)
+        cnt = buf[base + n_rows + 1 + 2 * cap:base + n_rows + 2 + 2 * cap]
+        nn = buf[base + n_rows + 2 + 2 * cap:base + n_rows + 3 + 2 * cap]
+        rp.copy_(t(rowptr)); cl[:len(col)].copy_(t(col)); vl[:len(val)].copy_(t(val))
+        cnt.fill_(n_rows - 10 * k); nn.fill_(n_cols)
+        views.append((rp, cl, vl, cnt, nn))
+        Zw = oracle.aggregate(rowptr, col, val, Xs[k], relu_on_input=True)
+        wants.append(oracle.layer_gemm(Zw, W)[:n_rows - 10 * k])
+    H = torch.full((n_inst, n_rows, N), float("nan"), dtype=torch.float32, device=dev)
+    Z = torch.full((n_inst, n_rows, K), float("nan"), dtype=torch.float32, device=dev)
+    rp, cl, vl, cnt, nn = views[0]
+    inst = csgs.InstStrides(n_inst, 0, stride, Xd.stride(0) * 4, 0, H.stride(0) * 4)
+    csgs.csgs_layer_forward(rp, cl, vl, nn, Xd[0], None, None, True, Wd, H[0], Z[0], nS_dev=cnt, inst=inst, z_stride=Z.stride(0) * 4)
+    torch.cuda.synchronize()
+    for k in range(n_inst):
+        rp, cl, vl, cnt, nn = views[k]
+        H1 = torch.full((n_rows, N), float("nan"), dtype=torch.float32, device=dev)
+        Z1 = torch.full((n_rows, K), float("nan"), dtype=torch.float32, device=dev)
+        csgs.csgs_layer_forward(rp, cl, vl, nn, Xd[k], None, None, True, Wd, H1, Z1, nS_dev=cnt)
+        torch.cuda.synchronize()
+        m = n_rows - 10 * k
+        assert bool((H1[:m] == H[k, :m]).all()) and bool((Z1[:m] == Z[k, :m]).all()), f"instance {k} differs from its own call"
+        assert bool(torch.isnan(H[k, m:]).all()) and bool(torch.isnan(Z[k, m:]).all())
+        chain.assert_close(H[k, :m].cpu().numpy(), wants[k], chain.RTOL, chain.ATOL, f"instance {k}")
+    say("[layer_forward] 3 instances in one launch equal their own calls")
+    for K_bad, dt in ((300, torch.float32), (512, torch.float32), (602, torch.int16), (101, torch.float32), (130, torch.float32)):
+        Xb = torch.zeros((8, K_bad), dtype=dt, device=dev)
+        assert not csgs.csgs_layer_forward_supported(Xb)
+        with pytest.raises(csgs.CsgsError) as e:
+            csgs.csgs_layer_forward(views[0][0], views[0][1], views[0][2], views[0][4], Xb, None, None, True,
+                                    torch.zeros((K_bad, 8), dtype=torch.float32, device=dev),
+                                    torch.zeros((n_rows, 8), dtype=torch.float32, device=dev))
+        assert e.value.code == csgs.EUNSUPPORTED, K_bad
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("mean_len,device_count", [(2, False), (2, True), (24, False), (24, True)])
