@@ -56,8 +56,11 @@ def algorithmic_bytes(s, N):
 
 
 class Workload:
-    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1, n_inst=1, batch_compute=False):
+    def __init__(self, cfg, g, dg, Xd, dev, n_batches, torch, pipeline, synth, csgs, n_samplers=1, n_inst=1, batch_compute=False,
+                 fused=None, n_comp=1):
         self.cfg, self.g, self.dg, self.Xd, self.dev = cfg, g, dg, Xd, dev
+        self.n_comp = n_comp    # streams for the layer compute: buffer set k is computed on stream k % n_comp
+        self.fused = fused      # None: csgs_aggregate + csgs_layer_gemm; "h" / "hz": csgs_layer_forward where it takes the width
         self.torch, self.pipeline, self.csgs = torch, pipeline, csgs
         self.bf16 = cfg.feat_dtype == "bf16"
         self.dims = synth.layer_dims(cfg)
@@ -95,10 +98,11 @@ class Workload:
         self.staged = torch.zeros((B, Xd.shape[1]), dtype=Xd.dtype, device=dev)   # sampled remote feature rows
         # all instances of a group through the same compute launches: per-instance Z, H and staged rows
         self.batch_compute = batch_compute and n_inst > 1
-        if self.batch_compute:
-            self.ZsK = [torch.empty((n_inst, nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)]
-            self.HsK = [torch.empty((n_inst, nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)]
-            self.stagedK = torch.zeros((n_inst, B, Xd.shape[1]), dtype=Xd.dtype, device=dev)
+        if self.batch_compute:      # one set of these per compute stream
+            self.ZsK_c = [[torch.empty((n_inst, nS_max, dims[M - 1 - l][0]), dtype=torch.float32, device=dev) for l in range(M)] for _ in range(n_comp)]
+            self.HsK_c = [[torch.empty((n_inst, nS_max, dims[M - 1 - l][1]), dtype=torch.float32, device=dev) for l in range(M)] for _ in range(n_comp)]
+            self.stagedK_c = [torch.zeros((n_inst, B, Xd.shape[1]), dtype=Xd.dtype, device=dev) for _ in range(n_comp)]
+            self.ZsK, self.HsK, self.stagedK = self.ZsK_c[0], self.HsK_c[0], self.stagedK_c[0]
 
     def enqueue_sampling(self, S0, it, lbs, ws):
         """Top-down sampling calls on the current stream, for one mini-batch or, when `ws` and `lbs`
@@ -122,30 +126,31 @@ class Workload:
             nS_dev = None if l == 0 else lbs[l - 1].n_next
             Z, Hn = self.Zs[l][:nS], self.Hs[l][:nS]
             if l == M - 1:
-                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev)
+                pipeline.compute_step(lbs[l], nS, self.X_local, self.staged, True, False, self.Wd[0], Z, Hn, nS_dev=nS_dev, fused=self.fused)
             else:
-                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev)
+                pipeline.compute_step(lbs[l], nS, H, None, False, True, self.Wd[M - 1 - l], Z, Hn, nS_dev=nS_dev, fused=self.fused)
             H = Hn
         return H
 
-    def enqueue_compute_group(self, lbs, n0, kk=None):
+    def enqueue_compute_group(self, lbs, n0, kk=None, c=0):
         """The same for the first kk instances (default: all) of a buffer set in the same launches (the _n
-        forms of the calls)."""
+        forms of the calls), into the Z / H / staged-row buffers of compute stream c."""
         M, B, pipeline = self.M, self.B, self.pipeline
         kk = self.n_inst if kk is None else kk
         nb = lambda t: t.stride(0) * t.element_size()
-        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, self.stagedK[0], out_stride=nb(self.stagedK), n_inst=kk)
+        ZsK, HsK, stagedK = self.ZsK_c[c], self.HsK_c[c], self.stagedK_c[c]
+        pipeline.stage_remote_rows(lbs[M - 1], self.Xd, stagedK[0], out_stride=nb(stagedK), n_inst=kk)
         for l in range(M - 1, -1, -1):
             nS = n0 if l == 0 else B
             nS_dev = None if l == 0 else lbs[l - 1].n_next
-            Z, H = self.ZsK[l], self.HsK[l]
+            Z, H = ZsK[l], HsK[l]
             if l == M - 1:
-                pipeline.compute_step(lbs[l], nS, self.X_local, self.stagedK[0], True, False, self.Wd[0], Z[0, :nS], H[0, :nS],
-                                      nS_dev=nS_dev, strides=(0, nb(self.stagedK), nb(Z), nb(H)), n_inst=kk)
+                pipeline.compute_step(lbs[l], nS, self.X_local, stagedK[0], True, False, self.Wd[0], Z[0, :nS], H[0, :nS],
+                                      nS_dev=nS_dev, strides=(0, nb(stagedK), nb(Z), nb(H)), n_inst=kk, fused=self.fused)
             else:
-                pipeline.compute_step(lbs[l], nS, self.HsK[l + 1][0, :B], None, False, True, self.Wd[M - 1 - l], Z[0, :nS], H[0, :nS],
-                                      nS_dev=nS_dev, strides=(nb(self.HsK[l + 1]), 0, nb(Z), nb(H)), n_inst=kk)
-        return self.HsK[0][kk - 1, :n0]
+                pipeline.compute_step(lbs[l], nS, HsK[l + 1][0, :B], None, False, True, self.Wd[M - 1 - l], Z[0, :nS], H[0, :nS],
+                                      nS_dev=nS_dev, strides=(nb(HsK[l + 1]), 0, nb(Z), nb(H)), n_inst=kk, fused=self.fused)
+        return HsK[0][kk - 1, :n0]
 
     def prepare_backward(self):
         """Buffers for the gradients of every layer (dW, dZ, dH_prev, scratch), sized for the capacities."""
@@ -217,13 +222,14 @@ class Workload:
         is one call."""
         torch, K, dev = self.torch, self.n_inst, self.dev
         samplers = [torch.cuda.Stream() for _ in range(self.n_samplers)]
-        s_comp = torch.cuda.Stream()
+        s_comps = [torch.cuda.Stream() for _ in range(self.n_comp)]
         self.S_all = torch.stack(self.Sd)        # all batches, resident: [n_batches, batch]
         n0 = self.Sd[0].numel()
         sizes_k = [K] + ([rem] if 0 < rem < K else [])
         sets = []
         for k in range(self.n_sets):
             s_samp = samplers[k % self.n_samplers]
+            c, s_comp = k % self.n_comp, s_comps[k % self.n_comp]
             lbs, ws = self.lb_sets[k], self.wss[k % self.n_samplers]
             lb0 = lbs[0]
             # first-layer rows of all instances: the S0 arrays of the set, one stride apart
@@ -244,9 +250,9 @@ class Workload:
                 self.enqueue_sampling(lb0.S0[:n0], idx, lbs, ws)      # the library reads idx[0]; instance k uses idx[0] + k
                 ws.desc.n_inst = K
 
-            def compute(kk=K, k=k, lbs=lbs):
+            def compute(kk=K, k=k, lbs=lbs, c=c):
                 if self.batch_compute:
-                    return self.enqueue_compute_group(lbs, n0, kk)
+                    return self.enqueue_compute_group(lbs, n0, kk, c)
                 H = None
                 for lk in self.lb_inst[k][:kk]:
                     H = self.enqueue_compute(lk, n0)
@@ -277,12 +283,12 @@ class Workload:
                     self.use_graphs = False
                     graphs = {}
             torch.cuda.synchronize()
-            H_of = lambda kk: self.HsK[0][kk - 1, :n0] if self.batch_compute else self.Hs[0][:n0]
+            H_of = lambda kk, c=c: self.HsK_c[c][0][kk - 1, :n0] if self.batch_compute else self.Hs[0][:n0]
             sets.append(dict(idx=idx, graphs=graphs, sample_fn=sample, compute_fn=compute, H_of=H_of,
-                             s_samp=s_samp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
+                             s_samp=s_samp, s_comp=s_comp, samp_done=torch.cuda.Event(), comp_done=torch.cuda.Event(), used=False))
         self.it_host = torch.arange(0, len(self.Sd), dtype=torch.int64, device=dev)   # iteration numbers, resident
         self.graph_it = [None] * self.n_sets     # first iteration number each set's counters hold for its next replay
-        self.overlap = dict(sets=sets, s_comp=s_comp)
+        self.overlap = dict(sets=sets, s_comp=s_comps[0])
 
     def group(self, it0, kk=None):
         """Mini-batches it0 .. it0 + kk - 1 (kk = n_inst unless it is the last, smaller group; it0 a
@@ -297,7 +303,7 @@ class Workload:
         kk = K if kk is None else kk
         k = (it0 // K) % self.n_sets
         st = self.overlap["sets"][k]
-        s_comp = self.overlap["s_comp"]
+        s_comp = self.overlap["s_comp"] if self.one_stream else st["s_comp"]
         g_samp, g_comp = st["graphs"].get(kk, (None, None))
         if self.one_stream:     # everything in order on the compute stream: every kernel has the device to itself
             with torch.cuda.stream(s_comp):
@@ -472,13 +478,20 @@ class Workload:
         sizes_once = sizes
         sizes = sizes * n_rep       # what the timed launches of pass (4) processed
         steps = n_rep * len(full) * K       # the steps the per-kernel passes covered: what the averages below are over
-        alg, flops = {}, 0.0
+        alg, flops, flops_fused = {}, 0.0, 0.0
+        one_kernel = lambda s: bool(self.fused) and bool(csgs.lib().csgs_layer_forward_supported(s["F_in"], 0, s["F_in"], s["F_in"]))
         for s in sizes:
-            for k, b in algorithmic_bytes(s, self.g.n_nodes).items():
+            ab = algorithmic_bytes(s, self.g.n_nodes)
+            if one_kernel(s):   # Z stays on the chip (or is written once, never read back), W and H as in the product
+                z = 4.0 * s["nS"] * s["F_in"]
+                ab["layer_forward"] = ab.pop("aggregate") - z + ab.pop("layer_gemm") - z + (z if self.fused == "hz" else 0.0)
+                flops_fused += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
+            else:
+                flops += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
+            for k, b in ab.items():
                 alg[k] = alg.get(k, 0.0) + b
             if s["layer"] == self.M - 1:    # staged remote rows: read once, written once
                 alg["gather_rows"] = alg.get("gather_rows", 0.0) + 2.0 * s["remote"] * s["F_in"] * s["elt"]
-            flops += 2.0 * s["nS"] * s["F_in"] * s["F_out"]
         kernels = {}
         for k, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             if k == "fill_zero":
@@ -493,12 +506,16 @@ class Workload:
             if sm:      # launch by launch: median and the 10th / 90th percentile, in us
                 pick = lambda f: sm[min(len(sm) - 1, int(f * len(sm)))] * 1e3
                 kernels[k].update(p10_us=pick(0.10), p50_us=pick(0.50), p90_us=pick(0.90))
-        agg_ms = prof["aggregate"][0]
-        agg_GBps = alg["aggregate"] / (agg_ms * 1e-3) / 1e9
-        gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
-
-        kernels["layer_gemm"]["TFLOPs"] = gemm_TF
-        kernels["layer_gemm"]["flop_per_launch"] = flops / prof["layer_gemm"][1]
+        agg_GBps = gemm_TF = None
+        if "aggregate" in prof:
+            agg_GBps = alg["aggregate"] / (prof["aggregate"][0] * 1e-3) / 1e9
+        if "layer_gemm" in prof:
+            gemm_TF = flops / (prof["layer_gemm"][0] * 1e-3) / 1e12
+            kernels["layer_gemm"]["TFLOPs"] = gemm_TF
+            kernels["layer_gemm"]["flop_per_launch"] = flops / prof["layer_gemm"][1]
+        if "layer_forward" in prof:
+            kernels["layer_forward"]["TFLOPs"] = flops_fused / (prof["layer_forward"][0] * 1e-3) / 1e12
+            kernels["layer_forward"]["flop_per_launch"] = flops_fused / prof["layer_forward"][1]
         tot = lambda key: sum(s[key] for s in sizes) / steps
         per_step = dict(edges_scanned=tot("E"), candidates=tot("nc"), sampled_nodes=tot("n_next"),
                         sampled_edges=tot("nnz"), remote_nodes=tot("remote"))
@@ -520,7 +537,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3    # the fp32 matrix peak, for comparison: the GEMM
 def roofline_of(kernels, name, traffic, k_inst):
     """Roofline object of one kernel.  traffic: (bytes per launch by kernel name or None, where from / why not)."""
     k = kernels[name]
-    if name == "layer_gemm":
+    if name in ("layer_gemm", "layer_forward"):
         r = dict(bound="mfma", kernel=name, achieved=k["TFLOPs"], peak=MFMA_F64_PEAK_TFLOPS, unit="TFLOP/s",
                  frac=k["TFLOPs"] / MFMA_F64_PEAK_TFLOPS, alg_per_launch=k["flop_per_launch"],
                  peak_is="fp64 matrix cores (the kernel multiplies and accumulates in double)",
@@ -537,10 +554,11 @@ def roofline_of(kernels, name, traffic, k_inst):
     return r
 
 
-def load_traffic(workload, k_inst):
-    """HBM bytes per launch and kernel from the committed counter summary profiles/<workload>_step_hbm_traffic.txt,
-    if that summary was taken with the same number of mini-batches per launch; else (None, why)."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_step_hbm_traffic.txt")
+def load_traffic(workload, k_inst, one_kernel=False):
+    """HBM bytes per launch and kernel from the committed counter summary profiles/<workload>_step_hbm_traffic.txt
+    (<workload>_step_layer_forward_hbm_traffic.txt for the schedule with csgs_layer_forward), if that summary was
+    taken with the same number of mini-batches per launch; else (None, why)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_step_{'layer_forward_' if one_kernel else ''}hbm_traffic.txt")
     if not os.path.exists(path):
         return None, f"no counter summary for workload {workload} under profiles/"
     lines = open(path).read().splitlines()
@@ -580,6 +598,7 @@ def main():
     ap.add_argument("--config", default="large")
     ap.add_argument("--scale", type=int, default=1, help="multiply batch and samples per layer of the main workload")
     ap.add_argument("--samplers", type=int, default=2, help="sampling streams (groups of batches sampled side by side)")
+    ap.add_argument("--compute-streams", type=int, default=1, help="streams for the layer compute (consecutive groups round-robin)")
     ap.add_argument("--instances", type=int, default=8, help="mini-batches per library call in the timed schedule (at most)")
     ap.add_argument("--no-batch-compute", action="store_true", help="with --instances K: sample K mini-batches per call but "
                     "compute their layers batch by batch (what a training loop must do: its forward passes depend on "
@@ -593,6 +612,9 @@ def main():
     ap.add_argument("--no-scaled", action="store_true", help="skip the x16 scaled-up variant")
     ap.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
     ap.add_argument("--no-theorem1", action="store_true", help="skip the sweep of D with the skew chosen by Theorem 1")
+    ap.add_argument("--no-layer-compare", action="store_true", help="skip the timing of the other --layer-compute choice")
+    ap.add_argument("--layer-compute", default="two", choices=["two", "h", "hz"],
+                    help="two: csgs_aggregate + csgs_layer_gemm; h: csgs_layer_forward (Z stays in LDS); hz: the same with Z written as well")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share); --gpus above 1 is not supported",
@@ -618,8 +640,9 @@ def main():
     dg = pipeline.DeviceGraph(g, dev)
     Xh = synth.to_bf16_bits(X).view(np.int16) if bf16 else X
     Xd = torch.from_numpy(Xh).to(dev)
-    mk = lambda c, nb, K: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
-                                   batch_compute=not args.no_batch_compute)
+    fused = None if args.layer_compute == "two" else args.layer_compute
+    mk = lambda c, nb, K, fused=fused: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
+                                                batch_compute=not args.no_batch_compute, fused=fused, n_comp=args.compute_streams)
     # a step is one mini-batch; the timed schedule handles K of them per call, whatever --steps is: exactly --steps
     # steps are timed, the last group being smaller when K does not divide them, and the per-kernel timing passes
     # (what the roofline figures come from) cover the full groups only.  The (untimed) warm-up is rounded up to a
@@ -713,7 +736,7 @@ def main():
     ms_per_step = res["ms_per_step"]
     log(f"timed {args.steps} steps: {ms_per_step:.3f} ms/step")
     dominant = next(iter(res["kernels"]))
-    roofline = roofline_of(res["kernels"], dominant, load_traffic(name, K), K)
+    roofline = roofline_of(res["kernels"], dominant, load_traffic(name, K, fused is not None), K)
     roofline["copy_kernel_GBps"] = copy_GBps
     roofline["atomic_adds_Gps"] = atomic_Gups      # what bounds scan_edges: one such add per scanned edge
     roofline["random_lookups_Gps"] = lookup_Gps    # 8-byte reads of random table entries: the adjacency pass does one per scanned edge
@@ -723,6 +746,22 @@ def main():
     if "scan_edges" in res["kernels"]:
         per_launch = res["per_step"]["edges_scanned"] / res["kernels"]["scan_edges"]["launches_per_step"]
         roofline["scan_edges_adds_Gps"] = per_launch / (res["kernels"]["scan_edges"]["avg_us"] * 1e-6) / 1e9
+
+    # the other way through a layer (one kernel instead of two, or two instead of one): the same schedule, timed the same
+    # way on its own buffers, so that the two stand beside each other in every line
+    other = None
+    if not args.no_layer_compare:
+        alt = "h" if fused is None else None
+        wo = mk(cfg, 48 + args.warmup, K, fused=alt)
+        wo.one_stream = args.one_stream
+        ro = wo.measure(48, args.warmup, serial=False)
+        pick = ("layer_forward",) if alt else ("aggregate", "layer_gemm")
+        other = dict(layer_compute="csgs_layer_forward (Z stays in LDS)" if alt else "csgs_aggregate + csgs_layer_gemm",
+                     steps=48, ms_per_step=ro["ms_per_step"],
+                     kernels={k: {a: round(b, 3) for a, b in ro["kernels"][k].items()} for k in pick if k in ro["kernels"]})
+        log(f"layer compute the other way ({other['layer_compute']}): {ro['ms_per_step']:.3f} ms/step over 48 steps; " +
+            ", ".join(f"{k} {v['avg_us']:.1f} us per launch" for k, v in other["kernels"].items()))
+        del wo, ro
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -790,15 +829,17 @@ def main():
         cfg_s = dataclasses.replace(cfg, batch=cfg.batch * sc, samples=cfg.samples * sc)
         rs = mk(cfg_s, 8, 1).measure(6, 2)
         tr = load_traffic(f"{cfg.name}_x{sc}", 1)
-        shown = ("aggregate", "layer_gemm", "scan_edges", "adj_fused", "cand_emit")
+        shown = ("aggregate", "layer_gemm", "layer_forward", "scan_edges", "adj_fused", "cand_emit")
         scaled = dict(workload=f"{cfg.name} x{sc}: batch {cfg_s.batch}, {cfg_s.samples} samples/layer",
                       ms_per_step=rs["ms_per_step"], one_stream_ms_per_step=rs["serial_ms_per_step"],
                       sampled_edges_per_s=rs["per_step"]["sampled_edges"] / (rs["ms_per_step"] * 1e-3),
                       per_step=rs["per_step"], aggregate_GBps=rs["aggregate_GBps"], gemm_TFLOPs=rs["gemm_TFLOPs"],
                       rooflines=[roofline_of(rs["kernels"], k, tr, 1) for k in rs["kernels"] if k in shown],
                       kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in rs["kernels"].items()})
-        log(f"scaled x{sc}: {rs['ms_per_step']:.3f} ms/step, aggregate {rs['aggregate_GBps']:.0f} GB/s, "
-            f"gemm {rs['gemm_TFLOPs']:.1f} TFLOP/s")
+        fmt = lambda v, f: "-" if v is None else format(v, f)
+        log(f"scaled x{sc}: {rs['ms_per_step']:.3f} ms/step, aggregate {fmt(rs['aggregate_GBps'], '.0f')} GB/s, "
+            f"gemm {fmt(rs['gemm_TFLOPs'], '.1f')} TFLOP/s" +
+            (f", layer_forward {rs['kernels']['layer_forward']['TFLOPs']:.1f} TFLOP/s" if "layer_forward" in rs["kernels"] else ""))
 
     dims = synth.layer_dims(cfg)
     out = dict(
@@ -821,6 +862,7 @@ def main():
                  ("replayed from a HIP graph" if res["graphs"] else "launched call by call"),
         aggregate_GBps=res["aggregate_GBps"], gemm_TFLOPs=res["gemm_TFLOPs"],
         scanned_edges_per_s=res["per_step"]["edges_scanned"] / (ms_per_step * 1e-3),
+        layer_compute="csgs_aggregate + csgs_layer_gemm" if fused is None else f"csgs_layer_forward ({fused})", layer_compute_other=other,
         roofline=roofline, cpu_baseline=cpu_baseline, backward=backward, theorem1_sweep=t1, instances_sweep=sweep,
         kernels={k: {a: round(b, 3) for a, b in v.items()} for k, v in res["kernels"].items()}, scaled=scaled)
     print(json.dumps(out))

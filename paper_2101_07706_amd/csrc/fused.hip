@@ -24,6 +24,16 @@ namespace csgs {
 constexpr int FUSED_ROWS = 32;   // rows of Z per block: one 8-row tile per wavefront
 constexpr int FUSED_POOL = 64;   // edges a wavefront stages at a time (8 rows hold a few dozen)
 
+// A store the compiler does not keep count of.  Loads and stores share one counter of outstanding operations, and loads
+// come back in order only among themselves; with a store of its own outstanding the compiler therefore waits for
+// everything before it uses any loaded value, which would drain the ring of weight fetches at every step.  A store
+// it does not see leaves its count of the loads exact, and the extra outstanding operation only makes a wait for
+// "all but the last n" longer, never shorter.  Nothing in the kernel reads what these stores write.
+__device__ inline void store_untracked(float *p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+
 // KP: capacity of the LDS tile in features (64, 128 or 256); a lane holds V = KP / 64 consecutive features.
 template <typename T, int KP, bool RELU>
 __global__ __launch_bounds__(AGG_BLOCK, 3) void layer_forward_k(const int32_t *__restrict__ adj_rowptr,
@@ -98,25 +108,16 @@ __global__ __launch_bounds__(AGG_BLOCK, 3) void layer_forward_k(const int32_t *_
             b[s] = col[(int64_t)(k < K ? k : K - 1) * ldw];
         }
     };
-    float b_cur[8], b_nxt[8];
-    if (n_steps > 0) fetch_b(0, b_cur);   // on its way while the block gathers its last rows
-    __syncthreads();                      // the tile is complete
-
-    if (Zout) {   // the caller wants Z as well: rows below the count, K floats each
-        const int32_t rows_here = nS - block_row0 < FUSED_ROWS ? (int32_t)(nS - block_row0) : FUSED_ROWS;
-        for (int i = tid; i < rows_here * K; i += AGG_BLOCK) {
-            const int r = i / K, k = i % K;
-            Zout[(block_row0 + r) * ldz + k] = Zt[r * ZS + k];
-        }
-    }
-
+    // The weights of the next PF steps are on their way while a step's MFMAs run (one step is 16 MFMAs, far less than a
+    // trip to L2): a ring of PF register sets, set d serving the chunks c with c % PF = d.  PF divides the chunks of a
+    // tile (4, 2 or 1), and neither a fetch nor a store sits under a condition: the wavefront's memory operations
+    // then come in one fixed order, and each wait is for exactly the set that is needed, with the later ones
+    // still in flight.  (A fetch past the last step repeats the last step's.)
     doublex4 acc[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) acc[r] = doublex4{0.0, 0.0, 0.0, 0.0};
     const int a_off = l16 * ZS + 8 * grp;
-    for (int j = 0; j < n_steps; ++j) {
-        const int c = j % n_chunks;
-        if (j + 1 < n_steps) fetch_b(j + 1, b_nxt);
+    auto mfma_chunk = [&](int c, const float (&bj)[8]) {
         float av[RT][8];
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
@@ -125,35 +126,58 @@ __global__ __launch_bounds__(AGG_BLOCK, 3) void layer_forward_k(const int32_t *_
             av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
             av[r][4] = y.x; av[r][5] = y.y; av[r][6] = y.z; av[r][7] = y.w;
         }
-        const int k_lane = c * BK + 8 * grp;          // this lane's first k of the chunk
-        const bool last = c + 1 == n_chunks;
-        const int k_left = K - c * BK;                // real k in this chunk (>= 1)
-        const int s_end = (!last || k_left >= 8) ? 8 : k_left;   // steps in which any lane group holds a real k
+        // (no step is skipped, not even one of the last chunk in which every k is padding: a branch inside the loop
+        // makes the compiler lose count of the fetches in flight, and it then waits for all of them at every step)
+        const int k_lane = c * BK + 8 * grp;      // this lane's first k of the chunk
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            if (s < s_end) {
-                const float bs = (!last || k_lane + s < K) ? b_cur[s] : 0.f;
-                const double b = (double)bs;
+            const float bs = k_lane + s < K ? bj[s] : 0.f;
+            const double b = (double)bs;
 #pragma unroll
-                for (int r = 0; r < RT; ++r) acc[r] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[r][s], b, acc[r], 0, 0, 0);
-            }
+            for (int r = 0; r < RT; ++r) acc[r] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[r][s], b, acc[r], 0, 0, 0);
         }
-        if (last) {
+    };
+    auto run = [&](auto pf) {
+        constexpr int PF = decltype(pf)::value;
+        float bq[PF][8];
+        const int j_last = n_steps > 0 ? n_steps - 1 : 0;
+        if (n_steps > 0) {
+#pragma unroll
+            for (int d = 0; d < PF; ++d) fetch_b(d < n_steps ? d : j_last, bq[d]);   // on their way while the block gathers its last rows
+        }
+        __syncthreads();                          // the tile is complete
+        for (int tl = 0; tl < my_tiles; ++tl) {
+            for (int c0 = 0; c0 < n_chunks; c0 += PF) {
+#pragma unroll
+                for (int d = 0; d < PF; ++d) {
+                    mfma_chunk(c0 + d, bq[d]);
+                    const int jn = tl * n_chunks + c0 + d + PF;   // this set's next turn
+                    fetch_b(jn < n_steps ? jn : j_last, bq[d]);
+                }
+            }
             // accumulator element i of lane l holds row l / 16 + 4 i, column l % 16 of its 16 x 16 tile
-            const int t = wave + (j / n_chunks) * AGG_WAVES;
-            const int64_t col = (int64_t)t * 16 + l16;
+            const int64_t col = (int64_t)(wave + tl * AGG_WAVES) * 16 + l16;
+            const bool col_ok = col < N;
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int64_t row = block_row0 + r * 16 + grp + 4 * i;
-                    if (row < nS && col < N) H[row * ldh + col] = (float)acc[r][i];
+                    if (row < nS && col_ok) store_untracked(H + row * ldh + col, (float)acc[r][i]);
                 }
                 acc[r] = doublex4{0.0, 0.0, 0.0, 0.0};
             }
         }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) b_cur[s] = b_nxt[s];
+    };
+    if (n_chunks % 4 == 0) run(std::integral_constant<int, 4>{});
+    else if (n_chunks % 2 == 0) run(std::integral_constant<int, 2>{});
+    else run(std::integral_constant<int, 1>{});
+    if (Zout) {   // the caller wants Z as well: rows below the count, K floats each (the tile is still whole)
+        const int32_t rows_here = nS - block_row0 < FUSED_ROWS ? (int32_t)(nS - block_row0) : FUSED_ROWS;
+        for (int i = tid; i < rows_here * K; i += AGG_BLOCK) {
+            const int r = i / K, k = i % K;
+            Zout[(block_row0 + r) * ldz + k] = Zt[r * ZS + k];
+        }
     }
 }
 
