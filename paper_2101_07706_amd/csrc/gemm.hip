@@ -138,9 +138,11 @@ __global__ __launch_bounds__(256, (MODE == MODE_FWD && BM_ == 128 && BN == 64) ?
     // 16-column MFMA tiles of this block that hold any real column (47 output classes fill 3 of 4), and
     // k steps of the last chunk that hold any real k (lane group g feeds k = 8 g + s at step s, so with
     // k_left <= 8 only the first k_left steps of group 0 are not padding): the rest would multiply zeros
-    const int nt_valid = (int)(N - n0 >= BN ? NT : (N - n0 + 15) / 16);
+    // (a regular shape has neither: then nothing in the chunk loop sits under a condition, and the compiler is free to
+    // order the conversions, the MFMAs and the next chunk's loads)
+    const int nt_valid = FULL ? NT : (int)(N - n0 >= BN ? NT : (N - n0 + 15) / 16);
     const int k_left = n_chunks > 0 ? (k_end - k_begin) - (n_chunks - 1) * BK : 0;
-    const int s_last = k_left >= 8 ? 8 : k_left;
+    const int s_last = (FULL || k_left >= 8) ? 8 : k_left;
     for (int c = 0; c < n_chunks; ++c) {
         const int cur = c & 1;
         if (c + 1 < n_chunks) fetch(k_begin + (c + 1) * BK);
@@ -166,16 +168,16 @@ __global__ __launch_bounds__(256, (MODE == MODE_FWD && BM_ == 128 && BN == 64) ?
             bv[t][0] = x.x; bv[t][1] = x.y; bv[t][2] = x.z; bv[t][3] = x.w;
             bv[t][4] = y.x; bv[t][5] = y.y; bv[t][6] = y.z; bv[t][7] = y.w;
         }
-        const int s_end = c + 1 < n_chunks ? 8 : s_last;
+        const int s_end = (FULL || c + 1 < n_chunks) ? 8 : s_last;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            if (s < s_end) {
+            if (FULL || s < s_end) {
                 double a[RT];
 #pragma unroll
                 for (int r = 0; r < RT; ++r) a[r] = (double)av[r][s];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    if (t < nt_valid) {
+                    if (FULL || t < nt_valid) {
                         const double b = (double)bv[t][s];
 #pragma unroll
                         for (int r = 0; r < RT; ++r) acc[r][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[r][t], 0, 0, 0);
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256, (MODE == MODE_FWD && BM_ == 128 && BN == 64) ?
         for (int r = 0; r < RT; ++r) a[r] = (double)As[last][(wave * (BM_ / 4) + r * 16 + l16) * LDS_STRIDE + BK + grp];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            if (t < nt_valid) {
+            if (FULL || t < nt_valid) {
                 const double b = (double)(SWZ ? Bt[(t * 16 + l16) * 4 + grp] : Bs[last][(t * 16 + l16) * LDS_STRIDE + BK + grp]);
 #pragma unroll
                 for (int r = 0; r < RT; ++r) acc[r][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[r][t], 0, 0, 0);
