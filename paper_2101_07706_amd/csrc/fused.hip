@@ -90,88 +90,133 @@ __global__ __launch_bounds__(AGG_BLOCK, 3) void layer_forward_k(const int32_t *_
         aggregate_long_rows<T, V, G, RELU, true>(part, block_row0, block_row0, is_long, f, active, adj_rowptr, adj_col, adj_val, n_cols, Xl,
                                                  ldl, rows_l, Xr, ldr, rows_r, src_row, Zt, ZS, nullptr, 0);
 
-    // ---- 2. the product.  Tile t of 16 columns, chunk c of 32 k: step j = t_local * n_chunks + c of this wavefront
+    // ---- 2. the product.  Tile t of 16 columns, chunk c of 32 k; this wavefront takes the tiles wave, wave + 4, ...
     const int grp = lane >> 4, l16 = lane & 15;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int n_tiles16 = (N + 15) / 16;
-    const int my_tiles = n_tiles16 > wave ? (n_tiles16 - wave + AGG_WAVES - 1) / AGG_WAVES : 0;
-    const int n_steps = my_tiles * n_chunks;
-    // lane (g, n) of step j needs W[32 c + 8 g + s][16 t + n], s = 0..7; a k or a column that does not exist reads
-    // the nearest real element (such a k meets zeros of the tile and is masked when used, such a column is not stored)
-    auto fetch_b = [&](int j, float (&b)[8]) {
-        const int t = wave + (j / n_chunks) * AGG_WAVES, c = j % n_chunks;
-        const int n = t * 16 + l16;
-        const float *col = W + (n < N ? n : N - 1);
-        const int k0 = c * BK + 8 * grp;
+    const int my_tiles = n_tiles16 > wave_u ? (n_tiles16 - wave_u + AGG_WAVES - 1) / AGG_WAVES : 0;
+    // Lane (g, n) needs W[32 c + 8 g + s][first column of the tile + n], s = 0..7.  The address is a part that the whole
+    // wavefront shares (chunk and tile: scalar arithmetic) plus a lane's own byte offset that never changes, so a
+    // fetch costs no vector arithmetic.  A ragged last tile is moved left to end at column N (its first columns repeat
+    // the tile before and are not stored; with fewer than 16 columns in all, lanes beyond N read column N - 1).  In a
+    // ragged last chunk a k that does not exist reads the last real one and is dropped when used.
+    const int lc = N >= 16 ? l16 : (l16 < N ? l16 : N - 1);
+    const int k_last0 = (n_chunks - 1) * BK;
+    uint32_t off[8], off_last[8];
+    bool k_real[8];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int k = k0 + s;
-            b[s] = col[(int64_t)(k < K ? k : K - 1) * ldw];
-        }
+    for (int s = 0; s < 8; ++s) {
+        const int k = 8 * grp + s;
+        off[s] = (uint32_t)(((int64_t)k * ldw + lc) * 4);      // ldw is below 2^24 (checked on the host)
+        k_real[s] = k_last0 + k < K;
+        off_last[s] = (uint32_t)(((int64_t)(k_real[s] ? k : K - 1 - k_last0) * ldw + lc) * 4);
+    }
+    auto tile_col0 = [&](int tl) {   // first column of this wavefront's tile tl
+        const int c0 = (wave_u + tl * AGG_WAVES) * 16;
+        return N >= 16 ? (c0 < N - 16 ? c0 : N - 16) : 0;
     };
-    // The weights of the next PF steps are on their way while a step's MFMAs run (one step is 16 MFMAs, far less than a
-    // trip to L2): a ring of PF register sets, set d serving the chunks c with c % PF = d.  PF divides the chunks of a
-    // tile (4, 2 or 1), and neither a fetch nor a store sits under a condition: the wavefront's memory operations
+    // The weights of the next PF steps are on their way while a step's MFMAs run (one step is 16 or 32 MFMAs, far less
+    // than a trip to L2): a ring of PF register sets, set d serving the chunks c with c % PF = d.  PF divides the chunks
+    // of a tile (4, 2 or 1), and neither a fetch nor a store sits under a condition: the wavefront's memory operations
     // then come in one fixed order, and each wait is for exactly the set that is needed, with the later ones
-    // still in flight.  (A fetch past the last step repeats the last step's.)
-    doublex4 acc[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) acc[r] = doublex4{0.0, 0.0, 0.0, 0.0};
+    // still in flight.
+    // NT: column tiles a wavefront works on at a time.  RAGGED: K is no multiple of 32 (only then the last chunk
+    // needs its own offsets and drops values).
     const int a_off = l16 * ZS + 8 * grp;
-    auto mfma_chunk = [&](int c, const float (&bj)[8]) {
-        float av[RT][8];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            const float *ap = &Zt[a_off + r * 16 * ZS + c * BK];
-            const float4 x = *reinterpret_cast<const float4 *>(ap), y = *reinterpret_cast<const float4 *>(ap + 4);
-            av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
-            av[r][4] = y.x; av[r][5] = y.y; av[r][6] = y.z; av[r][7] = y.w;
-        }
-        // (no step is skipped, not even one of the last chunk in which every k is padding: a branch inside the loop
-        // makes the compiler lose count of the fetches in flight, and it then waits for all of them at every step)
-        const int k_lane = c * BK + 8 * grp;      // this lane's first k of the chunk
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const float bs = k_lane + s < K ? bj[s] : 0.f;
-            const double b = (double)bs;
-#pragma unroll
-            for (int r = 0; r < RT; ++r) acc[r] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[r][s], b, acc[r], 0, 0, 0);
-        }
-    };
-    auto run = [&](auto pf) {
+    auto run = [&](auto pf, auto nt, auto ragged) {
         constexpr int PF = decltype(pf)::value;
-        float bq[PF][8];
-        const int j_last = n_steps > 0 ? n_steps - 1 : 0;
-        if (n_steps > 0) {
+        constexpr int NT = decltype(nt)::value;
+        constexpr bool RAGGED = decltype(ragged)::value;
+        const int my_groups = my_tiles / NT;
+        doublex4 acc[NT][RT];
 #pragma unroll
-            for (int d = 0; d < PF; ++d) fetch_b(d < n_steps ? d : j_last, bq[d]);   // on their way while the block gathers its last rows
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < RT; ++r) acc[t][r] = doublex4{0.0, 0.0, 0.0, 0.0};
+        int ft = 0, fc = 0;   // tile group and chunk of the next fetch
+        auto fetch_b = [&](float (&bv)[NT][8]) {
+            const bool last = RAGGED && fc + 1 == n_chunks;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const char *base = reinterpret_cast<const char *>(W) + ((int64_t)fc * BK * ldw + tile_col0(ft * NT + t)) * 4;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) bv[t][s] = *reinterpret_cast<const float *>(base + (last ? off_last[s] : off[s]));
+            }
+            // on to the next step; past the last one the position stays, and the fetch is repeated
+            const bool wrap = fc + 1 == n_chunks;
+            const int nft = ft + (wrap ? 1 : 0), nfc = wrap ? 0 : fc + 1;
+            const bool end = nft >= my_groups;
+            ft = end ? ft : nft;
+            fc = end ? fc : nfc;
+        };
+        auto mfma_chunk = [&](int c, const float (&bj)[NT][8]) {
+            float av[RT][8];
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const float *ap = &Zt[a_off + r * 16 * ZS + c * BK];
+                const float4 x = *reinterpret_cast<const float4 *>(ap), y = *reinterpret_cast<const float4 *>(ap + 4);
+                av[r][0] = x.x; av[r][1] = x.y; av[r][2] = x.z; av[r][3] = x.w;
+                av[r][4] = y.x; av[r][5] = y.y; av[r][6] = y.z; av[r][7] = y.w;
+            }
+            // (no step is skipped, not even one of the last chunk in which every k is padding: a branch inside the loop
+            // makes the compiler lose count of the fetches in flight, and it then waits for all of them at every step)
+            const bool last = RAGGED && c + 1 == n_chunks;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                double a[RT];
+#pragma unroll
+                for (int r = 0; r < RT; ++r) a[r] = (double)av[r][s];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const float bs = (!last || k_real[s]) ? bj[t][s] : 0.f;
+                    const double b = (double)bs;
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) acc[t][r] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[r], b, acc[t][r], 0, 0, 0);
+                }
+            }
+        };
+        float bq[PF][NT][8];
+        if (my_groups > 0) {
+#pragma unroll
+            for (int d = 0; d < PF; ++d) fetch_b(bq[d]);   // on their way while the block gathers its last rows
         }
         __syncthreads();                          // the tile is complete
-        for (int tl = 0; tl < my_tiles; ++tl) {
+        for (int tl = 0; tl < my_groups; ++tl) {
             for (int c0 = 0; c0 < n_chunks; c0 += PF) {
 #pragma unroll
                 for (int d = 0; d < PF; ++d) {
                     mfma_chunk(c0 + d, bq[d]);
-                    const int jn = tl * n_chunks + c0 + d + PF;   // this set's next turn
-                    fetch_b(jn < n_steps ? jn : j_last, bq[d]);
+                    fetch_b(bq[d]);               // this set's next turn
                 }
             }
             // accumulator element i of lane l holds row l / 16 + 4 i, column l % 16 of its 16 x 16 tile
-            const int64_t col = (int64_t)(wave + tl * AGG_WAVES) * 16 + l16;
-            const bool col_ok = col < N;
 #pragma unroll
-            for (int r = 0; r < RT; ++r) {
+            for (int t = 0; t < NT; ++t) {
+                const int first_new = (wave_u + (tl * NT + t) * AGG_WAVES) * 16;   // columns before it belong to the tile before
+                const int64_t col = (int64_t)tile_col0(tl * NT + t) + l16;
+                const bool col_ok = col >= first_new && col < N;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int64_t row = block_row0 + r * 16 + grp + 4 * i;
-                    if (row < nS && col_ok) store_untracked(H + row * ldh + col, (float)acc[r][i]);
+                for (int r = 0; r < RT; ++r) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int64_t row = block_row0 + r * 16 + grp + 4 * i;
+                        if (row < nS && col_ok) store_untracked(H + row * ldh + col, (float)acc[t][r][i]);
+                    }
+                    acc[t][r] = doublex4{0.0, 0.0, 0.0, 0.0};
                 }
-                acc[r] = doublex4{0.0, 0.0, 0.0, 0.0};
             }
         }
     };
-    if (n_chunks % 4 == 0) run(std::integral_constant<int, 4>{});
-    else if (n_chunks % 2 == 0) run(std::integral_constant<int, 2>{});
-    else run(std::integral_constant<int, 1>{});
+    using std::integral_constant;
+    auto pick_pf = [&](auto nt, auto ragged) {
+        if (n_chunks % 4 == 0) run(integral_constant<int, 4>{}, nt, ragged);
+        else if (n_chunks % 2 == 0) run(integral_constant<int, 2>{}, nt, ragged);
+        else run(integral_constant<int, 1>{}, nt, ragged);
+    };
+    // (two column tiles at a time per wavefront, the conversions of A shared by two MFMAs, were measured: 168 instead
+    // of 118 registers and no faster)
+    if (K % BK == 0) pick_pf(integral_constant<int, 1>{}, std::false_type{});
+    else pick_pf(integral_constant<int, 1>{}, std::true_type{});
     if (Zout) {   // the caller wants Z as well: rows below the count, K floats each (the tile is still whole)
         const int32_t rows_here = nS - block_row0 < FUSED_ROWS ? (int32_t)(nS - block_row0) : FUSED_ROWS;
         for (int i = tid; i < rows_here * K; i += AGG_BLOCK) {
@@ -249,7 +294,7 @@ extern "C" int csgs_layer_forward_n(const csgs_inst_strides *inst, const int32_t
     if (dtype != CSGS_F32 && dtype != CSGS_BF16) return CSGS_EUNSUPPORTED;
     if (rows_remote > 0x7FFFFFFEll) return CSGS_EUNSUPPORTED;   // staged rows are addressed as -1 - row in 32 bits
     const int v = fused_vec(F_in);
-    if (v == 0) return CSGS_EUNSUPPORTED;
+    if (v == 0 || ldw >= (1ll << 24)) return CSGS_EUNSUPPORTED;   // (the kernel keeps byte offsets into a 32-row chunk of W in 32 bits)
     // every gathered row must start on a multiple of the lanes' load width
     const uintptr_t bytes = (uintptr_t)v * (dtype == CSGS_F32 ? 4 : 2);
     if ((X_local && (ld_local % v != 0 || (uintptr_t)X_local % bytes != 0)) || (X_remote && (ld_remote % v != 0 || (uintptr_t)X_remote % bytes != 0)))
