@@ -181,3 +181,28 @@ def test_compute_instance_strides_are_checked():
         assert L.csgs_aggregate_n(C.byref(inst), p, p, p, 4, z, z, p, 8, 4, z, 0, 0, z, 8, 0, 0, p, 8, z) == csgs.EINVAL
         assert L.csgs_layer_gemm_n(C.byref(inst), p, 8, 4, z, 8, p, 8, 8, p, 8, z) == csgs.EINVAL
         assert L.csgs_gather_rows_n(C.byref(inst), p, 8, 4, 8, 0, p, 4, z, p, 8, z) == csgs.EINVAL
+
+
+def test_layer_forward_checks_its_arguments_on_the_host():
+    """csgs_layer_forward: which input widths it takes, and what it refuses before anything is enqueued."""
+    L = csgs.lib()
+    z, p = C.c_void_p(0), C.c_void_p(4096)
+    sup = L.csgs_layer_forward_supported
+    assert [sup(k, csgs.F32, k, k) for k in (1, 33, 64, 100, 128, 256)] == [1] * 6
+    assert [sup(k, csgs.F32, k, k) for k in (0, 65, 101, 130, 258, 300, 512, 602)] == [0] * 8
+    assert sup(100, csgs.BF16, 100, 0) == 1 and sup(100, csgs.BF16, 101, 0) == 0 and sup(256, csgs.F32, 256, 258) == 0
+    assert sup(64, 7, 64, 64) == 0      # no such element type
+
+    def call(F_in=64, dtype=csgs.F32, ld=64, W=p, ldw=32, H=p, ldh=32, Z=z, ldz=0, adj=p):
+        return L.csgs_layer_forward(adj, p, p, 100, z, z, p, ld, 1000, z, 0, 0, z, F_in, dtype, 1, W, ldw, 32, H, ldh, Z, ldz, z)
+
+    assert call(adj=z) == csgs.EINVAL and call(W=z) == csgs.EINVAL and call(H=z) == csgs.EINVAL
+    assert call(ld=63) == csgs.EINVAL and call(ldw=31) == csgs.EINVAL and call(ldh=31) == csgs.EINVAL and call(Z=p, ldz=63) == csgs.EINVAL
+    assert call(F_in=300, ld=300) == csgs.EUNSUPPORTED and call(F_in=100, ld=101) == csgs.EUNSUPPORTED
+    assert call(dtype=7) == csgs.EUNSUPPORTED and call(ldw=1 << 24) == csgs.EUNSUPPORTED
+    inst = csgs.InstStrides(3, 0, 16, 16, 0, 16)
+    bad = csgs.InstStrides(3, 0, 16, 16, 0, 8)
+    args = (p, p, p, 100, z, z, p, 64, 1000, z, 0, 0, z, 64, csgs.F32, 1, p, 32, 32, p, 32, z, 0)
+    assert L.csgs_layer_forward_n(C.byref(bad), *args, 0, z) == csgs.EINVAL
+    assert L.csgs_layer_forward_n(C.byref(inst), *args, 8, z) == csgs.EINVAL      # stride of Z: a multiple of 16
+    assert L.csgs_layer_forward_n(C.byref(inst), *args[:13], 300, *args[14:], 0, z) == csgs.EINVAL   # ld_local below the width
