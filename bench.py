@@ -290,9 +290,10 @@ class Workload:
         self.graph_it = [None] * self.n_sets     # first iteration number each set's counters hold for its next replay
         self.overlap = dict(sets=sets, s_comp=s_comps[0])
 
-    def group(self, it0, kk=None):
-        """Mini-batches it0 .. it0 + kk - 1 (kk = n_inst unless it is the last, smaller group; it0 a
-        multiple of n_inst), enqueued without the host waiting for anything.  Their sampling (top-down)
+    def group(self, it0, kk=None, seq=None):
+        """Mini-batches it0 .. it0 + kk - 1 (kk = n_inst unless it is the one smaller group), enqueued without the
+        host waiting for anything; seq: the group's number in the sequence of groups (default it0 // n_inst), which
+        picks its buffer set and streams.  Their sampling (top-down)
         is ONE sequence of library calls over kk instances; consecutive groups go round-robin to
         n_samplers streams, each with its own workspace.  The layer compute (bottom-up) of all batches
         runs in batch order on one more stream; events tie a group's compute to its sampling and a
@@ -301,7 +302,7 @@ class Workload:
         Every step still does all of its work."""
         torch, K = self.torch, self.n_inst
         kk = K if kk is None else kk
-        k = (it0 // K) % self.n_sets
+        k = (it0 // K if seq is None else seq) % self.n_sets
         st = self.overlap["sets"][k]
         s_comp = self.overlap["s_comp"] if self.one_stream else st["s_comp"]
         g_samp, g_comp = st["graphs"].get(kk, (None, None))
@@ -390,14 +391,17 @@ class Workload:
         return H
 
     def measure(self, steps, warmup, serial=True):
-        """Timed region: exactly `steps` steps in groups of n_inst mini-batches, the last group smaller
+        """Timed region: exactly `steps` steps in groups of n_inst mini-batches, the first group smaller
         when n_inst does not divide them (warmup is a multiple of n_inst).  Then the full groups again,
         launched call by call with every kernel launch bracketed by HIP events (recorded on the launch
         stream): every launch these passes time handles n_inst mini-batches, whatever `steps` is."""
         torch, csgs, K = self.torch, self.csgs, self.n_inst
         assert steps >= K and warmup % K == 0 and len(self.Sd) >= steps + warmup
         n0 = self.Sd[0].numel()
-        chunks = [(it0, min(K, warmup + steps - it0)) for it0 in range(warmup, warmup + steps, K)]
+        # the one smaller group (when K does not divide the steps) goes first: the compute stream, idle until the first
+        # group is sampled, then starts sooner, and what the region ends with is a full group's compute either way
+        rem = steps % K
+        chunks = ([(warmup, rem)] if rem else []) + [(it0, K) for it0 in range(warmup + rem, warmup + steps, K)]
         full = [c for c in chunks if c[1] == K]
         # (1) one stream, one mini-batch per call, steps back to back: the latency of a step
         serial_ms, h_serial = None, None
@@ -418,8 +422,8 @@ class Workload:
             self.group(it0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for it0, kk in chunks:
-            H = self.group(it0, kk)
+        for seq, (it0, kk) in enumerate(chunks):
+            H = self.group(it0, kk, seq)
         enqueue_ms = (time.perf_counter() - t0) / steps * 1e3     # host time to enqueue a step (no waiting in it)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) / steps * 1e3
@@ -428,7 +432,7 @@ class Workload:
         assert all(int(lb.status.item()) == 0 for set_ in self.lb_inst for lk in set_ for lb in lk), \
             "a status bit was set in the timed run"
         log(f"host enqueue {enqueue_ms:.3f} ms/step; " + (f"one stream, one batch per call {serial_ms:.3f} ms/step; " if serial else "") +
-            f"{K} batches per sampling call" + (f" (last group {chunks[-1][1]})" if chunks[-1][1] != K else "") + ", " +
+            f"{K} batches per sampling call" + (f" (first group {chunks[0][1]})" if chunks[0][1] != K else "") + ", " +
             ("everything in order on one stream" if self.one_stream else "sampling and compute overlapped") +
             f" {ms_per_step:.3f} ms/step")
         # (3) how long the kernels take inside the timed schedule, beside the kernels of the other streams: the full
@@ -527,8 +531,8 @@ class Workload:
             per_layer.append(dict(layer=l, rows=avg("nS"), edges_scanned=avg("E"), candidates=avg("nc"), sampled_nodes=avg("n_next"),
                                   sampled_edges=avg("nnz"), remote_nodes=avg("remote"), F_in=ls[0]["F_in"], F_out=ls[0]["F_out"]))
         per_step["per_layer"] = per_layer
-        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes_once,
-                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF, last_group=chunks[-1][1])
+        return dict(ms_per_step=ms_per_step, serial_ms_per_step=serial_ms, graphs=self.use_graphs, kernels=kernels, per_step=per_step, sizes=sizes_once, sizes_it=full[0][0],
+                    aggregate_GBps=agg_GBps, gemm_TFLOPs=gemm_TF, smaller_group=chunks[0][1] if chunks[0][1] != K else None)
 
 
 MFMA_F32_PEAK_TFLOPS = 157.3    # the fp32 matrix peak, for comparison: the GEMM's inputs and outputs are fp32
@@ -644,7 +648,7 @@ def main():
     mk = lambda c, nb, K, fused=fused: Workload(c, g, dg, Xd, dev, nb, torch, pipeline, synth, csgs, n_samplers=args.samplers, n_inst=K,
                                                 batch_compute=not args.no_batch_compute, fused=fused, n_comp=args.compute_streams)
     # a step is one mini-batch; the timed schedule handles K of them per call, whatever --steps is: exactly --steps
-    # steps are timed, the last group being smaller when K does not divide them, and the per-kernel timing passes
+    # steps are timed, the first group being smaller when K does not divide them, and the per-kernel timing passes
     # (what the roofline figures come from) cover the full groups only.  The (untimed) warm-up is rounded up to a
     # multiple of K
     K = max(1, min(args.instances, args.steps))
@@ -780,7 +784,7 @@ def main():
         for it in range(args.warmup, args.warmup + n_cpu):
             osteps = chain.oracle_chain(g, X, wl.Ws, wl.batches[it], cfg.skew, wl.B, wl.seed, it, bf16)
             cpu_nnz += sum(o.sm.adj_nnz for o in osteps)
-            if it == args.warmup:   # spot check: the GPU step of the same batch drew the same nodes
+            if it == res["sizes_it"]:   # spot check: the GPU step of the same batch (the first of the first full group) drew the same nodes
                 for l, o in enumerate(osteps):
                     got = res["sizes"][l]
                     assert got["n_next"] == o.sm.n_next and got["nnz"] == o.sm.adj_nnz and got["remote"] == o.rc.remote_total
@@ -853,7 +857,7 @@ def main():
                     precision=("bf16 features, " if bf16 else "f32 features, ") + "u64 fixed-point weights and CDF, f64 accumulation, f32 outputs",
                     per_step=res["per_step"]),
         one_stream_ms_per_step=res["serial_ms_per_step"],
-        mini_batches_per_call=K, last_group=res["last_group"],
+        mini_batches_per_call=K, smaller_first_group=res["smaller_group"],
         schedule=(f"{K} consecutive mini-batches per library call, sampling then compute of every group in order on one stream; each part "
                   if args.one_stream else
                   f"{K} consecutive mini-batches per sampling call, such groups round-robin on {args.samplers} streams (own "
