@@ -657,6 +657,50 @@ def test_layer_forward_shapes(dev, K, N, bf16, mode):
         chain.assert_close(Z[:count].cpu().numpy(), Z_want[:count], chain.RTOL, chain.ATOL, f"device row count {count}, Z")
 
 
+def test_layer_forward_random_shapes(dev):
+    """Forty seeded random shapes (widths the call takes, any number of columns and rows, leading dimensions wider than
+    the rows) against the oracle: ragged K chunks, ragged and single column tiles, blocks with fewer than 32 rows."""
+    from paper_2101_07706_amd import csgs
+    rng = np.random.default_rng(20240607)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    done = 0
+    while done < 40:
+        K = int(rng.integers(1, 257))
+        v = 1 if K <= 64 else (2 if K <= 128 else 4)
+        if K % v:
+            K += v - K % v
+        N, n_rows, n_cols = int(rng.integers(1, 330)), int(rng.integers(1, 200)), int(rng.integers(1, 300))
+        bf16 = bool(rng.integers(0, 2))
+        rowptr, col, val = _random_adj(rng, n_rows, n_cols, int(rng.integers(0, 70)))
+        ld = K + v * int(rng.integers(0, 3))
+        X = np.zeros((n_cols, ld), np.float32)
+        X[:, :K] = rng.standard_normal((n_cols, K))
+        W = np.zeros((K, N + int(rng.integers(0, 5))), np.float32)
+        W[:, :N] = rng.standard_normal((K, N)) / np.sqrt(K)
+        relu = bool(rng.integers(0, 2))
+        if bf16:
+            Xh = synth.to_bf16_bits(X)
+            Xd = torch.from_numpy(Xh.view(np.int16)).to(dev)[:, :K]
+            Xo = Xh[:, :K]
+        else:
+            Xd = t(X)[:, :K]
+            Xo = X[:, :K]
+        Wd = t(W)[:, :N]
+        Z_want = oracle.aggregate(rowptr, col, val, np.ascontiguousarray(Xo), relu_on_input=relu)
+        H_want = oracle.layer_gemm(Z_want, np.ascontiguousarray(W[:, :N]))
+        say(f"[layer_forward] random shape {done}: K={K} N={N} rows={n_rows} cols={n_cols} bf16={bf16} relu={relu} ld={ld} nnz={len(col)}")
+        assert csgs.csgs_layer_forward_supported(Xd)
+        H = torch.full((n_rows, N + 3), float("nan"), dtype=torch.float32, device=dev)
+        Z = torch.full((n_rows, K + 1), float("nan"), dtype=torch.float32, device=dev)
+        csgs.csgs_layer_forward(t(rowptr), t(col), t(val), torch.tensor([n_cols], dtype=torch.int32, device=dev), Xd, None, None, relu,
+                                Wd, H[:, :N], Z[:, :K])
+        torch.cuda.synchronize()
+        chain.assert_close(Z[:, :K].cpu().numpy(), Z_want, chain.RTOL, chain.ATOL, f"random shape {done}: Z")
+        chain.assert_close(H[:, :N].cpu().numpy(), H_want, chain.RTOL, chain.ATOL, f"random shape {done}: H")
+        assert bool(torch.isnan(H[:, N:]).all()) and bool(torch.isnan(Z[:, K:]).all()), "wrote beyond the row width"
+        done += 1
+
+
 def test_layer_forward_instances_and_unsupported_widths(dev):
     """Three instances in one launch equal three separate calls bit for bit; widths the kernel does not take are refused
     before anything is enqueued."""
