@@ -157,6 +157,25 @@ __device__ inline void apply_mask(double (&acc)[V], const float *__restrict__ m)
 // ZLDS: `z` points into LDS (the tile of Z that the layer product reads next); the stores then say so, instead of
 // going through the flat path that a pointer of unknown kind takes.
 #define CSGS_LDS __attribute__((address_space(3)))
+// Stores to global memory that the compiler does not keep count of.  Loads and stores share one counter of outstanding
+// operations on this part, and loads come back in order only among themselves: with a store of its own outstanding the
+// compiler waits for everything before it uses any loaded value, so a row's store inside a loop that keeps the next
+// loads in flight would drain them at every turn.  A store it does not see leaves its count of the loads exact, and
+// the extra outstanding operation only makes a wait for "all but the last n" longer, never shorter.  Only for memory
+// that the kernel itself never reads again.
+__device__ inline void store_untracked(float *p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ inline void store_untracked(float *p, f32x2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ inline void store_untracked(float *p, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+
 template <int V, bool ZLDS = false>
 __device__ inline void store_row(float *z, const double (&acc)[V])
 {
@@ -168,12 +187,12 @@ __device__ inline void store_row(float *z, const double (&acc)[V])
     if (V >= 4) {
 #pragma unroll
         for (int q = 0; q + 4 <= V; q += 4)
-            *reinterpret_cast<float4 *>(z + q) = make_float4((float)acc[q], (float)acc[q + 1 < V ? q + 1 : 0], (float)acc[q + 2 < V ? q + 2 : 0],
-                                                             (float)acc[q + 3 < V ? q + 3 : 0]);
+            store_untracked(z + q, f32x4{(float)acc[q], (float)acc[q + 1 < V ? q + 1 : 0], (float)acc[q + 2 < V ? q + 2 : 0],
+                                         (float)acc[q + 3 < V ? q + 3 : 0]});
     } else if (V == 2) {
-        *reinterpret_cast<float2 *>(z) = make_float2((float)acc[0], (float)acc[V > 1 ? 1 : 0]);
+        store_untracked(z, f32x2{(float)acc[0], (float)acc[V > 1 ? 1 : 0]});
     } else {
-        z[0] = (float)acc[0];
+        store_untracked(z, (float)acc[0]);
     }
 }
 
@@ -379,13 +398,15 @@ __device__ inline bool aggregate_tile(WaveStage<tile_rows(G), PL> &st, double *_
             }
         };
         {
+            // No load of this loop sits under a condition (a batch beyond the share asks for the edge that does not
+            // count: cached zeros), and the rows' stores are ones the compiler does not count: it then knows how many
+            // loads are in flight at every point and waits for the batch it consumes, not for the one just asked for.
             Batch a, b2;
             issue(0, a);
             for (int32_t t0 = 0; t0 < Lmax; t0 += 2 * UNR) {
-                if (t0 + UNR < Lmax) issue(t0 + UNR, b2);
+                issue(t0 + UNR, b2);
                 consume(a);
-                if (t0 + UNR >= Lmax) break;
-                if (t0 + 2 * UNR < Lmax) issue(t0 + 2 * UNR, a);
+                issue(t0 + 2 * UNR, a);
                 consume(b2);
             }
         }

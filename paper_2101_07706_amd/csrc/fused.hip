@@ -24,16 +24,6 @@ namespace csgs {
 constexpr int FUSED_ROWS = 32;   // rows of Z per block: one 8-row tile per wavefront
 constexpr int FUSED_POOL = 64;   // edges a wavefront stages at a time (8 rows hold a few dozen)
 
-// A store the compiler does not keep count of.  Loads and stores share one counter of outstanding operations, and loads
-// come back in order only among themselves; with a store of its own outstanding the compiler therefore waits for
-// everything before it uses any loaded value, which would drain the ring of weight fetches at every step.  A store
-// it does not see leaves its count of the loads exact, and the extra outstanding operation only makes a wait for
-// "all but the last n" longer, never shorter.  Nothing in the kernel reads what these stores write.
-__device__ inline void store_untracked(float *p, float v)
-{
-    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
-}
-
 // KP: capacity of the LDS tile in features (64, 128 or 256); a lane holds V = KP / 64 consecutive features.
 template <typename T, int KP, bool RELU>
 __global__ __launch_bounds__(AGG_BLOCK, 3) void layer_forward_k(const int32_t *__restrict__ adj_rowptr,
