@@ -124,14 +124,11 @@ __device__ inline void accumulate_staged(double (&acc)[V], const T *src, float w
             const int srcl = gbase + ((j0 + u) & (WAVE - 1));
             const uint64_t pj = __shfl((uint64_t)(uintptr_t)src, srcl, WAVE);
             wj[u] = __shfl(w, srcl, WAVE);
+            // (no load under a condition: what must not count reads the zero row with weight 0, and the compiler
+            // keeps exact count of the loads in flight)
             const bool ok = active && (j0 + u) < n_here && pj != 0;
-            if (ok) {
-                x[u] = load_row<T, V>(reinterpret_cast<const T *>((uintptr_t)pj) + f);
-            } else {
-                wj[u] = 0.f;
-#pragma unroll
-                for (int v = 0; v < V; ++v) x[u].x[v] = 0.f;
-            }
+            if (!ok) wj[u] = 0.f;
+            x[u] = load_row<T, V>(ok ? reinterpret_cast<const T *>((uintptr_t)pj) + f : reinterpret_cast<const T *>(g_zero_row));
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {

@@ -235,13 +235,6 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
     }
 }
 
-// rank entry of node c for the call tagged rank_tag: position in S_next + 1, or 0
-__device__ inline int32_t rank_of(const uint64_t *__restrict__ rank, int32_t c, uint64_t rank_tag)
-{
-    const uint64_t e = rank[c];
-    return (e & 0xFFFFFFFF00000000ull) == rank_tag ? (int32_t)(e & 0xFFFFFFFFull) : 0;
-}
-
 // S_next ascends and the local partition is one id range, so the sampled remote nodes are the
 // entries before the first id >= lo and from the first id >= hi on: two searches give every
 // element its place, no scan needed.
@@ -401,23 +394,38 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         stage_slice<FROM_NOTE>(slice, eoff, rowstart, nS, c0, c1, FROM_NOTE ? chunk_note + t : nullptr);
         const int32_t len = (int32_t)(c1 - c0);
         // wave w owns positions [w * 256, w * 256 + 256): four 64-edge words
+        // A lane's four edges go through each step together, and no load sits under a condition (an edge that does
+        // not exist reads entry 0 and is dropped): the four columns travel at the same time, then the four table
+        // lookups, instead of eight trips one after the other.
         int32_t rk[4];
         int64_t ea[4];
+        bool live[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int32_t x = wave * 256 + k * 64 + lane;
-            rk[k] = 0;
             ea[k] = 0;
+            live[k] = false;
             if (x < len) {
                 int32_t r;
-                ea[k] = edge_address(slice, eoff, rowstart, c0, x, &r);
-                if (ea[k] >= 0 && ea[k] < nnz) {   // (an address outside the graph can only follow a failed wait)
-                    const int32_t c = colidx[ea[k]];
-                    if (c >= 0 && c < n_nodes) rk[k] = rank_of(rank, c, rank_tag);
-                } else {
-                    ea[k] = 0;
+                const int64_t a = edge_address(slice, eoff, rowstart, c0, x, &r);
+                if (a >= 0 && a < nnz) {   // (an address outside the graph can only follow a failed wait)
+                    ea[k] = a;
+                    live[k] = true;
                 }
             }
+        }
+        int32_t ck[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ck[k] = colidx[ea[k]];
+        uint64_t re[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            live[k] = live[k] && ck[k] >= 0 && ck[k] < n_nodes;
+            re[k] = rank[live[k] ? ck[k] : 0];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            rk[k] = (live[k] && (re[k] & 0xFFFFFFFF00000000ull) == rank_tag) ? (int32_t)(re[k] & 0xFFFFFFFFull) : 0;
             const uint64_t m = __ballot(rk[k] > 0);
             if (lane == 0) s_mask[wave * 4 + k] = m;
         }
@@ -434,7 +442,11 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         // values of the kept edges do not depend on the prefix: fetch and divide while it is resolved
         float pv[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) pv[k] = rk[k] > 0 ? (float)((double)val[ea[k]] / pdbl[rk[k] - 1]) : 0.f;
+        for (int k = 0; k < 4; ++k) {   // (unconditional loads again: entry 0 stands in for an edge that was not kept)
+            const float vv = val[ea[k]];
+            const double pp = pdbl[rk[k] > 0 ? rk[k] - 1 : 0];
+            pv[k] = rk[k] > 0 ? (float)((double)vv / pp) : 0.f;
+        }
         lookback_resolve<1>(ts, tag, t, n_chunks, local, excl, s_lb, status);
         const int64_t base = (int64_t)excl[0];
         // row pointers of the rows that start inside this chunk: kept edges before the row start
