@@ -61,6 +61,7 @@ struct Workspace {
     // persistent: zeroed once, then never cleared; an entry counts only if it carries the tag of
     // the current call
     uint64_t *rank;      // [n_nodes]  (tag << 32) | (position in S_next + 1)
+    uint64_t *member;    // [(n_nodes + 31) / 32]  (tag << 32) | one bit per id of the word's 32: in S_next of the draw with that tag
     uint64_t *partial;   // [4 * n_tiles] per-tile candidate counts and weight sums
     uint64_t *gtot;      // [4 * ceil(n_tiles / 64)] the same per group of 64 tiles
     uint64_t *cand_flag; // [n_tiles] tag of the call whose partial sums a tile holds
@@ -149,6 +150,7 @@ __host__ inline Workspace carve(void *base, int64_t n_nodes, int64_t nS_max, int
     w.cbitmap = (uint64_t *)take(words * 8);
     w.clean_bytes = off;
     w.rank = (uint64_t *)take((size_t)n_nodes * 8);
+    w.member = (uint64_t *)take((size_t)((n_nodes + 31) / 32) * 8);
     w.partial = (uint64_t *)take((size_t)w.n_tiles * 4 * 8);
     w.gtot = (uint64_t *)take((size_t)((w.n_tiles + 63) / 64) * 4 * 8);
     w.cand_flag = (uint64_t *)take((size_t)w.n_tiles * 8);

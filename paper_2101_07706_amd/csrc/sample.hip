@@ -57,17 +57,20 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
                                                    const uint64_t *__restrict__ iter_dev, uint32_t layer,
                                                    uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
                                                    const uint64_t *__restrict__ epoch, uint64_t *__restrict__ rank,
-                                                   int64_t n_nodes, InstStride is)
+                                                   uint64_t *__restrict__ member, int64_t n_nodes, InstStride is)
 {
     __shared__ uint64_t top[TOP];
     cdf = inst_ptr(cdf, is.buf); stats = inst_ptr(stats, is.buf);
     hit = inst_ptr(hit, is.ws); cbitmap = inst_ptr(cbitmap, is.ws); epoch = inst_ptr(epoch, is.ws); rank = inst_ptr(rank, is.ws);
-    // rank entries carry the low 32 bits of the call number; when those wrap, stale entries could
-    // look current, so the table is wiped once every 2^32 calls (the compaction kernel that follows
-    // writes the new entries)
+    member = inst_ptr(member, is.ws);
+    // rank entries and membership words carry the low 32 bits of the call number; when those wrap, stale
+    // entries could look current, so both tables are wiped once every 2^32 calls (the compaction kernel that
+    // follows writes the new entries)
     if ((call_number(epoch) & 0xFFFFFFFFull) == 0) {
-        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_nodes; i += (int64_t)gridDim.x * blockDim.x)
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_nodes; i += (int64_t)gridDim.x * blockDim.x) {
             rank[i] = 0ull;
+            if (i < (n_nodes + 31) / 32) member[i] = 0ull;
+        }
     }
     if (iter_dev) iter = *iter_dev;
     iter += blockIdx.z;   // consecutive instances are consecutive iterations
@@ -125,18 +128,58 @@ __global__ __launch_bounds__(DRAW_BLOCK) void draw(const uint64_t *__restrict__ 
                                 __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The membership words: word id / 32 holds (tag << 32) | one bit per id, set when the id is in S_next of the draw
+// with that tag; the adjacency pass looks an edge's column up here (612 KB for 2.4 M nodes: it stays in the L2s)
+// and goes to the 8-byte-per-node rank table only for the one column in twenty that is a member.
+// Merging bits into a word that other wavefronts may write as well: a word of an older draw counts as empty.  Two
+// updates nobody waits for: a 64-bit maximum with (tag << 32) replaces an older draw's word by the empty word of this
+// draw and leaves a current one alone (tags ascend from draw to draw; the table is wiped when they wrap), then the
+// bits are or-ed in.  Updates of one address by one lane take effect in program order.
+__device__ inline void member_merge(uint64_t *word, uint32_t bits, uint32_t tag32)
+{
+    unsigned long long *p = reinterpret_cast<unsigned long long *>(word);
+    (void)__hip_atomic_fetch_max(p, (unsigned long long)tag32 << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    (void)__hip_atomic_fetch_or(p, (unsigned long long)bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every lane of a wavefront calls this with the id of its hit (-1: none).  The hits of a wavefront are consecutive
+// entries of the ascending list, so the ids that share a word sit in neighbouring lanes: their bits are put
+// together by lane exchanges and the first lane of the run stores the word.  All ids of a word that lies strictly
+// inside the wavefront's hits are in this wavefront, so that store is a plain one; a run next to a lane without a
+// hit, or at either end of the wavefront, may go on in another wavefront and is merged atomically.
+__device__ inline void mark_members(uint64_t *__restrict__ member, int32_t id, uint32_t tag32)
+{
+    const int lane = lane_id();
+    const int32_t w = id >= 0 ? id >> 5 : -1;
+    uint32_t bits = id >= 0 ? 1u << (id & 31) : 0u;
+    const int32_t wp = __shfl_up(w, 1, WAVE), wn = __shfl_down(w, 1, WAVE);
+    const bool head = w >= 0 && (lane == 0 || wp != w);
+    uint32_t open = (w >= 0 && (lane == WAVE - 1 || wn < 0)) ? 1u : 0u;   // matters in the run's last lane: nothing valid follows it here
+#pragma unroll
+    for (int d = 1; d <= 16; d <<= 1) {   // a run has at most 32 lanes
+        const uint32_t ob = __shfl_down(bits, d, WAVE), oo = __shfl_down(open, d, WAVE);
+        const int32_t w2 = __shfl_down(w, d, WAVE);
+        if (lane + d < WAVE && w2 == w) { bits |= ob; open |= oo; }
+    }
+    if (head) {
+        if (open || lane == 0 || wp < 0) member_merge(&member[w], bits, tag32);
+        else member[w] = ((uint64_t)tag32 << 32) | bits;
+    }
+}
+
 __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ cand_id,
                                                   const uint64_t *__restrict__ cdf,
                                                   const csgs_prob_stats *__restrict__ stats, int64_t cand_cap,
                                                   int64_t n_nodes, int32_t B, uint64_t *__restrict__ epoch,
                                                   uint64_t *__restrict__ ts_mem, int64_t ts_tiles,
                                                   uint32_t *__restrict__ hit, uint64_t *__restrict__ cbitmap,
-                                                  uint64_t *__restrict__ rank, int32_t *__restrict__ S_next,
+                                                  uint64_t *__restrict__ rank, uint64_t *__restrict__ member,
+                                                  int32_t *__restrict__ S_next,
                                                   int32_t *__restrict__ mult, float *__restrict__ p_incl,
                                                   double *__restrict__ pdbl, int32_t *__restrict__ n_next,
                                                   int32_t *__restrict__ status, InstStride is)
 {
     __shared__ uint32_t lds[17];
+    member = inst_ptr(member, is.ws);
     cand_id = inst_ptr(cand_id, is.buf); cdf = inst_ptr(cdf, is.buf); stats = inst_ptr(stats, is.buf);
     S_next = inst_ptr(S_next, is.buf); mult = inst_ptr(mult, is.buf); p_incl = inst_ptr(p_incl, is.buf);
     n_next = inst_ptr(n_next, is.buf); status = inst_ptr(status, is.buf);
@@ -196,6 +239,7 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
             id0 = cand_id[kpos0];
         }
         lookback_resolve<1>(ts, tag, t, n_tiles, local, excl, s_lb, status);
+        int32_t member_id = -1;
         if (i0 < tile_total) {
             const uint64_t pos = excl[0] + i0;
             if (pos < (uint64_t)B) {  // at most B distinct hits exist; the guard keeps stores in bounds regardless
@@ -203,25 +247,37 @@ __global__ __launch_bounds__(256) void hits_fused(const int32_t *__restrict__ ca
                 mult[pos] = (int32_t)m0;
                 p_incl[pos] = (float)pk0;
                 pdbl[pos] = pk0;
-                if (id0 >= 0 && id0 < n_nodes) rank[id0] = rank_tag | (pos + 1);
+                if (id0 >= 0 && id0 < n_nodes) {
+                    rank[id0] = rank_tag | (pos + 1);
+                    member_id = id0;
+                }
             }
         }
-        for (uint32_t i = blockDim.x + threadIdx.x; i < tile_total; i += blockDim.x) {  // crowded tiles
-            const int64_t kpos = t * (HIT_TILE_WORDS * 64) + s_list[i];
-            const uint64_t pos = excl[0] + i;
-            const uint32_t m = hit[kpos];
-            hit[kpos] = 0u;
-            if (pos < (uint64_t)B) {
-                const uint64_t wk = cdf[kpos] - (kpos ? cdf[kpos - 1] : 0ull);
-                const double qk = (double)wk / total;
-                const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
-                const int32_t id = cand_id[kpos];
-                S_next[pos] = id;
-                mult[pos] = (int32_t)m;
-                p_incl[pos] = (float)pk;
-                pdbl[pos] = pk;
-                if (id >= 0 && id < n_nodes) rank[id] = rank_tag | (pos + 1);
+        mark_members(member, member_id, (uint32_t)(rank_tag >> 32));
+        for (uint32_t i_base = blockDim.x; i_base < tile_total; i_base += blockDim.x) {  // crowded tiles (every lane goes round together)
+            const uint32_t i = i_base + threadIdx.x;
+            int32_t marked = -1;
+            if (i < tile_total) {
+                const int64_t kpos = t * (HIT_TILE_WORDS * 64) + s_list[i];
+                const uint64_t pos = excl[0] + i;
+                const uint32_t m = hit[kpos];
+                hit[kpos] = 0u;
+                if (pos < (uint64_t)B) {
+                    const uint64_t wk = cdf[kpos] - (kpos ? cdf[kpos - 1] : 0ull);
+                    const double qk = (double)wk / total;
+                    const double pk = (qk >= 1.0) ? 1.0 : -expm1((double)B * log1p(-qk));
+                    const int32_t id = cand_id[kpos];
+                    S_next[pos] = id;
+                    mult[pos] = (int32_t)m;
+                    p_incl[pos] = (float)pk;
+                    pdbl[pos] = pk;
+                    if (id >= 0 && id < n_nodes) {
+                        rank[id] = rank_tag | (pos + 1);
+                        marked = id;
+                    }
+                }
             }
+            mark_members(member, marked, (uint32_t)(rank_tag >> 32));
         }
         if (t == n_tiles - 1 && threadIdx.x == 0) {
             const uint64_t tot = excl[0] + tile_total;
@@ -311,7 +367,8 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
                                                  int64_t n_nodes, int64_t nnz, const int64_t *__restrict__ meta,
                                                  const int64_t *__restrict__ eoff,
                                                  const int64_t *__restrict__ rowstart,
-                                                 const uint64_t *__restrict__ rank, const double *__restrict__ pdbl,
+                                                 const uint64_t *__restrict__ rank, const uint64_t *__restrict__ member,
+                                                 const double *__restrict__ pdbl,
                                                  uint64_t *__restrict__ epoch, uint64_t *__restrict__ ts_mem, int64_t chunk_cap,
                                                  int2 *__restrict__ chunk_note, int32_t *__restrict__ adj_rowptr,
                                                  int32_t *__restrict__ adj_col, float *__restrict__ adj_val,
@@ -348,7 +405,7 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         return;
     }
     meta = inst_ptr(meta, is.ws); eoff = inst_ptr(eoff, is.ws); rowstart = inst_ptr(rowstart, is.ws);
-    rank = inst_ptr(rank, is.ws); pdbl = inst_ptr(pdbl, is.ws); ts_mem = inst_ptr(ts_mem, is.ws);
+    rank = inst_ptr(rank, is.ws); member = inst_ptr(member, is.ws); pdbl = inst_ptr(pdbl, is.ws); ts_mem = inst_ptr(ts_mem, is.ws);
     chunk_note = inst_ptr(chunk_note, is.ws);
     adj_rowptr = inst_ptr(adj_rowptr, is.buf); adj_col = inst_ptr(adj_col, is.buf); adj_val = inst_ptr(adj_val, is.buf);
     adj_nnz = inst_ptr(adj_nnz, is.buf);
@@ -417,10 +474,17 @@ __global__ __launch_bounds__(256) void adj_fused(const int32_t *__restrict__ col
         int32_t ck[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) ck[k] = colidx[ea[k]];
-        uint64_t re[4];
+        // the membership word of every column first (a small table that stays in the L2s), then the rank entry, which
+        // only a member's lane reads from its own place (the others read entry 0)
+        uint64_t mw[4], re[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             live[k] = live[k] && ck[k] >= 0 && ck[k] < n_nodes;
+            mw[k] = member[live[k] ? ck[k] >> 5 : 0];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            live[k] = live[k] && (mw[k] & 0xFFFFFFFF00000000ull) == rank_tag && ((mw[k] >> (ck[k] & 31)) & 1ull);
             re[k] = rank[live[k] ? ck[k] : 0];
         }
 #pragma unroll
@@ -506,14 +570,14 @@ extern "C" int csgs_draw_nodes(int64_t n_nodes, const int32_t *cand_id, const ui
     const unsigned nz = (unsigned)w.n_inst;
     const InstStride is = inst_stride(w);
     CSGS_LAUNCH(K_DRAW, draw, dim3((unsigned)((B + DRAW_BLOCK - 1) / DRAW_BLOCK), 1, nz), dim3(DRAW_BLOCK), st, cdf, stats,
-                cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), iter, iter_dev, layer, w.hit, w.cbitmap, w.epoch, w.rank,
+                cand_cap, B, (uint32_t)seed, (uint32_t)(seed >> 32), iter, iter_dev, layer, w.hit, w.cbitmap, w.epoch, w.rank, w.member,
                 n_nodes, is);
     CSGS_LAUNCH_CHECK();
     const int64_t cap_words = (cand_cap + 63) / 64;
     const int64_t hit_tiles = (cap_words + HIT_TILE_WORDS - 1) / HIT_TILE_WORDS;
     const unsigned hit_blocks = (unsigned)(hit_tiles < resident_grid(1) ? hit_tiles : resident_grid(1));
     CSGS_LAUNCH(K_HITS_FUSED, hits_fused, dim3(hit_blocks, 1, nz), dim3(256), st, cand_id, cdf, stats, cand_cap, n_nodes, B,
-                w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, S_next, mult, p_incl, w.pdbl, n_next, status, is);
+                w.epoch, w.hit_ts, w.hit_tiles, w.hit, w.cbitmap, w.rank, w.member, S_next, mult, p_incl, w.pdbl, n_next, status, is);
     CSGS_LAUNCH_CHECK();
     ws->has_draw = 1;
     ws->draw_B = B;
@@ -555,11 +619,11 @@ static int sampled_adjacency_impl(const csgs_graph *g, const int32_t *rows, int3
     const InstStride is = inst_stride(w);
     if (reuse_offsets)
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<true>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
+                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.member, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
                     adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt, is);
     else
         CSGS_LAUNCH(K_ADJ_FUSED, adj_fused<false>, grid, dim3(256), st, g->colidx, g->val, g->n_nodes,
-                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
+                    g->nnz, cur.meta, cur.eoff, cur.rowstart, w.rank, w.member, w.pdbl, w.epoch, w.adj_ts, w.chunk_cap, cur.chunk_note,
                     adj_rowptr, adj_col, adj_val, adj_cap, adj_nnz, status, rem, nxt, is);
     CSGS_LAUNCH_CHECK();
     return CSGS_OK;
