@@ -249,9 +249,7 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
                 hc[k] = c;
                 hr[k] = atomicAdd(&hist[hb[k]], 1u);      // place inside the owner's group (any order)
             } else {
-                (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)qk[k], __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
-                tileflag[c >> 3] = 1;  // same value from every writer
+                hb[k] = -2;   // goes through a device-scope atomic, issued after the chunk's hand-over (below)
             }
         }
         if (staged) {
@@ -289,6 +287,17 @@ __global__ __launch_bounds__(256) void scan_edges(const int32_t *__restrict__ co
             wait_memory_ops();     // this wavefront's hand-over stores have been acknowledged
             __syncthreads();
             if (threadIdx.x == 0) st_flag(&stg.done[t], tag);
+        }
+        // The edges that end outside the local range (all edges without the hand-over).  After the flag: the wait above
+        // would otherwise include these updates, which take far longer to be acknowledged than the stores, and the
+        // owners would start that much later.
+#pragma unroll
+        for (int k = 0; k < EDGE_TILE / 256; ++k) {
+            if (hb[k] != -2) continue;
+            const int32_t c = ck[k];
+            (void)__hip_atomic_fetch_add((unsigned long long *)&wtable[c], (unsigned long long)qk[k], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            tileflag[c >> 3] = 1;  // same value from every writer
         }
     }
     if (bad) atomicOr(status, CSGS_ST_BAD_EDGE_VALUE);
